@@ -1,0 +1,119 @@
+"""Whole-network oracle: SK-Net forward / backward / SGD and U-Net forward, composed from the
+layer functions in oracle/layers.py in the order the paper's tables list them.
+TEST INFRASTRUCTURE ONLY.
+"""
+import numpy as np
+
+from . import layers as L
+from .alg1 import context
+
+
+def pad_amounts(v):
+    """Split the context v over the borders: ceil(v/2) top/left, floor(v/2) bottom/right
+    (Section 3.3.2: an odd v is handled by a one-pixel crop on the bottom and right)."""
+    return (v + 1) // 2, (v + 1) // 2, v // 2, v // 2
+
+
+def sknet_forward(image, sk_layers, weights, biases, pad=True, pad_mode=0, keep=False):
+    """image[n,c,h,w] -> class probabilities [n,classes,h,w] (pad=True) for an SK net
+    (laid out like the SK network configuration table of Section 3.3.2: conv SK + ReLU, max pool SK, ..., conv, softmax).
+    keep=True also returns every intermediate (for per-layer parity and for backward)."""
+    x = np.asarray(image, dtype=np.float64)
+    if pad:
+        t, l, b, r = pad_amounts(context(sk_layers))
+        x = L.mirror_pad(x, t, l, b, r, pad_mode)
+    acts, argmaxes = [x], []
+    wi = 0
+    for lay in sk_layers:
+        if lay["type"] == "conv":
+            x = L.conv_sk(x, weights[wi], biases[wi], lay["d"], lay.get("relu", False))
+            wi += 1
+            argmaxes.append(None)
+        elif lay["type"] == "pool":
+            x, am = L.maxpool_sk(x, lay["k"], lay["d"], lay.get("s", 1))
+            argmaxes.append(am)
+        else:
+            raise ValueError(lay["type"])
+        acts.append(x)
+    prob = L.softmax(x)
+    if keep:
+        return prob, acts, argmaxes
+    return prob
+
+
+def sknet_backward(sk_layers, weights, acts, argmaxes, labels):
+    """Exact gradient of the mean softmax loss w.r.t. every conv weight and bias.
+    acts/argmaxes come from sknet_forward(keep=True).  Returns (loss, dW list, db list, d_input)."""
+    loss, g = L.softmax_loss(acts[-1], labels)
+    conv_ids = [i for i, l in enumerate(sk_layers) if l["type"] == "conv"]
+    dws, dbs = [None] * len(conv_ids), [None] * len(conv_ids)
+    wi = len(conv_ids) - 1
+    for li in range(len(sk_layers) - 1, -1, -1):
+        lay = sk_layers[li]
+        x_in, y_out = acts[li], acts[li + 1]
+        if lay["type"] == "conv":
+            if lay.get("relu", False):
+                g = L.relu_bwd(y_out, g)
+            dws[wi], dbs[wi] = L.conv_sk_bwd_weights(x_in, g, lay["k"], lay["d"])
+            g = L.conv_sk_bwd_data(g, weights[wi], lay["d"], x_in.shape[2:])
+            wi -= 1
+        else:
+            g = L.maxpool_bwd(g, argmaxes[li], x_in.shape[2:])
+    return loss, dws, dbs, g
+
+
+def sgd_step(weights, biases, dws, dbs, lr, momentum=0.0, weight_decay=0.0, vel_w=None, vel_b=None):
+    for i in range(len(weights)):
+        L.sgd(weights[i], dws[i], None if vel_w is None else vel_w[i], lr, momentum, weight_decay)
+        L.sgd(biases[i], dbs[i], None if vel_b is None else vel_b[i], lr, momentum, weight_decay)
+
+
+# ---------------------------------------------------------------------------------------------
+# U-Net (Section 3.4, the U network configuration table)
+
+def unet_spec(depth=4, base=64):
+    """Per-level channel counts of the U-Net table: 64,128,256,512 down, 1024 at the bottom."""
+    return [base * 2 ** i for i in range(depth + 1)]
+
+
+def unet_forward(image, params, depth=4, keep=False):
+    """image[n,c,h,w] (already context-padded, e.g. 572) -> probabilities (e.g. 388).
+
+    params is a dict of (weight, bias) pairs, in table order:
+      "down{i}a", "down{i}b"  i = 0..depth   3x3 conv + ReLU (level `depth` is the bottom)
+      "up{i}"                 i = depth-1..0 2x2 stride-2 up-convolution f -> f/2, no ReLU,
+                                             weight [f, f/2, 2, 2]
+      "dec{i}a", "dec{i}b"    3x3 conv + ReLU on mergecrop(up path, skip)
+      "head"                  1x1 conv to the classes
+    The paper's up step (fixed nearest-neighbour grouped deconvolution, then a 1x1 conv f -> f/2
+    without ReLU) is the special case weight[c,o,a,b] = W1x1[o,c]; see upstep_from_paper().
+    """
+    x = np.asarray(image, dtype=np.float64)
+    skips, trace = [], {}
+    for i in range(depth + 1):
+        x = L.conv_sk(x, *params["down%da" % i], d=1, relu=True)
+        x = L.conv_sk(x, *params["down%db" % i], d=1, relu=True)
+        trace["down%d" % i] = x
+        if i < depth:
+            skips.append(x)
+            if x.shape[2] % 2 or x.shape[3] % 2:
+                raise ValueError("U-Net pooling needs an even map size")
+            x, _ = L.maxpool_sk(x, 2, 1, 2)
+    for i in range(depth - 1, -1, -1):
+        x = L.upconv2x2(x, *params["up%d" % i])
+        trace["up%d" % i] = x
+        x = L.mergecrop(x, skips[i])
+        x = L.conv_sk(x, *params["dec%da" % i], d=1, relu=True)
+        x = L.conv_sk(x, *params["dec%db" % i], d=1, relu=True)
+        trace["dec%d" % i] = x
+    z = L.conv_sk(x, *params["head"], d=1, relu=False)
+    trace["logits"] = z
+    prob = L.softmax(z)
+    return (prob, trace) if keep else prob
+
+
+def upstep_from_paper(w1x1):
+    """Fold the paper's two-layer up step (nearest-neighbour 2x2 up-sampling of every map, then a
+    1x1 convolution w1x1[o,c,1,1]) into one up-convolution weight [c,o,2,2]."""
+    o, c = w1x1.shape[:2]
+    return np.broadcast_to(w1x1.reshape(o, c).T[:, :, None, None], (c, o, 2, 2)).copy()
