@@ -1,0 +1,212 @@
+/*
+ * libsknet — dense pixelwise classification with strided-kernel (SK) networks and a U-Net
+ * forward pass on one AMD MI355X (gfx950).  C ABI; no C++ or framework types cross it.
+ *
+ * Method: F. Tschopp, "Efficient Convolutional Neural Networks for Pixelwise Classification on
+ * Heterogeneous Hardware Systems" (arXiv 1509.03371).  Symbols follow its Section 1.6:
+ * f_in/f_out feature maps, w map size, v total context of the net, k kernel size, s layer
+ * stride, d kernel stride (dilation), n minibatch.
+ *
+ * Pointer conventions: every pointer argument is marked HOST or DEVICE.  DEVICE buffers are
+ * owned by the caller (e.g. a PyTorch tensor's data_ptr()); the library never frees or keeps
+ * them beyond the call.  HOST buffers are plain caller memory.  Weights, packed weights,
+ * activations, pool masks and gradients are owned by the handle.
+ *
+ * Errors: every function returns an sk_status (0 = success) and never throws or aborts; all
+ * argument and shape checks happen on the host before anything is launched.  The message for
+ * the last failure on the calling thread is available from sknet_last_error().
+ *
+ * Asynchrony: forward / backward / sgd_step only enqueue work on the given HIP stream
+ * (a hipStream_t passed as void*, NULL = the default stream) and return; the get_* accessors
+ * and sknet_time_step synchronise that stream themselves.  One handle must not be used from
+ * two host threads, or on two streams, at the same time.
+ */
+#ifndef SKNET_H
+#define SKNET_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sknet sknet_t; /* opaque */
+typedef struct unet unet_t;   /* opaque */
+
+typedef enum {
+    SK_OK = 0,
+    SK_EINVAL = 1,       /* null pointer, bad enum, bad index */
+    SK_ESHAPE = 2,       /* sizes that the layer rules reject */
+    SK_ESTATE = 3,       /* call order: forward before plan, backward before a training forward ... */
+    SK_ENOMEM = 4,       /* device or host allocation failed */
+    SK_EDEVICE = 5,      /* a HIP call failed, or no usable GPU */
+    SK_EUNSUPPORTED = 6  /* valid request that this build does not implement */
+} sk_status;
+
+/* Arithmetic/storage type of activations and packed weights.  Accumulation is always fp32;
+ * images, probabilities, labels, weights and gradients cross the ABI as fp32 / int32. */
+typedef enum { SK_F32 = 0, SK_BF16 = 1, SK_F16 = 2 } sk_dtype;
+
+typedef enum { SK_CONV = 0, SK_MAXPOOL = 1 } sk_kind;
+
+/* One layer of an SK net, in the terms of the paper's configuration tables (Section 3.3.2):
+ *   SK_CONV    : f_out = c_out maps, kernel k x k, kernel stride d, s must be 1; relu != 0 applies
+ *                max(0, .) to the output.  Y[o,y,x] = b[o] + sum_{c,i,j} W[o,c,i,j] X[c,y+i*d,x+j*d]
+ *                (Section 5.2.1; cross-correlation, no padding).
+ *   SK_MAXPOOL : kernel k x k, kernel stride d, layer stride s (1 for SK pooling; s = k with d = 1
+ *                for an ordinary down-sampling pool).  c_out and relu are ignored.
+ * Every layer with a kernel shrinks the map by (k-1)*d (Algorithm 1). */
+typedef struct {
+    int32_t kind;  /* sk_kind */
+    int32_t c_out;
+    int32_t k;
+    int32_t d;
+    int32_t s;
+    int32_t relu;
+} sk_layer;
+
+/* A layer of a sliding-window net, input of Algorithm 1.  kind: 0 convolution (k, c_out, relu),
+ * 1 pooling (k, s), 2 inner product (c_out, relu; its kernel is the whole remaining map),
+ * 3 any other layer (must have k = 1, i.e. be element-wise; it is dropped from the output). */
+typedef struct {
+    int32_t kind;
+    int32_t c_out;
+    int32_t k;
+    int32_t s;
+    int32_t relu;
+} sw_layer;
+
+/* ---------------------------------------------------------------- host-only helpers (no GPU) */
+
+/* Algorithm 1 (Section 3.3.1): convert a sliding-window net with patch size w0_sw into SK layers.
+ * sw, sk_out: HOST arrays; sk_out must have room for n entries; *n_out receives the count
+ * written.  Returns SK_ESHAPE when the algorithm's checks fail: a pool with w mod k != 0 or
+ * k != s, another layer type with k > 1, a map that shrinks below 1, or a final kernel
+ * stride != 1. */
+sk_status sknet_convert_sw(const sw_layer *sw, int32_t n, int32_t w0_sw, sk_layer *sk_out,
+                           int32_t *n_out);
+
+/* Convolution cost model of Section 5.5: f_out * w_out^2 * (2 * f_in * k^2 - 1). */
+int64_t sknet_conv_flops(int64_t f_in, int64_t f_out, int64_t k, int64_t w_out);
+
+/* Message of the last error on this thread (never NULL; valid until the next failing call). */
+const char *sknet_last_error(void);
+
+/* ---------------------------------------------------------------- SK-Net */
+
+/* Build a net description (host only; no GPU needed).  layers: HOST array, copied.
+ * The net is: mirror padding by the context v, the layers in order, then a per-pixel softmax
+ * over the maps of the last layer (Section 3.3.2's table ends in such a "prob" layer).
+ * n_classes must equal the map count of the last layer.  pad_mode: 0 = reflect (edge sample not
+ * repeated), 1 = symmetric (edge sample repeated).  Conv weights start as zeros.
+ * SK_EINVAL for bad arguments, SK_ESHAPE for k < 1, d < 1, a pool whose s is neither 1 nor k
+ * (or s = k with d != 1), SK_EUNSUPPORTED for a dtype this build lacks. */
+sk_status sknet_create(const sk_layer *layers, int32_t n_layers, int32_t c_in, int32_t n_classes,
+                       sk_dtype dtype, int32_t pad_mode, sknet_t **out);
+void sknet_destroy(sknet_t *net);
+
+/* *v = total context, the sum of (k-1)*d over all layers (only defined for nets whose pools
+ * all have s = 1; SK_ESHAPE otherwise).  The image is padded by ceil(v/2) rows/columns at the
+ * top/left and floor(v/2) at the bottom/right (Section 3.3.2's handling of an odd v). */
+sk_status sknet_context(const sknet_t *net, int32_t *v);
+
+/* Map sizes for an h x w image: dims (HOST) receives (n_layers + 1) triples {maps, height,
+ * width}: entry 0 is the padded image, entry i the output of layer i-1.  pad != 0 applies the
+ * context padding first.  SK_ESHAPE if a map would shrink below one pixel, a down-sampling pool
+ * meets an odd size, or the mirror border does not fit the image. */
+sk_status sknet_infer_shapes(const sknet_t *net, int32_t h, int32_t w, int32_t pad, int32_t *dims);
+
+/* Number of convolution layers, and for conv number conv_idx (0-based, in layer order) its
+ * weight shape {f_out, f_in, k, k} written to shape4 (HOST). */
+sk_status sknet_num_convs(const sknet_t *net, int32_t *count);
+sk_status sknet_conv_shape(const sknet_t *net, int32_t conv_idx, int32_t *shape4);
+
+/* Set / read the fp32 master weights [f_out][f_in][k][k] and biases [f_out] of one conv (HOST
+ * buffers; b may be NULL in set = keep).  May be called before or after sknet_plan; after a plan
+ * the device copies are refreshed at once (synchronously). */
+sk_status sknet_set_weights(sknet_t *net, int32_t conv_idx, const float *w_host, const float *b_host);
+sk_status sknet_get_weights(sknet_t *net, int32_t conv_idx, float *w_host, float *b_host);
+
+/* Fix the problem size: n images of h x w pixels, and allocate every workspace on the current
+ * HIP device (hipMalloc).  pad != 0: the library mirror-pads the image by v so that the output
+ * is h x w; pad = 0: the caller's image already contains its context and the output is
+ * (h - v) x (w - v).  training != 0 also keeps pool masks and allocates gradient buffers.
+ * May be called again to change the size.  SK_ESHAPE as in sknet_infer_shapes. */
+sk_status sknet_plan(sknet_t *net, int32_t n, int32_t h, int32_t w, int32_t pad, int32_t training);
+
+/* Whole forward pass (Section 1.3: image in, per-pixel class probabilities out).
+ * image_dev: DEVICE fp32 [n][c_in][h][w];  prob_dev: DEVICE fp32 [n][n_classes][h_out][w_out].
+ * Needs a plan (SK_ESTATE otherwise). */
+sk_status sknet_forward(sknet_t *net, const float *image_dev, float *prob_dev, void *hip_stream);
+
+/* Softmax loss and exact gradients of every conv weight and bias, after a forward on a
+ * training plan (SK_ESTATE otherwise).  labels_dev: DEVICE int32 [n][h_out][w_out], values in
+ * [0, n_classes).  loss_dev: DEVICE fp32 scalar = -(1/P) * sum over the P = n*h_out*w_out pixels
+ * of log p_label (Section 4.3: accumulated over all pixels, then normalised).  Pool gradients go
+ * to the recorded maximum; ReLU passes gradient where its output is > 0. */
+sk_status sknet_backward(sknet_t *net, const int32_t *labels_dev, float *loss_dev, void *hip_stream);
+
+/* SGD on the fp32 master weights with the gradients of the last backward:
+ * g = dW + weight_decay*W;  V = momentum*V + lr*g;  W = W - V; then the packed device weights
+ * are rebuilt (rounded to the compute dtype). */
+sk_status sknet_sgd_step(sknet_t *net, float lr, float momentum, float weight_decay, void *hip_stream);
+
+/* Debug / parity accessors; each synchronises the stream of the last call first.
+ * get_grad: gradients of conv conv_idx as fp32 [f_out][f_in][k][k] and [f_out] (HOST).
+ * get_activation: output of layer layer_idx (-1 = the padded image) as fp32 NCHW (HOST), sized
+ *   as sknet_infer_shapes reports.
+ * get_pool_argmax: for max-pool number pool_idx (0-based among pools), per output element the
+ *   flat offset (y*W_in + x) of the winning input sample inside its input plane, int32 NCHW
+ *   (HOST).  Taps are scanned row-major and only a strictly greater value replaces the
+ *   incumbent, so the first maximum wins.  Needs a training plan. */
+sk_status sknet_get_grad(sknet_t *net, int32_t conv_idx, float *dw_host, float *db_host);
+sk_status sknet_get_activation(sknet_t *net, int32_t layer_idx, float *nchw_host);
+sk_status sknet_get_pool_argmax(sknet_t *net, int32_t pool_idx, int32_t *idx_host);
+
+/* Number of device steps of the planned forward pass (pad, one per layer, softmax), a short
+ * name for step i copied into name (HOST, at most cap bytes), and the average duration in
+ * milliseconds of step i re-run iters times on hip_stream between two HIP events (the step
+ * reads the activations the last forward left behind).  For benchmarking. */
+sk_status sknet_num_steps(const sknet_t *net, int32_t *count);
+sk_status sknet_step_name(const sknet_t *net, int32_t step, char *name, int32_t cap);
+sk_status sknet_time_step(sknet_t *net, int32_t step, int32_t iters, void *hip_stream, float *avg_ms);
+
+/* ---------------------------------------------------------------- U-Net forward */
+
+/* U-Net of Section 3.4's configuration table: `depth` contracting steps (two 3x3 convs + ReLU,
+ * then a 2x2 stride-2 max pool), two 3x3 convs at the bottom, `depth` expanding steps (2x2
+ * stride-2 up-convolution f -> f/2 without ReLU, MergeCrop with the skip connection, two 3x3
+ * convs + ReLU), a 1x1 conv to n_classes and a per-pixel softmax.  Maps: base_ch * 2^level.
+ * Host only. */
+sk_status unet_create(int32_t c_in, int32_t n_classes, int32_t depth, int32_t base_ch,
+                      sk_dtype dtype, unet_t **out);
+void unet_destroy(unet_t *net);
+
+/* Parameter tensors, in forward order: per level i = 0..depth "down{i}a", "down{i}b"; then per
+ * level i = depth-1..0 "up{i}", "dec{i}a", "dec{i}b"; then "head".  Convs are [f_out][f_in][k][k];
+ * up-convolutions are [f_in][f_out][2][2] with Y[o,2y+a,2x+b] = bias[o] + sum_c W[c,o,a,b] X[c,y,x]
+ * (the paper's fixed nearest-neighbour up-sampling followed by a 1x1 conv is the case
+ * W[c,o,a,b] = W1x1[o,c]).  shape4 (HOST) receives the four extents. */
+sk_status unet_num_params(const unet_t *net, int32_t *count);
+sk_status unet_param_shape(const unet_t *net, int32_t idx, int32_t *shape4);
+sk_status unet_set_weights(unet_t *net, int32_t idx, const float *w_host, const float *b_host);
+
+/* Output size for an input of h_in x w_in (which already contains the context; 572 -> 388 in the
+ * paper's table).  SK_ESHAPE when a pool meets an odd size or a map vanishes. */
+sk_status unet_output_size(const unet_t *net, int32_t h_in, int32_t w_in, int32_t *h_out, int32_t *w_out);
+
+/* Allocate workspaces for n images of h_in x w_in on the current HIP device. */
+sk_status unet_plan(unet_t *net, int32_t n, int32_t h_in, int32_t w_in);
+
+/* image_dev: DEVICE fp32 [n][c_in][h_in][w_in];  prob_dev: DEVICE fp32 [n][n_classes][h_out][w_out].
+ * MergeCrop puts the up path's maps first, then the skip maps centre-cropped with offset
+ * floor((w_skip - w_up)/2) (Section 5.3.1). */
+sk_status unet_forward(unet_t *net, const float *image_dev, float *prob_dev, void *hip_stream);
+
+/* Output of named stage (HOST fp32 NCHW): "down{i}", "up{i}", "dec{i}", "logits". *dims3 = maps,h,w. */
+sk_status unet_get_activation(unet_t *net, const char *stage, float *nchw_host, int32_t *dims3);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SKNET_H */

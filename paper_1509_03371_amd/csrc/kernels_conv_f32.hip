@@ -1,0 +1,217 @@
+// Implicit-GEMM SK (dilated) convolution for fp32 activations on gfx950, MFMA 16x16x4 fp32.
+//
+// GEMM view (paper, Section 5.5): M = f_out, N = output pixels, K = f_in*k*k.  Unlike the
+// paper's im2col + SGEMM there is no column buffer: a workgroup stages the dilated input tile it
+// needs in LDS and forms the K index (c, i, j) by address arithmetic.
+//
+// Tiling.  A workgroup (4 waves) owns R = 4*RW output rows that lie d apart (one row phase of the
+// kernel stride d) and 64 consecutive columns.  Because the rows are d apart, the k kernel rows of
+// all R output rows fall on only R + k - 1 input rows, whatever d is, so the staged tile is
+// (R + k - 1) x (64 + (k-1)*d) samples per input map instead of (R + (k-1)*d) rows.  Rows are
+// separate lines in memory anyway, so taking every d-th row costs no coalescing.
+// Input maps are consumed four at a time (K chunk = 4*k*k); the matching slice of the packed
+// weights is staged beside the tile.
+//
+// MFMA operand roles: A = weights (16 output maps x 4 K values), B = input (4 K values x 16
+// pixels), D = 16 maps x 16 pixels.  Lane l supplies A[m = l%16][kk = l/16] and
+// B[kk = l/16][pixel = l%16] and receives D[m = 4*(l/16) + r][pixel = l%16], r = 0..3, so each
+// store instruction writes 64-byte runs of consecutive pixels of one map.
+#include "sk_kernels.h"
+
+namespace sk {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+constexpr int CONV_TX = 64;   // output columns per workgroup
+constexpr int CONV_CC = 4;    // input maps per K chunk
+
+template <int NT, int RW>
+__global__ __launch_bounds__(256) void conv_f32_kernel(ConvF32Args a, int tiles_hi, int tiles_lo,
+                                                       int rem, int nblocks)
+{
+    extern __shared__ float smem[];
+    constexpr int R = 4 * RW, WN = NT * 16;
+    const int k = a.k, d = a.d, kk2 = k * k;
+    const int RR = R + k - 1, PW = CONV_TX + (k - 1) * d, PITCH = PW;
+    const int KC = CONV_CC * kk2;
+    float *xs = smem;
+    float *ws = xs + CONV_CC * RR * PITCH;
+    int *koff = reinterpret_cast<int *>(ws + KC * WN);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l16 = lane & 15, g = lane >> 4;
+
+    // blockIdx.y enumerates (row phase py, row tile ty): phases below `rem` have tiles_hi tiles
+    int py, ty;
+    {
+        const int by = blockIdx.y;
+        if (by < rem * tiles_hi) {
+            py = by / tiles_hi;
+            ty = by - py * tiles_hi;
+        } else {
+            const int b2 = by - rem * tiles_hi;
+            py = rem + b2 / tiles_lo;
+            ty = b2 % tiles_lo;
+        }
+    }
+    const int b = blockIdx.z / nblocks, nb = blockIdx.z - b * nblocks;
+    const int x0 = blockIdx.x * CONV_TX;
+
+    for (int q = tid; q < KC; q += 256) {
+        const int c = q / kk2, r = q - c * kk2;
+        const int i = r / k, j = r - i * k;
+        koff[q] = (c * RR + i) * PITCH + j * d;
+    }
+
+    floatx4 acc[RW][4][NT];
+#pragma unroll
+    for (int rw = 0; rw < RW; ++rw)
+#pragma unroll
+        for (int xt = 0; xt < 4; ++xt)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) acc[rw][xt][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    const long plane = (long)a.H * a.W;
+    const float *xb = a.x + (long)b * a.c_in * plane;
+    const int c_pad = (a.c_in + CONV_CC - 1) / CONV_CC * CONV_CC;
+
+    for (int c0 = 0; c0 < c_pad; c0 += CONV_CC) {
+        __syncthreads();
+        // stage the input tile: tile row t of map c holds input row py + d*(ty*R + t) - in_off
+        for (int rowid = wave; rowid < CONV_CC * RR; rowid += 4) {
+            const int cl = rowid / RR, t = rowid - cl * RR;
+            const int c = c0 + cl;
+            const int gy = py + d * (ty * R + t) - a.in_off;
+            const bool rowok = (c < a.c_in) && gy >= 0 && gy < a.H;
+            const float *src = xb + (long)c * plane + (long)gy * a.W;
+            float *dst = xs + rowid * PITCH;
+            for (int xc = lane; xc < PW; xc += 64) {
+                const int gx = x0 + xc - a.in_off;
+                float v = 0.f;
+                if (rowok && gx >= 0 && gx < a.W) v = src[gx];
+                dst[xc] = v;
+            }
+        }
+        // stage the weight slice: K rows [c0*k*k, +KC), map columns [nb*WN, +WN)
+        for (int q = tid; q < KC * WN; q += 256) {
+            const int r = q / WN, cn = q - r * WN;
+            const int col = nb * WN + cn;
+            ws[q] = (col < a.n_pad) ? a.wp[(long)(c0 * kk2 + r) * a.n_pad + col] : 0.f;
+        }
+        __syncthreads();
+
+        for (int kk = 0; kk < KC; kk += 4) {
+            const int ko = koff[kk + g];
+            float av[NT];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) av[nt] = ws[(kk + g) * WN + nt * 16 + l16];
+#pragma unroll
+            for (int rw = 0; rw < RW; ++rw) {
+                const float *xrow = xs + ko + (wave * RW + rw) * PITCH + l16;
+#pragma unroll
+                for (int xt = 0; xt < 4; ++xt) {
+                    const float bv = xrow[xt * 16];
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
+                        acc[rw][xt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[nt], bv, acc[rw][xt][nt], 0, 0, 0);
+                }
+            }
+        }
+    }
+
+    // epilogue: bias, ReLU, optional mask, predicated store
+#pragma unroll
+    for (int rw = 0; rw < RW; ++rw) {
+        const int oy = py + d * (ty * R + wave * RW + rw);
+        if (oy >= a.Ho) continue;
+#pragma unroll
+        for (int xt = 0; xt < 4; ++xt) {
+            const int ox = x0 + xt * 16 + l16;
+            if (ox >= a.Wo) continue;
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const int o = nb * WN + nt * 16 + 4 * g + r4;
+                    if (o >= a.c_out) continue;
+                    float v = acc[rw][xt][nt][r4];
+                    if (a.bias) v += a.bias[o];
+                    if (a.relu) v = v > 0.f ? v : 0.f;
+                    const long idx = (((long)b * a.out_maps + o + a.o_off) * a.OH + (long)oy * a.oy_mul + a.oy_off) * a.OW +
+                                     (long)ox * a.ox_mul + a.ox_off;
+                    if (a.mask && !(a.mask[idx] > 0.f)) v = 0.f;
+                    a.y[idx] = v;
+                }
+            }
+        }
+    }
+}
+
+template <int NT, int RW>
+static hipError_t launch_conv_f32_t(const ConvF32Args &a, hipStream_t stream)
+{
+    constexpr int R = 4 * RW, WN = NT * 16;
+    const int k = a.k, d = a.d;
+    const int RR = R + k - 1, PW = CONV_TX + (k - 1) * d;
+    const int KC = CONV_CC * k * k;
+    const size_t smem = sizeof(float) * ((size_t)CONV_CC * RR * PW + (size_t)KC * WN) + sizeof(int) * KC;
+    if (smem > 150 * 1024) return hipErrorInvalidValue;
+    static bool attr_set = false;
+    if (smem > 48 * 1024 && !attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_f32_kernel<NT, RW>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    // row phases: phase py has ceil((Ho - py)/d) rows
+    const int q = a.Ho / d, rem = a.Ho % d;
+    const int tiles_hi = (q + 1 + R - 1) / R, tiles_lo = (q + R - 1) / R;
+    const int gy = rem * tiles_hi + (d - rem) * tiles_lo;
+    const int nblocks = (a.n_pad / 16 + NT - 1) / NT;
+    dim3 grid((a.Wo + CONV_TX - 1) / CONV_TX, gy, a.n * nblocks);
+    if (grid.x == 0 || gy <= 0 || grid.z == 0 || gy > 65535 || grid.z > 65535) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((conv_f32_kernel<NT, RW>), grid, dim3(256), smem, stream, a, tiles_hi,
+                       tiles_lo > 0 ? tiles_lo : 1, rem, nblocks);
+    return hipGetLastError();
+}
+
+hipError_t launch_conv_f32(const ConvF32Args &a, hipStream_t stream)
+{
+    if (a.n_pad % 16 != 0 || a.c_out > a.n_pad || a.k < 1 || a.d < 1 || a.Ho < 1 || a.Wo < 1)
+        return hipErrorInvalidValue;
+    const int tiles = a.n_pad / 16;
+    if (tiles == 1) return launch_conv_f32_t<1, 2>(a, stream);
+    if (tiles == 2) return launch_conv_f32_t<2, 2>(a, stream);
+    const int pad3 = (tiles + 2) / 3 * 3, pad4 = (tiles + 3) / 4 * 4;
+    if (pad3 < pad4) return launch_conv_f32_t<3, 2>(a, stream);
+    return launch_conv_f32_t<4, 2>(a, stream);
+}
+
+// ------------------------------------------------------------------------------------------------
+__global__ void pack_weights_f32_kernel(const float *w, float *wp, int c_out, int c_in, int k,
+                                        int flip_transpose, int rows, int n_pad)
+{
+    const long total = (long)rows * n_pad;
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
+        const int col = (int)(q % n_pad), row = (int)(q / n_pad);
+        const int j = row % k, i = (row / k) % k, m = row / (k * k);   // m = input map of this GEMM
+        float v = 0.f;
+        if (!flip_transpose) {
+            if (m < c_in && col < c_out) v = w[(((long)col * c_in + m) * k + i) * k + j];
+        } else {
+            if (m < c_out && col < c_in) v = w[(((long)m * c_in + col) * k + (k - 1 - i)) * k + (k - 1 - j)];
+        }
+        wp[q] = v;
+    }
+}
+
+hipError_t launch_pack_weights_f32(const float *w_oihw, float *wp, int c_out, int c_in, int k,
+                                   int flip_transpose, int rows, int n_pad, hipStream_t stream)
+{
+    const long total = (long)rows * n_pad;
+    const int blocks = (int)((total + 255) / 256 < 1024 ? (total + 255) / 256 : 1024);
+    hipLaunchKernelGGL(pack_weights_f32_kernel, dim3(blocks), dim3(256), 0, stream, w_oihw, wp, c_out,
+                       c_in, k, flip_transpose, rows, n_pad);
+    return hipGetLastError();
+}
+
+}  // namespace sk

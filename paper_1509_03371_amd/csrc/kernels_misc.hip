@@ -1,0 +1,310 @@
+// HBM-bound layers of the SK-Net / U-Net path for gfx950: mirror padding, max pooling with
+// kernel stride (forward with tap codes, gather-form backward), per-pixel softmax and softmax
+// loss, SGD, crop-and-place copy.  One element per thread, x fastest, so that a 64-lane
+// wavefront reads and writes consecutive addresses.
+#include "sk_kernels.h"
+
+namespace sk {
+
+static inline int grid_for(long total, int block = 256, int cap = 1 << 20)
+{
+    long b = (total + block - 1) / block;
+    if (b < 1) b = 1;
+    return (int)(b < cap ? b : cap);
+}
+
+// ---- mirror padding (Section 1.3) ---------------------------------------------------------------
+__device__ __forceinline__ int mirror_index(int t, int len, int mode)
+{
+    if (len == 1) return 0;
+    if (mode == 0) {                       // reflect: ... 2 1 | 0 1 2 ... L-1 | L-2 L-3 ...
+        const int period = 2 * (len - 1);
+        t %= period;
+        if (t < 0) t += period;
+        return t < len ? t : period - t;
+    }
+    const int period = 2 * len;            // symmetric: ... 1 0 | 0 1 ... L-1 | L-1 L-2 ...
+    t %= period;
+    if (t < 0) t += period;
+    return t < len ? t : period - 1 - t;
+}
+
+__global__ void mirror_pad_f32_kernel(const float *in, float *out, int planes, int h, int w, int top,
+                                      int left, int ho, int wo, int mode)
+{
+    const long total = (long)planes * ho * wo;
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
+        const int x = (int)(q % wo);
+        const long t = q / wo;
+        const int y = (int)(t % ho);
+        const long p = t / ho;
+        out[q] = in[(p * h + mirror_index(y - top, h, mode)) * w + mirror_index(x - left, w, mode)];
+    }
+}
+
+hipError_t launch_mirror_pad_f32(const float *in, float *out, int planes, int h, int w, int top,
+                                 int left, int ho, int wo, int mode, hipStream_t stream)
+{
+    const long total = (long)planes * ho * wo;
+    hipLaunchKernelGGL(mirror_pad_f32_kernel, dim3(grid_for(total)), dim3(256), 0, stream, in, out,
+                       planes, h, w, top, left, ho, wo, mode);
+    return hipGetLastError();
+}
+
+// ---- max pooling with kernel stride d and layer stride s (Section 5.2.1) --------------------------
+__global__ void maxpool_f32_kernel(const float *x, float *y, uint8_t *tap, int planes, int H, int W,
+                                   int Ho, int Wo, int k, int d, int s)
+{
+    const long total = (long)planes * Ho * Wo;
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
+        const int xx = (int)(q % Wo);
+        const long t = q / Wo;
+        const int yy = (int)(t % Ho);
+        const long p = t / Ho;
+        const float *src = x + (p * H + (long)s * yy) * W + (long)s * xx;
+        float best = src[0];
+        int code = 0;
+        for (int i = 0; i < k; ++i)
+            for (int j = 0; j < k; ++j) {
+                const float v = src[(long)i * d * W + j * d];
+                if (v > best) {            // strictly greater: the first maximum wins
+                    best = v;
+                    code = i * k + j;
+                }
+            }
+        y[q] = best;
+        if (tap) tap[q] = (uint8_t)code;
+    }
+}
+
+hipError_t launch_maxpool_f32(const float *x, float *y, uint8_t *tap, int planes, int H, int W,
+                              int Ho, int Wo, int k, int d, int s, hipStream_t stream)
+{
+    const long total = (long)planes * Ho * Wo;
+    hipLaunchKernelGGL(maxpool_f32_kernel, dim3(grid_for(total)), dim3(256), 0, stream, x, y, tap, planes,
+                       H, W, Ho, Wo, k, d, s);
+    return hipGetLastError();
+}
+
+// Gather form of the pool gradient: input sample (u, v) can only have won the windows whose
+// output sits at (u - i*d, v - j*d); it collects dY from those whose recorded tap is (i, j).
+// No atomics, so the result does not depend on scheduling.
+__global__ void maxpool_bwd_f32_kernel(const float *dy, const uint8_t *tap, const float *relu_src,
+                                       float *dx, int planes, int H, int W, int Ho, int Wo, int k, int d)
+{
+    const long total = (long)planes * H * W;
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
+        const int v = (int)(q % W);
+        const long t = q / W;
+        const int u = (int)(t % H);
+        const long p = t / H;
+        float acc = 0.f;
+        for (int i = 0; i < k; ++i) {
+            const int yy = u - i * d;
+            if (yy < 0 || yy >= Ho) continue;
+            for (int j = 0; j < k; ++j) {
+                const int xx = v - j * d;
+                if (xx < 0 || xx >= Wo) continue;
+                const long o = (p * Ho + yy) * Wo + xx;
+                if (tap[o] == i * k + j) acc += dy[o];
+            }
+        }
+        if (relu_src && !(relu_src[q] > 0.f)) acc = 0.f;
+        dx[q] = acc;
+    }
+}
+
+hipError_t launch_maxpool_bwd_f32(const float *dy, const uint8_t *tap, const float *relu_src,
+                                  float *dx, int planes, int H, int W, int Ho, int Wo, int k, int d,
+                                  hipStream_t stream)
+{
+    const long total = (long)planes * H * W;
+    hipLaunchKernelGGL(maxpool_bwd_f32_kernel, dim3(grid_for(total)), dim3(256), 0, stream, dy, tap,
+                       relu_src, dx, planes, H, W, Ho, Wo, k, d);
+    return hipGetLastError();
+}
+
+__global__ void tap_to_index_kernel(const uint8_t *tap, int32_t *idx, int planes, int Ho, int Wo, int W,
+                                    int k, int d, int s)
+{
+    const long total = (long)planes * Ho * Wo;
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
+        const int xx = (int)(q % Wo);
+        const int yy = (int)((q / Wo) % Ho);
+        const int code = tap[q], i = code / k, j = code - i * k;
+        idx[q] = (s * yy + i * d) * W + s * xx + j * d;
+    }
+}
+
+hipError_t launch_tap_to_index(const uint8_t *tap, int32_t *idx, int planes, int Ho, int Wo, int W,
+                               int k, int d, int s, hipStream_t stream)
+{
+    const long total = (long)planes * Ho * Wo;
+    hipLaunchKernelGGL(tap_to_index_kernel, dim3(grid_for(total)), dim3(256), 0, stream, tap, idx, planes,
+                       Ho, Wo, W, k, d, s);
+    return hipGetLastError();
+}
+
+// ---- per-pixel softmax over the class maps ----------------------------------------------------------
+__global__ void softmax_f32_kernel(const float *z, float *p, int n, int classes, int hw)
+{
+    const long total = (long)n * hw;
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
+        const long b = q / hw, pix = q - b * hw;
+        const float *zp = z + b * classes * hw + pix;
+        float m = zp[0];
+        for (int c = 1; c < classes; ++c) m = fmaxf(m, zp[(long)c * hw]);
+        float sum = 0.f;
+        for (int c = 0; c < classes; ++c) sum += expf(zp[(long)c * hw] - m);
+        const float inv = 1.f / sum;
+        float *pp = p + b * classes * hw + pix;
+        for (int c = 0; c < classes; ++c) pp[(long)c * hw] = expf(zp[(long)c * hw] - m) * inv;
+    }
+}
+
+hipError_t launch_softmax_f32(const float *z, float *p, int n, int classes, int hw, hipStream_t stream)
+{
+    hipLaunchKernelGGL(softmax_f32_kernel, dim3(grid_for((long)n * hw)), dim3(256), 0, stream, z, p, n,
+                       classes, hw);
+    return hipGetLastError();
+}
+
+// ---- softmax loss (Section 4.3): mean over all pixels of -log p_label, and its gradient ----------------
+constexpr int LOSS_BLOCK = 256;
+constexpr int LOSS_MAX_BLOCKS = 1024;
+
+int softmax_loss_partials(long pixels)
+{
+    long b = (pixels + LOSS_BLOCK - 1) / LOSS_BLOCK;
+    return (int)(b < LOSS_MAX_BLOCKS ? (b < 1 ? 1 : b) : LOSS_MAX_BLOCKS);
+}
+
+__device__ __forceinline__ float block_sum(float v, float *sh)
+{
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) sh[wave] = v;
+    __syncthreads();
+    float r = 0.f;
+    if (threadIdx.x == 0)
+        for (int w = 0; w < (int)(blockDim.x >> 6); ++w) r += sh[w];
+    __syncthreads();
+    return r;   // valid on thread 0
+}
+
+__global__ void softmax_loss_f32_kernel(const float *z, const int32_t *labels, float *dz, float *partial,
+                                        int n, int classes, int hw)
+{
+    __shared__ float sh[LOSS_BLOCK / 64];
+    const long total = (long)n * hw;
+    const float invP = 1.f / (float)total;
+    float local = 0.f;
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
+        const long b = q / hw, pix = q - b * hw;
+        const float *zp = z + b * classes * hw + pix;
+        float m = zp[0];
+        for (int c = 1; c < classes; ++c) m = fmaxf(m, zp[(long)c * hw]);
+        float sum = 0.f;
+        for (int c = 0; c < classes; ++c) sum += expf(zp[(long)c * hw] - m);
+        const int lab = labels[q];
+        local -= zp[(long)lab * hw] - m - logf(sum);
+        const float inv = 1.f / sum;
+        float *gp = dz + b * classes * hw + pix;
+        for (int c = 0; c < classes; ++c)
+            gp[(long)c * hw] = (expf(zp[(long)c * hw] - m) * inv - (c == lab ? 1.f : 0.f)) * invP;
+    }
+    const float s = block_sum(local, sh);
+    if (threadIdx.x == 0) partial[blockIdx.x] = s;
+}
+
+__global__ void loss_finish_kernel(const float *partial, int count, float scale, float *loss)
+{
+    __shared__ float sh[LOSS_BLOCK / 64];
+    float v = 0.f;
+    for (int q = threadIdx.x; q < count; q += blockDim.x) v += partial[q];
+    const float s = block_sum(v, sh);
+    if (threadIdx.x == 0) *loss = s * scale;
+}
+
+hipError_t launch_softmax_loss_f32(const float *z, const int32_t *labels, float *dz, float *loss,
+                                   float *partial, int n, int classes, int hw, hipStream_t stream)
+{
+    const long pixels = (long)n * hw;
+    const int blocks = softmax_loss_partials(pixels);
+    hipLaunchKernelGGL(softmax_loss_f32_kernel, dim3(blocks), dim3(LOSS_BLOCK), 0, stream, z, labels, dz,
+                       partial, n, classes, hw);
+    hipLaunchKernelGGL(loss_finish_kernel, dim3(1), dim3(LOSS_BLOCK), 0, stream, partial, blocks,
+                       1.f / (float)pixels, loss);
+    return hipGetLastError();
+}
+
+// ---- SGD ---------------------------------------------------------------------------------------------
+__global__ void sgd_f32_kernel(float *w, const float *dw, float *v, long count, float lr, float mu, float wd)
+{
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < count; q += (long)gridDim.x * blockDim.x) {
+        const float g = dw[q] + wd * w[q];
+        const float vel = (v ? mu * v[q] : 0.f) + lr * g;
+        if (v) v[q] = vel;
+        w[q] -= vel;
+    }
+}
+
+hipError_t launch_sgd_f32(float *w, const float *dw, float *v, long count, float lr, float mu, float wd,
+                          hipStream_t stream)
+{
+    hipLaunchKernelGGL(sgd_f32_kernel, dim3(grid_for(count, 256, 1024)), dim3(256), 0, stream, w, dw, v,
+                       count, lr, mu, wd);
+    return hipGetLastError();
+}
+
+// ---- crop-and-place copy (the two halves of MergeCrop, Section 5.3.1) -----------------------------------
+__global__ void crop_copy_f32_kernel(const float *in, float *out, int n, int maps, int hi, int wi,
+                                     int out_maps, int o_off, int ho, int wo, int oy, int ox)
+{
+    const long total = (long)n * maps * ho * wo;
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
+        const int x = (int)(q % wo);
+        long t = q / wo;
+        const int y = (int)(t % ho);
+        t /= ho;
+        const int c = (int)(t % maps);
+        const long b = t / maps;
+        out[((b * out_maps + o_off + c) * ho + y) * wo + x] = in[((b * maps + c) * hi + y + oy) * wi + x + ox];
+    }
+}
+
+hipError_t launch_crop_copy_f32(const float *in, float *out, int n, int maps, int hi, int wi,
+                                int out_maps, int o_off, int ho, int wo, int oy, int ox,
+                                hipStream_t stream)
+{
+    const long total = (long)n * maps * ho * wo;
+    hipLaunchKernelGGL(crop_copy_f32_kernel, dim3(grid_for(total)), dim3(256), 0, stream, in, out, n, maps,
+                       hi, wi, out_maps, o_off, ho, wo, oy, ox);
+    return hipGetLastError();
+}
+
+// g[q] = act[q] > 0 ? g[q] : 0   (ReLU backward where no producer kernel could fuse it)
+__global__ void relu_mask_f32_kernel(float *g, const float *act, long count)
+{
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < count; q += (long)gridDim.x * blockDim.x)
+        if (!(act[q] > 0.f)) g[q] = 0.f;
+}
+
+hipError_t launch_relu_mask_f32(float *g, const float *act, long count, hipStream_t stream)
+{
+    hipLaunchKernelGGL(relu_mask_f32_kernel, dim3(grid_for(count)), dim3(256), 0, stream, g, act, count);
+    return hipGetLastError();
+}
+
+__global__ void fill_f32_kernel(float *p, float v, long count)
+{
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < count; q += (long)gridDim.x * blockDim.x) p[q] = v;
+}
+
+hipError_t launch_fill_f32(float *p, float v, long count, hipStream_t stream)
+{
+    hipLaunchKernelGGL(fill_f32_kernel, dim3(grid_for(count, 256, 4096)), dim3(256), 0, stream, p, v, count);
+    return hipGetLastError();
+}
+
+}  // namespace sk

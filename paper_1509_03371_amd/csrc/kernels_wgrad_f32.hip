@@ -1,0 +1,218 @@
+// Weight and bias gradient of the SK convolution, fp32, MFMA 16x16x4 fp32 (gfx950).
+//
+//   dW[o][c][i][j] = sum_{b,y,x} dY[b,o,y,x] * X[b,c,y+i*d,x+j*d]        db[o] = sum dY[b,o,y,x]
+//
+// GEMM view: the paper's forward GEMM (Section 5.5) transposed: M = f_out, N = f_in*k*k, and the
+// reduction runs over all output pixels.  The result is tiny (f_out x f_in*k*k) and the reduction
+// is huge, so the pixels are split over a persistent grid: each workgroup walks over row segments
+// (one output row, 64 columns), stages that segment of dY for all output maps and the k input
+// rows it touches for all input maps in LDS, and accumulates a private copy of dW in MFMA
+// accumulators.  The copies are written to scratch and summed by a second kernel in a fixed order,
+// so the result is reproducible (no float atomics).
+//
+// MFMA roles: A[m = output map][kk = pixel] = dY, B[kk = pixel][n = (c,i,j)] = X shifted by the
+// tap, D[m][n] = dW laid out exactly as OIHW.  Wave w of a workgroup owns MB row tiles (16 output
+// maps each) times NB column tiles (16 (c,i,j) triples each); blockIdx.y selects further groups.
+#include "sk_kernels.h"
+
+namespace sk {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+constexpr int WG_SEG = 64;          // output pixels per segment
+constexpr int WG_DYP = WG_SEG + 4;  // LDS pitch of a dY row
+constexpr int WG_MAX_BLOCKS = 512;
+
+struct WgradArgs {
+    const float *x, *dy;
+    float *scratch;
+    int n, c_in, H, W, c_out, k, d, Ho, Wo;
+    int MTo, NTk;          // 16-wide tiles over output maps / over (c,i,j)
+    int xsegs, total_segs;
+    int xpitch;            // LDS pitch of an input row
+};
+
+template <int MB, int NB>
+__global__ __launch_bounds__(256) void wgrad_f32_kernel(WgradArgs a)
+{
+    extern __shared__ float smem[];
+    const int k = a.k, d = a.d, K = a.c_in * k * k;
+    const int m_rows = a.MTo * 16;
+    float *dys = smem;                                   // [m_rows][WG_DYP]
+    float *xs = dys + m_rows * WG_DYP;                   // [c_in*k][xpitch]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l16 = lane & 15, g = lane >> 4;
+    const int PW = WG_SEG + (k - 1) * d;
+
+    // tile groups: blockIdx.y = mgroup * ngroups + ngroup
+    const int ngroups = (a.NTk + 4 * NB - 1) / (4 * NB);
+    const int mgroup = blockIdx.y / ngroups, ngroup = blockIdx.y - mgroup * ngroups;
+    const int mo0 = mgroup * MB;
+    // column tiles of this wave: nk = (ngroup*NB + q)*4 + wave
+    int xoff[NB];
+#pragma unroll
+    for (int q = 0; q < NB; ++q) {
+        const int nk = (ngroup * NB + q) * 4 + wave;
+        const int cij = nk * 16 + l16;
+        int off = 0;
+        if (nk < a.NTk && cij < K) {
+            const int c = cij / (k * k), r = cij - c * k * k, i = r / k, j = r - i * k;
+            off = (c * k + i) * a.xpitch + j * d;
+        }
+        xoff[q] = off + g;
+    }
+    floatx4 acc[MB][NB];
+#pragma unroll
+    for (int m = 0; m < MB; ++m)
+#pragma unroll
+        for (int q = 0; q < NB; ++q) acc[m][q] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    const long xplane = (long)a.H * a.W, yplane = (long)a.Ho * a.Wo;
+    for (int seg = blockIdx.x; seg < a.total_segs; seg += gridDim.x) {
+        const int xs_i = seg % a.xsegs;
+        const int t = seg / a.xsegs;
+        const int y = t % a.Ho, b = t / a.Ho;
+        const int x0 = xs_i * WG_SEG;
+        __syncthreads();
+        // dY rows of this segment (zero beyond the map and for padded output maps)
+        for (int row = wave; row < m_rows; row += 4) {
+            float v = 0.f;
+            if (row < a.c_out && x0 + lane < a.Wo) v = a.dy[((long)b * a.c_out + row) * yplane + (long)y * a.Wo + x0 + lane];
+            dys[row * WG_DYP + lane] = v;
+        }
+        // input rows y + i*d for every map
+        for (int row = wave; row < a.c_in * k; row += 4) {
+            const int c = row / k, i = row - c * k;
+            const float *src = a.x + ((long)b * a.c_in + c) * xplane + (long)(y + i * d) * a.W + x0;
+            float *dst = xs + row * a.xpitch;
+            for (int xc = lane; xc < PW; xc += 64) dst[xc] = (x0 + xc < a.W) ? src[xc] : 0.f;
+        }
+        __syncthreads();
+#pragma unroll 2
+        for (int p = 0; p < WG_SEG; p += 4) {
+            float av[MB];
+#pragma unroll
+            for (int m = 0; m < MB; ++m) {
+                const int row = (mo0 + m) * 16 + l16;
+                av[m] = (mo0 + m < a.MTo) ? dys[row * WG_DYP + p + g] : 0.f;
+            }
+#pragma unroll
+            for (int q = 0; q < NB; ++q) {
+                const float bv = xs[xoff[q] + p];
+#pragma unroll
+                for (int m = 0; m < MB; ++m)
+                    acc[m][q] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[m], bv, acc[m][q], 0, 0, 0);
+            }
+        }
+    }
+    // private copy -> scratch[blockIdx.x][o][cij]  (o < MTo*16, cij < NTk*16)
+    const long ncols = (long)a.NTk * 16;
+    float *dst = a.scratch + (long)blockIdx.x * m_rows * ncols;
+#pragma unroll
+    for (int m = 0; m < MB; ++m) {
+        if (mo0 + m >= a.MTo) continue;
+#pragma unroll
+        for (int q = 0; q < NB; ++q) {
+            const int nk = (ngroup * NB + q) * 4 + wave;
+            if (nk >= a.NTk) continue;
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4)
+                dst[((long)(mo0 + m) * 16 + 4 * g + r4) * ncols + nk * 16 + l16] = acc[m][q][r4];
+        }
+    }
+}
+
+// dW[o][cij] = sum over the private copies, in block order
+__global__ void wgrad_reduce_kernel(const float *scratch, float *dw, int copies, int c_out, int K,
+                                    int m_rows, int ncols)
+{
+    const long total = (long)c_out * K;
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
+        const int o = (int)(q / K), cij = (int)(q - (long)o * K);
+        float s = 0.f;
+        for (int cpy = 0; cpy < copies; ++cpy) s += scratch[((long)cpy * m_rows + o) * ncols + cij];
+        dw[q] = s;
+    }
+}
+
+// db[o] = sum over images and pixels of dY; one workgroup per output map, fixed summation order
+__global__ void bias_grad_kernel(const float *dy, float *db, int n, int c_out, long plane)
+{
+    __shared__ float sh[4];
+    const int o = blockIdx.x;
+    float v = 0.f;
+    for (int b = 0; b < n; ++b) {
+        const float *src = dy + ((long)b * c_out + o) * plane;
+        for (long q = threadIdx.x; q < plane; q += blockDim.x) v += src[q];
+    }
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) db[o] = sh[0] + sh[1] + sh[2] + sh[3];
+}
+
+static void wgrad_tiling(int c_out, int c_in, int k, int &MTo, int &NTk, int &MB, int &NB)
+{
+    MTo = (c_out + 15) / 16;
+    NTk = (c_in * k * k + 15) / 16;
+    MB = MTo == 1 ? 1 : (MTo % 3 == 0 ? 3 : 4);
+    NB = NTk >= 48 ? 12 : (NTk > 4 ? 4 : 1);
+}
+
+size_t wgrad_f32_scratch_floats(int c_out, int c_in, int k)
+{
+    int MTo, NTk, MB, NB;
+    wgrad_tiling(c_out, c_in, k, MTo, NTk, MB, NB);
+    return (size_t)WG_MAX_BLOCKS * MTo * 16 * NTk * 16;
+}
+
+template <int MB, int NB>
+static hipError_t launch_wgrad_t(const WgradArgs &a, size_t smem, int blocks, hipStream_t stream)
+{
+    static bool attr_set = false;
+    if (smem > 48 * 1024 && !attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_f32_kernel<MB, NB>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int mgroups = (a.MTo + MB - 1) / MB, ngroups = (a.NTk + 4 * NB - 1) / (4 * NB);
+    hipLaunchKernelGGL((wgrad_f32_kernel<MB, NB>), dim3(blocks, mgroups * ngroups), dim3(256), smem, stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_wgrad_f32(const float *x, const float *dy, float *dw, float *db, float *scratch,
+                            int n, int c_in, int H, int W, int c_out, int k, int d,
+                            hipStream_t stream)
+{
+    WgradArgs a;
+    a.x = x; a.dy = dy; a.scratch = scratch;
+    a.n = n; a.c_in = c_in; a.H = H; a.W = W; a.c_out = c_out; a.k = k; a.d = d;
+    a.Ho = H - (k - 1) * d; a.Wo = W - (k - 1) * d;
+    if (a.Ho < 1 || a.Wo < 1) return hipErrorInvalidValue;
+    int MB, NB;
+    wgrad_tiling(c_out, c_in, k, a.MTo, a.NTk, MB, NB);
+    a.xsegs = (a.Wo + WG_SEG - 1) / WG_SEG;
+    a.total_segs = a.xsegs * a.Ho * n;
+    const int PW = WG_SEG + (k - 1) * d;
+    a.xpitch = (PW + 31) / 32 * 32 + 4;
+    const size_t smem = sizeof(float) * ((size_t)a.MTo * 16 * WG_DYP + (size_t)c_in * k * a.xpitch);
+    if (smem > 150 * 1024) return hipErrorInvalidValue;
+    const int blocks = a.total_segs < WG_MAX_BLOCKS ? a.total_segs : WG_MAX_BLOCKS;
+    hipError_t e = hipErrorInvalidValue;
+#define SK_WG_CASE(mb, nb) if (MB == mb && NB == nb) e = launch_wgrad_t<mb, nb>(a, smem, blocks, stream);
+    SK_WG_CASE(1, 1) SK_WG_CASE(1, 4) SK_WG_CASE(1, 12)
+    SK_WG_CASE(3, 1) SK_WG_CASE(3, 4) SK_WG_CASE(3, 12)
+    SK_WG_CASE(4, 1) SK_WG_CASE(4, 4) SK_WG_CASE(4, 12)
+#undef SK_WG_CASE
+    if (e != hipSuccess) return e;
+    const int K = c_in * k * k;
+    const long total = (long)c_out * K;
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((int)((total + 255) / 256)), dim3(256), 0, stream, scratch, dw,
+                       blocks, c_out, K, a.MTo * 16, a.NTk * 16);
+    if (db)
+        hipLaunchKernelGGL(bias_grad_kernel, dim3(c_out), dim3(256), 0, stream, dy, db, n, c_out,
+                           (long)a.Ho * a.Wo);
+    return hipGetLastError();
+}
+
+}  // namespace sk

@@ -1,0 +1,77 @@
+// Launchers of the gfx950 kernels.  Internal to libsknet; everything here works on raw device
+// pointers and sizes.  All launchers enqueue on `stream` and return the hipError_t of the launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sk {
+
+// ---- implicit-GEMM SK convolution, fp32 activations, fp32 MFMA --------------------------------
+// Computes, for every image b, output map o and output position (y, x) in [0,Ho) x [0,Wo):
+//   acc = bias[o] + sum_{c,i,j} Wp[(c*k+i)*k+j][o] * X[b, c, y + i*d - in_off, x + j*d - in_off]
+// with X read as zero outside [0,H) x [0,W)  (in_off = 0: the forward "valid" SK convolution;
+// in_off = (k-1)*d with flipped, transposed weights: its data gradient),
+// then optional ReLU, then optional masking (acc = mask[...] > 0 ? acc : 0, same index as the
+// output), and stores it at
+//   Y[((b*out_maps + o + o_off)*OH + y*oy_mul + oy_off)*OW + x*ox_mul + ox_off].
+struct ConvF32Args {
+    const float *x;      // [n][c_in][H][W]
+    const float *wp;     // packed weights [c_pad*k*k][n_pad], c_pad = roundup(c_in, 4), n_pad = roundup(c_out, 16)
+    const float *bias;   // [n_pad] or nullptr
+    const float *mask;   // optional, indexed like y
+    float *y;
+    int n, c_in, H, W;
+    int c_out, n_pad;
+    int k, d, in_off;
+    int Ho, Wo;
+    int relu;
+    int out_maps, o_off, OH, OW, oy_mul, oy_off, ox_mul, ox_off;
+};
+hipError_t launch_conv_f32(const ConvF32Args &a, hipStream_t stream);
+
+// Pack OIHW fp32 master weights [c_out][c_in][k][k] into the K-major layout launch_conv_f32 reads.
+// flip_transpose = 0: Wp[(c*k+i)*k+j][o] = W[o][c][i][j]                       (forward)
+// flip_transpose = 1: Wp[(o*k+i)*k+j][c] = W[o][c][k-1-i][k-1-j]               (data gradient)
+// Rows/columns beyond the real extents are zero.  rows = roundup(in_maps,4)*k*k, cols = n_pad.
+hipError_t launch_pack_weights_f32(const float *w_oihw, float *wp, int c_out, int c_in, int k,
+                                   int flip_transpose, int rows, int n_pad, hipStream_t stream);
+
+// ---- weight / bias gradient of the SK convolution (fp32) ---------------------------------------
+// dW[o][c][i][j] = sum_{b,y,x} dY[b,o,y,x] * X[b,c,y+i*d,x+j*d];  db[o] = sum dY[b,o,:,:].
+// scratch must hold wgrad_scratch_floats(...) floats; the result is deterministic.
+size_t wgrad_f32_scratch_floats(int c_out, int c_in, int k);
+hipError_t launch_wgrad_f32(const float *x, const float *dy, float *dw, float *db, float *scratch,
+                            int n, int c_in, int H, int W, int c_out, int k, int d,
+                            hipStream_t stream);
+
+// ---- HBM-bound layers ---------------------------------------------------------------------------
+hipError_t launch_mirror_pad_f32(const float *in, float *out, int planes, int h, int w, int top,
+                                 int left, int ho, int wo, int mode, hipStream_t stream);
+// Y[p,y,x] = max_{i,j<k} X[p, s*y+i*d, s*x+j*d]; first maximum wins; tap (optional) = i*k+j.
+hipError_t launch_maxpool_f32(const float *x, float *y, uint8_t *tap, int planes, int H, int W,
+                              int Ho, int Wo, int k, int d, int s, hipStream_t stream);
+// dX[p,u,v] = sum over outputs whose recorded winner is (u,v) of dY; if relu_src != nullptr the
+// result is zeroed where relu_src[p,u,v] <= 0 (ReLU backward of the layer below, fused).  s = 1 only.
+hipError_t launch_maxpool_bwd_f32(const float *dy, const uint8_t *tap, const float *relu_src,
+                                  float *dx, int planes, int H, int W, int Ho, int Wo, int k, int d,
+                                  hipStream_t stream);
+hipError_t launch_softmax_f32(const float *z, float *p, int n, int classes, int hw, hipStream_t stream);
+// loss = -(1/P) sum log p_label, dz = (p - onehot)/P, P = n*hw; partial must hold
+// softmax_loss_partials(n*hw) floats.
+int softmax_loss_partials(long pixels);
+hipError_t launch_softmax_loss_f32(const float *z, const int32_t *labels, float *dz, float *loss,
+                                   float *partial, int n, int classes, int hw, hipStream_t stream);
+// g = dw + wd*w; v = mu*v + lr*g; w -= v   (v may be nullptr when mu = 0)
+hipError_t launch_sgd_f32(float *w, const float *dw, float *v, long count, float lr, float mu,
+                          float wd, hipStream_t stream);
+// out[b, o_off + c, y, x] = in[b, c, y + oy, x + ox] for c < maps (crop-and-place, MergeCrop halves)
+hipError_t launch_crop_copy_f32(const float *in, float *out, int n, int maps, int hi, int wi,
+                                int out_maps, int o_off, int ho, int wo, int oy, int ox,
+                                hipStream_t stream);
+// expand tap codes into flat offsets inside the input plane
+hipError_t launch_tap_to_index(const uint8_t *tap, int32_t *idx, int planes, int Ho, int Wo, int W,
+                               int k, int d, int s, hipStream_t stream);
+hipError_t launch_relu_mask_f32(float *g, const float *act, long count, hipStream_t stream);
+hipError_t launch_fill_f32(float *p, float v, long count, hipStream_t stream);
+
+}  // namespace sk

@@ -1,0 +1,536 @@
+// Host side of libsknet: handles, Algorithm 1, shape inference, workspace planning and the
+// per-layer launch sequences.  See include/sknet.h for the contract of every entry point.
+#include <hip/hip_runtime.h>
+
+#include <new>
+
+#include "sk_host.h"
+
+using namespace skh;
+
+// ================================================================================ SK-Net handle
+struct sknet {
+    std::vector<sk_layer> layers;
+    int c_in = 0, n_classes = 0, dtype = 0, pad_mode = 0;
+    std::vector<ConvParams> convs;
+    std::vector<int> conv_of_layer;   // layer -> conv index or -1
+    // plan
+    bool planned = false;
+    int n = 0, h = 0, w = 0, pad = 0, training = 0;
+    int pad_top = 0, pad_left = 0;
+    std::vector<Dims> dims;           // dims[0] padded image, dims[i+1] output of layer i
+    std::vector<float *> act;         // same indexing
+    std::vector<uint8_t *> tap;       // per layer (pools on a training plan), else nullptr
+    float *gbuf[2] = {nullptr, nullptr};
+    float *loss_partial = nullptr, *wgrad_scratch = nullptr;
+    bool forward_done = false, backward_done = false;
+    hipStream_t last_stream = nullptr;
+    const float *last_image = nullptr;
+    float *last_prob = nullptr;
+
+    void release_plan()
+    {
+        for (auto &p : act) free_dev(p);
+        act.clear();
+        for (auto &t : tap) {
+            if (t) (void)hipFree(t);
+            t = nullptr;
+        }
+        tap.clear();
+        free_dev(gbuf[0]); free_dev(gbuf[1]); free_dev(loss_partial); free_dev(wgrad_scratch);
+        for (auto &c : convs) release_conv(c);
+        planned = forward_done = backward_done = false;
+    }
+};
+
+namespace {
+
+// sizes of every map for an h x w image; shared by infer_shapes and plan
+sk_status infer(const sknet *net, int h, int w, int pad, std::vector<Dims> &dims, int *pt, int *pl)
+{
+    int v = 0;
+    bool stride1 = true;
+    for (const auto &l : net->layers) {
+        v += (l.k - 1) * l.d;
+        if (l.kind == SK_MAXPOOL && l.s != 1) stride1 = false;
+    }
+    Dims cur;
+    cur.c = net->c_in; cur.h = h; cur.w = w;
+    int top = 0, left = 0;
+    if (pad) {
+        if (!stride1) return fail(SK_ESHAPE, "context padding is only defined for nets whose pools have s = 1");
+        top = left = (v + 1) / 2;
+        const int bottom = v / 2;
+        const int limit_h = net->pad_mode == 0 ? h - 1 : h, limit_w = net->pad_mode == 0 ? w - 1 : w;
+        if (top > limit_h || top > limit_w || bottom > limit_h)
+            return fail(SK_ESHAPE, "mirror border %d does not fit a %dx%d image", top, h, w);
+        cur.h = h + v; cur.w = w + v;
+    }
+    if (h < 1 || w < 1) return fail(SK_ESHAPE, "image size %dx%d", h, w);
+    dims.clear();
+    dims.push_back(cur);
+    for (size_t i = 0; i < net->layers.size(); ++i) {
+        const sk_layer &l = net->layers[i];
+        const int shrink = (l.k - 1) * l.d;
+        if (l.kind == SK_CONV || l.s == 1) {
+            cur.h -= shrink; cur.w -= shrink;
+        } else {   // down-sampling pool, s = k, d = 1
+            if (cur.h % l.k != 0 || cur.w % l.k != 0)
+                return fail(SK_ESHAPE, "layer %zu: pooling needs w mod k = 0 (map %dx%d, k %d)", i, cur.h, cur.w, l.k);
+            cur.h /= l.k; cur.w /= l.k;
+        }
+        if (l.kind == SK_CONV) cur.c = l.c_out;
+        if (cur.h < 1 || cur.w < 1)
+            return fail(SK_ESHAPE, "layer %zu: map shrinks below one pixel", i);
+        dims.push_back(cur);
+    }
+    if (pt) *pt = top;
+    if (pl) *pl = left;
+    return SK_OK;
+}
+
+sk_status check_net(const sknet_t *net)
+{
+    if (!net) return fail(SK_EINVAL, "null net handle");
+    return SK_OK;
+}
+
+// forward step `step`: 0 = pad/copy, 1..L = layers, L+1 = softmax
+sk_status run_forward_step(sknet *net, int step, hipStream_t stream)
+{
+    const int L = (int)net->layers.size();
+    if (step == 0) {
+        const Dims &d0 = net->dims[0];
+        if (net->pad)
+            SK_HIP(sk::launch_mirror_pad_f32(net->last_image, net->act[0], net->n * net->c_in, net->h, net->w,
+                                             net->pad_top, net->pad_left, d0.h, d0.w, net->pad_mode, stream));
+        else
+            SK_HIP(hipMemcpyAsync(net->act[0], net->last_image, sizeof(float) * d0.count(net->n),
+                                  hipMemcpyDeviceToDevice, stream));
+        return SK_OK;
+    }
+    if (step <= L) {
+        const int li = step - 1;
+        const sk_layer &l = net->layers[li];
+        const Dims &in = net->dims[li], &out = net->dims[li + 1];
+        if (l.kind == SK_CONV) {
+            const ConvParams &c = net->convs[net->conv_of_layer[li]];
+            sk::ConvF32Args a = conv_args(c, net->act[li], net->n, in, l.d, l.relu, net->act[li + 1], out);
+            SK_HIP(sk::launch_conv_f32(a, stream));
+        } else {
+            SK_HIP(sk::launch_maxpool_f32(net->act[li], net->act[li + 1], net->tap[li], net->n * in.c, in.h, in.w,
+                                          out.h, out.w, l.k, l.d, l.s, stream));
+        }
+        return SK_OK;
+    }
+    const Dims &o = net->dims[L];
+    SK_HIP(sk::launch_softmax_f32(net->act[L], net->last_prob, net->n, o.c, o.h * o.w, stream));
+    return SK_OK;
+}
+
+}  // namespace
+
+// ================================================================================ host-only helpers
+extern "C" {
+
+const char *sknet_last_error(void) { return g_last_error.c_str(); }
+
+int64_t sknet_conv_flops(int64_t f_in, int64_t f_out, int64_t k, int64_t w_out)
+{
+    return f_out * w_out * w_out * (2 * f_in * k * k - 1);
+}
+
+sk_status sknet_convert_sw(const sw_layer *sw, int32_t n, int32_t w0_sw, sk_layer *sk_out, int32_t *n_out)
+{
+    if (!sw || !sk_out || !n_out || n < 1 || w0_sw < 1) return fail(SK_EINVAL, "convert_sw: bad arguments");
+    int d_temp = 1, w_sw = w0_sw, w_sk = w0_sw, written = 0;
+    for (int i = 0; i < n; ++i) {
+        const sw_layer &l = sw[i];
+        sk_layer o{};
+        if (l.kind == 0) {                       // convolution keeps k, takes the current kernel stride
+            if (l.k < 1) return fail(SK_ESHAPE, "layer %d: k < 1", i);
+            o.kind = SK_CONV; o.c_out = l.c_out; o.k = l.k; o.d = d_temp; o.s = 1; o.relu = l.relu;
+            w_sk -= (l.k - 1) * d_temp;
+            w_sw -= l.k - 1;
+        } else if (l.kind == 1) {                // down-sampling pool becomes a stride-1 SK pool
+            if (l.k < 1 || w_sw % l.k != 0 || l.k != l.s)
+                return fail(SK_ESHAPE, "layer %d: pooling needs w mod k = 0 and k = s (w=%d k=%d s=%d)", i, w_sw, l.k, l.s);
+            o.kind = SK_MAXPOOL; o.k = l.k; o.d = d_temp; o.s = 1;
+            w_sk -= (l.k - 1) * d_temp;
+            w_sw /= l.k;
+            d_temp *= l.k;
+        } else if (l.kind == 2) {                // inner product spans the whole remaining map
+            o.kind = SK_CONV; o.c_out = l.c_out; o.k = w_sw; o.d = d_temp; o.s = 1; o.relu = l.relu;
+            w_sk -= (w_sw - 1) * d_temp;
+            w_sw = 1;
+            d_temp = 1;
+        } else {
+            if (l.k > 1) return fail(SK_ESHAPE, "layer %d: only element-wise layers (k = 1) convert unchanged", i);
+            continue;
+        }
+        if (w_sk < 1 || w_sw < 1) return fail(SK_ESHAPE, "layer %d: map shrinks below one pixel", i);
+        sk_out[written++] = o;
+    }
+    if (d_temp != 1) return fail(SK_ESHAPE, "kernel stride is %d after the last layer; it must be 1", d_temp);
+    *n_out = written;
+    return SK_OK;
+}
+
+// ================================================================================ SK-Net
+sk_status sknet_create(const sk_layer *layers, int32_t n_layers, int32_t c_in, int32_t n_classes,
+                       sk_dtype dtype, int32_t pad_mode, sknet_t **out)
+{
+    if (!out) return fail(SK_EINVAL, "create: out is null");
+    *out = nullptr;
+    if (!layers || n_layers < 1 || c_in < 1 || n_classes < 1) return fail(SK_EINVAL, "create: bad arguments");
+    if (pad_mode != 0 && pad_mode != 1) return fail(SK_EINVAL, "create: pad_mode must be 0 or 1");
+    if (dtype != SK_F32) {
+        if (dtype == SK_BF16 || dtype == SK_F16) return fail(SK_EUNSUPPORTED, "create: only SK_F32 is built");
+        return fail(SK_EINVAL, "create: bad dtype");
+    }
+    sknet *net = new (std::nothrow) sknet;
+    if (!net) return fail(SK_ENOMEM, "create: out of host memory");
+    net->c_in = c_in; net->n_classes = n_classes; net->dtype = dtype; net->pad_mode = pad_mode;
+    int maps = c_in;
+    for (int i = 0; i < n_layers; ++i) {
+        const sk_layer &l = layers[i];
+        sk_status bad = SK_OK;
+        if (l.kind != SK_CONV && l.kind != SK_MAXPOOL) bad = fail(SK_EINVAL, "layer %d: bad kind", i);
+        else if (l.k < 1 || l.d < 1) bad = fail(SK_ESHAPE, "layer %d: k and d must be >= 1", i);
+        else if (l.k > 15) bad = fail(SK_EUNSUPPORTED, "layer %d: k > 15", i);
+        else if (l.kind == SK_CONV && (l.s != 1 || l.c_out < 1)) bad = fail(SK_ESHAPE, "layer %d: conv needs s = 1 and c_out >= 1", i);
+        else if (l.kind == SK_MAXPOOL && !(l.s == 1 || (l.s == l.k && l.d == 1)))
+            bad = fail(SK_ESHAPE, "layer %d: pool needs s = 1, or s = k with d = 1", i);
+        if (bad != SK_OK) {
+            delete net;
+            return bad;
+        }
+        net->layers.push_back(l);
+        if (l.kind == SK_CONV) {
+            ConvParams c;
+            c.c_in = maps; c.c_out = l.c_out; c.k = l.k;
+            c.w.assign((size_t)c.wcount(), 0.f);
+            c.b.assign((size_t)c.c_out, 0.f);
+            net->conv_of_layer.push_back((int)net->convs.size());
+            net->convs.push_back(std::move(c));
+            maps = l.c_out;
+        } else {
+            net->conv_of_layer.push_back(-1);
+        }
+    }
+    if (maps != n_classes) {
+        delete net;
+        return fail(SK_ESHAPE, "create: the last layer has %d maps but n_classes is %d", maps, n_classes);
+    }
+    *out = net;
+    return SK_OK;
+}
+
+void sknet_destroy(sknet_t *net)
+{
+    if (!net) return;
+    net->release_plan();
+    delete net;
+}
+
+sk_status sknet_context(const sknet_t *net, int32_t *v)
+{
+    SK_TRY(check_net(net));
+    if (!v) return fail(SK_EINVAL, "context: v is null");
+    int sum = 0;
+    for (const auto &l : net->layers) {
+        if (l.kind == SK_MAXPOOL && l.s != 1) return fail(SK_ESHAPE, "context is only defined when every pool has s = 1");
+        sum += (l.k - 1) * l.d;
+    }
+    *v = sum;
+    return SK_OK;
+}
+
+sk_status sknet_infer_shapes(const sknet_t *net, int32_t h, int32_t w, int32_t pad, int32_t *dims)
+{
+    SK_TRY(check_net(net));
+    if (!dims) return fail(SK_EINVAL, "infer_shapes: dims is null");
+    std::vector<Dims> d;
+    SK_TRY(infer(net, h, w, pad, d, nullptr, nullptr));
+    for (size_t i = 0; i < d.size(); ++i) {
+        dims[3 * i] = d[i].c; dims[3 * i + 1] = d[i].h; dims[3 * i + 2] = d[i].w;
+    }
+    return SK_OK;
+}
+
+sk_status sknet_num_convs(const sknet_t *net, int32_t *count)
+{
+    SK_TRY(check_net(net));
+    if (!count) return fail(SK_EINVAL, "num_convs: count is null");
+    *count = (int32_t)net->convs.size();
+    return SK_OK;
+}
+
+sk_status sknet_conv_shape(const sknet_t *net, int32_t conv_idx, int32_t *shape4)
+{
+    SK_TRY(check_net(net));
+    if (!shape4 || conv_idx < 0 || conv_idx >= (int)net->convs.size()) return fail(SK_EINVAL, "conv_shape: bad index");
+    const ConvParams &c = net->convs[conv_idx];
+    shape4[0] = c.c_out; shape4[1] = c.c_in; shape4[2] = c.k; shape4[3] = c.k;
+    return SK_OK;
+}
+
+sk_status sknet_set_weights(sknet_t *net, int32_t conv_idx, const float *w_host, const float *b_host)
+{
+    SK_TRY(check_net(net));
+    if (!w_host || conv_idx < 0 || conv_idx >= (int)net->convs.size()) return fail(SK_EINVAL, "set_weights: bad arguments");
+    ConvParams &c = net->convs[conv_idx];
+    std::memcpy(c.w.data(), w_host, sizeof(float) * c.wcount());
+    if (b_host) std::memcpy(c.b.data(), b_host, sizeof(float) * c.c_out);
+    if (net->planned) SK_TRY(upload_conv(c, net->training, net->last_stream));
+    return SK_OK;
+}
+
+sk_status sknet_get_weights(sknet_t *net, int32_t conv_idx, float *w_host, float *b_host)
+{
+    SK_TRY(check_net(net));
+    if (conv_idx < 0 || conv_idx >= (int)net->convs.size()) return fail(SK_EINVAL, "get_weights: bad index");
+    ConvParams &c = net->convs[conv_idx];
+    if (net->planned) {   // the device copy is the one SGD updates
+        SK_HIP(hipStreamSynchronize(net->last_stream));
+        SK_HIP(hipMemcpy(c.w.data(), c.w_dev, sizeof(float) * c.wcount(), hipMemcpyDeviceToHost));
+        std::vector<float> bp(c.n_pad);
+        SK_HIP(hipMemcpy(bp.data(), c.b_dev, sizeof(float) * c.n_pad, hipMemcpyDeviceToHost));
+        std::memcpy(c.b.data(), bp.data(), sizeof(float) * c.c_out);
+    }
+    if (w_host) std::memcpy(w_host, c.w.data(), sizeof(float) * c.wcount());
+    if (b_host) std::memcpy(b_host, c.b.data(), sizeof(float) * c.c_out);
+    return SK_OK;
+}
+
+sk_status sknet_plan(sknet_t *net, int32_t n, int32_t h, int32_t w, int32_t pad, int32_t training)
+{
+    SK_TRY(check_net(net));
+    if (n < 1) return fail(SK_EINVAL, "plan: n must be >= 1");
+    std::vector<Dims> dims;
+    int pt = 0, pl = 0;
+    SK_TRY(infer(net, h, w, pad, dims, &pt, &pl));
+    const int L = (int)net->layers.size();
+    if (training)
+        for (int i = 0; i < L; ++i)
+            if (net->layers[i].kind == SK_MAXPOOL && net->layers[i].s != 1)
+                return fail(SK_EUNSUPPORTED, "plan: training through a down-sampling pool is not built");
+    // keep the host masters (a planned net's masters may have been updated on the device)
+    if (net->planned)
+        for (int i = 0; i < (int)net->convs.size(); ++i) SK_TRY(sknet_get_weights(net, i, nullptr, nullptr));
+    net->release_plan();
+    net->n = n; net->h = h; net->w = w; net->pad = pad ? 1 : 0; net->training = training ? 1 : 0;
+    net->pad_top = pt; net->pad_left = pl;
+    net->dims = dims;
+    net->act.assign(L + 1, nullptr);
+    net->tap.assign(L, nullptr);
+    long max_count = 0;
+    sk_status st = SK_OK;
+    for (int i = 0; i <= L && st == SK_OK; ++i) {
+        st = alloc_f(&net->act[i], dims[i].count(n));
+        if (dims[i].count(n) > max_count) max_count = dims[i].count(n);
+    }
+    size_t scratch = 0;
+    for (int i = 0; i < L && st == SK_OK; ++i) {
+        const sk_layer &l = net->layers[i];
+        if (l.kind == SK_MAXPOOL && training) {
+            hipError_t e = hipMalloc(reinterpret_cast<void **>(&net->tap[i]), (size_t)dims[i + 1].count(n));
+            if (e != hipSuccess) st = fail(SK_ENOMEM, "plan: hipMalloc of a pool mask failed: %s", hipGetErrorString(e));
+        }
+        if (l.kind == SK_CONV) {
+            ConvParams &c = net->convs[net->conv_of_layer[i]];
+            st = alloc_conv(c, training != 0);
+            if (st == SK_OK) st = upload_conv(c, training != 0, nullptr);
+            const size_t s = sk::wgrad_f32_scratch_floats(c.c_out, c.c_in, c.k);
+            if (s > scratch) scratch = s;
+        }
+    }
+    if (st == SK_OK && training) {
+        st = alloc_f(&net->gbuf[0], max_count);
+        if (st == SK_OK) st = alloc_f(&net->gbuf[1], max_count);
+        if (st == SK_OK) st = alloc_f(&net->loss_partial, sk::softmax_loss_partials((long)n * dims[L].h * dims[L].w));
+        if (st == SK_OK) st = alloc_f(&net->wgrad_scratch, (long)scratch);
+    }
+    if (st != SK_OK) {
+        std::string keep = g_last_error;
+        net->release_plan();
+        g_last_error = keep;
+        return st;
+    }
+    net->planned = true;
+    net->last_stream = nullptr;
+    return SK_OK;
+}
+
+sk_status sknet_forward(sknet_t *net, const float *image_dev, float *prob_dev, void *hip_stream)
+{
+    SK_TRY(check_net(net));
+    if (!net->planned) return fail(SK_ESTATE, "forward: call sknet_plan first");
+    if (!image_dev || !prob_dev) return fail(SK_EINVAL, "forward: null buffer");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    net->last_stream = stream;
+    net->last_image = image_dev;
+    net->last_prob = prob_dev;
+    net->backward_done = false;
+    const int steps = (int)net->layers.size() + 2;
+    for (int s = 0; s < steps; ++s) SK_TRY(run_forward_step(net, s, stream));
+    net->forward_done = true;
+    return SK_OK;
+}
+
+sk_status sknet_backward(sknet_t *net, const int32_t *labels_dev, float *loss_dev, void *hip_stream)
+{
+    SK_TRY(check_net(net));
+    if (!net->planned || !net->training) return fail(SK_ESTATE, "backward: needs a training plan");
+    if (!net->forward_done) return fail(SK_ESTATE, "backward: run sknet_forward first");
+    if (!labels_dev || !loss_dev) return fail(SK_EINVAL, "backward: null buffer");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    net->last_stream = stream;
+    const int L = (int)net->layers.size(), n = net->n;
+    const Dims &o = net->dims[L];
+    float *gcur = net->gbuf[0], *gnext = net->gbuf[1];
+    SK_HIP(sk::launch_softmax_loss_f32(net->act[L], labels_dev, gcur, loss_dev, net->loss_partial, n, o.c,
+                                       o.h * o.w, stream));
+    if (net->layers[L - 1].kind == SK_CONV && net->layers[L - 1].relu)
+        SK_HIP(sk::launch_relu_mask_f32(gcur, net->act[L], o.count(n), stream));
+    for (int li = L - 1; li >= 0; --li) {
+        const sk_layer &l = net->layers[li];
+        const Dims &in = net->dims[li], &out = net->dims[li + 1];
+        // ReLU of the layer below acts on this layer's input: fuse its mask into whatever
+        // kernel produces the gradient of that input
+        const float *relu_src = (li > 0 && net->layers[li - 1].kind == SK_CONV && net->layers[li - 1].relu)
+                                    ? net->act[li] : nullptr;
+        if (l.kind == SK_CONV) {
+            ConvParams &c = net->convs[net->conv_of_layer[li]];
+            SK_HIP(sk::launch_wgrad_f32(net->act[li], gcur, c.dw, c.db, net->wgrad_scratch, n, in.c, in.h, in.w,
+                                        c.c_out, c.k, l.d, stream));
+            if (li == 0) break;   // nothing below needs the image gradient
+            sk::ConvF32Args a{};
+            a.x = gcur; a.wp = c.wp_bwd; a.bias = nullptr; a.mask = relu_src; a.y = gnext;
+            a.n = n; a.c_in = out.c; a.H = out.h; a.W = out.w;
+            a.c_out = in.c; a.n_pad = c.n_pad_bwd;
+            a.k = c.k; a.d = l.d; a.in_off = (c.k - 1) * l.d;
+            a.Ho = in.h; a.Wo = in.w; a.relu = 0;
+            a.out_maps = in.c; a.o_off = 0; a.OH = in.h; a.OW = in.w;
+            a.oy_mul = 1; a.oy_off = 0; a.ox_mul = 1; a.ox_off = 0;
+            SK_HIP(sk::launch_conv_f32(a, stream));
+        } else {
+            if (li == 0) break;
+            SK_HIP(sk::launch_maxpool_bwd_f32(gcur, net->tap[li], relu_src, gnext, n * in.c, in.h, in.w, out.h,
+                                              out.w, l.k, l.d, stream));
+        }
+        float *t = gcur; gcur = gnext; gnext = t;
+    }
+    net->backward_done = true;
+    return SK_OK;
+}
+
+sk_status sknet_sgd_step(sknet_t *net, float lr, float momentum, float weight_decay, void *hip_stream)
+{
+    SK_TRY(check_net(net));
+    if (!net->planned || !net->training || !net->backward_done)
+        return fail(SK_ESTATE, "sgd_step: needs a backward pass on a training plan");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    net->last_stream = stream;
+    for (auto &c : net->convs) {
+        SK_HIP(sk::launch_sgd_f32(c.w_dev, c.dw, momentum != 0.f ? c.vw : nullptr, c.wcount(), lr, momentum, weight_decay, stream));
+        SK_HIP(sk::launch_sgd_f32(c.b_dev, c.db, momentum != 0.f ? c.vb : nullptr, c.c_out, lr, momentum, weight_decay, stream));
+        SK_HIP(sk::launch_pack_weights_f32(c.w_dev, c.wp_fwd, c.c_out, c.c_in, c.k, 0, c.rows_fwd, c.n_pad, stream));
+        SK_HIP(sk::launch_pack_weights_f32(c.w_dev, c.wp_bwd, c.c_out, c.c_in, c.k, 1, c.rows_bwd, c.n_pad_bwd, stream));
+    }
+    return SK_OK;
+}
+
+sk_status sknet_get_grad(sknet_t *net, int32_t conv_idx, float *dw_host, float *db_host)
+{
+    SK_TRY(check_net(net));
+    if (conv_idx < 0 || conv_idx >= (int)net->convs.size()) return fail(SK_EINVAL, "get_grad: bad index");
+    if (!net->backward_done) return fail(SK_ESTATE, "get_grad: no backward pass yet");
+    ConvParams &c = net->convs[conv_idx];
+    SK_HIP(hipStreamSynchronize(net->last_stream));
+    if (dw_host) SK_HIP(hipMemcpy(dw_host, c.dw, sizeof(float) * c.wcount(), hipMemcpyDeviceToHost));
+    if (db_host) SK_HIP(hipMemcpy(db_host, c.db, sizeof(float) * c.c_out, hipMemcpyDeviceToHost));
+    return SK_OK;
+}
+
+sk_status sknet_get_activation(sknet_t *net, int32_t layer_idx, float *nchw_host)
+{
+    SK_TRY(check_net(net));
+    if (!nchw_host || layer_idx < -1 || layer_idx >= (int)net->layers.size()) return fail(SK_EINVAL, "get_activation: bad arguments");
+    if (!net->forward_done) return fail(SK_ESTATE, "get_activation: no forward pass yet");
+    SK_HIP(hipStreamSynchronize(net->last_stream));
+    const int i = layer_idx + 1;
+    SK_HIP(hipMemcpy(nchw_host, net->act[i], sizeof(float) * net->dims[i].count(net->n), hipMemcpyDeviceToHost));
+    return SK_OK;
+}
+
+sk_status sknet_get_pool_argmax(sknet_t *net, int32_t pool_idx, int32_t *idx_host)
+{
+    SK_TRY(check_net(net));
+    if (!idx_host || pool_idx < 0) return fail(SK_EINVAL, "get_pool_argmax: bad arguments");
+    if (!net->forward_done || !net->training) return fail(SK_ESTATE, "get_pool_argmax: needs a forward pass on a training plan");
+    int li = -1, seen = 0;
+    for (int i = 0; i < (int)net->layers.size(); ++i)
+        if (net->layers[i].kind == SK_MAXPOOL && seen++ == pool_idx) { li = i; break; }
+    if (li < 0) return fail(SK_EINVAL, "get_pool_argmax: the net has no pool %d", pool_idx);
+    const sk_layer &l = net->layers[li];
+    const Dims &in = net->dims[li], &out = net->dims[li + 1];
+    const long count = out.count(net->n);
+    int32_t *tmp = nullptr;
+    SK_HIP(hipMalloc(reinterpret_cast<void **>(&tmp), sizeof(int32_t) * (size_t)count));
+    hipError_t e = sk::launch_tap_to_index(net->tap[li], tmp, net->n * out.c, out.h, out.w, in.w, l.k, l.d, l.s, net->last_stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(net->last_stream);
+    if (e == hipSuccess) e = hipMemcpy(idx_host, tmp, sizeof(int32_t) * (size_t)count, hipMemcpyDeviceToHost);
+    (void)hipFree(tmp);
+    if (e != hipSuccess) return fail(SK_EDEVICE, "get_pool_argmax: %s", hipGetErrorString(e));
+    return SK_OK;
+}
+
+sk_status sknet_num_steps(const sknet_t *net, int32_t *count)
+{
+    SK_TRY(check_net(net));
+    if (!count) return fail(SK_EINVAL, "num_steps: count is null");
+    *count = (int32_t)net->layers.size() + 2;
+    return SK_OK;
+}
+
+sk_status sknet_step_name(const sknet_t *net, int32_t step, char *name, int32_t cap)
+{
+    SK_TRY(check_net(net));
+    const int L = (int)net->layers.size();
+    if (!name || cap < 1 || step < 0 || step > L + 1) return fail(SK_EINVAL, "step_name: bad arguments");
+    if (step == 0) snprintf(name, cap, "pad");
+    else if (step == L + 1) snprintf(name, cap, "softmax");
+    else {
+        const sk_layer &l = net->layers[step - 1];
+        if (l.kind == SK_CONV) snprintf(name, cap, "conv%d_k%d_d%d_o%d", step - 1, l.k, l.d, l.c_out);
+        else snprintf(name, cap, "pool%d_k%d_d%d_s%d", step - 1, l.k, l.d, l.s);
+    }
+    return SK_OK;
+}
+
+sk_status sknet_time_step(sknet_t *net, int32_t step, int32_t iters, void *hip_stream, float *avg_ms)
+{
+    SK_TRY(check_net(net));
+    if (!avg_ms || iters < 1 || step < 0 || step > (int)net->layers.size() + 1) return fail(SK_EINVAL, "time_step: bad arguments");
+    if (!net->forward_done) return fail(SK_ESTATE, "time_step: run sknet_forward first");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipEvent_t e0, e1;
+    SK_HIP(hipEventCreate(&e0));
+    SK_HIP(hipEventCreate(&e1));
+    sk_status st = run_forward_step(net, step, stream);   // warm-up
+    hipError_t e = hipEventRecord(e0, stream);
+    for (int i = 0; i < iters && st == SK_OK; ++i) st = run_forward_step(net, step, stream);
+    if (e == hipSuccess) e = hipEventRecord(e1, stream);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (st != SK_OK) return st;
+    if (e != hipSuccess) return fail(SK_EDEVICE, "time_step: %s", hipGetErrorString(e));
+    *avg_ms = ms / (float)iters;
+    return SK_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,371 @@
+// U-Net forward (paper Section 3.4 and its configuration table) on the same kernels as the SK
+// net: 3x3 convolutions are the SK convolution at d = 1, the 2x2 stride-2 up-convolution is four
+// 1x1 convolutions whose outputs interleave, MergeCrop is the up path written in place plus a
+// crop-and-place copy of the skip maps.  See include/sknet.h for the contract.
+#include <new>
+
+#include "sk_host.h"
+
+using namespace skh;
+
+namespace {
+
+struct UpParams {
+    int c_in = 0, c_out = 0;
+    std::vector<float> w, b;        // host master [c_in][c_out][2][2], [c_out]
+    float *w_dev = nullptr;         // same layout on the device
+    ConvParams tap[4];              // per (a, b): a 1x1 convolution with weight W1[o][c] = w[c][o][a][b]
+};
+
+struct Stage {
+    std::string name;
+    Dims dims;
+    float *buf = nullptr;
+};
+
+}  // namespace
+
+struct unet {
+    int c_in = 0, n_classes = 0, depth = 0, base = 0;
+    // parameters in forward order; kind 0 = conv (index into convs), 1 = up-convolution (index into ups)
+    struct Param { std::string name; int kind; int idx; };
+    std::vector<Param> params;
+    std::vector<ConvParams> convs;
+    std::vector<UpParams> ups;
+    // plan
+    bool planned = false, forward_done = false;
+    int n = 0, h_in = 0, w_in = 0;
+    std::vector<float *> buffers;            // every device activation buffer, for release
+    struct Op {
+        int kind;                            // 0 conv, 1 pool, 2 up-convolution, 3 crop copy
+        int param;                           // conv / up index
+        int relu;
+        const float *src;                    // nullptr = the caller's image
+        float *dst;
+        Dims in, out;                        // out.c = maps of the destination buffer
+        int o_off, crop;                     // map offset in dst; crop offset for kind 3
+        int src_maps;
+    };
+    std::vector<Op> ops;
+    std::vector<Stage> stages;
+    float *logits = nullptr;
+    Dims out_dims;
+    hipStream_t last_stream = nullptr;
+
+    void release_plan()
+    {
+        for (auto &p : buffers) free_dev(p);
+        buffers.clear();
+        ops.clear();
+        stages.clear();
+        for (auto &c : convs) release_conv(c);
+        for (auto &u : ups) {
+            free_dev(u.w_dev);
+            for (auto &t : u.tap) release_conv(t);
+        }
+        planned = forward_done = false;
+    }
+};
+
+namespace {
+
+sk_status check(const unet_t *net)
+{
+    if (!net) return fail(SK_EINVAL, "null U-Net handle");
+    return SK_OK;
+}
+
+// spatial sizes: every level two valid 3x3 convs, then a k = s = 2 pool; mirrored on the way up
+sk_status walk_sizes(const unet *net, int h, int w, int *ho, int *wo)
+{
+    for (int i = 0; i <= net->depth; ++i) {
+        h -= 4; w -= 4;
+        if (h < 1 || w < 1) return fail(SK_ESHAPE, "U-Net: map vanishes at level %d", i);
+        if (i < net->depth) {
+            if (h % 2 || w % 2) return fail(SK_ESHAPE, "U-Net: pooling needs an even map at level %d (got %dx%d)", i, h, w);
+            h /= 2; w /= 2;
+        }
+    }
+    for (int i = net->depth - 1; i >= 0; --i) {
+        h = 2 * h - 4; w = 2 * w - 4;
+        if (h < 1 || w < 1) return fail(SK_ESHAPE, "U-Net: map vanishes on the expanding path at level %d", i);
+    }
+    *ho = h; *wo = w;
+    return SK_OK;
+}
+
+sk_status upload_up(UpParams &u)
+{
+    for (int a = 0; a < 2; ++a)
+        for (int b = 0; b < 2; ++b) {
+            ConvParams &t = u.tap[a * 2 + b];
+            t.c_in = u.c_in; t.c_out = u.c_out; t.k = 1;
+            t.w.resize((size_t)u.c_in * u.c_out);
+            for (int c = 0; c < u.c_in; ++c)
+                for (int o = 0; o < u.c_out; ++o)
+                    t.w[(size_t)o * u.c_in + c] = u.w[(((size_t)c * u.c_out + o) * 2 + a) * 2 + b];
+            t.b = u.b;
+            SK_TRY(upload_conv(t, false, nullptr));
+        }
+    return SK_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+sk_status unet_create(int32_t c_in, int32_t n_classes, int32_t depth, int32_t base_ch, sk_dtype dtype, unet_t **out)
+{
+    if (!out) return fail(SK_EINVAL, "unet_create: out is null");
+    *out = nullptr;
+    if (c_in < 1 || n_classes < 1 || depth < 1 || depth > 6 || base_ch < 1) return fail(SK_EINVAL, "unet_create: bad arguments");
+    if (dtype != SK_F32) return fail(dtype == SK_BF16 || dtype == SK_F16 ? SK_EUNSUPPORTED : SK_EINVAL, "unet_create: only SK_F32 is built");
+    unet *net = new (std::nothrow) unet;
+    if (!net) return fail(SK_ENOMEM, "unet_create: out of host memory");
+    net->c_in = c_in; net->n_classes = n_classes; net->depth = depth; net->base = base_ch;
+    auto add_conv = [&](const std::string &name, int fi, int fo, int k) {
+        ConvParams c;
+        c.c_in = fi; c.c_out = fo; c.k = k;
+        c.w.assign((size_t)c.wcount(), 0.f);
+        c.b.assign((size_t)fo, 0.f);
+        net->params.push_back({name, 0, (int)net->convs.size()});
+        net->convs.push_back(std::move(c));
+    };
+    int f = c_in;
+    for (int i = 0; i <= depth; ++i) {
+        const int ch = base_ch << i;
+        add_conv("down" + std::to_string(i) + "a", f, ch, 3);
+        add_conv("down" + std::to_string(i) + "b", ch, ch, 3);
+        f = ch;
+    }
+    for (int i = depth - 1; i >= 0; --i) {
+        const int ch = base_ch << i;
+        UpParams u;
+        u.c_in = 2 * ch; u.c_out = ch;
+        u.w.assign((size_t)u.c_in * u.c_out * 4, 0.f);
+        u.b.assign((size_t)ch, 0.f);
+        net->params.push_back({"up" + std::to_string(i), 1, (int)net->ups.size()});
+        net->ups.push_back(std::move(u));
+        add_conv("dec" + std::to_string(i) + "a", 2 * ch, ch, 3);
+        add_conv("dec" + std::to_string(i) + "b", ch, ch, 3);
+    }
+    add_conv("head", base_ch, n_classes, 1);
+    *out = net;
+    return SK_OK;
+}
+
+void unet_destroy(unet_t *net)
+{
+    if (!net) return;
+    net->release_plan();
+    delete net;
+}
+
+sk_status unet_num_params(const unet_t *net, int32_t *count)
+{
+    SK_TRY(check(net));
+    if (!count) return fail(SK_EINVAL, "unet_num_params: count is null");
+    *count = (int32_t)net->params.size();
+    return SK_OK;
+}
+
+sk_status unet_param_shape(const unet_t *net, int32_t idx, int32_t *shape4)
+{
+    SK_TRY(check(net));
+    if (!shape4 || idx < 0 || idx >= (int)net->params.size()) return fail(SK_EINVAL, "unet_param_shape: bad index");
+    const auto &p = net->params[idx];
+    if (p.kind == 0) {
+        const ConvParams &c = net->convs[p.idx];
+        shape4[0] = c.c_out; shape4[1] = c.c_in; shape4[2] = c.k; shape4[3] = c.k;
+    } else {
+        const UpParams &u = net->ups[p.idx];
+        shape4[0] = u.c_in; shape4[1] = u.c_out; shape4[2] = 2; shape4[3] = 2;
+    }
+    return SK_OK;
+}
+
+sk_status unet_set_weights(unet_t *net, int32_t idx, const float *w_host, const float *b_host)
+{
+    SK_TRY(check(net));
+    if (!w_host || idx < 0 || idx >= (int)net->params.size()) return fail(SK_EINVAL, "unet_set_weights: bad arguments");
+    const auto &p = net->params[idx];
+    if (p.kind == 0) {
+        ConvParams &c = net->convs[p.idx];
+        std::memcpy(c.w.data(), w_host, sizeof(float) * c.wcount());
+        if (b_host) std::memcpy(c.b.data(), b_host, sizeof(float) * c.c_out);
+        if (net->planned) SK_TRY(upload_conv(c, false, net->last_stream));
+    } else {
+        UpParams &u = net->ups[p.idx];
+        std::memcpy(u.w.data(), w_host, sizeof(float) * u.w.size());
+        if (b_host) std::memcpy(u.b.data(), b_host, sizeof(float) * u.c_out);
+        if (net->planned) SK_TRY(upload_up(u));
+    }
+    return SK_OK;
+}
+
+sk_status unet_output_size(const unet_t *net, int32_t h_in, int32_t w_in, int32_t *h_out, int32_t *w_out)
+{
+    SK_TRY(check(net));
+    if (!h_out || !w_out) return fail(SK_EINVAL, "unet_output_size: null output");
+    return walk_sizes(net, h_in, w_in, h_out, w_out);
+}
+
+sk_status unet_plan(unet_t *net, int32_t n, int32_t h_in, int32_t w_in)
+{
+    SK_TRY(check(net));
+    if (n < 1) return fail(SK_EINVAL, "unet_plan: n must be >= 1");
+    int ho, wo;
+    SK_TRY(walk_sizes(net, h_in, w_in, &ho, &wo));
+    net->release_plan();
+    net->n = n; net->h_in = h_in; net->w_in = w_in;
+    sk_status st = SK_OK;
+    auto new_buf = [&](const Dims &d) -> float * {
+        float *p = nullptr;
+        if (st == SK_OK) st = alloc_f(&p, d.count(n));
+        if (p) net->buffers.push_back(p);
+        return p;
+    };
+    auto conv_op = [&](int conv_idx, int relu, const float *src, const Dims &in, float *dst, const Dims &out) {
+        unet::Op op{};
+        op.kind = 0; op.param = conv_idx; op.relu = relu; op.src = src; op.dst = dst; op.in = in; op.out = out;
+        net->ops.push_back(op);
+    };
+    int ci = 0;   // running conv index
+    Dims cur;
+    cur.c = net->c_in; cur.h = h_in; cur.w = w_in;
+    const float *src = nullptr;
+    std::vector<Dims> skip_dims;
+    std::vector<const float *> skip_buf;
+    for (int i = 0; i <= net->depth && st == SK_OK; ++i) {
+        const int ch = net->base << i;
+        Dims a = {ch, cur.h - 2, cur.w - 2}, b = {ch, cur.h - 4, cur.w - 4};
+        float *ba = new_buf(a), *bb = new_buf(b);
+        conv_op(ci++, 1, src, cur, ba, a);
+        conv_op(ci++, 1, ba, a, bb, b);
+        net->stages.push_back({"down" + std::to_string(i), b, bb});
+        cur = b; src = bb;
+        if (i < net->depth) {
+            skip_dims.push_back(b);
+            skip_buf.push_back(bb);
+            Dims p = {ch, b.h / 2, b.w / 2};
+            float *bp = new_buf(p);
+            unet::Op op{};
+            op.kind = 1; op.src = bb; op.dst = bp; op.in = b; op.out = p;
+            net->ops.push_back(op);
+            cur = p; src = bp;
+        }
+    }
+    int ui = 0;
+    for (int i = net->depth - 1; i >= 0 && st == SK_OK; --i) {
+        const int ch = net->base << i;
+        Dims merged = {2 * ch, 2 * cur.h, 2 * cur.w};
+        float *bm = new_buf(merged);
+        unet::Op up{};
+        up.kind = 2; up.param = ui++; up.src = src; up.dst = bm; up.in = cur; up.out = merged; up.o_off = 0;
+        net->ops.push_back(up);
+        Dims upd = {ch, merged.h, merged.w};
+        net->stages.push_back({"up" + std::to_string(i), upd, bm});
+        unet::Op cp{};
+        cp.kind = 3; cp.src = skip_buf[i]; cp.dst = bm; cp.in = skip_dims[i]; cp.out = merged; cp.o_off = ch;
+        cp.crop = (skip_dims[i].h - merged.h) / 2; cp.src_maps = ch;
+        if (skip_dims[i].h < merged.h || skip_dims[i].w < merged.w) st = fail(SK_ESHAPE, "U-Net: skip map smaller than the up path at level %d", i);
+        net->ops.push_back(cp);
+        Dims a = {ch, merged.h - 2, merged.w - 2}, b = {ch, merged.h - 4, merged.w - 4};
+        float *ba = new_buf(a), *bb = new_buf(b);
+        conv_op(ci++, 1, bm, merged, ba, a);
+        conv_op(ci++, 1, ba, a, bb, b);
+        net->stages.push_back({"dec" + std::to_string(i), b, bb});
+        cur = b; src = bb;
+    }
+    if (st == SK_OK) {
+        Dims z = {net->n_classes, cur.h, cur.w};
+        net->logits = new_buf(z);
+        conv_op(ci++, 0, src, cur, net->logits, z);
+        net->stages.push_back({"logits", z, net->logits});
+        net->out_dims = z;
+    }
+    for (auto &c : net->convs) {
+        if (st != SK_OK) break;
+        st = alloc_conv(c, false);
+        if (st == SK_OK) st = upload_conv(c, false, nullptr);
+    }
+    for (auto &u : net->ups) {
+        if (st != SK_OK) break;
+        for (auto &t : u.tap) {
+            t.c_in = u.c_in; t.c_out = u.c_out; t.k = 1;
+            if (st == SK_OK) st = alloc_conv(t, false);
+        }
+        if (st == SK_OK) st = upload_up(u);
+    }
+    if (st != SK_OK) {
+        std::string keep = g_last_error;
+        net->release_plan();
+        g_last_error = keep;
+        return st;
+    }
+    net->planned = true;
+    return SK_OK;
+}
+
+sk_status unet_forward(unet_t *net, const float *image_dev, float *prob_dev, void *hip_stream)
+{
+    SK_TRY(check(net));
+    if (!net->planned) return fail(SK_ESTATE, "unet_forward: call unet_plan first");
+    if (!image_dev || !prob_dev) return fail(SK_EINVAL, "unet_forward: null buffer");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    net->last_stream = stream;
+    const int n = net->n;
+    for (const auto &op : net->ops) {
+        const float *src = op.src ? op.src : image_dev;
+        if (op.kind == 0) {
+            const ConvParams &c = net->convs[op.param];
+            sk::ConvF32Args a = conv_args(c, src, n, op.in, 1, op.relu, op.dst, op.out);
+            SK_HIP(sk::launch_conv_f32(a, stream));
+        } else if (op.kind == 1) {
+            SK_HIP(sk::launch_maxpool_f32(src, op.dst, nullptr, n * op.in.c, op.in.h, op.in.w, op.out.h, op.out.w, 2, 1, 2, stream));
+        } else if (op.kind == 2) {
+            const UpParams &u = net->ups[op.param];
+            for (int t = 0; t < 4; ++t) {
+                Dims lowres = {u.c_out, op.in.h, op.in.w};
+                sk::ConvF32Args a = conv_args(u.tap[t], src, n, op.in, 1, 0, op.dst, lowres);
+                a.out_maps = op.out.c; a.OH = op.out.h; a.OW = op.out.w;
+                a.oy_mul = 2; a.oy_off = t / 2; a.ox_mul = 2; a.ox_off = t % 2;
+                SK_HIP(sk::launch_conv_f32(a, stream));
+            }
+        } else {
+            SK_HIP(sk::launch_crop_copy_f32(src, op.dst, n, op.src_maps, op.in.h, op.in.w, op.out.c, op.o_off,
+                                            op.out.h, op.out.w, op.crop, (op.in.w - op.out.w) / 2, stream));
+        }
+    }
+    SK_HIP(sk::launch_softmax_f32(net->logits, prob_dev, n, net->out_dims.c, net->out_dims.h * net->out_dims.w, stream));
+    net->forward_done = true;
+    return SK_OK;
+}
+
+sk_status unet_get_activation(unet_t *net, const char *stage, float *nchw_host, int32_t *dims3)
+{
+    SK_TRY(check(net));
+    if (!stage) return fail(SK_EINVAL, "unet_get_activation: stage is null");
+    if (!net->planned) return fail(SK_ESTATE, "unet_get_activation: call unet_plan first");
+    for (const auto &s : net->stages) {
+        if (s.name != stage) continue;
+        if (dims3) { dims3[0] = s.dims.c; dims3[1] = s.dims.h; dims3[2] = s.dims.w; }
+        if (!nchw_host) return SK_OK;
+        if (!net->forward_done) return fail(SK_ESTATE, "unet_get_activation: no forward pass yet");
+        SK_HIP(hipStreamSynchronize(net->last_stream));
+        if (s.name.rfind("up", 0) == 0) {
+            // the up path occupies the first maps of the merged buffer: copy image by image
+            const int merged_c = 2 * s.dims.c;
+            const size_t img = (size_t)s.dims.c * s.dims.h * s.dims.w;
+            for (int b = 0; b < net->n; ++b)
+                SK_HIP(hipMemcpy(nchw_host + b * img, s.buf + (size_t)b * merged_c * s.dims.h * s.dims.w,
+                                 sizeof(float) * img, hipMemcpyDeviceToHost));
+        } else {
+            SK_HIP(hipMemcpy(nchw_host, s.buf, sizeof(float) * s.dims.count(net->n), hipMemcpyDeviceToHost));
+        }
+        return SK_OK;
+    }
+    return fail(SK_EINVAL, "unet_get_activation: unknown stage '%s'", stage);
+}
+
+}  // extern "C"
