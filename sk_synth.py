@@ -110,7 +110,8 @@ def unet_param_names(depth=4):
 
 
 def unet_params(c_in, classes, seed, depth=4, base=64, bias_scale=0.0):
-    """He-normal weights for every U-Net layer, fan-in f_in*k^2; returns {name: (w, b)} fp32.
+    """He-normal weights for every U-Net layer (fan-in f_in*k^2 for convs, f_in for the
+    up-convolutions); returns {name: (w, b)} fp32.
     conv weights [f_out,f_in,3,3]; up-convolution weights [f_in, f_in/2, 2, 2]; head [classes,base,1,1]."""
     rng = np.random.default_rng(seed)
     ch = [base * 2 ** i for i in range(depth + 1)]
@@ -129,7 +130,7 @@ def unet_params(c_in, classes, seed, depth=4, base=64, bias_scale=0.0):
     for name in unet_param_names(depth):
         shp = shapes[name]
         if name.startswith("up"):
-            fan_in, f_out = shp[0] * 4, shp[1]
+            fan_in, f_out = shp[0], shp[1]      # every output pixel sees one tap per input map
         else:
             fan_in, f_out = shp[1] * shp[2] * shp[3], shp[0]
         w = rng.standard_normal(shp) * np.sqrt(2.0 / fan_in)
