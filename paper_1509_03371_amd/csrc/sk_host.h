@@ -98,9 +98,9 @@ inline sk_status alloc_conv(ConvParams &c, bool training)
 {
     release_conv(c);
     c.n_pad = round_up(c.c_out, 16);
-    c.rows_fwd = round_up(c.c_in, 4) * c.k * c.k;
+    c.rows_fwd = round_up(c.c_in, 16) * c.k * c.k;
     c.n_pad_bwd = round_up(c.c_in, 16);
-    c.rows_bwd = round_up(c.c_out, 4) * c.k * c.k;
+    c.rows_bwd = round_up(c.c_out, 16) * c.k * c.k;
     SK_TRY(alloc_f(&c.w_dev, c.wcount()));
     SK_TRY(alloc_f(&c.b_dev, c.n_pad));
     SK_TRY(alloc_f(&c.wp_fwd, (long)c.rows_fwd * c.n_pad));

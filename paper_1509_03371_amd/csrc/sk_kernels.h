@@ -16,7 +16,7 @@ namespace sk {
 //   Y[((b*out_maps + o + o_off)*OH + y*oy_mul + oy_off)*OW + x*ox_mul + ox_off].
 struct ConvF32Args {
     const float *x;      // [n][c_in][H][W]
-    const float *wp;     // packed weights [c_pad*k*k][n_pad], c_pad = roundup(c_in, 4), n_pad = roundup(c_out, 16)
+    const float *wp;     // packed weights [c_pad*k*k][n_pad], c_pad = roundup(c_in, 16), n_pad = roundup(c_out, 16)
     const float *bias;   // [n_pad] or nullptr
     const float *mask;   // optional, indexed like y
     float *y;
@@ -32,7 +32,7 @@ hipError_t launch_conv_f32(const ConvF32Args &a, hipStream_t stream);
 // Pack OIHW fp32 master weights [c_out][c_in][k][k] into the K-major layout launch_conv_f32 reads.
 // flip_transpose = 0: Wp[(c*k+i)*k+j][o] = W[o][c][i][j]                       (forward)
 // flip_transpose = 1: Wp[(o*k+i)*k+j][c] = W[o][c][k-1-i][k-1-j]               (data gradient)
-// Rows/columns beyond the real extents are zero.  rows = roundup(in_maps,4)*k*k, cols = n_pad.
+// Rows/columns beyond the real extents are zero.  rows = roundup(in_maps,16)*k*k, cols = n_pad.
 hipError_t launch_pack_weights_f32(const float *w_oihw, float *wp, int c_out, int c_in, int k,
                                    int flip_transpose, int rows, int n_pad, hipStream_t stream);
 
