@@ -1,0 +1,452 @@
+// Implicit-GEMM SK (dilated) convolution for 16-bit activations (bf16 or fp16, fp32 accumulate) on
+// gfx950, MFMA 16x16x32.
+//
+// Storage ("octet layout"): a tensor with C maps is [n][ceil(C/8)][H][W][8] 16-bit elements, so
+// the 8 consecutive K values that one MFMA lane supplies are one aligned 16-byte load, and
+// consecutive pixels are consecutive 16-byte units (coalesced in HBM, conflict-free in LDS).
+// Maps beyond C inside the last octet are zero.
+//
+// GEMM view (paper, Section 5.5): M = f_out, N = output pixels, K = f_in*k*k; no column buffer.
+// MFMA roles: A = weights (16 output maps x 32 K), B = input (32 K x 16 pixels); lane (g = l/16,
+// l16 = l%16) supplies K values 8g..8g+7 and receives D[map 4g+r][pixel l16], r = 0..3: four
+// consecutive maps of one pixel, i.e. half an octet, so lanes g = 2q and 2q+1 together write one
+// 16-byte unit and 16 lanes write 256 contiguous bytes.
+//
+// How the 32 K values of one MFMA are chosen ("column step"):
+//   MAP4 (k = 4): the four lane groups take the four kernel columns j = g of one input octet.
+//   otherwise   : the four lane groups take four input octets at one kernel column j.
+// Either way a B fragment is tied to one INPUT row r of the staged tile and is reused for every
+// kernel row i (output row y = r - i) and every output-map tile: the rows of a tile lie d apart
+// (one row phase of the kernel stride), so tile row r + i is the input row of output row r, tap i.
+// Per column step a wave reads R + k - 1 B fragments and k*MT A fragments from LDS for R*k*MT MFMAs.
+//
+// A workgroup is 8 waves and owns R output rows (d apart) x 128 columns (wave w: columns 16w..);
+// the grid is persistent (one workgroup per CU), walks tiles in an XCD-aware order and keeps a
+// two-stage LDS pipeline running across tile boundaries: while chunk q is multiplied, chunk q+1
+// (next octets, or the first octets of the next tile) is in flight from HBM/L2 into registers.
+#include "sk_kernels.h"
+
+namespace sk {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
+typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
+typedef unsigned int uint2v __attribute__((ext_vector_type(2)));
+
+constexpr int CH_TX = 128;     // output columns per workgroup
+constexpr int CH_WAVES = 8;
+constexpr int CH_THREADS = 64 * CH_WAVES;
+constexpr int CH_VU = 3;       // 64-unit column groups staged per row: tile width <= 192 units
+
+template <int DT> struct H;    // DT = 1 bf16, 2 fp16
+template <> struct H<1> {
+    static __device__ __forceinline__ floatx4 mfma(uint4v a, uint4v b, floatx4 c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ unsigned short cvt(float f)
+    {
+        return __builtin_bit_cast(unsigned short, static_cast<__bf16>(f));
+    }
+    static __device__ __forceinline__ float up(unsigned short u) { return __uint_as_float((unsigned)u << 16); }
+};
+template <> struct H<2> {
+    static __device__ __forceinline__ floatx4 mfma(uint4v a, uint4v b, floatx4 c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(halfx8, a), __builtin_bit_cast(halfx8, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ unsigned short cvt(float f)
+    {
+        return __builtin_bit_cast(unsigned short, static_cast<_Float16>(f));
+    }
+    static __device__ __forceinline__ float up(unsigned short u) { return (float)__builtin_bit_cast(_Float16, u); }
+};
+
+// positive (> 0) test on a 16-bit float bit pattern (both formats: sign bit clear, magnitude non-zero)
+__device__ __forceinline__ bool pos16(unsigned v) { return (v & 0x8000u) == 0 && (v & 0x7fffu) != 0; }
+
+struct TilePos {
+    int b, mg, py, ty, x0;
+};
+
+template <int DT, int KS, int MT, bool MAP4, int R>
+__global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
+{
+    extern __shared__ uint4v lds[];
+    constexpr int RR = R + KS - 1;
+    constexpr int OC = MAP4 ? 1 : 4;            // input octets per chunk
+    constexpr int CS = MAP4 ? 1 : KS;           // column steps per chunk
+    constexpr int ROWS = OC * RR;               // staged tile rows per chunk
+    constexpr int RU = (ROWS + CH_WAVES - 1) / CH_WAVES;
+    constexpr int WUNITS = CS * KS * MT * 64;   // 16-byte units of the weight slab of one chunk
+    constexpr int WU = (WUNITS + CH_THREADS - 1) / CH_THREADS;
+
+    const int d = a.d;
+    const int PW = CH_TX + (KS - 1) * d;        // tile width in 16-byte units
+    const int tile_units = ROWS * PW;
+    const int stage_units = tile_units + WUNITS;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l16 = lane & 15, g = lane >> 4;
+
+    // XCD-aware persistent schedule: workgroup ids go round-robin over the 8 XCDs, so XCD x takes
+    // the x-th contiguous eighth of the tile list (neighbouring tiles share halo in that XCD's L2)
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, nslots = gridDim.x >> 3;
+    const int t_begin = (int)((long)a.total_tiles * xcd / 8), t_end = (int)((long)a.total_tiles * (xcd + 1) / 8);
+
+    auto decode = [&](int t) {
+        TilePos p;
+        const int xt = t % a.xtiles;
+        int rest = t / a.xtiles;
+        const int yt = rest % a.ytiles_total;
+        rest /= a.ytiles_total;
+        p.mg = rest % a.mgroups;
+        p.b = rest / a.mgroups;
+        if (yt < a.rem * a.tiles_hi) {
+            p.py = yt / a.tiles_hi;
+            p.ty = yt - p.py * a.tiles_hi;
+        } else {
+            const int y2 = yt - a.rem * a.tiles_hi;
+            p.py = a.rem + y2 / a.tiles_lo;
+            p.ty = y2 % a.tiles_lo;
+        }
+        p.x0 = xt * CH_TX;
+        return p;
+    };
+
+    // chunk-invariant column bookkeeping of this lane
+    const long plane = (long)a.H * a.W;
+    uint4v xr[RU][CH_VU];
+    uint4v wr[WU];
+
+    auto prefetch = [&](const TilePos &p, int ch) {
+        const int gy0 = p.py + d * (p.ty * R) - a.in_off;
+        const int gx0 = p.x0 - a.in_off;
+#pragma unroll
+        for (int u = 0; u < RU; ++u) {
+            int rid = wave + CH_WAVES * u;
+            rid = rid < ROWS ? rid : ROWS - 1;
+            const int oc = rid / RR, r = rid - oc * RR;
+            int o = ch * OC + oc;
+            o = o < a.c8_in ? o : a.c8_in - 1;
+            int gy = gy0 + r * d;
+            gy = gy < 0 ? 0 : (gy >= a.H ? a.H - 1 : gy);
+            const uint4v *row = reinterpret_cast<const uint4v *>(a.x) + ((long)p.b * a.c8_in + o) * plane + (long)gy * a.W;
+#pragma unroll
+            for (int v = 0; v < CH_VU; ++v) {
+                int gx = gx0 + lane + 64 * v;
+                gx = gx < 0 ? 0 : (gx >= a.W ? a.W - 1 : gx);
+                xr[u][v] = row[gx];
+            }
+        }
+        const uint4v *wsrc = reinterpret_cast<const uint4v *>(a.wp) + ((long)p.mg * a.nchunks + ch) * WUNITS;
+#pragma unroll
+        for (int u = 0; u < WU; ++u) {
+            int q = tid + CH_THREADS * u;
+            q = q < WUNITS ? q : WUNITS - 1;
+            wr[u] = wsrc[q];
+        }
+    };
+    auto commit = [&](const TilePos &p, int ch, int buf) {
+        uint4v *dst = lds + buf * stage_units;
+        const int gy0 = p.py + d * (p.ty * R) - a.in_off;
+        const int gx0 = p.x0 - a.in_off;
+        const uint4v zero = uint4v{0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int u = 0; u < RU; ++u) {
+            const int rid = wave + CH_WAVES * u;
+            if (rid < ROWS) {
+                const int oc = rid / RR, r = rid - oc * RR;
+                const int gy = gy0 + r * d;
+                const bool rowok = (ch * OC + oc < a.c8_in) && gy >= 0 && gy < a.H;
+#pragma unroll
+                for (int v = 0; v < CH_VU; ++v) {
+                    const int xc = lane + 64 * v, gx = gx0 + xc;
+                    if (xc < PW) dst[rid * PW + xc] = (rowok && gx >= 0 && gx < a.W) ? xr[u][v] : zero;
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < WU; ++u) {
+            const int q = tid + CH_THREADS * u;
+            if (q < WUNITS) dst[tile_units + q] = wr[u];
+        }
+    };
+
+    floatx4 acc[R][MT];
+#pragma unroll
+    for (int y = 0; y < R; ++y)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[y][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    auto compute = [&](int buf) {
+        const uint4v *tile = lds + buf * stage_units;
+        const uint4v *wl = tile + tile_units;
+#pragma unroll
+        for (int cs = 0; cs < CS; ++cs) {
+            uint4v afr[KS][MT];
+#pragma unroll
+            for (int i = 0; i < KS; ++i)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) afr[i][mt] = wl[((cs * KS + i) * MT + mt) * 64 + lane];
+            const int off = (MAP4 ? g * d : g * RR * PW + cs * d) + wave * 16 + l16;
+            uint4v bcur = tile[off];
+#pragma unroll
+            for (int r = 0; r < RR; ++r) {
+                uint4v bnext = bcur;
+                if (r + 1 < RR) bnext = tile[off + (r + 1) * PW];
+#pragma unroll
+                for (int i = 0; i < KS; ++i) {
+                    const int y = r - i;
+                    if (y >= 0 && y < R) {
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt) acc[y][mt] = H<DT>::mfma(afr[i][mt], bcur, acc[y][mt]);
+                    }
+                }
+                bcur = bnext;
+            }
+        }
+    };
+
+    auto epilogue = [&](const TilePos &p) {
+        const int ox = p.x0 + wave * 16 + l16;
+#pragma unroll
+        for (int y = 0; y < R; ++y) {
+            const int oy = p.py + d * (p.ty * R + y);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const int mtile = p.mg * MT + mt;
+                floatx4 v = acc[y][mt];
+                acc[y][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+                if (oy >= a.Ho || ox >= a.Wo || mtile >= a.m_tiles) continue;
+                const int o = mtile * 16 + 4 * g;           // first of this lane's four output maps
+                const long py_out = (long)oy * a.oy_mul + a.oy_off, px_out = (long)ox * a.ox_mul + a.ox_off;
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    if (a.bias) v[r4] += a.bias[o + r4];
+                    if (a.relu) v[r4] = v[r4] > 0.f ? v[r4] : 0.f;
+                }
+                if (a.out_f32) {
+                    float *yf = reinterpret_cast<float *>(a.y);
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4)
+                        if (o + r4 < a.c_out)
+                            yf[(((long)p.b * a.c_out + o + r4) * a.OH + py_out) * a.OW + px_out] = v[r4];
+                } else {
+                    const int o8 = o >> 3;
+                    if (o8 >= a.c8_out) continue;
+                    const long unit = (((long)p.b * a.c8_out_total + o8 + a.o8_off) * a.OH + py_out) * a.OW + px_out;
+                    unsigned short h[4];
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4) h[r4] = H<DT>::cvt(v[r4]);
+                    uint2v packed = uint2v{(unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16)};
+                    if (a.mask) {
+                        const uint2v m = reinterpret_cast<const uint2v *>(a.mask)[unit * 2 + (g & 1)];
+                        unsigned lo = packed[0], hi = packed[1];
+                        if (!pos16(m[0] & 0xffffu)) lo &= 0xffff0000u;
+                        if (!pos16(m[0] >> 16)) lo &= 0x0000ffffu;
+                        if (!pos16(m[1] & 0xffffu)) hi &= 0xffff0000u;
+                        if (!pos16(m[1] >> 16)) hi &= 0x0000ffffu;
+                        packed = uint2v{lo, hi};
+                    }
+                    reinterpret_cast<uint2v *>(a.y)[unit * 2 + (g & 1)] = packed;
+                }
+            }
+        }
+    };
+
+    int t = t_begin + slot;
+    if (t >= t_end) return;
+    TilePos cur = decode(t), nxt = cur;
+    int ch = 0, buf = 0;
+    prefetch(cur, 0);
+    commit(cur, 0, 0);
+    __syncthreads();
+    while (true) {
+        int nch = ch + 1, ntile = t;
+        if (nch == a.nchunks) {
+            nch = 0;
+            ntile = t + nslots;
+        }
+        const bool has_next = ntile < t_end;
+        if (has_next) {
+            if (nch == 0) nxt = decode(ntile);
+            prefetch(nxt, nch);
+        }
+        compute(buf);
+        if (ch == a.nchunks - 1) epilogue(cur);
+        if (has_next) commit(nxt, nch, buf ^ 1);
+        __syncthreads();
+        if (!has_next) break;
+        t = ntile;
+        ch = nch;
+        cur = nxt;
+        buf ^= 1;
+    }
+}
+
+template <int DT, int KS, int MT, bool MAP4, int R>
+static hipError_t launch_conv_h_t(ConvHArgs a, hipStream_t stream)
+{
+    constexpr int RR = R + KS - 1, OC = MAP4 ? 1 : 4, CS = MAP4 ? 1 : KS;
+    const int PW = CH_TX + (KS - 1) * a.d;
+    if (PW > 64 * CH_VU) return hipErrorInvalidValue;
+    const size_t stage = (size_t)OC * RR * PW + (size_t)CS * KS * MT * 64;
+    const size_t smem = 2 * stage * 16;
+    if (smem > 160 * 1024) return hipErrorInvalidValue;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_h_kernel<DT, KS, MT, MAP4, R>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    a.m_tiles = (a.c_out + 15) / 16;
+    a.mgroups = (a.m_tiles + MT - 1) / MT;
+    a.nchunks = (a.c8_in + OC - 1) / OC;
+    a.xtiles = (a.Wo + CH_TX - 1) / CH_TX;
+    const int q = a.Ho / a.d;
+    a.rem = a.Ho % a.d;
+    a.tiles_hi = (q + 1 + R - 1) / R;
+    a.tiles_lo = (q + R - 1) / R;
+    a.ytiles_total = a.rem * a.tiles_hi + (a.d - a.rem) * a.tiles_lo;
+    if (a.tiles_lo < 1) a.tiles_lo = 1;
+    const long total = (long)a.xtiles * a.ytiles_total * a.mgroups * a.n;
+    if (total < 1 || total > 0x7fffffffL) return hipErrorInvalidValue;
+    a.total_tiles = (int)total;
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 8)
+            cus = 256;
+    }
+    int blocks = cus / 8 * 8;               // one workgroup per CU, a multiple of the 8 XCDs
+    if (total < blocks) blocks = (int)((total + 7) / 8 * 8);
+    hipLaunchKernelGGL((conv_h_kernel<DT, KS, MT, MAP4, R>), dim3(blocks), dim3(CH_THREADS), smem, stream, a);
+    return hipGetLastError();
+}
+
+template <int DT, int MT>
+static hipError_t launch_conv_h_mt(const ConvHArgs &a, hipStream_t stream)
+{
+    switch (a.k) {
+    case 1: return launch_conv_h_t<DT, 1, MT, false, 4>(a, stream);
+    case 2: return launch_conv_h_t<DT, 2, MT, false, 4>(a, stream);
+    case 3:
+        if constexpr (MT <= 3) return launch_conv_h_t<DT, 3, MT, false, 4>(a, stream);
+        else return hipErrorInvalidValue;
+    case 4:
+        if constexpr (MT <= 3) return launch_conv_h_t<DT, 4, MT, true, 8>(a, stream);
+        else return launch_conv_h_t<DT, 4, MT, true, 4>(a, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+// output-map tiles (16 maps each) per workgroup: as few padded tiles as possible; a 3x3 kernel's
+// weight slab (k*k KB per tile and chunk) only leaves LDS room for three
+int conv_h_mt(int c_out, int k)
+{
+    const int tiles = (c_out + 15) / 16;
+    if (tiles <= 2) return tiles;
+    const int pad3 = (tiles + 2) / 3 * 3, pad4 = (tiles + 3) / 4 * 4;
+    if (k == 3) return 3;
+    return pad3 <= pad4 ? 3 : 4;
+}
+
+bool conv_h_supported(int k, int d)
+{
+    return (k >= 1 && k <= 4) && CH_TX + (k - 1) * d <= 64 * CH_VU;
+}
+
+hipError_t launch_conv_h(const ConvHArgs &a, hipStream_t stream)
+{
+    if (!conv_h_supported(a.k, a.d) || a.Ho < 1 || a.Wo < 1 || a.c8_in < 1 || a.c_out < 1) return hipErrorInvalidValue;
+    const int mt = conv_h_mt(a.c_out, a.k);
+    if (a.dtype == 1) {
+        switch (mt) {
+        case 1: return launch_conv_h_mt<1, 1>(a, stream);
+        case 2: return launch_conv_h_mt<1, 2>(a, stream);
+        case 3: return launch_conv_h_mt<1, 3>(a, stream);
+        default: return launch_conv_h_mt<1, 4>(a, stream);
+        }
+    }
+    if (a.dtype == 2) {
+        switch (mt) {
+        case 1: return launch_conv_h_mt<2, 1>(a, stream);
+        case 2: return launch_conv_h_mt<2, 2>(a, stream);
+        case 3: return launch_conv_h_mt<2, 3>(a, stream);
+        default: return launch_conv_h_mt<2, 4>(a, stream);
+        }
+    }
+    return hipErrorInvalidValue;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Weight packing for conv_h_kernel.  The packed array is a sequence of 1 KB MFMA A fragments,
+//   [mgroup][chunk][column step cs][kernel row i][m-tile mt][lane group g][l16][e = 0..7]
+// with element = W[o][c][i][j] (forward) where o = (mgroup*MT + mt)*16 + l16 and
+//   MAP4 (k = 4): c = chunk*8 + e,            j = g
+//   otherwise   : c = (chunk*4 + g)*8 + e,    j = cs
+// flip_transpose = 1 builds the data-gradient operator instead: the roles of input and output maps
+// are swapped and both taps are mirrored (element = W[c][o][k-1-i][k-1-j]).
+// Entries whose o or c lie beyond the real extents are zero.
+template <int DT>
+__global__ void pack_weights_h_kernel(const float *w, unsigned short *wp, int c_out, int c_in, int k, int flip_transpose,
+                                      int mt_per_group, int map4, int gemm_m, int gemm_c8, long total)
+{
+    const int OC = map4 ? 1 : 4, CS = map4 ? 1 : k;
+    const int nchunks = (gemm_c8 + OC - 1) / OC;
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
+        long r = q;
+        const int e = (int)(r % 8); r /= 8;
+        const int l16 = (int)(r % 16); r /= 16;
+        const int g = (int)(r % 4); r /= 4;
+        const int mt = (int)(r % mt_per_group); r /= mt_per_group;
+        const int i = (int)(r % k); r /= k;
+        const int cs = (int)(r % CS); r /= CS;
+        const int ch = (int)(r % nchunks); r /= nchunks;
+        const int mg = (int)r;
+        const int m = (mg * mt_per_group + mt) * 16 + l16;          // GEMM output map
+        const int c = map4 ? ch * 8 + e : (ch * 4 + g) * 8 + e;     // GEMM input map
+        const int j = map4 ? g : cs;
+        float v = 0.f;
+        if (m < gemm_m && c < gemm_c8 * 8) {
+            if (!flip_transpose) {
+                if (m < c_out && c < c_in) v = w[(((long)m * c_in + c) * k + i) * k + j];
+            } else {
+                if (c < c_out && m < c_in) v = w[(((long)c * c_in + m) * k + (k - 1 - i)) * k + (k - 1 - j)];
+            }
+        }
+        wp[q] = H<DT>::cvt(v);
+    }
+}
+
+// size in 16-bit elements of the packing of a GEMM with gemm_m output maps and gemm_c8 input octets
+long packed_h_elems(int gemm_m, int gemm_c8, int k)
+{
+    const int mt = conv_h_mt(gemm_m, k);
+    const int m_tiles = (gemm_m + 15) / 16, mgroups = (m_tiles + mt - 1) / mt;
+    const bool map4 = k == 4;
+    const int OC = map4 ? 1 : 4, CS = map4 ? 1 : k;
+    const int nchunks = (gemm_c8 + OC - 1) / OC;
+    return (long)mgroups * nchunks * CS * k * mt * 512;
+}
+
+hipError_t launch_pack_weights_h(const float *w_oihw, void *wp, int dtype, int c_out, int c_in, int k,
+                                 int flip_transpose, hipStream_t stream)
+{
+    const int gemm_m = flip_transpose ? c_in : c_out;
+    const int gemm_c8 = ((flip_transpose ? c_out : c_in) + 7) / 8;
+    const long total = packed_h_elems(gemm_m, gemm_c8, k);
+    const int blocks = (int)((total + 255) / 256 < 2048 ? (total + 255) / 256 : 2048);
+    const int mt = conv_h_mt(gemm_m, k);
+    if (dtype == 1)
+        hipLaunchKernelGGL(pack_weights_h_kernel<1>, dim3(blocks), dim3(256), 0, stream, w_oihw,
+                           static_cast<unsigned short *>(wp), c_out, c_in, k, flip_transpose, mt, k == 4 ? 1 : 0, gemm_m, gemm_c8, total);
+    else
+        hipLaunchKernelGGL(pack_weights_h_kernel<2>, dim3(blocks), dim3(256), 0, stream, w_oihw,
+                           static_cast<unsigned short *>(wp), c_out, c_in, k, flip_transpose, mt, k == 4 ? 1 : 0, gemm_m, gemm_c8, total);
+    return hipGetLastError();
+}
+
+}  // namespace sk

@@ -1,0 +1,290 @@
+// HBM-bound layers on the 16-bit octet layout ([n][ceil(C/8)][H][W][8] bf16 or fp16): conversion
+// from / to fp32 NCHW (with the mirror padding of Section 1.3 fused into the conversion of the
+// image), max pooling with kernel stride (forward with winner codes, gather-form backward) and the
+// bias gradient.  One 16-byte unit (8 maps of one pixel) per thread, pixels fastest, so a wavefront
+// moves 1 KB of consecutive addresses per access.  Comparisons are done on the exactly widened
+// fp32 values, so pooling is bit-exact in both formats.
+#include "sk_kernels.h"
+
+namespace sk {
+
+typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
+typedef unsigned int uint2v __attribute__((ext_vector_type(2)));
+
+static inline int grid_for(long total, int block = 256, int cap = 1 << 20)
+{
+    long b = (total + block - 1) / block;
+    if (b < 1) b = 1;
+    return (int)(b < cap ? b : cap);
+}
+
+template <int DT> __device__ __forceinline__ float up16(unsigned u);
+template <> __device__ __forceinline__ float up16<1>(unsigned u) { return __uint_as_float(u << 16); }
+template <> __device__ __forceinline__ float up16<2>(unsigned u) { return (float)__builtin_bit_cast(_Float16, (unsigned short)u); }
+template <int DT> __device__ __forceinline__ unsigned down16(float f);
+template <> __device__ __forceinline__ unsigned down16<1>(float f) { return __builtin_bit_cast(unsigned short, static_cast<__bf16>(f)); }
+template <> __device__ __forceinline__ unsigned down16<2>(float f) { return __builtin_bit_cast(unsigned short, static_cast<_Float16>(f)); }
+
+__device__ __forceinline__ unsigned elem16(const uint4v &u, int e) { return (u[e >> 1] >> ((e & 1) * 16)) & 0xffffu; }
+
+__device__ __forceinline__ int mirror_index_h(int t, int len, int mode)
+{
+    if (len == 1) return 0;
+    if (mode == 0) {
+        const int period = 2 * (len - 1);
+        t %= period;
+        if (t < 0) t += period;
+        return t < len ? t : period - t;
+    }
+    const int period = 2 * len;
+    t %= period;
+    if (t < 0) t += period;
+    return t < len ? t : period - 1 - t;
+}
+
+// out[b][o][y][x][e] = in[b][8o+e][m(y-top)][m(x-left)] rounded to nearest even (0 for maps >= c)
+template <int DT>
+__global__ void pad_pack_h_kernel(const float *in, uint4v *out, int n, int c, int h, int w, int top, int left,
+                                  int ho, int wo, int mode)
+{
+    const int c8 = (c + 7) / 8;
+    const long total = (long)n * c8 * ho * wo;
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
+        const int x = (int)(q % wo);
+        long t = q / wo;
+        const int y = (int)(t % ho);
+        t /= ho;
+        const int o = (int)(t % c8);
+        const long b = t / c8;
+        const int sy = (top | left) ? mirror_index_h(y - top, h, mode) : y;
+        const int sx = (top | left) ? mirror_index_h(x - left, w, mode) : x;
+        unsigned hv[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int ch = o * 8 + e;
+            hv[e] = ch < c ? down16<DT>(in[((b * c + ch) * h + sy) * (long)w + sx]) : 0u;
+        }
+        out[q] = uint4v{hv[0] | (hv[1] << 16), hv[2] | (hv[3] << 16), hv[4] | (hv[5] << 16), hv[6] | (hv[7] << 16)};
+    }
+}
+
+hipError_t launch_pad_pack_h(const float *in, void *out, int dtype, int n, int c, int h, int w, int top, int left,
+                             int ho, int wo, int mode, hipStream_t stream)
+{
+    const long total = (long)n * ((c + 7) / 8) * ho * wo;
+    if (dtype == 1)
+        hipLaunchKernelGGL(pad_pack_h_kernel<1>, dim3(grid_for(total)), dim3(256), 0, stream, in, static_cast<uint4v *>(out), n, c, h, w, top, left, ho, wo, mode);
+    else
+        hipLaunchKernelGGL(pad_pack_h_kernel<2>, dim3(grid_for(total)), dim3(256), 0, stream, in, static_cast<uint4v *>(out), n, c, h, w, top, left, ho, wo, mode);
+    return hipGetLastError();
+}
+
+template <int DT>
+__global__ void unpack_h_kernel(const uint4v *in, float *out, int n, int c, int h, int w)
+{
+    const int c8 = (c + 7) / 8;
+    const long plane = (long)h * w, total = (long)n * c8 * plane;
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
+        const long pix = q % plane;
+        const long t = q / plane;
+        const int o = (int)(t % c8);
+        const long b = t / c8;
+        const uint4v u = in[q];
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (o * 8 + e < c) out[(b * c + o * 8 + e) * plane + pix] = up16<DT>(elem16(u, e));
+    }
+}
+
+hipError_t launch_unpack_h(const void *in, float *out, int dtype, int n, int c, int h, int w, hipStream_t stream)
+{
+    const long total = (long)n * ((c + 7) / 8) * h * w;
+    if (dtype == 1)
+        hipLaunchKernelGGL(unpack_h_kernel<1>, dim3(grid_for(total)), dim3(256), 0, stream, static_cast<const uint4v *>(in), out, n, c, h, w);
+    else
+        hipLaunchKernelGGL(unpack_h_kernel<2>, dim3(grid_for(total)), dim3(256), 0, stream, static_cast<const uint4v *>(in), out, n, c, h, w);
+    return hipGetLastError();
+}
+
+// ---- max pooling with kernel stride d and layer stride s (Section 5.2.1) on octets --------------------
+template <int DT>
+__global__ void maxpool_h_kernel(const uint4v *x, uint4v *y, uint2v *tap, long planes, int H, int W, int Ho, int Wo,
+                                 int k, int d, int s)
+{
+    const long total = planes * Ho * Wo;
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
+        const int xx = (int)(q % Wo);
+        const long t = q / Wo;
+        const int yy = (int)(t % Ho);
+        const long p = t / Ho;
+        const uint4v *src = x + (p * H + (long)s * yy) * W + (long)s * xx;
+        const uint4v first = src[0];
+        float best[8];
+        unsigned bits[8], code[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            bits[e] = elem16(first, e);
+            best[e] = up16<DT>(bits[e]);
+            code[e] = 0;
+        }
+        for (int i = 0; i < k; ++i)
+            for (int j = 0; j < k; ++j) {
+                const uint4v u = src[(long)i * d * W + j * d];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const unsigned b16 = elem16(u, e);
+                    const float v = up16<DT>(b16);
+                    if (v > best[e]) {          // strictly greater: the first maximum wins
+                        best[e] = v;
+                        bits[e] = b16;
+                        code[e] = i * k + j;
+                    }
+                }
+            }
+        y[q] = uint4v{bits[0] | (bits[1] << 16), bits[2] | (bits[3] << 16), bits[4] | (bits[5] << 16), bits[6] | (bits[7] << 16)};
+        if (tap)
+            tap[q] = uint2v{code[0] | (code[1] << 8) | (code[2] << 16) | (code[3] << 24),
+                            code[4] | (code[5] << 8) | (code[6] << 16) | (code[7] << 24)};
+    }
+}
+
+hipError_t launch_maxpool_h(const void *x, void *y, void *tap, int dtype, long planes8, int H, int W, int Ho, int Wo,
+                            int k, int d, int s, hipStream_t stream)
+{
+    const long total = planes8 * Ho * Wo;
+    if (dtype == 1)
+        hipLaunchKernelGGL(maxpool_h_kernel<1>, dim3(grid_for(total)), dim3(256), 0, stream, static_cast<const uint4v *>(x),
+                           static_cast<uint4v *>(y), static_cast<uint2v *>(tap), planes8, H, W, Ho, Wo, k, d, s);
+    else
+        hipLaunchKernelGGL(maxpool_h_kernel<2>, dim3(grid_for(total)), dim3(256), 0, stream, static_cast<const uint4v *>(x),
+                           static_cast<uint4v *>(y), static_cast<uint2v *>(tap), planes8, H, W, Ho, Wo, k, d, s);
+    return hipGetLastError();
+}
+
+// Gather form of the pool gradient (s = 1): input unit (u, v) collects, per map, dY of the windows
+// whose recorded winner it is.  Sums are formed in fp32 and rounded once.  relu_src (optional,
+// same shape as dx) zeroes the result where the layer below produced a non-positive value.
+template <int DT>
+__global__ void maxpool_bwd_h_kernel(const uint4v *dy, const uint2v *tap, const uint4v *relu_src, uint4v *dx,
+                                     long planes, int H, int W, int Ho, int Wo, int k, int d)
+{
+    const long total = planes * H * W;
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
+        const int v = (int)(q % W);
+        const long t = q / W;
+        const int u = (int)(t % H);
+        const long p = t / H;
+        float acc[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+        for (int i = 0; i < k; ++i) {
+            const int yy = u - i * d;
+            if (yy < 0 || yy >= Ho) continue;
+            for (int j = 0; j < k; ++j) {
+                const int xx = v - j * d;
+                if (xx < 0 || xx >= Wo) continue;
+                const long o = (p * Ho + yy) * Wo + xx;
+                const uint2v c = tap[o];
+                const uint4v g = dy[o];
+                const unsigned want = i * k + j;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const unsigned code = (c[e >> 2] >> ((e & 3) * 8)) & 0xffu;
+                    if (code == want) acc[e] += up16<DT>(elem16(g, e));
+                }
+            }
+        }
+        unsigned hv[8];
+        uint4v rs = uint4v{0u, 0u, 0u, 0u};
+        if (relu_src) rs = relu_src[q];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float a = acc[e];
+            if (relu_src && !(up16<DT>(elem16(rs, e)) > 0.f)) a = 0.f;
+            hv[e] = down16<DT>(a);
+        }
+        dx[q] = uint4v{hv[0] | (hv[1] << 16), hv[2] | (hv[3] << 16), hv[4] | (hv[5] << 16), hv[6] | (hv[7] << 16)};
+    }
+}
+
+hipError_t launch_maxpool_bwd_h(const void *dy, const void *tap, const void *relu_src, void *dx, int dtype,
+                                long planes8, int H, int W, int Ho, int Wo, int k, int d, hipStream_t stream)
+{
+    const long total = planes8 * H * W;
+    if (dtype == 1)
+        hipLaunchKernelGGL(maxpool_bwd_h_kernel<1>, dim3(grid_for(total)), dim3(256), 0, stream, static_cast<const uint4v *>(dy),
+                           static_cast<const uint2v *>(tap), static_cast<const uint4v *>(relu_src), static_cast<uint4v *>(dx),
+                           planes8, H, W, Ho, Wo, k, d);
+    else
+        hipLaunchKernelGGL(maxpool_bwd_h_kernel<2>, dim3(grid_for(total)), dim3(256), 0, stream, static_cast<const uint4v *>(dy),
+                           static_cast<const uint2v *>(tap), static_cast<const uint4v *>(relu_src), static_cast<uint4v *>(dx),
+                           planes8, H, W, Ho, Wo, k, d);
+    return hipGetLastError();
+}
+
+// winner codes on the octet layout -> flat input offsets, int32 NCHW (for the parity accessor)
+__global__ void tap_to_index_h_kernel(const uint2v *tap, int32_t *idx, int n, int c, int Ho, int Wo, int W, int k, int d, int s)
+{
+    const int c8 = (c + 7) / 8;
+    const long plane = (long)Ho * Wo, total = (long)n * c8 * plane;
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
+        const long pix = q % plane;
+        const int xx = (int)(pix % Wo), yy = (int)(pix / Wo);
+        const long t = q / plane;
+        const int o = (int)(t % c8);
+        const long b = t / c8;
+        const uint2v cd = tap[q];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            if (o * 8 + e >= c) continue;
+            const int code = (cd[e >> 2] >> ((e & 3) * 8)) & 0xff, i = code / k, j = code - i * k;
+            idx[(b * c + o * 8 + e) * plane + pix] = (s * yy + i * d) * W + s * xx + j * d;
+        }
+    }
+}
+
+hipError_t launch_tap_to_index_h(const void *tap, int32_t *idx, int n, int c, int Ho, int Wo, int W, int k, int d, int s,
+                                 hipStream_t stream)
+{
+    const long total = (long)n * ((c + 7) / 8) * Ho * Wo;
+    hipLaunchKernelGGL(tap_to_index_h_kernel, dim3(grid_for(total)), dim3(256), 0, stream, static_cast<const uint2v *>(tap), idx, n, c, Ho, Wo, W, k, d, s);
+    return hipGetLastError();
+}
+
+// db[o] = sum over images and pixels of dY (octet layout); one workgroup per octet, fixed order
+template <int DT>
+__global__ void bias_grad_h_kernel(const uint4v *dy, float *db, int n, int c, long plane)
+{
+    __shared__ float sh[4][8];
+    const int c8 = (c + 7) / 8, o = blockIdx.x;
+    float v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = 0.f;
+    for (int b = 0; b < n; ++b) {
+        const uint4v *src = dy + ((long)b * c8 + o) * plane;
+        for (long q = threadIdx.x; q < plane; q += blockDim.x) {
+            const uint4v u = src[q];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] += up16<DT>(elem16(u, e));
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        for (int off = 32; off > 0; off >>= 1) v[e] += __shfl_down(v[e], off, 64);
+        if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6][e] = v[e];
+    }
+    __syncthreads();
+    if (threadIdx.x < 8 && o * 8 + threadIdx.x < c)
+        db[o * 8 + threadIdx.x] = sh[0][threadIdx.x] + sh[1][threadIdx.x] + sh[2][threadIdx.x] + sh[3][threadIdx.x];
+}
+
+hipError_t launch_bias_grad_h(const void *dy, float *db, int dtype, int n, int c, long plane, hipStream_t stream)
+{
+    if (dtype == 1)
+        hipLaunchKernelGGL(bias_grad_h_kernel<1>, dim3((c + 7) / 8), dim3(256), 0, stream, static_cast<const uint4v *>(dy), db, n, c, plane);
+    else
+        hipLaunchKernelGGL(bias_grad_h_kernel<2>, dim3((c + 7) / 8), dim3(256), 0, stream, static_cast<const uint4v *>(dy), db, n, c, plane);
+    return hipGetLastError();
+}
+
+}  // namespace sk

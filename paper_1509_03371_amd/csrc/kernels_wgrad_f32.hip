@@ -23,8 +23,15 @@ constexpr int WG_SEG = 64;          // output pixels per segment
 constexpr int WG_DYP = WG_SEG + 4;  // LDS pitch of a dY row
 constexpr int WG_MAX_BLOCKS = 512;
 
+typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
+
+template <int DT> __device__ __forceinline__ float up16(unsigned u);
+template <> __device__ __forceinline__ float up16<0>(unsigned u) { return __uint_as_float(u); }
+template <> __device__ __forceinline__ float up16<1>(unsigned u) { return __uint_as_float(u << 16); }
+template <> __device__ __forceinline__ float up16<2>(unsigned u) { return (float)__builtin_bit_cast(_Float16, (unsigned short)u); }
+
 struct WgradArgs {
-    const float *x, *dy;
+    const void *x, *dy;     // fp32 NCHW planar (DT = 0) or 16-bit octet layout (DT = 1 bf16, 2 fp16)
     float *scratch;
     int n, c_in, H, W, c_out, k, d, Ho, Wo;
     int MTo, NTk;          // 16-wide tiles over output maps / over (c,i,j)
@@ -32,7 +39,7 @@ struct WgradArgs {
     int xpitch;            // LDS pitch of an input row
 };
 
-template <int MB, int NB>
+template <int MB, int NB, int DT>
 __global__ __launch_bounds__(256) void wgrad_f32_kernel(WgradArgs a)
 {
     extern __shared__ float smem[];
@@ -73,18 +80,55 @@ __global__ __launch_bounds__(256) void wgrad_f32_kernel(WgradArgs a)
         const int y = t % a.Ho, b = t / a.Ho;
         const int x0 = xs_i * WG_SEG;
         __syncthreads();
-        // dY rows of this segment (zero beyond the map and for padded output maps)
-        for (int row = wave; row < m_rows; row += 4) {
-            float v = 0.f;
-            if (row < a.c_out && x0 + lane < a.Wo) v = a.dy[((long)b * a.c_out + row) * yplane + (long)y * a.Wo + x0 + lane];
-            dys[row * WG_DYP + lane] = v;
-        }
-        // input rows y + i*d for every map
-        for (int row = wave; row < a.c_in * k; row += 4) {
-            const int c = row / k, i = row - c * k;
-            const float *src = a.x + ((long)b * a.c_in + c) * xplane + (long)(y + i * d) * a.W + x0;
-            float *dst = xs + row * a.xpitch;
-            for (int xc = lane; xc < PW; xc += 64) dst[xc] = (x0 + xc < a.W) ? src[xc] : 0.f;
+        if constexpr (DT == 0) {
+            const float *dyp = static_cast<const float *>(a.dy), *xp = static_cast<const float *>(a.x);
+            // dY rows of this segment (zero beyond the map and for padded output maps)
+            const int xl = x0 + lane < a.Wo ? x0 + lane : a.Wo - 1;
+#pragma unroll 4
+            for (int row = wave; row < m_rows; row += 4) {
+                const int rc = row < a.c_out ? row : a.c_out - 1;
+                const float v = dyp[((long)b * a.c_out + rc) * yplane + (long)y * a.Wo + xl];
+                dys[row * WG_DYP + lane] = (row < a.c_out && x0 + lane < a.Wo) ? v : 0.f;
+            }
+            // input rows y + i*d for every map
+            for (int row = wave; row < a.c_in * k; row += 4) {
+                const int c = row / k, i = row - c * k;
+                const float *src = xp + ((long)b * a.c_in + c) * xplane + (long)(y + i * d) * a.W;
+                float *dst = xs + row * a.xpitch;
+#pragma unroll 3
+                for (int xc = lane; xc < PW; xc += 64) {
+                    const int gx = x0 + xc < a.W ? x0 + xc : a.W - 1;
+                    const float v = src[gx];
+                    dst[xc] = (x0 + xc < a.W) ? v : 0.f;
+                }
+            }
+        } else {
+            // 16-bit octet layout: one 16-byte load brings 8 maps of a pixel; widen to fp32 in LDS
+            const uint4v *dyp = static_cast<const uint4v *>(a.dy), *xp = static_cast<const uint4v *>(a.x);
+            const int c8o = (a.c_out + 7) / 8, c8i = (a.c_in + 7) / 8;
+            const int xl = x0 + lane < a.Wo ? x0 + lane : a.Wo - 1;
+#pragma unroll 2
+            for (int oc = wave; oc < a.MTo * 2; oc += 4) {
+                const int occ = oc < c8o ? oc : c8o - 1;
+                const uint4v u = dyp[((long)b * c8o + occ) * yplane + (long)y * a.Wo + xl];
+                const bool ok = oc < c8o && x0 + lane < a.Wo;
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    dys[(oc * 8 + e) * WG_DYP + lane] = ok ? up16<DT>((u[e >> 1] >> ((e & 1) * 16)) & 0xffffu) : 0.f;
+            }
+            for (int rid = wave; rid < c8i * k; rid += 4) {
+                const int oc = rid / k, i = rid - oc * k;
+                const uint4v *src = xp + ((long)b * c8i + oc) * xplane + (long)(y + i * d) * a.W;
+#pragma unroll 3
+                for (int xc = lane; xc < PW; xc += 64) {
+                    const int gx = x0 + xc < a.W ? x0 + xc : a.W - 1;
+                    const uint4v u = src[gx];
+                    const bool ok = x0 + xc < a.W;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        xs[((oc * 8 + e) * k + i) * a.xpitch + xc] = ok ? up16<DT>((u[e >> 1] >> ((e & 1) * 16)) & 0xffffu) : 0.f;
+                }
+            }
         }
         __syncthreads();
 #pragma unroll 2
@@ -165,24 +209,24 @@ size_t wgrad_f32_scratch_floats(int c_out, int c_in, int k)
     return (size_t)WG_MAX_BLOCKS * MTo * 16 * NTk * 16;
 }
 
-template <int MB, int NB>
+template <int MB, int NB, int DT>
 static hipError_t launch_wgrad_t(const WgradArgs &a, size_t smem, int blocks, hipStream_t stream)
 {
     static bool attr_set = false;
     if (smem > 48 * 1024 && !attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_f32_kernel<MB, NB>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_f32_kernel<MB, NB, DT>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const int mgroups = (a.MTo + MB - 1) / MB, ngroups = (a.NTk + 4 * NB - 1) / (4 * NB);
-    hipLaunchKernelGGL((wgrad_f32_kernel<MB, NB>), dim3(blocks, mgroups * ngroups), dim3(256), smem, stream, a);
+    hipLaunchKernelGGL((wgrad_f32_kernel<MB, NB, DT>), dim3(blocks, mgroups * ngroups), dim3(256), smem, stream, a);
     return hipGetLastError();
 }
 
-hipError_t launch_wgrad_f32(const float *x, const float *dy, float *dw, float *db, float *scratch,
-                            int n, int c_in, int H, int W, int c_out, int k, int d,
-                            hipStream_t stream)
+template <int DT>
+static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, float *scratch, int n, int c_in, int H,
+                                  int W, int c_out, int k, int d, hipStream_t stream)
 {
     WgradArgs a;
     a.x = x; a.dy = dy; a.scratch = scratch;
@@ -195,11 +239,12 @@ hipError_t launch_wgrad_f32(const float *x, const float *dy, float *dw, float *d
     a.total_segs = a.xsegs * a.Ho * n;
     const int PW = WG_SEG + (k - 1) * d;
     a.xpitch = (PW + 31) / 32 * 32 + 4;
-    const size_t smem = sizeof(float) * ((size_t)a.MTo * 16 * WG_DYP + (size_t)c_in * k * a.xpitch);
+    const int x_rows = (DT == 0 ? c_in : (c_in + 7) / 8 * 8) * k;
+    const size_t smem = sizeof(float) * ((size_t)a.MTo * 16 * WG_DYP + (size_t)x_rows * a.xpitch);
     if (smem > 150 * 1024) return hipErrorInvalidValue;
     const int blocks = a.total_segs < WG_MAX_BLOCKS ? a.total_segs : WG_MAX_BLOCKS;
     hipError_t e = hipErrorInvalidValue;
-#define SK_WG_CASE(mb, nb) if (MB == mb && NB == nb) e = launch_wgrad_t<mb, nb>(a, smem, blocks, stream);
+#define SK_WG_CASE(mb, nb) if (MB == mb && NB == nb) e = launch_wgrad_t<mb, nb, DT>(a, smem, blocks, stream);
     SK_WG_CASE(1, 1) SK_WG_CASE(1, 4) SK_WG_CASE(1, 12)
     SK_WG_CASE(3, 1) SK_WG_CASE(3, 4) SK_WG_CASE(3, 12)
     SK_WG_CASE(4, 1) SK_WG_CASE(4, 4) SK_WG_CASE(4, 12)
@@ -209,10 +254,31 @@ hipError_t launch_wgrad_f32(const float *x, const float *dy, float *dw, float *d
     const long total = (long)c_out * K;
     hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((int)((total + 255) / 256)), dim3(256), 0, stream, scratch, dw,
                        blocks, c_out, K, a.MTo * 16, a.NTk * 16);
+    return hipGetLastError();
+}
+
+hipError_t launch_wgrad_f32(const float *x, const float *dy, float *dw, float *db, float *scratch,
+                            int n, int c_in, int H, int W, int c_out, int k, int d,
+                            hipStream_t stream)
+{
+    hipError_t e = launch_wgrad_dt<0>(x, dy, dw, scratch, n, c_in, H, W, c_out, k, d, stream);
+    if (e != hipSuccess) return e;
     if (db)
         hipLaunchKernelGGL(bias_grad_kernel, dim3(c_out), dim3(256), 0, stream, dy, db, n, c_out,
-                           (long)a.Ho * a.Wo);
+                           (long)(H - (k - 1) * d) * (W - (k - 1) * d));
     return hipGetLastError();
+}
+
+// same gradient from 16-bit octet-layout activations (dtype 1 = bf16, 2 = fp16): the operands are
+// widened to fp32 while they are staged, the contraction runs on the fp32 MFMA path
+hipError_t launch_wgrad_h(const void *x, const void *dy, float *dw, float *db, float *scratch, int dtype,
+                          int n, int c_in, int H, int W, int c_out, int k, int d, hipStream_t stream)
+{
+    hipError_t e = dtype == 1 ? launch_wgrad_dt<1>(x, dy, dw, scratch, n, c_in, H, W, c_out, k, d, stream)
+                              : launch_wgrad_dt<2>(x, dy, dw, scratch, n, c_in, H, W, c_out, k, d, stream);
+    if (e != hipSuccess) return e;
+    if (db) return launch_bias_grad_h(dy, db, dtype, n, c_out, (long)(H - (k - 1) * d) * (W - (k - 1) * d), stream);
+    return hipSuccess;
 }
 
 }  // namespace sk

@@ -53,7 +53,8 @@ struct ConvParams {
     int c_in = 0, c_out = 0, k = 1;
     std::vector<float> w, b;   // host master, OIHW and [c_out]
     float *w_dev = nullptr, *b_dev = nullptr;   // b_dev has n_pad entries (zero padded)
-    float *wp_fwd = nullptr, *wp_bwd = nullptr;
+    float *wp_fwd = nullptr, *wp_bwd = nullptr;       // fp32 packings
+    float *wp16_fwd = nullptr, *wp16_bwd = nullptr;   // 16-bit packings (typed loosely; see kernels_conv_h.hip)
     float *dw = nullptr, *db = nullptr, *vw = nullptr, *vb = nullptr;
     int n_pad = 0, rows_fwd = 0;          // forward packing: [rows_fwd][n_pad]
     int n_pad_bwd = 0, rows_bwd = 0;      // data-gradient packing: [rows_bwd][n_pad_bwd]
@@ -69,6 +70,7 @@ inline void free_dev(float *&p)
 inline void release_conv(ConvParams &c)
 {
     free_dev(c.w_dev); free_dev(c.b_dev); free_dev(c.wp_fwd); free_dev(c.wp_bwd);
+    free_dev(c.wp16_fwd); free_dev(c.wp16_bwd);
     free_dev(c.dw); free_dev(c.db); free_dev(c.vw); free_dev(c.vb);
 }
 
@@ -80,21 +82,34 @@ inline sk_status alloc_f(float **p, long count)
     return SK_OK;
 }
 
+// rebuild the packed forms of one conv from its device master weights (asynchronous)
+inline sk_status repack_conv(ConvParams &c, bool training, int dtype, hipStream_t stream)
+{
+    if (dtype == SK_F32) {
+        SK_HIP(sk::launch_pack_weights_f32(c.w_dev, c.wp_fwd, c.c_out, c.c_in, c.k, 0, c.rows_fwd, c.n_pad, stream));
+        if (training && c.wp_bwd)
+            SK_HIP(sk::launch_pack_weights_f32(c.w_dev, c.wp_bwd, c.c_out, c.c_in, c.k, 1, c.rows_bwd, c.n_pad_bwd, stream));
+    } else {
+        SK_HIP(sk::launch_pack_weights_h(c.w_dev, c.wp16_fwd, dtype, c.c_out, c.c_in, c.k, 0, stream));
+        if (training && c.wp16_bwd)
+            SK_HIP(sk::launch_pack_weights_h(c.w_dev, c.wp16_bwd, dtype, c.c_out, c.c_in, c.k, 1, stream));
+    }
+    return SK_OK;
+}
+
 // upload master weights and rebuild the packed forms (synchronous on `stream`)
-inline sk_status upload_conv(ConvParams &c, bool training, hipStream_t stream)
+inline sk_status upload_conv(ConvParams &c, bool training, hipStream_t stream, int dtype = SK_F32)
 {
     SK_HIP(hipMemcpyAsync(c.w_dev, c.w.data(), sizeof(float) * c.wcount(), hipMemcpyHostToDevice, stream));
     std::vector<float> bp(c.n_pad, 0.f);
     std::memcpy(bp.data(), c.b.data(), sizeof(float) * c.c_out);
     SK_HIP(hipMemcpyAsync(c.b_dev, bp.data(), sizeof(float) * c.n_pad, hipMemcpyHostToDevice, stream));
-    SK_HIP(sk::launch_pack_weights_f32(c.w_dev, c.wp_fwd, c.c_out, c.c_in, c.k, 0, c.rows_fwd, c.n_pad, stream));
-    if (training && c.wp_bwd)
-        SK_HIP(sk::launch_pack_weights_f32(c.w_dev, c.wp_bwd, c.c_out, c.c_in, c.k, 1, c.rows_bwd, c.n_pad_bwd, stream));
+    SK_TRY(repack_conv(c, training, dtype, stream));
     SK_HIP(hipStreamSynchronize(stream));
     return SK_OK;
 }
 
-inline sk_status alloc_conv(ConvParams &c, bool training)
+inline sk_status alloc_conv(ConvParams &c, bool training, int dtype = SK_F32)
 {
     release_conv(c);
     c.n_pad = round_up(c.c_out, 16);
@@ -103,9 +118,14 @@ inline sk_status alloc_conv(ConvParams &c, bool training)
     c.rows_bwd = round_up(c.c_out, 16) * c.k * c.k;
     SK_TRY(alloc_f(&c.w_dev, c.wcount()));
     SK_TRY(alloc_f(&c.b_dev, c.n_pad));
-    SK_TRY(alloc_f(&c.wp_fwd, (long)c.rows_fwd * c.n_pad));
+    if (dtype == SK_F32) {
+        SK_TRY(alloc_f(&c.wp_fwd, (long)c.rows_fwd * c.n_pad));
+        if (training) SK_TRY(alloc_f(&c.wp_bwd, (long)c.rows_bwd * c.n_pad_bwd));
+    } else {   // 16-bit elements, allocated in floats
+        SK_TRY(alloc_f(&c.wp16_fwd, (sk::packed_h_elems(c.c_out, (c.c_in + 7) / 8, c.k) + 1) / 2));
+        if (training) SK_TRY(alloc_f(&c.wp16_bwd, (sk::packed_h_elems(c.c_in, (c.c_out + 7) / 8, c.k) + 1) / 2));
+    }
     if (training) {
-        SK_TRY(alloc_f(&c.wp_bwd, (long)c.rows_bwd * c.n_pad_bwd));
         SK_TRY(alloc_f(&c.dw, c.wcount()));
         SK_TRY(alloc_f(&c.db, c.c_out));
         SK_TRY(alloc_f(&c.vw, c.wcount()));
@@ -114,6 +134,22 @@ inline sk_status alloc_conv(ConvParams &c, bool training)
         SK_HIP(hipMemset(c.vb, 0, sizeof(float) * c.c_out));
     }
     return SK_OK;
+}
+
+// element counts on the 16-bit octet layout, expressed in floats (what alloc_f takes)
+inline long octet_floats(int n, const Dims &d) { return (long)n * ((d.c + 7) / 8) * d.h * d.w * 4; }
+
+inline sk::ConvHArgs conv_h_args(const ConvParams &c, int dtype, const void *x, int n, const Dims &in, int d, int relu,
+                                 void *y, const Dims &out, bool out_f32)
+{
+    sk::ConvHArgs a{};
+    a.x = x; a.wp = c.wp16_fwd; a.bias = c.b_dev; a.mask = nullptr; a.y = y; a.dtype = dtype;
+    a.n = n; a.c8_in = (in.c + 7) / 8; a.H = in.h; a.W = in.w;
+    a.c_out = c.c_out; a.c8_out = (c.c_out + 7) / 8;
+    a.k = c.k; a.d = d; a.in_off = 0; a.Ho = out.h; a.Wo = out.w; a.relu = relu; a.out_f32 = out_f32 ? 1 : 0;
+    a.c8_out_total = (out.c + 7) / 8; a.o8_off = 0; a.OH = out.h; a.OW = out.w;
+    a.oy_mul = 1; a.oy_off = 0; a.ox_mul = 1; a.ox_off = 0;
+    return a;
 }
 
 inline sk::ConvF32Args conv_args(const ConvParams &c, const float *x, int n, const Dims &in, int d, int relu,

@@ -36,6 +36,48 @@ hipError_t launch_conv_f32(const ConvF32Args &a, hipStream_t stream);
 hipError_t launch_pack_weights_f32(const float *w_oihw, float *wp, int c_out, int c_in, int k,
                                    int flip_transpose, int rows, int n_pad, hipStream_t stream);
 
+// ---- implicit-GEMM SK convolution, 16-bit activations (dtype 1 = bf16, 2 = fp16), MFMA 16x16x32 -------
+// Same contract as launch_conv_f32, on the octet layout: a tensor with C maps is stored as
+// [n][ceil(C/8)][H][W][8] 16-bit elements (maps beyond C are zero).  k in 1..4, (k-1)*d <= 64.
+struct ConvHArgs {
+    const void *x;        // input, octet layout, c8_in octets
+    const void *wp;       // packed weights (launch_pack_weights_h)
+    const float *bias;    // fp32 [roundup(c_out,16)] or nullptr
+    const void *mask;     // optional, octet layout, indexed like y: output zeroed where mask <= 0
+    void *y;              // octet layout (out_f32 = 0) or fp32 NCHW planar [n][c_out][OH][OW] (out_f32 = 1)
+    int dtype;
+    int n, c8_in, H, W;
+    int c_out, c8_out;    // real output maps and ceil(c_out/8)
+    int k, d, in_off;
+    int Ho, Wo;
+    int relu, out_f32;
+    int c8_out_total, o8_off, OH, OW, oy_mul, oy_off, ox_mul, ox_off;
+    // filled in by the launcher
+    int m_tiles, mgroups, nchunks, xtiles, tiles_hi, tiles_lo, rem, ytiles_total, total_tiles;
+};
+bool conv_h_supported(int k, int d);
+hipError_t launch_conv_h(const ConvHArgs &a, hipStream_t stream);
+// 16-bit elements of the packed weights of a GEMM with gemm_m output maps and gemm_c8 input octets
+long packed_h_elems(int gemm_m, int gemm_c8, int k);
+// forward packing (flip_transpose = 0: gemm_m = c_out, input octets of c_in) or data-gradient
+// packing (flip_transpose = 1: gemm_m = c_in, input octets of c_out) from OIHW fp32 master weights
+hipError_t launch_pack_weights_h(const float *w_oihw, void *wp, int dtype, int c_out, int c_in, int k,
+                                 int flip_transpose, hipStream_t stream);
+
+// ---- HBM-bound layers on the octet layout (dtype 1 = bf16, 2 = fp16) ------------------------------------
+// fp32 NCHW -> octets with optional mirror padding (top = left = 0 and ho = h, wo = w: plain conversion)
+hipError_t launch_pad_pack_h(const float *in, void *out, int dtype, int n, int c, int h, int w, int top, int left,
+                             int ho, int wo, int mode, hipStream_t stream);
+hipError_t launch_unpack_h(const void *in, float *out, int dtype, int n, int c, int h, int w, hipStream_t stream);
+// planes8 = n * ceil(C/8); tap (optional) holds one byte per element, laid out like y
+hipError_t launch_maxpool_h(const void *x, void *y, void *tap, int dtype, long planes8, int H, int W, int Ho, int Wo,
+                            int k, int d, int s, hipStream_t stream);
+hipError_t launch_maxpool_bwd_h(const void *dy, const void *tap, const void *relu_src, void *dx, int dtype,
+                                long planes8, int H, int W, int Ho, int Wo, int k, int d, hipStream_t stream);
+hipError_t launch_tap_to_index_h(const void *tap, int32_t *idx, int n, int c, int Ho, int Wo, int W, int k, int d, int s,
+                                 hipStream_t stream);
+hipError_t launch_bias_grad_h(const void *dy, float *db, int dtype, int n, int c, long plane, hipStream_t stream);
+
 // ---- weight / bias gradient of the SK convolution (fp32) ---------------------------------------
 // dW[o][c][i][j] = sum_{b,y,x} dY[b,o,y,x] * X[b,c,y+i*d,x+j*d];  db[o] = sum dY[b,o,:,:].
 // scratch must hold wgrad_scratch_floats(...) floats; the result is deterministic.
@@ -43,6 +85,9 @@ size_t wgrad_f32_scratch_floats(int c_out, int c_in, int k);
 hipError_t launch_wgrad_f32(const float *x, const float *dy, float *dw, float *db, float *scratch,
                             int n, int c_in, int H, int W, int c_out, int k, int d,
                             hipStream_t stream);
+
+hipError_t launch_wgrad_h(const void *x, const void *dy, float *dw, float *db, float *scratch, int dtype,
+                          int n, int c_in, int H, int W, int c_out, int k, int d, hipStream_t stream);
 
 // ---- HBM-bound layers ---------------------------------------------------------------------------
 hipError_t launch_mirror_pad_f32(const float *in, float *out, int planes, int h, int w, int top,

@@ -23,6 +23,9 @@ struct sknet {
     std::vector<uint8_t *> tap;       // per layer (pools on a training plan), else nullptr
     float *gbuf[2] = {nullptr, nullptr};
     float *loss_partial = nullptr, *wgrad_scratch = nullptr;
+    float *logits_f32 = nullptr;      // 16-bit nets: fp32 logits when the last layer is a pool; else alias of act[L]
+    float *dz_f32 = nullptr;          // 16-bit training: fp32 gradient of the logits before it is packed
+    bool half() const { return dtype != SK_F32; }
     bool forward_done = false, backward_done = false;
     hipStream_t last_stream = nullptr;
     const float *last_image = nullptr;
@@ -38,6 +41,7 @@ struct sknet {
         }
         tap.clear();
         free_dev(gbuf[0]); free_dev(gbuf[1]); free_dev(loss_partial); free_dev(wgrad_scratch);
+        free_dev(logits_f32); free_dev(dz_f32);
         for (auto &c : convs) release_conv(c);
         planned = forward_done = backward_done = false;
     }
@@ -99,9 +103,14 @@ sk_status check_net(const sknet_t *net)
 sk_status run_forward_step(sknet *net, int step, hipStream_t stream)
 {
     const int L = (int)net->layers.size();
+    const bool half = net->half();
     if (step == 0) {
         const Dims &d0 = net->dims[0];
-        if (net->pad)
+        if (half)   // mirror padding fused into the conversion to the 16-bit octet layout
+            SK_HIP(sk::launch_pad_pack_h(net->last_image, net->act[0], net->dtype, net->n, net->c_in, net->h, net->w,
+                                         net->pad ? net->pad_top : 0, net->pad ? net->pad_left : 0, d0.h, d0.w,
+                                         net->pad_mode, stream));
+        else if (net->pad)
             SK_HIP(sk::launch_mirror_pad_f32(net->last_image, net->act[0], net->n * net->c_in, net->h, net->w,
                                              net->pad_top, net->pad_left, d0.h, d0.w, net->pad_mode, stream));
         else
@@ -115,8 +124,17 @@ sk_status run_forward_step(sknet *net, int step, hipStream_t stream)
         const Dims &in = net->dims[li], &out = net->dims[li + 1];
         if (l.kind == SK_CONV) {
             const ConvParams &c = net->convs[net->conv_of_layer[li]];
-            sk::ConvF32Args a = conv_args(c, net->act[li], net->n, in, l.d, l.relu, net->act[li + 1], out);
-            SK_HIP(sk::launch_conv_f32(a, stream));
+            if (half) {
+                sk::ConvHArgs a = conv_h_args(c, net->dtype, net->act[li], net->n, in, l.d, l.relu, net->act[li + 1], out,
+                                              li == L - 1);   // the last conv writes fp32 logits
+                SK_HIP(sk::launch_conv_h(a, stream));
+            } else {
+                sk::ConvF32Args a = conv_args(c, net->act[li], net->n, in, l.d, l.relu, net->act[li + 1], out);
+                SK_HIP(sk::launch_conv_f32(a, stream));
+            }
+        } else if (half) {
+            SK_HIP(sk::launch_maxpool_h(net->act[li], net->act[li + 1], net->tap[li], net->dtype,
+                                        (long)net->n * ((in.c + 7) / 8), in.h, in.w, out.h, out.w, l.k, l.d, l.s, stream));
         } else {
             SK_HIP(sk::launch_maxpool_f32(net->act[li], net->act[li + 1], net->tap[li], net->n * in.c, in.h, in.w,
                                           out.h, out.w, l.k, l.d, l.s, stream));
@@ -124,8 +142,20 @@ sk_status run_forward_step(sknet *net, int step, hipStream_t stream)
         return SK_OK;
     }
     const Dims &o = net->dims[L];
-    SK_HIP(sk::launch_softmax_f32(net->act[L], net->last_prob, net->n, o.c, o.h * o.w, stream));
+    const float *logits = net->act[L];
+    if (half && net->layers[L - 1].kind != SK_CONV) {
+        SK_HIP(sk::launch_unpack_h(net->act[L], net->logits_f32, net->dtype, net->n, o.c, o.h, o.w, stream));
+        logits = net->logits_f32;
+    }
+    SK_HIP(sk::launch_softmax_f32(logits, net->last_prob, net->n, o.c, o.h * o.w, stream));
     return SK_OK;
+}
+
+// does layer i (0-based) store its output as fp32 NCHW?  (always for fp32 nets; for 16-bit nets
+// only the last layer when it is a conv: it writes the fp32 logits)
+bool stored_f32(const sknet *net, int i)
+{
+    return !net->half() || (i == (int)net->layers.size() - 1 && net->layers[i].kind == SK_CONV);
 }
 
 }  // namespace
@@ -184,10 +214,7 @@ sk_status sknet_create(const sk_layer *layers, int32_t n_layers, int32_t c_in, i
     *out = nullptr;
     if (!layers || n_layers < 1 || c_in < 1 || n_classes < 1) return fail(SK_EINVAL, "create: bad arguments");
     if (pad_mode != 0 && pad_mode != 1) return fail(SK_EINVAL, "create: pad_mode must be 0 or 1");
-    if (dtype != SK_F32) {
-        if (dtype == SK_BF16 || dtype == SK_F16) return fail(SK_EUNSUPPORTED, "create: only SK_F32 is built");
-        return fail(SK_EINVAL, "create: bad dtype");
-    }
+    if (dtype != SK_F32 && dtype != SK_BF16 && dtype != SK_F16) return fail(SK_EINVAL, "create: bad dtype");
     sknet *net = new (std::nothrow) sknet;
     if (!net) return fail(SK_ENOMEM, "create: out of host memory");
     net->c_in = c_in; net->n_classes = n_classes; net->dtype = dtype; net->pad_mode = pad_mode;
@@ -201,6 +228,8 @@ sk_status sknet_create(const sk_layer *layers, int32_t n_layers, int32_t c_in, i
         else if (l.kind == SK_CONV && (l.s != 1 || l.c_out < 1)) bad = fail(SK_ESHAPE, "layer %d: conv needs s = 1 and c_out >= 1", i);
         else if (l.kind == SK_MAXPOOL && !(l.s == 1 || (l.s == l.k && l.d == 1)))
             bad = fail(SK_ESHAPE, "layer %d: pool needs s = 1, or s = k with d = 1", i);
+        else if (dtype != SK_F32 && l.kind == SK_CONV && !sk::conv_h_supported(l.k, l.d))
+            bad = fail(SK_EUNSUPPORTED, "layer %d: 16-bit convolutions need k <= 4 and (k-1)*d <= 64", i);
         if (bad != SK_OK) {
             delete net;
             return bad;
@@ -282,7 +311,7 @@ sk_status sknet_set_weights(sknet_t *net, int32_t conv_idx, const float *w_host,
     ConvParams &c = net->convs[conv_idx];
     std::memcpy(c.w.data(), w_host, sizeof(float) * c.wcount());
     if (b_host) std::memcpy(c.b.data(), b_host, sizeof(float) * c.c_out);
-    if (net->planned) SK_TRY(upload_conv(c, net->training, net->last_stream));
+    if (net->planned) SK_TRY(upload_conv(c, net->training, net->last_stream, net->dtype));
     return SK_OK;
 }
 
@@ -324,23 +353,29 @@ sk_status sknet_plan(sknet_t *net, int32_t n, int32_t h, int32_t w, int32_t pad,
     net->dims = dims;
     net->act.assign(L + 1, nullptr);
     net->tap.assign(L, nullptr);
-    long max_count = 0;
+    long max_count = 0;   // largest activation, in floats (16-bit tensors counted in floats as well)
     sk_status st = SK_OK;
+    const bool half = net->half();
     for (int i = 0; i <= L && st == SK_OK; ++i) {
-        st = alloc_f(&net->act[i], dims[i].count(n));
-        if (dims[i].count(n) > max_count) max_count = dims[i].count(n);
+        const bool f32 = (i == 0) ? !half : stored_f32(net, i - 1);
+        const long count = f32 ? dims[i].count(n) : octet_floats(n, dims[i]);
+        st = alloc_f(&net->act[i], count);
+        if (count > max_count) max_count = count;
     }
+    if (st == SK_OK && half && net->layers[L - 1].kind != SK_CONV) st = alloc_f(&net->logits_f32, dims[L].count(n));
     size_t scratch = 0;
     for (int i = 0; i < L && st == SK_OK; ++i) {
         const sk_layer &l = net->layers[i];
         if (l.kind == SK_MAXPOOL && training) {
-            hipError_t e = hipMalloc(reinterpret_cast<void **>(&net->tap[i]), (size_t)dims[i + 1].count(n));
+            const size_t bytes = half ? (size_t)n * ((dims[i + 1].c + 7) / 8) * dims[i + 1].h * dims[i + 1].w * 8
+                                      : (size_t)dims[i + 1].count(n);
+            hipError_t e = hipMalloc(reinterpret_cast<void **>(&net->tap[i]), bytes);
             if (e != hipSuccess) st = fail(SK_ENOMEM, "plan: hipMalloc of a pool mask failed: %s", hipGetErrorString(e));
         }
         if (l.kind == SK_CONV) {
             ConvParams &c = net->convs[net->conv_of_layer[i]];
-            st = alloc_conv(c, training != 0);
-            if (st == SK_OK) st = upload_conv(c, training != 0, nullptr);
+            st = alloc_conv(c, training != 0, net->dtype);
+            if (st == SK_OK) st = upload_conv(c, training != 0, nullptr, net->dtype);
             const size_t s = sk::wgrad_f32_scratch_floats(c.c_out, c.c_in, c.k);
             if (s > scratch) scratch = s;
         }
@@ -350,6 +385,7 @@ sk_status sknet_plan(sknet_t *net, int32_t n, int32_t h, int32_t w, int32_t pad,
         if (st == SK_OK) st = alloc_f(&net->gbuf[1], max_count);
         if (st == SK_OK) st = alloc_f(&net->loss_partial, sk::softmax_loss_partials((long)n * dims[L].h * dims[L].w));
         if (st == SK_OK) st = alloc_f(&net->wgrad_scratch, (long)scratch);
+        if (st == SK_OK && half) st = alloc_f(&net->dz_f32, dims[L].count(n));
     }
     if (st != SK_OK) {
         std::string keep = g_last_error;
@@ -389,10 +425,16 @@ sk_status sknet_backward(sknet_t *net, const int32_t *labels_dev, float *loss_de
     const int L = (int)net->layers.size(), n = net->n;
     const Dims &o = net->dims[L];
     float *gcur = net->gbuf[0], *gnext = net->gbuf[1];
-    SK_HIP(sk::launch_softmax_loss_f32(net->act[L], labels_dev, gcur, loss_dev, net->loss_partial, n, o.c,
-                                       o.h * o.w, stream));
-    if (net->layers[L - 1].kind == SK_CONV && net->layers[L - 1].relu)
-        SK_HIP(sk::launch_relu_mask_f32(gcur, net->act[L], o.count(n), stream));
+    const bool half = net->half();
+    const int dt = net->dtype;
+    {
+        const float *logits = (half && net->layers[L - 1].kind != SK_CONV) ? net->logits_f32 : net->act[L];
+        float *dz = half ? net->dz_f32 : gcur;
+        SK_HIP(sk::launch_softmax_loss_f32(logits, labels_dev, dz, loss_dev, net->loss_partial, n, o.c, o.h * o.w, stream));
+        if (net->layers[L - 1].kind == SK_CONV && net->layers[L - 1].relu)
+            SK_HIP(sk::launch_relu_mask_f32(dz, net->act[L], o.count(n), stream));
+        if (half) SK_HIP(sk::launch_pad_pack_h(dz, gcur, dt, n, o.c, o.h, o.w, 0, 0, o.h, o.w, 0, stream));
+    }
     for (int li = L - 1; li >= 0; --li) {
         const sk_layer &l = net->layers[li];
         const Dims &in = net->dims[li], &out = net->dims[li + 1];
@@ -402,22 +444,41 @@ sk_status sknet_backward(sknet_t *net, const int32_t *labels_dev, float *loss_de
                                     ? net->act[li] : nullptr;
         if (l.kind == SK_CONV) {
             ConvParams &c = net->convs[net->conv_of_layer[li]];
-            SK_HIP(sk::launch_wgrad_f32(net->act[li], gcur, c.dw, c.db, net->wgrad_scratch, n, in.c, in.h, in.w,
-                                        c.c_out, c.k, l.d, stream));
+            if (half)
+                SK_HIP(sk::launch_wgrad_h(net->act[li], gcur, c.dw, c.db, net->wgrad_scratch, dt, n, in.c, in.h, in.w,
+                                          c.c_out, c.k, l.d, stream));
+            else
+                SK_HIP(sk::launch_wgrad_f32(net->act[li], gcur, c.dw, c.db, net->wgrad_scratch, n, in.c, in.h, in.w,
+                                            c.c_out, c.k, l.d, stream));
             if (li == 0) break;   // nothing below needs the image gradient
-            sk::ConvF32Args a{};
-            a.x = gcur; a.wp = c.wp_bwd; a.bias = nullptr; a.mask = relu_src; a.y = gnext;
-            a.n = n; a.c_in = out.c; a.H = out.h; a.W = out.w;
-            a.c_out = in.c; a.n_pad = c.n_pad_bwd;
-            a.k = c.k; a.d = l.d; a.in_off = (c.k - 1) * l.d;
-            a.Ho = in.h; a.Wo = in.w; a.relu = 0;
-            a.out_maps = in.c; a.o_off = 0; a.OH = in.h; a.OW = in.w;
-            a.oy_mul = 1; a.oy_off = 0; a.ox_mul = 1; a.ox_off = 0;
-            SK_HIP(sk::launch_conv_f32(a, stream));
+            if (half) {
+                sk::ConvHArgs a{};
+                a.x = gcur; a.wp = c.wp16_bwd; a.bias = nullptr; a.mask = relu_src; a.y = gnext; a.dtype = dt;
+                a.n = n; a.c8_in = (out.c + 7) / 8; a.H = out.h; a.W = out.w;
+                a.c_out = in.c; a.c8_out = (in.c + 7) / 8;
+                a.k = c.k; a.d = l.d; a.in_off = (c.k - 1) * l.d; a.Ho = in.h; a.Wo = in.w; a.relu = 0; a.out_f32 = 0;
+                a.c8_out_total = (in.c + 7) / 8; a.o8_off = 0; a.OH = in.h; a.OW = in.w;
+                a.oy_mul = 1; a.oy_off = 0; a.ox_mul = 1; a.ox_off = 0;
+                SK_HIP(sk::launch_conv_h(a, stream));
+            } else {
+                sk::ConvF32Args a{};
+                a.x = gcur; a.wp = c.wp_bwd; a.bias = nullptr; a.mask = relu_src; a.y = gnext;
+                a.n = n; a.c_in = out.c; a.H = out.h; a.W = out.w;
+                a.c_out = in.c; a.n_pad = c.n_pad_bwd;
+                a.k = c.k; a.d = l.d; a.in_off = (c.k - 1) * l.d;
+                a.Ho = in.h; a.Wo = in.w; a.relu = 0;
+                a.out_maps = in.c; a.o_off = 0; a.OH = in.h; a.OW = in.w;
+                a.oy_mul = 1; a.oy_off = 0; a.ox_mul = 1; a.ox_off = 0;
+                SK_HIP(sk::launch_conv_f32(a, stream));
+            }
         } else {
             if (li == 0) break;
-            SK_HIP(sk::launch_maxpool_bwd_f32(gcur, net->tap[li], relu_src, gnext, n * in.c, in.h, in.w, out.h,
-                                              out.w, l.k, l.d, stream));
+            if (half)
+                SK_HIP(sk::launch_maxpool_bwd_h(gcur, net->tap[li], relu_src, gnext, dt, (long)n * ((in.c + 7) / 8), in.h,
+                                                in.w, out.h, out.w, l.k, l.d, stream));
+            else
+                SK_HIP(sk::launch_maxpool_bwd_f32(gcur, net->tap[li], relu_src, gnext, n * in.c, in.h, in.w, out.h,
+                                                  out.w, l.k, l.d, stream));
         }
         float *t = gcur; gcur = gnext; gnext = t;
     }
@@ -435,8 +496,7 @@ sk_status sknet_sgd_step(sknet_t *net, float lr, float momentum, float weight_de
     for (auto &c : net->convs) {
         SK_HIP(sk::launch_sgd_f32(c.w_dev, c.dw, momentum != 0.f ? c.vw : nullptr, c.wcount(), lr, momentum, weight_decay, stream));
         SK_HIP(sk::launch_sgd_f32(c.b_dev, c.db, momentum != 0.f ? c.vb : nullptr, c.c_out, lr, momentum, weight_decay, stream));
-        SK_HIP(sk::launch_pack_weights_f32(c.w_dev, c.wp_fwd, c.c_out, c.c_in, c.k, 0, c.rows_fwd, c.n_pad, stream));
-        SK_HIP(sk::launch_pack_weights_f32(c.w_dev, c.wp_bwd, c.c_out, c.c_in, c.k, 1, c.rows_bwd, c.n_pad_bwd, stream));
+        SK_TRY(repack_conv(c, true, net->dtype, stream));
     }
     return SK_OK;
 }
@@ -460,7 +520,19 @@ sk_status sknet_get_activation(sknet_t *net, int32_t layer_idx, float *nchw_host
     if (!net->forward_done) return fail(SK_ESTATE, "get_activation: no forward pass yet");
     SK_HIP(hipStreamSynchronize(net->last_stream));
     const int i = layer_idx + 1;
-    SK_HIP(hipMemcpy(nchw_host, net->act[i], sizeof(float) * net->dims[i].count(net->n), hipMemcpyDeviceToHost));
+    const Dims &dm = net->dims[i];
+    const bool f32 = (i == 0) ? !net->half() : stored_f32(net, i - 1);
+    if (f32) {
+        SK_HIP(hipMemcpy(nchw_host, net->act[i], sizeof(float) * dm.count(net->n), hipMemcpyDeviceToHost));
+        return SK_OK;
+    }
+    float *tmp = nullptr;   // widen the 16-bit octet layout to fp32 NCHW on the device first
+    SK_TRY(alloc_f(&tmp, dm.count(net->n)));
+    hipError_t e = sk::launch_unpack_h(net->act[i], tmp, net->dtype, net->n, dm.c, dm.h, dm.w, net->last_stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(net->last_stream);
+    if (e == hipSuccess) e = hipMemcpy(nchw_host, tmp, sizeof(float) * dm.count(net->n), hipMemcpyDeviceToHost);
+    (void)hipFree(tmp);
+    if (e != hipSuccess) return fail(SK_EDEVICE, "get_activation: %s", hipGetErrorString(e));
     return SK_OK;
 }
 
@@ -478,7 +550,9 @@ sk_status sknet_get_pool_argmax(sknet_t *net, int32_t pool_idx, int32_t *idx_hos
     const long count = out.count(net->n);
     int32_t *tmp = nullptr;
     SK_HIP(hipMalloc(reinterpret_cast<void **>(&tmp), sizeof(int32_t) * (size_t)count));
-    hipError_t e = sk::launch_tap_to_index(net->tap[li], tmp, net->n * out.c, out.h, out.w, in.w, l.k, l.d, l.s, net->last_stream);
+    hipError_t e = net->half()
+                       ? sk::launch_tap_to_index_h(net->tap[li], tmp, net->n, out.c, out.h, out.w, in.w, l.k, l.d, l.s, net->last_stream)
+                       : sk::launch_tap_to_index(net->tap[li], tmp, net->n * out.c, out.h, out.w, in.w, l.k, l.d, l.s, net->last_stream);
     if (e == hipSuccess) e = hipStreamSynchronize(net->last_stream);
     if (e == hipSuccess) e = hipMemcpy(idx_host, tmp, sizeof(int32_t) * (size_t)count, hipMemcpyDeviceToHost);
     (void)hipFree(tmp);

@@ -1,0 +1,147 @@
+"""GPU parity of the 16-bit (bf16 / fp16 storage, fp32 accumulate) SK-Net path against the fp64
+oracle.  The oracle runs on the unrounded fp32 weights and images, so the error measured here
+contains every rounding of the 16-bit path.  Tolerance: 2e-2 of the tensor's largest magnitude on
+activations and logits (the spec bar for bf16/fp16); pooling is exact on identical inputs."""
+import numpy as np
+import pytest
+import torch
+
+import sk_synth as S
+from oracle import layers as OL, nets as ON
+
+pytestmark = pytest.mark.gpu
+
+HALF_TOL = 2e-2
+
+
+def relerr(got, ref):
+    return float(np.abs(np.asarray(got, dtype=np.float64) - ref).max() / max(np.abs(ref).max(), 1e-30))
+
+
+def make_net(layers, c_in, ws, bs, dtype):
+    from paper_1509_03371_amd import binding as B
+    convs = [l for l in layers if l["type"] == "conv"]
+    net = B.SKNet(layers, c_in, convs[-1]["f_out"] if convs else c_in, dtype=dtype)
+    for i, (w, b) in enumerate(zip(ws, bs)):
+        net.set_weights(i, w, b)
+    return net
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp16"])
+@pytest.mark.parametrize("k,d,c_in,c_out,h,w", [
+    (4, 1, 1, 48, 70, 150), (4, 2, 48, 48, 41, 131), (4, 8, 48, 48, 57, 300), (4, 4, 48, 48, 100, 129),
+    (3, 1, 64, 128, 20, 23), (1, 1, 48, 200, 19, 70), (1, 1, 200, 2, 19, 140), (3, 4, 3, 5, 30, 40),
+    (2, 3, 5, 7, 9, 200), (4, 8, 6, 4, 25, 25), (4, 2, 20, 72, 30, 135), (3, 2, 40, 48, 33, 260),
+])
+def test_conv_layer_shapes_half(dtype, k, d, c_in, c_out, h, w):
+    dt = "f16" if dtype == "fp16" else dtype
+    layers = [S.conv(c_out, k, d, relu=True), S.conv(c_out, 1, 1, relu=False)]   # 2nd conv: identity, exposes layer 0
+    ws, bs = S.he_normal_weights(layers[:1], c_in, 7 + k + d, bias_scale=0.5)
+    ws.append(np.eye(c_out, dtype=np.float32).reshape(c_out, c_out, 1, 1))
+    bs.append(np.zeros(c_out, np.float32))
+    img = np.random.default_rng(3).standard_normal((2, c_in, h, w)).astype(np.float32)
+    net = make_net(layers, c_in, ws, bs, dt)
+    net.plan(2, h, w, pad=False)
+    net.forward(torch.from_numpy(img).cuda())
+    ref = OL.conv_sk(img, ws[0], bs[0], d, relu=True)
+    got0 = net.get_activation(0)          # stored in 16 bits
+    got1 = net.get_activation(1)          # fp32 logits of the identity conv on the stored values
+    assert got0.shape == ref.shape
+    assert relerr(got0, ref) <= HALF_TOL
+    assert np.abs(got1 - got0).max() <= 1e-6 * max(1.0, np.abs(got0).max())
+    net.close()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("k,d,s,h,w", [(2, 1, 1, 33, 70), (2, 2, 1, 40, 131), (2, 8, 1, 57, 66), (3, 2, 1, 20, 21),
+                                       (2, 1, 2, 30, 62), (2, 4, 1, 9, 300)])
+def test_pool_bit_exact_half(dtype, k, d, s, h, w):
+    layers = [S.pool(k, d, s)]
+    rng = np.random.default_rng(11)
+    img = np.maximum(rng.standard_normal((2, 11, h, w)), 0).astype(np.float32)
+    net = make_net(layers, 11, [], [], dtype)
+    net.plan(2, h, w, pad=False, training=(s == 1))
+    net.forward(torch.from_numpy(img).cuda())
+    stored = net.get_activation(-1)                       # the input as the library holds it (rounded to 16 bits)
+    assert relerr(stored, img) <= 2.0 ** -8
+    ref, ref_am = OL.maxpool_sk(stored, k, d, s)
+    assert np.array_equal(net.get_activation(0).astype(np.float64), ref)
+    if s == 1:
+        assert np.array_equal(net.get_pool_argmax(0), ref_am)
+    net.close()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_small_sknet_forward_half(dtype):
+    layers = S.sknet_layers(width=48, hidden=200)
+    ws, bs = S.he_normal_weights(layers, 1, 1001, bias_scale=0.05)
+    img = S.em_like_batch(2, 100, 140, 20)
+    net = make_net(layers, 1, ws, bs, dtype)
+    net.plan(2, 100, 140, pad=True)
+    prob = net.forward(torch.from_numpy(img).cuda()).cpu().numpy()
+    ref_prob, acts, _ = ON.sknet_forward(img, layers, ws, bs, keep=True)
+    for li in range(len(layers)):
+        got = net.get_activation(li)
+        assert got.shape == acts[li + 1].shape
+        assert relerr(got, acts[li + 1]) <= HALF_TOL, (li, layers[li])
+    assert np.abs(prob - ref_prob).max() <= HALF_TOL
+    assert np.abs(prob.sum(1) - 1).max() < 1e-5
+    net.close()
+
+
+def test_mirror_pad_fused_into_packing():
+    layers = [S.conv(4, 3, 1), S.pool(2, 1), S.conv(3, 2, 2, relu=False)]     # odd context v = 5
+    ws, bs = S.he_normal_weights(layers, 2, 21, bias_scale=0.2)
+    img = S.uniform_image(2, 2, 17, 23, 5)
+    for mode in (0, 1):
+        from paper_1509_03371_amd import binding as B
+        net = B.SKNet(layers, 2, 3, dtype="bf16", pad_mode=mode)
+        for i, (w, b) in enumerate(zip(ws, bs)):
+            net.set_weights(i, w, b)
+        net.plan(2, 17, 23, pad=True)
+        prob = net.forward(torch.from_numpy(img).cuda()).cpu().numpy()
+        ref = ON.sknet_forward(img, layers, ws, bs, pad_mode=mode)
+        assert np.abs(prob - ref).max() <= HALF_TOL
+        padded = net.get_activation(-1)
+        rounded = torch.from_numpy(OL.mirror_pad(img, 3, 3, 2, 2, mode).astype(np.float32)).bfloat16().float().numpy()
+        assert np.array_equal(padded, rounded)                  # padding is a copy; conversion is round-to-nearest-even
+        net.close()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_training_step_half(dtype):
+    layers = S.sknet_layers(width=48, hidden=200)
+    ws, bs = S.he_normal_weights(layers, 1, 1001, bias_scale=0.05)
+    img = S.em_like_batch(1, 96, 130, 30)
+    labels = S.binary_labels(1, 96, 130, 31)
+    net = make_net(layers, 1, ws, bs, dtype)
+    net.plan(1, 96, 130, pad=True, training=True)
+    net.forward(torch.from_numpy(img).cuda())
+    loss = net.backward(torch.from_numpy(labels).cuda())
+    ow = [x.astype(np.float64) for x in ws]
+    ob = [x.astype(np.float64) for x in bs]
+    _, acts, ams = ON.sknet_forward(img, layers, ow, ob, keep=True)
+    ref_loss, dws, dbs, _ = ON.sknet_backward(layers, ow, acts, ams, labels)
+    assert abs(loss.item() - ref_loss) <= HALF_TOL * abs(ref_loss)
+    worst = 0.0
+    for i in range(net.num_convs()):
+        dw, db = net.get_grad(i)
+        worst = max(worst, relerr(dw, dws[i]))
+        assert relerr(dw, dws[i]) <= 5e-2, ("dW", i, relerr(dw, dws[i]))
+        assert np.abs(db - dbs[i]).max() <= 5e-2 * max(np.abs(dbs[i]).max(), np.abs(dws[i]).max()), ("db", i)
+    # SGD keeps fp32 master weights: one step matches the closed form on the library's own gradients
+    before = [net.get_weights(i) for i in range(net.num_convs())]
+    grads = [net.get_grad(i) for i in range(net.num_convs())]
+    net.sgd_step(0.01)
+    for i in range(net.num_convs()):
+        w1, b1 = net.get_weights(i)
+        assert np.abs(w1 - (before[i][0] - np.float32(0.01) * grads[i][0])).max() <= 1e-7
+        assert np.abs(b1 - (before[i][1] - np.float32(0.01) * grads[i][1])).max() <= 1e-7
+    net.close()
+
+
+def test_unsupported_kernel_size_is_reported():
+    from paper_1509_03371_amd import binding as B
+    with pytest.raises(B.SknetError) as e:
+        B.SKNet([S.conv(2, 5, 2, relu=False)], 1, 2, dtype="bf16")
+    assert e.value.status_name == "SK_EUNSUPPORTED"
