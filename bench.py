@@ -1,9 +1,13 @@
-"""Benchmark of the SK-Net hot path on one MI355X.
+"""Benchmark of the SK-Net hot path on one MI355X.  Prints ONE JSON line.
 
-Workload (BASELINE config 2): SK-Net forward on one 1x1x512x512 fp32 image -- mirror padding,
-four stages of [conv k4 -> 48 maps + ReLU, max pool k2 s1] at kernel strides 1/2/4/8, 1x1 conv
-48 -> 200 + ReLU, 1x1 conv 200 -> 2, per-pixel softmax.  A step is one such pass; the image is
-resident in HBM before the timed region.  Prints ONE JSON line.
+Default workload (BASELINE configs[1], the one the headline metric is quoted on): SK-Net forward on
+one 1x1x512x512 fp32 image -- mirror padding, four stages of [conv k4 -> 48 maps + ReLU, max pool
+k2 s1] at kernel strides 1/2/4/8, 1x1 conv 48 -> 200 + ReLU, 1x1 conv 200 -> 2, per-pixel softmax.
+A step is one such pass over one synthetic image that is resident in HBM before the timed region.
+
+--workload c3 : the same net in bf16 (fp32 accumulate) on 8 images of 1024x1024 (configs[2])
+--workload c4 : one bf16 training step at 512x512 (configs[3]): forward, softmax loss, backward, SGD
+The default run also appends short c3 / c4 measurements under "extras" (skip with --no-extras).
 """
 import argparse
 import json
@@ -14,8 +18,95 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-MFMA_FP32_PEAK_TFLOPS = 157.3     # MI355X dense fp32 matrix peak
+PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0, "f16": 2500.0}   # MI355X dense MFMA peaks
 HBM_PEAK_GBS = 8000.0
+METRIC = "labelled pixels/sec SK-Net fwd (and fwd+bwd) 1 GPU; conv % MFMA peak"
+
+
+def build_net(B, S, dtype, n, H, W, training):
+    layers = S.sknet_layers()
+    ws, bs = S.he_normal_weights(layers, 1, 1001)
+    net = B.SKNet(layers, 1, 2, dtype=dtype)
+    for i, (w, b) in enumerate(zip(ws, bs)):
+        net.set_weights(i, w, b)
+    net.plan(n, H, W, pad=True, training=training)
+    return net, layers, ws, bs
+
+
+def images(S, n, H, W, first_seed):
+    return S.em_like_batch(n, H, W, first_seed)
+
+
+def measure_forward(torch, B, S, dtype, n, H, W, steps, warmup, first_seed, kernel_iters=20):
+    net, layers, ws, bs = build_net(B, S, dtype, n, H, W, False)
+    img = images(S, n, H, W, first_seed)
+    timg = torch.from_numpy(img).cuda()
+    prob = torch.empty(net.out_shape(), dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+    for _ in range(warmup):
+        net.forward(timg, prob, stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        net.forward(timg, prob, stream)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / steps * 1e3
+
+    # per-kernel durations: HIP events recorded on the same stream, inside the library
+    shapes = net.infer_shapes(H, W)
+    esize = 4 if dtype == "f32" else 2
+    step_ms, conv_flops, conv_ms, total_flops = {}, 0.0, 0.0, 0.0
+    pool_bytes, pool_ms = 0.0, 0.0
+    f_in = 1
+    for step in range(net.num_steps()):
+        ms = net.time_step(step, kernel_iters, stream)
+        step_ms[net.step_name(step)] = round(ms, 5)
+        if 1 <= step <= len(layers):
+            l = layers[step - 1]
+            c, ho, wo = shapes[step]
+            if l["type"] == "conv":
+                fl = 2.0 * f_in * l["k"] ** 2 * l["f_out"] * ho * wo * n
+                total_flops += fl
+                if f_in == 48 and l["f_out"] == 48:      # the dominant kernel: 48 -> 48, k4, dilated
+                    conv_flops += fl
+                    conv_ms += ms
+                f_in = l["f_out"]
+            else:                                         # pool: one element read + one written
+                pool_bytes += 2.0 * esize * n * c * ho * wo
+                pool_ms += ms
+    res = {
+        "ms_per_step": ms_per_step, "pixels_per_s": n * H * W * steps / dt, "step_ms": step_ms,
+        "conv_tflops": conv_flops / (conv_ms * 1e-3) / 1e12, "forward_tflops": total_flops / (ms_per_step * 1e-3) / 1e12,
+        "pool_gbs": pool_bytes / (pool_ms * 1e-3) / 1e9, "layers": layers, "ws": ws, "bs": bs, "img": img,
+    }
+    net.close()
+    return res
+
+
+def measure_train(torch, B, S, dtype, n, H, W, steps, warmup, first_seed):
+    net, layers, ws, bs = build_net(B, S, dtype, n, H, W, True)
+    timg = torch.from_numpy(images(S, n, H, W, first_seed)).cuda()
+    labels = torch.from_numpy(S.binary_labels(n, H, W, 2004)).cuda()
+    prob = torch.empty(net.out_shape(), dtype=torch.float32, device="cuda")
+    loss = torch.empty(1, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def one():
+        net.forward(timg, prob, stream)
+        net.backward(labels, loss, stream)
+        net.sgd_step(0.01, stream=stream)
+
+    for _ in range(warmup):
+        one()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        one()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    net.close()
+    return {"pixels_per_s": n * H * W * steps / dt, "ms_per_step": dt / steps * 1e3, "steps": steps}
 
 
 def main():
@@ -23,116 +114,76 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--size", type=int, default=512, help="image side (512 = BASELINE config 2)")
+    ap.add_argument("--workload", choices=["c2", "c3", "c4"], default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-train", action="store_true")
+    ap.add_argument("--no-extras", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
               file=sys.stderr)
         sys.exit(2)
 
-    import numpy as np
     import torch
 
     import sk_synth as S
     from paper_1509_03371_amd import binding as B
 
     torch.cuda.set_device(0)
-    H = W = args.size
-    layers = S.sknet_layers()
-    ws, bs = S.he_normal_weights(layers, 1, 1001)
-    img = S.em_like_batch(1, H, W, 2)
-    net = B.SKNet(layers, 1, 2, dtype="f32")
-    for i, (w, b) in enumerate(zip(ws, bs)):
-        net.set_weights(i, w, b)
-    net.plan(1, H, W, pad=True, training=False)
-    timg = torch.from_numpy(img).cuda()
-    prob = torch.empty(net.out_shape(), dtype=torch.float32, device="cuda")
-    stream = torch.cuda.current_stream()
+    net_desc = "4x[conv k4 48 + ReLU, pool k2] d=1/2/4/8, 1x1 48->200 + ReLU, 1x1 200->2, softmax"
+    out = {"metric": METRIC, "unit": "pixels/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "data": "synthetic"}
 
-    for _ in range(args.warmup):
-        net.forward(timg, prob, stream)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        net.forward(timg, prob, stream)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt / args.steps * 1e3
-    px_per_s = H * W * args.steps / dt
+    if args.workload in ("c2", "c3"):
+        dtype, n, H, seed = ("f32", 1, 512, 2) if args.workload == "c2" else ("bf16", 8, 1024, 3)
+        r = measure_forward(torch, B, S, dtype, n, H, H, args.steps, args.warmup, seed)
+        peak = PEAK_TFLOPS[dtype]
+        out.update({
+            "value": round(r["pixels_per_s"], 1), "ms_per_step": round(r["ms_per_step"], 4), "dtype": dtype,
+            "config": {"workload": "SK-Net forward, %dx1x%dx%d %s image(s), %s (BASELINE configs[%d])"
+                                   % (n, H, H, "fp32" if dtype == "f32" else dtype, net_desc, 1 if args.workload == "c2" else 2),
+                       "global_batch": n, "parallelism": "single GPU"},
+            "roofline": {"bound": "mfma", "achieved": round(r["conv_tflops"], 2), "peak": peak, "unit": "TFLOP/s",
+                         "frac": round(r["conv_tflops"] / peak, 4), "traffic": None,
+                         "kernel": "48->48 k4 SK convolutions at d=2,4,8 (%s)"
+                                   % ("conv_f32_pf_kernel<3,1,4,4,2>" if dtype == "f32" else "conv_h_kernel<bf16,4,3,MAP4,8>")},
+            "forward_tflops": round(r["forward_tflops"], 2),
+            "pool_gbs": round(r["pool_gbs"], 1), "pool_frac_of_hbm_peak": round(r["pool_gbs"] / HBM_PEAK_GBS, 4),
+            "step_ms": r["step_ms"],
+        })
+    else:
+        r = measure_train(torch, B, S, "bf16", 1, 512, 512, args.steps, args.warmup, 2)
+        out.update({
+            "value": round(r["pixels_per_s"], 1), "ms_per_step": round(r["ms_per_step"], 4), "dtype": "bf16",
+            "config": {"workload": "SK-Net training step, 1x1x512x512 bf16: forward, softmax loss, backward, SGD; "
+                                   + net_desc + " (BASELINE configs[3])", "global_batch": 1, "parallelism": "single GPU"},
+            "roofline": None,
+        })
 
-    # per-kernel durations, HIP events on the same stream (inside the library)
-    shapes = net.infer_shapes(H, W)
-    step_ms, conv_flops, conv_ms = {}, 0.0, 0.0
-    total_flops = 0.0
-    f_in = 1
-    for step in range(net.num_steps()):
-        ms = net.time_step(step, 20, stream)
-        name = net.step_name(step)
-        step_ms[name] = round(ms, 5)
-        if 1 <= step <= len(layers) and layers[step - 1]["type"] == "conv":
-            l = layers[step - 1]
-            c, ho, wo = shapes[step]
-            fl = 2.0 * f_in * l["k"] ** 2 * l["f_out"] * ho * wo
-            total_flops += fl
-            if f_in == 48 and l["f_out"] == 48:      # the dominant kernel: 48 -> 48, k4, dilated
-                conv_flops += fl
-                conv_ms += ms
-            f_in = l["f_out"]
-    achieved = conv_flops / (conv_ms * 1e-3) / 1e12
+    if args.workload == "c2" and not args.no_extras:
+        extras = {}
+        r3 = measure_forward(torch, B, S, "bf16", 8, 1024, 1024, 10, 3, 3, kernel_iters=5)
+        extras["c3_bf16_forward_8x1024"] = {
+            "pixels_per_s": round(r3["pixels_per_s"], 1), "ms_per_step": round(r3["ms_per_step"], 4),
+            "conv_tflops": round(r3["conv_tflops"], 1), "conv_frac_of_bf16_mfma_peak": round(r3["conv_tflops"] / 2500.0, 4),
+            "pool_gbs": round(r3["pool_gbs"], 1), "pool_frac_of_hbm_peak": round(r3["pool_gbs"] / HBM_PEAK_GBS, 4),
+            "step_ms": r3["step_ms"]}
+        for name, dt in (("c4_bf16_train_512", "bf16"), ("c4_as_f32_train_512", "f32")):
+            rt = measure_train(torch, B, S, dt, 1, 512, 512, 20, 3, 2)
+            extras[name] = {"pixels_per_s": round(rt["pixels_per_s"], 1), "ms_per_step": round(rt["ms_per_step"], 4)}
+        out["extras"] = extras
 
-    out = {
-        "metric": "labelled pixels/sec SK-Net fwd (and fwd+bwd) 1 GPU; conv % MFMA peak",
-        "value": round(px_per_s, 1), "unit": "pixels/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "SK-Net forward, 1x1x%dx%d fp32 image, 4x[conv k4 48 + ReLU, pool k2] d=1/2/4/8, "
-                               "1x1 48->200 + ReLU, 1x1 200->2, softmax (BASELINE configs[1])" % (H, W),
-                   "global_batch": 1, "parallelism": "single GPU"},
-        "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_FP32_PEAK_TFLOPS,
-                     "unit": "TFLOP/s", "frac": round(achieved / MFMA_FP32_PEAK_TFLOPS, 4), "traffic": None,
-                     "kernel": "conv_f32_kernel<3,2> (48->48 k4 convs at d=2,4,8)"},
-        "forward_tflops": round(total_flops / (ms_per_step * 1e-3) / 1e12, 2),
-        "step_ms": step_ms,
-    }
-
-    if not args.no_train:
-        tnet = B.SKNet(layers, 1, 2, dtype="f32")
-        for i, (w, b) in enumerate(zip(ws, bs)):
-            tnet.set_weights(i, w, b)
-        tnet.plan(1, H, W, pad=True, training=True)
-        labels = torch.from_numpy(S.binary_labels(1, H, W, 2004)).cuda()
-        loss = torch.empty(1, dtype=torch.float32, device="cuda")
-        tsteps = max(1, args.steps // 2)
-        for _ in range(max(1, args.warmup // 2)):
-            tnet.forward(timg, prob, stream); tnet.backward(labels, loss, stream); tnet.sgd_step(0.0, stream=stream)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(tsteps):
-            tnet.forward(timg, prob, stream)
-            tnet.backward(labels, loss, stream)
-            tnet.sgd_step(0.0, stream=stream)      # lr 0 keeps the weights (and the timings) stationary
-        torch.cuda.synchronize()
-        tdt = time.perf_counter() - t0
-        out["train"] = {"workload": "forward + softmax loss + backward + SGD, same net and image, fp32",
-                        "pixels_per_s": round(H * W * tsteps / tdt, 1), "ms_per_step": round(tdt / tsteps * 1e3, 4),
-                        "steps": tsteps}
-        tnet.close()
-
-    if not args.no_cpu_baseline:
+    if args.workload == "c2" and not args.no_cpu_baseline:
         from oracle import nets as ON
         reps, t_cpu = 0, 0.0
         while t_cpu < 10.0 and reps < 4:
             t0 = time.perf_counter()
-            ON.sknet_forward(img, layers, ws, bs)
+            ON.sknet_forward(r["img"], r["layers"], r["ws"], r["bs"])
             t_cpu += time.perf_counter() - t0
             reps += 1
-        out["cpu_baseline"] = {"value": round(H * W * reps / t_cpu, 1), "unit": "pixels/s",
+        out["cpu_baseline"] = {"value": round(512 * 512 * reps / t_cpu, 1), "unit": "pixels/s",
                                "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)),
                                "kind": "oracle",
-                               "sample": "%d full forward pass(es) of the same %dx%d workload, fp64 C oracle with OpenMP" % (reps, H, W)}
-    net.close()
+                               "sample": "%d full forward pass(es) of the same 512x512 workload, fp64 C oracle with OpenMP" % reps}
     print(json.dumps(out))
 
 

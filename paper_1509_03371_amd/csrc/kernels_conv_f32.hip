@@ -119,6 +119,15 @@ __global__ __launch_bounds__(256) void conv_f32_kernel(ConvF32Args a, int tiles_
     }
 
     // epilogue: bias, ReLU, optional mask, predicated store
+    // bias first, in one batch: a load issued between stores would make its wait cover the stores too
+    float bia[NT][4];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+            const int o = nb * WN + nt * 16 + 4 * g + r4;
+            bia[nt][r4] = (a.bias && o < a.n_pad) ? a.bias[o] : 0.f;
+        }
 #pragma unroll
     for (int rw = 0; rw < RW; ++rw) {
         const int oy = py + d * (ty * R + wave * RW + rw);
@@ -133,8 +142,7 @@ __global__ __launch_bounds__(256) void conv_f32_kernel(ConvF32Args a, int tiles_
                 for (int r4 = 0; r4 < 4; ++r4) {
                     const int o = nb * WN + nt * 16 + 4 * g + r4;
                     if (o >= a.c_out) continue;
-                    float v = acc[rw][xt][nt][r4];
-                    if (a.bias) v += a.bias[o];
+                    float v = acc[rw][xt][nt][r4] + bia[nt][r4];
                     if (a.relu) v = v > 0.f ? v : 0.f;
                     const long idx = (((long)b * a.out_maps + o + a.o_off) * a.OH + (long)oy * a.oy_mul + a.oy_off) * a.OW +
                                      (long)ox * a.ox_mul + a.ox_off;
@@ -325,6 +333,15 @@ __global__ __launch_bounds__(256) void conv_f32_pf_kernel(ConvF32Args a, int til
         }
     }
 
+    // bias first, in one batch: a load issued between stores would make its wait cover the stores too
+    float bia[NT][4];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+            const int o = nb * WN + nt * 16 + 4 * g + r4;
+            bia[nt][r4] = (a.bias && o < a.n_pad) ? a.bias[o] : 0.f;
+        }
 #pragma unroll
     for (int rw = 0; rw < RW; ++rw) {
         const int oy = py + d * (ty * R + wave * RW + rw);
@@ -339,8 +356,7 @@ __global__ __launch_bounds__(256) void conv_f32_pf_kernel(ConvF32Args a, int til
                 for (int r4 = 0; r4 < 4; ++r4) {
                     const int o = nb * WN + nt * 16 + 4 * g + r4;
                     if (o >= a.c_out) continue;
-                    float v = acc[rw][xt][nt][r4];
-                    if (a.bias) v += a.bias[o];
+                    float v = acc[rw][xt][nt][r4] + bia[nt][r4];
                     if (a.relu) v = v > 0.f ? v : 0.f;
                     const long idx = (((long)b * a.out_maps + o + a.o_off) * a.OH + (long)oy * a.oy_mul + a.oy_off) * a.OW +
                                      (long)ox * a.ox_mul + a.ox_off;

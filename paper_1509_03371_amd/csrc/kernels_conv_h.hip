@@ -208,11 +208,42 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
         }
     };
 
+    // bias of every output map, staged in LDS once (zeros when the layer has none)
+    float *bias_lds = reinterpret_cast<float *>(lds + 2 * stage_units);
+    for (int q = tid; q < a.mgroups * MT * 16; q += CH_THREADS) bias_lds[q] = (a.bias && q < a.m_tiles * 16) ? a.bias[q] : 0.f;
+
+    // Epilogue of one tile.  Everything it reads comes first (bias from LDS, the optional ReLU mask
+    // in one batch of global loads) and the stores follow without any load in between: on this ISA a
+    // wait for a load also waits for every store issued before it, which would serialise the stores.
     auto epilogue = [&](const TilePos &p) {
         const int ox = p.x0 + wave * 16 + l16;
+        const long px_out = (long)ox * a.ox_mul + a.ox_off;
+        float bia[MT][4];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) bia[mt][r4] = bias_lds[(p.mg * MT + mt) * 16 + 4 * g + r4];
+        uint2v mk[R][MT];
+        if (a.mask) {
+#pragma unroll
+            for (int y = 0; y < R; ++y) {
+                int oy = p.py + d * (p.ty * R + y);
+                oy = oy < a.Ho ? oy : a.Ho - 1;
+                const long py_out = (long)oy * a.oy_mul + a.oy_off;
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    int o8 = ((p.mg * MT + mt) * 16 + 4 * g) >> 3;
+                    o8 = o8 < a.c8_out ? o8 : a.c8_out - 1;
+                    const long unit = (((long)p.b * a.c8_out_total + o8 + a.o8_off) * a.OH + py_out) * a.OW +
+                                      (ox < a.Wo ? px_out : (long)a.ox_off);
+                    mk[y][mt] = reinterpret_cast<const uint2v *>(a.mask)[unit * 2 + (g & 1)];
+                }
+            }
+        }
 #pragma unroll
         for (int y = 0; y < R; ++y) {
             const int oy = p.py + d * (p.ty * R + y);
+            const long py_out = (long)oy * a.oy_mul + a.oy_off;
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
                 const int mtile = p.mg * MT + mt;
@@ -220,10 +251,9 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
                 acc[y][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
                 if (oy >= a.Ho || ox >= a.Wo || mtile >= a.m_tiles) continue;
                 const int o = mtile * 16 + 4 * g;           // first of this lane's four output maps
-                const long py_out = (long)oy * a.oy_mul + a.oy_off, px_out = (long)ox * a.ox_mul + a.ox_off;
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
-                    if (a.bias) v[r4] += a.bias[o + r4];
+                    v[r4] += bia[mt][r4];
                     if (a.relu) v[r4] = v[r4] > 0.f ? v[r4] : 0.f;
                 }
                 if (a.out_f32) {
@@ -241,7 +271,7 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
                     for (int r4 = 0; r4 < 4; ++r4) h[r4] = H<DT>::cvt(v[r4]);
                     uint2v packed = uint2v{(unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16)};
                     if (a.mask) {
-                        const uint2v m = reinterpret_cast<const uint2v *>(a.mask)[unit * 2 + (g & 1)];
+                        const uint2v m = mk[y][mt];
                         unsigned lo = packed[0], hi = packed[1];
                         if (!pos16(m[0] & 0xffffu)) lo &= 0xffff0000u;
                         if (!pos16(m[0] >> 16)) lo &= 0x0000ffffu;
@@ -292,7 +322,8 @@ static hipError_t launch_conv_h_t(ConvHArgs a, hipStream_t stream)
     const int PW = CH_TX + (KS - 1) * a.d;
     if (PW > 64 * CH_VU) return hipErrorInvalidValue;
     const size_t stage = (size_t)OC * RR * PW + (size_t)CS * KS * MT * 64;
-    const size_t smem = 2 * stage * 16;
+    const int m_tiles_all = ((a.c_out + 15) / 16 + MT - 1) / MT * MT;
+    const size_t smem = 2 * stage * 16 + (size_t)m_tiles_all * 16 * sizeof(float);
     if (smem > 160 * 1024) return hipErrorInvalidValue;
     static bool attr_set = false;
     if (!attr_set) {
