@@ -66,11 +66,16 @@ template <> struct H<2> {
 // positive (> 0) test on a 16-bit float bit pattern (both formats: sign bit clear, magnitude non-zero)
 __device__ __forceinline__ bool pos16(unsigned v) { return (v & 0x8000u) == 0 && (v & 0x7fffu) != 0; }
 
+// Workgroup barrier for LDS traffic only: wait for this wave's own LDS operations, then s_barrier.
+// (__syncthreads() also drains every outstanding global load and store of the wave, which would
+// serialise the chunk pipelines below with HBM latency.)
+__device__ __forceinline__ void block_sync_lds() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 struct TilePos {
     int b, mg, py, ty, x0;
 };
 
-template <int DT, int KS, int MT, bool MAP4, int R>
+template <int DT, int KS, int MT, bool MAP4, int R, bool HAS_MASK>
 __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
 {
     extern __shared__ uint4v lds[];
@@ -217,60 +222,65 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
     // wait for a load also waits for every store issued before it, which would serialise the stores.
     auto epilogue = [&](const TilePos &p) {
         const int ox = p.x0 + wave * 16 + l16;
-        const long px_out = (long)ox * a.ox_mul + a.ox_off;
+        const bool colok = ox < a.Wo;
+        const int oxc = colok ? ox : 0;
         float bia[MT][4];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int r4 = 0; r4 < 4; ++r4) bia[mt][r4] = bias_lds[(p.mg * MT + mt) * 16 + 4 * g + r4];
-        uint2v mk[R][MT];
-        if (a.mask) {
+        // byte offsets inside one image of the destination stay below 2^31 (checked by the launcher)
+        const int row_bytes = a.OW * (a.out_f32 ? 4 : 16);
+        const int plane_bytes = a.OH * row_bytes;
+        char *ybase;      // this lane's column in map (or octet) 0, row 0 of image b
+        if (a.out_f32)
+            ybase = reinterpret_cast<char *>(a.y) + (long)p.b * a.c_out * plane_bytes + (long)(oxc * a.ox_mul + a.ox_off) * 4;
+        else
+            ybase = reinterpret_cast<char *>(a.y) + ((long)p.b * a.c8_out_total + a.o8_off) * plane_bytes +
+                    (long)(oxc * a.ox_mul + a.ox_off) * 16 + (g & 1) * 8;
+        uint2v mk[HAS_MASK ? R : 1][HAS_MASK ? MT : 1];
+        if constexpr (HAS_MASK) {
+            const char *mbase = reinterpret_cast<const char *>(a.mask) + (ybase - reinterpret_cast<char *>(a.y));
 #pragma unroll
             for (int y = 0; y < R; ++y) {
                 int oy = p.py + d * (p.ty * R + y);
                 oy = oy < a.Ho ? oy : a.Ho - 1;
-                const long py_out = (long)oy * a.oy_mul + a.oy_off;
+                const int yoff = (oy * a.oy_mul + a.oy_off) * row_bytes;
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) {
-                    int o8 = ((p.mg * MT + mt) * 16 + 4 * g) >> 3;
+                    int o8 = (p.mg * MT + mt) * 2 + (g >> 1);
                     o8 = o8 < a.c8_out ? o8 : a.c8_out - 1;
-                    const long unit = (((long)p.b * a.c8_out_total + o8 + a.o8_off) * a.OH + py_out) * a.OW +
-                                      (ox < a.Wo ? px_out : (long)a.ox_off);
-                    mk[y][mt] = reinterpret_cast<const uint2v *>(a.mask)[unit * 2 + (g & 1)];
+                    mk[y][mt] = *reinterpret_cast<const uint2v *>(mbase + o8 * plane_bytes + yoff);
                 }
             }
         }
 #pragma unroll
         for (int y = 0; y < R; ++y) {
             const int oy = p.py + d * (p.ty * R + y);
-            const long py_out = (long)oy * a.oy_mul + a.oy_off;
+            const int yoff = (oy * a.oy_mul + a.oy_off) * row_bytes;
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
                 const int mtile = p.mg * MT + mt;
                 floatx4 v = acc[y][mt];
                 acc[y][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
-                if (oy >= a.Ho || ox >= a.Wo || mtile >= a.m_tiles) continue;
-                const int o = mtile * 16 + 4 * g;           // first of this lane's four output maps
+                if (oy >= a.Ho || mtile >= a.m_tiles) continue;      // uniform
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
                     v[r4] += bia[mt][r4];
-                    if (a.relu) v[r4] = v[r4] > 0.f ? v[r4] : 0.f;
+                    if (a.relu) v[r4] = fmaxf(v[r4], 0.f);
                 }
                 if (a.out_f32) {
-                    float *yf = reinterpret_cast<float *>(a.y);
+                    const int o = mtile * 16 + 4 * g;
 #pragma unroll
                     for (int r4 = 0; r4 < 4; ++r4)
-                        if (o + r4 < a.c_out)
-                            yf[(((long)p.b * a.c_out + o + r4) * a.OH + py_out) * a.OW + px_out] = v[r4];
+                        if (colok && o + r4 < a.c_out) *reinterpret_cast<float *>(ybase + (o + r4) * plane_bytes + yoff) = v[r4];
                 } else {
-                    const int o8 = o >> 3;
-                    if (o8 >= a.c8_out) continue;
-                    const long unit = (((long)p.b * a.c8_out_total + o8 + a.o8_off) * a.OH + py_out) * a.OW + px_out;
+                    const int o8 = mtile * 2 + (g >> 1);
                     unsigned short h[4];
 #pragma unroll
                     for (int r4 = 0; r4 < 4; ++r4) h[r4] = H<DT>::cvt(v[r4]);
                     uint2v packed = uint2v{(unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16)};
-                    if (a.mask) {
+                    if constexpr (HAS_MASK) {
                         const uint2v m = mk[y][mt];
                         unsigned lo = packed[0], hi = packed[1];
                         if (!pos16(m[0] & 0xffffu)) lo &= 0xffff0000u;
@@ -279,7 +289,7 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
                         if (!pos16(m[1] >> 16)) hi &= 0x0000ffffu;
                         packed = uint2v{lo, hi};
                     }
-                    reinterpret_cast<uint2v *>(a.y)[unit * 2 + (g & 1)] = packed;
+                    if (colok && o8 < a.c8_out) *reinterpret_cast<uint2v *>(ybase + o8 * plane_bytes + yoff) = packed;
                 }
             }
         }
@@ -287,36 +297,304 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
 
     int t = t_begin + slot;
     if (t >= t_end) return;
+    // The chunk pipeline is written without data-dependent branches around the loads and the LDS
+    // writes (the last chunk is peeled off), so that the compiler's wait-count bookkeeping stays
+    // exact and the prefetched loads really remain in flight across the MFMA block.
+    const int my_tiles = (t_end - t + nslots - 1) / nslots;
+    const int total_chunks = my_tiles * a.nchunks;
     TilePos cur = decode(t), nxt = cur;
     int ch = 0, buf = 0;
     prefetch(cur, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);
     commit(cur, 0, 0);
-    __syncthreads();
-    while (true) {
-        int nch = ch + 1, ntile = t;
+    block_sync_lds();
+    for (int q = 0; q + 1 < total_chunks; ++q) {
+        int nch = ch + 1;
         if (nch == a.nchunks) {
             nch = 0;
-            ntile = t + nslots;
+            t += nslots;
+            nxt = decode(t);
         }
-        const bool has_next = ntile < t_end;
-        if (has_next) {
-            if (nch == 0) nxt = decode(ntile);
-            prefetch(nxt, nch);
-        }
+        prefetch(nxt, nch);
         compute(buf);
-        if (ch == a.nchunks - 1) epilogue(cur);
-        if (has_next) commit(nxt, nch, buf ^ 1);
-        __syncthreads();
-        if (!has_next) break;
-        t = ntile;
+        // Explicit vmcnt(0): every prefetched register is consumed below, some only by part of the
+        // lanes; without it the compiler would carry "load pending" states around the loop and wait
+        // (also for the stores of the epilogue) before it reuses those registers.  The stores of the
+        // previous tile are older than these loads and long finished, and the epilogue's own stores
+        // come after the commit, so nothing here waits for a store in flight.
+        __builtin_amdgcn_sched_barrier(0);   // keep the wait behind the MFMA block
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __builtin_amdgcn_sched_barrier(0);
+        commit(nxt, nch, buf ^ 1);
+        if (nch == 0) epilogue(cur);
+        block_sync_lds();
         ch = nch;
         cur = nxt;
         buf ^= 1;
     }
+    compute(buf);
+    epilogue(cur);
 }
 
-template <int DT, int KS, int MT, bool MAP4, int R>
-static hipError_t launch_conv_h_t(ConvHArgs a, hipStream_t stream)
+// ------------------------------------------------------------------------------------------------
+// Ring variant: the same tiling and MFMA schedule, but the input tile and the weight slab of a
+// chunk go from HBM/L2 straight into LDS (global_load_lds_dwordx4: lane l's 16 bytes land at
+// base + 16*l, inactive lanes write nothing), into a ring of S stages.  No staging registers and no
+// LDS-write instructions; the loads of the next S-1 chunks are in flight while one chunk is
+// multiplied, which is what covers the HBM latency (one chunk of look-ahead does not).
+// What lies outside the image is read from a small zero buffer instead.
+template <int DT, int KS, int MT, bool MAP4, int R, bool HAS_MASK, int S>
+__global__ __launch_bounds__(CH_THREADS) void conv_h_ring_kernel(ConvHArgs a)
+{
+    extern __shared__ uint4v lds[];
+    constexpr int RR = R + KS - 1;
+    constexpr int OC = MAP4 ? 1 : 4;
+    constexpr int CS = MAP4 ? 1 : KS;
+    constexpr int ROWS = OC * RR;
+    constexpr int RU = (ROWS + CH_WAVES - 1) / CH_WAVES;
+    constexpr int WUNITS = CS * KS * MT * 64;
+    constexpr int WBLK = WUNITS / 64;                          // 1 KB fragments in the weight slab
+    constexpr int WL = (WBLK + CH_WAVES - 1) / CH_WAVES;
+    constexpr int VUE = KS == 1 ? 2 : 3;                       // 64-unit column groups per staged row
+    constexpr int L = RU * VUE + WL;                           // loads issued per wave and chunk
+
+    const int d = a.d;
+    const int PW = CH_TX + (KS - 1) * d;
+    const int tile_units = ROWS * PW;
+    const int stage_units = tile_units + WUNITS;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l16 = lane & 15, g = lane >> 4;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, nslots = gridDim.x >> 3;
+    const int t_begin = (int)((long)a.total_tiles * xcd / 8), t_end = (int)((long)a.total_tiles * (xcd + 1) / 8);
+
+    auto decode = [&](int t) {
+        TilePos p;
+        const int xt = t % a.xtiles;
+        int rest = t / a.xtiles;
+        const int yt = rest % a.ytiles_total;
+        rest /= a.ytiles_total;
+        p.mg = rest % a.mgroups;
+        p.b = rest / a.mgroups;
+        if (yt < a.rem * a.tiles_hi) {
+            p.py = yt / a.tiles_hi;
+            p.ty = yt - p.py * a.tiles_hi;
+        } else {
+            const int y2 = yt - a.rem * a.tiles_hi;
+            p.py = a.rem + y2 / a.tiles_lo;
+            p.ty = y2 % a.tiles_lo;
+        }
+        p.x0 = xt * CH_TX;
+        return p;
+    };
+
+
+    const long plane = (long)a.H * a.W;
+    const uint4v *zeros = reinterpret_cast<const uint4v *>(a.zeros);
+
+    // issue the loads of chunk `ch` of tile `p` into ring stage `st`
+    auto issue = [&](const TilePos &p, int ch, int st) {
+        uint4v *dst = lds + st * stage_units;
+        const int gy0 = p.py + d * (p.ty * R) - a.in_off;
+        const int gx0 = p.x0 - a.in_off + lane;
+#pragma unroll
+        for (int u = 0; u < RU; ++u) {
+            int rid = wave + CH_WAVES * u;
+            rid = rid < ROWS ? rid : rid - CH_WAVES;            // surplus slots repeat this wave's previous row
+            const int oc = rid / RR, r = rid - oc * RR;
+            const int o = ch * OC + oc;
+            const int gy = gy0 + r * d;
+            const bool rowok = o < a.c8_in && gy >= 0 && gy < a.H;
+            const uint4v *row = reinterpret_cast<const uint4v *>(a.x) + ((long)p.b * a.c8_in + (rowok ? o : 0)) * plane +
+                                (long)(rowok ? gy : 0) * a.W;
+#pragma unroll
+            for (int v = 0; v < VUE; ++v) {
+                const int xc = lane + 64 * v, gx = gx0 + 64 * v;
+                const bool ok = rowok && gx >= 0 && gx < a.W;
+                const uint4v *src = ok ? row + gx : zeros;
+                if (xc < PW)
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                                     (__attribute__((address_space(3))) void *)(dst + rid * PW + 64 * v), 16, 0, 0);
+            }
+        }
+        const uint4v *wsrc = reinterpret_cast<const uint4v *>(a.wp) + ((long)p.mg * a.nchunks + ch) * WUNITS;
+#pragma unroll
+        for (int u = 0; u < WL; ++u) {
+            int blk = wave + CH_WAVES * u;
+            blk = blk < WBLK ? blk : blk % WBLK;                // surplus slots repeat a block (same data, same place)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(wsrc + blk * 64 + lane),
+                                             (__attribute__((address_space(3))) void *)(dst + tile_units + blk * 64), 16, 0, 0);
+        }
+    };
+
+    floatx4 acc[R][MT];
+#pragma unroll
+    for (int y = 0; y < R; ++y)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[y][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    auto compute = [&](int buf) {
+        const uint4v *tile = lds + buf * stage_units;
+        const uint4v *wl = tile + tile_units;
+#pragma unroll
+        for (int cs = 0; cs < CS; ++cs) {
+            uint4v afr[KS][MT];
+#pragma unroll
+            for (int i = 0; i < KS; ++i)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) afr[i][mt] = wl[((cs * KS + i) * MT + mt) * 64 + lane];
+            const int off = (MAP4 ? g * d : g * RR * PW + cs * d) + wave * 16 + l16;
+            uint4v bcur = tile[off];
+#pragma unroll
+            for (int r = 0; r < RR; ++r) {
+                uint4v bnext = bcur;
+                if (r + 1 < RR) bnext = tile[off + (r + 1) * PW];
+#pragma unroll
+                for (int i = 0; i < KS; ++i) {
+                    const int y = r - i;
+                    if (y >= 0 && y < R) {
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt) acc[y][mt] = H<DT>::mfma(afr[i][mt], bcur, acc[y][mt]);
+                    }
+                }
+                bcur = bnext;
+            }
+        }
+    };
+
+
+    // bias of every output map, staged in LDS once (zeros when the layer has none)
+    float *bias_lds = reinterpret_cast<float *>(lds + S * stage_units);
+    for (int q = tid; q < a.mgroups * MT * 16; q += CH_THREADS) bias_lds[q] = (a.bias && q < a.m_tiles * 16) ? a.bias[q] : 0.f;
+
+    // Epilogue of one tile.  Everything it reads comes first (bias from LDS, the optional ReLU mask
+    // in one batch of global loads) and the stores follow without any load in between: on this ISA a
+    // wait for a load also waits for every store issued before it, which would serialise the stores.
+    auto epilogue = [&](const TilePos &p) {
+        const int ox = p.x0 + wave * 16 + l16;
+        const bool colok = ox < a.Wo;
+        const int oxc = colok ? ox : 0;
+        float bia[MT][4];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) bia[mt][r4] = bias_lds[(p.mg * MT + mt) * 16 + 4 * g + r4];
+        // byte offsets inside one image of the destination stay below 2^31 (checked by the launcher)
+        const int row_bytes = a.OW * (a.out_f32 ? 4 : 16);
+        const int plane_bytes = a.OH * row_bytes;
+        char *ybase;      // this lane's column in map (or octet) 0, row 0 of image b
+        if (a.out_f32)
+            ybase = reinterpret_cast<char *>(a.y) + (long)p.b * a.c_out * plane_bytes + (long)(oxc * a.ox_mul + a.ox_off) * 4;
+        else
+            ybase = reinterpret_cast<char *>(a.y) + ((long)p.b * a.c8_out_total + a.o8_off) * plane_bytes +
+                    (long)(oxc * a.ox_mul + a.ox_off) * 16 + (g & 1) * 8;
+        uint2v mk[HAS_MASK ? R : 1][HAS_MASK ? MT : 1];
+        if constexpr (HAS_MASK) {
+            const char *mbase = reinterpret_cast<const char *>(a.mask) + (ybase - reinterpret_cast<char *>(a.y));
+#pragma unroll
+            for (int y = 0; y < R; ++y) {
+                int oy = p.py + d * (p.ty * R + y);
+                oy = oy < a.Ho ? oy : a.Ho - 1;
+                const int yoff = (oy * a.oy_mul + a.oy_off) * row_bytes;
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    int o8 = (p.mg * MT + mt) * 2 + (g >> 1);
+                    o8 = o8 < a.c8_out ? o8 : a.c8_out - 1;
+                    mk[y][mt] = *reinterpret_cast<const uint2v *>(mbase + o8 * plane_bytes + yoff);
+                }
+            }
+        }
+#pragma unroll
+        for (int y = 0; y < R; ++y) {
+            const int oy = p.py + d * (p.ty * R + y);
+            const int yoff = (oy * a.oy_mul + a.oy_off) * row_bytes;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const int mtile = p.mg * MT + mt;
+                floatx4 v = acc[y][mt];
+                acc[y][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+                if (oy >= a.Ho || mtile >= a.m_tiles) continue;      // uniform
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    v[r4] += bia[mt][r4];
+                    if (a.relu) v[r4] = fmaxf(v[r4], 0.f);
+                }
+                if (a.out_f32) {
+                    const int o = mtile * 16 + 4 * g;
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4)
+                        if (colok && o + r4 < a.c_out) *reinterpret_cast<float *>(ybase + (o + r4) * plane_bytes + yoff) = v[r4];
+                } else {
+                    const int o8 = mtile * 2 + (g >> 1);
+                    unsigned short h[4];
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4) h[r4] = H<DT>::cvt(v[r4]);
+                    uint2v packed = uint2v{(unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16)};
+                    if constexpr (HAS_MASK) {
+                        const uint2v m = mk[y][mt];
+                        unsigned lo = packed[0], hi = packed[1];
+                        if (!pos16(m[0] & 0xffffu)) lo &= 0xffff0000u;
+                        if (!pos16(m[0] >> 16)) lo &= 0x0000ffffu;
+                        if (!pos16(m[1] & 0xffffu)) hi &= 0xffff0000u;
+                        if (!pos16(m[1] >> 16)) hi &= 0x0000ffffu;
+                        packed = uint2v{lo, hi};
+                    }
+                    if (colok && o8 < a.c8_out) *reinterpret_cast<uint2v *>(ybase + o8 * plane_bytes + yoff) = packed;
+                }
+            }
+        }
+    };
+
+
+    int t = t_begin + slot;
+    if (t >= t_end) return;
+    const int my_tiles = (t_end - t + nslots - 1) / nslots;
+    const int total_chunks = my_tiles * a.nchunks;
+
+    // issue cursor (runs S-1 chunks ahead of the compute cursor)
+    TilePos ipos = decode(t);
+    int it = t, ich = 0, issued = 0;
+    auto issue_next = [&]() {
+        issue(ipos, ich, issued % S);
+        ++issued;
+        if (++ich == a.nchunks) {
+            ich = 0;
+            it += nslots;
+            if (it < t_end) ipos = decode(it);
+        }
+    };
+#pragma unroll
+    for (int j = 0; j < S - 1; ++j)
+        if (j < total_chunks) issue_next();
+
+    TilePos cur = decode(t);
+    int ch = 0;
+    for (int q = 0; q < total_chunks; ++q) {
+        // chunk q must have landed; the loads of the younger chunks may stay in flight.  (Stores of
+        // an epilogue issued since then are younger still and make this wait longer than needed, never
+        // shorter: the counter retires in issue order.)
+        const int younger = issued - q - 1;
+        __builtin_amdgcn_sched_barrier(0);
+        if (younger >= 2) __builtin_amdgcn_s_waitcnt(0x0F70 | ((2 * L) & 15) | (((2 * L) >> 4) << 14));
+        else if (younger == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | (L & 15) | ((L >> 4) << 14));
+        else __builtin_amdgcn_s_waitcnt(0x0F70);
+        __builtin_amdgcn_sched_barrier(0);
+        block_sync_lds();
+        // stage (q-1)%S was read by everybody before this barrier: refill it
+        if (issued < total_chunks) issue_next();
+        compute(q % S);
+        if (ch == a.nchunks - 1) {
+            epilogue(cur);
+            ch = 0;
+            t += nslots;
+            if (t < t_end) cur = decode(t);
+        } else {
+            ++ch;
+        }
+    }
+}
+
+template <int DT, int KS, int MT, bool MAP4, int R, bool HAS_MASK>
+static hipError_t launch_conv_h_m(ConvHArgs a, hipStream_t stream)
 {
     constexpr int RR = R + KS - 1, OC = MAP4 ? 1 : 4, CS = MAP4 ? 1 : KS;
     const int PW = CH_TX + (KS - 1) * a.d;
@@ -327,7 +605,7 @@ static hipError_t launch_conv_h_t(ConvHArgs a, hipStream_t stream)
     if (smem > 160 * 1024) return hipErrorInvalidValue;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_h_kernel<DT, KS, MT, MAP4, R>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_h_kernel<DT, KS, MT, MAP4, R, HAS_MASK>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
@@ -344,6 +622,8 @@ static hipError_t launch_conv_h_t(ConvHArgs a, hipStream_t stream)
     if (a.tiles_lo < 1) a.tiles_lo = 1;
     const long total = (long)a.xtiles * a.ytiles_total * a.mgroups * a.n;
     if (total < 1 || total > 0x7fffffffL) return hipErrorInvalidValue;
+    // the epilogue addresses one image of the destination with 32-bit byte offsets
+    if ((long)(a.out_f32 ? a.c_out * 4L : a.c8_out_total * 16L) * a.OH * a.OW >= 0x7fffffffL) return hipErrorInvalidValue;
     a.total_tiles = (int)total;
     static int cus = 0;
     if (cus == 0) {
@@ -353,22 +633,110 @@ static hipError_t launch_conv_h_t(ConvHArgs a, hipStream_t stream)
     }
     int blocks = cus / 8 * 8;               // one workgroup per CU, a multiple of the 8 XCDs
     if (total < blocks) blocks = (int)((total + 7) / 8 * 8);
-    hipLaunchKernelGGL((conv_h_kernel<DT, KS, MT, MAP4, R>), dim3(blocks), dim3(CH_THREADS), smem, stream, a);
+    hipLaunchKernelGGL((conv_h_kernel<DT, KS, MT, MAP4, R, HAS_MASK>), dim3(blocks), dim3(CH_THREADS), smem, stream, a);
     return hipGetLastError();
+}
+
+template <int DT, int KS, int MT, bool MAP4, int R>
+static hipError_t launch_conv_h_t(const ConvHArgs &a, hipStream_t stream)
+{
+    if (a.mask) return launch_conv_h_m<DT, KS, MT, MAP4, R, true>(a, stream);
+    return launch_conv_h_m<DT, KS, MT, MAP4, R, false>(a, stream);
+}
+
+static int device_cus()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 8)
+            cus = 256;
+    }
+    return cus;
+}
+
+// a few KB of zeros in device memory, read in place of samples outside the image
+static const void *zero_page()
+{
+    static void *page = nullptr;
+    if (!page) {
+        if (hipMalloc(&page, 4096) != hipSuccess || hipMemset(page, 0, 4096) != hipSuccess) page = nullptr;
+    }
+    return page;
+}
+
+constexpr int RING_S = 4;
+
+template <int DT, int KS, int MT, bool MAP4, int R, bool HAS_MASK>
+static hipError_t launch_conv_h_ring_m(ConvHArgs a, hipStream_t stream)
+{
+    constexpr int RR = R + KS - 1, OC = MAP4 ? 1 : 4, CS = MAP4 ? 1 : KS;
+    const int PW = CH_TX + (KS - 1) * a.d;
+    const size_t stage = (size_t)OC * RR * PW + (size_t)CS * KS * MT * 64;
+    const int m_tiles_all = ((a.c_out + 15) / 16 + MT - 1) / MT * MT;
+    const size_t smem = RING_S * stage * 16 + (size_t)m_tiles_all * 16 * sizeof(float);
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_h_ring_kernel<DT, KS, MT, MAP4, R, HAS_MASK, RING_S>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    a.zeros = zero_page();
+    if (!a.zeros) return hipErrorOutOfMemory;
+    a.m_tiles = (a.c_out + 15) / 16;
+    a.mgroups = (a.m_tiles + MT - 1) / MT;
+    a.nchunks = (a.c8_in + OC - 1) / OC;
+    a.xtiles = (a.Wo + CH_TX - 1) / CH_TX;
+    const int q = a.Ho / a.d;
+    a.rem = a.Ho % a.d;
+    a.tiles_hi = (q + 1 + R - 1) / R;
+    a.tiles_lo = (q + R - 1) / R;
+    a.ytiles_total = a.rem * a.tiles_hi + (a.d - a.rem) * a.tiles_lo;
+    if (a.tiles_lo < 1) a.tiles_lo = 1;
+    const long total = (long)a.xtiles * a.ytiles_total * a.mgroups * a.n;
+    if (total < 1 || total > 0x7fffffffL) return hipErrorInvalidValue;
+    if ((long)(a.out_f32 ? a.c_out * 4L : a.c8_out_total * 16L) * a.OH * a.OW >= 0x7fffffffL) return hipErrorInvalidValue;
+    a.total_tiles = (int)total;
+    int blocks = device_cus() / 8 * 8;
+    if (total < blocks) blocks = (int)((total + 7) / 8 * 8);
+    hipLaunchKernelGGL((conv_h_ring_kernel<DT, KS, MT, MAP4, R, HAS_MASK, RING_S>), dim3(blocks), dim3(CH_THREADS), smem, stream, a);
+    return hipGetLastError();
+}
+
+// does the S-stage ring of this configuration fit into the 160 KB of LDS?
+template <int KS, int MT, bool MAP4, int R>
+static bool ring_fits(int d, int c_out)
+{
+    constexpr int RR = R + KS - 1, OC = MAP4 ? 1 : 4, CS = MAP4 ? 1 : KS;
+    const int PW = CH_TX + (KS - 1) * d;
+    const size_t stage = (size_t)OC * RR * PW + (size_t)CS * KS * MT * 64;
+    const int m_tiles_all = ((c_out + 15) / 16 + MT - 1) / MT * MT;
+    return RING_S * stage * 16 + (size_t)m_tiles_all * 64 <= 160 * 1024;
+}
+
+template <int DT, int KS, int MT, bool MAP4, int R>
+static hipError_t launch_conv_h_ring_or_staged(const ConvHArgs &a, hipStream_t stream)
+{
+    if (ring_fits<KS, MT, MAP4, R>(a.d, a.c_out)) {
+        if (a.mask) return launch_conv_h_ring_m<DT, KS, MT, MAP4, R, true>(a, stream);
+        return launch_conv_h_ring_m<DT, KS, MT, MAP4, R, false>(a, stream);
+    }
+    return launch_conv_h_t<DT, KS, MT, MAP4, R>(a, stream);
 }
 
 template <int DT, int MT>
 static hipError_t launch_conv_h_mt(const ConvHArgs &a, hipStream_t stream)
 {
     switch (a.k) {
-    case 1: return launch_conv_h_t<DT, 1, MT, false, 4>(a, stream);
+    case 1: return launch_conv_h_ring_or_staged<DT, 1, MT, false, 4>(a, stream);
     case 2: return launch_conv_h_t<DT, 2, MT, false, 4>(a, stream);
     case 3:
         if constexpr (MT <= 3) return launch_conv_h_t<DT, 3, MT, false, 4>(a, stream);
         else return hipErrorInvalidValue;
     case 4:
-        if constexpr (MT <= 3) return launch_conv_h_t<DT, 4, MT, true, 8>(a, stream);
-        else return launch_conv_h_t<DT, 4, MT, true, 4>(a, stream);
+        if constexpr (MT <= 3) return launch_conv_h_ring_or_staged<DT, 4, MT, true, 8>(a, stream);
+        else return launch_conv_h_ring_or_staged<DT, 4, MT, true, 4>(a, stream);
     default: return hipErrorInvalidValue;
     }
 }

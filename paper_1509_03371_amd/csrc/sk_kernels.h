@@ -54,6 +54,7 @@ struct ConvHArgs {
     int c8_out_total, o8_off, OH, OW, oy_mul, oy_off, ox_mul, ox_off;
     // filled in by the launcher
     int m_tiles, mgroups, nchunks, xtiles, tiles_hi, tiles_lo, rem, ytiles_total, total_tiles;
+    const void *zeros;    // >= 16 bytes of zeros in device memory
 };
 bool conv_h_supported(int k, int d);
 hipError_t launch_conv_h(const ConvHArgs &a, hipStream_t stream);
