@@ -100,7 +100,8 @@ const char *sknet_last_error(void);
  * n_classes must equal the map count of the last layer.  pad_mode: 0 = reflect (edge sample not
  * repeated), 1 = symmetric (edge sample repeated).  Conv weights start as zeros.
  * SK_EINVAL for bad arguments, SK_ESHAPE for k < 1, d < 1, a pool whose s is neither 1 nor k
- * (or s = k with d != 1), SK_EUNSUPPORTED for a dtype this build lacks. */
+ * (or s = k with d != 1), SK_EUNSUPPORTED for k > 15, and for SK_BF16 / SK_F16 nets a conv with
+ * k > 4 or (k-1)*d > 64 (the 16-bit kernels stage at most 192 columns per tile row). */
 sk_status sknet_create(const sk_layer *layers, int32_t n_layers, int32_t c_in, int32_t n_classes,
                        sk_dtype dtype, int32_t pad_mode, sknet_t **out);
 void sknet_destroy(sknet_t *net);
@@ -130,9 +131,14 @@ sk_status sknet_get_weights(sknet_t *net, int32_t conv_idx, float *w_host, float
 /* Fix the problem size: n images of h x w pixels, and allocate every workspace on the current
  * HIP device (hipMalloc).  pad != 0: the library mirror-pads the image by v so that the output
  * is h x w; pad = 0: the caller's image already contains its context and the output is
- * (h - v) x (w - v).  training != 0 also keeps pool masks and allocates gradient buffers.
- * May be called again to change the size.  SK_ESHAPE as in sknet_infer_shapes. */
-sk_status sknet_plan(sknet_t *net, int32_t n, int32_t h, int32_t w, int32_t pad, int32_t training);
+ * (h - v) x (w - v).
+ * mode 0 = inference: layers may be fused (at present: a trailing "1x1 conv + ReLU, 1x1 conv,
+ *          softmax" runs as one kernel whose hidden maps and logits never reach memory; then
+ *          sknet_get_activation reports SK_ESTATE for those two layers);
+ * mode 1 = training: every activation and the pool winners are kept, gradient buffers allocated;
+ * mode 2 = inference with every layer's output kept in memory (for parity checks).
+ * May be called again to change the size or mode.  SK_ESHAPE as in sknet_infer_shapes. */
+sk_status sknet_plan(sknet_t *net, int32_t n, int32_t h, int32_t w, int32_t pad, int32_t mode);
 
 /* Whole forward pass (Section 1.3: image in, per-pixel class probabilities out).
  * image_dev: DEVICE fp32 [n][c_in][h][w];  prob_dev: DEVICE fp32 [n][n_classes][h_out][w_out].
@@ -163,7 +169,7 @@ sk_status sknet_get_grad(sknet_t *net, int32_t conv_idx, float *dw_host, float *
 sk_status sknet_get_activation(sknet_t *net, int32_t layer_idx, float *nchw_host);
 sk_status sknet_get_pool_argmax(sknet_t *net, int32_t pool_idx, int32_t *idx_host);
 
-/* Number of device steps of the planned forward pass (pad, one per layer, softmax), a short
+/* Number of device steps of the planned forward pass (pad, one per layer or fused group, softmax), a short
  * name for step i copied into name (HOST, at most cap bytes), and the average duration in
  * milliseconds of step i re-run iters times on hip_stream between two HIP events (the step
  * reads the activations the last forward left behind).  For benchmarking. */

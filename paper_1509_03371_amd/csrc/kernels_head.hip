@@ -1,0 +1,272 @@
+// Fused classification head of an SK net for inference on gfx950:
+//   h = ReLU(W1 x + b1)   (1x1 convolution, f_in -> hidden)
+//   z = W2 h + b2         (1x1 convolution, hidden -> classes)
+//   p = softmax(z)        (per pixel)
+// i.e. the layers that Algorithm 1 makes out of the inner-product layers of a sliding-window net
+// (ip1/ip2/ip3 + prob in the paper's SK table) when their kernel is 1x1.  Unfused, the hidden maps
+// go out to HBM and come back (1800 B per pixel for 48 -> 200 -> 2 in fp32); fused, a pixel costs
+// its f_in inputs and its class probabilities only.
+//
+// The first product runs on MFMA (A = W1 fragments kept in LDS, B = the pixels, loaded from global
+// memory straight into registers, M = hidden maps, N = 16 pixels).  Its accumulator layout gives
+// lane (g, l16) the hidden maps 4g..4g+3 of every 16-map tile for pixel l16, so the second product
+// is a per-lane partial dot product followed by a reduction over the four lane groups; softmax and
+// the store are done by lane group 0.
+#include "sk_kernels.h"
+
+namespace sk {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
+typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
+
+constexpr int HEAD_THREADS = 256;
+constexpr int HEAD_MAX_CLASSES = 8;
+
+// DT = 0: fp32 NCHW input, MFMA 16x16x4 fp32, one K step = 4 input maps.
+// DT = 1/2: bf16/fp16 octet-layout input, MFMA 16x16x32, one K step = 4 input octets.
+// HT hidden tiles of 16 maps, NTP pixel tiles of 16 pixels per wave and pass, CL class slots.
+template <int DT, int HT, int NTP, int CL>
+__global__ __launch_bounds__(HEAD_THREADS, 2) void head_fused_kernel(HeadArgs a)
+{
+    extern __shared__ float smem[];
+    // LDS: [W1 fragments][b1: HT*16][W2: CL*HT*16][b2: CL]
+    constexpr int FRAG_FLOATS = DT == 0 ? 64 : 256;       // one A fragment: 64 lanes x (4 B | 16 B)
+    const int ksteps = a.ksteps;
+    float *w1 = smem;
+    float *b1 = w1 + HT * ksteps * FRAG_FLOATS;
+    float *w2 = b1 + HT * 16;
+    float *b2 = w2 + CL * HT * 16;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l16 = lane & 15, g = lane >> 4;
+
+    for (int q = tid; q < HT * ksteps * FRAG_FLOATS; q += HEAD_THREADS) w1[q] = static_cast<const float *>(a.w1p)[q];
+    for (int q = tid; q < HT * 16; q += HEAD_THREADS) b1[q] = q < a.hidden ? a.b1[q] : 0.f;
+    for (int q = tid; q < CL * HT * 16; q += HEAD_THREADS) {
+        const int c = q / (HT * 16), m = q - c * (HT * 16);
+        w2[q] = (c < a.classes && m < a.hidden) ? a.w2[c * a.hidden + m] : 0.f;
+    }
+    for (int q = tid; q < CL; q += HEAD_THREADS) b2[q] = q < a.classes ? a.b2[q] : 0.f;
+    __syncthreads();
+
+    // pixel counts fit 32 bits (checked by the launcher)
+    const int plane = a.H * a.W, total = a.n * plane;
+    const int groups = (total + 16 * NTP - 1) / (16 * NTP);
+    const int wave_id = blockIdx.x * (HEAD_THREADS / 64) + wave, wave_cnt = gridDim.x * (HEAD_THREADS / 64);
+    const int c8 = (a.c_in + 7) / 8;
+
+    for (int grp = wave_id; grp < groups; grp += wave_cnt) {
+        floatx4 acc[HT][NTP];
+#pragma unroll
+        for (int mt = 0; mt < HT; ++mt)
+#pragma unroll
+            for (int pt = 0; pt < NTP; ++pt) acc[mt][pt] = floatx4{0.f, 0.f, 0.f, 0.f};
+        long base[NTP];       // element offset of (image, map/octet 0, pixel) for this lane
+        int pix[NTP], img[NTP];
+        bool ok[NTP];
+#pragma unroll
+        for (int pt = 0; pt < NTP; ++pt) {
+            const int p = (grp * NTP + pt) * 16 + l16;
+            ok[pt] = p < total;
+            const int pc = ok[pt] ? p : total - 1;
+            img[pt] = pc / plane;
+            pix[pt] = pc - img[pt] * plane;
+            base[pt] = (long)img[pt] * (DT == 0 ? a.c_in : c8) * plane + pix[pt];
+        }
+        for (int ks = 0; ks < ksteps; ++ks) {
+            if constexpr (DT == 0) {
+                float bv[NTP];
+                const int c = ks * 4 + g;
+                const int cc = c < a.c_in ? c : a.c_in - 1;
+#pragma unroll
+                for (int pt = 0; pt < NTP; ++pt) {
+                    const float v = static_cast<const float *>(a.x)[base[pt] + (long)cc * plane];
+                    bv[pt] = c < a.c_in ? v : 0.f;
+                }
+#pragma unroll
+                for (int mt = 0; mt < HT; ++mt) {
+                    const float av = w1[(mt * ksteps + ks) * 64 + lane];
+#pragma unroll
+                    for (int pt = 0; pt < NTP; ++pt)
+                        acc[mt][pt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bv[pt], acc[mt][pt], 0, 0, 0);
+                }
+            } else {
+                uint4v bv[NTP];
+                const int o = ks * 4 + g;
+                const int oc = o < c8 ? o : c8 - 1;
+#pragma unroll
+                for (int pt = 0; pt < NTP; ++pt) {
+                    const uint4v v = static_cast<const uint4v *>(a.x)[base[pt] + (long)oc * plane];
+                    bv[pt] = o < c8 ? v : uint4v{0u, 0u, 0u, 0u};
+                }
+#pragma unroll
+                for (int mt = 0; mt < HT; ++mt) {
+                    const uint4v av = reinterpret_cast<const uint4v *>(w1)[(mt * ksteps + ks) * 64 + lane];
+#pragma unroll
+                    for (int pt = 0; pt < NTP; ++pt) {
+                        if constexpr (DT == 1)
+                            acc[mt][pt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av), __builtin_bit_cast(bf16x8, bv[pt]), acc[mt][pt], 0, 0, 0);
+                        else
+                            acc[mt][pt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(halfx8, av), __builtin_bit_cast(halfx8, bv[pt]), acc[mt][pt], 0, 0, 0);
+                    }
+                }
+            }
+        }
+        // hidden activation and second product: b1 / W2 fragments are read once per hidden tile and
+        // used for every pixel tile of the pass
+        float z[NTP][CL];
+#pragma unroll
+        for (int pt = 0; pt < NTP; ++pt)
+#pragma unroll
+            for (int c = 0; c < CL; ++c) z[pt][c] = 0.f;
+#pragma unroll
+        for (int mt = 0; mt < HT; ++mt) {
+            const floatx4 bb = *reinterpret_cast<const floatx4 *>(b1 + mt * 16 + 4 * g);
+            floatx4 ww[CL];
+#pragma unroll
+            for (int c = 0; c < CL; ++c) ww[c] = *reinterpret_cast<const floatx4 *>(w2 + (c * HT + mt) * 16 + 4 * g);
+#pragma unroll
+            for (int pt = 0; pt < NTP; ++pt) {
+                floatx4 h = acc[mt][pt] + bb;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) h[r] = fmaxf(h[r], 0.f);
+#pragma unroll
+                for (int c = 0; c < CL; ++c) z[pt][c] += h[0] * ww[c][0] + h[1] * ww[c][1] + h[2] * ww[c][2] + h[3] * ww[c][3];
+            }
+            // keep the compiler from hoisting the LDS reads of all hidden tiles above this point
+            // (it would hold every b1 / W2 fragment in registers at once and spill)
+            if (mt % 2 == 1) __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int pt = 0; pt < NTP; ++pt) {
+#pragma unroll
+            for (int c = 0; c < CL; ++c) {
+                z[pt][c] += __shfl_xor(z[pt][c], 16, 64);
+                z[pt][c] += __shfl_xor(z[pt][c], 32, 64);
+                z[pt][c] += b2[c];
+            }
+            if (g == 0 && ok[pt]) {       // per-pixel softmax over the real classes
+                float m = z[pt][0];
+#pragma unroll
+                for (int c = 1; c < CL; ++c)
+                    if (c < a.classes) m = fmaxf(m, z[pt][c]);
+                float e[CL], sum = 0.f;
+#pragma unroll
+                for (int c = 0; c < CL; ++c) {
+                    e[c] = c < a.classes ? expf(z[pt][c] - m) : 0.f;
+                    sum += e[c];
+                }
+                const float inv = 1.f / sum;
+                float *dst = a.prob + (long)img[pt] * a.classes * plane + pix[pt];
+#pragma unroll
+                for (int c = 0; c < CL; ++c)
+                    if (c < a.classes) dst[(long)c * plane] = e[c] * inv;
+            }
+        }
+    }
+}
+
+// W1 [hidden][c_in] fp32 -> MFMA A fragments, [hidden tile][K step][lane][values]:
+//   DT = 0: value            = W1[16*mt + l16][4*ks + g]
+//   DT > 0: values e = 0..7  = W1[16*mt + l16][8*(4*ks + g) + e]   (16-bit)
+template <int DT>
+__global__ void pack_head_w1_kernel(const float *w1, void *out, int hidden, int c_in, int ht, int ksteps)
+{
+    const int per = DT == 0 ? 1 : 8;
+    const long total = (long)ht * ksteps * 64 * per;
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
+        long r = q;
+        const int e = (int)(r % per); r /= per;
+        const int lane = (int)(r % 64); r /= 64;
+        const int ks = (int)(r % ksteps); r /= ksteps;
+        const int mt = (int)r;
+        const int m = mt * 16 + (lane & 15), g = lane >> 4;
+        const int c = DT == 0 ? ks * 4 + g : (ks * 4 + g) * 8 + e;
+        const float v = (m < hidden && c < c_in) ? w1[(long)m * c_in + c] : 0.f;
+        if constexpr (DT == 0) static_cast<float *>(out)[q] = v;
+        else if constexpr (DT == 1) static_cast<unsigned short *>(out)[q] = __builtin_bit_cast(unsigned short, static_cast<__bf16>(v));
+        else static_cast<unsigned short *>(out)[q] = __builtin_bit_cast(unsigned short, static_cast<_Float16>(v));
+    }
+}
+
+int head_hidden_tiles(int hidden)
+{
+    const int t = (hidden + 15) / 16;
+    return t <= 4 ? 4 : t <= 8 ? 8 : t <= 13 ? 13 : 16;
+}
+
+int head_ksteps(int dtype, int c_in) { return dtype == 0 ? (c_in + 3) / 4 : ((c_in + 7) / 8 + 3) / 4; }
+
+bool head_supported(int dtype, int c_in, int hidden, int classes)
+{
+    if (hidden < 1 || hidden > 256 || classes < 1 || classes > HEAD_MAX_CLASSES || c_in < 1 || c_in > 512) return false;
+    const size_t frag = dtype == 0 ? 256 : 1024;
+    const int ht = head_hidden_tiles(hidden);
+    return ht * head_ksteps(dtype, c_in) * frag + (size_t)(ht * 16 * (HEAD_MAX_CLASSES + 1) + HEAD_MAX_CLASSES) * 4 <= 150 * 1024;
+}
+
+long head_w1_packed_bytes(int dtype, int c_in, int hidden)
+{
+    return (long)head_hidden_tiles(hidden) * head_ksteps(dtype, c_in) * (dtype == 0 ? 256 : 1024);
+}
+
+hipError_t launch_pack_head_w1(const float *w1, void *out, int dtype, int hidden, int c_in, hipStream_t stream)
+{
+    const int ht = head_hidden_tiles(hidden), ks = head_ksteps(dtype, c_in);
+    if (dtype == 0) hipLaunchKernelGGL(pack_head_w1_kernel<0>, dim3(64), dim3(256), 0, stream, w1, out, hidden, c_in, ht, ks);
+    else if (dtype == 1) hipLaunchKernelGGL(pack_head_w1_kernel<1>, dim3(64), dim3(256), 0, stream, w1, out, hidden, c_in, ht, ks);
+    else hipLaunchKernelGGL(pack_head_w1_kernel<2>, dim3(64), dim3(256), 0, stream, w1, out, hidden, c_in, ht, ks);
+    return hipGetLastError();
+}
+
+template <int DT, int HT, int CL>
+static hipError_t launch_head_t(const HeadArgs &a, hipStream_t stream)
+{
+    constexpr int NTP = HT <= 4 ? 4 : (HT <= 8 ? 2 : (CL <= 2 ? 2 : 1));   // bounded by the register file
+    const size_t smem = (size_t)HT * a.ksteps * (DT == 0 ? 256 : 1024) + (size_t)(HT * 16 * (CL + 1) + CL) * 4;
+    static bool attr_set = false;
+    if (smem > 48 * 1024 && !attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&head_fused_kernel<DT, HT, NTP, CL>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const long total = (long)a.n * a.H * a.W;
+    const long groups = (total + 16 * NTP - 1) / (16 * NTP);
+    long blocks = (groups + 3) / 4;
+    if (blocks > 1024) blocks = 1024;     // persistent-style grid: waves stride over the pixel groups
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL((head_fused_kernel<DT, HT, NTP, CL>), dim3((int)blocks), dim3(HEAD_THREADS), smem, stream, a);
+    return hipGetLastError();
+}
+
+template <int DT, int CL>
+static hipError_t launch_head_cl(const HeadArgs &a, hipStream_t stream)
+{
+    switch (head_hidden_tiles(a.hidden)) {
+    case 4: return launch_head_t<DT, 4, CL>(a, stream);
+    case 8: return launch_head_t<DT, 8, CL>(a, stream);
+    case 13: return launch_head_t<DT, 13, CL>(a, stream);
+    default: return launch_head_t<DT, 16, CL>(a, stream);
+    }
+}
+
+template <int DT>
+static hipError_t launch_head_dt(const HeadArgs &a, hipStream_t stream)
+{
+    if (a.classes <= 2) return launch_head_cl<DT, 2>(a, stream);
+    if (a.classes <= 4) return launch_head_cl<DT, 4>(a, stream);
+    return launch_head_cl<DT, 8>(a, stream);
+}
+
+hipError_t launch_head_fused(HeadArgs a, hipStream_t stream)
+{
+    if (!head_supported(a.dtype, a.c_in, a.hidden, a.classes)) return hipErrorInvalidValue;
+    if ((long)a.n * a.H * a.W >= 0x7fffffffL - 64) return hipErrorInvalidValue;
+    a.ksteps = head_ksteps(a.dtype, a.c_in);
+    if (a.dtype == 0) return launch_head_dt<0>(a, stream);
+    if (a.dtype == 1) return launch_head_dt<1>(a, stream);
+    return launch_head_dt<2>(a, stream);
+}
+
+}  // namespace sk

@@ -79,6 +79,22 @@ hipError_t launch_tap_to_index_h(const void *tap, int32_t *idx, int n, int c, in
                                  hipStream_t stream);
 hipError_t launch_bias_grad_h(const void *dy, float *db, int dtype, int n, int c, long plane, hipStream_t stream);
 
+// ---- fused inference head: 1x1 conv + ReLU, 1x1 conv, per-pixel softmax (see kernels_head.hip) -------------
+struct HeadArgs {
+    const void *x;        // input maps: fp32 NCHW (dtype 0) or 16-bit octet layout (dtype 1 bf16, 2 fp16)
+    const void *w1p;      // first conv's weights packed by launch_pack_head_w1
+    const float *b1;      // [hidden]
+    const float *w2;      // second conv's weights, fp32 [classes][hidden]
+    const float *b2;      // [classes]
+    float *prob;          // fp32 NCHW [n][classes][H][W]
+    int dtype, n, c_in, H, W, hidden, classes;
+    int ksteps;           // filled in by the launcher
+};
+bool head_supported(int dtype, int c_in, int hidden, int classes);
+long head_w1_packed_bytes(int dtype, int c_in, int hidden);
+hipError_t launch_pack_head_w1(const float *w1, void *out, int dtype, int hidden, int c_in, hipStream_t stream);
+hipError_t launch_head_fused(HeadArgs a, hipStream_t stream);
+
 // ---- weight / bias gradient of the SK convolution (fp32) ---------------------------------------
 // dW[o][c][i][j] = sum_{b,y,x} dY[b,o,y,x] * X[b,c,y+i*d,x+j*d];  db[o] = sum dY[b,o,:,:].
 // scratch must hold wgrad_scratch_floats(...) floats; the result is deterministic.

@@ -23,6 +23,11 @@ struct sknet {
     std::vector<uint8_t *> tap;       // per layer (pools on a training plan), else nullptr
     float *gbuf[2] = {nullptr, nullptr};
     float *loss_partial = nullptr, *wgrad_scratch = nullptr;
+    // forward schedule of the plan: kind 0 = pad / convert, 1 = layer `arg`, 2 = softmax, 3 = fused head
+    struct Step { int kind, arg; };
+    std::vector<Step> steps;
+    bool fuse_head = false;           // inference plans: last two 1x1 convs + softmax run as one kernel
+    float *head_w1p = nullptr;
     float *logits_f32 = nullptr;      // 16-bit nets: fp32 logits when the last layer is a pool; else alias of act[L]
     float *dz_f32 = nullptr;          // 16-bit training: fp32 gradient of the logits before it is packed
     bool half() const { return dtype != SK_F32; }
@@ -41,7 +46,9 @@ struct sknet {
         }
         tap.clear();
         free_dev(gbuf[0]); free_dev(gbuf[1]); free_dev(loss_partial); free_dev(wgrad_scratch);
-        free_dev(logits_f32); free_dev(dz_f32);
+        free_dev(logits_f32); free_dev(dz_f32); free_dev(head_w1p);
+        steps.clear();
+        fuse_head = false;
         for (auto &c : convs) release_conv(c);
         planned = forward_done = backward_done = false;
     }
@@ -100,10 +107,22 @@ sk_status check_net(const sknet_t *net)
 }
 
 // forward step `step`: 0 = pad/copy, 1..L = layers, L+1 = softmax
-sk_status run_forward_step(sknet *net, int step, hipStream_t stream)
+sk_status run_forward_step(sknet *net, int step_idx, hipStream_t stream)
 {
     const int L = (int)net->layers.size();
     const bool half = net->half();
+    const sknet::Step st = net->steps[step_idx];
+    if (st.kind == 3) {   // fused head on the input of layer L-2
+        const ConvParams &c1 = net->convs[net->conv_of_layer[L - 2]], &c2 = net->convs[net->conv_of_layer[L - 1]];
+        const Dims &in = net->dims[L - 2];
+        sk::HeadArgs a{};
+        a.x = net->act[L - 2]; a.w1p = net->head_w1p; a.b1 = c1.b_dev; a.w2 = c2.w_dev; a.b2 = c2.b_dev;
+        a.prob = net->last_prob; a.dtype = net->dtype; a.n = net->n; a.c_in = in.c; a.H = in.h; a.W = in.w;
+        a.hidden = c1.c_out; a.classes = c2.c_out;
+        SK_HIP(sk::launch_head_fused(a, stream));
+        return SK_OK;
+    }
+    const int step = st.kind == 0 ? 0 : (st.kind == 1 ? st.arg + 1 : L + 1);
     if (step == 0) {
         const Dims &d0 = net->dims[0];
         if (half)   // mirror padding fused into the conversion to the 16-bit octet layout
@@ -311,7 +330,14 @@ sk_status sknet_set_weights(sknet_t *net, int32_t conv_idx, const float *w_host,
     ConvParams &c = net->convs[conv_idx];
     std::memcpy(c.w.data(), w_host, sizeof(float) * c.wcount());
     if (b_host) std::memcpy(c.b.data(), b_host, sizeof(float) * c.c_out);
-    if (net->planned) SK_TRY(upload_conv(c, net->training, net->last_stream, net->dtype));
+    if (net->planned) {
+        SK_TRY(upload_conv(c, net->training, net->last_stream, net->dtype));
+        const int L = (int)net->layers.size();
+        if (net->fuse_head && conv_idx == net->conv_of_layer[L - 2]) {
+            SK_HIP(sk::launch_pack_head_w1(c.w_dev, net->head_w1p, net->dtype, c.c_out, c.c_in, net->last_stream));
+            SK_HIP(hipStreamSynchronize(net->last_stream));
+        }
+    }
     return SK_OK;
 }
 
@@ -332,10 +358,12 @@ sk_status sknet_get_weights(sknet_t *net, int32_t conv_idx, float *w_host, float
     return SK_OK;
 }
 
-sk_status sknet_plan(sknet_t *net, int32_t n, int32_t h, int32_t w, int32_t pad, int32_t training)
+sk_status sknet_plan(sknet_t *net, int32_t n, int32_t h, int32_t w, int32_t pad, int32_t mode)
 {
     SK_TRY(check_net(net));
     if (n < 1) return fail(SK_EINVAL, "plan: n must be >= 1");
+    if (mode < 0 || mode > 2) return fail(SK_EINVAL, "plan: mode must be 0 (inference), 1 (training) or 2 (inference, every layer kept)");
+    const int training = mode == 1;
     std::vector<Dims> dims;
     int pt = 0, pl = 0;
     SK_TRY(infer(net, h, w, pad, dims, &pt, &pl));
@@ -356,7 +384,17 @@ sk_status sknet_plan(sknet_t *net, int32_t n, int32_t h, int32_t w, int32_t pad,
     long max_count = 0;   // largest activation, in floats (16-bit tensors counted in floats as well)
     sk_status st = SK_OK;
     const bool half = net->half();
+    net->fuse_head = false;
+    if (mode == 0 && L >= 2 && net->layers[L - 2].kind == SK_CONV && net->layers[L - 1].kind == SK_CONV &&
+        net->layers[L - 2].k == 1 && net->layers[L - 1].k == 1 && net->layers[L - 2].relu && !net->layers[L - 1].relu &&
+        sk::head_supported(net->dtype, dims[L - 2].c, net->layers[L - 2].c_out, net->layers[L - 1].c_out))
+        net->fuse_head = true;
+    net->steps.clear();
+    net->steps.push_back({0, 0});
+    for (int i = 0; i < (net->fuse_head ? L - 2 : L); ++i) net->steps.push_back({1, i});
+    net->steps.push_back({net->fuse_head ? 3 : 2, 0});
     for (int i = 0; i <= L && st == SK_OK; ++i) {
+        if (net->fuse_head && i >= L - 1) continue;   // hidden maps and logits never leave the head kernel
         const bool f32 = (i == 0) ? !half : stored_f32(net, i - 1);
         const long count = f32 ? dims[i].count(n) : octet_floats(n, dims[i]);
         st = alloc_f(&net->act[i], count);
@@ -378,6 +416,15 @@ sk_status sknet_plan(sknet_t *net, int32_t n, int32_t h, int32_t w, int32_t pad,
             if (st == SK_OK) st = upload_conv(c, training != 0, nullptr, net->dtype);
             const size_t s = sk::wgrad_f32_scratch_floats(c.c_out, c.c_in, c.k);
             if (s > scratch) scratch = s;
+        }
+    }
+    if (st == SK_OK && net->fuse_head) {
+        ConvParams &c1 = net->convs[net->conv_of_layer[L - 2]];
+        st = alloc_f(&net->head_w1p, (sk::head_w1_packed_bytes(net->dtype, c1.c_in, c1.c_out) + 3) / 4);
+        if (st == SK_OK) {
+            hipError_t e = sk::launch_pack_head_w1(c1.w_dev, net->head_w1p, net->dtype, c1.c_out, c1.c_in, nullptr);
+            if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
+            if (e != hipSuccess) st = fail(SK_EDEVICE, "plan: packing the head weights failed: %s", hipGetErrorString(e));
         }
     }
     if (st == SK_OK && training) {
@@ -408,8 +455,7 @@ sk_status sknet_forward(sknet_t *net, const float *image_dev, float *prob_dev, v
     net->last_image = image_dev;
     net->last_prob = prob_dev;
     net->backward_done = false;
-    const int steps = (int)net->layers.size() + 2;
-    for (int s = 0; s < steps; ++s) SK_TRY(run_forward_step(net, s, stream));
+    for (int s = 0; s < (int)net->steps.size(); ++s) SK_TRY(run_forward_step(net, s, stream));
     net->forward_done = true;
     return SK_OK;
 }
@@ -518,6 +564,8 @@ sk_status sknet_get_activation(sknet_t *net, int32_t layer_idx, float *nchw_host
     SK_TRY(check_net(net));
     if (!nchw_host || layer_idx < -1 || layer_idx >= (int)net->layers.size()) return fail(SK_EINVAL, "get_activation: bad arguments");
     if (!net->forward_done) return fail(SK_ESTATE, "get_activation: no forward pass yet");
+    if (net->fuse_head && layer_idx >= (int)net->layers.size() - 2)
+        return fail(SK_ESTATE, "get_activation: this plan fuses the last two layers; plan with mode 2 to keep them");
     SK_HIP(hipStreamSynchronize(net->last_stream));
     const int i = layer_idx + 1;
     const Dims &dm = net->dims[i];
@@ -564,21 +612,24 @@ sk_status sknet_num_steps(const sknet_t *net, int32_t *count)
 {
     SK_TRY(check_net(net));
     if (!count) return fail(SK_EINVAL, "num_steps: count is null");
-    *count = (int32_t)net->layers.size() + 2;
+    if (!net->planned) return fail(SK_ESTATE, "num_steps: call sknet_plan first");
+    *count = (int32_t)net->steps.size();
     return SK_OK;
 }
 
 sk_status sknet_step_name(const sknet_t *net, int32_t step, char *name, int32_t cap)
 {
     SK_TRY(check_net(net));
-    const int L = (int)net->layers.size();
-    if (!name || cap < 1 || step < 0 || step > L + 1) return fail(SK_EINVAL, "step_name: bad arguments");
-    if (step == 0) snprintf(name, cap, "pad");
-    else if (step == L + 1) snprintf(name, cap, "softmax");
+    if (!net->planned) return fail(SK_ESTATE, "step_name: call sknet_plan first");
+    if (!name || cap < 1 || step < 0 || step >= (int)net->steps.size()) return fail(SK_EINVAL, "step_name: bad arguments");
+    const sknet::Step st = net->steps[step];
+    if (st.kind == 0) snprintf(name, cap, "pad");
+    else if (st.kind == 2) snprintf(name, cap, "softmax");
+    else if (st.kind == 3) snprintf(name, cap, "head_fused");
     else {
-        const sk_layer &l = net->layers[step - 1];
-        if (l.kind == SK_CONV) snprintf(name, cap, "conv%d_k%d_d%d_o%d", step - 1, l.k, l.d, l.c_out);
-        else snprintf(name, cap, "pool%d_k%d_d%d_s%d", step - 1, l.k, l.d, l.s);
+        const sk_layer &l = net->layers[st.arg];
+        if (l.kind == SK_CONV) snprintf(name, cap, "conv%d_k%d_d%d_o%d", st.arg, l.k, l.d, l.c_out);
+        else snprintf(name, cap, "pool%d_k%d_d%d_s%d", st.arg, l.k, l.d, l.s);
     }
     return SK_OK;
 }
@@ -586,7 +637,7 @@ sk_status sknet_step_name(const sknet_t *net, int32_t step, char *name, int32_t 
 sk_status sknet_time_step(sknet_t *net, int32_t step, int32_t iters, void *hip_stream, float *avg_ms)
 {
     SK_TRY(check_net(net));
-    if (!avg_ms || iters < 1 || step < 0 || step > (int)net->layers.size() + 1) return fail(SK_EINVAL, "time_step: bad arguments");
+    if (!avg_ms || iters < 1 || step < 0 || step >= (int)net->steps.size()) return fail(SK_EINVAL, "time_step: bad arguments");
     if (!net->forward_done) return fail(SK_ESTATE, "time_step: run sknet_forward first");
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     hipEvent_t e0, e1;

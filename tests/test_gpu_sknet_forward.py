@@ -27,7 +27,7 @@ def make_net(layers, c_in, ws, bs, **kw):
 def run_and_compare(layers, c_in, img, ws, bs, pad=True, pad_mode=0, tol=FP32_TOL):
     net = make_net(layers, c_in, ws, bs, pad_mode=pad_mode)
     n, _, h, w = img.shape
-    net.plan(n, h, w, pad=pad)
+    net.plan(n, h, w, pad=pad, keep=True)
     prob = net.forward(torch.from_numpy(img).cuda())
     torch.cuda.synchronize()
     ref_prob, acts, _ = ON.sknet_forward(img, layers, ws, bs, pad=pad, pad_mode=pad_mode, keep=True)
@@ -39,6 +39,10 @@ def run_and_compare(layers, c_in, img, ws, bs, pad=True, pad_mode=0, tol=FP32_TO
     got = prob.cpu().numpy()
     assert got.shape == ref_prob.shape
     assert np.abs(got - ref_prob).max() <= tol
+    # the inference plan (mode 0) may fuse layers: same probabilities
+    net.plan(n, h, w, pad=pad)
+    fused = net.forward(torch.from_numpy(img).cuda()).cpu().numpy()
+    assert np.abs(fused - ref_prob).max() <= tol
     net.close()
     return got, ref_prob
 
@@ -64,7 +68,7 @@ def test_conv_layer_shapes(k, d, c_in, c_out, h, w):
     ws, bs = S.he_normal_weights(layers, c_in, 7 + k + d, bias_scale=0.5)
     img = np.random.default_rng(3).standard_normal((2, c_in, h, w)).astype(np.float32)
     net = make_net(layers, c_in, ws, bs)
-    net.plan(2, h, w, pad=False)
+    net.plan(2, h, w, pad=False, keep=True)
     net.forward(torch.from_numpy(img).cuda())
     got = net.get_activation(0)
     ref = OL.conv_sk(img, ws[0], bs[0], d, relu=True)
@@ -107,6 +111,31 @@ def test_softmax_many_classes():
     ws, bs = S.he_normal_weights(layers, 4, 33, bias_scale=1.0)
     img = (np.random.default_rng(4).standard_normal((1, 4, 31, 37)) * 3).astype(np.float32)
     run_and_compare(layers, 4, img, ws, bs, pad=False)
+
+
+@pytest.mark.parametrize("c_in,hidden,classes,h,w", [(48, 200, 2, 37, 53), (16, 32, 2, 20, 70), (5, 100, 3, 9, 200),
+                                                       (130, 256, 8, 17, 19), (48, 7, 4, 33, 31)])
+def test_fused_head_matches_oracle(c_in, hidden, classes, h, w):
+    """1x1 conv + ReLU, 1x1 conv, softmax as one kernel (inference plan): probabilities against the
+    oracle, and the layers are reported as not materialised."""
+    from paper_1509_03371_amd import binding as B
+    layers = [S.conv(hidden, 1, 1, relu=True), S.conv(classes, 1, 1, relu=False)]
+    ws, bs = S.he_normal_weights(layers, c_in, 55, bias_scale=0.3)
+    img = np.random.default_rng(8).standard_normal((3, c_in, h, w)).astype(np.float32)
+    net = make_net(layers, c_in, ws, bs)
+    net.plan(3, h, w, pad=False)
+    assert [net.step_name(i) for i in range(net.num_steps())] == ["pad", "head_fused"]
+    prob = net.forward(torch.from_numpy(img).cuda()).cpu().numpy()
+    ref = ON.sknet_forward(img, layers, ws, bs, pad=False)
+    assert np.abs(prob - ref).max() <= FP32_TOL
+    with pytest.raises(B.SknetError) as e:
+        net.get_activation(0)
+    assert e.value.status_name == "SK_ESTATE"
+    net.set_weights(0, ws[0] * 0.5, bs[0])          # re-packing after a weight change
+    prob2 = net.forward(torch.from_numpy(img).cuda()).cpu().numpy()
+    ref2 = ON.sknet_forward(img, layers, [ws[0] * 0.5, ws[1]], bs, pad=False)
+    assert np.abs(prob2 - ref2).max() <= FP32_TOL
+    net.close()
 
 
 def test_tile_and_stitch_on_gpu():

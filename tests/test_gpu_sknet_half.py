@@ -41,7 +41,7 @@ def test_conv_layer_shapes_half(dtype, k, d, c_in, c_out, h, w):
     bs.append(np.zeros(c_out, np.float32))
     img = np.random.default_rng(3).standard_normal((2, c_in, h, w)).astype(np.float32)
     net = make_net(layers, c_in, ws, bs, dt)
-    net.plan(2, h, w, pad=False)
+    net.plan(2, h, w, pad=False, keep=True)
     net.forward(torch.from_numpy(img).cuda())
     ref = OL.conv_sk(img, ws[0], bs[0], d, relu=True)
     got0 = net.get_activation(0)          # stored in 16 bits
@@ -77,7 +77,7 @@ def test_small_sknet_forward_half(dtype):
     ws, bs = S.he_normal_weights(layers, 1, 1001, bias_scale=0.05)
     img = S.em_like_batch(2, 100, 140, 20)
     net = make_net(layers, 1, ws, bs, dtype)
-    net.plan(2, 100, 140, pad=True)
+    net.plan(2, 100, 140, pad=True, keep=True)
     prob = net.forward(torch.from_numpy(img).cuda()).cpu().numpy()
     ref_prob, acts, _ = ON.sknet_forward(img, layers, ws, bs, keep=True)
     for li in range(len(layers)):
@@ -86,6 +86,10 @@ def test_small_sknet_forward_half(dtype):
         assert relerr(got, acts[li + 1]) <= HALF_TOL, (li, layers[li])
     assert np.abs(prob - ref_prob).max() <= HALF_TOL
     assert np.abs(prob.sum(1) - 1).max() < 1e-5
+    net.plan(2, 100, 140, pad=True)                     # inference plan: fused head
+    assert net.step_name(net.num_steps() - 1) == "head_fused"
+    fused = net.forward(torch.from_numpy(img).cuda()).cpu().numpy()
+    assert np.abs(fused - ref_prob).max() <= HALF_TOL
     net.close()
 
 
