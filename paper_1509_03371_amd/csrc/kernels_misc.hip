@@ -52,36 +52,33 @@ hipError_t launch_mirror_pad_f32(const float *in, float *out, int planes, int h,
 }
 
 // ---- max pooling with kernel stride d and layer stride s (Section 5.2.1) --------------------------
-__global__ void maxpool_f32_kernel(const float *x, float *y, uint8_t *tap, int planes, int H, int W,
-                                   int Ho, int Wo, int k, int d, int s)
+// grid: x = column blocks, y = output row, z = plane; no index division on the hot path
+__global__ void maxpool_f32_kernel(const float *x, float *y, uint8_t *tap, int H, int W, int Ho, int Wo, int k, int d, int s)
 {
-    const long total = (long)planes * Ho * Wo;
-    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
-        const int xx = (int)(q % Wo);
-        const long t = q / Wo;
-        const int yy = (int)(t % Ho);
-        const long p = t / Ho;
-        const float *src = x + (p * H + (long)s * yy) * W + (long)s * xx;
-        float best = src[0];
-        int code = 0;
-        for (int i = 0; i < k; ++i)
-            for (int j = 0; j < k; ++j) {
-                const float v = src[(long)i * d * W + j * d];
-                if (v > best) {            // strictly greater: the first maximum wins
-                    best = v;
-                    code = i * k + j;
-                }
+    const int xx = blockIdx.x * blockDim.x + threadIdx.x, yy = blockIdx.y;
+    if (xx >= Wo) return;
+    const long p = blockIdx.z;
+    const float *src = x + (p * H + (long)s * yy) * W + (long)s * xx;
+    float best = src[0];
+    int code = 0;
+    for (int i = 0; i < k; ++i)
+        for (int j = 0; j < k; ++j) {
+            const float v = src[(long)i * d * W + j * d];
+            if (v > best) {            // strictly greater: the first maximum wins
+                best = v;
+                code = i * k + j;
             }
-        y[q] = best;
-        if (tap) tap[q] = (uint8_t)code;
-    }
+        }
+    const long q = (p * Ho + yy) * Wo + xx;
+    y[q] = best;
+    if (tap) tap[q] = (uint8_t)code;
 }
 
 hipError_t launch_maxpool_f32(const float *x, float *y, uint8_t *tap, int planes, int H, int W,
                               int Ho, int Wo, int k, int d, int s, hipStream_t stream)
 {
-    const long total = (long)planes * Ho * Wo;
-    hipLaunchKernelGGL(maxpool_f32_kernel, dim3(grid_for(total)), dim3(256), 0, stream, x, y, tap, planes,
+    if (Ho > 65535 || planes > 65535) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(maxpool_f32_kernel, dim3((Wo + 255) / 256, Ho, planes), dim3(256), 0, stream, x, y, tap,
                        H, W, Ho, Wo, k, d, s);
     return hipGetLastError();
 }
@@ -90,37 +87,34 @@ hipError_t launch_maxpool_f32(const float *x, float *y, uint8_t *tap, int planes
 // output sits at (u - i*d, v - j*d); it collects dY from those whose recorded tap is (i, j).
 // No atomics, so the result does not depend on scheduling.
 __global__ void maxpool_bwd_f32_kernel(const float *dy, const uint8_t *tap, const float *relu_src,
-                                       float *dx, int planes, int H, int W, int Ho, int Wo, int k, int d)
+                                       float *dx, int H, int W, int Ho, int Wo, int k, int d)
 {
-    const long total = (long)planes * H * W;
-    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
-        const int v = (int)(q % W);
-        const long t = q / W;
-        const int u = (int)(t % H);
-        const long p = t / H;
-        float acc = 0.f;
-        for (int i = 0; i < k; ++i) {
-            const int yy = u - i * d;
-            if (yy < 0 || yy >= Ho) continue;
-            for (int j = 0; j < k; ++j) {
-                const int xx = v - j * d;
-                if (xx < 0 || xx >= Wo) continue;
-                const long o = (p * Ho + yy) * Wo + xx;
-                if (tap[o] == i * k + j) acc += dy[o];
-            }
+    const int v = blockIdx.x * blockDim.x + threadIdx.x, u = blockIdx.y;
+    if (v >= W) return;
+    const long p = blockIdx.z;
+    float acc = 0.f;
+    for (int i = 0; i < k; ++i) {
+        const int yy = u - i * d;
+        if (yy < 0 || yy >= Ho) continue;
+        for (int j = 0; j < k; ++j) {
+            const int xx = v - j * d;
+            if (xx < 0 || xx >= Wo) continue;
+            const long o = (p * Ho + yy) * Wo + xx;
+            if (tap[o] == i * k + j) acc += dy[o];
         }
-        if (relu_src && !(relu_src[q] > 0.f)) acc = 0.f;
-        dx[q] = acc;
     }
+    const long q = (p * H + u) * W + v;
+    if (relu_src && !(relu_src[q] > 0.f)) acc = 0.f;
+    dx[q] = acc;
 }
 
 hipError_t launch_maxpool_bwd_f32(const float *dy, const uint8_t *tap, const float *relu_src,
                                   float *dx, int planes, int H, int W, int Ho, int Wo, int k, int d,
                                   hipStream_t stream)
 {
-    const long total = (long)planes * H * W;
-    hipLaunchKernelGGL(maxpool_bwd_f32_kernel, dim3(grid_for(total)), dim3(256), 0, stream, dy, tap,
-                       relu_src, dx, planes, H, W, Ho, Wo, k, d);
+    if (H > 65535 || planes > 65535) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(maxpool_bwd_f32_kernel, dim3((W + 255) / 256, H, planes), dim3(256), 0, stream, dy, tap,
+                       relu_src, dx, H, W, Ho, Wo, k, d);
     return hipGetLastError();
 }
 

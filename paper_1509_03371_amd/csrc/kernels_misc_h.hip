@@ -107,57 +107,56 @@ hipError_t launch_unpack_h(const void *in, float *out, int dtype, int n, int c, 
 }
 
 // ---- max pooling with kernel stride d and layer stride s (Section 5.2.1) on octets --------------------
+// grid: x = column blocks, y = output row, z = plane (image x octet); no index division
 template <int DT>
-__global__ void maxpool_h_kernel(const uint4v *x, uint4v *y, uint2v *tap, long planes, int H, int W, int Ho, int Wo,
+__global__ void maxpool_h_kernel(const uint4v *x, uint4v *y, uint2v *tap, int H, int W, int Ho, int Wo,
                                  int k, int d, int s)
 {
-    const long total = planes * Ho * Wo;
-    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
-        const int xx = (int)(q % Wo);
-        const long t = q / Wo;
-        const int yy = (int)(t % Ho);
-        const long p = t / Ho;
-        const uint4v *src = x + (p * H + (long)s * yy) * W + (long)s * xx;
-        const uint4v first = src[0];
-        float best[8];
-        unsigned bits[8], code[8];
+    const int xx = blockIdx.x * blockDim.x + threadIdx.x, yy = blockIdx.y;
+    if (xx >= Wo) return;
+    const long p = blockIdx.z;
+    const uint4v *src = x + (p * H + (long)s * yy) * W + (long)s * xx;
+    const uint4v first = src[0];
+    float best[8];
+    unsigned bits[8], code[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            bits[e] = elem16(first, e);
-            best[e] = up16<DT>(bits[e]);
-            code[e] = 0;
-        }
-        for (int i = 0; i < k; ++i)
-            for (int j = 0; j < k; ++j) {
-                const uint4v u = src[(long)i * d * W + j * d];
+    for (int e = 0; e < 8; ++e) {
+        bits[e] = elem16(first, e);
+        best[e] = up16<DT>(bits[e]);
+        code[e] = 0;
+    }
+    for (int i = 0; i < k; ++i)
+        for (int j = 0; j < k; ++j) {
+            const uint4v u = src[(long)i * d * W + j * d];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const unsigned b16 = elem16(u, e);
-                    const float v = up16<DT>(b16);
-                    if (v > best[e]) {          // strictly greater: the first maximum wins
-                        best[e] = v;
-                        bits[e] = b16;
-                        code[e] = i * k + j;
-                    }
+            for (int e = 0; e < 8; ++e) {
+                const unsigned b16 = elem16(u, e);
+                const float v = up16<DT>(b16);
+                if (v > best[e]) {          // strictly greater: the first maximum wins
+                    best[e] = v;
+                    bits[e] = b16;
+                    code[e] = i * k + j;
                 }
             }
-        y[q] = uint4v{bits[0] | (bits[1] << 16), bits[2] | (bits[3] << 16), bits[4] | (bits[5] << 16), bits[6] | (bits[7] << 16)};
-        if (tap)
-            tap[q] = uint2v{code[0] | (code[1] << 8) | (code[2] << 16) | (code[3] << 24),
-                            code[4] | (code[5] << 8) | (code[6] << 16) | (code[7] << 24)};
-    }
+        }
+    const long q = (p * Ho + yy) * Wo + xx;
+    y[q] = uint4v{bits[0] | (bits[1] << 16), bits[2] | (bits[3] << 16), bits[4] | (bits[5] << 16), bits[6] | (bits[7] << 16)};
+    if (tap)
+        tap[q] = uint2v{code[0] | (code[1] << 8) | (code[2] << 16) | (code[3] << 24),
+                        code[4] | (code[5] << 8) | (code[6] << 16) | (code[7] << 24)};
 }
 
 hipError_t launch_maxpool_h(const void *x, void *y, void *tap, int dtype, long planes8, int H, int W, int Ho, int Wo,
                             int k, int d, int s, hipStream_t stream)
 {
-    const long total = planes8 * Ho * Wo;
+    if (Ho > 65535 || planes8 > 65535) return hipErrorInvalidValue;
+    const dim3 grid((Wo + 255) / 256, Ho, (unsigned)planes8);
     if (dtype == 1)
-        hipLaunchKernelGGL(maxpool_h_kernel<1>, dim3(grid_for(total)), dim3(256), 0, stream, static_cast<const uint4v *>(x),
-                           static_cast<uint4v *>(y), static_cast<uint2v *>(tap), planes8, H, W, Ho, Wo, k, d, s);
+        hipLaunchKernelGGL(maxpool_h_kernel<1>, grid, dim3(256), 0, stream, static_cast<const uint4v *>(x),
+                           static_cast<uint4v *>(y), static_cast<uint2v *>(tap), H, W, Ho, Wo, k, d, s);
     else
-        hipLaunchKernelGGL(maxpool_h_kernel<2>, dim3(grid_for(total)), dim3(256), 0, stream, static_cast<const uint4v *>(x),
-                           static_cast<uint4v *>(y), static_cast<uint2v *>(tap), planes8, H, W, Ho, Wo, k, d, s);
+        hipLaunchKernelGGL(maxpool_h_kernel<2>, grid, dim3(256), 0, stream, static_cast<const uint4v *>(x),
+                           static_cast<uint4v *>(y), static_cast<uint2v *>(tap), H, W, Ho, Wo, k, d, s);
     return hipGetLastError();
 }
 
@@ -166,59 +165,57 @@ hipError_t launch_maxpool_h(const void *x, void *y, void *tap, int dtype, long p
 // same shape as dx) zeroes the result where the layer below produced a non-positive value.
 template <int DT>
 __global__ void maxpool_bwd_h_kernel(const uint4v *dy, const uint2v *tap, const uint4v *relu_src, uint4v *dx,
-                                     long planes, int H, int W, int Ho, int Wo, int k, int d)
+                                     int H, int W, int Ho, int Wo, int k, int d)
 {
-    const long total = planes * H * W;
-    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
-        const int v = (int)(q % W);
-        const long t = q / W;
-        const int u = (int)(t % H);
-        const long p = t / H;
-        float acc[8];
+    const int v = blockIdx.x * blockDim.x + threadIdx.x, u = blockIdx.y;
+    if (v >= W) return;
+    const long p = blockIdx.z;
+    float acc[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-        for (int i = 0; i < k; ++i) {
-            const int yy = u - i * d;
-            if (yy < 0 || yy >= Ho) continue;
-            for (int j = 0; j < k; ++j) {
-                const int xx = v - j * d;
-                if (xx < 0 || xx >= Wo) continue;
-                const long o = (p * Ho + yy) * Wo + xx;
-                const uint2v c = tap[o];
-                const uint4v g = dy[o];
-                const unsigned want = i * k + j;
+    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+    for (int i = 0; i < k; ++i) {
+        const int yy = u - i * d;
+        if (yy < 0 || yy >= Ho) continue;
+        for (int j = 0; j < k; ++j) {
+            const int xx = v - j * d;
+            if (xx < 0 || xx >= Wo) continue;
+            const long o = (p * Ho + yy) * Wo + xx;
+            const uint2v c = tap[o];
+            const uint4v g = dy[o];
+            const unsigned want = i * k + j;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const unsigned code = (c[e >> 2] >> ((e & 3) * 8)) & 0xffu;
-                    if (code == want) acc[e] += up16<DT>(elem16(g, e));
-                }
+            for (int e = 0; e < 8; ++e) {
+                const unsigned code = (c[e >> 2] >> ((e & 3) * 8)) & 0xffu;
+                if (code == want) acc[e] += up16<DT>(elem16(g, e));
             }
         }
-        unsigned hv[8];
-        uint4v rs = uint4v{0u, 0u, 0u, 0u};
-        if (relu_src) rs = relu_src[q];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            float a = acc[e];
-            if (relu_src && !(up16<DT>(elem16(rs, e)) > 0.f)) a = 0.f;
-            hv[e] = down16<DT>(a);
-        }
-        dx[q] = uint4v{hv[0] | (hv[1] << 16), hv[2] | (hv[3] << 16), hv[4] | (hv[5] << 16), hv[6] | (hv[7] << 16)};
     }
+    const long q = (p * H + u) * W + v;
+    unsigned hv[8];
+    uint4v rs = uint4v{0u, 0u, 0u, 0u};
+    if (relu_src) rs = relu_src[q];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        float a = acc[e];
+        if (relu_src && !(up16<DT>(elem16(rs, e)) > 0.f)) a = 0.f;
+        hv[e] = down16<DT>(a);
+    }
+    dx[q] = uint4v{hv[0] | (hv[1] << 16), hv[2] | (hv[3] << 16), hv[4] | (hv[5] << 16), hv[6] | (hv[7] << 16)};
 }
 
 hipError_t launch_maxpool_bwd_h(const void *dy, const void *tap, const void *relu_src, void *dx, int dtype,
                                 long planes8, int H, int W, int Ho, int Wo, int k, int d, hipStream_t stream)
 {
-    const long total = planes8 * H * W;
+    if (H > 65535 || planes8 > 65535) return hipErrorInvalidValue;
+    const dim3 grid((W + 255) / 256, H, (unsigned)planes8);
     if (dtype == 1)
-        hipLaunchKernelGGL(maxpool_bwd_h_kernel<1>, dim3(grid_for(total)), dim3(256), 0, stream, static_cast<const uint4v *>(dy),
+        hipLaunchKernelGGL(maxpool_bwd_h_kernel<1>, grid, dim3(256), 0, stream, static_cast<const uint4v *>(dy),
                            static_cast<const uint2v *>(tap), static_cast<const uint4v *>(relu_src), static_cast<uint4v *>(dx),
-                           planes8, H, W, Ho, Wo, k, d);
+                           H, W, Ho, Wo, k, d);
     else
-        hipLaunchKernelGGL(maxpool_bwd_h_kernel<2>, dim3(grid_for(total)), dim3(256), 0, stream, static_cast<const uint4v *>(dy),
+        hipLaunchKernelGGL(maxpool_bwd_h_kernel<2>, grid, dim3(256), 0, stream, static_cast<const uint4v *>(dy),
                            static_cast<const uint2v *>(tap), static_cast<const uint4v *>(relu_src), static_cast<uint4v *>(dx),
-                           planes8, H, W, Ho, Wo, k, d);
+                           H, W, Ho, Wo, k, d);
     return hipGetLastError();
 }
 
