@@ -71,6 +71,24 @@ __device__ __forceinline__ bool pos16(unsigned v) { return (v & 0x8000u) == 0 &&
 // serialise the chunk pipelines below with HBM latency.)
 __device__ __forceinline__ void block_sync_lds() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
+// s_waitcnt vmcnt(n) with n chosen at run time (the instruction takes an immediate): n in 0..63
+#define SK_VMW(n) case n: __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14)); break;
+__device__ __forceinline__ void wait_vmcnt_at_most(int n)
+{
+    switch (n) {
+        SK_VMW(0) SK_VMW(1) SK_VMW(2) SK_VMW(3) SK_VMW(4) SK_VMW(5) SK_VMW(6) SK_VMW(7)
+        SK_VMW(8) SK_VMW(9) SK_VMW(10) SK_VMW(11) SK_VMW(12) SK_VMW(13) SK_VMW(14) SK_VMW(15)
+        SK_VMW(16) SK_VMW(17) SK_VMW(18) SK_VMW(19) SK_VMW(20) SK_VMW(21) SK_VMW(22) SK_VMW(23)
+        SK_VMW(24) SK_VMW(25) SK_VMW(26) SK_VMW(27) SK_VMW(28) SK_VMW(29) SK_VMW(30) SK_VMW(31)
+        SK_VMW(32) SK_VMW(33) SK_VMW(34) SK_VMW(35) SK_VMW(36) SK_VMW(37) SK_VMW(38) SK_VMW(39)
+        SK_VMW(40) SK_VMW(41) SK_VMW(42) SK_VMW(43) SK_VMW(44) SK_VMW(45) SK_VMW(46) SK_VMW(47)
+        SK_VMW(48) SK_VMW(49) SK_VMW(50) SK_VMW(51) SK_VMW(52) SK_VMW(53) SK_VMW(54) SK_VMW(55)
+        SK_VMW(56) SK_VMW(57) SK_VMW(58) SK_VMW(59) SK_VMW(60) SK_VMW(61) SK_VMW(62)
+    default: __builtin_amdgcn_s_waitcnt(0x0F70 | 15 | (3 << 14)); break;
+    }
+}
+#undef SK_VMW
+
 struct TilePos {
     int b, mg, py, ty, x0;
 };
@@ -343,7 +361,7 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
 // LDS-write instructions; the loads of the next S-1 chunks are in flight while one chunk is
 // multiplied, which is what covers the HBM latency (one chunk of look-ahead does not).
 // What lies outside the image is read from a small zero buffer instead.
-template <int DT, int KS, int MT, bool MAP4, int R, bool HAS_MASK, int S>
+template <int DT, int KS, int MT, bool MAP4, int R, bool HAS_MASK, int S, bool RESW>
 __global__ __launch_bounds__(CH_THREADS) void conv_h_ring_kernel(ConvHArgs a)
 {
     extern __shared__ uint4v lds[];
@@ -356,72 +374,143 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_ring_kernel(ConvHArgs a)
     constexpr int WBLK = WUNITS / 64;                          // 1 KB fragments in the weight slab
     constexpr int WL = (WBLK + CH_WAVES - 1) / CH_WAVES;
     constexpr int VUE = KS == 1 ? 2 : 3;                       // 64-unit column groups per staged row
-    constexpr int L = RU * VUE + WL;                           // loads issued per wave and chunk
 
     const int d = a.d;
     const int PW = CH_TX + (KS - 1) * d;
     const int tile_units = ROWS * PW;
-    const int stage_units = tile_units + WUNITS;
+    // RESW: the weights of every chunk stay in LDS for the whole kernel (one map group only) and the
+    // ring stages hold input tiles only; otherwise each stage also carries its chunk's weight slab
+    const int stage_units = tile_units + (RESW ? 0 : WUNITS);
+    const int wres_units = RESW ? a.nchunks * WUNITS : 0;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l16 = lane & 15, g = lane >> 4;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), l16 = lane & 15, g = lane >> 4;
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, nslots = gridDim.x >> 3;
     const int t_begin = (int)((long)a.total_tiles * xcd / 8), t_end = (int)((long)a.total_tiles * (xcd + 1) / 8);
 
-    auto decode = [&](int t) {
-        TilePos p;
-        const int xt = t % a.xtiles;
-        int rest = t / a.xtiles;
-        const int yt = rest % a.ytiles_total;
-        rest /= a.ytiles_total;
-        p.mg = rest % a.mgroups;
-        p.b = rest / a.mgroups;
+    // (row phase, row tile) of every y-tile index, looked up instead of divided out per tile
+    const uint4v *wres = lds + S * stage_units;
+    float *bias_lds = reinterpret_cast<float *>(lds + S * stage_units + wres_units);
+    int *ypos = reinterpret_cast<int *>(bias_lds + a.mgroups * MT * 16);
+    if constexpr (RESW) {
+        uint4v *wdst = lds + S * stage_units;
+        const uint4v *wsrc_all = reinterpret_cast<const uint4v *>(a.wp);
+        for (int q = tid; q < wres_units; q += CH_THREADS) wdst[q] = wsrc_all[q];
+    }
+    for (int q = tid; q < a.mgroups * MT * 16; q += CH_THREADS) bias_lds[q] = (a.bias && q < a.m_tiles * 16) ? a.bias[q] : 0.f;
+    for (int yt = tid; yt < a.ytiles_total; yt += CH_THREADS) {
+        int py, ty;
         if (yt < a.rem * a.tiles_hi) {
-            p.py = yt / a.tiles_hi;
-            p.ty = yt - p.py * a.tiles_hi;
+            py = yt / a.tiles_hi;
+            ty = yt - py * a.tiles_hi;
         } else {
             const int y2 = yt - a.rem * a.tiles_hi;
-            p.py = a.rem + y2 / a.tiles_lo;
-            p.ty = y2 % a.tiles_lo;
+            py = a.rem + y2 / a.tiles_lo;
+            ty = y2 % a.tiles_lo;
         }
-        p.x0 = xt * CH_TX;
+        ypos[yt] = (py << 16) | ty;
+    }
+
+    // A tile cursor: index t split into (x tile, y tile, image*mgroups + mgroup); advancing by the
+    // persistent stride nslots is three adds with carries (the split of nslots comes from the host)
+    struct Cursor {
+        int xt, yt, mb;
+    };
+    auto cursor_at = [&](int t) {
+        Cursor c;
+        c.xt = t % a.xtiles;
+        const int rest = t / a.xtiles;
+        c.yt = rest % a.ytiles_total;
+        c.mb = rest / a.ytiles_total;
+        return c;
+    };
+    const int step_x = nslots % a.xtiles, step_y = (nslots / a.xtiles) % a.ytiles_total,
+              step_mb = nslots / a.xtiles / a.ytiles_total;
+    auto advance = [&](Cursor &c) {
+        c.xt += step_x;
+        int carry = c.xt >= a.xtiles;
+        c.xt -= carry ? a.xtiles : 0;
+        c.yt += step_y + carry;
+        carry = c.yt >= a.ytiles_total;
+        c.yt -= carry ? a.ytiles_total : 0;
+        c.mb += step_mb + carry;
+    };
+    auto position = [&](const Cursor &c) {
+        TilePos p;
+        const int yp = ypos[c.yt];
+        p.py = yp >> 16;
+        p.ty = yp & 0xffff;
+        p.x0 = c.xt * CH_TX;
+        if (a.mgroups == 1) {
+            p.mg = 0;
+            p.b = c.mb;
+        } else {
+            p.b = c.mb / a.mgroups;
+            p.mg = c.mb - p.b * a.mgroups;
+        }
         return p;
     };
 
+    // loads this wave issues per chunk: its tile rows (wave, wave + 8, ...) times the column groups,
+    // plus its 1 KB blocks of the weight slab
+    const int L = ((ROWS - wave + CH_WAVES - 1) / CH_WAVES) * VUE + (RESW ? 0 : (WBLK - wave + CH_WAVES - 1) / CH_WAVES);
+    // Waves 4..7 share their SIMDs with waves 0..3.  The first four issue a chunk's loads before
+    // they multiply, the last four after: while one wave of a SIMD sits in the memory pipeline's
+    // queue, the other one keeps the matrix unit busy.
+    const bool late_issue = wave >= CH_WAVES / 2;
+    const long plane_bytes_in = (long)a.H * a.W * 16;
+    const char *zeros = reinterpret_cast<const char *>(a.zeros);
 
-    const long plane = (long)a.H * a.W;
-    const uint4v *zeros = reinterpret_cast<const uint4v *>(a.zeros);
-
-    // issue the loads of chunk `ch` of tile `p` into ring stage `st`
+    // Loads of chunk `ch` of the tile at `p` into ring stage `st`.  Exactly L load instructions for
+    // this wave, whatever the position (the pipeline counts them): a row or a 64-column group that lies
+    // outside the image as a whole is read from the zero page; a group that straddles the image
+    // border is loaded for the lanes inside and the lanes outside write their zeros themselves.
+    // Inside the image the address is a scalar row base plus a per-lane 32-bit column offset.
     auto issue = [&](const TilePos &p, int ch, int st) {
         uint4v *dst = lds + st * stage_units;
         const int gy0 = p.py + d * (p.ty * R) - a.in_off;
         const int gx0 = p.x0 - a.in_off + lane;
+        unsigned coff[VUE];
+        bool cok[VUE];
+#pragma unroll
+        for (int v = 0; v < VUE; ++v) {
+            const int gx = gx0 + 64 * v;
+            cok[v] = gx >= 0 && gx < a.W;
+            coff[v] = (unsigned)(cok[v] ? gx : 0) * 16u;
+        }
 #pragma unroll
         for (int u = 0; u < RU; ++u) {
-            int rid = wave + CH_WAVES * u;
-            rid = rid < ROWS ? rid : rid - CH_WAVES;            // surplus slots repeat this wave's previous row
+            const int rid = wave + CH_WAVES * u;
+            if (rid >= ROWS) break;                              // uniform: this wave has no further row
             const int oc = rid / RR, r = rid - oc * RR;
             const int o = ch * OC + oc;
             const int gy = gy0 + r * d;
             const bool rowok = o < a.c8_in && gy >= 0 && gy < a.H;
-            const uint4v *row = reinterpret_cast<const uint4v *>(a.x) + ((long)p.b * a.c8_in + (rowok ? o : 0)) * plane +
-                                (long)(rowok ? gy : 0) * a.W;
+            const char *rowbase = reinterpret_cast<const char *>(a.x) + ((long)p.b * a.c8_in + (rowok ? o : 0)) * plane_bytes_in +
+                                  (long)(rowok ? gy : 0) * a.W * 16;
 #pragma unroll
             for (int v = 0; v < VUE; ++v) {
-                const int xc = lane + 64 * v, gx = gx0 + 64 * v;
-                const bool ok = rowok && gx >= 0 && gx < a.W;
-                const uint4v *src = ok ? row + gx : zeros;
-                if (xc < PW)
-                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                                     (__attribute__((address_space(3))) void *)(dst + rid * PW + 64 * v), 16, 0, 0);
+                const int xc = lane + 64 * v;
+                uint4v *slot_dst = dst + rid * PW + 64 * v;
+                const bool inside = cok[v] && xc < PW;
+                const bool any_inside = __builtin_amdgcn_ballot_w64(inside) != 0;
+                if (rowok && any_inside) {
+                    if (inside)
+                        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(rowbase + coff[v]),
+                                                         (__attribute__((address_space(3))) void *)slot_dst, 16, 0, 0);
+                    else if (xc < PW)
+                        slot_dst[lane] = uint4v{0u, 0u, 0u, 0u};
+                } else if (xc < PW) {
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(zeros + lane * 16),
+                                                     (__attribute__((address_space(3))) void *)slot_dst, 16, 0, 0);
+                }
             }
         }
-        const uint4v *wsrc = reinterpret_cast<const uint4v *>(a.wp) + ((long)p.mg * a.nchunks + ch) * WUNITS;
+        const char *wsrc = reinterpret_cast<const char *>(a.wp) + ((long)p.mg * a.nchunks + ch) * (WUNITS * 16);
 #pragma unroll
-        for (int u = 0; u < WL; ++u) {
-            int blk = wave + CH_WAVES * u;
-            blk = blk < WBLK ? blk : blk % WBLK;                // surplus slots repeat a block (same data, same place)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(wsrc + blk * 64 + lane),
+        for (int u = 0; u < (RESW ? 0 : WL); ++u) {
+            const int blk = wave + CH_WAVES * u;
+            if (blk >= WBLK) break;                              // uniform
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(wsrc + (unsigned)(blk * 1024 + lane * 16)),
                                              (__attribute__((address_space(3))) void *)(dst + tile_units + blk * 64), 16, 0, 0);
         }
     };
@@ -432,9 +521,9 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_ring_kernel(ConvHArgs a)
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc[y][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    auto compute = [&](int buf) {
+    auto compute = [&](int buf, int chunk) {
         const uint4v *tile = lds + buf * stage_units;
-        const uint4v *wl = tile + tile_units;
+        const uint4v *wl = RESW ? wres + chunk * WUNITS : tile + tile_units;
 #pragma unroll
         for (int cs = 0; cs < CS; ++cs) {
             uint4v afr[KS][MT];
@@ -462,17 +551,23 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_ring_kernel(ConvHArgs a)
     };
 
 
-    // bias of every output map, staged in LDS once (zeros when the layer has none)
-    float *bias_lds = reinterpret_cast<float *>(lds + S * stage_units);
-    for (int q = tid; q < a.mgroups * MT * 16; q += CH_THREADS) bias_lds[q] = (a.bias && q < a.m_tiles * 16) ? a.bias[q] : 0.f;
 
-    // Epilogue of one tile.  Everything it reads comes first (bias from LDS, the optional ReLU mask
-    // in one batch of global loads) and the stores follow without any load in between: on this ISA a
-    // wait for a load also waits for every store issued before it, which would serialise the stores.
-    auto epilogue = [&](const TilePos &p) {
+    // Epilogue of one tile: bias, ReLU, optional ReLU mask of the layer below, conversion, store.
+    // Everything it reads comes first (bias from LDS, the mask in one batch) and the stores follow
+    // without a load in between.  Rows / map tiles outside the output are skipped by uniform
+    // branches, columns outside by the lane mask; the number of memory instructions actually issued
+    // is returned, because the pipeline below counts outstanding operations.
+    auto epilogue = [&](const TilePos &p) -> int {
         const int ox = p.x0 + wave * 16 + l16;
         const bool colok = ox < a.Wo;
-        const int oxc = colok ? ox : 0;
+        if (__builtin_amdgcn_ballot_w64(colok) == 0) {          // this wave's 16 columns lie outside
+#pragma unroll
+            for (int y = 0; y < R; ++y)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) acc[y][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+            return 0;
+        }
+        int ops = 0;
         float bia[MT][4];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
@@ -481,32 +576,39 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_ring_kernel(ConvHArgs a)
         // byte offsets inside one image of the destination stay below 2^31 (checked by the launcher)
         const int row_bytes = a.OW * (a.out_f32 ? 4 : 16);
         const int plane_bytes = a.OH * row_bytes;
-        char *ybase;      // this lane's column in map (or octet) 0, row 0 of image b
-        if (a.out_f32)
-            ybase = reinterpret_cast<char *>(a.y) + (long)p.b * a.c_out * plane_bytes + (long)(oxc * a.ox_mul + a.ox_off) * 4;
-        else
-            ybase = reinterpret_cast<char *>(a.y) + ((long)p.b * a.c8_out_total + a.o8_off) * plane_bytes +
-                    (long)(oxc * a.ox_mul + a.ox_off) * 16 + (g & 1) * 8;
+        const int oxc = colok ? ox : 0;
+        // scalar base of image b (and of the first octet / map), per-lane 32-bit offsets of the column
+        // and of each map tile
+        char *img_base = reinterpret_cast<char *>(a.y) + (a.out_f32 ? (long)p.b * a.c_out : (long)p.b * a.c8_out_total + a.o8_off) * plane_bytes;
+        const char *mask_base = reinterpret_cast<const char *>(a.mask) + (img_base - reinterpret_cast<char *>(a.y));
+        unsigned voff[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const int mtile = p.mg * MT + mt;
+            if (a.out_f32) voff[mt] = (unsigned)((mtile * 16 + 4 * g) * plane_bytes + (oxc * a.ox_mul + a.ox_off) * 4);
+            else voff[mt] = (unsigned)((mtile * 2 + (g >> 1)) * plane_bytes + (oxc * a.ox_mul + a.ox_off) * 16 + (g & 1) * 8);
+        }
         uint2v mk[HAS_MASK ? R : 1][HAS_MASK ? MT : 1];
         if constexpr (HAS_MASK) {
-            const char *mbase = reinterpret_cast<const char *>(a.mask) + (ybase - reinterpret_cast<char *>(a.y));
 #pragma unroll
             for (int y = 0; y < R; ++y) {
-                int oy = p.py + d * (p.ty * R + y);
-                oy = oy < a.Ho ? oy : a.Ho - 1;
-                const int yoff = (oy * a.oy_mul + a.oy_off) * row_bytes;
+                const int oy = p.py + d * (p.ty * R + y);
+                if (oy >= a.Ho) continue;
+                const char *rowp = mask_base + (long)(oy * a.oy_mul + a.oy_off) * row_bytes;
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) {
-                    int o8 = (p.mg * MT + mt) * 2 + (g >> 1);
-                    o8 = o8 < a.c8_out ? o8 : a.c8_out - 1;
-                    mk[y][mt] = *reinterpret_cast<const uint2v *>(mbase + o8 * plane_bytes + yoff);
+                    if (p.mg * MT + mt >= a.m_tiles) continue;
+                    const bool ok = colok && (p.mg * MT + mt) * 2 + (g >> 1) < a.c8_out;
+                    mk[y][mt] = uint2v{0u, 0u};
+                    if (ok) mk[y][mt] = *reinterpret_cast<const uint2v *>(rowp + voff[mt]);
+                    ++ops;
                 }
             }
         }
 #pragma unroll
         for (int y = 0; y < R; ++y) {
             const int oy = p.py + d * (p.ty * R + y);
-            const int yoff = (oy * a.oy_mul + a.oy_off) * row_bytes;
+            char *rowp = img_base + (long)(oy * a.oy_mul + a.oy_off) * row_bytes;
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
                 const int mtile = p.mg * MT + mt;
@@ -521,10 +623,12 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_ring_kernel(ConvHArgs a)
                 if (a.out_f32) {
                     const int o = mtile * 16 + 4 * g;
 #pragma unroll
-                    for (int r4 = 0; r4 < 4; ++r4)
-                        if (colok && o + r4 < a.c_out) *reinterpret_cast<float *>(ybase + (o + r4) * plane_bytes + yoff) = v[r4];
+                    for (int r4 = 0; r4 < 4; ++r4) {
+                        // lane group 0 of a valid column always owns a real map, so every one of these is issued
+                        if (colok && o + r4 < a.c_out) *reinterpret_cast<float *>(rowp + voff[mt] + (unsigned)(r4 * plane_bytes)) = v[r4];
+                        ops += (mtile * 16 + r4 < a.c_out) ? 1 : 0;
+                    }
                 } else {
-                    const int o8 = mtile * 2 + (g >> 1);
                     unsigned short h[4];
 #pragma unroll
                     for (int r4 = 0; r4 < 4; ++r4) h[r4] = H<DT>::cvt(v[r4]);
@@ -538,58 +642,76 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_ring_kernel(ConvHArgs a)
                         if (!pos16(m[1] >> 16)) hi &= 0x0000ffffu;
                         packed = uint2v{lo, hi};
                     }
-                    if (colok && o8 < a.c8_out) *reinterpret_cast<uint2v *>(ybase + o8 * plane_bytes + yoff) = packed;
+                    if (colok && mtile * 2 + (g >> 1) < a.c8_out) *reinterpret_cast<uint2v *>(rowp + voff[mt]) = packed;
+                    ++ops;
                 }
             }
         }
+        return ops;
     };
-
 
     int t = t_begin + slot;
     if (t >= t_end) return;
     const int my_tiles = (t_end - t + nslots - 1) / nslots;
     const int total_chunks = my_tiles * a.nchunks;
+    block_sync_lds();                                   // ypos / bias tables are in place
 
     // issue cursor (runs S-1 chunks ahead of the compute cursor)
-    TilePos ipos = decode(t);
-    int it = t, ich = 0, issued = 0;
+    Cursor icur = cursor_at(t), ccur = icur;
+    TilePos ipos = position(icur);
+    int ich = 0, issued = 0, itiles = 0;
     auto issue_next = [&]() {
         issue(ipos, ich, issued % S);
         ++issued;
         if (++ich == a.nchunks) {
             ich = 0;
-            it += nslots;
-            if (it < t_end) ipos = decode(it);
+            if (++itiles < my_tiles) {
+                advance(icur);
+                ipos = position(icur);
+            }
         }
     };
 #pragma unroll
     for (int j = 0; j < S - 1; ++j)
         if (j < total_chunks) issue_next();
 
-    TilePos cur = decode(t);
-    int ch = 0;
+    TilePos cur = position(ccur);
+    int ch = 0, ctiles = 0;
+    int ep_ops[S - 1];            // memory operations of the epilogues of the last S-1 iterations
+#pragma unroll
+    for (int j = 0; j < S - 1; ++j) ep_ops[j] = 0;
     for (int q = 0; q < total_chunks; ++q) {
-        // chunk q must have landed; the loads of the younger chunks may stay in flight.  (Stores of
-        // an epilogue issued since then are younger still and make this wait longer than needed, never
-        // shorter: the counter retires in issue order.)
-        const int younger = issued - q - 1;
+        // Chunk q must have landed.  The counter retires operations in issue order, so it may still
+        // show whatever was issued after chunk q's loads: the loads of the (up to S-2) younger chunks
+        // and the epilogue operations of the last S-1 iterations.  Allowing fewer is safe (it only
+        // waits longer), allowing more is not.
+        int allow = (issued - q - 1) * L;
+#pragma unroll
+        for (int j = 0; j < S - 1; ++j)
+            if (j < S - 2 || !late_issue) allow += ep_ops[j];   // a late issuer's oldest epilogue precedes chunk q's loads
+        allow = allow < 63 ? allow : 63;
         __builtin_amdgcn_sched_barrier(0);
-        if (younger >= 2) __builtin_amdgcn_s_waitcnt(0x0F70 | ((2 * L) & 15) | (((2 * L) >> 4) << 14));
-        else if (younger == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | (L & 15) | ((L >> 4) << 14));
-        else __builtin_amdgcn_s_waitcnt(0x0F70);
+        wait_vmcnt_at_most(allow);
         __builtin_amdgcn_sched_barrier(0);
         block_sync_lds();
-        // stage (q-1)%S was read by everybody before this barrier: refill it
-        if (issued < total_chunks) issue_next();
-        compute(q % S);
+        // stage (q-1)%S was read by everybody before this barrier: refill it, before or after the
+        // multiplication depending on the wave
+        if (!late_issue && issued < total_chunks) issue_next();
+        compute(q % S, ch);
+#pragma unroll
+        for (int j = S - 2; j > 0; --j) ep_ops[j] = ep_ops[j - 1];
+        ep_ops[0] = 0;
         if (ch == a.nchunks - 1) {
-            epilogue(cur);
+            ep_ops[0] = epilogue(cur);
             ch = 0;
-            t += nslots;
-            if (t < t_end) cur = decode(t);
+            if (++ctiles < my_tiles) {
+                advance(ccur);
+                cur = position(ccur);
+            }
         } else {
             ++ch;
         }
+        if (late_issue && issued < total_chunks) issue_next();
     }
 }
 
@@ -665,19 +787,28 @@ static const void *zero_page()
     return page;
 }
 
-constexpr int RING_S = 4;
-
-template <int DT, int KS, int MT, bool MAP4, int R, bool HAS_MASK>
-static hipError_t launch_conv_h_ring_m(ConvHArgs a, hipStream_t stream)
+// LDS bytes of the ring kernel: S stages (+ resident weights) + bias + y-tile table
+template <int KS, int MT, bool MAP4, int R, int S, bool RESW>
+static size_t ring_smem(int d, int c_out, int c8_in, int Ho)
 {
     constexpr int RR = R + KS - 1, OC = MAP4 ? 1 : 4, CS = MAP4 ? 1 : KS;
-    const int PW = CH_TX + (KS - 1) * a.d;
-    const size_t stage = (size_t)OC * RR * PW + (size_t)CS * KS * MT * 64;
-    const int m_tiles_all = ((a.c_out + 15) / 16 + MT - 1) / MT * MT;
-    const size_t smem = RING_S * stage * 16 + (size_t)m_tiles_all * 16 * sizeof(float);
+    const int PW = CH_TX + (KS - 1) * d;
+    const size_t tile = (size_t)OC * RR * PW, slab = (size_t)CS * KS * MT * 64;
+    const int nchunks = (c8_in + OC - 1) / OC;
+    const int m_tiles_all = ((c_out + 15) / 16 + MT - 1) / MT * MT;
+    const size_t units = RESW ? S * tile + nchunks * slab : S * (tile + slab);
+    return units * 16 + (size_t)m_tiles_all * 64 + (size_t)(Ho / R + 2 * d + 2) * 4;
+}
+
+template <int DT, int KS, int MT, bool MAP4, int R, bool HAS_MASK, int S, bool RESW>
+static hipError_t launch_conv_h_ring_m(ConvHArgs a, hipStream_t stream)
+{
+    constexpr int OC = MAP4 ? 1 : 4;
+    const size_t smem = ring_smem<KS, MT, MAP4, R, S, RESW>(a.d, a.c_out, a.c8_in, a.Ho);
+    if (smem > 160 * 1024) return hipErrorInvalidValue;            // callers check the size first
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_h_ring_kernel<DT, KS, MT, MAP4, R, HAS_MASK, RING_S>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_h_ring_kernel<DT, KS, MT, MAP4, R, HAS_MASK, S, RESW>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
@@ -694,34 +825,35 @@ static hipError_t launch_conv_h_ring_m(ConvHArgs a, hipStream_t stream)
     a.tiles_lo = (q + R - 1) / R;
     a.ytiles_total = a.rem * a.tiles_hi + (a.d - a.rem) * a.tiles_lo;
     if (a.tiles_lo < 1) a.tiles_lo = 1;
+    if (RESW && a.mgroups != 1) return hipErrorInvalidValue;
     const long total = (long)a.xtiles * a.ytiles_total * a.mgroups * a.n;
     if (total < 1 || total > 0x7fffffffL) return hipErrorInvalidValue;
     if ((long)(a.out_f32 ? a.c_out * 4L : a.c8_out_total * 16L) * a.OH * a.OW >= 0x7fffffffL) return hipErrorInvalidValue;
     a.total_tiles = (int)total;
     int blocks = device_cus() / 8 * 8;
     if (total < blocks) blocks = (int)((total + 7) / 8 * 8);
-    hipLaunchKernelGGL((conv_h_ring_kernel<DT, KS, MT, MAP4, R, HAS_MASK, RING_S>), dim3(blocks), dim3(CH_THREADS), smem, stream, a);
+    hipLaunchKernelGGL((conv_h_ring_kernel<DT, KS, MT, MAP4, R, HAS_MASK, S, RESW>), dim3(blocks), dim3(CH_THREADS), smem, stream, a);
     return hipGetLastError();
 }
 
-// does the S-stage ring of this configuration fit into the 160 KB of LDS?
-template <int KS, int MT, bool MAP4, int R>
-static bool ring_fits(int d, int c_out)
+template <int DT, int KS, int MT, bool MAP4, int R, int S, bool RESW>
+static hipError_t launch_conv_h_ring_mask(const ConvHArgs &a, hipStream_t stream)
 {
-    constexpr int RR = R + KS - 1, OC = MAP4 ? 1 : 4, CS = MAP4 ? 1 : KS;
-    const int PW = CH_TX + (KS - 1) * d;
-    const size_t stage = (size_t)OC * RR * PW + (size_t)CS * KS * MT * 64;
-    const int m_tiles_all = ((c_out + 15) / 16 + MT - 1) / MT * MT;
-    return RING_S * stage * 16 + (size_t)m_tiles_all * 64 <= 160 * 1024;
+    if (a.mask) return launch_conv_h_ring_m<DT, KS, MT, MAP4, R, true, S, RESW>(a, stream);
+    return launch_conv_h_ring_m<DT, KS, MT, MAP4, R, false, S, RESW>(a, stream);
 }
 
+// Preference: weights resident in LDS with a 3-stage ring of input tiles (one map group, all chunk
+// slabs fit), else a 4-stage ring that streams the weight slab with each chunk, else the
+// register-staged two-stage kernel.
 template <int DT, int KS, int MT, bool MAP4, int R>
 static hipError_t launch_conv_h_ring_or_staged(const ConvHArgs &a, hipStream_t stream)
 {
-    if (ring_fits<KS, MT, MAP4, R>(a.d, a.c_out)) {
-        if (a.mask) return launch_conv_h_ring_m<DT, KS, MT, MAP4, R, true>(a, stream);
-        return launch_conv_h_ring_m<DT, KS, MT, MAP4, R, false>(a, stream);
-    }
+    const bool one_group = ((a.c_out + 15) / 16 + MT - 1) / MT == 1;
+    if (one_group && ring_smem<KS, MT, MAP4, R, 3, true>(a.d, a.c_out, a.c8_in, a.Ho) <= 160 * 1024)
+        return launch_conv_h_ring_mask<DT, KS, MT, MAP4, R, 3, true>(a, stream);
+    if (ring_smem<KS, MT, MAP4, R, 4, false>(a.d, a.c_out, a.c8_in, a.Ho) <= 160 * 1024)
+        return launch_conv_h_ring_mask<DT, KS, MT, MAP4, R, 4, false>(a, stream);
     return launch_conv_h_t<DT, KS, MT, MAP4, R>(a, stream);
 }
 
