@@ -7,6 +7,8 @@ A step is one such pass over one synthetic image that is resident in HBM before 
 
 --workload c3 : the same net in bf16 (fp32 accumulate) on 8 images of 1024x1024 (configs[2])
 --workload c4 : one bf16 training step at 512x512 (configs[3]): forward, softmax loss, backward, SGD
+--workload copy : only the streaming-copy probe on 2 x 1 GiB (the known-size kernel that the HBM
+                  byte counters of a profiler run are calibrated against)
 The default run also appends short c3 / c4 measurements under "extras" (skip with --no-extras).
 """
 import argparse
@@ -109,12 +111,25 @@ def measure_train(torch, B, S, dtype, n, H, W, steps, warmup, first_seed):
     return {"pixels_per_s": n * H * W * steps / dt, "ms_per_step": dt / steps * 1e3, "steps": steps}
 
 
+def measured_peaks(torch, B):
+    """What this GPU sustains on a bare MFMA issue loop and on a streaming copy (not the method)."""
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)   # 1 GiB each
+    dst = torch.empty_like(src)
+    peaks = {"mfma_f32_tflops": round(B.sk_probe_mfma("f32", 100000), 1),
+             "mfma_bf16_tflops": round(B.sk_probe_mfma("bf16", 100000), 1),
+             "mfma_f16_tflops": round(B.sk_probe_mfma("f16", 100000), 1),
+             "copy_gbs_1gib": round(B.sk_probe_copy(src, dst, 10), 1)}
+    del src, dst
+    torch.cuda.empty_cache()
+    return peaks
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", choices=["c2", "c3", "c4"], default="c2")
+    ap.add_argument("--workload", choices=["c2", "c3", "c4", "copy"], default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
     args = ap.parse_args()
@@ -133,6 +148,15 @@ def main():
     out = {"metric": METRIC, "unit": "pixels/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "data": "synthetic"}
 
+    if args.workload == "copy":
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
+        dst = torch.empty_like(src)
+        gbs = B.sk_probe_copy(src, dst, max(1, args.steps))
+        print(json.dumps({"metric": "streaming copy", "value": round(gbs, 1), "unit": "GB/s (read + written)",
+                          "bytes_read_per_launch": src.numel() * 4, "bytes_written_per_launch": src.numel() * 4,
+                          "launches": max(1, args.steps) + 1, "kernel": "stream_copy_kernel"}))
+        return
+
     if args.workload in ("c2", "c3"):
         dtype, n, H, seed = ("f32", 1, 512, 2) if args.workload == "c2" else ("bf16", 8, 1024, 3)
         r = measure_forward(torch, B, S, dtype, n, H, H, args.steps, args.warmup, seed)
@@ -149,6 +173,7 @@ def main():
             "forward_tflops": round(r["forward_tflops"], 2),
             "pool_gbs": round(r["pool_gbs"], 1), "pool_frac_of_hbm_peak": round(r["pool_gbs"] / HBM_PEAK_GBS, 4),
             "step_ms": r["step_ms"],
+            "measured_peaks": measured_peaks(torch, B),
         })
     else:
         r = measure_train(torch, B, S, "bf16", 1, 512, 512, args.steps, args.warmup, 2)

@@ -67,6 +67,8 @@ _SIGS = {
     "unet_plan": [_vp, _i32, _i32, _i32],
     "unet_forward": [_vp, _vp, _vp, _vp],
     "unet_get_activation": [_vp, C.c_char_p, _fp, _ip],
+    "sk_probe_mfma": [_i32, _i32, _vp, C.POINTER(C.c_double)],
+    "sk_probe_copy": [_vp, _vp, C.c_uint64, _i32, _vp, C.POINTER(C.c_double)],
 }
 for _name, _args in _SIGS.items():
     _f = getattr(lib, _name)
@@ -117,6 +119,24 @@ def layers_to_c(layers):
         else:
             raise ValueError("unknown layer type %r" % (l["type"],))
     return arr
+
+
+def sk_probe_mfma(dtype, iters=20000, stream=None):
+    """Sustained TFLOP/s of a bare MFMA issue loop of the shape used for dtype ('f32'|'bf16'|'f16')."""
+    out = C.c_double(0.0)
+    _check(lib.sk_probe_mfma(DTYPES[dtype], iters, _stream(stream), C.byref(out)))
+    return out.value
+
+
+def sk_probe_copy(src, dst, reps=10, stream=None):
+    """GB/s (read + written) of a streaming copy between two equally sized CUDA tensors."""
+    nbytes = src.numel() * src.element_size()
+    if not (src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous()
+            and dst.numel() * dst.element_size() == nbytes):
+        raise TypeError("sk_probe_copy: two contiguous CUDA tensors of the same byte size")
+    out = C.c_double(0.0)
+    _check(lib.sk_probe_copy(C.c_void_p(src.data_ptr()), C.c_void_p(dst.data_ptr()), nbytes, reps, _stream(stream), C.byref(out)))
+    return out.value
 
 
 def sknet_conv_flops(f_in, f_out, k, w_out):
