@@ -16,6 +16,8 @@
 // pixels), D = 16 maps x 16 pixels.  Lane l supplies A[m = l%16][kk = l/16] and
 // B[kk = l/16][pixel = l%16] and receives D[m = 4*(l/16) + r][pixel = l%16], r = 0..3, so each
 // store instruction writes 64-byte runs of consecutive pixels of one map.
+#include <type_traits>
+
 #include "sk_kernels.h"
 
 namespace sk {
@@ -24,6 +26,75 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int CONV_TX = 64;   // output columns per workgroup
 constexpr int CONV_CC = 4;    // input maps per K chunk
+
+// Epilogue shared by the kernels below: bias, ReLU, optional ReLU-derivative mask, predicated store.
+// acc[rw][xt][nt][r] belongs to output map o_first + 16*nt + r, row oy_first + rw*d, column
+// ox_first + 16*xt.  The vector memory counter is one in-order queue for loads and stores, so a
+// load awaited between stores makes that wait cover every store before it.  The bias is therefore
+// fetched in one batch and awaited once; the store loop without a mask then contains no load at
+// all, and the masked variant fetches the masks of a whole pixel tile before its first store.
+template <int NT, int RW>
+__device__ __forceinline__ void store_outputs(const ConvF32Args &a, floatx4 (&acc)[RW][4][NT], int b, int o_first,
+                                              int oy_first, int d, int ox_first)
+{
+    float bia[NT][4];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) bia[nt][r4] = 0.f;
+    if (a.bias) {                                       // uniform branch; the vector holds n_pad entries
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                const int o = o_first + nt * 16 + r4;
+                bia[nt][r4] = a.bias[o < a.n_pad ? o : a.n_pad - 1];
+            }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0): the bias is in registers from here on
+    __builtin_amdgcn_sched_barrier(0);
+    const long oplane = (long)a.OH * a.OW;
+    auto store_tiles = [&](auto masked) {
+#pragma unroll
+        for (int rw = 0; rw < RW; ++rw) {
+            const int oy = oy_first + rw * d;
+            if (oy >= a.Ho) continue;
+            const long rowbase = (((long)b * a.out_maps + a.o_off + o_first) * a.OH + (long)oy * a.oy_mul + a.oy_off) * a.OW + a.ox_off;
+#pragma unroll
+            for (int xt = 0; xt < 4; ++xt) {
+                const int ox = ox_first + xt * 16;
+                if (ox >= a.Wo) continue;
+                const long pbase = rowbase + (long)ox * a.ox_mul;
+                float mk[NT][4];
+                if constexpr (decltype(masked)::value) {
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                        for (int r4 = 0; r4 < 4; ++r4) {
+                            // maps beyond c_out are never stored; their mask address is clamped to
+                            // map 0 of the same pixel so that the load stays inside the tensor
+                            const int oo = nt * 16 + r4;
+                            mk[nt][r4] = a.mask[pbase + (o_first + oo < a.c_out ? oo : -o_first) * oplane];
+                        }
+                }
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4) {
+                        const int oo = nt * 16 + r4;
+                        if (o_first + oo >= a.c_out) continue;
+                        float v = acc[rw][xt][nt][r4] + bia[nt][r4];
+                        if (a.relu) v = v > 0.f ? v : 0.f;
+                        if constexpr (decltype(masked)::value)
+                            if (!(mk[nt][r4] > 0.f)) v = 0.f;
+                        a.y[pbase + oo * oplane] = v;
+                    }
+            }
+        }
+    };
+    if (a.mask) store_tiles(std::true_type{});
+    else store_tiles(std::false_type{});
+}
 
 template <int NT, int RW>
 __global__ __launch_bounds__(256) void conv_f32_kernel(ConvF32Args a, int tiles_hi, int tiles_lo,
@@ -118,40 +189,7 @@ __global__ __launch_bounds__(256) void conv_f32_kernel(ConvF32Args a, int tiles_
         }
     }
 
-    // epilogue: bias, ReLU, optional mask, predicated store
-    // bias first, in one batch: a load issued between stores would make its wait cover the stores too
-    float bia[NT][4];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-            const int o = nb * WN + nt * 16 + 4 * g + r4;
-            bia[nt][r4] = (a.bias && o < a.n_pad) ? a.bias[o] : 0.f;
-        }
-#pragma unroll
-    for (int rw = 0; rw < RW; ++rw) {
-        const int oy = py + d * (ty * R + wave * RW + rw);
-        if (oy >= a.Ho) continue;
-#pragma unroll
-        for (int xt = 0; xt < 4; ++xt) {
-            const int ox = x0 + xt * 16 + l16;
-            if (ox >= a.Wo) continue;
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-#pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4) {
-                    const int o = nb * WN + nt * 16 + 4 * g + r4;
-                    if (o >= a.c_out) continue;
-                    float v = acc[rw][xt][nt][r4] + bia[nt][r4];
-                    if (a.relu) v = v > 0.f ? v : 0.f;
-                    const long idx = (((long)b * a.out_maps + o + a.o_off) * a.OH + (long)oy * a.oy_mul + a.oy_off) * a.OW +
-                                     (long)ox * a.ox_mul + a.ox_off;
-                    if (a.mask && !(a.mask[idx] > 0.f)) v = 0.f;
-                    a.y[idx] = v;
-                }
-            }
-        }
-    }
+    store_outputs<NT, RW>(a, acc, b, nb * WN + 4 * g, py + d * (ty * R + wave * RW), d, x0 + l16);
 }
 
 template <int NT, int RW>
@@ -199,7 +237,6 @@ __global__ __launch_bounds__(256) void conv_f32_pf_kernel(ConvF32Args a, int til
     const int PW = CONV_TX + (KS - 1) * d, PITCH = PW;
     float *xs = smem;
     float *ws = xs + CC * RR * PITCH;
-    int *koff = reinterpret_cast<int *>(ws + KC * WN);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l16 = lane & 15, g = lane >> 4;
     int py, ty;
@@ -217,10 +254,15 @@ __global__ __launch_bounds__(256) void conv_f32_pf_kernel(ConvF32Args a, int til
     const int b = blockIdx.z / nblocks, nb = blockIdx.z - b * nblocks;
     const int x0 = blockIdx.x * CONV_TX;
 
-    for (int q = tid; q < KC; q += 256) {
+    // LDS offset of K index (c, i, j) inside the staged tile, for the K values this lane group
+    // supplies in each of the KC/4 steps of a chunk; the same for every chunk, so kept in registers
+    int kreg[KC / 4];
+#pragma unroll
+    for (int sidx = 0; sidx < KC / 4; ++sidx) {
+        const int q = 4 * sidx + g;
         const int c = q / KK2, r = q - c * KK2;
         const int i = r / KS, j = r - i * KS;
-        koff[q] = (c * RR + i) * PITCH + j * d;
+        kreg[sidx] = (c * RR + i) * PITCH + j * d + wave * RW * PITCH + l16;
     }
 
     floatx4 acc[RW][4][NT];
@@ -310,16 +352,16 @@ __global__ __launch_bounds__(256) void conv_f32_pf_kernel(ConvF32Args a, int til
         // K loop with the operand fragments of step kk+4 fetched from LDS while the MFMAs of step kk run
         float av[2][NT], bv[2][RW][4];
         auto fetch = [&](int kk, int buf) {
-            const int ko = koff[kk + g];
+            const int ko = kreg[kk >> 2];
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) av[buf][nt] = ws[(kk + g) * WN + nt * 16 + l16];
 #pragma unroll
             for (int rw = 0; rw < RW; ++rw)
 #pragma unroll
-                for (int xt = 0; xt < 4; ++xt) bv[buf][rw][xt] = xs[ko + (wave * RW + rw) * PITCH + l16 + xt * 16];
+                for (int xt = 0; xt < 4; ++xt) bv[buf][rw][xt] = xs[ko + rw * PITCH + xt * 16];
         };
         fetch(0, 0);
-#pragma unroll 2
+#pragma unroll
         for (int kk = 0; kk < KC; kk += 4) {
             const int cur = (kk >> 2) & 1;
             if (kk + 4 < KC) fetch(kk + 4, cur ^ 1);
@@ -333,39 +375,7 @@ __global__ __launch_bounds__(256) void conv_f32_pf_kernel(ConvF32Args a, int til
         }
     }
 
-    // bias first, in one batch: a load issued between stores would make its wait cover the stores too
-    float bia[NT][4];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-            const int o = nb * WN + nt * 16 + 4 * g + r4;
-            bia[nt][r4] = (a.bias && o < a.n_pad) ? a.bias[o] : 0.f;
-        }
-#pragma unroll
-    for (int rw = 0; rw < RW; ++rw) {
-        const int oy = py + d * (ty * R + wave * RW + rw);
-        if (oy >= a.Ho) continue;
-#pragma unroll
-        for (int xt = 0; xt < 4; ++xt) {
-            const int ox = x0 + xt * 16 + l16;
-            if (ox >= a.Wo) continue;
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-#pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4) {
-                    const int o = nb * WN + nt * 16 + 4 * g + r4;
-                    if (o >= a.c_out) continue;
-                    float v = acc[rw][xt][nt][r4] + bia[nt][r4];
-                    if (a.relu) v = v > 0.f ? v : 0.f;
-                    const long idx = (((long)b * a.out_maps + o + a.o_off) * a.OH + (long)oy * a.oy_mul + a.oy_off) * a.OW +
-                                     (long)ox * a.ox_mul + a.ox_off;
-                    if (a.mask && !(a.mask[idx] > 0.f)) v = 0.f;
-                    a.y[idx] = v;
-                }
-            }
-        }
-    }
+    store_outputs<NT, RW>(a, acc, b, nb * WN + 4 * g, py + d * (ty * R + wave * RW), d, x0 + l16);
 }
 
 template <int NT, int RW, int KS, int CC, int NCG>

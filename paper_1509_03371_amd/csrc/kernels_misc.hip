@@ -74,10 +74,74 @@ __global__ void maxpool_f32_kernel(const float *x, float *y, uint8_t *tap, int H
     if (tap) tap[q] = (uint8_t)code;
 }
 
+// k = 2, s = 1 (every SK pool of the paper): window (y, x) is {h[y], h[y + d]} where h[r] is the
+// first maximum of X[r][x], X[r][x + d].  A thread walks one column down the rows y0, y0 + d,
+// y0 + 2d, ... of one residue class mod d, so each h is formed once and serves both windows it
+// belongs to, and a block reads every input row it needs exactly once.  grid: x = column blocks,
+// y = residue class x segments of M chain links, z = plane.  Winner codes follow the row-major
+// scan (0,1 for row y; 2,3 for row y + d), strictly-greater replaces.
+template <bool TAP>
+__global__ void __launch_bounds__(256) maxpool2_chain_f32_kernel(const float *__restrict__ x, float *__restrict__ y,
+                                                                 uint8_t *__restrict__ tap, int H, int W, int Ho, int Wo,
+                                                                 int d, int M, int nseg)
+{
+    const int xx = blockIdx.x * 256 + threadIdx.x;
+    const int phase = blockIdx.y / nseg, seg = blockIdx.y - phase * nseg;
+    if (xx >= Wo || phase >= Ho) return;
+    const int links = (Ho - phase + d - 1) / d;
+    const int m0 = seg * M, m1 = min(links, m0 + M);
+    if (m0 >= m1) return;
+    const long p = blockIdx.z;
+    const long rstep = (long)d * W, ostep = (long)d * Wo;
+    const float *src = x + (p * H + phase + (long)m0 * d) * W + xx;
+    float *dst = y + (p * Ho + phase + (long)m0 * d) * Wo + xx;
+    uint8_t *tdst = TAP ? tap + (p * Ho + phase + (long)m0 * d) * Wo + xx : nullptr;
+    float h = src[0];
+    int hc = 0;
+    {
+        const float b = src[d];
+        if (b > h) { h = b; hc = 1; }
+    }
+    constexpr int U = 8;
+    for (int m = m0; m < m1; m += U) {
+        float a[U], b[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {                     // all loads of the group first
+            const float *r = src + (m + u < m1 ? (long)(u + 1) * rstep : 0);
+            a[u] = r[0];
+            b[u] = r[d];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (m + u >= m1) break;
+            float h2 = a[u];
+            int hc2 = 0;
+            if (b[u] > h2) { h2 = b[u]; hc2 = 1; }
+            const bool lower = h2 > h;
+            dst[(long)u * ostep] = lower ? h2 : h;
+            if (TAP) tdst[(long)u * ostep] = (uint8_t)(lower ? 2 + hc2 : hc);
+            h = h2;
+            hc = hc2;
+        }
+        src += (long)U * rstep;
+        dst += (long)U * ostep;
+        if (TAP) tdst += (long)U * ostep;
+    }
+}
+
 hipError_t launch_maxpool_f32(const float *x, float *y, uint8_t *tap, int planes, int H, int W,
                               int Ho, int Wo, int k, int d, int s, hipStream_t stream)
 {
     if (Ho > 65535 || planes > 65535) return hipErrorInvalidValue;
+    if (k == 2 && s == 1 && Ho == H - d && Wo == W - d) {
+        const int M = 32, links = (Ho + d - 1) / d, nseg = (links + M - 1) / M;
+        if ((long)d * nseg <= 65535) {
+            const dim3 grid((Wo + 255) / 256, (unsigned)(d * nseg), (unsigned)planes);
+            if (tap) hipLaunchKernelGGL(maxpool2_chain_f32_kernel<true>, grid, dim3(256), 0, stream, x, y, tap, H, W, Ho, Wo, d, M, nseg);
+            else hipLaunchKernelGGL(maxpool2_chain_f32_kernel<false>, grid, dim3(256), 0, stream, x, y, tap, H, W, Ho, Wo, d, M, nseg);
+            return hipGetLastError();
+        }
+    }
     hipLaunchKernelGGL(maxpool_f32_kernel, dim3((Wo + 255) / 256, Ho, planes), dim3(256), 0, stream, x, y, tap,
                        H, W, Ho, Wo, k, d, s);
     return hipGetLastError();

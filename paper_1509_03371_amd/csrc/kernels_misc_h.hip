@@ -146,10 +146,112 @@ __global__ void maxpool_h_kernel(const uint4v *x, uint4v *y, uint2v *tap, int H,
                         code[4] | (code[5] << 8) | (code[6] << 16) | (code[7] << 24)};
 }
 
+// k = 2, s = 1 (every SK pool of the paper): window (y, x) is {h[y], h[y + d]} where h[r] is the
+// first maximum of X[r][x], X[r][x + d].  A thread walks one column down the rows y0, y0 + d,
+// y0 + 2d, ... of one residue class mod d, so each h is formed once and serves both windows it
+// belongs to, and a block reads every input row it needs exactly once (no second workgroup, on
+// another XCD with another L2, fetches the same rows again).  grid: x = column blocks,
+// y = residue class x segments of M chain links, z = plane.  Winner codes follow the row-major
+// scan: 0,1 for row y, 2,3 for row y + d, strictly-greater replaces.
+template <int DT>
+__device__ __forceinline__ void row_first_max(const uint4v a, const uint4v b, uint4v &h, unsigned &hc)
+{
+    hc = 0u;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        unsigned m = 0u;
+        if (up16<DT>(b[w] & 0xffffu) > up16<DT>(a[w] & 0xffffu)) { m |= 0x0000ffffu; hc |= 1u << (2 * w); }
+        if (up16<DT>(b[w] >> 16) > up16<DT>(a[w] >> 16)) { m |= 0xffff0000u; hc |= 1u << (2 * w + 1); }
+        h[w] = (a[w] & ~m) | (b[w] & m);
+    }
+}
+
+template <int DT, bool TAP>
+__global__ void __launch_bounds__(256) maxpool2_chain_h_kernel(const uint4v *__restrict__ x, uint4v *__restrict__ y,
+                                                               uint2v *__restrict__ tap, int H, int W, int Ho, int Wo,
+                                                               int d, int M, int nseg)
+{
+    const int xx = blockIdx.x * 256 + threadIdx.x;
+    const int phase = blockIdx.y / nseg, seg = blockIdx.y - phase * nseg;
+    if (xx >= Wo || phase >= Ho) return;
+    const int links = (Ho - phase + d - 1) / d;           // windows of this residue class
+    const int m0 = seg * M, m1 = min(links, m0 + M);
+    if (m0 >= m1) return;
+    const long p = blockIdx.z;
+    const long rstep = (long)d * W;
+    const uint4v *src = x + (p * H + phase + (long)m0 * d) * W + xx;
+    uint4v *dst = y + (p * Ho + phase + (long)m0 * d) * Wo + xx;
+    uint2v *tdst = TAP ? tap + (p * Ho + phase + (long)m0 * d) * Wo + xx : nullptr;
+    const long ostep = (long)d * Wo;
+    uint4v h;
+    unsigned hc;
+    row_first_max<DT>(src[0], src[d], h, hc);
+    constexpr int U = 4;
+    for (int m = m0; m < m1; m += U) {
+        uint4v a[U], b[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {                     // all loads of the group first
+            const bool live = m + u < m1;
+            const uint4v *r = src + (live ? (long)(u + 1) * rstep : 0);
+            a[u] = r[0];
+            b[u] = r[d];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (m + u >= m1) break;
+            uint4v h2;
+            unsigned hc2;
+            row_first_max<DT>(a[u], b[u], h2, hc2);
+            uint4v o;
+            unsigned c_lo = 0u, c_hi = 0u;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                unsigned msk = 0u;
+#pragma unroll
+                for (int hh = 0; hh < 2; ++hh) {
+                    const int e = 2 * w + hh;
+                    const unsigned v1 = hh ? (h[w] >> 16) : (h[w] & 0xffffu), v2 = hh ? (h2[w] >> 16) : (h2[w] & 0xffffu);
+                    const bool lower = up16<DT>(v2) > up16<DT>(v1);
+                    if (lower) msk |= hh ? 0xffff0000u : 0x0000ffffu;
+                    if (TAP) {
+                        const unsigned code = lower ? 2u + ((hc2 >> e) & 1u) : ((hc >> e) & 1u);
+                        if (e < 4) c_lo |= code << (8 * e); else c_hi |= code << (8 * (e - 4));
+                    }
+                }
+                o[w] = (h[w] & ~msk) | (h2[w] & msk);
+            }
+            dst[(long)u * ostep] = o;
+            if (TAP) tdst[(long)u * ostep] = uint2v{c_lo, c_hi};
+            h = h2;
+            hc = hc2;
+        }
+        src += (long)U * rstep;
+        dst += (long)U * ostep;
+        if (TAP) tdst += (long)U * ostep;
+    }
+}
+
 hipError_t launch_maxpool_h(const void *x, void *y, void *tap, int dtype, long planes8, int H, int W, int Ho, int Wo,
                             int k, int d, int s, hipStream_t stream)
 {
     if (Ho > 65535 || planes8 > 65535) return hipErrorInvalidValue;
+    if (k == 2 && s == 1 && Ho == H - d && Wo == W - d) {
+        const int M = 32, links = (Ho + d - 1) / d, nseg = (links + M - 1) / M;
+        if ((long)d * nseg <= 65535) {
+            const dim3 grid((Wo + 255) / 256, (unsigned)(d * nseg), (unsigned)planes8);
+            const uint4v *xi = static_cast<const uint4v *>(x);
+            uint4v *yo = static_cast<uint4v *>(y);
+            uint2v *tp = static_cast<uint2v *>(tap);
+            if (dtype == 1) {
+                if (tap) hipLaunchKernelGGL((maxpool2_chain_h_kernel<1, true>), grid, dim3(256), 0, stream, xi, yo, tp, H, W, Ho, Wo, d, M, nseg);
+                else hipLaunchKernelGGL((maxpool2_chain_h_kernel<1, false>), grid, dim3(256), 0, stream, xi, yo, tp, H, W, Ho, Wo, d, M, nseg);
+            } else {
+                if (tap) hipLaunchKernelGGL((maxpool2_chain_h_kernel<2, true>), grid, dim3(256), 0, stream, xi, yo, tp, H, W, Ho, Wo, d, M, nseg);
+                else hipLaunchKernelGGL((maxpool2_chain_h_kernel<2, false>), grid, dim3(256), 0, stream, xi, yo, tp, H, W, Ho, Wo, d, M, nseg);
+            }
+            return hipGetLastError();
+        }
+    }
     const dim3 grid((Wo + 255) / 256, Ho, (unsigned)planes8);
     if (dtype == 1)
         hipLaunchKernelGGL(maxpool_h_kernel<1>, grid, dim3(256), 0, stream, static_cast<const uint4v *>(x),

@@ -18,7 +18,11 @@ typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
 constexpr int kAcc = 8;   // independent accumulators per wave: hides the MFMA result latency
 
 // Each wave issues iters * kAcc dependent-free MFMAs of one shape; nothing touches memory until
-// the single store at the end (kept so the loop is not removed).
+// the single store at the end (kept so the loop is not removed).  The MFMAs are written as inline
+// assembly with the accumulators pinned to vector registers: with the builtin the register
+// allocator shuttles the loop-carried accumulators between register files and the loop no longer
+// measures the matrix pipe.  Eight independent accumulators separate dependent instructions by
+// far more than the pipe's depth, and the s_nop pair covers the read of the results afterwards.
 template <int DT>
 __global__ void __launch_bounds__(256) mfma_issue_kernel(float *out, int iters)
 {
@@ -30,7 +34,7 @@ __global__ void __launch_bounds__(256) mfma_issue_kernel(float *out, int iters)
         const float a = seed, b = 1.0f;
         for (int it = 0; it < iters; ++it) {
 #pragma unroll
-            for (int i = 0; i < kAcc; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[i], 0, 0, 0);
+            for (int i = 0; i < kAcc; ++i) asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" : "+v"(acc[i]) : "v"(a), "v"(b));
         }
     } else if constexpr (DT == SK_BF16) {
         bf16x8 a, b;
@@ -38,7 +42,7 @@ __global__ void __launch_bounds__(256) mfma_issue_kernel(float *out, int iters)
         for (int i = 0; i < 8; ++i) { a[i] = (__bf16)seed; b[i] = (__bf16)1.0f; }
         for (int it = 0; it < iters; ++it) {
 #pragma unroll
-            for (int i = 0; i < kAcc; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[i], 0, 0, 0);
+            for (int i = 0; i < kAcc; ++i) asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc[i]) : "v"(a), "v"(b));
         }
     } else {
         halfx8 a, b;
@@ -46,9 +50,10 @@ __global__ void __launch_bounds__(256) mfma_issue_kernel(float *out, int iters)
         for (int i = 0; i < 8; ++i) { a[i] = (_Float16)seed; b[i] = (_Float16)1.0f; }
         for (int it = 0; it < iters; ++it) {
 #pragma unroll
-            for (int i = 0; i < kAcc; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, acc[i], 0, 0, 0);
+            for (int i = 0; i < kAcc; ++i) asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+v"(acc[i]) : "v"(a), "v"(b));
         }
     }
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
     float s = 0.f;
 #pragma unroll
     for (int i = 0; i < kAcc; ++i) s += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
