@@ -169,7 +169,7 @@ def main():
             "roofline": {"bound": "mfma", "achieved": round(r["conv_tflops"], 2), "peak": peak, "unit": "TFLOP/s",
                          "frac": round(r["conv_tflops"] / peak, 4), "traffic": None,
                          "kernel": "48->48 k4 SK convolutions at d=2,4,8 (%s)"
-                                   % ("conv_f32_pf_kernel<3,1,4,4,2>" if dtype == "f32" else "conv_h_kernel<bf16,4,3,MAP4,8>")},
+                                   % ("conv_f32_pf_kernel<3,1,4,4,2,false>" if dtype == "f32" else "conv_h_ring_kernel<bf16,4,3,MAP4,8,false,3,true>")},
             "forward_tflops": round(r["forward_tflops"], 2),
             "pool_gbs": round(r["pool_gbs"], 1), "pool_frac_of_hbm_peak": round(r["pool_gbs"] / HBM_PEAK_GBS, 4),
             "step_ms": r["step_ms"],

@@ -226,19 +226,265 @@ static hipError_t launch_conv_f32_t(const ConvF32Args &a, hipStream_t stream)
 // flight; they are written to LDS after the loop.  Wave w stages input maps c0 + w, c0 + w + 4, ...
 // of the chunk (CC/4 maps, RR rows each, NCG groups of 64 columns), so every count is a compile-time
 // constant and the prefetched values stay in registers.
-template <int NT, int RW, int KS, int CC, int NCG>
+template <int NT, int RW, int KS, int CC, int NCG, bool PADZ>
 __global__ __launch_bounds__(256) void conv_f32_pf_kernel(ConvF32Args a, int tiles_hi, int tiles_lo,
-                                                          int rem, int nblocks)
+                                                          int rem, int nblocks, int gx, int gy, int total_tiles)
 {
     extern __shared__ float smem[];
     constexpr int R = 4 * RW, WN = NT * 16, RR = R + KS - 1, KK2 = KS * KS, KC = CC * KK2, CPW = CC / 4;
     constexpr int WV4 = (KC * WN / 4 + 255) / 256;   // float4 weight loads per thread and chunk
+    constexpr int PITCH = 64 * NCG;                  // floats per staged row; holds 64 + (KS-1)*d columns
     const int d = a.d;
-    const int PW = CONV_TX + (KS - 1) * d, PITCH = PW;
     float *xs = smem;
     float *ws = xs + CC * RR * PITCH;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l16 = lane & 15, g = lane >> 4;
+    // While other waves of a SIMD stream MFMAs, every other instruction a wave issues waits tens of
+    // cycles for its turn, so the staging code below is kept to as few instructions as possible:
+    // wave-uniform quantities (map, row, slab bases) are made scalar, whatever is the same for every
+    // K chunk (per-lane column offsets, per-thread weight and LDS offsets) is computed once, and
+    // LDS offsets that depend only on the K index are compile-time constants.
+    const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, g = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // LDS offset of K index (c, i, j) inside the staged tile for the K values lane group g supplies
+    // in step s of a chunk: klane + kconst(s) when the k*k taps of a map fill whole steps, else a
+    // per-lane table in registers.
+    constexpr bool KSPLIT = KK2 % 4 == 0 || KK2 == 1;
+    int klane = 0;
+    int kreg[KSPLIT ? 1 : KC / 4];
+    if constexpr (KK2 == 1) klane = g * RR * PITCH;
+    else if constexpr (KSPLIT) klane = (g / KS) * PITCH + (g % KS) * d;
+    else {
+#pragma unroll
+        for (int sidx = 0; sidx < KC / 4; ++sidx) {
+            const int q = 4 * sidx + g;
+            const int c = q / KK2, r = q - c * KK2;
+            const int i = r / KS, j = r - i * KS;
+            kreg[sidx] = (c * RR + i) * PITCH + j * d;
+        }
+    }
+    auto kconst = [](int sidx) {
+        if constexpr (KK2 == 1) return 4 * sidx * RR * PITCH;
+        else return ((4 * sidx / KK2) * RR + (4 * sidx % KK2) / KS) * PITCH;
+    };
+
+    const int kthread = wave * RW * PITCH + l16;
+
+    // Persistent workgroups: the grid holds as many workgroups as fit on the GPU at once and each
+    // walks over tiles tile, tile + gridDim.x, ...; a tail of tiles then runs on workgroups that are
+    // spread over all CUs instead of as a second, mostly empty wave of fresh workgroups.
+    for (int tile = blockIdx.x; tile < total_tiles; tile += gridDim.x) {
+    const int bx = tile % gx, byz = tile / gx;
+    const int by = byz % gy, bz = byz / gy;
+    int py, ty;
+    if (by < rem * tiles_hi) {
+        py = by / tiles_hi;
+        ty = by - py * tiles_hi;
+    } else {
+        const int b2 = by - rem * tiles_hi;
+        py = rem + b2 / tiles_lo;
+        ty = b2 % tiles_lo;
+    }
+    const int b = bz / nblocks, nb = bz - b * nblocks;
+    const int x0 = bx * CONV_TX;
+
+    floatx4 acc[RW][4][NT];
+#pragma unroll
+    for (int rw = 0; rw < RW; ++rw)
+#pragma unroll
+        for (int xt = 0; xt < 4; ++xt)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) acc[rw][xt][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    const long plane = (long)a.H * a.W;
+    const float *xb = a.x + (long)b * a.c_in * plane;
+    const int nchunks = (a.c_in + CC - 1) / CC;
+    const int gy0 = py + d * (ty * R) - a.in_off;       // input row of tile row 0
+    const int gx0 = x0 - a.in_off + lane;                // input column of this lane, column group 0
+
+    float xr[CPW][RR][NCG];
+    floatx4 wr[WV4];
+
+    // Loads are unconditional (addresses clamped into the tensor) so that they can stay in flight
+    // across the MFMA loop.  With zero padding (PADZ: the transposed convolution of the backward
+    // pass) what lies outside the image is replaced by zero when the registers are written to LDS.
+    // Without it (in_off = 0) a clamped address can only feed outputs that are never stored, and a
+    // clamped map index meets zero weights; activations are finite by contract.
+    unsigned coff[NCG];        // byte offset of this lane's column inside a row
+    bool colok[NCG];
+#pragma unroll
+    for (int cg = 0; cg < NCG; ++cg) {
+        const int gx = gx0 + 64 * cg;
+        colok[cg] = gx >= 0 && gx < a.W;
+        coff[cg] = 4u * (unsigned)(gx < 0 ? 0 : (gx >= a.W ? a.W - 1 : gx));
+    }
+    int roff[RR];              // element offset of staged row t inside a map (wave-uniform)
+    bool rowok[RR];
+#pragma unroll
+    for (int t = 0; t < RR; ++t) {
+        const int gy = gy0 + t * d;
+        rowok[t] = gy >= 0 && gy < a.H;
+        roff[t] = (gy < 0 ? 0 : (gy >= a.H ? a.H - 1 : gy)) * a.W;
+    }
+    unsigned woff[WV4];        // byte offset of this thread's float4 inside a chunk's weight slab
+#pragma unroll
+    for (int u = 0; u < WV4; ++u) {
+        int q = tid + 256 * u;               // float4 index inside the [KC][WN] slab
+        q = q < KC * WN / 4 ? q : KC * WN / 4 - 1;
+        const int r = q / (WN / 4), cn = (q - r * (WN / 4)) * 4;
+        int col = nb * WN + cn;
+        col = col < a.n_pad ? col : a.n_pad - 4;         // such columns belong to maps that are never stored
+        woff[u] = 4u * (unsigned)(r * a.n_pad + col);
+    }
+    const int xs_thread = wave * RR * PITCH + lane;
+    auto prefetch = [&](int chunk) {
+#pragma unroll
+        for (int cw = 0; cw < CPW; ++cw) {
+            int c = chunk * CC + wave + 4 * cw;
+            c = c < a.c_in ? c : a.c_in - 1;
+            const float *src = xb + (long)c * plane;
+#pragma unroll
+            for (int t = 0; t < RR; ++t) {
+                const char *row = reinterpret_cast<const char *>(src + roff[t]);
+#pragma unroll
+                for (int cg = 0; cg < NCG; ++cg) xr[cw][t][cg] = *reinterpret_cast<const float *>(row + coff[cg]);
+            }
+        }
+        const char *slab = reinterpret_cast<const char *>(a.wp + (long)chunk * KC * a.n_pad);
+#pragma unroll
+        for (int u = 0; u < WV4; ++u) wr[u] = *reinterpret_cast<const floatx4 *>(slab + woff[u]);
+    };
+    auto commit = [&](int chunk) {
+#pragma unroll
+        for (int cw = 0; cw < CPW; ++cw) {
+            const bool cok = chunk * CC + wave + 4 * cw < a.c_in;
+#pragma unroll
+            for (int t = 0; t < RR; ++t)
+#pragma unroll
+                for (int cg = 0; cg < NCG; ++cg) {
+                    float v = xr[cw][t][cg];
+                    if constexpr (PADZ) v = (cok && rowok[t] && colok[cg]) ? v : 0.f;
+                    xs[xs_thread + (4 * cw * RR + t) * PITCH + 64 * cg] = v;
+                }
+        }
+#pragma unroll
+        for (int u = 0; u < WV4; ++u) {
+            const int q = tid + 256 * u;
+            if (KC * WN / 4 % 256 == 0 || q < KC * WN / 4) *reinterpret_cast<floatx4 *>(ws + 4 * q) = wr[u];
+        }
+    };
+
+    prefetch(0);
+    for (int chunk = 0; chunk < nchunks; ++chunk) {
+        __syncthreads();
+        commit(chunk);
+        __syncthreads();
+        if (chunk + 1 < nchunks) prefetch(chunk + 1);
+        // K loop with the operand fragments of step s+1 fetched from LDS while the MFMAs of step s run
+        float av[2][NT], bv[2][RW][4];
+        auto fetch = [&](int sidx, int buf) {
+            int ko = klane + kthread + kconst(sidx);
+            if constexpr (!KSPLIT) ko = kreg[sidx] + kthread;
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) av[buf][nt] = ws[(4 * sidx + g) * WN + nt * 16 + l16];
+#pragma unroll
+            for (int rw = 0; rw < RW; ++rw)
+#pragma unroll
+                for (int xt = 0; xt < 4; ++xt) bv[buf][rw][xt] = xs[ko + rw * PITCH + xt * 16];
+        };
+        fetch(0, 0);
+#pragma unroll
+        for (int sidx = 0; sidx < KC / 4; ++sidx) {
+            const int cur = sidx & 1;
+            if (sidx + 1 < KC / 4) fetch(sidx + 1, cur ^ 1);
+            // the scheduler otherwise sinks each LDS read to just before its first use and the wave
+            // waits out the LDS latency several times per step
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int rw = 0; rw < RW; ++rw)
+#pragma unroll
+                for (int xt = 0; xt < 4; ++xt)
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
+                        acc[rw][xt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[cur][nt], bv[cur][rw][xt], acc[rw][xt][nt], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+
+    store_outputs<NT, RW>(a, acc, b, nb * WN + 4 * g, py + d * (ty * R + wave * RW), d, x0 + l16);
+    }
+}
+
+template <int NT, int RW, int KS, int CC, int NCG, bool PADZ>
+static hipError_t launch_conv_f32_pf_z(const ConvF32Args &a, hipStream_t stream)
+{
+    constexpr int R = 4 * RW, WN = NT * 16, RR = R + KS - 1, KC = CC * KS * KS, PITCH = 64 * NCG;
+    if (CONV_TX + (KS - 1) * a.d > PITCH) return hipErrorInvalidValue;
+    if ((long)a.H * a.W >= (1L << 29)) return hipErrorInvalidValue;     // 32-bit byte offsets inside a map
+    if ((long)KC * a.n_pad >= (1L << 29)) return hipErrorInvalidValue;  // and inside a weight slab
+    const size_t smem = sizeof(float) * ((size_t)CC * RR * PITCH + (size_t)KC * WN);
+    if (smem > 150 * 1024) return hipErrorInvalidValue;
+    static bool attr_set = false;
+    if (smem > 48 * 1024 && !attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_f32_pf_kernel<NT, RW, KS, CC, NCG, PADZ>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int q = a.Ho / a.d, rem = a.Ho % a.d;
+    const int tiles_hi = (q + 1 + R - 1) / R, tiles_lo = (q + R - 1) / R;
+    const int gy = rem * tiles_hi + (a.d - rem) * tiles_lo;
+    const int nblocks = (a.n_pad / 16 + NT - 1) / NT;
+    const int gx = (a.Wo + CONV_TX - 1) / CONV_TX;
+    const long total = (long)gx * gy * a.n * nblocks;
+    if (gx <= 0 || gy <= 0 || total <= 0 || total > 0x7fffffffL) return hipErrorInvalidValue;
+    static int slots = 0;                  // workgroups of this kernel that are resident at once
+    if (slots == 0) {
+        int dev = 0, cus = 0, per_cu = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e == hipSuccess)
+            e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, conv_f32_pf_kernel<NT, RW, KS, CC, NCG, PADZ>, 256, smem);
+        if (e != hipSuccess) return e;
+        slots = cus * (per_cu > 0 ? per_cu : 1);
+    }
+    const int blocks = (int)(total < slots ? total : slots);
+    hipLaunchKernelGGL((conv_f32_pf_kernel<NT, RW, KS, CC, NCG, PADZ>), dim3(blocks), dim3(256), smem, stream, a, tiles_hi,
+                       tiles_lo > 0 ? tiles_lo : 1, rem, nblocks, gx, gy, (int)total);
+    return hipGetLastError();
+}
+
+template <int NT, int RW, int KS, int CC, int NCG>
+static hipError_t launch_conv_f32_pf_t(const ConvF32Args &a, hipStream_t stream)
+{
+    if (a.in_off != 0) return launch_conv_f32_pf_z<NT, RW, KS, CC, NCG, true>(a, stream);
+    return launch_conv_f32_pf_z<NT, RW, KS, CC, NCG, false>(a, stream);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Direct-to-LDS variant for convolutions that need no zero padding (in_off = 0: every forward
+// convolution) and whose packed weights are exactly NT*16 columns wide.  The input rows and the
+// weight slab of a K chunk go from global memory straight into LDS (global_load_lds: lane l's
+// 4 or 16 bytes land at base + 4l or 16l), into one of two stages, while the other stage is being
+// multiplied.  No staging registers and no LDS-write instructions, so the kernel needs few enough
+// registers for five workgroups per CU, and the only instructions outside the MFMA loop are the
+// handful of loads each wave issues per chunk and one barrier.
+// Tile: 4 output rows that lie d apart x 64 columns x NT*16 maps, one row per wave; chunk = CC maps.
+template <int NT, int KS, int CC>
+__global__ __launch_bounds__(256, NT <= 3 ? 5 : 3) void conv_f32_dl_kernel(ConvF32Args a, int tiles_hi, int tiles_lo, int rem)
+{
+    extern __shared__ float smem[];
+    constexpr int R = 4, WN = NT * 16, RR = R + KS - 1, KK2 = KS * KS, KC = CC * KK2, PITCH = 128, NCG = 2;
+    constexpr int XS = CC * RR * PITCH, WS = KC * WN, STAGE = XS + WS;   // floats
+    constexpr int ROWU = CC * RR * NCG / 4;      // row loads (64 floats each) per wave and chunk
+    constexpr int WUNITS = WS * 4 / 1024;        // weight loads (1 KB each) per workgroup and chunk
+    constexpr int WU = (WUNITS + 3) / 4;         // ... per wave (the last one may be absent)
+    static_assert(CC * RR * NCG % 4 == 0, "row loads must divide evenly over the four waves");
+    static_assert(WS * 4 % 1024 == 0, "the weight slab of a chunk must be whole kilobytes");
+    static_assert(KK2 % 4 == 0, "a map's taps must fill whole K steps");
+
+    const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, g = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int d = a.d;
     int py, ty;
     {
         const int by = blockIdx.y;
@@ -251,156 +497,113 @@ __global__ __launch_bounds__(256) void conv_f32_pf_kernel(ConvF32Args a, int til
             ty = b2 % tiles_lo;
         }
     }
-    const int b = blockIdx.z / nblocks, nb = blockIdx.z - b * nblocks;
+    const int b = blockIdx.z;
     const int x0 = blockIdx.x * CONV_TX;
-
-    // LDS offset of K index (c, i, j) inside the staged tile, for the K values this lane group
-    // supplies in each of the KC/4 steps of a chunk; the same for every chunk, so kept in registers
-    int kreg[KC / 4];
-#pragma unroll
-    for (int sidx = 0; sidx < KC / 4; ++sidx) {
-        const int q = 4 * sidx + g;
-        const int c = q / KK2, r = q - c * KK2;
-        const int i = r / KS, j = r - i * KS;
-        kreg[sidx] = (c * RR + i) * PITCH + j * d + wave * RW * PITCH + l16;
-    }
-
-    floatx4 acc[RW][4][NT];
-#pragma unroll
-    for (int rw = 0; rw < RW; ++rw)
-#pragma unroll
-        for (int xt = 0; xt < 4; ++xt)
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) acc[rw][xt][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
-
     const long plane = (long)a.H * a.W;
     const float *xb = a.x + (long)b * a.c_in * plane;
-    const int c_pad = (a.c_in + CC - 1) / CC * CC;
-    const int gy0 = py + d * (ty * R) - a.in_off;       // input row of tile row 0
-    const int gx0 = x0 - a.in_off + lane;                // input column of this lane, column group 0
+    const int nchunks = (a.c_in + CC - 1) / CC;
+    const int gy0 = py + d * (ty * R);
 
-    float xr[CPW][RR][NCG];
-    floatx4 wr[WV4];
-
-    // Loads are unconditional (addresses clamped into the tensor) so that they can stay in flight
-    // across the MFMA loop; what lies outside the image or beyond the last map is replaced by zero
-    // when the registers are written to LDS.
-    int gxc[NCG];
-    bool colok[NCG];
+    // Row load i of this wave: unit u = wave + 4i -> column group u % 2 (the same for every i),
+    // staged row (u / 2) % RR of chunk-local map (u / 2) / RR.  Addresses are clamped into the
+    // tensor: a clamped row or column only feeds outputs that are never stored, a clamped map meets
+    // zero weights (activations are finite by contract).
+    const int cg = wave & 1;
+    const int gx = x0 + lane + 64 * cg;
+    const unsigned coff = 4u * (unsigned)(gx < a.W ? gx : a.W - 1);
+    int row_map[ROWU], row_off[ROWU], row_lds[ROWU];
 #pragma unroll
-    for (int cg = 0; cg < NCG; ++cg) {
-        const int gx = gx0 + 64 * cg;
-        colok[cg] = gx >= 0 && gx < a.W && lane + 64 * cg < PW;
-        gxc[cg] = gx < 0 ? 0 : (gx >= a.W ? a.W - 1 : gx);
+    for (int i = 0; i < ROWU; ++i) {
+        const int rt = (wave >> 1) + 2 * i;
+        const int cl = rt / RR, t = rt - cl * RR;
+        const int gy = gy0 + t * d;
+        row_map[i] = cl;
+        row_off[i] = (gy < a.H ? gy : a.H - 1) * a.W;
+        row_lds[i] = rt * PITCH + 64 * cg;
     }
-    auto prefetch = [&](int c0) {
+    auto issue = [&](int chunk, int stage) {
+        float *dst = smem + stage * STAGE;
 #pragma unroll
-        for (int cw = 0; cw < CPW; ++cw) {
-            int c = c0 + wave + 4 * cw;
+        for (int i = 0; i < ROWU; ++i) {
+            int c = chunk * CC + row_map[i];
             c = c < a.c_in ? c : a.c_in - 1;
-            const float *src = xb + (long)c * plane;
-#pragma unroll
-            for (int t = 0; t < RR; ++t) {
-                int gy = gy0 + t * d;
-                gy = gy < 0 ? 0 : (gy >= a.H ? a.H - 1 : gy);
-                const float *row = src + (long)gy * a.W;
-#pragma unroll
-                for (int cg = 0; cg < NCG; ++cg) xr[cw][t][cg] = row[gxc[cg]];
-            }
+            const char *row = reinterpret_cast<const char *>(xb + (long)c * plane + row_off[i]);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(row + coff),
+                                             (__attribute__((address_space(3))) void *)(dst + row_lds[i]), 4, 0, 0);
         }
+        const char *slab = reinterpret_cast<const char *>(a.wp + (long)chunk * WS);
 #pragma unroll
-        for (int u = 0; u < WV4; ++u) {
-            int q = tid + 256 * u;               // float4 index inside the [KC][WN] slab
-            q = q < KC * WN / 4 ? q : KC * WN / 4 - 1;
-            const int r = q / (WN / 4), cn = (q - r * (WN / 4)) * 4;
-            int col = nb * WN + cn;
-            col = col < a.n_pad ? col : a.n_pad - 4;
-            wr[u] = *reinterpret_cast<const floatx4 *>(a.wp + (long)(c0 * KK2 + r) * a.n_pad + col);
-        }
-    };
-    auto commit = [&](int c0) {
-#pragma unroll
-        for (int cw = 0; cw < CPW; ++cw) {
-            const bool cok = c0 + wave + 4 * cw < a.c_in;
-#pragma unroll
-            for (int t = 0; t < RR; ++t) {
-                const int gy = gy0 + t * d;
-                const bool rowok = cok && gy >= 0 && gy < a.H;
-#pragma unroll
-                for (int cg = 0; cg < NCG; ++cg)
-                    if (lane + 64 * cg < PW)
-                        xs[((wave + 4 * cw) * RR + t) * PITCH + lane + 64 * cg] = (rowok && colok[cg]) ? xr[cw][t][cg] : 0.f;
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < WV4; ++u) {
-            const int q = tid + 256 * u;
-            if (q < KC * WN / 4) {
-                const int r = q / (WN / 4), cn = (q - r * (WN / 4)) * 4;
-                const bool ok = nb * WN + cn < a.n_pad;
-                *reinterpret_cast<floatx4 *>(ws + 4 * q) = ok ? wr[u] : floatx4{0.f, 0.f, 0.f, 0.f};
-            }
+        for (int u = 0; u < WU; ++u) {
+            const int blk = wave + 4 * u;
+            if (blk < WUNITS)                                   // uniform
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(slab + (unsigned)(blk * 1024 + lane * 16)),
+                                                 (__attribute__((address_space(3))) void *)(dst + XS + blk * 256), 16, 0, 0);
         }
     };
 
-    prefetch(0);
-    for (int c0 = 0; c0 < c_pad; c0 += CC) {
-        __syncthreads();
-        commit(c0);
-        __syncthreads();
-        if (c0 + CC < c_pad) prefetch(c0 + CC);
-        // K loop with the operand fragments of step kk+4 fetched from LDS while the MFMAs of step kk run
-        float av[2][NT], bv[2][RW][4];
-        auto fetch = [&](int kk, int buf) {
-            const int ko = kreg[kk >> 2];
+    floatx4 acc[1][4][NT];
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) av[buf][nt] = ws[(kk + g) * WN + nt * 16 + l16];
+    for (int xt = 0; xt < 4; ++xt)
 #pragma unroll
-            for (int rw = 0; rw < RW; ++rw)
+        for (int nt = 0; nt < NT; ++nt) acc[0][xt][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    const int kthread = g * d + wave * PITCH + l16;      // KS*KS % 4 == 0: lane group g holds tap column g % KS of tap row g / KS
+    const int klane = (g / KS) * PITCH + (g % KS) * d - g * d;
+    issue(0, 0);
+    for (int chunk = 0; chunk < nchunks; ++chunk) {
+        // this wave's loads of the chunk have landed; after the barrier so have everybody's, and
+        // every wave is done reading the other stage
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        asm volatile("s_barrier" ::: "memory");
+        if (chunk + 1 < nchunks) issue(chunk + 1, (chunk + 1) & 1);
+        const float *xs = smem + (chunk & 1) * STAGE;
+        const float *ws = xs + XS;
+        float av[2][NT], bv[2][4];
+        auto fetch = [&](int sidx, int buf) {
+            const int ko = kthread + klane + ((4 * sidx / KK2) * RR + (4 * sidx % KK2) / KS) * PITCH;
 #pragma unroll
-                for (int xt = 0; xt < 4; ++xt) bv[buf][rw][xt] = xs[ko + rw * PITCH + xt * 16];
+            for (int nt = 0; nt < NT; ++nt) av[buf][nt] = ws[(4 * sidx + g) * WN + nt * 16 + l16];
+#pragma unroll
+            for (int xt = 0; xt < 4; ++xt) bv[buf][xt] = xs[ko + xt * 16];
         };
         fetch(0, 0);
 #pragma unroll
-        for (int kk = 0; kk < KC; kk += 4) {
-            const int cur = (kk >> 2) & 1;
-            if (kk + 4 < KC) fetch(kk + 4, cur ^ 1);
+        for (int sidx = 0; sidx < KC / 4; ++sidx) {
+            const int cur = sidx & 1;
+            if (sidx + 1 < KC / 4) fetch(sidx + 1, cur ^ 1);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int rw = 0; rw < RW; ++rw)
+            for (int xt = 0; xt < 4; ++xt)
 #pragma unroll
-                for (int xt = 0; xt < 4; ++xt)
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt)
-                        acc[rw][xt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[cur][nt], bv[cur][rw][xt], acc[rw][xt][nt], 0, 0, 0);
+                for (int nt = 0; nt < NT; ++nt)
+                    acc[0][xt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[cur][nt], bv[cur][xt], acc[0][xt][nt], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
-
-    store_outputs<NT, RW>(a, acc, b, nb * WN + 4 * g, py + d * (ty * R + wave * RW), d, x0 + l16);
+    store_outputs<NT, 1>(a, acc, b, 4 * g, py + d * (ty * R + wave), d, x0 + l16);
 }
 
-template <int NT, int RW, int KS, int CC, int NCG>
-static hipError_t launch_conv_f32_pf_t(const ConvF32Args &a, hipStream_t stream)
+template <int NT, int KS, int CC>
+static hipError_t launch_conv_f32_dl_t(const ConvF32Args &a, hipStream_t stream)
 {
-    constexpr int R = 4 * RW, WN = NT * 16, RR = R + KS - 1, KC = CC * KS * KS;
-    const int PW = CONV_TX + (KS - 1) * a.d;
-    const size_t smem = sizeof(float) * ((size_t)CC * RR * PW + (size_t)KC * WN) + sizeof(int) * KC;
-    if (smem > 150 * 1024) return hipErrorInvalidValue;
-    static bool attr_set = false;
-    if (smem > 48 * 1024 && !attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_f32_pf_kernel<NT, RW, KS, CC, NCG>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    constexpr int R = 4, WN = NT * 16, RR = R + KS - 1, KC = CC * KS * KS, PITCH = 128;
+    constexpr size_t smem = sizeof(float) * 2 * ((size_t)CC * RR * PITCH + (size_t)KC * WN);
+    static_assert(smem <= 48 * 1024, "two stages must fit the default LDS limit");
     const int q = a.Ho / a.d, rem = a.Ho % a.d;
     const int tiles_hi = (q + 1 + R - 1) / R, tiles_lo = (q + R - 1) / R;
     const int gy = rem * tiles_hi + (a.d - rem) * tiles_lo;
-    const int nblocks = (a.n_pad / 16 + NT - 1) / NT;
-    dim3 grid((a.Wo + CONV_TX - 1) / CONV_TX, gy, a.n * nblocks);
+    dim3 grid((a.Wo + CONV_TX - 1) / CONV_TX, gy, a.n);
     if (grid.x == 0 || gy <= 0 || grid.z == 0 || gy > 65535 || grid.z > 65535) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((conv_f32_pf_kernel<NT, RW, KS, CC, NCG>), grid, dim3(256), smem, stream, a, tiles_hi,
-                       tiles_lo > 0 ? tiles_lo : 1, rem, nblocks);
+    hipLaunchKernelGGL((conv_f32_dl_kernel<NT, KS, CC>), grid, dim3(256), smem, stream, a, tiles_hi,
+                       tiles_lo > 0 ? tiles_lo : 1, rem);
     return hipGetLastError();
+}
+
+// true if the direct-to-LDS kernel covers this convolution
+static bool conv_f32_dl_ok(const ConvF32Args &a, int nt)
+{
+    return a.k == 4 && a.in_off == 0 && a.n_pad == nt * 16 && CONV_TX + 3 * a.d <= 128 &&
+           (long)a.H * a.W < (1L << 29) && a.Ho == a.H - 3 * a.d && a.Wo == a.W - 3 * a.d;
 }
 
 template <int NT>
