@@ -460,152 +460,6 @@ static hipError_t launch_conv_f32_pf_t(const ConvF32Args &a, hipStream_t stream)
     return launch_conv_f32_pf_z<NT, RW, KS, CC, NCG, false>(a, stream);
 }
 
-// ------------------------------------------------------------------------------------------------
-// Direct-to-LDS variant for convolutions that need no zero padding (in_off = 0: every forward
-// convolution) and whose packed weights are exactly NT*16 columns wide.  The input rows and the
-// weight slab of a K chunk go from global memory straight into LDS (global_load_lds: lane l's
-// 4 or 16 bytes land at base + 4l or 16l), into one of two stages, while the other stage is being
-// multiplied.  No staging registers and no LDS-write instructions, so the kernel needs few enough
-// registers for five workgroups per CU, and the only instructions outside the MFMA loop are the
-// handful of loads each wave issues per chunk and one barrier.
-// Tile: 4 output rows that lie d apart x 64 columns x NT*16 maps, one row per wave; chunk = CC maps.
-template <int NT, int KS, int CC>
-__global__ __launch_bounds__(256, NT <= 3 ? 5 : 3) void conv_f32_dl_kernel(ConvF32Args a, int tiles_hi, int tiles_lo, int rem)
-{
-    extern __shared__ float smem[];
-    constexpr int R = 4, WN = NT * 16, RR = R + KS - 1, KK2 = KS * KS, KC = CC * KK2, PITCH = 128, NCG = 2;
-    constexpr int XS = CC * RR * PITCH, WS = KC * WN, STAGE = XS + WS;   // floats
-    constexpr int ROWU = CC * RR * NCG / 4;      // row loads (64 floats each) per wave and chunk
-    constexpr int WUNITS = WS * 4 / 1024;        // weight loads (1 KB each) per workgroup and chunk
-    constexpr int WU = (WUNITS + 3) / 4;         // ... per wave (the last one may be absent)
-    static_assert(CC * RR * NCG % 4 == 0, "row loads must divide evenly over the four waves");
-    static_assert(WS * 4 % 1024 == 0, "the weight slab of a chunk must be whole kilobytes");
-    static_assert(KK2 % 4 == 0, "a map's taps must fill whole K steps");
-
-    const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, g = lane >> 4;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int d = a.d;
-    int py, ty;
-    {
-        const int by = blockIdx.y;
-        if (by < rem * tiles_hi) {
-            py = by / tiles_hi;
-            ty = by - py * tiles_hi;
-        } else {
-            const int b2 = by - rem * tiles_hi;
-            py = rem + b2 / tiles_lo;
-            ty = b2 % tiles_lo;
-        }
-    }
-    const int b = blockIdx.z;
-    const int x0 = blockIdx.x * CONV_TX;
-    const long plane = (long)a.H * a.W;
-    const float *xb = a.x + (long)b * a.c_in * plane;
-    const int nchunks = (a.c_in + CC - 1) / CC;
-    const int gy0 = py + d * (ty * R);
-
-    // Row load i of this wave: unit u = wave + 4i -> column group u % 2 (the same for every i),
-    // staged row (u / 2) % RR of chunk-local map (u / 2) / RR.  Addresses are clamped into the
-    // tensor: a clamped row or column only feeds outputs that are never stored, a clamped map meets
-    // zero weights (activations are finite by contract).
-    const int cg = wave & 1;
-    const int gx = x0 + lane + 64 * cg;
-    const unsigned coff = 4u * (unsigned)(gx < a.W ? gx : a.W - 1);
-    int row_map[ROWU], row_off[ROWU], row_lds[ROWU];
-#pragma unroll
-    for (int i = 0; i < ROWU; ++i) {
-        const int rt = (wave >> 1) + 2 * i;
-        const int cl = rt / RR, t = rt - cl * RR;
-        const int gy = gy0 + t * d;
-        row_map[i] = cl;
-        row_off[i] = (gy < a.H ? gy : a.H - 1) * a.W;
-        row_lds[i] = rt * PITCH + 64 * cg;
-    }
-    auto issue = [&](int chunk, int stage) {
-        float *dst = smem + stage * STAGE;
-#pragma unroll
-        for (int i = 0; i < ROWU; ++i) {
-            int c = chunk * CC + row_map[i];
-            c = c < a.c_in ? c : a.c_in - 1;
-            const char *row = reinterpret_cast<const char *>(xb + (long)c * plane + row_off[i]);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(row + coff),
-                                             (__attribute__((address_space(3))) void *)(dst + row_lds[i]), 4, 0, 0);
-        }
-        const char *slab = reinterpret_cast<const char *>(a.wp + (long)chunk * WS);
-#pragma unroll
-        for (int u = 0; u < WU; ++u) {
-            const int blk = wave + 4 * u;
-            if (blk < WUNITS)                                   // uniform
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(slab + (unsigned)(blk * 1024 + lane * 16)),
-                                                 (__attribute__((address_space(3))) void *)(dst + XS + blk * 256), 16, 0, 0);
-        }
-    };
-
-    floatx4 acc[1][4][NT];
-#pragma unroll
-    for (int xt = 0; xt < 4; ++xt)
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) acc[0][xt][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
-
-    const int kthread = g * d + wave * PITCH + l16;      // KS*KS % 4 == 0: lane group g holds tap column g % KS of tap row g / KS
-    const int klane = (g / KS) * PITCH + (g % KS) * d - g * d;
-    issue(0, 0);
-    for (int chunk = 0; chunk < nchunks; ++chunk) {
-        // this wave's loads of the chunk have landed; after the barrier so have everybody's, and
-        // every wave is done reading the other stage
-        __builtin_amdgcn_s_waitcnt(0x0F70);
-        asm volatile("s_barrier" ::: "memory");
-        if (chunk + 1 < nchunks) issue(chunk + 1, (chunk + 1) & 1);
-        const float *xs = smem + (chunk & 1) * STAGE;
-        const float *ws = xs + XS;
-        float av[2][NT], bv[2][4];
-        auto fetch = [&](int sidx, int buf) {
-            const int ko = kthread + klane + ((4 * sidx / KK2) * RR + (4 * sidx % KK2) / KS) * PITCH;
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) av[buf][nt] = ws[(4 * sidx + g) * WN + nt * 16 + l16];
-#pragma unroll
-            for (int xt = 0; xt < 4; ++xt) bv[buf][xt] = xs[ko + xt * 16];
-        };
-        fetch(0, 0);
-#pragma unroll
-        for (int sidx = 0; sidx < KC / 4; ++sidx) {
-            const int cur = sidx & 1;
-            if (sidx + 1 < KC / 4) fetch(sidx + 1, cur ^ 1);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int xt = 0; xt < 4; ++xt)
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt)
-                    acc[0][xt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[cur][nt], bv[cur][xt], acc[0][xt][nt], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    }
-    store_outputs<NT, 1>(a, acc, b, 4 * g, py + d * (ty * R + wave), d, x0 + l16);
-}
-
-template <int NT, int KS, int CC>
-static hipError_t launch_conv_f32_dl_t(const ConvF32Args &a, hipStream_t stream)
-{
-    constexpr int R = 4, WN = NT * 16, RR = R + KS - 1, KC = CC * KS * KS, PITCH = 128;
-    constexpr size_t smem = sizeof(float) * 2 * ((size_t)CC * RR * PITCH + (size_t)KC * WN);
-    static_assert(smem <= 48 * 1024, "two stages must fit the default LDS limit");
-    const int q = a.Ho / a.d, rem = a.Ho % a.d;
-    const int tiles_hi = (q + 1 + R - 1) / R, tiles_lo = (q + R - 1) / R;
-    const int gy = rem * tiles_hi + (a.d - rem) * tiles_lo;
-    dim3 grid((a.Wo + CONV_TX - 1) / CONV_TX, gy, a.n);
-    if (grid.x == 0 || gy <= 0 || grid.z == 0 || gy > 65535 || grid.z > 65535) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((conv_f32_dl_kernel<NT, KS, CC>), grid, dim3(256), smem, stream, a, tiles_hi,
-                       tiles_lo > 0 ? tiles_lo : 1, rem);
-    return hipGetLastError();
-}
-
-// true if the direct-to-LDS kernel covers this convolution
-static bool conv_f32_dl_ok(const ConvF32Args &a, int nt)
-{
-    return a.k == 4 && a.in_off == 0 && a.n_pad == nt * 16 && CONV_TX + 3 * a.d <= 128 &&
-           (long)a.H * a.W < (1L << 29) && a.Ho == a.H - 3 * a.d && a.Wo == a.W - 3 * a.d;
-}
-
 template <int NT>
 static hipError_t launch_conv_f32_nt(const ConvF32Args &a, hipStream_t stream)
 {
