@@ -270,9 +270,16 @@ __global__ __launch_bounds__(256) void conv_f32_pf_kernel(ConvF32Args a, int til
     const int kthread = wave * RW * PITCH + l16;
 
     // Persistent workgroups: the grid holds as many workgroups as fit on the GPU at once and each
-    // walks over tiles tile, tile + gridDim.x, ...; a tail of tiles then runs on workgroups that are
-    // spread over all CUs instead of as a second, mostly empty wave of fresh workgroups.
-    for (int tile = blockIdx.x; tile < total_tiles; tile += gridDim.x) {
+    // walks over several tiles; a tail of tiles then runs on workgroups that are spread over all CUs
+    // instead of as a second, mostly empty wave of fresh workgroups.
+    // Workgroup w runs on XCD w % 8 (round-robin dispatch), and each XCD has an L2 of its own, so
+    // every XCD takes one contiguous eighth of the tile list: tiles that share input rows then share
+    // an L2 instead of each XCD fetching every row.
+    const int xcds = (gridDim.x & 7) == 0 ? 8 : 1;
+    const int xcd = blockIdx.x % xcds, per_xcd = (total_tiles + xcds - 1) / xcds;
+    for (int q = blockIdx.x / xcds; q < per_xcd; q += gridDim.x / xcds) {
+    const int tile = xcd * per_xcd + q;
+    if (tile >= total_tiles) break;
     const int bx = tile % gx, byz = tile / gx;
     const int by = byz % gy, bz = byz / gy;
     int py, ty;
