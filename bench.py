@@ -23,6 +23,13 @@ sys.path.insert(0, ROOT)
 PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0, "f16": 2500.0}   # MI355X dense MFMA peaks
 HBM_PEAK_GBS = 8000.0
 METRIC = "labelled pixels/sec SK-Net fwd (and fwd+bwd) 1 GPU; conv % MFMA peak"
+# Bytes moved beyond L2 per launch of the dominant kernel (average of its three launches per pass),
+# from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by what the same counters
+# read for stream_copy_kernel on 1 GiB (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); the runs and their
+# figures are in profiles/sknet_c{2,3}_forward_hbm_traffic_pmc.txt and
+# profiles/stream_copy_1gib_pmc_calibration.txt.  KiB: (fetch x 2, write).
+TRAFFIC_KIB = {"c2": (2.0 * (35732.9 + 34228.8 + 30794.4) / 3, (78159.3 + 70656.6 + 58114.7) / 3),
+               "c3": (2.0 * (482197.5 + 475659.7 + 456620.1) / 3, (865863.4 + 843289.0 + 798768.0) / 3)}
 
 
 def build_net(B, S, dtype, n, H, W, training):
@@ -59,6 +66,7 @@ def measure_forward(torch, B, S, dtype, n, H, W, steps, warmup, first_seed, kern
     shapes = net.infer_shapes(H, W)
     esize = 4 if dtype == "f32" else 2
     step_ms, conv_flops, conv_ms, total_flops = {}, 0.0, 0.0, 0.0
+    conv_bytes, conv_launches = 0.0, 0
     pool_bytes, pool_ms = 0.0, 0.0
     f_in = 1
     for step in range(net.num_steps()):
@@ -73,6 +81,9 @@ def measure_forward(torch, B, S, dtype, n, H, W, steps, warmup, first_seed, kern
                 if f_in == 48 and l["f_out"] == 48:      # the dominant kernel: 48 -> 48, k4, dilated
                     conv_flops += fl
                     conv_ms += ms
+                    hi, wi = shapes[step - 1][1:]
+                    conv_bytes += esize * n * 48.0 * (hi * wi + ho * wo)   # every input and output element once
+                    conv_launches += 1
                 f_in = l["f_out"]
             else:                                         # pool: one element read + one written
                 pool_bytes += 2.0 * esize * n * c * ho * wo
@@ -80,7 +91,7 @@ def measure_forward(torch, B, S, dtype, n, H, W, steps, warmup, first_seed, kern
     res = {
         "ms_per_step": ms_per_step, "pixels_per_s": n * H * W * steps / dt, "step_ms": step_ms,
         "conv_tflops": conv_flops / (conv_ms * 1e-3) / 1e12, "forward_tflops": total_flops / (ms_per_step * 1e-3) / 1e12,
-        "pool_gbs": pool_bytes / (pool_ms * 1e-3) / 1e9, "layers": layers, "ws": ws, "bs": bs, "img": img,
+        "pool_gbs": pool_bytes / (pool_ms * 1e-3) / 1e9, "conv_alg_bytes": conv_bytes / max(conv_launches, 1), "layers": layers, "ws": ws, "bs": bs, "img": img,
     }
     net.close()
     return res
@@ -167,7 +178,10 @@ def main():
                                    % (n, H, H, "fp32" if dtype == "f32" else dtype, net_desc, 1 if args.workload == "c2" else 2),
                        "global_batch": n, "parallelism": "single GPU"},
             "roofline": {"bound": "mfma", "achieved": round(r["conv_tflops"], 2), "peak": peak, "unit": "TFLOP/s",
-                         "frac": round(r["conv_tflops"] / peak, 4), "traffic": None,
+                         "frac": round(r["conv_tflops"] / peak, 4),
+                         "traffic": int(sum(TRAFFIC_KIB[args.workload]) * 1024),
+                         "traffic_unit": "bytes beyond L2 per launch (read + written), from profiles/",
+                         "algorithmic_bytes": int(r["conv_alg_bytes"]),
                          "kernel": "48->48 k4 SK convolutions at d=2,4,8 (%s)"
                                    % ("conv_f32_pf_kernel<3,1,4,4,2,false>" if dtype == "f32" else "conv_h_ring_kernel<bf16,4,3,MAP4,8,false,3,true>")},
             "forward_tflops": round(r["forward_tflops"], 2),
