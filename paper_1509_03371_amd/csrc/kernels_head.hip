@@ -20,6 +20,9 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
 typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 halfx2 __attribute__((ext_vector_type(2)));
 
 constexpr int HEAD_THREADS = 256;
 constexpr int HEAD_MAX_CLASSES = 8;
@@ -166,6 +169,178 @@ __global__ __launch_bounds__(HEAD_THREADS, 2) void head_fused_kernel(HeadArgs a)
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// 16-bit head with both products on MFMA 16x16x32.  The accumulator of the first product gives lane
+// (g, l16) the hidden maps 4g..4g+3 of a 16-map tile for pixel l16; two such tiles, ReLU'd and
+// rounded to the storage type, are exactly one lane's share (8 K values) of the B operand of a
+// second MFMA whose K index runs over the 32 hidden maps of the tile pair in the order
+// [tile 2p: 4g..4g+3 | tile 2p+1: 4g..4g+3] -- the W2 fragments are packed in that order, so the
+// second product needs no shuffle and costs 3 VALU instructions per two hidden values (max, max,
+// pack) instead of bias + max + a multiply-add per class.  b1 and b2 enter as the initial value of
+// the accumulators.  Rounding h to the storage type is what the unfused path does when it stores
+// the hidden layer.  Hidden tiles are processed in groups of at most GT so that four pixel tiles
+// (64 pixels) share each W1 fragment read from LDS; the pixels of the next pass are loaded while
+// the current one is multiplied.
+template <int DT, int HT, int KSTEPS>
+__global__ __launch_bounds__(HEAD_THREADS, 2) void head_fused_h_kernel(HeadArgs a)
+{
+    extern __shared__ float smem[];
+    constexpr int NTP = 4, GT = 6, HP = (HT + 1) / 2;   // GT even: tile pairs never straddle two groups
+    uint4v *w1 = reinterpret_cast<uint4v *>(smem);               // [HT][KSTEPS][64]
+    uint4v *w2f = w1 + HT * KSTEPS * 64;                         // [HP][64]
+    float *b1 = reinterpret_cast<float *>(w2f + HP * 64);        // [HT*16]
+    float *b2 = b1 + HT * 16;                                    // [4]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l16 = lane & 15, g = lane >> 4;
+
+    for (int q = tid; q < HT * KSTEPS * 64; q += HEAD_THREADS) w1[q] = static_cast<const uint4v *>(a.w1p)[q];
+    for (int q = tid; q < HP * 64; q += HEAD_THREADS) {
+        const int pr = q >> 6, ln = q & 63, cls = ln & 15, gg = ln >> 4;
+        unsigned short v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int h = 16 * (2 * pr + (e >> 2)) + 4 * gg + (e & 3);
+            const float f = (cls < a.classes && h < a.hidden) ? a.w2[cls * a.hidden + h] : 0.f;
+            if constexpr (DT == 1) v[e] = __builtin_bit_cast(unsigned short, static_cast<__bf16>(f));
+            else v[e] = __builtin_bit_cast(unsigned short, static_cast<_Float16>(f));
+        }
+        w2f[q] = uint4v{v[0] | ((unsigned)v[1] << 16), v[2] | ((unsigned)v[3] << 16), v[4] | ((unsigned)v[5] << 16), v[6] | ((unsigned)v[7] << 16)};
+    }
+    for (int q = tid; q < HT * 16; q += HEAD_THREADS) b1[q] = q < a.hidden ? a.b1[q] : 0.f;
+    if (tid < 4) b2[tid] = tid < a.classes ? a.b2[tid] : 0.f;
+    __syncthreads();
+
+    const int plane = a.H * a.W, total = a.n * plane;          // fit 32 bits (checked by the launcher)
+    const int groups = (total + 16 * NTP - 1) / (16 * NTP);
+    const int wave_id = blockIdx.x * (HEAD_THREADS / 64) + wave, wave_cnt = gridDim.x * (HEAD_THREADS / 64);
+    const int c8 = (a.c_in + 7) / 8;
+    const uint4v *xin = static_cast<const uint4v *>(a.x);
+
+    // one division per pass: pixel tile pt + 1 starts 16 pixels after tile pt and may wrap into the
+    // following image(s)
+    auto load_pixels = [&](int grp, uint4v (&bv)[KSTEPS][NTP]) {
+        int p = grp * (16 * NTP) + l16;
+        p = p < total ? p : total - 1;
+        int img = p / plane, pix = p - img * plane;
+#pragma unroll
+        for (int pt = 0; pt < NTP; ++pt) {
+            const long base = (long)img * c8 * plane + pix;
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ++ks) {
+                const int o = ks * 4 + g;
+                const uint4v v = xin[base + (long)(o < c8 ? o : c8 - 1) * plane];
+                bv[ks][pt] = o < c8 ? v : uint4v{0u, 0u, 0u, 0u};
+            }
+            pix += 16;                                           // next tile; clamp at the very end
+            while (pix >= plane && img + 1 < a.n) { pix -= plane; ++img; }
+            if (pix >= plane) pix = plane - 1;
+        }
+    };
+    auto mfma = [](uint4v av, uint4v bvv, floatx4 c) {
+        if constexpr (DT == 1) return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av), __builtin_bit_cast(bf16x8, bvv), c, 0, 0, 0);
+        else return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(halfx8, av), __builtin_bit_cast(halfx8, bvv), c, 0, 0, 0);
+    };
+    // ReLU as a signed-integer max on the bit pattern (negative floats, -0 included, are negative
+    // integers; one instruction, where fmaxf costs a NaN canonicalisation besides the max), then
+    // both values are rounded to the storage type by one packed conversion
+    auto pack2 = [](float lo, float hi) -> unsigned {
+        const floatx2 r = {__int_as_float(max(__float_as_int(lo), 0)), __int_as_float(max(__float_as_int(hi), 0))};
+        if constexpr (DT == 1) return __builtin_bit_cast(unsigned, __builtin_convertvector(r, bf16x2));
+        else return __builtin_bit_cast(unsigned, __builtin_convertvector(r, halfx2));
+    };
+
+    uint4v bv[KSTEPS][NTP], nx[KSTEPS][NTP];
+    if (wave_id < groups) load_pixels(wave_id, bv);
+    for (int grp = wave_id; grp < groups; grp += wave_cnt) {
+        const int nxt = grp + wave_cnt;
+        load_pixels(nxt < groups ? nxt : grp, nx);               // in flight during this pass
+        floatx4 z[NTP];
+        {
+            const floatx4 zb = g == 0 ? *reinterpret_cast<const floatx4 *>(b2) : floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int pt = 0; pt < NTP; ++pt) z[pt] = zb;
+        }
+#pragma unroll
+        for (int t0 = 0; t0 < HT; t0 += GT) {
+            const int nt = HT - t0 < GT ? HT - t0 : GT;           // compile-time after unrolling
+            floatx4 acc[GT][NTP];
+#pragma unroll
+            for (int t = 0; t < GT; ++t) {
+                if (t >= nt) break;
+                const floatx4 bb = *reinterpret_cast<const floatx4 *>(b1 + (t0 + t) * 16 + 4 * g);
+#pragma unroll
+                for (int pt = 0; pt < NTP; ++pt) acc[t][pt] = bb;
+            }
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ++ks)
+#pragma unroll
+                for (int t = 0; t < GT; ++t) {
+                    if (t >= nt) break;
+                    const uint4v av = w1[((t0 + t) * KSTEPS + ks) * 64 + lane];
+#pragma unroll
+                    for (int pt = 0; pt < NTP; ++pt) acc[t][pt] = mfma(av, bv[ks][pt], acc[t][pt]);
+                    // keep the LDS reads of later tiles from being hoisted (they would spill)
+                    if (t % 2 == 1) __builtin_amdgcn_sched_barrier(0);
+                }
+#pragma unroll
+            for (int t = 0; t < GT; t += 2) {
+                if (t >= nt) break;
+                const uint4v wv = w2f[((t0 + t) >> 1) * 64 + lane];
+                const bool two = t + 1 < nt;
+#pragma unroll
+                for (int pt = 0; pt < NTP; ++pt) {
+                    uint4v hb;
+                    hb[0] = pack2(acc[t][pt][0], acc[t][pt][1]);
+                    hb[1] = pack2(acc[t][pt][2], acc[t][pt][3]);
+                    hb[2] = two ? pack2(acc[t + 1 < GT ? t + 1 : t][pt][0], acc[t + 1 < GT ? t + 1 : t][pt][1]) : 0u;
+                    hb[3] = two ? pack2(acc[t + 1 < GT ? t + 1 : t][pt][2], acc[t + 1 < GT ? t + 1 : t][pt][3]) : 0u;
+                    z[pt] = mfma(wv, hb, z[pt]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        // Classes 0..3 of pixel (pt, l16) sit in lane (0, l16) of z[pt].  Lane (g, l16) fetches those
+        // of pixel tile pt = g, so that all 64 lanes do one softmax each and a store instruction
+        // writes 64 consecutive pixels of one class.
+        {
+            float zc[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                zc[c] = 0.f;
+                if (c < a.classes) {                              // uniform
+#pragma unroll
+                    for (int pt = 0; pt < NTP; ++pt) {
+                        const float v = __shfl(z[pt][c], l16, 64);
+                        if (g == pt) zc[c] = v;
+                    }
+                }
+            }
+            const int p = grp * (16 * NTP) + lane;
+            if (p < total) {
+                const int img = p / plane, pix = p - img * plane;
+                float m = zc[0];
+#pragma unroll
+                for (int c = 1; c < 4; ++c)
+                    if (c < a.classes) m = fmaxf(m, zc[c]);
+                float e[4], sum = 0.f;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    e[c] = c < a.classes ? __expf(zc[c] - m) : 0.f;
+                    sum += e[c];
+                }
+                const float inv = __frcp_rn(sum);
+                float *dst = a.prob + (long)img * a.classes * plane + pix;
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (c < a.classes) dst[(long)c * plane] = e[c] * inv;
+            }
+        }
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks)
+#pragma unroll
+            for (int pt = 0; pt < NTP; ++pt) bv[ks][pt] = nx[ks][pt];
+    }
+}
+
 // W1 [hidden][c_in] fp32 -> MFMA A fragments, [hidden tile][K step][lane][values]:
 //   DT = 0: value            = W1[16*mt + l16][4*ks + g]
 //   DT > 0: values e = 0..7  = W1[16*mt + l16][8*(4*ks + g) + e]   (16-bit)
@@ -251,9 +426,54 @@ static hipError_t launch_head_cl(const HeadArgs &a, hipStream_t stream)
     }
 }
 
+template <int DT, int HT, int KSTEPS>
+static hipError_t launch_head_h_t(const HeadArgs &a, hipStream_t stream)
+{
+    constexpr int HP = (HT + 1) / 2;
+    const size_t smem = (size_t)(HT * KSTEPS + HP) * 1024 + (size_t)(HT * 16 + 4) * 4;
+    static bool attr_set = false;
+    if (smem > 48 * 1024 && !attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&head_fused_h_kernel<DT, HT, KSTEPS>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const long total = (long)a.n * a.H * a.W;
+    const long groups = (total + 63) / 64;
+    long blocks = (groups + 3) / 4;
+    if (blocks > 512) blocks = 512;       // two workgroups per CU, persistent over the pixel groups
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL((head_fused_h_kernel<DT, HT, KSTEPS>), dim3((int)blocks), dim3(HEAD_THREADS), smem, stream, a);
+    return hipGetLastError();
+}
+
+// the MFMA-only 16-bit kernel covers up to 4 classes and up to 64 input maps
+template <int DT>
+static bool launch_head_h(const HeadArgs &a, hipStream_t stream, hipError_t *err)
+{
+    if (a.classes > 4 || a.ksteps > 2) return false;
+    const int ht = head_hidden_tiles(a.hidden);
+    if (a.ksteps == 1) {
+        if (ht == 4) *err = launch_head_h_t<DT, 4, 1>(a, stream);
+        else if (ht == 8) *err = launch_head_h_t<DT, 8, 1>(a, stream);
+        else if (ht == 13) *err = launch_head_h_t<DT, 13, 1>(a, stream);
+        else *err = launch_head_h_t<DT, 16, 1>(a, stream);
+    } else {
+        if (ht == 4) *err = launch_head_h_t<DT, 4, 2>(a, stream);
+        else if (ht == 8) *err = launch_head_h_t<DT, 8, 2>(a, stream);
+        else if (ht == 13) *err = launch_head_h_t<DT, 13, 2>(a, stream);
+        else *err = launch_head_h_t<DT, 16, 2>(a, stream);
+    }
+    return true;
+}
+
 template <int DT>
 static hipError_t launch_head_dt(const HeadArgs &a, hipStream_t stream)
 {
+    if constexpr (DT != 0) {
+        hipError_t err = hipSuccess;
+        if (launch_head_h<DT>(a, stream, &err)) return err;
+    }
     if (a.classes <= 2) return launch_head_cl<DT, 2>(a, stream);
     if (a.classes <= 4) return launch_head_cl<DT, 4>(a, stream);
     return launch_head_cl<DT, 8>(a, stream);
