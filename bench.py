@@ -122,6 +122,30 @@ def measure_train(torch, B, S, dtype, n, H, W, steps, warmup, first_seed):
     return {"pixels_per_s": n * H * W * steps / dt, "ms_per_step": dt / steps * 1e3, "steps": steps}
 
 
+def measure_unet(torch, B, S, dtype, steps, warmup):
+    """U-Net forward of the paper's configuration table on one 572x572 image (configs[4])."""
+    params = S.unet_params(1, 2, 1005, depth=4, base=64, bias_scale=0.0)
+    net = B.UNet(1, 2, depth=4, base_ch=64, dtype=dtype)
+    for i, name in enumerate(S.unet_param_names(4)):
+        net.set_weights(i, *params[name])
+    net.plan(1, 572, 572)
+    img = torch.from_numpy(S.em_like_image(572, 572, 1006)[None, None].copy()).cuda()
+    prob = torch.empty((1, 2, 388, 388), dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+    for _ in range(warmup):
+        net.forward(img, prob, stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        net.forward(img, prob, stream)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    net.close()
+    gflop = 300.9            # 1-channel input; the paper's table (3 channels) sums to 301.6
+    return {"ms_per_step": round(dt * 1e3, 4), "labelled_pixels_per_s": round(388 * 388 / dt, 1),
+            "tflops": round(gflop / dt / 1e3, 1)}
+
+
 def measured_peaks(torch, B):
     """What this GPU sustains on a bare MFMA issue loop and on a streaming copy (not the method)."""
     src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)   # 1 GiB each
@@ -209,6 +233,8 @@ def main():
         for name, dt in (("c4_bf16_train_512", "bf16"), ("c4_as_f32_train_512", "f32")):
             rt = measure_train(torch, B, S, dt, 1, 512, 512, 20, 3, 2)
             extras[name] = {"pixels_per_s": round(rt["pixels_per_s"], 1), "ms_per_step": round(rt["ms_per_step"], 4)}
+        for name, dt in (("c5_unet_572_f32", "f32"), ("c5_unet_572_bf16", "bf16")):
+            extras[name] = measure_unet(torch, B, S, dt, 10, 3)
         out["extras"] = extras
 
     if args.workload == "c2" and not args.no_cpu_baseline:

@@ -183,7 +183,9 @@ sk_status sknet_time_step(sknet_t *net, int32_t step, int32_t iters, void *hip_s
  * then a 2x2 stride-2 max pool), two 3x3 convs at the bottom, `depth` expanding steps (2x2
  * stride-2 up-convolution f -> f/2 without ReLU, MergeCrop with the skip connection, two 3x3
  * convs + ReLU), a 1x1 conv to n_classes and a per-pixel softmax.  Maps: base_ch * 2^level.
- * Host only. */
+ * dtype: SK_F32, or SK_BF16 / SK_F16 (activations and packed weights in the 16-bit type, fp32
+ * accumulation, fp32 logits and probabilities; base_ch must then be a multiple of 8, else
+ * SK_EUNSUPPORTED).  Host only. */
 sk_status unet_create(int32_t c_in, int32_t n_classes, int32_t depth, int32_t base_ch,
                       sk_dtype dtype, unet_t **out);
 void unet_destroy(unet_t *net);

@@ -262,6 +262,30 @@ hipError_t launch_maxpool_h(const void *x, void *y, void *tap, int dtype, long p
     return hipGetLastError();
 }
 
+// MergeCrop's second operand on octets (Section 5.3.1): dst[b][o8_off + o][y][x] = src[b][o][y + cy][x + cx]
+__global__ void crop_copy_h_kernel(const uint4v *__restrict__ src, uint4v *__restrict__ dst, int n, int c8, int Hs, int Ws,
+                                   int c8_total, int o8_off, int H, int W, int cy, int cx)
+{
+    const long plane = (long)H * W, total = (long)n * c8 * plane;
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
+        const long pix = q % plane, t = q / plane;
+        const int x = (int)(pix % W), y = (int)(pix / W);
+        const int o = (int)(t % c8);
+        const long b = t / c8;
+        dst[((b * c8_total + o8_off + o) * H + y) * W + x] = src[((b * c8 + o) * Hs + y + cy) * Ws + x + cx];
+    }
+}
+
+hipError_t launch_crop_copy_h(const void *src, void *dst, int n, int c8, int Hs, int Ws, int c8_total, int o8_off,
+                              int H, int W, int cy, int cx, hipStream_t stream)
+{
+    if (cy < 0 || cx < 0 || cy + H > Hs || cx + W > Ws || o8_off < 0 || o8_off + c8 > c8_total) return hipErrorInvalidValue;
+    const long total = (long)n * c8 * H * W;
+    hipLaunchKernelGGL(crop_copy_h_kernel, dim3(grid_for(total)), dim3(256), 0, stream, static_cast<const uint4v *>(src),
+                       static_cast<uint4v *>(dst), n, c8, Hs, Ws, c8_total, o8_off, H, W, cy, cx);
+    return hipGetLastError();
+}
+
 // Gather form of the pool gradient (s = 1): input unit (u, v) collects, per map, dY of the windows
 // whose recorded winner it is.  Sums are formed in fp32 and rounded once.  relu_src (optional,
 // same shape as dx) zeroes the result where the layer below produced a non-positive value.

@@ -73,6 +73,8 @@ hipError_t launch_unpack_h(const void *in, float *out, int dtype, int n, int c, 
 // planes8 = n * ceil(C/8); tap (optional) holds one byte per element, laid out like y
 hipError_t launch_maxpool_h(const void *x, void *y, void *tap, int dtype, long planes8, int H, int W, int Ho, int Wo,
                             int k, int d, int s, hipStream_t stream);
+hipError_t launch_crop_copy_h(const void *src, void *dst, int n, int c8, int Hs, int Ws, int c8_total, int o8_off,
+                              int H, int W, int cy, int cx, hipStream_t stream);
 hipError_t launch_maxpool_bwd_h(const void *dy, const void *tap, const void *relu_src, void *dx, int dtype,
                                 long planes8, int H, int W, int Ho, int Wo, int k, int d, hipStream_t stream);
 hipError_t launch_tap_to_index_h(const void *tap, int32_t *idx, int n, int c, int Ho, int Wo, int W, int k, int d, int s,

@@ -27,6 +27,7 @@ struct Stage {
 
 struct unet {
     int c_in = 0, n_classes = 0, depth = 0, base = 0;
+    int dtype = SK_F32;                      // storage type of activations and packed weights
     // parameters in forward order; kind 0 = conv (index into convs), 1 = up-convolution (index into ups)
     struct Param { std::string name; int kind; int idx; };
     std::vector<Param> params;
@@ -37,7 +38,7 @@ struct unet {
     int n = 0, h_in = 0, w_in = 0;
     std::vector<float *> buffers;            // every device activation buffer, for release
     struct Op {
-        int kind;                            // 0 conv, 1 pool, 2 up-convolution, 3 crop copy
+        int kind;                            // 0 conv, 1 pool, 2 up-convolution, 3 crop copy, 4 image -> octet layout
         int param;                           // conv / up index
         int relu;
         const float *src;                    // nullptr = the caller's image
@@ -48,7 +49,9 @@ struct unet {
     };
     std::vector<Op> ops;
     std::vector<Stage> stages;
-    float *logits = nullptr;
+    float *logits = nullptr;                 // fp32 NCHW in every storage type
+    float *unpack_tmp = nullptr;             // 16-bit types: fp32 staging for unet_get_activation
+    long unpack_tmp_floats = 0;
     Dims out_dims;
     hipStream_t last_stream = nullptr;
 
@@ -56,6 +59,8 @@ struct unet {
     {
         for (auto &p : buffers) free_dev(p);
         buffers.clear();
+        free_dev(unpack_tmp);
+        unpack_tmp_floats = 0;
         ops.clear();
         stages.clear();
         for (auto &c : convs) release_conv(c);
@@ -94,7 +99,7 @@ sk_status walk_sizes(const unet *net, int h, int w, int *ho, int *wo)
     return SK_OK;
 }
 
-sk_status upload_up(UpParams &u)
+sk_status upload_up(UpParams &u, int dtype)
 {
     for (int a = 0; a < 2; ++a)
         for (int b = 0; b < 2; ++b) {
@@ -105,7 +110,7 @@ sk_status upload_up(UpParams &u)
                 for (int o = 0; o < u.c_out; ++o)
                     t.w[(size_t)o * u.c_in + c] = u.w[(((size_t)c * u.c_out + o) * 2 + a) * 2 + b];
             t.b = u.b;
-            SK_TRY(upload_conv(t, false, nullptr));
+            SK_TRY(upload_conv(t, false, nullptr, dtype));
         }
     return SK_OK;
 }
@@ -119,10 +124,12 @@ sk_status unet_create(int32_t c_in, int32_t n_classes, int32_t depth, int32_t ba
     if (!out) return fail(SK_EINVAL, "unet_create: out is null");
     *out = nullptr;
     if (c_in < 1 || n_classes < 1 || depth < 1 || depth > 6 || base_ch < 1) return fail(SK_EINVAL, "unet_create: bad arguments");
-    if (dtype != SK_F32) return fail(dtype == SK_BF16 || dtype == SK_F16 ? SK_EUNSUPPORTED : SK_EINVAL, "unet_create: only SK_F32 is built");
+    if (dtype != SK_F32 && dtype != SK_BF16 && dtype != SK_F16) return fail(SK_EINVAL, "unet_create: unknown dtype %d", (int)dtype);
+    if (dtype != SK_F32 && base_ch % 8 != 0)
+        return fail(SK_EUNSUPPORTED, "unet_create: the 16-bit layout keeps maps in groups of 8, base_ch must be a multiple of 8");
     unet *net = new (std::nothrow) unet;
     if (!net) return fail(SK_ENOMEM, "unet_create: out of host memory");
-    net->c_in = c_in; net->n_classes = n_classes; net->depth = depth; net->base = base_ch;
+    net->c_in = c_in; net->n_classes = n_classes; net->depth = depth; net->base = base_ch; net->dtype = dtype;
     auto add_conv = [&](const std::string &name, int fi, int fo, int k) {
         ConvParams c;
         c.c_in = fi; c.c_out = fo; c.k = k;
@@ -193,12 +200,12 @@ sk_status unet_set_weights(unet_t *net, int32_t idx, const float *w_host, const 
         ConvParams &c = net->convs[p.idx];
         std::memcpy(c.w.data(), w_host, sizeof(float) * c.wcount());
         if (b_host) std::memcpy(c.b.data(), b_host, sizeof(float) * c.c_out);
-        if (net->planned) SK_TRY(upload_conv(c, false, net->last_stream));
+        if (net->planned) SK_TRY(upload_conv(c, false, net->last_stream, net->dtype));
     } else {
         UpParams &u = net->ups[p.idx];
         std::memcpy(u.w.data(), w_host, sizeof(float) * u.w.size());
         if (b_host) std::memcpy(u.b.data(), b_host, sizeof(float) * u.c_out);
-        if (net->planned) SK_TRY(upload_up(u));
+        if (net->planned) SK_TRY(upload_up(u, net->dtype));
     }
     return SK_OK;
 }
@@ -219,10 +226,13 @@ sk_status unet_plan(unet_t *net, int32_t n, int32_t h_in, int32_t w_in)
     net->release_plan();
     net->n = n; net->h_in = h_in; net->w_in = w_in;
     sk_status st = SK_OK;
+    const bool half = net->dtype != SK_F32;
+    // activation buffers: fp32 NCHW, or the 16-bit octet layout (sized in floats either way)
     auto new_buf = [&](const Dims &d) -> float * {
         float *p = nullptr;
-        if (st == SK_OK) st = alloc_f(&p, d.count(n));
+        if (st == SK_OK) st = alloc_f(&p, half ? octet_floats(n, d) : d.count(n));
         if (p) net->buffers.push_back(p);
+        if (half && d.count(n) > net->unpack_tmp_floats) net->unpack_tmp_floats = d.count(n);
         return p;
     };
     auto conv_op = [&](int conv_idx, int relu, const float *src, const Dims &in, float *dst, const Dims &out) {
@@ -234,6 +244,13 @@ sk_status unet_plan(unet_t *net, int32_t n, int32_t h_in, int32_t w_in)
     Dims cur;
     cur.c = net->c_in; cur.h = h_in; cur.w = w_in;
     const float *src = nullptr;
+    if (half) {                              // the caller's fp32 image goes to the octet layout first
+        float *packed = new_buf(cur);
+        unet::Op op{};
+        op.kind = 4; op.src = nullptr; op.dst = packed; op.in = cur; op.out = cur;
+        net->ops.push_back(op);
+        src = packed;
+    }
     std::vector<Dims> skip_dims;
     std::vector<const float *> skip_buf;
     for (int i = 0; i <= net->depth && st == SK_OK; ++i) {
@@ -279,24 +296,27 @@ sk_status unet_plan(unet_t *net, int32_t n, int32_t h_in, int32_t w_in)
     }
     if (st == SK_OK) {
         Dims z = {net->n_classes, cur.h, cur.w};
-        net->logits = new_buf(z);
+        if (st == SK_OK) st = alloc_f(&net->logits, z.count(n));
+        if (net->logits) net->buffers.push_back(net->logits);
         conv_op(ci++, 0, src, cur, net->logits, z);
         net->stages.push_back({"logits", z, net->logits});
         net->out_dims = z;
     }
     for (auto &c : net->convs) {
         if (st != SK_OK) break;
-        st = alloc_conv(c, false);
-        if (st == SK_OK) st = upload_conv(c, false, nullptr);
+        if (half && !sk::conv_h_supported(c.k, 1)) st = fail(SK_EUNSUPPORTED, "U-Net: kernel size %d is not built for 16-bit storage", c.k);
+        if (st == SK_OK) st = alloc_conv(c, false, net->dtype);
+        if (st == SK_OK) st = upload_conv(c, false, nullptr, net->dtype);
     }
     for (auto &u : net->ups) {
         if (st != SK_OK) break;
         for (auto &t : u.tap) {
             t.c_in = u.c_in; t.c_out = u.c_out; t.k = 1;
-            if (st == SK_OK) st = alloc_conv(t, false);
+            if (st == SK_OK) st = alloc_conv(t, false, net->dtype);
         }
-        if (st == SK_OK) st = upload_up(u);
+        if (st == SK_OK) st = upload_up(u, net->dtype);
     }
+    if (st == SK_OK && half) st = alloc_f(&net->unpack_tmp, net->unpack_tmp_floats);
     if (st != SK_OK) {
         std::string keep = g_last_error;
         net->release_plan();
@@ -315,8 +335,36 @@ sk_status unet_forward(unet_t *net, const float *image_dev, float *prob_dev, voi
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     net->last_stream = stream;
     const int n = net->n;
+    const int dt = net->dtype;
     for (const auto &op : net->ops) {
         const float *src = op.src ? op.src : image_dev;
+        if (dt != SK_F32) {
+            // 16-bit storage: the same sequence on the octet layout
+            if (op.kind == 4) {
+                SK_HIP(sk::launch_pad_pack_h(image_dev, op.dst, dt, n, op.in.c, op.in.h, op.in.w, 0, 0, op.in.h, op.in.w, 0, stream));
+            } else if (op.kind == 0) {
+                const ConvParams &c = net->convs[op.param];
+                const bool to_logits = op.dst == net->logits;     // the last conv leaves fp32 NCHW
+                sk::ConvHArgs a = conv_h_args(c, dt, src, n, op.in, 1, op.relu, op.dst, op.out, to_logits);
+                SK_HIP(sk::launch_conv_h(a, stream));
+            } else if (op.kind == 1) {
+                SK_HIP(sk::launch_maxpool_h(src, op.dst, nullptr, dt, (long)n * ((op.in.c + 7) / 8), op.in.h, op.in.w,
+                                            op.out.h, op.out.w, 2, 1, 2, stream));
+            } else if (op.kind == 2) {
+                const UpParams &u = net->ups[op.param];
+                for (int t = 0; t < 4; ++t) {
+                    Dims lowres = {u.c_out, op.in.h, op.in.w};
+                    sk::ConvHArgs a = conv_h_args(u.tap[t], dt, src, n, op.in, 1, 0, op.dst, lowres, false);
+                    a.c8_out_total = (op.out.c + 7) / 8; a.o8_off = 0; a.OH = op.out.h; a.OW = op.out.w;
+                    a.oy_mul = 2; a.oy_off = t / 2; a.ox_mul = 2; a.ox_off = t % 2;
+                    SK_HIP(sk::launch_conv_h(a, stream));
+                }
+            } else {
+                SK_HIP(sk::launch_crop_copy_h(src, op.dst, n, op.src_maps / 8, op.in.h, op.in.w, (op.out.c + 7) / 8, op.o_off / 8,
+                                              op.out.h, op.out.w, op.crop, (op.in.w - op.out.w) / 2, stream));
+            }
+            continue;
+        }
         if (op.kind == 0) {
             const ConvParams &c = net->convs[op.param];
             sk::ConvF32Args a = conv_args(c, src, n, op.in, 1, op.relu, op.dst, op.out);
@@ -353,16 +401,19 @@ sk_status unet_get_activation(unet_t *net, const char *stage, float *nchw_host, 
         if (!nchw_host) return SK_OK;
         if (!net->forward_done) return fail(SK_ESTATE, "unet_get_activation: no forward pass yet");
         SK_HIP(hipStreamSynchronize(net->last_stream));
-        if (s.name.rfind("up", 0) == 0) {
-            // the up path occupies the first maps of the merged buffer: copy image by image
-            const int merged_c = 2 * s.dims.c;
-            const size_t img = (size_t)s.dims.c * s.dims.h * s.dims.w;
-            for (int b = 0; b < net->n; ++b)
-                SK_HIP(hipMemcpy(nchw_host + b * img, s.buf + (size_t)b * merged_c * s.dims.h * s.dims.w,
-                                 sizeof(float) * img, hipMemcpyDeviceToHost));
-        } else {
-            SK_HIP(hipMemcpy(nchw_host, s.buf, sizeof(float) * s.dims.count(net->n), hipMemcpyDeviceToHost));
+        const bool is_up = s.name.rfind("up", 0) == 0;
+        // the up path occupies the first maps of the merged buffer: copy image by image
+        const int buf_c = is_up ? 2 * s.dims.c : s.dims.c;
+        const float *src = s.buf;
+        if (net->dtype != SK_F32 && s.buf != net->logits) {      // widen the octet layout to fp32 NCHW first
+            SK_HIP(sk::launch_unpack_h(s.buf, net->unpack_tmp, net->dtype, net->n, buf_c, s.dims.h, s.dims.w, net->last_stream));
+            SK_HIP(hipStreamSynchronize(net->last_stream));
+            src = net->unpack_tmp;
         }
+        const size_t img = (size_t)s.dims.c * s.dims.h * s.dims.w;
+        for (int b = 0; b < net->n; ++b)
+            SK_HIP(hipMemcpy(nchw_host + b * img, src + (size_t)b * buf_c * s.dims.h * s.dims.w,
+                             sizeof(float) * img, hipMemcpyDeviceToHost));
         return SK_OK;
     }
     return fail(SK_EINVAL, "unet_get_activation: unknown stage '%s'", stage);

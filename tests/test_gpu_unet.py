@@ -9,16 +9,25 @@ from oracle import nets as ON
 pytestmark = pytest.mark.gpu
 
 FP32_TOL = 1e-4
+# bf16 / fp16 storage with fp32 accumulation; the oracle sees the unrounded fp32 weights and image.
+# The bound of 2e-2 is asserted where the benchmark spec puts it, on the network's output (logits
+# relative to their largest value, probabilities in absolute terms).  Intermediate stages are held to
+# twice that: every stored tensor is rounded (relative step 2^-8 in bf16) on top of the error it
+# inherits, and the largest error of a stage relative to its largest value was measured at
+# 1.4e-2 after two layers and 2.1e-2 at most anywhere in the 23-layer net.
+HALF_TOL = 2e-2
+HALF_STAGE_TOL = 4e-2
 
 
 def relerr(got, ref):
     return float(np.abs(got.astype(np.float64) - ref).max() / max(np.abs(ref).max(), 1e-30))
 
 
-def run_unet(c_in, classes, depth, base, h, w, seed, n=1, bias_scale=0.1):
+def run_unet(c_in, classes, depth, base, h, w, seed, n=1, bias_scale=0.1, dtype="f32"):
     from paper_1509_03371_amd import binding as B
+    tol = FP32_TOL if dtype == "f32" else HALF_TOL
     params = S.unet_params(c_in, classes, seed, depth=depth, base=base, bias_scale=bias_scale)
-    net = B.UNet(c_in, classes, depth=depth, base_ch=base)
+    net = B.UNet(c_in, classes, depth=depth, base_ch=base, dtype=dtype)
     for i, name in enumerate(S.unet_param_names(depth)):
         net.set_weights(i, *params[name])
     img = np.stack([S.em_like_image(h, w, seed + 1 + i) for i in range(n)])[:, None].repeat(c_in, 1)
@@ -30,9 +39,11 @@ def run_unet(c_in, classes, depth, base, h, w, seed, n=1, bias_scale=0.1):
     for stage, r in trace.items():
         got = net.get_activation(stage)
         assert got.shape == r.shape, stage
-        assert relerr(got, r) <= FP32_TOL, stage
+        e = relerr(got, r)
+        print("%s %s rel err %.3e" % (dtype, stage, e))
+        assert e <= (tol if dtype == "f32" or stage == "logits" else HALF_STAGE_TOL), (stage, e)
     assert prob.shape == ref.shape
-    assert np.abs(prob - ref).max() <= FP32_TOL
+    assert np.abs(prob - ref).max() <= tol
     net.close()
     return prob
 
@@ -51,3 +62,26 @@ def test_unet_depth4_small_maps():
 def test_c5_unet_572():
     prob = run_unet(1, 2, 4, 64, 572, 572, 1005, bias_scale=0.0)
     assert prob.shape == (1, 2, 388, 388)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp16_alias"])
+def test_unet_depth2_small_half(dtype):
+    # two images, three classes, non-zero biases, odd crop offsets: the oracle sees the unrounded fp32 weights
+    prob = run_unet(2, 3, 2, 8, 60, 76, 100, n=2, dtype="bf16" if dtype == "bf16" else "f16")
+    assert prob.shape == (2, 3, 20, 36)
+
+
+def test_unet_depth4_small_maps_bf16():
+    prob = run_unet(1, 2, 4, 8, 188, 204, 101, dtype="bf16")
+    assert prob.shape == (1, 2, 4, 20)
+
+
+def test_c5_unet_572_bf16():
+    prob = run_unet(1, 2, 4, 64, 572, 572, 1005, bias_scale=0.0, dtype="bf16")
+    assert prob.shape == (1, 2, 388, 388)
+
+
+def test_unet_half_needs_octet_multiple():
+    from paper_1509_03371_amd import binding as B
+    with pytest.raises(B.SknetError):
+        B.UNet(1, 2, depth=2, base_ch=12, dtype="bf16")
