@@ -7,6 +7,7 @@ A step is one such pass over one synthetic image that is resident in HBM before 
 
 --workload c3 : the same net in bf16 (fp32 accumulate) on 8 images of 1024x1024 (configs[2])
 --workload c4 : one bf16 training step at 512x512 (configs[3]): forward, softmax loss, backward, SGD
+--workload c5 / c5bf16 : U-Net forward on one 572x572 image (configs[4]) in fp32 / bf16
 --workload copy : only the streaming-copy probe on 2 x 1 GiB (the known-size kernel that the HBM
                   byte counters of a profiler run are calibrated against)
 The default run also appends short c3 / c4 measurements under "extras" (skip with --no-extras).
@@ -146,6 +147,36 @@ def measure_unet(torch, B, S, dtype, steps, warmup):
             "tflops": round(gflop / dt / 1e3, 1)}
 
 
+def measure_paper_sknet(torch, B, S, steps, warmup):
+    """The paper's own SK network (Section 3.3.2: 3 x 229^2 after padding -> 2 x 128^2; its inner product
+    is a k = 10, d = 8 convolution 192 -> 1024, 644 of the 695 GFLOP) in fp32: the workload of the
+    paper's label-throughput and layer-efficiency tables."""
+    layers = S.paper_sknet_layers()
+    ws, bs = S.he_normal_weights(layers, 3, 1003)
+    net = B.SKNet(layers, 3, 2, dtype="f32")
+    for i, (w, b) in enumerate(zip(ws, bs)):
+        net.set_weights(i, w, b)
+    net.plan(1, 128, 128, pad=True)
+    img = torch.from_numpy(S.uniform_image(1, 3, 128, 128, 12)).cuda()
+    prob = torch.empty(net.out_shape(), dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+    for _ in range(warmup):
+        net.forward(img, prob, stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        net.forward(img, prob, stream)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    ip1_ms = net.time_step(7, 3, stream)               # pad, 6 layers, then the k10 d8 convolution
+    name = net.step_name(7)
+    net.close()
+    return {"ms_per_step": round(dt * 1e3, 3), "pixels_per_s": round(128 * 128 / dt, 1),
+            "forward_tflops": round(694.6 / dt / 1e3, 1), name + "_ms": round(ip1_ms, 3),
+            name + "_tflops": round(644.23 / ip1_ms, 1),
+            "paper_pixels_per_s": {"W9100 OpenCL": 59513, "GTX 980 CUDA": 85460}}
+
+
 def measured_peaks(torch, B):
     """What this GPU sustains on a bare MFMA issue loop and on a streaming copy (not the method)."""
     src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)   # 1 GiB each
@@ -164,7 +195,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", choices=["c2", "c3", "c4", "copy"], default="c2")
+    ap.add_argument("--workload", choices=["c2", "c3", "c4", "c5", "c5bf16", "copy"], default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
     args = ap.parse_args()
@@ -190,6 +221,16 @@ def main():
         print(json.dumps({"metric": "streaming copy", "value": round(gbs, 1), "unit": "GB/s (read + written)",
                           "bytes_read_per_launch": src.numel() * 4, "bytes_written_per_launch": src.numel() * 4,
                           "launches": max(1, args.steps) + 1, "kernel": "stream_copy_kernel"}))
+        return
+
+    if args.workload in ("c5", "c5bf16"):
+        dt = "f32" if args.workload == "c5" else "bf16"
+        r = measure_unet(torch, B, S, dt, args.steps, args.warmup)
+        out.update({"value": r["labelled_pixels_per_s"], "ms_per_step": r["ms_per_step"], "dtype": dt,
+                    "config": {"workload": "U-Net forward 1x1x572x572 -> 2x388x388, %s (BASELINE configs[4])" % dt,
+                               "global_batch": 1, "parallelism": "single GPU"},
+                    "roofline": None, "forward_tflops": r["tflops"]})
+        print(json.dumps(out))
         return
 
     if args.workload in ("c2", "c3"):
@@ -235,6 +276,7 @@ def main():
             extras[name] = {"pixels_per_s": round(rt["pixels_per_s"], 1), "ms_per_step": round(rt["ms_per_step"], 4)}
         for name, dt in (("c5_unet_572_f32", "f32"), ("c5_unet_572_bf16", "bf16")):
             extras[name] = measure_unet(torch, B, S, dt, 10, 3)
+        extras["paper_sknet_128_f32"] = measure_paper_sknet(torch, B, S, 5, 2)
         out["extras"] = extras
 
     if args.workload == "c2" and not args.no_cpu_baseline:

@@ -42,6 +42,14 @@ def sknet_layers(width=48, hidden=200, classes=2, stages=4):
     return layers
 
 
+def paper_sknet_layers(classes=2):
+    """The SK network of Section 3.3.2's configuration table (3 input maps, context 101):
+    conv k7 -> 48, pool, conv k5 d2 -> 128, pool d2, conv k3 d4 -> 192, pool d4, then the three
+    inner-product layers as convolutions: k10 d8 -> 1024, 1x1 -> 512, 1x1 -> classes."""
+    return [conv(48, 7, 1), pool(2, 1), conv(128, 5, 2), pool(2, 2), conv(192, 3, 4), pool(2, 4),
+            conv(1024, 10, 8), conv(512, 1, 1), conv(classes, 1, 1, relu=False)]
+
+
 def he_normal_weights(layers, c_in, seed, bias_scale=0.0):
     """Per conv, in order: N(0, sqrt(2/(f_in k^2))) weights [f_out,f_in,k,k] (Section 3.4's
     initialisation), biases bias_scale*N(0,1) (0 in the benchmark configs). fp32."""

@@ -166,3 +166,13 @@ def test_c2_sknet_forward_512():
     img = S.em_like_batch(1, 512, 512, 2)
     got, ref = run_and_compare(layers, 1, img, ws, bs)
     assert got.shape == (1, 2, 512, 512)
+
+
+def test_paper_sknet_configuration_forward():
+    # the network of Section 3.3.2's SK table (k = 7, 5, 3 and the k = 10, d = 8 inner product, context 101,
+    # odd: 51 rows/columns of mirror padding before, 50 after) on a small 3-channel image
+    layers = S.paper_sknet_layers()
+    ws, bs = S.he_normal_weights(layers, 3, 1003, bias_scale=0.05)
+    img = S.uniform_image(1, 3, 60, 68, 11)          # reflect padding by 51 needs at least 52 rows/columns
+    got, ref = run_and_compare(layers, 3, img, ws, bs)
+    assert got.shape == (1, 2, 60, 68)
