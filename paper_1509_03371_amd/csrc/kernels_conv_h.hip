@@ -361,18 +361,25 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
 // LDS-write instructions; the loads of the next S-1 chunks are in flight while one chunk is
 // multiplied, which is what covers the HBM latency (one chunk of look-ahead does not).
 // What lies outside the image is read from a small zero buffer instead.
-template <int DT, int KS, int MT, bool MAP4, int R, bool HAS_MASK, int S, bool RESW>
-__global__ __launch_bounds__(CH_THREADS) void conv_h_ring_kernel(ConvHArgs a)
+// NP > 0 adds NP producer waves to the eight that multiply: the producers issue every load (and
+// wait for it), the others never touch the memory queue except for their tile's stores.  A load
+// or store instruction can sit in that queue for hundreds of cycles when HBM is the limit, and a
+// wave that waits there issues no MFMA; with the loads on waves of their own the multiplying waves
+// lose that time only for their stores.
+template <int DT, int KS, int MT, bool MAP4, int R, bool HAS_MASK, int S, bool RESW, int NP>
+__global__ __launch_bounds__(CH_THREADS + 64 * NP) void conv_h_ring_kernel(ConvHArgs a)
 {
+    constexpr int NTHREADS = CH_THREADS + 64 * NP;
+    constexpr int LW = NP > 0 ? NP : CH_WAVES;                 // waves that share a chunk's loads
     extern __shared__ uint4v lds[];
     constexpr int RR = R + KS - 1;
     constexpr int OC = MAP4 ? 1 : 4;
     constexpr int CS = MAP4 ? 1 : KS;
     constexpr int ROWS = OC * RR;
-    constexpr int RU = (ROWS + CH_WAVES - 1) / CH_WAVES;
+    constexpr int RU = (ROWS + LW - 1) / LW;
     constexpr int WUNITS = CS * KS * MT * 64;
     constexpr int WBLK = WUNITS / 64;                          // 1 KB fragments in the weight slab
-    constexpr int WL = (WBLK + CH_WAVES - 1) / CH_WAVES;
+    constexpr int WL = (WBLK + LW - 1) / LW;
     constexpr int VUE = KS == 1 ? 2 : 3;                       // 64-unit column groups per staged row
 
     const int d = a.d;
@@ -394,10 +401,10 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_ring_kernel(ConvHArgs a)
     if constexpr (RESW) {
         uint4v *wdst = lds + S * stage_units;
         const uint4v *wsrc_all = reinterpret_cast<const uint4v *>(a.wp);
-        for (int q = tid; q < wres_units; q += CH_THREADS) wdst[q] = wsrc_all[q];
+        for (int q = tid; q < wres_units; q += NTHREADS) wdst[q] = wsrc_all[q];
     }
-    for (int q = tid; q < a.mgroups * MT * 16; q += CH_THREADS) bias_lds[q] = (a.bias && q < a.m_tiles * 16) ? a.bias[q] : 0.f;
-    for (int yt = tid; yt < a.ytiles_total; yt += CH_THREADS) {
+    for (int q = tid; q < a.mgroups * MT * 16; q += NTHREADS) bias_lds[q] = (a.bias && q < a.m_tiles * 16) ? a.bias[q] : 0.f;
+    for (int yt = tid; yt < a.ytiles_total; yt += NTHREADS) {
         int py, ty;
         if (yt < a.rem * a.tiles_hi) {
             py = yt / a.tiles_hi;
@@ -452,7 +459,9 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_ring_kernel(ConvHArgs a)
 
     // loads this wave issues per chunk: its tile rows (wave, wave + 8, ...) times the column groups,
     // plus its 1 KB blocks of the weight slab
-    const int L = ((ROWS - wave + CH_WAVES - 1) / CH_WAVES) * VUE + (RESW ? 0 : (WBLK - wave + CH_WAVES - 1) / CH_WAVES);
+    // lw: this wave's index among the waves that issue loads (all eight, or the NP producers)
+    const int lw = NP > 0 ? wave - CH_WAVES : wave;
+    const int L = lw < 0 ? 0 : ((ROWS - lw + LW - 1) / LW) * VUE + (RESW ? 0 : (WBLK - lw + LW - 1) / LW);
     // Waves 4..7 share their SIMDs with waves 0..3.  The first four issue a chunk's loads before
     // they multiply, the last four after: while one wave of a SIMD sits in the memory pipeline's
     // queue, the other one keeps the matrix unit busy.
@@ -479,7 +488,7 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_ring_kernel(ConvHArgs a)
         }
 #pragma unroll
         for (int u = 0; u < RU; ++u) {
-            const int rid = wave + CH_WAVES * u;
+            const int rid = lw + LW * u;
             if (rid >= ROWS) break;                              // uniform: this wave has no further row
             const int oc = rid / RR, r = rid - oc * RR;
             const int o = ch * OC + oc;
@@ -508,7 +517,7 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_ring_kernel(ConvHArgs a)
         const char *wsrc = reinterpret_cast<const char *>(a.wp) + ((long)p.mg * a.nchunks + ch) * (WUNITS * 16);
 #pragma unroll
         for (int u = 0; u < (RESW ? 0 : WL); ++u) {
-            const int blk = wave + CH_WAVES * u;
+            const int blk = lw + LW * u;
             if (blk >= WBLK) break;                              // uniform
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(wsrc + (unsigned)(blk * 1024 + lane * 16)),
                                              (__attribute__((address_space(3))) void *)(dst + tile_units + blk * 64), 16, 0, 0);
@@ -650,6 +659,61 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_ring_kernel(ConvHArgs a)
         return ops;
     };
 
+    // Epilogue with 16-byte stores (16-bit output, no mask).  The memory pipeline takes about as long
+    // for a store instruction of 8 bytes per lane as for one of 16, so rows are stored in pairs:
+    // lanes of the even lane groups hold the low half of an octet and their neighbours 16 lanes up
+    // the high half; after one v_permlane16_swap per register the even groups own the whole octet
+    // of row y and the odd groups that of row y + 1, and one instruction stores both rows.
+    auto epilogue16 = [&](const TilePos &p) {
+        const int ox = p.x0 + wave * 16 + l16;
+        const bool colok = ox < a.Wo;
+        if (__builtin_amdgcn_ballot_w64(colok) == 0) {          // this wave's 16 columns lie outside
+#pragma unroll
+            for (int y = 0; y < R; ++y)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) acc[y][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+            return;
+        }
+        const int row_bytes = a.OW * 16, plane_bytes = a.OH * row_bytes;   // < 2^31 (checked by the launcher)
+        const int oxc = colok ? ox : 0;
+        char *img_base = reinterpret_cast<char *>(a.y) + ((long)p.b * a.c8_out_total + a.o8_off) * plane_bytes;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const int mtile = p.mg * MT + mt;
+            float bia[4];
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) bia[r4] = bias_lds[mtile * 16 + 4 * g + r4];
+            const bool octet_ok = colok && mtile < a.m_tiles && mtile * 2 + (g >> 1) < a.c8_out;
+            const unsigned voff = (unsigned)((mtile * 2 + (g >> 1)) * plane_bytes + (oxc * a.ox_mul + a.ox_off) * 16);
+#pragma unroll
+            for (int y = 0; y < R; y += 2) {
+                unsigned lo[2], hi[2];          // this lane's half octet of rows y and y + 1
+#pragma unroll
+                for (int yy = 0; yy < 2; ++yy) {
+                    floatx4 v = acc[y + yy][mt];
+                    acc[y + yy][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+                    unsigned short h[4];
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4) {
+                        v[r4] += bia[r4];
+                        if (a.relu) v[r4] = fmaxf(v[r4], 0.f);
+                        h[r4] = H<DT>::cvt(v[r4]);
+                    }
+                    lo[yy] = (unsigned)h[0] | ((unsigned)h[1] << 16);
+                    hi[yy] = (unsigned)h[2] | ((unsigned)h[3] << 16);
+                }
+                // odd groups of the first operand <-> even groups of the second
+                const auto s0 = __builtin_amdgcn_permlane16_swap(lo[0], lo[1], false, false);
+                const auto s1 = __builtin_amdgcn_permlane16_swap(hi[0], hi[1], false, false);
+                // even group: {own row y half, neighbour's row y half}; odd group: {neighbour's row y+1 half, own}
+                const uint4v octet = uint4v{s0[0], s1[0], s0[1], s1[1]};
+                const int oy = p.py + d * (p.ty * R + y + (g & 1));
+                if (octet_ok && oy < a.Ho)
+                    *reinterpret_cast<uint4v *>(img_base + (long)(oy * a.oy_mul + a.oy_off) * row_bytes + voff) = octet;
+            }
+        }
+    };
+
     int t = t_begin + slot;
     if (t >= t_end) return;
     const int my_tiles = (t_end - t + nslots - 1) / nslots;
@@ -673,8 +737,43 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_ring_kernel(ConvHArgs a)
     };
 #pragma unroll
     for (int j = 0; j < S - 1; ++j)
-        if (j < total_chunks) issue_next();
+        if (j < total_chunks && lw >= 0) issue_next();
 
+    if constexpr (NP > 0) {
+        // Every wave meets the same barrier once per chunk.  A producer arrives when its loads of
+        // chunk q have landed and then refills the stage that was multiplied in the previous
+        // iteration; a multiplying wave arrives when it is done with chunk q - 1.
+        if (wave >= CH_WAVES) {
+            for (int q = 0; q < total_chunks; ++q) {
+                int allow = (issued - q - 1) * L;          // loads of younger chunks may still be in flight
+                allow = allow < 63 ? allow : 63;
+                __builtin_amdgcn_sched_barrier(0);
+                wait_vmcnt_at_most(allow);
+                __builtin_amdgcn_sched_barrier(0);
+                block_sync_lds();
+                if (issued < total_chunks) issue_next();
+            }
+            return;
+        }
+        TilePos cur = position(ccur);
+        int ch = 0, ctiles = 0;
+        for (int q = 0; q < total_chunks; ++q) {
+            block_sync_lds();
+            compute(q % S, ch);
+            if (ch == a.nchunks - 1) {
+                if (HAS_MASK || a.out_f32 || (R & 1)) epilogue(cur);
+                else epilogue16(cur);
+                ch = 0;
+                if (++ctiles < my_tiles) {
+                    advance(ccur);
+                    cur = position(ccur);
+                }
+            } else {
+                ++ch;
+            }
+        }
+        return;
+    }
     TilePos cur = position(ccur);
     int ch = 0, ctiles = 0;
     int ep_ops[S - 1];            // memory operations of the epilogues of the last S-1 iterations
@@ -800,7 +899,7 @@ static size_t ring_smem(int d, int c_out, int c8_in, int Ho)
     return units * 16 + (size_t)m_tiles_all * 64 + (size_t)(Ho / R + 2 * d + 2) * 4;
 }
 
-template <int DT, int KS, int MT, bool MAP4, int R, bool HAS_MASK, int S, bool RESW>
+template <int DT, int KS, int MT, bool MAP4, int R, bool HAS_MASK, int S, bool RESW, int NP = 0>
 static hipError_t launch_conv_h_ring_m(ConvHArgs a, hipStream_t stream)
 {
     constexpr int OC = MAP4 ? 1 : 4;
@@ -808,7 +907,7 @@ static hipError_t launch_conv_h_ring_m(ConvHArgs a, hipStream_t stream)
     if (smem > 160 * 1024) return hipErrorInvalidValue;            // callers check the size first
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_h_ring_kernel<DT, KS, MT, MAP4, R, HAS_MASK, S, RESW>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_h_ring_kernel<DT, KS, MT, MAP4, R, HAS_MASK, S, RESW, NP>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
@@ -832,7 +931,7 @@ static hipError_t launch_conv_h_ring_m(ConvHArgs a, hipStream_t stream)
     a.total_tiles = (int)total;
     int blocks = device_cus() / 8 * 8;
     if (total < blocks) blocks = (int)((total + 7) / 8 * 8);
-    hipLaunchKernelGGL((conv_h_ring_kernel<DT, KS, MT, MAP4, R, HAS_MASK, S, RESW>), dim3(blocks), dim3(CH_THREADS), smem, stream, a);
+    hipLaunchKernelGGL((conv_h_ring_kernel<DT, KS, MT, MAP4, R, HAS_MASK, S, RESW, NP>), dim3(blocks), dim3(CH_THREADS + 64 * NP), smem, stream, a);
     return hipGetLastError();
 }
 
@@ -850,8 +949,12 @@ template <int DT, int KS, int MT, bool MAP4, int R>
 static hipError_t launch_conv_h_ring_or_staged(const ConvHArgs &a, hipStream_t stream)
 {
     const bool one_group = ((a.c_out + 15) / 16 + MT - 1) / MT == 1;
-    if (one_group && ring_smem<KS, MT, MAP4, R, 3, true>(a.d, a.c_out, a.c8_in, a.Ho) <= 160 * 1024)
+    if (one_group && ring_smem<KS, MT, MAP4, R, 3, true>(a.d, a.c_out, a.c8_in, a.Ho) <= 160 * 1024) {
+        // the forward 4x4 convolution of the benchmark nets: loads on four waves of their own (three waves per SIMD)
+        if constexpr (KS == 4 && MAP4 && R == 8)
+            if (!a.mask) return launch_conv_h_ring_m<DT, KS, MT, MAP4, R, false, 3, true, 4>(a, stream);
         return launch_conv_h_ring_mask<DT, KS, MT, MAP4, R, 3, true>(a, stream);
+    }
     if (ring_smem<KS, MT, MAP4, R, 4, false>(a.d, a.c_out, a.c8_in, a.Ho) <= 160 * 1024)
         return launch_conv_h_ring_mask<DT, KS, MT, MAP4, R, 4, false>(a, stream);
     return launch_conv_h_t<DT, KS, MT, MAP4, R>(a, stream);
