@@ -535,17 +535,23 @@ __global__ __launch_bounds__(CH_THREADS + 64 * NP) void conv_h_ring_kernel(ConvH
         const uint4v *wl = RESW ? wres + chunk * WUNITS : tile + tile_units;
 #pragma unroll
         for (int cs = 0; cs < CS; ++cs) {
+            // Tap row i is first needed by input row r = i, so its A fragments are fetched one input
+            // row ahead instead of all at the top: right after the barrier all waves would otherwise
+            // queue KS*MT + 1 LDS reads each before anybody's first MFMA.
             uint4v afr[KS][MT];
 #pragma unroll
-            for (int i = 0; i < KS; ++i)
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) afr[i][mt] = wl[((cs * KS + i) * MT + mt) * 64 + lane];
+            for (int mt = 0; mt < MT; ++mt) afr[0][mt] = wl[((cs * KS + 0) * MT + mt) * 64 + lane];
             const int off = (MAP4 ? g * d : g * RR * PW + cs * d) + wave * 16 + l16;
             uint4v bcur = tile[off];
 #pragma unroll
             for (int r = 0; r < RR; ++r) {
                 uint4v bnext = bcur;
                 if (r + 1 < RR) bnext = tile[off + (r + 1) * PW];
+                if (r + 1 < KS) {
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) afr[r + 1][mt] = wl[((cs * KS + r + 1) * MT + mt) * 64 + lane];
+                }
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int i = 0; i < KS; ++i) {
                     const int y = r - i;
