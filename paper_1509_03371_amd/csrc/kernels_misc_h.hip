@@ -374,18 +374,22 @@ hipError_t launch_tap_to_index_h(const void *tap, int32_t *idx, int n, int c, in
     return hipGetLastError();
 }
 
-// db[o] = sum over images and pixels of dY (octet layout); one workgroup per octet, fixed order
+// db[o] = sum over images and pixels of dY (octet layout), in two stages with a fixed summation
+// order: workgroup (s, octet) sums slice s of the pixels of its octet over all images into
+// part[(8*octet + e) * slices + s]; bias_grad_finish_kernel (kernels_wgrad_f32.hip) adds the slices.
 template <int DT>
-__global__ void bias_grad_h_kernel(const uint4v *dy, float *db, int n, int c, long plane)
+__global__ void __launch_bounds__(256) bias_grad_h_kernel(const uint4v *__restrict__ dy, float *__restrict__ part, int n, int c,
+                                                          long plane, int slices)
 {
     __shared__ float sh[4][8];
-    const int c8 = (c + 7) / 8, o = blockIdx.x;
+    const int c8 = (c + 7) / 8, o = blockIdx.y, sl = blockIdx.x;
+    const long per = (plane + slices - 1) / slices, q0 = sl * per, q1 = q0 + per < plane ? q0 + per : plane;
     float v[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] = 0.f;
     for (int b = 0; b < n; ++b) {
         const uint4v *src = dy + ((long)b * c8 + o) * plane;
-        for (long q = threadIdx.x; q < plane; q += blockDim.x) {
+        for (long q = q0 + threadIdx.x; q < q1; q += 256) {
             const uint4v u = src[q];
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[e] += up16<DT>(elem16(u, e));
@@ -397,16 +401,17 @@ __global__ void bias_grad_h_kernel(const uint4v *dy, float *db, int n, int c, lo
         if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6][e] = v[e];
     }
     __syncthreads();
-    if (threadIdx.x < 8 && o * 8 + threadIdx.x < c)
-        db[o * 8 + threadIdx.x] = sh[0][threadIdx.x] + sh[1][threadIdx.x] + sh[2][threadIdx.x] + sh[3][threadIdx.x];
+    if (threadIdx.x < 8)
+        part[(long)(o * 8 + threadIdx.x) * slices + sl] = sh[0][threadIdx.x] + sh[1][threadIdx.x] + sh[2][threadIdx.x] + sh[3][threadIdx.x];
 }
 
-hipError_t launch_bias_grad_h(const void *dy, float *db, int dtype, int n, int c, long plane, hipStream_t stream)
+hipError_t launch_bias_grad_h(const void *dy, float *part, int dtype, int n, int c, long plane, int slices, hipStream_t stream)
 {
+    const dim3 grid(slices, (c + 7) / 8);
     if (dtype == 1)
-        hipLaunchKernelGGL(bias_grad_h_kernel<1>, dim3((c + 7) / 8), dim3(256), 0, stream, static_cast<const uint4v *>(dy), db, n, c, plane);
+        hipLaunchKernelGGL(bias_grad_h_kernel<1>, grid, dim3(256), 0, stream, static_cast<const uint4v *>(dy), part, n, c, plane, slices);
     else
-        hipLaunchKernelGGL(bias_grad_h_kernel<2>, dim3((c + 7) / 8), dim3(256), 0, stream, static_cast<const uint4v *>(dy), db, n, c, plane);
+        hipLaunchKernelGGL(bias_grad_h_kernel<2>, grid, dim3(256), 0, stream, static_cast<const uint4v *>(dy), part, n, c, plane, slices);
     return hipGetLastError();
 }
 

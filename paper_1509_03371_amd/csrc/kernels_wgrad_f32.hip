@@ -165,33 +165,57 @@ __global__ __launch_bounds__(256) void wgrad_f32_kernel(WgradArgs a)
     }
 }
 
-// dW[o][cij] = sum over the private copies, in block order
-__global__ void wgrad_reduce_kernel(const float *scratch, float *dw, int copies, int c_out, int K,
+// dW[o][cij] = sum over the private copies.  Four running sums over copies 4i, 4i+1, 4i+2, 4i+3 keep
+// four loads in flight; the order is fixed, so the result is reproducible.
+__global__ void wgrad_reduce_kernel(const float *__restrict__ scratch, float *__restrict__ dw, int copies, int c_out, int K,
                                     int m_rows, int ncols)
 {
-    const long total = (long)c_out * K;
+    const long total = (long)c_out * K, stride = (long)m_rows * ncols;
     for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
         const int o = (int)(q / K), cij = (int)(q - (long)o * K);
-        float s = 0.f;
-        for (int cpy = 0; cpy < copies; ++cpy) s += scratch[((long)cpy * m_rows + o) * ncols + cij];
-        dw[q] = s;
+        const float *src = scratch + (long)o * ncols + cij;
+        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+        int cpy = 0;
+        for (; cpy + 4 <= copies; cpy += 4) {
+            s0 += src[(cpy + 0) * stride];
+            s1 += src[(cpy + 1) * stride];
+            s2 += src[(cpy + 2) * stride];
+            s3 += src[(cpy + 3) * stride];
+        }
+        for (; cpy < copies; ++cpy) s0 += src[cpy * stride];
+        dw[q] = (s0 + s1) + (s2 + s3);
     }
 }
 
-// db[o] = sum over images and pixels of dY; one workgroup per output map, fixed summation order
-__global__ void bias_grad_kernel(const float *dy, float *db, int n, int c_out, long plane)
+// Bias gradient db[o] = sum over images and pixels of dY, in two stages with a fixed summation order.
+// Stage 1 (fp32 NCHW): workgroup (s, o) sums slice s of the pixels of map o over all images.
+constexpr int BG_SLICES = 64;
+
+__global__ void __launch_bounds__(256) bias_grad_kernel(const float *__restrict__ dy, float *__restrict__ part, int n, int c_out,
+                                                        long plane, int slices)
 {
     __shared__ float sh[4];
-    const int o = blockIdx.x;
+    const int o = blockIdx.y, sl = blockIdx.x;
+    const long per = (plane + slices - 1) / slices, q0 = sl * per, q1 = q0 + per < plane ? q0 + per : plane;
     float v = 0.f;
     for (int b = 0; b < n; ++b) {
         const float *src = dy + ((long)b * c_out + o) * plane;
-        for (long q = threadIdx.x; q < plane; q += blockDim.x) v += src[q];
+        for (long q = q0 + threadIdx.x; q < q1; q += 256) v += src[q];
     }
     for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
     if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
     __syncthreads();
-    if (threadIdx.x == 0) db[o] = sh[0] + sh[1] + sh[2] + sh[3];
+    if (threadIdx.x == 0) part[(long)o * slices + sl] = sh[0] + sh[1] + sh[2] + sh[3];
+}
+
+// Stage 2: db[o] = part[o][0] + part[o][1] + ... in slice order
+__global__ void bias_grad_finish_kernel(const float *__restrict__ part, float *__restrict__ db, int c_out, int slices)
+{
+    const int o = blockIdx.x * blockDim.x + threadIdx.x;
+    if (o >= c_out) return;
+    float s = 0.f;
+    for (int sl = 0; sl < slices; ++sl) s += part[(long)o * slices + sl];
+    db[o] = s;
 }
 
 static void wgrad_tiling(int c_out, int c_in, int k, int &MTo, int &NTk, int &MB, int &NB)
@@ -242,7 +266,14 @@ static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, floa
     const int x_rows = (DT == 0 ? c_in : (c_in + 7) / 8 * 8) * k;
     const size_t smem = sizeof(float) * ((size_t)a.MTo * 16 * WG_DYP + (size_t)x_rows * a.xpitch);
     if (smem > 150 * 1024) return hipErrorInvalidValue;
-    const int blocks = a.total_segs < WG_MAX_BLOCKS ? a.total_segs : WG_MAX_BLOCKS;
+    // as many persistent workgroups as fit on the GPU at once (more would only add private copies
+    // for the reduction to read): LDS decides
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
+    const long per_cu = (long)(160 * 1024) / (long)(smem > 1 ? smem : 1);
+    long resident = (long)cus * (per_cu < 1 ? 1 : (per_cu > 2 ? 2 : per_cu));
+    if (resident > WG_MAX_BLOCKS) resident = WG_MAX_BLOCKS;
+    const int blocks = a.total_segs < resident ? a.total_segs : (int)resident;
     hipError_t e = hipErrorInvalidValue;
 #define SK_WG_CASE(mb, nb) if (MB == mb && NB == nb) e = launch_wgrad_t<mb, nb, DT>(a, smem, blocks, stream);
     SK_WG_CASE(1, 1) SK_WG_CASE(1, 4) SK_WG_CASE(1, 12)
@@ -263,9 +294,11 @@ hipError_t launch_wgrad_f32(const float *x, const float *dy, float *dw, float *d
 {
     hipError_t e = launch_wgrad_dt<0>(x, dy, dw, scratch, n, c_in, H, W, c_out, k, d, stream);
     if (e != hipSuccess) return e;
-    if (db)
-        hipLaunchKernelGGL(bias_grad_kernel, dim3(c_out), dim3(256), 0, stream, dy, db, n, c_out,
-                           (long)(H - (k - 1) * d) * (W - (k - 1) * d));
+    if (db) {                                   // the private dW copies in scratch have been consumed (stream order)
+        const long plane = (long)(H - (k - 1) * d) * (W - (k - 1) * d);
+        hipLaunchKernelGGL(bias_grad_kernel, dim3(BG_SLICES, c_out), dim3(256), 0, stream, dy, scratch, n, c_out, plane, BG_SLICES);
+        hipLaunchKernelGGL(bias_grad_finish_kernel, dim3((c_out + 255) / 256), dim3(256), 0, stream, scratch, db, c_out, BG_SLICES);
+    }
     return hipGetLastError();
 }
 
@@ -277,7 +310,12 @@ hipError_t launch_wgrad_h(const void *x, const void *dy, float *dw, float *db, f
     hipError_t e = dtype == 1 ? launch_wgrad_dt<1>(x, dy, dw, scratch, n, c_in, H, W, c_out, k, d, stream)
                               : launch_wgrad_dt<2>(x, dy, dw, scratch, n, c_in, H, W, c_out, k, d, stream);
     if (e != hipSuccess) return e;
-    if (db) return launch_bias_grad_h(dy, db, dtype, n, c_out, (long)(H - (k - 1) * d) * (W - (k - 1) * d), stream);
+    if (db) {
+        e = launch_bias_grad_h(dy, scratch, dtype, n, c_out, (long)(H - (k - 1) * d) * (W - (k - 1) * d), BG_SLICES, stream);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(bias_grad_finish_kernel, dim3((c_out + 255) / 256), dim3(256), 0, stream, scratch, db, c_out, BG_SLICES);
+        return hipGetLastError();
+    }
     return hipSuccess;
 }
 

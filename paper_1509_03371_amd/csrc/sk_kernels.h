@@ -79,7 +79,8 @@ hipError_t launch_maxpool_bwd_h(const void *dy, const void *tap, const void *rel
                                 long planes8, int H, int W, int Ho, int Wo, int k, int d, hipStream_t stream);
 hipError_t launch_tap_to_index_h(const void *tap, int32_t *idx, int n, int c, int Ho, int Wo, int W, int k, int d, int s,
                                  hipStream_t stream);
-hipError_t launch_bias_grad_h(const void *dy, float *db, int dtype, int n, int c, long plane, hipStream_t stream);
+// stage 1 of the bias gradient: part[(map) * slices + slice] (8 * ceil(c/8) maps); see kernels_wgrad_f32.hip
+hipError_t launch_bias_grad_h(const void *dy, float *part, int dtype, int n, int c, long plane, int slices, hipStream_t stream);
 
 // ---- fused inference head: 1x1 conv + ReLU, 1x1 conv, per-pixel softmax (see kernels_head.hip) -------------
 struct HeadArgs {
