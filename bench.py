@@ -29,8 +29,8 @@ METRIC = "labelled pixels/sec SK-Net fwd (and fwd+bwd) 1 GPU; conv % MFMA peak"
 # read for stream_copy_kernel on 1 GiB (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); the runs and their
 # figures are in profiles/sknet_c{2,3}_forward_hbm_traffic_pmc.txt and
 # profiles/stream_copy_1gib_pmc_calibration.txt.  KiB: (fetch x 2, write).
-TRAFFIC_KIB = {"c2": (2.0 * (35732.9 + 34228.8 + 30794.4) / 3, (78159.3 + 70656.6 + 58114.7) / 3),
-               "c3": (2.0 * (482197.5 + 475659.7 + 456620.1) / 3, (865863.4 + 843289.0 + 798768.0) / 3)}
+TRAFFIC_KIB = {"c2": (2.0 * (35737.6 + 34232.2 + 30812.6) / 3, (78928.0 + 70746.1 + 58095.5) / 3),
+               "c3": (2.0 * (481764.7 + 475194.9 + 454771.8) / 3, (869381.1 + 845296.9 + 798768.0) / 3)}
 
 
 def build_net(B, S, dtype, n, H, W, training):
@@ -248,7 +248,7 @@ def main():
                          "traffic_unit": "bytes beyond L2 per launch (read + written), from profiles/",
                          "algorithmic_bytes": int(r["conv_alg_bytes"]),
                          "kernel": "48->48 k4 SK convolutions at d=2,4,8 (%s)"
-                                   % ("conv_f32_pf_kernel<3,1,4,4,2,false>" if dtype == "f32" else "conv_h_ring_kernel<bf16,4,3,MAP4,8,false,3,true>")},
+                                   % ("conv_f32_pf_kernel<3,1,4,4,2,false>" if dtype == "f32" else "conv_h_ring_kernel<bf16,4,3,MAP4,8,false,3,true,4>")},
             "forward_tflops": round(r["forward_tflops"], 2),
             "pool_gbs": round(r["pool_gbs"], 1), "pool_frac_of_hbm_peak": round(r["pool_gbs"] / HBM_PEAK_GBS, 4),
             "step_ms": r["step_ms"],
