@@ -282,7 +282,7 @@ def main():
     if args.workload == "c2" and not args.no_cpu_baseline:
         from oracle import nets as ON
         reps, t_cpu = 0, 0.0
-        while t_cpu < 10.0 and reps < 4:
+        while t_cpu < 10.0 and reps < 40:
             t0 = time.perf_counter()
             ON.sknet_forward(r["img"], r["layers"], r["ws"], r["bs"])
             t_cpu += time.perf_counter() - t0

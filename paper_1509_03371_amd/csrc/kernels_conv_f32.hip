@@ -467,12 +467,28 @@ static hipError_t launch_conv_f32_pf_t(const ConvF32Args &a, hipStream_t stream)
     return launch_conv_f32_pf_z<NT, RW, KS, CC, NCG, false>(a, stream);
 }
 
+// Workgroup tiles of a launch with NT map tiles per workgroup and 4*RW rows per tile.  A layer with
+// fewer tiles than about three per CU leaves CUs idle; the dispatch below then trades operand reuse
+// for parallelism (fewer maps per workgroup, fewer rows per tile).
+constexpr long CONV_FEW_TILES = 768;
+static long conv_f32_tiles(const ConvF32Args &a, int nt, int rw)
+{
+    const long gx = (a.Wo + CONV_TX - 1) / CONV_TX;
+    const long gy = (long)a.d * ((a.Ho / a.d + 4 * rw) / (4 * rw));       // row phases x row tiles, rounded up
+    const long nblocks = (a.n_pad / 16 + nt - 1) / nt;
+    return gx * gy * a.n * nblocks;
+}
+
 template <int NT>
 static hipError_t launch_conv_f32_nt(const ConvF32Args &a, hipStream_t stream)
 {
     const int halo = (a.k - 1) * a.d;
     if (a.k == 1) return launch_conv_f32_pf_t<NT, 2, 1, 16, 1>(a, stream);
-    if (a.k == 3 && halo <= 64) return launch_conv_f32_pf_t<NT, 2, 3, 4, 2>(a, stream);
+    if (a.k == 3 && halo <= 64) {
+        // small maps (the deep U-Net levels): 4-row tiles double the number of workgroups
+        if (conv_f32_tiles(a, NT, 2) < CONV_FEW_TILES) return launch_conv_f32_pf_t<NT, 1, 3, 4, 2>(a, stream);
+        return launch_conv_f32_pf_t<NT, 2, 3, 4, 2>(a, stream);
+    }
     if (a.k == 4 && halo <= 64) {
         // 4-row tiles: twice as many workgroups as with 8 rows, which balances the 256 CUs better
         // at 512^2 (measured: 0.24 ms instead of 0.33 ms per 48->48 layer)
@@ -489,7 +505,13 @@ hipError_t launch_conv_f32(const ConvF32Args &a, hipStream_t stream)
     if (tiles == 1) return launch_conv_f32_nt<1>(a, stream);
     if (tiles == 2) return launch_conv_f32_nt<2>(a, stream);
     const int pad3 = (tiles + 2) / 3 * 3, pad4 = (tiles + 3) / 4 * 4;
-    if (pad3 < pad4) return launch_conv_f32_nt<3>(a, stream);
+    const int nt_wide = pad3 < pad4 ? 3 : 4;
+    // many maps on a small image: as few maps per workgroup as it takes to fill the GPU
+    if (conv_f32_tiles(a, nt_wide, 1) < CONV_FEW_TILES) {
+        if (conv_f32_tiles(a, 2, 1) >= CONV_FEW_TILES) return launch_conv_f32_nt<2>(a, stream);
+        return launch_conv_f32_nt<1>(a, stream);
+    }
+    if (nt_wide == 3) return launch_conv_f32_nt<3>(a, stream);
     return launch_conv_f32_nt<4>(a, stream);
 }
 

@@ -1001,7 +1001,9 @@ bool conv_h_supported(int k, int d)
 hipError_t launch_conv_h(const ConvHArgs &a, hipStream_t stream)
 {
     if (!conv_h_supported(a.k, a.d) || a.Ho < 1 || a.Wo < 1 || a.c8_in < 1 || a.c_out < 1) return hipErrorInvalidValue;
-    const int mt = conv_h_mt(a.c_out, a.k);
+    // the packed weights were laid out for this many map tiles per group (0 = the default choice)
+    const int mt = a.mt > 0 ? a.mt : conv_h_mt(a.c_out, a.k);
+    if (mt > 4 || (a.k == 3 && mt > 3)) return hipErrorInvalidValue;
     if (a.dtype == 1) {
         switch (mt) {
         case 1: return launch_conv_h_mt<1, 1>(a, stream);
@@ -1062,9 +1064,21 @@ __global__ void pack_weights_h_kernel(const float *w, unsigned short *wp, int c_
 }
 
 // size in 16-bit elements of the packing of a GEMM with gemm_m output maps and gemm_c8 input octets
-long packed_h_elems(int gemm_m, int gemm_c8, int k)
+// Map tiles per workgroup for a forward layer with this output size.  Many maps on a small image (the
+// deep U-Net levels): with one persistent workgroup per CU a layer wants at least about 160 tiles, and
+// fewer map tiles per workgroup give more of them (each then re-reads the input, so not more than needed).  The weights must be packed for the same value.
+int conv_h_pick_mt(int c_out, int k, int n, int Ho, int Wo)
 {
-    const int mt = conv_h_mt(gemm_m, k);
+    int mt = conv_h_mt(c_out, k);
+    const long sp = (long)((Wo + CH_TX - 1) / CH_TX) * ((Ho + 3) / 4) * n;   // tiles of 4 rows at least
+    const int m_tiles = (c_out + 15) / 16;
+    while (mt > 1 && sp * ((m_tiles + mt - 1) / mt) < 160) --mt;   // measured on the U-Net: 96..160 best, 256 worse
+    return mt;
+}
+
+long packed_h_elems(int gemm_m, int gemm_c8, int k, int mt)
+{
+    if (mt <= 0) mt = conv_h_mt(gemm_m, k);
     const int m_tiles = (gemm_m + 15) / 16, mgroups = (m_tiles + mt - 1) / mt;
     const bool map4 = k == 4;
     const int OC = map4 ? 1 : 4, CS = map4 ? 1 : k;
@@ -1073,13 +1087,13 @@ long packed_h_elems(int gemm_m, int gemm_c8, int k)
 }
 
 hipError_t launch_pack_weights_h(const float *w_oihw, void *wp, int dtype, int c_out, int c_in, int k,
-                                 int flip_transpose, hipStream_t stream)
+                                 int flip_transpose, int mt, hipStream_t stream)
 {
     const int gemm_m = flip_transpose ? c_in : c_out;
     const int gemm_c8 = ((flip_transpose ? c_out : c_in) + 7) / 8;
-    const long total = packed_h_elems(gemm_m, gemm_c8, k);
+    if (mt <= 0) mt = conv_h_mt(gemm_m, k);
+    const long total = packed_h_elems(gemm_m, gemm_c8, k, mt);
     const int blocks = (int)((total + 255) / 256 < 2048 ? (total + 255) / 256 : 2048);
-    const int mt = conv_h_mt(gemm_m, k);
     if (dtype == 1)
         hipLaunchKernelGGL(pack_weights_h_kernel<1>, dim3(blocks), dim3(256), 0, stream, w_oihw,
                            static_cast<unsigned short *>(wp), c_out, c_in, k, flip_transpose, mt, k == 4 ? 1 : 0, gemm_m, gemm_c8, total);

@@ -56,6 +56,7 @@ struct ConvParams {
     float *wp_fwd = nullptr, *wp_bwd = nullptr;       // fp32 packings
     float *wp16_fwd = nullptr, *wp16_bwd = nullptr;   // 16-bit packings (typed loosely; see kernels_conv_h.hip)
     float *dw = nullptr, *db = nullptr, *vw = nullptr, *vb = nullptr;
+    int mt16 = 0;                         // 16-bit forward packing: map tiles per workgroup (0 = default)
     int n_pad = 0, rows_fwd = 0;          // forward packing: [rows_fwd][n_pad]
     int n_pad_bwd = 0, rows_bwd = 0;      // data-gradient packing: [rows_bwd][n_pad_bwd]
     long wcount() const { return (long)c_out * c_in * k * k; }
@@ -90,9 +91,9 @@ inline sk_status repack_conv(ConvParams &c, bool training, int dtype, hipStream_
         if (training && c.wp_bwd)
             SK_HIP(sk::launch_pack_weights_f32(c.w_dev, c.wp_bwd, c.c_out, c.c_in, c.k, 1, c.rows_bwd, c.n_pad_bwd, stream));
     } else {
-        SK_HIP(sk::launch_pack_weights_h(c.w_dev, c.wp16_fwd, dtype, c.c_out, c.c_in, c.k, 0, stream));
+        SK_HIP(sk::launch_pack_weights_h(c.w_dev, c.wp16_fwd, dtype, c.c_out, c.c_in, c.k, 0, c.mt16, stream));
         if (training && c.wp16_bwd)
-            SK_HIP(sk::launch_pack_weights_h(c.w_dev, c.wp16_bwd, dtype, c.c_out, c.c_in, c.k, 1, stream));
+            SK_HIP(sk::launch_pack_weights_h(c.w_dev, c.wp16_bwd, dtype, c.c_out, c.c_in, c.k, 1, 0, stream));
     }
     return SK_OK;
 }
@@ -122,7 +123,7 @@ inline sk_status alloc_conv(ConvParams &c, bool training, int dtype = SK_F32)
         SK_TRY(alloc_f(&c.wp_fwd, (long)c.rows_fwd * c.n_pad));
         if (training) SK_TRY(alloc_f(&c.wp_bwd, (long)c.rows_bwd * c.n_pad_bwd));
     } else {   // 16-bit elements, allocated in floats
-        SK_TRY(alloc_f(&c.wp16_fwd, (sk::packed_h_elems(c.c_out, (c.c_in + 7) / 8, c.k) + 1) / 2));
+        SK_TRY(alloc_f(&c.wp16_fwd, (sk::packed_h_elems(c.c_out, (c.c_in + 7) / 8, c.k, c.mt16) + 1) / 2));
         if (training) SK_TRY(alloc_f(&c.wp16_bwd, (sk::packed_h_elems(c.c_in, (c.c_out + 7) / 8, c.k) + 1) / 2));
     }
     if (training) {
@@ -149,6 +150,7 @@ inline sk::ConvHArgs conv_h_args(const ConvParams &c, int dtype, const void *x, 
     a.k = c.k; a.d = d; a.in_off = 0; a.Ho = out.h; a.Wo = out.w; a.relu = relu; a.out_f32 = out_f32 ? 1 : 0;
     a.c8_out_total = (out.c + 7) / 8; a.o8_off = 0; a.OH = out.h; a.OW = out.w;
     a.oy_mul = 1; a.oy_off = 0; a.ox_mul = 1; a.ox_off = 0;
+    a.mt = c.mt16;
     return a;
 }
 

@@ -52,6 +52,7 @@ struct ConvHArgs {
     int Ho, Wo;
     int relu, out_f32;
     int c8_out_total, o8_off, OH, OW, oy_mul, oy_off, ox_mul, ox_off;
+    int mt;               // map tiles per workgroup the weights were packed for; 0 = default for (c_out, k)
     // filled in by the launcher
     int m_tiles, mgroups, nchunks, xtiles, tiles_hi, tiles_lo, rem, ytiles_total, total_tiles;
     const void *zeros;    // >= 16 bytes of zeros in device memory
@@ -59,11 +60,13 @@ struct ConvHArgs {
 bool conv_h_supported(int k, int d);
 hipError_t launch_conv_h(const ConvHArgs &a, hipStream_t stream);
 // 16-bit elements of the packed weights of a GEMM with gemm_m output maps and gemm_c8 input octets
-long packed_h_elems(int gemm_m, int gemm_c8, int k);
+long packed_h_elems(int gemm_m, int gemm_c8, int k, int mt = 0);
+// map tiles per workgroup (mt) that suit a forward layer of this output size; pass it to the packing too
+int conv_h_pick_mt(int c_out, int k, int n, int Ho, int Wo);
 // forward packing (flip_transpose = 0: gemm_m = c_out, input octets of c_in) or data-gradient
 // packing (flip_transpose = 1: gemm_m = c_in, input octets of c_out) from OIHW fp32 master weights
 hipError_t launch_pack_weights_h(const float *w_oihw, void *wp, int dtype, int c_out, int c_in, int k,
-                                 int flip_transpose, hipStream_t stream);
+                                 int flip_transpose, int mt, hipStream_t stream);
 
 // ---- HBM-bound layers on the octet layout (dtype 1 = bf16, 2 = fp16) ------------------------------------
 // fp32 NCHW -> octets with optional mirror padding (top = left = 0 and ho = h, wo = w: plain conversion)

@@ -302,6 +302,17 @@ sk_status unet_plan(unet_t *net, int32_t n, int32_t h_in, int32_t w_in)
         net->stages.push_back({"logits", z, net->logits});
         net->out_dims = z;
     }
+    if (half) {
+        // map tiles per workgroup that suit each layer's output size (the deep levels are small)
+        for (const auto &op : net->ops) {
+            if (op.kind == 0) {
+                ConvParams &c = net->convs[op.param];
+                c.mt16 = sk::conv_h_pick_mt(c.c_out, c.k, n, op.out.h, op.out.w);
+            } else if (op.kind == 2) {
+                for (auto &t : net->ups[op.param].tap) t.mt16 = sk::conv_h_pick_mt(net->ups[op.param].c_out, 1, n, op.in.h, op.in.w);
+            }
+        }
+    }
     for (auto &c : net->convs) {
         if (st != SK_OK) break;
         if (half && !sk::conv_h_supported(c.k, 1)) st = fail(SK_EUNSUPPORTED, "U-Net: kernel size %d is not built for 16-bit storage", c.k);
