@@ -1,0 +1,45 @@
+"""GPU: the forward pass can be recorded into a HIP graph (it allocates nothing, clears nothing with
+memset nodes and never synchronises) and every replay equals the eager result on new input."""
+import numpy as np
+import pytest
+import torch
+
+import sk_synth as S
+from oracle import nets as ON
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_forward_replays_from_a_hip_graph(dtype):
+    from paper_1509_03371_amd import binding as B
+    layers = S.sknet_layers(width=16, hidden=40)
+    ws, bs = S.he_normal_weights(layers, 1, 77, bias_scale=0.1)
+    net = B.SKNet(layers, 1, 2, dtype=dtype)
+    for i, (w, b) in enumerate(zip(ws, bs)):
+        net.set_weights(i, w, b)
+    n, h, w = 2, 70, 90
+    net.plan(n, h, w, pad=True)
+    img = torch.zeros((n, 1, h, w), dtype=torch.float32, device="cuda")
+    prob = torch.empty(net.out_shape(), dtype=torch.float32, device="cuda")
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        net.forward(img, prob, s)                      # first call eagerly: one-time set-up happens here
+        s.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s):
+            net.forward(img, prob, torch.cuda.current_stream())
+        for rep in range(3):
+            host = S.uniform_image(n, 1, h, w, 300 + rep)
+            img.copy_(torch.from_numpy(host))
+            net.forward(img, prob, torch.cuda.current_stream())     # the program's own eager work between replays
+            torch.cuda.current_stream().synchronize()
+            eager = prob.clone()
+            prob.zero_()
+            g.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(prob, eager), rep
+            if rep == 0:
+                ref = ON.sknet_forward(host, layers, ws, bs)
+                assert np.abs(prob.cpu().numpy() - ref).max() <= (1e-4 if dtype == "f32" else 2e-2)
+    net.close()
