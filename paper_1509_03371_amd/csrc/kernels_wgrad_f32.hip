@@ -13,6 +13,8 @@
 // MFMA roles: A[m = output map][kk = pixel] = dY, B[kk = pixel][n = (c,i,j)] = X shifted by the
 // tap, D[m][n] = dW laid out exactly as OIHW.  Wave w of a workgroup owns MB row tiles (16 output
 // maps each) times NB column tiles (16 (c,i,j) triples each); blockIdx.y selects further groups.
+#include <type_traits>
+
 #include "sk_kernels.h"
 
 namespace sk {
@@ -29,6 +31,9 @@ template <int DT> __device__ __forceinline__ float up16(unsigned u);
 template <> __device__ __forceinline__ float up16<0>(unsigned u) { return __uint_as_float(u); }
 template <> __device__ __forceinline__ float up16<1>(unsigned u) { return __uint_as_float(u << 16); }
 template <> __device__ __forceinline__ float up16<2>(unsigned u) { return (float)__builtin_bit_cast(_Float16, (unsigned short)u); }
+// a staged operand (fp32 as it is, 16-bit storage widened) as the MFMA's fp32 input
+template <int DT> __device__ __forceinline__ float staged(float f) { return f; }
+template <int DT> __device__ __forceinline__ float staged(unsigned short u) { return up16<DT>((unsigned)u); }
 
 struct WgradArgs {
     const void *x, *dy;     // fp32 NCHW planar (DT = 0) or 16-bit octet layout (DT = 1 bf16, 2 fp16)
@@ -45,8 +50,11 @@ __global__ __launch_bounds__(256) void wgrad_f32_kernel(WgradArgs a)
     extern __shared__ float smem[];
     const int k = a.k, d = a.d, K = a.c_in * k * k;
     const int m_rows = a.MTo * 16;
-    float *dys = smem;                                   // [m_rows][WG_DYP]
-    float *xs = dys + m_rows * WG_DYP;                   // [c_in*k][xpitch]
+    // staged operands: fp32, or (16-bit storage types) the raw 16-bit values, widened when they are read
+    // for the MFMA -- half the LDS, so two workgroups fit a CU and one stages while the other multiplies
+    typedef typename std::conditional<DT == 0, float, unsigned short>::type stage_t;
+    stage_t *dys = reinterpret_cast<stage_t *>(smem);    // [m_rows][WG_DYP]
+    stage_t *xs = dys + m_rows * WG_DYP;                 // [c_in*k][xpitch]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l16 = lane & 15, g = lane >> 4;
     const int PW = WG_SEG + (k - 1) * d;
 
@@ -114,7 +122,7 @@ __global__ __launch_bounds__(256) void wgrad_f32_kernel(WgradArgs a)
                 const bool ok = oc < c8o && x0 + lane < a.Wo;
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
-                    dys[(oc * 8 + e) * WG_DYP + lane] = ok ? up16<DT>((u[e >> 1] >> ((e & 1) * 16)) & 0xffffu) : 0.f;
+                    dys[(oc * 8 + e) * WG_DYP + lane] = ok ? (unsigned short)((u[e >> 1] >> ((e & 1) * 16)) & 0xffffu) : (unsigned short)0;
             }
             for (int rid = wave; rid < c8i * k; rid += 4) {
                 const int oc = rid / k, i = rid - oc * k;
@@ -126,7 +134,7 @@ __global__ __launch_bounds__(256) void wgrad_f32_kernel(WgradArgs a)
                     const bool ok = x0 + xc < a.W;
 #pragma unroll
                     for (int e = 0; e < 8; ++e)
-                        xs[((oc * 8 + e) * k + i) * a.xpitch + xc] = ok ? up16<DT>((u[e >> 1] >> ((e & 1) * 16)) & 0xffffu) : 0.f;
+                        xs[((oc * 8 + e) * k + i) * a.xpitch + xc] = ok ? (unsigned short)((u[e >> 1] >> ((e & 1) * 16)) & 0xffffu) : (unsigned short)0;
                 }
             }
         }
@@ -137,11 +145,11 @@ __global__ __launch_bounds__(256) void wgrad_f32_kernel(WgradArgs a)
 #pragma unroll
             for (int m = 0; m < MB; ++m) {
                 const int row = (mo0 + m) * 16 + l16;
-                av[m] = (mo0 + m < a.MTo) ? dys[row * WG_DYP + p + g] : 0.f;
+                av[m] = (mo0 + m < a.MTo) ? staged<DT>(dys[row * WG_DYP + p + g]) : 0.f;
             }
 #pragma unroll
             for (int q = 0; q < NB; ++q) {
-                const float bv = xs[xoff[q] + p];
+                const float bv = staged<DT>(xs[xoff[q] + p]);
 #pragma unroll
                 for (int m = 0; m < MB; ++m)
                     acc[m][q] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[m], bv, acc[m][q], 0, 0, 0);
@@ -264,7 +272,7 @@ static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, floa
     const int PW = WG_SEG + (k - 1) * d;
     a.xpitch = (PW + 31) / 32 * 32 + 4;
     const int x_rows = (DT == 0 ? c_in : (c_in + 7) / 8 * 8) * k;
-    const size_t smem = sizeof(float) * ((size_t)a.MTo * 16 * WG_DYP + (size_t)x_rows * a.xpitch);
+    const size_t smem = (DT == 0 ? sizeof(float) : sizeof(unsigned short)) * ((size_t)a.MTo * 16 * WG_DYP + (size_t)x_rows * a.xpitch);
     if (smem > 150 * 1024) return hipErrorInvalidValue;
     // as many persistent workgroups as fit on the GPU at once (more would only add private copies
     // for the reduction to read): LDS decides
