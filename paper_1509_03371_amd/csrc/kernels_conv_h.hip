@@ -882,14 +882,24 @@ static int device_cus()
     return cus;
 }
 
-// a few KB of zeros in device memory, read in place of samples outside the image
+// a few KB of zeros in device memory, read in place of samples outside the image; one page per
+// device, allocated on first use and kept until the process ends
 static const void *zero_page()
 {
-    static void *page = nullptr;
-    if (!page) {
-        if (hipMalloc(&page, 4096) != hipSuccess || hipMemset(page, 0, 4096) != hipSuccess) page = nullptr;
+    constexpr int kMaxDevices = 64;
+    static void *pages[kMaxDevices] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    if (!pages[dev]) {
+        void *page = nullptr;
+        if (hipMalloc(&page, 4096) != hipSuccess) return nullptr;
+        if (hipMemset(page, 0, 4096) != hipSuccess) {
+            (void)hipFree(page);
+            return nullptr;
+        }
+        pages[dev] = page;
     }
-    return page;
+    return pages[dev];
 }
 
 // LDS bytes of the ring kernel: S stages (+ resident weights) + bias + y-tile table
