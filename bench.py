@@ -184,6 +184,10 @@ def measured_peaks(torch, B):
     peaks = {"mfma_f32_tflops": round(B.sk_probe_mfma("f32", 100000), 1),
              "mfma_bf16_tflops": round(B.sk_probe_mfma("bf16", 100000), 1),
              "mfma_f16_tflops": round(B.sk_probe_mfma("f16", 100000), 1),
+             # same loop, every MFMA with hashed operands of its own: the rate under the power limit
+             "mfma_f32_tflops_varied_operands": round(B.sk_probe_mfma("f32", 100000, varied=True), 1),
+             "mfma_bf16_tflops_varied_operands": round(B.sk_probe_mfma("bf16", 100000, varied=True), 1),
+             "mfma_f16_tflops_varied_operands": round(B.sk_probe_mfma("f16", 100000, varied=True), 1),
              "copy_gbs_1gib": round(B.sk_probe_copy(src, dst, 10), 1)}
     del src, dst
     torch.cuda.empty_cache()

@@ -220,12 +220,15 @@ sk_status unet_get_activation(unet_t *net, const char *stage, float *nchw_host, 
  * sk_probe_mfma: every wave of a grid of 4 x (number of CUs) workgroups of 256 threads issues
  *   iters x 8 independent MFMA instructions of the shape the convolutions use for dtype
  *   (sk_dtype: fp32 16x16x4, bf16 / fp16 16x16x32) with no memory traffic; *tflops (HOST) receives
- *   the sustained rate.  1 <= iters <= 2^22.  Allocates and frees a small device buffer.
+ *   the sustained rate.  operands = 0: all MFMAs multiply the same two registers (a smooth value per
+ *   lane, and ones); operands = 1: each of the 8 has operands of its own with hashed bit patterns in
+ *   [-1, 1), the switching activity of real data -- the rate then shows what the chip sustains
+ *   under its power limit.  1 <= iters <= 2^22.  Allocates and frees a small device buffer.
  * sk_probe_copy: copies bytes (a positive multiple of 16) from src_dev to dst_dev (DEVICE, 16-byte
  *   aligned, caller-owned, non-overlapping) reps times with a 16-bytes-per-lane grid-stride
  *   kernel; *gb_per_s (HOST) receives (bytes read + bytes written) / time.
  * Both enqueue on hip_stream, time with HIP events on that stream and synchronise it. */
-sk_status sk_probe_mfma(int32_t dtype, int32_t iters, void *hip_stream, double *tflops);
+sk_status sk_probe_mfma(int32_t dtype, int32_t operands, int32_t iters, void *hip_stream, double *tflops);
 sk_status sk_probe_copy(const void *src_dev, void *dst_dev, uint64_t bytes, int32_t reps, void *hip_stream,
                         double *gb_per_s);
 

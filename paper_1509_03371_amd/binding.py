@@ -67,7 +67,7 @@ _SIGS = {
     "unet_plan": [_vp, _i32, _i32, _i32],
     "unet_forward": [_vp, _vp, _vp, _vp],
     "unet_get_activation": [_vp, C.c_char_p, _fp, _ip],
-    "sk_probe_mfma": [_i32, _i32, _vp, C.POINTER(C.c_double)],
+    "sk_probe_mfma": [_i32, _i32, _i32, _vp, C.POINTER(C.c_double)],
     "sk_probe_copy": [_vp, _vp, C.c_uint64, _i32, _vp, C.POINTER(C.c_double)],
 }
 for _name, _args in _SIGS.items():
@@ -121,10 +121,11 @@ def layers_to_c(layers):
     return arr
 
 
-def sk_probe_mfma(dtype, iters=20000, stream=None):
-    """Sustained TFLOP/s of a bare MFMA issue loop of the shape used for dtype ('f32'|'bf16'|'f16')."""
+def sk_probe_mfma(dtype, iters=20000, stream=None, varied=False):
+    """Sustained TFLOP/s of a bare MFMA issue loop of the shape used for dtype ('f32'|'bf16'|'f16');
+    varied=True gives every MFMA operands of its own with hashed bit patterns (real-data switching activity)."""
     out = C.c_double(0.0)
-    _check(lib.sk_probe_mfma(DTYPES[dtype], iters, _stream(stream), C.byref(out)))
+    _check(lib.sk_probe_mfma(DTYPES[dtype], 1 if varied else 0, iters, _stream(stream), C.byref(out)))
     return out.value
 
 

@@ -761,21 +761,34 @@ __global__ __launch_bounds__(CH_THREADS + 64 * NP) void conv_h_ring_kernel(ConvH
             }
             return;
         }
+        // One tile per trip, so that the accumulators live inside the trip only: a wave whose 16
+        // columns lie right of the image (the ragged last x tile) then skips the tile's MFMAs and
+        // stores as a whole and only keeps the barriers, and its SIMD is left to the other wave.
         TilePos cur = position(ccur);
-        int ch = 0, ctiles = 0;
-        for (int q = 0; q < total_chunks; ++q) {
-            block_sync_lds();
-            compute(q % S, ch);
-            if (ch == a.nchunks - 1) {
-                if (HAS_MASK || a.out_f32 || (R & 1)) epilogue(cur);
-                else epilogue16(cur);
-                ch = 0;
-                if (++ctiles < my_tiles) {
-                    advance(ccur);
-                    cur = position(ccur);
+        int st = 0;
+        for (int ctile = 0; ctile < my_tiles; ++ctile) {
+            const bool idle = __builtin_amdgcn_readfirstlane((int)(cur.x0 + wave * 16 >= a.Wo)) != 0;
+            if (idle) {
+                for (int ch = 0; ch < a.nchunks; ++ch) {
+                    block_sync_lds();
+                    st = st + 1 == S ? 0 : st + 1;
                 }
             } else {
-                ++ch;
+#pragma unroll
+                for (int y = 0; y < R; ++y)
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) acc[y][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+                for (int ch = 0; ch < a.nchunks; ++ch) {
+                    block_sync_lds();
+                    compute(st, ch);
+                    st = st + 1 == S ? 0 : st + 1;
+                }
+                if (HAS_MASK || a.out_f32 || (R & 1)) epilogue(cur);
+                else epilogue16(cur);
+            }
+            if (ctile + 1 < my_tiles) {
+                advance(ccur);
+                cur = position(ccur);
             }
         }
         return;

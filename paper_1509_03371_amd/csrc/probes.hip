@@ -11,8 +11,6 @@ using skh::fail;
 namespace {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
 typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kAcc = 8;   // independent accumulators per wave: hides the MFMA result latency
@@ -23,34 +21,75 @@ constexpr int kAcc = 8;   // independent accumulators per wave: hides the MFMA r
 // allocator shuttles the loop-carried accumulators between register files and the loop no longer
 // measures the matrix pipe.  Eight independent accumulators separate dependent instructions by
 // far more than the pipe's depth, and the s_nop pair covers the read of the results afterwards.
+// VARIED = false: every MFMA multiplies the same two registers (one smooth value per lane, and ones),
+// the least switching activity the pipe can see.  VARIED = true: each of the eight MFMAs of a trip
+// has operands of its own, filled with hashed bit patterns that decode to values in [-1, 1); that is
+// what real activations and weights look like to the multipliers, and the rate it sustains is the
+// one a kernel with real data can be held against when the chip runs into its power limit.
+__device__ __forceinline__ unsigned probe_hash(unsigned x)
+{
+    x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+    return x;
+}
+// a 16-bit float in [-1, 1) with hashed sign and mantissa (exponent field of 0.5 .. 1 minus a few steps)
 template <int DT>
+__device__ __forceinline__ unsigned probe_half_bits(unsigned h)
+{
+    if constexpr (DT == SK_BF16) return ((h & 1u) << 15) | ((0x7cu + ((h >> 1) & 3u)) << 7) | ((h >> 3) & 0x7fu);
+    else return ((h & 1u) << 15) | ((0x0cu + ((h >> 1) & 3u)) << 10) | ((h >> 3) & 0x3ffu);
+}
+
+template <int DT, bool VARIED>
 __global__ void __launch_bounds__(256) mfma_issue_kernel(float *out, int iters)
 {
+    constexpr int NOP = VARIED ? kAcc : 1;       // distinct operand pairs
     floatx4 acc[kAcc];
 #pragma unroll
     for (int i = 0; i < kAcc; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
     const float seed = (float)threadIdx.x * 0.001f;
+    const unsigned tid = blockIdx.x * blockDim.x + threadIdx.x;
     if constexpr (DT == SK_F32) {
-        const float a = seed, b = 1.0f;
-        for (int it = 0; it < iters; ++it) {
+        float a[NOP], b[NOP];
 #pragma unroll
-            for (int i = 0; i < kAcc; ++i) asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" : "+v"(acc[i]) : "v"(a), "v"(b));
+        for (int i = 0; i < NOP; ++i) {
+            if constexpr (VARIED) {
+                a[i] = __uint_as_float(0x3f800000u | (probe_hash(tid * 16 + i) >> 9)) - 1.5f;        // [-0.5, 0.5)
+                b[i] = __uint_as_float(0x3f800000u | (probe_hash(tid * 16 + 8 + i) >> 9)) - 1.5f;
+            } else {
+                a[i] = seed;
+                b[i] = 1.0f;
+            }
         }
-    } else if constexpr (DT == SK_BF16) {
-        bf16x8 a, b;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) { a[i] = (__bf16)seed; b[i] = (__bf16)1.0f; }
         for (int it = 0; it < iters; ++it) {
 #pragma unroll
-            for (int i = 0; i < kAcc; ++i) asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc[i]) : "v"(a), "v"(b));
+            for (int i = 0; i < kAcc; ++i) asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" : "+v"(acc[i]) : "v"(a[i % NOP]), "v"(b[i % NOP]));
         }
     } else {
-        halfx8 a, b;
+        uintx4 a[NOP], b[NOP];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) { a[i] = (_Float16)seed; b[i] = (_Float16)1.0f; }
+        for (int i = 0; i < NOP; ++i)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if constexpr (VARIED) {
+                    const unsigned ha = probe_hash((tid * 16 + i) * 8 + e), hb = probe_hash((tid * 16 + 8 + i) * 8 + e);
+                    a[i][e] = probe_half_bits<DT>(ha & 0xffffu) | (probe_half_bits<DT>(ha >> 16) << 16);
+                    b[i][e] = probe_half_bits<DT>(hb & 0xffffu) | (probe_half_bits<DT>(hb >> 16) << 16);
+                } else if constexpr (DT == SK_BF16) {
+                    const unsigned sa = __builtin_bit_cast(unsigned short, (__bf16)seed), sb = __builtin_bit_cast(unsigned short, (__bf16)1.0f);
+                    a[i][e] = sa | (sa << 16);
+                    b[i][e] = sb | (sb << 16);
+                } else {
+                    const unsigned sa = __builtin_bit_cast(unsigned short, (_Float16)seed), sb = __builtin_bit_cast(unsigned short, (_Float16)1.0f);
+                    a[i][e] = sa | (sa << 16);
+                    b[i][e] = sb | (sb << 16);
+                }
+            }
         for (int it = 0; it < iters; ++it) {
 #pragma unroll
-            for (int i = 0; i < kAcc; ++i) asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+v"(acc[i]) : "v"(a), "v"(b));
+            for (int i = 0; i < kAcc; ++i) {
+                if constexpr (DT == SK_BF16) asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc[i]) : "v"(a[i % NOP]), "v"(b[i % NOP]));
+                else asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+v"(acc[i]) : "v"(a[i % NOP]), "v"(b[i % NOP]));
+            }
         }
     }
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
@@ -92,10 +131,11 @@ sk_status time_launches(hipStream_t stream, int reps, F launch, float *avg_ms)
 
 extern "C" {
 
-sk_status sk_probe_mfma(int32_t dtype, int32_t iters, void *hip_stream, double *tflops)
+sk_status sk_probe_mfma(int32_t dtype, int32_t operands, int32_t iters, void *hip_stream, double *tflops)
 {
     if (!tflops || iters < 1 || iters > (1 << 22)) return fail(SK_EINVAL, "probe_mfma: bad arguments");
     if (dtype != SK_F32 && dtype != SK_BF16 && dtype != SK_F16) return fail(SK_EINVAL, "probe_mfma: unknown dtype %d", dtype);
+    if (operands != 0 && operands != 1) return fail(SK_EINVAL, "probe_mfma: operands must be 0 (constant) or 1 (varied)");
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     int dev = 0, cus = 0;
     SK_HIP(hipGetDevice(&dev));
@@ -104,11 +144,11 @@ sk_status sk_probe_mfma(int32_t dtype, int32_t iters, void *hip_stream, double *
     float *out = nullptr;
     SK_HIP(hipMalloc(&out, (size_t)blocks * threads * sizeof(float)));
     float ms = 0.f;
-    sk_status st = time_launches(stream, 3, [&] {
-        if (dtype == SK_F32) hipLaunchKernelGGL(mfma_issue_kernel<SK_F32>, dim3(blocks), dim3(threads), 0, stream, out, iters);
-        else if (dtype == SK_BF16) hipLaunchKernelGGL(mfma_issue_kernel<SK_BF16>, dim3(blocks), dim3(threads), 0, stream, out, iters);
-        else hipLaunchKernelGGL(mfma_issue_kernel<SK_F16>, dim3(blocks), dim3(threads), 0, stream, out, iters);
-    }, &ms);
+    void (*kernel)(float *, int) = nullptr;
+    if (dtype == SK_F32) kernel = operands ? mfma_issue_kernel<SK_F32, true> : mfma_issue_kernel<SK_F32, false>;
+    else if (dtype == SK_BF16) kernel = operands ? mfma_issue_kernel<SK_BF16, true> : mfma_issue_kernel<SK_BF16, false>;
+    else kernel = operands ? mfma_issue_kernel<SK_F16, true> : mfma_issue_kernel<SK_F16, false>;
+    sk_status st = time_launches(stream, 3, [&] { hipLaunchKernelGGL(kernel, dim3(blocks), dim3(threads), 0, stream, out, iters); }, &ms);
     (void)hipFree(out);
     if (st != SK_OK) return st;
     const double flop_per_mfma = dtype == SK_F32 ? 2.0 * 16 * 16 * 4 : 2.0 * 16 * 16 * 32;
