@@ -117,3 +117,59 @@ def upstep_from_paper(w1x1):
     1x1 convolution w1x1[o,c,1,1]) into one up-convolution weight [c,o,2,2]."""
     o, c = w1x1.shape[:2]
     return np.broadcast_to(w1x1.reshape(o, c).T[:, :, None, None], (c, o, 2, 2)).copy()
+
+
+# ---------------------------------------------------------------------------------------------
+# USK-Net (Section 3.5, the USK network configuration table): one contracting step of the U-Net,
+# the SK layer sequence on the half-resolution maps, one expanding step.
+
+def usknet_core(base=64):
+    """The SK part of the USK table (conv3 .. ip2) as (kind, f_out, k, d, relu) rows; it sees a
+    context of 5 + 1 + 6 + 2 + 12 + 4 + 56 = 86 pixels of the half-resolution map."""
+    return [("conv", 2 * base, 6, 1, True), ("pool", 0, 2, 1, False),
+            ("conv", 2 * base, 4, 2, True), ("pool", 0, 2, 2, False),
+            ("conv", 2 * base, 4, 4, True), ("pool", 0, 2, 4, False),
+            ("conv", 8 * base, 8, 8, True),              # ip1
+            ("conv", 4 * base, 1, 1, True)]              # ip2
+
+
+USK_CORE_NAMES = ("conv3", "pool2", "conv4", "pool3", "conv5", "pool4", "ip1", "ip2")
+
+
+def usknet_forward(image, params, base=64, keep=False):
+    """image[n,c,h,w] (context-padded, 692 in the table) -> probabilities (512 in the table).
+
+    params: {"conv1", "conv2"}   3x3 conv + ReLU (U part, full resolution)
+            {"conv3", "conv4", "conv5", "ip1", "ip2"}   SK convolutions + ReLU of usknet_core()
+            "up1"                2x2 stride-2 up-convolution 4*base -> 2*base, no ReLU, weight
+                                 [4*base, 2*base, 2, 2] (the table's upconv1 + conv6 pair is the
+                                 special case of upstep_from_paper())
+            {"conv7", "conv8"}   3x3 conv + ReLU on mergecrop(up path, conv2's maps)
+            "ip3"                1x1 conv to the classes
+    The max-pool between the parts is k = s = 2; the SK pools are k = 2, stride 1, at the layer's d.
+    """
+    x = np.asarray(image, dtype=np.float64)
+    trace = {}
+    x = L.conv_sk(x, *params["conv1"], d=1, relu=True)
+    x = L.conv_sk(x, *params["conv2"], d=1, relu=True)
+    trace["conv2"] = skip = x
+    if x.shape[2] % 2 or x.shape[3] % 2:
+        raise ValueError("USK-Net pooling needs an even map size")
+    x, _ = L.maxpool_sk(x, 2, 1, 2)
+    trace["pool1"] = x
+    for name, (kind, _, k, d, relu) in zip(USK_CORE_NAMES, usknet_core(base)):
+        if kind == "conv":
+            x = L.conv_sk(x, *params[name], d=d, relu=relu)
+        else:
+            x, _ = L.maxpool_sk(x, k, d, 1)
+        trace[name] = x
+    x = L.upconv2x2(x, *params["up1"])
+    trace["up1"] = x
+    x = L.mergecrop(x, skip)
+    x = L.conv_sk(x, *params["conv7"], d=1, relu=True)
+    x = L.conv_sk(x, *params["conv8"], d=1, relu=True)
+    trace["conv8"] = x
+    z = L.conv_sk(x, *params["ip3"], d=1, relu=False)
+    trace["logits"] = z
+    prob = L.softmax(z)
+    return (prob, trace) if keep else prob

@@ -145,3 +145,31 @@ def unet_params(c_in, classes, seed, depth=4, base=64, bias_scale=0.0):
         b = rng.standard_normal(f_out) * bias_scale
         out[name] = (w.astype(np.float32), b.astype(np.float32))
     return out
+
+
+# ---- USK-Net (the USK network configuration table, 692 -> 512) ----------------------------------------
+
+USKNET_PARAM_NAMES = ("conv1", "conv2", "conv3", "conv4", "conv5", "ip1", "ip2", "up1", "conv7", "conv8", "ip3")
+
+
+def usknet_params(c_in, classes, seed, base=64, bias_scale=0.0):
+    """He-normal weights for every USK-Net layer, {name: (w, b)} fp32, channel counts of the table
+    scaled by base/64: conv weights [f_out, f_in, k, k], the up-convolution [4*base, 2*base, 2, 2]."""
+    b = base
+    shapes = {"conv1": (b, c_in, 3, 3), "conv2": (b, b, 3, 3),
+              "conv3": (2 * b, b, 6, 6), "conv4": (2 * b, 2 * b, 4, 4), "conv5": (2 * b, 2 * b, 4, 4),
+              "ip1": (8 * b, 2 * b, 8, 8), "ip2": (4 * b, 8 * b, 1, 1),
+              "up1": (4 * b, 2 * b, 2, 2),
+              "conv7": (2 * b, 3 * b, 3, 3), "conv8": (b, 2 * b, 3, 3), "ip3": (classes, b, 1, 1)}
+    rng = np.random.default_rng(seed)
+    out = {}
+    for name in USKNET_PARAM_NAMES:
+        shp = shapes[name]
+        if name == "up1":
+            fan_in, f_out = shp[0], shp[1]
+        else:
+            fan_in, f_out = shp[1] * shp[2] * shp[3], shp[0]
+        w = rng.standard_normal(shp) * np.sqrt(2.0 / fan_in)
+        bias = rng.standard_normal(f_out) * bias_scale
+        out[name] = (w.astype(np.float32), bias.astype(np.float32))
+    return out

@@ -494,3 +494,35 @@ def test_unet_small_forward_shape_and_torch_crosscheck():
     z = F.conv2d(x, t(params["head"][0]), t(params["head"][1]))
     assert np.abs(tr["logits"] - z.numpy()).max() < 1e-12
     assert np.abs(prob - F.softmax(z, 1).numpy()).max() < 1e-14
+
+
+def test_usknet_forward_table_sizes_and_torch_crosscheck(golden_rows):
+    # The USK table's sizes (692 -> 512) with 1/32 of its channels, and the same composition written
+    # with the library's dilated convolution / pooling / transposed convolution.
+    base = 2
+    params = {k: (w.astype(np.float64), b.astype(np.float64))
+              for k, (w, b) in S.usknet_params(3, 2, 70, base=base, bias_scale=0.2).items()}
+    img = rng(71).random((1, 3, 692, 692))
+    prob, tr = nets.usknet_forward(img, params, base=base, keep=True)
+    table = {r[0]: int(r[2]) for r in golden_rows("usknet_table.txt")}
+    for stage, row in (("conv2", "conv2"), ("pool1", "pool1"), ("conv3", "conv3"), ("pool2", "pool2"), ("conv4", "conv4"),
+                       ("pool3", "pool3"), ("conv5", "conv5"), ("pool4", "pool4"), ("ip1", "ip1"), ("ip2", "ip2"),
+                       ("up1", "conv6"), ("conv8", "conv8"), ("logits", "ip3")):
+        assert tr[stage].shape[2] == tr[stage].shape[3] == table[row], (stage, tr[stage].shape)
+    assert tr["ip1"].shape[1] == 8 * base and tr["up1"].shape[1] == 2 * base
+    t = lambda a: torch.from_numpy(a)
+    cv = lambda x, name, d=1: F.conv2d(x, t(params[name][0]), t(params[name][1]), dilation=d)
+    x = F.relu(cv(F.relu(cv(t(img), "conv1")), "conv2"))
+    skip = x
+    x = F.max_pool2d(x, 2)
+    for name, d in (("conv3", 1), ("conv4", 2), ("conv5", 4)):
+        x = F.max_pool2d(F.relu(cv(x, name, d)), 2, stride=1, dilation=d)
+    x = F.relu(cv(F.relu(cv(x, "ip1", 8)), "ip2"))
+    x = F.conv_transpose2d(x, t(params["up1"][0]), t(params["up1"][1]), stride=2)
+    o = (skip.shape[2] - x.shape[2]) // 2
+    assert o == 86
+    x = torch.cat([x, skip[:, :, o:o + x.shape[2], o:o + x.shape[3]]], 1)
+    x = F.relu(cv(F.relu(cv(x, "conv7")), "conv8"))
+    z = cv(x, "ip3")
+    assert np.abs(tr["logits"] - z.numpy()).max() < 1e-11
+    assert np.abs(prob - F.softmax(z, 1).numpy()).max() < 1e-13
