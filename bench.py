@@ -147,6 +147,34 @@ def measure_unet(torch, B, S, dtype, steps, warmup):
             "tflops": round(gflop / dt / 1e3, 1)}
 
 
+def measure_usknet(torch, B, S, steps, warmup):
+    """USK-Net forward of the paper's USK configuration table (3 x 692^2 -> 2 x 512^2), fp32."""
+    params = S.usknet_params(3, 2, 1006, base=64)
+    net = B.USKNet(3, 2, base_ch=64)
+    for i, name in enumerate(S.USKNET_PARAM_NAMES):
+        net.set_weights(i, *params[name])
+    net.plan(1, 692, 692)
+    import numpy as np
+    img = torch.from_numpy(np.stack([S.em_like_image(692, 692, 1007 + c) for c in range(3)])[None].copy()).cuda()
+    prob = torch.empty((1, 2, 512, 512), dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+    for _ in range(warmup):
+        net.forward(img, prob, stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        net.forward(img, prob, stream)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    net.close()
+    # 2 f_in k^2 f_out w_out^2 over the table's convolutions and the up step
+    gflop = 2e-9 * (3 * 9 * 64 * 690 ** 2 + 64 * 9 * 64 * 688 ** 2 + 64 * 36 * 128 * 339 ** 2 + 128 * 16 * 128 * (332 ** 2 + 318 ** 2)
+                    + 128 * 64 * 512 * 258 ** 2 + 512 * 256 * 258 ** 2 + 256 * 128 * 516 ** 2 + 192 * 9 * 128 * 514 ** 2
+                    + 128 * 9 * 64 * 512 ** 2 + 64 * 2 * 512 ** 2)
+    return {"ms_per_step": round(dt * 1e3, 4), "labelled_pixels_per_s": round(512 * 512 / dt, 1),
+            "gflop": round(gflop, 1), "tflops": round(gflop / dt / 1e3, 1)}
+
+
 def measure_paper_sknet(torch, B, S, steps, warmup):
     """The paper's own SK network (Section 3.3.2: 3 x 229^2 after padding -> 2 x 128^2; its inner product
     is a k = 10, d = 8 convolution 192 -> 1024, 644 of the 695 GFLOP) in fp32: the workload of the
@@ -281,6 +309,7 @@ def main():
         for name, dt in (("c5_unet_572_f32", "f32"), ("c5_unet_572_bf16", "bf16")):
             extras[name] = measure_unet(torch, B, S, dt, 10, 3)
         extras["paper_sknet_128_f32"] = measure_paper_sknet(torch, B, S, 5, 2)
+        extras["usknet_692_f32_forward"] = measure_usknet(torch, B, S, 5, 2)
         out["extras"] = extras
 
     if args.workload == "c2" and not args.no_cpu_baseline:

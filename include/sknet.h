@@ -190,6 +190,19 @@ sk_status unet_create(int32_t c_in, int32_t n_classes, int32_t depth, int32_t ba
                       sk_dtype dtype, unet_t **out);
 void unet_destroy(unet_t *net);
 
+/* USK-Net of Section 3.5's configuration table, as a unet_t handle that every unet_* call below
+ * accepts: two 3x3 convs + ReLU and a 2x2 stride-2 max pool (U part); on the half-resolution maps
+ * the SK sequence conv k6 d1, pool k2 d1, conv k4 d2, pool k2 d2, conv k4 d4, pool k2 d4, conv k8
+ * d8 ("ip1"), conv 1x1 ("ip2"), all convs + ReLU, all pools stride 1 (context 86); a 2x2 stride-2
+ * up-convolution without ReLU, MergeCrop with the maps of the second 3x3 conv, two 3x3 convs + ReLU,
+ * a 1x1 conv to n_classes and a per-pixel softmax.  Maps: base_ch (64 in the table), 2, 8, 4, 2, 3,
+ * 2, 1 times base_ch along the path.  692 x 692 in -> 512 x 512 out.  Parameter order: "conv1",
+ * "conv2", "conv3", "conv4", "conv5", "ip1", "ip2", "up1" ([4b][2b][2][2]), "conv7", "conv8",
+ * "ip3".  Stages for unet_get_activation: "conv2", "pool1", "conv3", "pool2", "conv4", "pool3",
+ * "conv5", "pool4", "ip1", "ip2", "up1", "conv8", "logits".  dtype: SK_F32 only (the 6x6 and 8x8
+ * kernels have no 16-bit variant: SK_EUNSUPPORTED).  Host only. */
+sk_status usknet_create(int32_t c_in, int32_t n_classes, int32_t base_ch, sk_dtype dtype, unet_t **out);
+
 /* Parameter tensors, in forward order: per level i = 0..depth "down{i}a", "down{i}b"; then per
  * level i = depth-1..0 "up{i}", "dec{i}a", "dec{i}b"; then "head".  Convs are [f_out][f_in][k][k];
  * up-convolutions are [f_in][f_out][2][2] with Y[o,2y+a,2x+b] = bias[o] + sum_c W[c,o,a,b] X[c,y,x]

@@ -67,6 +67,7 @@ _SIGS = {
     "unet_plan": [_vp, _i32, _i32, _i32],
     "unet_forward": [_vp, _vp, _vp, _vp],
     "unet_get_activation": [_vp, C.c_char_p, _fp, _ip],
+    "usknet_create": [_i32, _i32, _i32, _i32, C.POINTER(_vp)],
     "sk_probe_mfma": [_i32, _i32, _i32, _vp, C.POINTER(C.c_double)],
     "sk_probe_copy": [_vp, _vp, C.c_uint64, _i32, _vp, C.POINTER(C.c_double)],
 }
@@ -303,9 +304,12 @@ class UNet:
 
     def __init__(self, c_in, n_classes, depth=4, base_ch=64, dtype="f32"):
         self._h = _vp()
-        _check(lib.unet_create(c_in, n_classes, depth, base_ch, DTYPES[dtype], C.byref(self._h)))
+        self._create(c_in, n_classes, depth, base_ch, dtype)
         self.c_in, self.n_classes, self.depth = c_in, n_classes, depth
         self._plan = None
+
+    def _create(self, c_in, n_classes, depth, base_ch, dtype):
+        _check(lib.unet_create(c_in, n_classes, depth, base_ch, DTYPES[dtype], C.byref(self._h)))
 
     def close(self):
         if self._h:
@@ -364,3 +368,13 @@ class UNet:
         out = np.empty((self._plan[0], dims[0], dims[1], dims[2]), np.float32)
         _check(lib.unet_get_activation(self._h, stage.encode(), out.ctypes.data_as(_fp), dims))
         return out
+
+
+class USKNet(UNet):
+    """USK-Net (usknet_create): the same handle type and calls as UNet."""
+
+    def __init__(self, c_in, n_classes, base_ch=64, dtype="f32"):
+        super().__init__(c_in, n_classes, 1, base_ch, dtype)
+
+    def _create(self, c_in, n_classes, depth, base_ch, dtype):
+        _check(lib.usknet_create(c_in, n_classes, base_ch, DTYPES[dtype], C.byref(self._h)))

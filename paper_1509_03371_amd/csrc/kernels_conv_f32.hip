@@ -248,11 +248,24 @@ __global__ __launch_bounds__(256) void conv_f32_pf_kernel(ConvF32Args a, int til
     // LDS offset of K index (c, i, j) inside the staged tile for the K values lane group g supplies
     // in step s of a chunk: klane + kconst(s) when the k*k taps of a map fill whole steps, else a
     // per-lane table in registers.
-    constexpr bool KSPLIT = KK2 % 4 == 0 || KK2 == 1;
+    // KTAB (k > 4 with k*k a multiple of 4): the taps of a map still fill whole steps, but the four
+    // taps of a step fall on different kernel rows and columns from step to step; the per-lane
+    // offsets of one map's k*k/4 steps are kept in registers and the map adds a constant.
+    constexpr bool KTAB = KS > 4 && KK2 % 4 == 0;
+    constexpr bool KSPLIT = !KTAB && (KK2 % 4 == 0 || KK2 == 1);
+    constexpr int SPM = KK2 / 4;                     // steps per input map (KTAB)
     int klane = 0;
-    int kreg[KSPLIT ? 1 : KC / 4];
+    int kreg[(KSPLIT || KTAB) ? 1 : KC / 4];
+    int ktab[KTAB ? SPM : 1];
     if constexpr (KK2 == 1) klane = g * RR * PITCH;
-    else if constexpr (KSPLIT) klane = (g / KS) * PITCH + (g % KS) * d;
+    else if constexpr (KTAB) {
+#pragma unroll
+        for (int sidx = 0; sidx < SPM; ++sidx) {
+            const int q = 4 * sidx + g;
+            const int i = q / KS, j = q - i * KS;
+            ktab[sidx] = i * PITCH + j * d;
+        }
+    } else if constexpr (KSPLIT) klane = (g / KS) * PITCH + (g % KS) * d;
     else {
 #pragma unroll
         for (int sidx = 0; sidx < KC / 4; ++sidx) {
@@ -390,7 +403,8 @@ __global__ __launch_bounds__(256) void conv_f32_pf_kernel(ConvF32Args a, int til
         float av[2][NT], bv[2][RW][4];
         auto fetch = [&](int sidx, int buf) {
             int ko = klane + kthread + kconst(sidx);
-            if constexpr (!KSPLIT) ko = kreg[sidx] + kthread;
+            if constexpr (KTAB) ko = ktab[sidx % SPM] + kthread + (sidx / SPM) * RR * PITCH;
+            else if constexpr (!KSPLIT) ko = kreg[sidx] + kthread;
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) av[buf][nt] = ws[(4 * sidx + g) * WN + nt * 16 + l16];
 #pragma unroll
@@ -493,6 +507,14 @@ static hipError_t launch_conv_f32_nt(const ConvF32Args &a, hipStream_t stream)
         // 4-row tiles: twice as many workgroups as with 8 rows, which balances the 256 CUs better
         // at 512^2 (measured: 0.24 ms instead of 0.33 ms per 48->48 layer)
         return launch_conv_f32_pf_t<NT, 1, 4, 4, 2>(a, stream);
+    }
+    // the large kernels of the USK-Net (6x6 at d = 1, 8x8 at d = 8) and of the paper's SK-Net (10x10 at
+    // d = 8, a 73-pixel window: three column groups); forward only, one chunk of four maps holds
+    // 4*k*k K values and its weight slab fills most of the LDS, so one workgroup per CU
+    if (a.in_off == 0) {
+        if (a.k == 6 && halo <= 64) return launch_conv_f32_pf_z<NT, 2, 6, 4, 2, false>(a, stream);
+        if (a.k == 8 && halo <= 64) return launch_conv_f32_pf_z<NT, 1, 8, 4, 2, false>(a, stream);
+        if (a.k == 10 && halo <= 128) return launch_conv_f32_pf_z<NT, 1, 10, 4, 3, false>(a, stream);
     }
     return launch_conv_f32_t<NT, 2>(a, stream);
 }

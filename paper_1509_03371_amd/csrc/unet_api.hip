@@ -1,7 +1,9 @@
 // U-Net forward (paper Section 3.4 and its configuration table) on the same kernels as the SK
 // net: 3x3 convolutions are the SK convolution at d = 1, the 2x2 stride-2 up-convolution is four
 // 1x1 convolutions whose outputs interleave, MergeCrop is the up path written in place plus a
-// crop-and-place copy of the skip maps.  See include/sknet.h for the contract.
+// crop-and-place copy of the skip maps.  The USK-Net (Section 3.5 and its configuration table) is
+// the same engine with another layer list: one contracting step, the SK layer sequence at d = 1, 2,
+// 4, 8 on the half-resolution maps, one expanding step.  See include/sknet.h for the contract.
 #include <new>
 
 #include "sk_host.h"
@@ -21,11 +23,13 @@ struct Stage {
     std::string name;
     Dims dims;
     float *buf = nullptr;
+    int buf_c = 0;                  // maps of the buffer the stage lives in (> dims.c for the up path inside a merged buffer)
 };
 
 }  // namespace
 
 struct unet {
+    int arch = 0;                            // 0 = U-Net, 1 = USK-Net
     int c_in = 0, n_classes = 0, depth = 0, base = 0;
     int dtype = SK_F32;                      // storage type of activations and packed weights
     // parameters in forward order; kind 0 = conv (index into convs), 1 = up-convolution (index into ups)
@@ -46,6 +50,7 @@ struct unet {
         Dims in, out;                        // out.c = maps of the destination buffer
         int o_off, crop;                     // map offset in dst; crop offset for kind 3
         int src_maps;
+        int k, d, s;                         // pool window / spacing / stride; d also the conv's kernel stride
     };
     std::vector<Op> ops;
     std::vector<Stage> stages;
@@ -81,8 +86,30 @@ sk_status check(const unet_t *net)
 }
 
 // spatial sizes: every level two valid 3x3 convs, then a k = s = 2 pool; mirrored on the way up
+// the SK part of the USK-Net: (conv?, f_out multiple of base, k, d)
+struct UskCore { bool conv; int f_mul, k, d; const char *name; };
+const UskCore kUskCore[] = {{true, 2, 6, 1, "conv3"}, {false, 0, 2, 1, "pool2"}, {true, 2, 4, 2, "conv4"}, {false, 0, 2, 2, "pool3"},
+                            {true, 2, 4, 4, "conv5"}, {false, 0, 2, 4, "pool4"}, {true, 8, 8, 8, "ip1"}, {true, 4, 1, 1, "ip2"}};
+
+sk_status walk_sizes_usk(int h, int w, int *ho, int *wo)
+{
+    h -= 4; w -= 4;
+    if (h < 2 || w < 2) return fail(SK_ESHAPE, "USK-Net: map vanishes before the pooling step");
+    if (h % 2 || w % 2) return fail(SK_ESHAPE, "USK-Net: pooling needs an even map (got %dx%d)", h, w);
+    h /= 2; w /= 2;
+    for (const auto &l : kUskCore) {
+        h -= (l.k - 1) * l.d; w -= (l.k - 1) * l.d;
+        if (h < 1 || w < 1) return fail(SK_ESHAPE, "USK-Net: map vanishes at %s", l.name);
+    }
+    h = 2 * h - 4; w = 2 * w - 4;
+    if (h < 1 || w < 1) return fail(SK_ESHAPE, "USK-Net: map vanishes on the expanding step");
+    *ho = h; *wo = w;
+    return SK_OK;
+}
+
 sk_status walk_sizes(const unet *net, int h, int w, int *ho, int *wo)
 {
+    if (net->arch == 1) return walk_sizes_usk(h, w, ho, wo);
     for (int i = 0; i <= net->depth; ++i) {
         h -= 4; w -= 4;
         if (h < 1 || w < 1) return fail(SK_ESHAPE, "U-Net: map vanishes at level %d", i);
@@ -161,6 +188,44 @@ sk_status unet_create(int32_t c_in, int32_t n_classes, int32_t depth, int32_t ba
     return SK_OK;
 }
 
+sk_status usknet_create(int32_t c_in, int32_t n_classes, int32_t base_ch, sk_dtype dtype, unet_t **out)
+{
+    if (!out) return fail(SK_EINVAL, "usknet_create: out is null");
+    *out = nullptr;
+    if (c_in < 1 || n_classes < 1 || base_ch < 1) return fail(SK_EINVAL, "usknet_create: bad arguments");
+    if (dtype != SK_F32) return fail(SK_EUNSUPPORTED, "usknet_create: only fp32 storage is built (its 6x6 and 8x8 kernels have no 16-bit variant)");
+    unet *net = new (std::nothrow) unet;
+    if (!net) return fail(SK_ENOMEM, "usknet_create: out of host memory");
+    net->arch = 1; net->c_in = c_in; net->n_classes = n_classes; net->depth = 1; net->base = base_ch; net->dtype = dtype;
+    auto add_conv = [&](const std::string &name, int fi, int fo, int k) {
+        ConvParams c;
+        c.c_in = fi; c.c_out = fo; c.k = k;
+        c.w.assign((size_t)c.wcount(), 0.f);
+        c.b.assign((size_t)fo, 0.f);
+        net->params.push_back({name, 0, (int)net->convs.size()});
+        net->convs.push_back(std::move(c));
+    };
+    add_conv("conv1", c_in, base_ch, 3);
+    add_conv("conv2", base_ch, base_ch, 3);
+    int f = base_ch;
+    for (const auto &l : kUskCore)
+        if (l.conv) {
+            add_conv(l.name, f, l.f_mul * base_ch, l.k);
+            f = l.f_mul * base_ch;
+        }
+    UpParams u;
+    u.c_in = f; u.c_out = 2 * base_ch;
+    u.w.assign((size_t)u.c_in * u.c_out * 4, 0.f);
+    u.b.assign((size_t)u.c_out, 0.f);
+    net->params.push_back({"up1", 1, 0});
+    net->ups.push_back(std::move(u));
+    add_conv("conv7", 3 * base_ch, 2 * base_ch, 3);
+    add_conv("conv8", 2 * base_ch, base_ch, 3);
+    add_conv("ip3", base_ch, n_classes, 1);
+    *out = net;
+    return SK_OK;
+}
+
 void unet_destroy(unet_t *net)
 {
     if (!net) return;
@@ -235,9 +300,14 @@ sk_status unet_plan(unet_t *net, int32_t n, int32_t h_in, int32_t w_in)
         if (half && d.count(n) > net->unpack_tmp_floats) net->unpack_tmp_floats = d.count(n);
         return p;
     };
-    auto conv_op = [&](int conv_idx, int relu, const float *src, const Dims &in, float *dst, const Dims &out) {
+    auto conv_op = [&](int conv_idx, int relu, const float *src, const Dims &in, float *dst, const Dims &out, int d = 1) {
         unet::Op op{};
-        op.kind = 0; op.param = conv_idx; op.relu = relu; op.src = src; op.dst = dst; op.in = in; op.out = out;
+        op.kind = 0; op.param = conv_idx; op.relu = relu; op.src = src; op.dst = dst; op.in = in; op.out = out; op.d = d;
+        net->ops.push_back(op);
+    };
+    auto pool_op = [&](const float *src, const Dims &in, float *dst, const Dims &out, int k, int d, int s) {
+        unet::Op op{};
+        op.kind = 1; op.src = src; op.dst = dst; op.in = in; op.out = out; op.k = k; op.d = d; op.s = s;
         net->ops.push_back(op);
     };
     int ci = 0;   // running conv index
@@ -251,55 +321,95 @@ sk_status unet_plan(unet_t *net, int32_t n, int32_t h_in, int32_t w_in)
         net->ops.push_back(op);
         src = packed;
     }
-    std::vector<Dims> skip_dims;
-    std::vector<const float *> skip_buf;
-    for (int i = 0; i <= net->depth && st == SK_OK; ++i) {
-        const int ch = net->base << i;
-        Dims a = {ch, cur.h - 2, cur.w - 2}, b = {ch, cur.h - 4, cur.w - 4};
+    if (net->arch == 1) {
+        // USK-Net: conv1, conv2 | pool k2 s2 | SK core at half resolution | up-convolution into the
+        // merged buffer, conv2's maps cropped in behind it | conv7, conv8
+        const int b0 = net->base;
+        Dims a = {b0, cur.h - 2, cur.w - 2}, b = {b0, cur.h - 4, cur.w - 4};
         float *ba = new_buf(a), *bb = new_buf(b);
         conv_op(ci++, 1, src, cur, ba, a);
         conv_op(ci++, 1, ba, a, bb, b);
-        net->stages.push_back({"down" + std::to_string(i), b, bb});
-        cur = b; src = bb;
-        if (i < net->depth) {
-            skip_dims.push_back(b);
-            skip_buf.push_back(bb);
-            Dims p = {ch, b.h / 2, b.w / 2};
-            float *bp = new_buf(p);
-            unet::Op op{};
-            op.kind = 1; op.src = bb; op.dst = bp; op.in = b; op.out = p;
-            net->ops.push_back(op);
-            cur = p; src = bp;
+        net->stages.push_back({"conv2", b, bb, b.c});
+        Dims p = {b0, b.h / 2, b.w / 2};
+        float *bp = new_buf(p);
+        pool_op(bb, b, bp, p, 2, 1, 2);
+        net->stages.push_back({"pool1", p, bp, p.c});
+        cur = p; src = bp;
+        for (const auto &l : kUskCore) {
+            Dims o = {l.conv ? l.f_mul * b0 : cur.c, cur.h - (l.k - 1) * l.d, cur.w - (l.k - 1) * l.d};
+            float *bo = new_buf(o);
+            if (l.conv) conv_op(ci++, 1, src, cur, bo, o, l.d);
+            else pool_op(src, cur, bo, o, l.k, l.d, 1);
+            net->stages.push_back({l.name, o, bo, o.c});
+            cur = o; src = bo;
         }
-    }
-    int ui = 0;
-    for (int i = net->depth - 1; i >= 0 && st == SK_OK; --i) {
-        const int ch = net->base << i;
-        Dims merged = {2 * ch, 2 * cur.h, 2 * cur.w};
+        Dims merged = {3 * b0, 2 * cur.h, 2 * cur.w};
         float *bm = new_buf(merged);
         unet::Op up{};
-        up.kind = 2; up.param = ui++; up.src = src; up.dst = bm; up.in = cur; up.out = merged; up.o_off = 0;
+        up.kind = 2; up.param = 0; up.src = src; up.dst = bm; up.in = cur; up.out = merged; up.o_off = 0;
         net->ops.push_back(up);
-        Dims upd = {ch, merged.h, merged.w};
-        net->stages.push_back({"up" + std::to_string(i), upd, bm});
+        Dims upd = {2 * b0, merged.h, merged.w};
+        net->stages.push_back({"up1", upd, bm, merged.c});
         unet::Op cp{};
-        cp.kind = 3; cp.src = skip_buf[i]; cp.dst = bm; cp.in = skip_dims[i]; cp.out = merged; cp.o_off = ch;
-        cp.crop = (skip_dims[i].h - merged.h) / 2; cp.src_maps = ch;
-        if (skip_dims[i].h < merged.h || skip_dims[i].w < merged.w) st = fail(SK_ESHAPE, "U-Net: skip map smaller than the up path at level %d", i);
+        cp.kind = 3; cp.src = bb; cp.dst = bm; cp.in = b; cp.out = merged; cp.o_off = 2 * b0;
+        cp.crop = (b.h - merged.h) / 2; cp.src_maps = b0;
+        if (b.h < merged.h || b.w < merged.w) st = fail(SK_ESHAPE, "USK-Net: skip map smaller than the up path");
         net->ops.push_back(cp);
-        Dims a = {ch, merged.h - 2, merged.w - 2}, b = {ch, merged.h - 4, merged.w - 4};
-        float *ba = new_buf(a), *bb = new_buf(b);
-        conv_op(ci++, 1, bm, merged, ba, a);
-        conv_op(ci++, 1, ba, a, bb, b);
-        net->stages.push_back({"dec" + std::to_string(i), b, bb});
-        cur = b; src = bb;
+        Dims c7 = {2 * b0, merged.h - 2, merged.w - 2}, c8 = {b0, merged.h - 4, merged.w - 4};
+        float *b7 = new_buf(c7), *b8 = new_buf(c8);
+        conv_op(ci++, 1, bm, merged, b7, c7);
+        conv_op(ci++, 1, b7, c7, b8, c8);
+        net->stages.push_back({"conv8", c8, b8, c8.c});
+        cur = c8; src = b8;
+    } else {
+        std::vector<Dims> skip_dims;
+        std::vector<const float *> skip_buf;
+        for (int i = 0; i <= net->depth && st == SK_OK; ++i) {
+            const int ch = net->base << i;
+            Dims a = {ch, cur.h - 2, cur.w - 2}, b = {ch, cur.h - 4, cur.w - 4};
+            float *ba = new_buf(a), *bb = new_buf(b);
+            conv_op(ci++, 1, src, cur, ba, a);
+            conv_op(ci++, 1, ba, a, bb, b);
+            net->stages.push_back({"down" + std::to_string(i), b, bb, b.c});
+            cur = b; src = bb;
+            if (i < net->depth) {
+                skip_dims.push_back(b);
+                skip_buf.push_back(bb);
+                Dims p = {ch, b.h / 2, b.w / 2};
+                float *bp = new_buf(p);
+                pool_op(bb, b, bp, p, 2, 1, 2);
+                cur = p; src = bp;
+            }
+        }
+        int ui = 0;
+        for (int i = net->depth - 1; i >= 0 && st == SK_OK; --i) {
+            const int ch = net->base << i;
+            Dims merged = {2 * ch, 2 * cur.h, 2 * cur.w};
+            float *bm = new_buf(merged);
+            unet::Op up{};
+            up.kind = 2; up.param = ui++; up.src = src; up.dst = bm; up.in = cur; up.out = merged; up.o_off = 0;
+            net->ops.push_back(up);
+            Dims upd = {ch, merged.h, merged.w};
+            net->stages.push_back({"up" + std::to_string(i), upd, bm, merged.c});
+            unet::Op cp{};
+            cp.kind = 3; cp.src = skip_buf[i]; cp.dst = bm; cp.in = skip_dims[i]; cp.out = merged; cp.o_off = ch;
+            cp.crop = (skip_dims[i].h - merged.h) / 2; cp.src_maps = ch;
+            if (skip_dims[i].h < merged.h || skip_dims[i].w < merged.w) st = fail(SK_ESHAPE, "U-Net: skip map smaller than the up path at level %d", i);
+            net->ops.push_back(cp);
+            Dims a = {ch, merged.h - 2, merged.w - 2}, b = {ch, merged.h - 4, merged.w - 4};
+            float *ba = new_buf(a), *bb = new_buf(b);
+            conv_op(ci++, 1, bm, merged, ba, a);
+            conv_op(ci++, 1, ba, a, bb, b);
+            net->stages.push_back({"dec" + std::to_string(i), b, bb, b.c});
+            cur = b; src = bb;
+        }
     }
     if (st == SK_OK) {
         Dims z = {net->n_classes, cur.h, cur.w};
         if (st == SK_OK) st = alloc_f(&net->logits, z.count(n));
         if (net->logits) net->buffers.push_back(net->logits);
         conv_op(ci++, 0, src, cur, net->logits, z);
-        net->stages.push_back({"logits", z, net->logits});
+        net->stages.push_back({"logits", z, net->logits, z.c});
         net->out_dims = z;
     }
     if (half) {
@@ -315,7 +425,7 @@ sk_status unet_plan(unet_t *net, int32_t n, int32_t h_in, int32_t w_in)
     }
     for (auto &c : net->convs) {
         if (st != SK_OK) break;
-        if (half && !sk::conv_h_supported(c.k, 1)) st = fail(SK_EUNSUPPORTED, "U-Net: kernel size %d is not built for 16-bit storage", c.k);
+        if (half && (net->arch != 0 || !sk::conv_h_supported(c.k, 1))) st = fail(SK_EUNSUPPORTED, "U-Net: kernel size %d is not built for 16-bit storage", c.k);
         if (st == SK_OK) st = alloc_conv(c, false, net->dtype);
         if (st == SK_OK) st = upload_conv(c, false, nullptr, net->dtype);
     }
@@ -356,11 +466,11 @@ sk_status unet_forward(unet_t *net, const float *image_dev, float *prob_dev, voi
             } else if (op.kind == 0) {
                 const ConvParams &c = net->convs[op.param];
                 const bool to_logits = op.dst == net->logits;     // the last conv leaves fp32 NCHW
-                sk::ConvHArgs a = conv_h_args(c, dt, src, n, op.in, 1, op.relu, op.dst, op.out, to_logits);
+                sk::ConvHArgs a = conv_h_args(c, dt, src, n, op.in, op.d, op.relu, op.dst, op.out, to_logits);
                 SK_HIP(sk::launch_conv_h(a, stream));
             } else if (op.kind == 1) {
                 SK_HIP(sk::launch_maxpool_h(src, op.dst, nullptr, dt, (long)n * ((op.in.c + 7) / 8), op.in.h, op.in.w,
-                                            op.out.h, op.out.w, 2, 1, 2, stream));
+                                            op.out.h, op.out.w, op.k, op.d, op.s, stream));
             } else if (op.kind == 2) {
                 const UpParams &u = net->ups[op.param];
                 for (int t = 0; t < 4; ++t) {
@@ -378,10 +488,10 @@ sk_status unet_forward(unet_t *net, const float *image_dev, float *prob_dev, voi
         }
         if (op.kind == 0) {
             const ConvParams &c = net->convs[op.param];
-            sk::ConvF32Args a = conv_args(c, src, n, op.in, 1, op.relu, op.dst, op.out);
+            sk::ConvF32Args a = conv_args(c, src, n, op.in, op.d, op.relu, op.dst, op.out);
             SK_HIP(sk::launch_conv_f32(a, stream));
         } else if (op.kind == 1) {
-            SK_HIP(sk::launch_maxpool_f32(src, op.dst, nullptr, n * op.in.c, op.in.h, op.in.w, op.out.h, op.out.w, 2, 1, 2, stream));
+            SK_HIP(sk::launch_maxpool_f32(src, op.dst, nullptr, n * op.in.c, op.in.h, op.in.w, op.out.h, op.out.w, op.k, op.d, op.s, stream));
         } else if (op.kind == 2) {
             const UpParams &u = net->ups[op.param];
             for (int t = 0; t < 4; ++t) {
@@ -412,9 +522,8 @@ sk_status unet_get_activation(unet_t *net, const char *stage, float *nchw_host, 
         if (!nchw_host) return SK_OK;
         if (!net->forward_done) return fail(SK_ESTATE, "unet_get_activation: no forward pass yet");
         SK_HIP(hipStreamSynchronize(net->last_stream));
-        const bool is_up = s.name.rfind("up", 0) == 0;
         // the up path occupies the first maps of the merged buffer: copy image by image
-        const int buf_c = is_up ? 2 * s.dims.c : s.dims.c;
+        const int buf_c = s.buf_c;
         const float *src = s.buf;
         if (net->dtype != SK_F32 && s.buf != net->logits) {      // widen the octet layout to fp32 NCHW first
             SK_HIP(sk::launch_unpack_h(s.buf, net->unpack_tmp, net->dtype, net->n, buf_c, s.dims.h, s.dims.w, net->last_stream));

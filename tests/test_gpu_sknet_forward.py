@@ -60,6 +60,8 @@ def test_c1_tiny_sknet_forward():
     (4, 1, 1, 48, 70, 90), (4, 2, 48, 48, 41, 131), (4, 8, 48, 48, 57, 66), (5, 2, 8, 16, 33, 29),
     (3, 1, 64, 128, 20, 23), (1, 1, 48, 200, 19, 70), (1, 1, 200, 2, 19, 70), (3, 4, 3, 5, 30, 40),
     (2, 3, 5, 7, 9, 200), (7, 1, 3, 48, 25, 25), (4, 8, 6, 4, 25, 25), (10, 2, 4, 20, 30, 24),
+    # the large kernels of the USK-Net and of the paper's SK-Net: map counts off the chunk of four, several map blocks
+    (6, 1, 10, 40, 30, 75), (6, 3, 5, 70, 40, 90), (8, 8, 12, 130, 70, 140), (8, 2, 3, 16, 33, 29), (10, 8, 6, 50, 90, 160),
 ])
 def test_conv_layer_shapes(k, d, c_in, c_out, h, w):
     """One SK convolution (+bias +ReLU) per case: several tiles, ragged tails, a row-phase count

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "sknet.h")).read()
-    declared = set(re.findall(r"\b((?:sknet|unet|sk_probe)_[a-z_0-9]+)\s*\(", header))
+    declared = set(re.findall(r"\b((?:sknet|unet|usknet|sk_probe)_[a-z_0-9]+)\s*\(", header))
     assert declared, "no declarations found"
     for name in declared:
         assert hasattr(B.lib, name), name
