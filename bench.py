@@ -227,7 +227,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", choices=["c2", "c3", "c4", "c5", "c5bf16", "copy"], default="c2")
+    ap.add_argument("--workload", choices=["c2", "c3", "c4", "c5", "c5bf16", "usk", "papersk", "copy"], default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
     args = ap.parse_args()
@@ -262,6 +262,18 @@ def main():
                     "config": {"workload": "U-Net forward 1x1x572x572 -> 2x388x388, %s (BASELINE configs[4])" % dt,
                                "global_batch": 1, "parallelism": "single GPU"},
                     "roofline": None, "forward_tflops": r["tflops"]})
+        print(json.dumps(out))
+        return
+
+    if args.workload in ("usk", "papersk"):
+        if args.workload == "usk":
+            r = measure_usknet(torch, B, S, args.steps, args.warmup)
+            px, what = r["labelled_pixels_per_s"], "USK-Net forward 1x3x692x692 -> 2x512x512, fp32 (the paper's USK configuration table)"
+        else:
+            r = measure_paper_sknet(torch, B, S, args.steps, args.warmup)
+            px, what = r["pixels_per_s"], "the paper's SK-Net forward, 3x128x128 -> 2x128x128 (padded to 229), fp32"
+        out.update({"value": px, "ms_per_step": r["ms_per_step"], "dtype": "f32",
+                    "config": {"workload": what, "global_batch": 1, "parallelism": "single GPU"}, "roofline": None, "detail": r})
         print(json.dumps(out))
         return
 
