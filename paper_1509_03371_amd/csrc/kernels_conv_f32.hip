@@ -538,8 +538,8 @@ hipError_t launch_conv_f32(const ConvF32Args &a, hipStream_t stream)
 }
 
 // ------------------------------------------------------------------------------------------------
-__global__ void pack_weights_f32_kernel(const float *w, float *wp, int c_out, int c_in, int k,
-                                        int flip_transpose, int rows, int n_pad)
+__device__ __forceinline__ void pack_weights_f32_body(const float *w, float *wp, int c_out, int c_in, int k,
+                                                      int flip_transpose, int rows, int n_pad)
 {
     const long total = (long)rows * n_pad;
     for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
@@ -553,6 +553,34 @@ __global__ void pack_weights_f32_kernel(const float *w, float *wp, int c_out, in
         }
         wp[q] = v;
     }
+}
+
+__global__ void pack_weights_f32_kernel(const float *w, float *wp, int c_out, int c_in, int k,
+                                        int flip_transpose, int rows, int n_pad)
+{
+    pack_weights_f32_body(w, wp, c_out, c_in, k, flip_transpose, rows, n_pad);
+}
+
+struct PackF32Jobs { PackF32Job job[BATCH_MAX]; };
+__global__ void pack_weights_f32_batch_kernel(PackF32Jobs b)
+{
+    const PackF32Job &j = b.job[blockIdx.y];
+    pack_weights_f32_body(j.w, j.wp, j.c_out, j.c_in, j.k, j.flip_transpose, j.rows, j.n_pad);
+}
+
+hipError_t launch_pack_weights_f32_batch(const PackF32Job *jobs, int n, hipStream_t stream)
+{
+    if (n < 1 || n > BATCH_MAX) return hipErrorInvalidValue;
+    PackF32Jobs b;
+    long most = 1;
+    for (int t = 0; t < n; ++t) {
+        b.job[t] = jobs[t];
+        const long total = (long)jobs[t].rows * jobs[t].n_pad;
+        most = total > most ? total : most;
+    }
+    const int blocks = (int)((most + 255) / 256 < 256 ? (most + 255) / 256 : 256);
+    hipLaunchKernelGGL(pack_weights_f32_batch_kernel, dim3(blocks, n), dim3(256), 0, stream, b);
+    return hipGetLastError();
 }
 
 hipError_t launch_pack_weights_f32(const float *w_oihw, float *wp, int c_out, int c_in, int k,

@@ -1056,8 +1056,8 @@ hipError_t launch_conv_h(const ConvHArgs &a, hipStream_t stream)
 // are swapped and both taps are mirrored (element = W[c][o][k-1-i][k-1-j]).
 // Entries whose o or c lie beyond the real extents are zero.
 template <int DT>
-__global__ void pack_weights_h_kernel(const float *w, unsigned short *wp, int c_out, int c_in, int k, int flip_transpose,
-                                      int mt_per_group, int map4, int gemm_m, int gemm_c8, long total)
+__device__ __forceinline__ void pack_weights_h_body(const float *w, unsigned short *wp, int c_out, int c_in, int k, int flip_transpose,
+                                                    int mt_per_group, int map4, int gemm_m, int gemm_c8, long total)
 {
     const int OC = map4 ? 1 : 4, CS = map4 ? 1 : k;
     const int nchunks = (gemm_c8 + OC - 1) / OC;
@@ -1084,6 +1084,22 @@ __global__ void pack_weights_h_kernel(const float *w, unsigned short *wp, int c_
         }
         wp[q] = H<DT>::cvt(v);
     }
+}
+
+template <int DT>
+__global__ void pack_weights_h_kernel(const float *w, unsigned short *wp, int c_out, int c_in, int k, int flip_transpose,
+                                      int mt_per_group, int map4, int gemm_m, int gemm_c8, long total)
+{
+    pack_weights_h_body<DT>(w, wp, c_out, c_in, k, flip_transpose, mt_per_group, map4, gemm_m, gemm_c8, total);
+}
+
+struct PackHJobDev { const float *w; unsigned short *wp; int c_out, c_in, k, flip_transpose, mt, map4, gemm_m, gemm_c8; long total; };
+struct PackHJobs { PackHJobDev job[BATCH_MAX]; };
+template <int DT>
+__global__ void pack_weights_h_batch_kernel(PackHJobs b)
+{
+    const PackHJobDev &j = b.job[blockIdx.y];
+    pack_weights_h_body<DT>(j.w, j.wp, j.c_out, j.c_in, j.k, j.flip_transpose, j.mt, j.map4, j.gemm_m, j.gemm_c8, j.total);
 }
 
 // size in 16-bit elements of the packing of a GEMM with gemm_m output maps and gemm_c8 input octets
@@ -1123,6 +1139,29 @@ hipError_t launch_pack_weights_h(const float *w_oihw, void *wp, int dtype, int c
     else
         hipLaunchKernelGGL(pack_weights_h_kernel<2>, dim3(blocks), dim3(256), 0, stream, w_oihw,
                            static_cast<unsigned short *>(wp), c_out, c_in, k, flip_transpose, mt, k == 4 ? 1 : 0, gemm_m, gemm_c8, total);
+    return hipGetLastError();
+}
+
+hipError_t launch_pack_weights_h_batch(const PackHJob *jobs, int n, int dtype, hipStream_t stream)
+{
+    if (n < 1 || n > BATCH_MAX || (dtype != 1 && dtype != 2)) return hipErrorInvalidValue;
+    PackHJobs b;
+    long most = 1;
+    for (int t = 0; t < n; ++t) {
+        const PackHJob &j = jobs[t];
+        PackHJobDev &o = b.job[t];
+        o.w = j.w; o.wp = static_cast<unsigned short *>(j.wp);
+        o.c_out = j.c_out; o.c_in = j.c_in; o.k = j.k; o.flip_transpose = j.flip_transpose;
+        o.gemm_m = j.flip_transpose ? j.c_in : j.c_out;
+        o.gemm_c8 = ((j.flip_transpose ? j.c_out : j.c_in) + 7) / 8;
+        o.mt = j.mt > 0 ? j.mt : conv_h_mt(o.gemm_m, j.k);
+        o.map4 = j.k == 4 ? 1 : 0;
+        o.total = packed_h_elems(o.gemm_m, o.gemm_c8, j.k, o.mt);
+        most = o.total > most ? o.total : most;
+    }
+    const int blocks = (int)((most + 255) / 256 < 256 ? (most + 255) / 256 : 256);
+    if (dtype == 1) hipLaunchKernelGGL(pack_weights_h_batch_kernel<1>, dim3(blocks, n), dim3(256), 0, stream, b);
+    else hipLaunchKernelGGL(pack_weights_h_batch_kernel<2>, dim3(blocks, n), dim3(256), 0, stream, b);
     return hipGetLastError();
 }
 

@@ -315,6 +315,30 @@ hipError_t launch_sgd_f32(float *w, const float *dw, float *v, long count, float
     return hipGetLastError();
 }
 
+// one launch for all parameter tensors of a net: blockIdx.y selects the tensor
+__global__ void sgd_batch_f32_kernel(SgdBatch b, float lr, float mu, float wd)
+{
+    const int t = blockIdx.y;
+    float *w = b.w[t], *v = b.v[t];
+    const float *dw = b.dw[t];
+    const long count = b.count[t];
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < count; q += (long)gridDim.x * blockDim.x) {
+        const float g = dw[q] + wd * w[q];
+        const float vel = (v ? mu * v[q] : 0.f) + lr * g;
+        if (v) v[q] = vel;
+        w[q] -= vel;
+    }
+}
+
+hipError_t launch_sgd_batch_f32(const SgdBatch &b, float lr, float mu, float wd, hipStream_t stream)
+{
+    if (b.n < 1 || b.n > BATCH_MAX) return hipErrorInvalidValue;
+    long most = 1;
+    for (int t = 0; t < b.n; ++t) most = b.count[t] > most ? b.count[t] : most;
+    hipLaunchKernelGGL(sgd_batch_f32_kernel, dim3(grid_for(most, 256, 256), b.n), dim3(256), 0, stream, b, lr, mu, wd);
+    return hipGetLastError();
+}
+
 // ---- crop-and-place copy (the two halves of MergeCrop, Section 5.3.1) -----------------------------------
 __global__ void crop_copy_f32_kernel(const float *in, float *out, int n, int maps, int hi, int wi,
                                      int out_maps, int o_off, int ho, int wo, int oy, int ox)

@@ -376,7 +376,7 @@ hipError_t launch_tap_to_index_h(const void *tap, int32_t *idx, int n, int c, in
 
 // db[o] = sum over images and pixels of dY (octet layout), in two stages with a fixed summation
 // order: workgroup (s, octet) sums slice s of the pixels of its octet over all images into
-// part[(8*octet + e) * slices + s]; bias_grad_finish_kernel (kernels_wgrad_f32.hip) adds the slices.
+// part[(8*octet + e) * slices + s]; wgrad_reduce_kernel (kernels_wgrad_f32.hip) adds the slices.
 template <int DT>
 __global__ void __launch_bounds__(256) bias_grad_h_kernel(const uint4v *__restrict__ dy, float *__restrict__ part, int n, int c,
                                                           long plane, int slices)

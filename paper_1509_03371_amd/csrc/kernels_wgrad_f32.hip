@@ -92,8 +92,10 @@ __global__ __launch_bounds__(256) void wgrad_f32_kernel(WgradArgs a)
             const float *dyp = static_cast<const float *>(a.dy), *xp = static_cast<const float *>(a.x);
             // dY rows of this segment (zero beyond the map and for padded output maps)
             const int xl = x0 + lane < a.Wo ? x0 + lane : a.Wo - 1;
+            // only the rows of this workgroup's map group (several groups: each reads its own part of dY)
+            const int row_end = (mo0 + MB) * 16 < m_rows ? (mo0 + MB) * 16 : m_rows;
 #pragma unroll 4
-            for (int row = wave; row < m_rows; row += 4) {
+            for (int row = mo0 * 16 + wave; row < row_end; row += 4) {
                 const int rc = row < a.c_out ? row : a.c_out - 1;
                 const float v = dyp[((long)b * a.c_out + rc) * yplane + (long)y * a.Wo + xl];
                 dys[row * WG_DYP + lane] = (row < a.c_out && x0 + lane < a.Wo) ? v : 0.f;
@@ -115,8 +117,9 @@ __global__ __launch_bounds__(256) void wgrad_f32_kernel(WgradArgs a)
             const uint4v *dyp = static_cast<const uint4v *>(a.dy), *xp = static_cast<const uint4v *>(a.x);
             const int c8o = (a.c_out + 7) / 8, c8i = (a.c_in + 7) / 8;
             const int xl = x0 + lane < a.Wo ? x0 + lane : a.Wo - 1;
+            const int oc_end = (mo0 + MB) * 2 < a.MTo * 2 ? (mo0 + MB) * 2 : a.MTo * 2;
 #pragma unroll 2
-            for (int oc = wave; oc < a.MTo * 2; oc += 4) {
+            for (int oc = mo0 * 2 + wave; oc < oc_end; oc += 4) {
                 const int occ = oc < c8o ? oc : c8o - 1;
                 const uint4v u = dyp[((long)b * c8o + occ) * yplane + (long)y * a.Wo + xl];
                 const bool ok = oc < c8o && x0 + lane < a.Wo;
@@ -173,26 +176,242 @@ __global__ __launch_bounds__(256) void wgrad_f32_kernel(WgradArgs a)
     }
 }
 
-// dW[o][cij] = sum over the private copies.  Four running sums over copies 4i, 4i+1, 4i+2, 4i+3 keep
-// four loads in flight; the order is fixed, so the result is reproducible.
-__global__ void wgrad_reduce_kernel(const float *__restrict__ scratch, float *__restrict__ dw, int copies, int c_out, int K,
-                                    int m_rows, int ncols)
+// ------------------------------------------------------------------------------------------------
+// The same gradient on the 16-bit matrix path (MFMA 16x16x32, bf16 or fp16 operands, fp32
+// accumulation) for 16-bit storage.  The contraction runs over pixels, so a lane must supply 8
+// consecutive pixels of ONE map -- the octet layout holds 8 maps of one pixel -- and the staging
+// loop is where the transposition happens: it scatters every loaded octet into map-major LDS rows
+// (pixels contiguous), exactly as the fp32-path kernel above does.  An A fragment (dY) is then one
+// aligned 16-byte LDS read; a B fragment (X shifted by tap column j) starts j*d elements into its
+// row, so its alignment is that of j*d: RB = 16, 8 or 4 bytes per read for d % 8 == 0 (and 1x1
+// kernels), d % 4 == 0, d % 2 == 0.  Odd d stays on the fp32-path kernel.
+typedef __bf16 bf16x8v __attribute__((ext_vector_type(8)));
+typedef _Float16 halfx8v __attribute__((ext_vector_type(8)));
+typedef unsigned int uint2v __attribute__((ext_vector_type(2)));
+template <int DT> __device__ __forceinline__ floatx4 mfma32(uint4v a, uint4v b, floatx4 c);
+template <> __device__ __forceinline__ floatx4 mfma32<1>(uint4v a, uint4v b, floatx4 c)
 {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8v, a), __builtin_bit_cast(bf16x8v, b), c, 0, 0, 0);
+}
+template <> __device__ __forceinline__ floatx4 mfma32<2>(uint4v a, uint4v b, floatx4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(halfx8v, a), __builtin_bit_cast(halfx8v, b), c, 0, 0, 0);
+}
+// 8 consecutive 16-bit elements from LDS at an address aligned to RB bytes
+template <int RB> __device__ __forceinline__ uint4v lds_read8(const unsigned short *p)
+{
+    if constexpr (RB == 16) return *reinterpret_cast<const uint4v *>(p);
+    else if constexpr (RB == 8) {
+        const uint2v lo = *reinterpret_cast<const uint2v *>(p), hi = *reinterpret_cast<const uint2v *>(p + 4);
+        return uint4v{lo[0], lo[1], hi[0], hi[1]};
+    } else {
+        const unsigned *q = reinterpret_cast<const unsigned *>(p);
+        return uint4v{q[0], q[1], q[2], q[3]};
+    }
+}
+
+constexpr int WG_DYH = WG_SEG + 8;   // LDS pitch (elements) of a dY row: rows stay 16-byte aligned
+
+// Staging is what this kernel's time goes to (a segment is only 72 MFMAs per wave), so the global
+// loads of the next segment -- this wave's dY octets and the first batch of its input rows -- are
+// issued before the MFMA loop and sit in registers until the next trip writes them to LDS; a net
+// with more input rows than one batch holds (XU row ids per wave) loads the rest in place.
+template <int MB, int NB, int DT, int RB>
+__global__ __launch_bounds__(256) void wgrad_h_kernel(WgradArgs a)
+{
+    constexpr int DYL = (2 * MB + 3) / 4;   // dY octet loads per wave and segment
+    constexpr int XU = 6, XV = 2;           // input loads per wave and batch: XU row ids x XV groups of 64 columns
+    extern __shared__ uint4v smem16[];
+    const int k = a.k, d = a.d, K = a.c_in * k * k;
+    const int m_rows = a.MTo * 16;
+    unsigned short *dys = reinterpret_cast<unsigned short *>(smem16);   // [m_rows][WG_DYH]
+    unsigned short *xs = dys + m_rows * WG_DYH;                          // [8*ceil(c_in/8)*k][xpitch]
+    const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, g = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int PW = WG_SEG + (k - 1) * d;        // <= 64 * XV (checked by the launcher)
+
+    const int ngroups = (a.NTk + 4 * NB - 1) / (4 * NB);
+    const int mgroup = blockIdx.y / ngroups, ngroup = blockIdx.y - mgroup * ngroups;
+    const int mo0 = mgroup * MB;
+    int xoff[NB];
+#pragma unroll
+    for (int q = 0; q < NB; ++q) {
+        const int nk = (ngroup * NB + q) * 4 + wave;
+        const int cij = nk * 16 + l16;
+        int off = 0;
+        if (nk < a.NTk && cij < K) {
+            const int c = cij / (k * k), r = cij - c * k * k, i = r / k, j = r - i * k;
+            off = (c * k + i) * a.xpitch + j * d;
+        }
+        xoff[q] = off + 8 * g;
+    }
+    floatx4 acc[MB][NB];
+#pragma unroll
+    for (int m = 0; m < MB; ++m)
+#pragma unroll
+        for (int q = 0; q < NB; ++q) acc[m][q] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    const long xplane = (long)a.H * a.W, yplane = (long)a.Ho * a.Wo;
+    const uint4v *dyp = static_cast<const uint4v *>(a.dy), *xp = static_cast<const uint4v *>(a.x);
+    const int c8o = (a.c_out + 7) / 8, c8i = (a.c_in + 7) / 8;
+    const int oc_end = (mo0 + MB) * 2 < a.MTo * 2 ? (mo0 + MB) * 2 : a.MTo * 2;
+    const int nrid = c8i * k;                                   // (input octet, kernel row) pairs to stage
+    const int nbat = (nrid + 4 * XU - 1) / (4 * XU);
+    const int kxp = k * a.xpitch;                               // LDS distance between the 8 maps of an octet
+
+    uint4v pdy[DYL], px[XU][XV];
+    // all addresses are clamped into the tensors; what lies outside is replaced by zero when it is stored
+    auto load_dy = [&](int b, int y, int x0) {
+        const int xl = x0 + lane < a.Wo ? x0 + lane : a.Wo - 1;
+#pragma unroll
+        for (int t = 0; t < DYL; ++t) {
+            const int oc = mo0 * 2 + wave + 4 * t;
+            const int occ = oc < c8o ? oc : c8o - 1;
+            pdy[t] = dyp[((long)b * c8o + occ) * yplane + (long)y * a.Wo + xl];
+        }
+    };
+    auto load_x = [&](int bat, int b, int y, int x0) {
+#pragma unroll
+        for (int u = 0; u < XU; ++u) {
+            const int rid = wave + 4 * (bat * XU + u);
+            const int ridc = rid < nrid ? rid : nrid - 1;
+            const int oc = ridc / k, i = ridc - oc * k;
+            const uint4v *src = xp + ((long)b * c8i + oc) * xplane + (long)(y + i * d) * a.W;
+#pragma unroll
+            for (int v = 0; v < XV; ++v) {
+                const int xc = lane + 64 * v;
+                px[u][v] = src[x0 + xc < a.W ? x0 + xc : a.W - 1];
+            }
+        }
+    };
+    auto scatter = [&](unsigned short *dst, int stride, uint4v u, bool ok) {
+        if (!ok) u = uint4v{0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dst[e * stride] = (unsigned short)((u[e >> 1] >> ((e & 1) * 16)) & 0xffffu);
+    };
+    auto store_dy = [&](int x0) {
+#pragma unroll
+        for (int t = 0; t < DYL; ++t) {
+            const int oc = mo0 * 2 + wave + 4 * t;
+            if (oc < oc_end) scatter(dys + oc * 8 * WG_DYH + lane, WG_DYH, pdy[t], oc < c8o && x0 + lane < a.Wo);
+        }
+    };
+    auto store_x = [&](int bat, int x0) {
+#pragma unroll
+        for (int u = 0; u < XU; ++u) {
+            const int rid = wave + 4 * (bat * XU + u);
+            if (rid >= nrid) continue;                          // uniform
+            const int oc = rid / k, i = rid - oc * k;
+            unsigned short *row = xs + (oc * 8 * k + i) * a.xpitch;
+#pragma unroll
+            for (int v = 0; v < XV; ++v) {
+                const int xc = lane + 64 * v;
+                if (xc < PW) scatter(row + xc, kxp, px[u][v], x0 + xc < a.W);
+            }
+        }
+    };
+    auto locate = [&](int seg, int &b, int &y, int &x0) {
+        const int xs_i = seg % a.xsegs, t = seg / a.xsegs;
+        y = t % a.Ho;
+        b = t / a.Ho;
+        x0 = xs_i * WG_SEG;
+    };
+
+    int seg = blockIdx.x, b = 0, y = 0, x0 = 0;
+    if (seg < a.total_segs) {
+        locate(seg, b, y, x0);
+        load_dy(b, y, x0);
+        load_x(0, b, y, x0);
+    }
+    for (; seg < a.total_segs; seg += gridDim.x) {
+        __syncthreads();                                        // the previous segment's MFMAs have read LDS
+        store_dy(x0);
+        store_x(0, x0);
+        for (int bat = 1; bat < nbat; ++bat) {
+            load_x(bat, b, y, x0);
+            store_x(bat, x0);
+        }
+        __syncthreads();
+        const int nseg = seg + gridDim.x;
+        if (nseg < a.total_segs) {                              // in flight while this segment is multiplied
+            locate(nseg, b, y, x0);
+            load_dy(b, y, x0);
+            load_x(0, b, y, x0);
+        }
+#pragma unroll
+        for (int p = 0; p < WG_SEG; p += 32) {
+            uint4v av[MB];
+#pragma unroll
+            for (int m = 0; m < MB; ++m) {
+                const int row = (mo0 + m) * 16 + l16;
+                av[m] = uint4v{0u, 0u, 0u, 0u};
+                if (mo0 + m < a.MTo) av[m] = *reinterpret_cast<const uint4v *>(dys + row * WG_DYH + p + 8 * g);
+            }
+#pragma unroll
+            for (int q = 0; q < NB; ++q) {
+                const uint4v bv = lds_read8<RB>(xs + xoff[q] + p);
+#pragma unroll
+                for (int m = 0; m < MB; ++m) acc[m][q] = mfma32<DT>(av[m], bv, acc[m][q]);
+            }
+        }
+    }
+    const long ncols = (long)a.NTk * 16;
+    float *dst = a.scratch + (long)blockIdx.x * m_rows * ncols;
+#pragma unroll
+    for (int m = 0; m < MB; ++m) {
+        if (mo0 + m >= a.MTo) continue;
+#pragma unroll
+        for (int q = 0; q < NB; ++q) {
+            const int nk = (ngroup * NB + q) * 4 + wave;
+            if (nk >= a.NTk) continue;
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4)
+                dst[((long)(mo0 + m) * 16 + 4 * g + r4) * ncols + nk * 16 + l16] = acc[m][q][r4];
+        }
+    }
+}
+
+// dW[o][cij] = sum over the private copies, and (last workgroups of the grid) db[o] = sum over the
+// slices of the bias partials.  A workgroup of 256 threads sums 64 consecutive elements: wave w takes
+// the copies w, w+4, w+8, ... with four running sums (copies w+4(4i+u), u = 0..3), so that sixteen
+// loads per element are in flight and the grid has a few hundred workgroups even for a 48x768
+// gradient; the four waves' sums are added through LDS.  The order is fixed: reproducible results.
+constexpr int RED_ELEMS = 64;
+__global__ void __launch_bounds__(256) wgrad_reduce_kernel(const float *__restrict__ scratch, float *__restrict__ dw, int copies, int c_out, int K,
+                                                           int m_rows, int ncols, int dw_blocks, const float *__restrict__ bias_part,
+                                                           float *__restrict__ db, int slices)
+{
+    __shared__ float sh[4][RED_ELEMS];
+    const int e = threadIdx.x & 63, w = threadIdx.x >> 6;
+    if ((int)blockIdx.x >= dw_blocks) {
+        // bias: 64 maps per workgroup, wave w adds slices w, w+4, ...; then the waves in order
+        const int o = ((int)blockIdx.x - dw_blocks) * RED_ELEMS + e;
+        float v = 0.f;
+        if (o < c_out)
+            for (int sl = w; sl < slices; sl += 4) v += bias_part[(long)o * slices + sl];
+        sh[w][e] = v;
+        __syncthreads();
+        if (w == 0 && o < c_out) db[o] = (sh[0][e] + sh[1][e]) + (sh[2][e] + sh[3][e]);
+        return;
+    }
     const long total = (long)c_out * K, stride = (long)m_rows * ncols;
-    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
+    const long q = (long)blockIdx.x * RED_ELEMS + e;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    if (q < total) {
         const int o = (int)(q / K), cij = (int)(q - (long)o * K);
         const float *src = scratch + (long)o * ncols + cij;
-        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-        int cpy = 0;
-        for (; cpy + 4 <= copies; cpy += 4) {
+        int cpy = w;
+        for (; cpy + 12 < copies; cpy += 16) {
             s0 += src[(cpy + 0) * stride];
-            s1 += src[(cpy + 1) * stride];
-            s2 += src[(cpy + 2) * stride];
-            s3 += src[(cpy + 3) * stride];
+            s1 += src[(cpy + 4) * stride];
+            s2 += src[(cpy + 8) * stride];
+            s3 += src[(cpy + 12) * stride];
         }
-        for (; cpy < copies; ++cpy) s0 += src[cpy * stride];
-        dw[q] = (s0 + s1) + (s2 + s3);
+        for (; cpy < copies; cpy += 4) s0 += src[cpy * stride];
     }
+    sh[w][e] = (s0 + s1) + (s2 + s3);
+    __syncthreads();
+    if (w == 0 && q < total) dw[q] = (sh[0][e] + sh[1][e]) + (sh[2][e] + sh[3][e]);
 }
 
 // Bias gradient db[o] = sum over images and pixels of dY, in two stages with a fixed summation order.
@@ -216,16 +435,6 @@ __global__ void __launch_bounds__(256) bias_grad_kernel(const float *__restrict_
     if (threadIdx.x == 0) part[(long)o * slices + sl] = sh[0] + sh[1] + sh[2] + sh[3];
 }
 
-// Stage 2: db[o] = part[o][0] + part[o][1] + ... in slice order
-__global__ void bias_grad_finish_kernel(const float *__restrict__ part, float *__restrict__ db, int c_out, int slices)
-{
-    const int o = blockIdx.x * blockDim.x + threadIdx.x;
-    if (o >= c_out) return;
-    float s = 0.f;
-    for (int sl = 0; sl < slices; ++sl) s += part[(long)o * slices + sl];
-    db[o] = s;
-}
-
 static void wgrad_tiling(int c_out, int c_in, int k, int &MTo, int &NTk, int &MB, int &NB)
 {
     MTo = (c_out + 15) / 16;
@@ -238,7 +447,8 @@ size_t wgrad_f32_scratch_floats(int c_out, int c_in, int k)
 {
     int MTo, NTk, MB, NB;
     wgrad_tiling(c_out, c_in, k, MTo, NTk, MB, NB);
-    return (size_t)WG_MAX_BLOCKS * MTo * 16 * NTk * 16;
+    // private dW copies, then the bias partials (8 * ceil(c_out/8) maps x BG_SLICES)
+    return (size_t)WG_MAX_BLOCKS * MTo * 16 * NTk * 16 + (size_t)(c_out + 7) / 8 * 8 * BG_SLICES;
 }
 
 template <int MB, int NB, int DT>
@@ -256,8 +466,35 @@ static hipError_t launch_wgrad_t(const WgradArgs &a, size_t smem, int blocks, hi
     return hipGetLastError();
 }
 
+template <int MB, int NB, int DT, int RB>
+static hipError_t launch_wgrad_h_t(const WgradArgs &a, size_t smem, int blocks, hipStream_t stream)
+{
+    static bool attr_set = false;
+    if (smem > 48 * 1024 && !attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_h_kernel<MB, NB, DT, RB>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int mgroups = (a.MTo + MB - 1) / MB, ngroups = (a.NTk + 4 * NB - 1) / (4 * NB);
+    hipLaunchKernelGGL((wgrad_h_kernel<MB, NB, DT, RB>), dim3(blocks, mgroups * ngroups), dim3(256), smem, stream, a);
+    return hipGetLastError();
+}
+
+template <int DT, int RB>
+static hipError_t launch_wgrad_h_rb(const WgradArgs &a, int MB, int NB, size_t smem, int blocks, hipStream_t stream)
+{
+    hipError_t e = hipErrorInvalidValue;
+#define SK_WG_CASE(mb, nb) if (MB == mb && NB == nb) e = launch_wgrad_h_t<mb, nb, DT, RB>(a, smem, blocks, stream);
+    SK_WG_CASE(1, 1) SK_WG_CASE(1, 4) SK_WG_CASE(1, 12)
+    SK_WG_CASE(3, 1) SK_WG_CASE(3, 4) SK_WG_CASE(3, 12)
+    SK_WG_CASE(4, 1) SK_WG_CASE(4, 4) SK_WG_CASE(4, 12)
+#undef SK_WG_CASE
+    return e;
+}
+
 template <int DT>
-static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, float *scratch, int n, int c_in, int H,
+static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, float *db, float *scratch, int n, int c_in, int H,
                                   int W, int c_out, int k, int d, hipStream_t stream)
 {
     WgradArgs a;
@@ -270,9 +507,12 @@ static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, floa
     a.xsegs = (a.Wo + WG_SEG - 1) / WG_SEG;
     a.total_segs = a.xsegs * a.Ho * n;
     const int PW = WG_SEG + (k - 1) * d;
-    a.xpitch = (PW + 31) / 32 * 32 + 4;
+    // 16-bit storage with an even kernel stride (or a 1x1 kernel): the 16-bit matrix path
+    const bool h_path = DT != 0 && (k == 1 || d % 2 == 0) && PW <= 128;
+    a.xpitch = h_path ? (PW + 7) / 8 * 8 + 8 : (PW + 31) / 32 * 32 + 4;
     const int x_rows = (DT == 0 ? c_in : (c_in + 7) / 8 * 8) * k;
-    const size_t smem = (DT == 0 ? sizeof(float) : sizeof(unsigned short)) * ((size_t)a.MTo * 16 * WG_DYP + (size_t)x_rows * a.xpitch);
+    const size_t smem = (DT == 0 ? sizeof(float) : sizeof(unsigned short)) *
+                        ((size_t)a.MTo * 16 * (h_path ? WG_DYH : WG_DYP) + (size_t)x_rows * a.xpitch);
     if (smem > 150 * 1024) return hipErrorInvalidValue;
     // as many persistent workgroups as fit on the GPU at once (more would only add private copies
     // for the reduction to read): LDS decides
@@ -283,16 +523,40 @@ static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, floa
     if (resident > WG_MAX_BLOCKS) resident = WG_MAX_BLOCKS;
     const int blocks = a.total_segs < resident ? a.total_segs : (int)resident;
     hipError_t e = hipErrorInvalidValue;
+    if constexpr (DT != 0) {
+        if (h_path) {
+            if (k == 1 || d % 8 == 0) e = launch_wgrad_h_rb<DT, 16>(a, MB, NB, smem, blocks, stream);
+            else if (d % 4 == 0) e = launch_wgrad_h_rb<DT, 8>(a, MB, NB, smem, blocks, stream);
+            else e = launch_wgrad_h_rb<DT, 4>(a, MB, NB, smem, blocks, stream);
+        }
+    }
+    if (!h_path) {
 #define SK_WG_CASE(mb, nb) if (MB == mb && NB == nb) e = launch_wgrad_t<mb, nb, DT>(a, smem, blocks, stream);
-    SK_WG_CASE(1, 1) SK_WG_CASE(1, 4) SK_WG_CASE(1, 12)
-    SK_WG_CASE(3, 1) SK_WG_CASE(3, 4) SK_WG_CASE(3, 12)
-    SK_WG_CASE(4, 1) SK_WG_CASE(4, 4) SK_WG_CASE(4, 12)
+        SK_WG_CASE(1, 1) SK_WG_CASE(1, 4) SK_WG_CASE(1, 12)
+        SK_WG_CASE(3, 1) SK_WG_CASE(3, 4) SK_WG_CASE(3, 12)
+        SK_WG_CASE(4, 1) SK_WG_CASE(4, 4) SK_WG_CASE(4, 12)
 #undef SK_WG_CASE
+    }
     if (e != hipSuccess) return e;
+    // stage 1 of the bias gradient into the partials behind the dW copies, then one kernel that sums
+    // the copies and the partials
+    float *bias_part = scratch + (size_t)WG_MAX_BLOCKS * a.MTo * 16 * a.NTk * 16;
+    if (db) {
+        const long plane = (long)a.Ho * a.Wo;
+        if constexpr (DT == 0) {
+            hipLaunchKernelGGL(bias_grad_kernel, dim3(BG_SLICES, c_out), dim3(256), 0, stream, static_cast<const float *>(dy), bias_part,
+                               n, c_out, plane, BG_SLICES);
+            e = hipGetLastError();
+        } else {
+            e = launch_bias_grad_h(dy, bias_part, DT, n, c_out, plane, BG_SLICES, stream);
+        }
+        if (e != hipSuccess) return e;
+    }
     const int K = c_in * k * k;
     const long total = (long)c_out * K;
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((int)((total + 255) / 256)), dim3(256), 0, stream, scratch, dw,
-                       blocks, c_out, K, a.MTo * 16, a.NTk * 16);
+    const int dw_blocks = (int)((total + RED_ELEMS - 1) / RED_ELEMS), db_blocks = db ? (c_out + RED_ELEMS - 1) / RED_ELEMS : 0;
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(dw_blocks + db_blocks), dim3(256), 0, stream, scratch, dw, blocks, c_out, K,
+                       a.MTo * 16, a.NTk * 16, dw_blocks, bias_part, db, BG_SLICES);
     return hipGetLastError();
 }
 
@@ -300,31 +564,16 @@ hipError_t launch_wgrad_f32(const float *x, const float *dy, float *dw, float *d
                             int n, int c_in, int H, int W, int c_out, int k, int d,
                             hipStream_t stream)
 {
-    hipError_t e = launch_wgrad_dt<0>(x, dy, dw, scratch, n, c_in, H, W, c_out, k, d, stream);
-    if (e != hipSuccess) return e;
-    if (db) {                                   // the private dW copies in scratch have been consumed (stream order)
-        const long plane = (long)(H - (k - 1) * d) * (W - (k - 1) * d);
-        hipLaunchKernelGGL(bias_grad_kernel, dim3(BG_SLICES, c_out), dim3(256), 0, stream, dy, scratch, n, c_out, plane, BG_SLICES);
-        hipLaunchKernelGGL(bias_grad_finish_kernel, dim3((c_out + 255) / 256), dim3(256), 0, stream, scratch, db, c_out, BG_SLICES);
-    }
-    return hipGetLastError();
+    return launch_wgrad_dt<0>(x, dy, dw, db, scratch, n, c_in, H, W, c_out, k, d, stream);
 }
 
 // same gradient from 16-bit octet-layout activations (dtype 1 = bf16, 2 = fp16): the operands are
-// widened to fp32 while they are staged, the contraction runs on the fp32 MFMA path
+// staged as they are and widened to fp32 when read, the contraction runs on the fp32 MFMA path
 hipError_t launch_wgrad_h(const void *x, const void *dy, float *dw, float *db, float *scratch, int dtype,
                           int n, int c_in, int H, int W, int c_out, int k, int d, hipStream_t stream)
 {
-    hipError_t e = dtype == 1 ? launch_wgrad_dt<1>(x, dy, dw, scratch, n, c_in, H, W, c_out, k, d, stream)
-                              : launch_wgrad_dt<2>(x, dy, dw, scratch, n, c_in, H, W, c_out, k, d, stream);
-    if (e != hipSuccess) return e;
-    if (db) {
-        e = launch_bias_grad_h(dy, scratch, dtype, n, c_out, (long)(H - (k - 1) * d) * (W - (k - 1) * d), BG_SLICES, stream);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(bias_grad_finish_kernel, dim3((c_out + 255) / 256), dim3(256), 0, stream, scratch, db, c_out, BG_SLICES);
-        return hipGetLastError();
-    }
-    return hipSuccess;
+    return dtype == 1 ? launch_wgrad_dt<1>(x, dy, dw, db, scratch, n, c_in, H, W, c_out, k, d, stream)
+                      : launch_wgrad_dt<2>(x, dy, dw, db, scratch, n, c_in, H, W, c_out, k, d, stream);
 }
 
 }  // namespace sk

@@ -35,6 +35,9 @@ hipError_t launch_conv_f32(const ConvF32Args &a, hipStream_t stream);
 // Rows/columns beyond the real extents are zero.  rows = roundup(in_maps,16)*k*k, cols = n_pad.
 hipError_t launch_pack_weights_f32(const float *w_oihw, float *wp, int c_out, int c_in, int k,
                                    int flip_transpose, int rows, int n_pad, hipStream_t stream);
+// several packings in one launch (n <= 32 jobs)
+struct PackF32Job { const float *w; float *wp; int c_out, c_in, k, flip_transpose, rows, n_pad; };
+hipError_t launch_pack_weights_f32_batch(const PackF32Job *jobs, int n, hipStream_t stream);
 
 // ---- implicit-GEMM SK convolution, 16-bit activations (dtype 1 = bf16, 2 = fp16), MFMA 16x16x32 -------
 // Same contract as launch_conv_f32, on the octet layout: a tensor with C maps is stored as
@@ -67,6 +70,9 @@ int conv_h_pick_mt(int c_out, int k, int n, int Ho, int Wo);
 // packing (flip_transpose = 1: gemm_m = c_in, input octets of c_out) from OIHW fp32 master weights
 hipError_t launch_pack_weights_h(const float *w_oihw, void *wp, int dtype, int c_out, int c_in, int k,
                                  int flip_transpose, int mt, hipStream_t stream);
+// several packings in one launch (n <= 32 jobs, one dtype)
+struct PackHJob { const float *w; void *wp; int c_out, c_in, k, flip_transpose, mt; };
+hipError_t launch_pack_weights_h_batch(const PackHJob *jobs, int n, int dtype, hipStream_t stream);
 
 // ---- HBM-bound layers on the octet layout (dtype 1 = bf16, 2 = fp16) ------------------------------------
 // fp32 NCHW -> octets with optional mirror padding (top = left = 0 and ho = h, wo = w: plain conversion)
@@ -132,6 +138,16 @@ hipError_t launch_softmax_loss_f32(const float *z, const int32_t *labels, float 
 // g = dw + wd*w; v = mu*v + lr*g; w -= v   (v may be nullptr when mu = 0)
 hipError_t launch_sgd_f32(float *w, const float *dw, float *v, long count, float lr, float mu,
                           float wd, hipStream_t stream);
+// the same update for up to BATCH_MAX tensors in one launch (the parameters of a net are many small tensors)
+constexpr int BATCH_MAX = 32;
+struct SgdBatch {
+    float *w[BATCH_MAX];
+    const float *dw[BATCH_MAX];
+    float *v[BATCH_MAX];          // nullptr entries: no momentum buffer
+    long count[BATCH_MAX];
+    int n;
+};
+hipError_t launch_sgd_batch_f32(const SgdBatch &b, float lr, float mu, float wd, hipStream_t stream);
 // out[b, o_off + c, y, x] = in[b, c, y + oy, x + ox] for c < maps (crop-and-place, MergeCrop halves)
 hipError_t launch_crop_copy_f32(const float *in, float *out, int n, int maps, int hi, int wi,
                                 int out_maps, int o_off, int ho, int wo, int oy, int ox,

@@ -539,11 +539,35 @@ sk_status sknet_sgd_step(sknet_t *net, float lr, float momentum, float weight_de
         return fail(SK_ESTATE, "sgd_step: needs a backward pass on a training plan");
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     net->last_stream = stream;
-    for (auto &c : net->convs) {
-        SK_HIP(sk::launch_sgd_f32(c.w_dev, c.dw, momentum != 0.f ? c.vw : nullptr, c.wcount(), lr, momentum, weight_decay, stream));
-        SK_HIP(sk::launch_sgd_f32(c.b_dev, c.db, momentum != 0.f ? c.vb : nullptr, c.c_out, lr, momentum, weight_decay, stream));
-        SK_TRY(repack_conv(c, true, net->dtype, stream));
+    // one launch updates every weight and bias tensor, a second rebuilds every packed form
+    // (a net is a dozen small tensors: one launch each would cost more than the work)
+    const int nc = (int)net->convs.size();
+    if (2 * nc > sk::BATCH_MAX) {
+        for (auto &c : net->convs) {
+            SK_HIP(sk::launch_sgd_f32(c.w_dev, c.dw, momentum != 0.f ? c.vw : nullptr, c.wcount(), lr, momentum, weight_decay, stream));
+            SK_HIP(sk::launch_sgd_f32(c.b_dev, c.db, momentum != 0.f ? c.vb : nullptr, c.c_out, lr, momentum, weight_decay, stream));
+            SK_TRY(repack_conv(c, true, net->dtype, stream));
+        }
+        return SK_OK;
     }
+    sk::SgdBatch sb{};
+    sk::PackF32Job pf[sk::BATCH_MAX];
+    sk::PackHJob ph[sk::BATCH_MAX];
+    int np = 0;
+    for (auto &c : net->convs) {
+        sb.w[sb.n] = c.w_dev; sb.dw[sb.n] = c.dw; sb.v[sb.n] = momentum != 0.f ? c.vw : nullptr; sb.count[sb.n] = c.wcount(); ++sb.n;
+        sb.w[sb.n] = c.b_dev; sb.dw[sb.n] = c.db; sb.v[sb.n] = momentum != 0.f ? c.vb : nullptr; sb.count[sb.n] = c.c_out; ++sb.n;
+        if (net->dtype == SK_F32) {
+            pf[np++] = {c.w_dev, c.wp_fwd, c.c_out, c.c_in, c.k, 0, c.rows_fwd, c.n_pad};
+            if (c.wp_bwd) pf[np++] = {c.w_dev, c.wp_bwd, c.c_out, c.c_in, c.k, 1, c.rows_bwd, c.n_pad_bwd};
+        } else {
+            ph[np++] = {c.w_dev, c.wp16_fwd, c.c_out, c.c_in, c.k, 0, c.mt16};
+            if (c.wp16_bwd) ph[np++] = {c.w_dev, c.wp16_bwd, c.c_out, c.c_in, c.k, 1, 0};
+        }
+    }
+    SK_HIP(sk::launch_sgd_batch_f32(sb, lr, momentum, weight_decay, stream));
+    if (net->dtype == SK_F32) SK_HIP(sk::launch_pack_weights_f32_batch(pf, np, stream));
+    else SK_HIP(sk::launch_pack_weights_h_batch(ph, np, net->dtype, stream));
     return SK_OK;
 }
 
