@@ -519,10 +519,100 @@ static hipError_t launch_conv_f32_nt(const ConvF32Args &a, hipStream_t stream)
     return launch_conv_f32_t<NT, 2>(a, stream);
 }
 
+// ------------------------------------------------------------------------------------------------
+// One input map (the first layer of the BASELINE nets): K = k*k is a single MFMA step or two, and
+// the layer is bound by writing its output, so it runs on the vector ALU instead.  A thread owns PX
+// output pixels (64 apart in the flattened [Ho*Wo] plane, so every load and store of a wave covers
+// 64 consecutive pixels), keeps their k*k taps in registers and walks over the output maps four at a
+// time; the weights sit in LDS and are read with wave-uniform addresses, four per instruction.
+template <int KS, int PX>
+__global__ __launch_bounds__(256) void conv_c1_f32_kernel(const float *__restrict__ x, const float *__restrict__ wp,
+                                                          const float *__restrict__ bias, float *__restrict__ y, int H, int W,
+                                                          int Ho, int Wo, int d, int c_out, int n_pad, int out_maps, int o_off, int relu)
+{
+    constexpr int KK = KS * KS;
+    extern __shared__ float smem[];                 // [KK][n_pad] weights, then [n_pad] bias
+    float *wl = smem, *bl = smem + KK * n_pad;
+    for (int q = threadIdx.x; q < KK * n_pad; q += 256) wl[q] = wp[q];
+    for (int q = threadIdx.x; q < n_pad; q += 256) bl[q] = bias ? bias[q] : 0.f;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, b = blockIdx.y;
+    const long P = (long)Ho * Wo;
+    const long base = ((long)blockIdx.x * 4 + wave) * 64 * PX + lane;
+    const float *xin = x + (long)b * H * W;
+    float tap[KK][PX];
+#pragma unroll
+    for (int p = 0; p < PX; ++p) {
+        long q = base + 64 * p;
+        q = q < P ? q : P - 1;
+        const int oy = (int)(q / Wo), ox = (int)(q - (long)oy * Wo);
+#pragma unroll
+        for (int i = 0; i < KS; ++i)
+#pragma unroll
+            for (int j = 0; j < KS; ++j) tap[i * KS + j][p] = xin[(long)(oy + i * d) * W + ox + j * d];
+    }
+    __syncthreads();
+    float *yb = y + ((long)b * out_maps + o_off) * P;
+    unsigned qoff[PX];
+    bool qok[PX];
+#pragma unroll
+    for (int p = 0; p < PX; ++p) {
+        qok[p] = base + 64 * p < P;
+        qoff[p] = qok[p] ? 4u * (unsigned)(base + 64 * p) : 0u;
+    }
+    // four output maps per trip: 4*PX accumulators next to the k*k*PX taps
+#pragma unroll 1
+    for (int o4 = 0; o4 < n_pad; o4 += 4) {
+        if (o4 >= c_out) break;                                  // uniform
+        floatx4 acc[PX];
+        const floatx4 bv = *reinterpret_cast<const floatx4 *>(bl + o4);
+#pragma unroll
+        for (int p = 0; p < PX; ++p) acc[p] = bv;
+#pragma unroll
+        for (int t = 0; t < KK; ++t) {
+            const floatx4 w = *reinterpret_cast<const floatx4 *>(wl + t * n_pad + o4);
+#pragma unroll
+            for (int p = 0; p < PX; ++p)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[p][e] = fmaf(w[e], tap[t][p], acc[p][e]);
+        }
+        // scalar base of the map plus a 32-bit byte offset per lane (4*P < 2^32, checked by the launcher)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (o4 + e >= c_out) break;                          // uniform
+            char *ymap = reinterpret_cast<char *>(yb + (long)(o4 + e) * P);
+#pragma unroll
+            for (int p = 0; p < PX; ++p) {
+                const float v = relu ? fmaxf(acc[p][e], 0.f) : acc[p][e];
+                if (qok[p]) *reinterpret_cast<float *>(ymap + qoff[p]) = v;
+            }
+        }
+    }
+}
+
+template <int KS>
+static hipError_t launch_conv_c1_f32(const ConvF32Args &a, hipStream_t stream)
+{
+    constexpr int PX = 4;
+    const long P = (long)a.Ho * a.Wo;
+    const long blocks = (P + 256 * PX - 1) / (256 * PX);
+    if (blocks > 0x7fffffffL || a.n > 65535 || P >= (1L << 29)) return hipErrorInvalidValue;
+    const size_t smem = sizeof(float) * ((size_t)KS * KS + 1) * a.n_pad;
+    if (smem > 48 * 1024) return hipErrorInvalidValue;          // callers check c_out first
+    hipLaunchKernelGGL((conv_c1_f32_kernel<KS, PX>), dim3((unsigned)blocks, a.n), dim3(256), smem, stream, a.x, a.wp, a.bias, a.y, a.H, a.W,
+                       a.Ho, a.Wo, a.d, a.c_out, a.n_pad, a.out_maps, a.o_off, a.relu);
+    return hipGetLastError();
+}
+
 hipError_t launch_conv_f32(const ConvF32Args &a, hipStream_t stream)
 {
     if (a.n_pad % 16 != 0 || a.c_out > a.n_pad || a.k < 1 || a.d < 1 || a.Ho < 1 || a.Wo < 1)
         return hipErrorInvalidValue;
+    // a single input map, plain forward placement (contiguous NCHW output, no mask)
+    if (a.c_in == 1 && a.in_off == 0 && !a.mask && a.OH == a.Ho && a.OW == a.Wo && a.oy_mul == 1 && a.ox_mul == 1 &&
+        a.oy_off == 0 && a.ox_off == 0 && a.Ho == a.H - (a.k - 1) * a.d && a.Wo == a.W - (a.k - 1) * a.d && a.n_pad <= 512) {
+        if (a.k == 3) return launch_conv_c1_f32<3>(a, stream);
+        if (a.k == 4) return launch_conv_c1_f32<4>(a, stream);
+    }
     const int tiles = a.n_pad / 16;
     if (tiles == 1) return launch_conv_f32_nt<1>(a, stream);
     if (tiles == 2) return launch_conv_f32_nt<2>(a, stream);
