@@ -1021,6 +1021,20 @@ bool conv_h_supported(int k, int d)
     return (k >= 1 && k <= 4) && CH_TX + (k - 1) * d <= 64 * CH_VU;
 }
 
+// ... and the two-stage tile of the register-staged kernel (what every shape can fall back to) fits
+// the LDS for a GEMM with gemm_m output maps: a 3x3 kernel with 48 maps or more stops at d = 6
+bool conv_h_supported(int k, int d, int gemm_m)
+{
+    if (!conv_h_supported(k, d) || gemm_m < 1) return false;
+    const int mt = conv_h_mt(gemm_m, k);
+    const bool map4 = k == 4;
+    const int R = map4 && mt <= 3 ? 8 : 4, RR = R + k - 1, OC = map4 ? 1 : 4, CS = map4 ? 1 : k;
+    const long PW = CH_TX + (k - 1) * d;
+    const long stage = OC * RR * PW + (long)CS * k * mt * 64;
+    const long m_tiles_all = ((gemm_m + 15) / 16 + mt - 1) / mt * mt;
+    return 2 * stage * 16 + m_tiles_all * 64 <= 160 * 1024;
+}
+
 hipError_t launch_conv_h(const ConvHArgs &a, hipStream_t stream)
 {
     if (!conv_h_supported(a.k, a.d) || a.Ho < 1 || a.Wo < 1 || a.c8_in < 1 || a.c_out < 1) return hipErrorInvalidValue;

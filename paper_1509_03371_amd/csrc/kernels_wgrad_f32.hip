@@ -183,8 +183,9 @@ __global__ __launch_bounds__(256) void wgrad_f32_kernel(WgradArgs a)
 // loop is where the transposition happens: it scatters every loaded octet into map-major LDS rows
 // (pixels contiguous), exactly as the fp32-path kernel above does.  An A fragment (dY) is then one
 // aligned 16-byte LDS read; a B fragment (X shifted by tap column j) starts j*d elements into its
-// row, so its alignment is that of j*d: RB = 16, 8 or 4 bytes per read for d % 8 == 0 (and 1x1
-// kernels), d % 4 == 0, d % 2 == 0.  Odd d stays on the fp32-path kernel.
+// row, so its alignment is that of j*d: RB = 16, 8, 4 or 2 bytes per read for d % 8 == 0 (and 1x1
+// kernels), d % 4 == 0, d % 2 == 0, odd d (eight 2-byte reads per fragment: still far fewer cycles
+// than the fp32 matrix path).
 typedef __bf16 bf16x8v __attribute__((ext_vector_type(8)));
 typedef _Float16 halfx8v __attribute__((ext_vector_type(8)));
 typedef unsigned int uint2v __attribute__((ext_vector_type(2)));
@@ -204,9 +205,14 @@ template <int RB> __device__ __forceinline__ uint4v lds_read8(const unsigned sho
     else if constexpr (RB == 8) {
         const uint2v lo = *reinterpret_cast<const uint2v *>(p), hi = *reinterpret_cast<const uint2v *>(p + 4);
         return uint4v{lo[0], lo[1], hi[0], hi[1]};
-    } else {
+    } else if constexpr (RB == 4) {
         const unsigned *q = reinterpret_cast<const unsigned *>(p);
         return uint4v{q[0], q[1], q[2], q[3]};
+    } else {
+        uint4v r;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) r[e] = (unsigned)p[2 * e] | ((unsigned)p[2 * e + 1] << 16);
+        return r;
     }
 }
 
@@ -507,8 +513,8 @@ static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, floa
     a.xsegs = (a.Wo + WG_SEG - 1) / WG_SEG;
     a.total_segs = a.xsegs * a.Ho * n;
     const int PW = WG_SEG + (k - 1) * d;
-    // 16-bit storage with an even kernel stride (or a 1x1 kernel): the 16-bit matrix path
-    const bool h_path = DT != 0 && (k == 1 || d % 2 == 0) && PW <= 128;
+    // 16-bit storage (and a window of at most 128 columns): the 16-bit matrix path
+    const bool h_path = DT != 0 && PW <= 128;
     a.xpitch = h_path ? (PW + 7) / 8 * 8 + 8 : (PW + 31) / 32 * 32 + 4;
     const int x_rows = (DT == 0 ? c_in : (c_in + 7) / 8 * 8) * k;
     const size_t smem = (DT == 0 ? sizeof(float) : sizeof(unsigned short)) *
@@ -527,7 +533,8 @@ static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, floa
         if (h_path) {
             if (k == 1 || d % 8 == 0) e = launch_wgrad_h_rb<DT, 16>(a, MB, NB, smem, blocks, stream);
             else if (d % 4 == 0) e = launch_wgrad_h_rb<DT, 8>(a, MB, NB, smem, blocks, stream);
-            else e = launch_wgrad_h_rb<DT, 4>(a, MB, NB, smem, blocks, stream);
+            else if (d % 2 == 0) e = launch_wgrad_h_rb<DT, 4>(a, MB, NB, smem, blocks, stream);
+            else e = launch_wgrad_h_rb<DT, 2>(a, MB, NB, smem, blocks, stream);
         }
     }
     if (!h_path) {

@@ -61,6 +61,8 @@ struct ConvHArgs {
     const void *zeros;    // >= 16 bytes of zeros in device memory
 };
 bool conv_h_supported(int k, int d);
+// ... and for a GEMM with gemm_m output maps (c_out forward, c_in for the data gradient) the tile fits the LDS
+bool conv_h_supported(int k, int d, int gemm_m);
 hipError_t launch_conv_h(const ConvHArgs &a, hipStream_t stream);
 // 16-bit elements of the packed weights of a GEMM with gemm_m output maps and gemm_c8 input octets
 long packed_h_elems(int gemm_m, int gemm_c8, int k, int mt = 0);

@@ -249,6 +249,8 @@ sk_status sknet_create(const sk_layer *layers, int32_t n_layers, int32_t c_in, i
             bad = fail(SK_ESHAPE, "layer %d: pool needs s = 1, or s = k with d = 1", i);
         else if (dtype != SK_F32 && l.kind == SK_CONV && !sk::conv_h_supported(l.k, l.d))
             bad = fail(SK_EUNSUPPORTED, "layer %d: 16-bit convolutions need k <= 4 and (k-1)*d <= 64", i);
+        else if (dtype != SK_F32 && l.kind == SK_CONV && !sk::conv_h_supported(l.k, l.d, l.c_out))
+            bad = fail(SK_EUNSUPPORTED, "layer %d: a 16-bit %dx%d convolution to %d maps at d = %d does not fit the LDS tile", i, l.k, l.k, l.c_out, l.d);
         if (bad != SK_OK) {
             delete net;
             return bad;
@@ -372,6 +374,11 @@ sk_status sknet_plan(sknet_t *net, int32_t n, int32_t h, int32_t w, int32_t pad,
         for (int i = 0; i < L; ++i)
             if (net->layers[i].kind == SK_MAXPOOL && net->layers[i].s != 1)
                 return fail(SK_EUNSUPPORTED, "plan: training through a down-sampling pool is not built");
+    if (training && net->dtype != SK_F32)
+        for (int i = 1; i < L; ++i)      // data gradients: the GEMM's output maps are the layer's input maps (the first layer needs none)
+            if (net->layers[i].kind == SK_CONV && !sk::conv_h_supported(net->layers[i].k, net->layers[i].d, dims[i].c))
+                return fail(SK_EUNSUPPORTED, "plan: the 16-bit data gradient of layer %d (%dx%d, d = %d, %d input maps) does not fit the LDS tile",
+                            i, net->layers[i].k, net->layers[i].k, net->layers[i].d, dims[i].c);
     // keep the host masters (a planned net's masters may have been updated on the device)
     if (net->planned)
         for (int i = 0; i < (int)net->convs.size(); ++i) SK_TRY(sknet_get_weights(net, i, nullptr, nullptr));

@@ -144,8 +144,49 @@ def test_training_step_half(dtype):
     net.close()
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("c_in,spec,h,w", [
+    (5, [(12, 3, 3), (10, 2, 1), (3, 1, 1)], 40, 75),        # odd kernel strides, ragged map counts (2-byte fragment reads)
+    (9, [(24, 4, 6), (2, 1, 1)], 50, 90),                    # d = 6: 4-byte reads
+    (3, [(16, 3, 12), (20, 2, 4), (2, 1, 1)], 60, 100),      # d = 12 and 4: 8-byte reads
+    (4, [(8, 4, 1), (72, 4, 8), (2, 1, 1)], 45, 140),        # d = 8: 16-byte reads; 72 maps = several map tiles
+])
+def test_weight_gradient_kernel_strides_half(dtype, c_in, spec, h, w):
+    """The 16-bit weight gradient reads its input fragments at the alignment the kernel stride allows:
+    every alignment class, two images, map counts off the octet and off the 16-map tile."""
+    layers = [S.conv(f, k, d, relu=(i + 1 < len(spec))) for i, (f, k, d) in enumerate(spec)]
+    ws, bs = S.he_normal_weights(layers, c_in, 77, bias_scale=0.05)
+    img = np.ascontiguousarray(S.em_like_batch(2, h, w, 40).repeat(c_in, 1) * np.linspace(0.5, 1.5, c_in, dtype=np.float32)[None, :, None, None])
+    classes = spec[-1][0]
+    labels = (np.random.default_rng(41).integers(0, classes, (2, h, w))).astype(np.int32)
+    net = make_net(layers, c_in, ws, bs, dtype)
+    net.plan(2, h, w, pad=True, training=True)
+    net.forward(torch.from_numpy(img).cuda())
+    loss = net.backward(torch.from_numpy(labels).cuda())
+    ow = [x.astype(np.float64) for x in ws]
+    ob = [x.astype(np.float64) for x in bs]
+    _, acts, ams = ON.sknet_forward(img, layers, ow, ob, keep=True)
+    ref_loss, dws, dbs, _ = ON.sknet_backward(layers, ow, acts, ams, labels)
+    assert abs(loss.item() - ref_loss) <= HALF_TOL * abs(ref_loss)
+    # gradients pass through up to three layers of 16-bit storage: 8 mantissa bits (bf16) leave a few
+    # per cent on the largest entry, 11 bits (fp16) well under one per cent -- the fp16 bound is the
+    # one that would catch a misread fragment
+    tol = 8e-2 if dtype == "bf16" else 1e-2
+    grads = [net.get_grad(i) for i in range(net.num_convs())]
+    net.close()
+    for i, (dw, db) in enumerate(grads):
+        print(dtype, "conv", i, "dW rel err %.3e" % relerr(dw, dws[i]), "db abs err %.3e of %.3e" % (np.abs(db - dbs[i]).max(), np.abs(dbs[i]).max()), flush=True)
+    for i, (dw, db) in enumerate(grads):
+        assert relerr(dw, dws[i]) <= tol, ("dW", i, relerr(dw, dws[i]))
+        assert np.abs(db - dbs[i]).max() <= tol * max(np.abs(dbs[i]).max(), np.abs(dws[i]).max()), ("db", i)
+
+
 def test_unsupported_kernel_size_is_reported():
     from paper_1509_03371_amd import binding as B
+    with pytest.raises(B.SknetError) as e:
+        B.SKNet([S.conv(72, 3, 8, relu=True), S.conv(2, 1, 1, relu=False)], 1, 2, dtype="bf16")    # 3x3 at d = 8 to 72 maps: tile beyond the LDS
+    assert e.value.status_name == "SK_EUNSUPPORTED"
+    B.SKNet([S.conv(32, 3, 8, relu=True), S.conv(2, 1, 1, relu=False)], 1, 2, dtype="bf16").close()  # two map tiles fit
     with pytest.raises(B.SknetError) as e:
         B.SKNet([S.conv(2, 5, 2, relu=False)], 1, 2, dtype="bf16")
     assert e.value.status_name == "SK_EUNSUPPORTED"
