@@ -1,4 +1,5 @@
-// Weight and bias gradient of the SK convolution, fp32, MFMA 16x16x4 fp32 (gfx950).
+// Weight and bias gradient of the SK convolution (gfx950): MFMA 16x16x4 fp32 for fp32 storage,
+// MFMA 16x16x32 bf16 / fp16 for 16-bit storage (second kernel below); fp32 accumulation in both.
 //
 //   dW[o][c][i][j] = sum_{b,y,x} dY[b,o,y,x] * X[b,c,y+i*d,x+j*d]        db[o] = sum dY[b,o,y,x]
 //
