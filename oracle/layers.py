@@ -134,11 +134,12 @@ def softmax(z):
 
 
 def softmax_loss(z, labels, want_grad=True):
-    """Mean over all n*h*w pixels of -log p_label (Section 4.3); returns (loss, dz)."""
+    """Mean of -log p_label over the labelled pixels (Section 4.3); a pixel whose label is -1 is
+    masked out of the error map (Section 4.2): no loss, zero gradient, not counted.  Returns (loss, dz)."""
     z = _f64(z)
     labels = np.ascontiguousarray(labels, dtype=np.int32)
     n, c, h, w = z.shape
-    assert labels.shape == (n, h, w) and labels.min() >= 0 and labels.max() < c
+    assert labels.shape == (n, h, w) and labels.min() >= -1 and labels.max() < c
     dz = np.empty_like(z) if want_grad else None
     loss = _lib.osk_softmax_loss(_d(z), _i(labels), n, c, h * w, _d(dz))
     return loss, dz

@@ -197,14 +197,27 @@ void osk_softmax(const double *z, long n, long classes, long hw, double *p)
         }
 }
 
-/* ---- softmax loss (Section 4.3: the loss is accumulated over all labelled pixels and then
- *      normalised): L = -(1/P) sum_pixels log p_label, P = n*h*w;  dz = (p - onehot)/P ---- */
+/* ---- softmax loss (Section 4.3: the loss is accumulated over all error pixels and then
+ *      normalised): L = -(1/P) sum log p_label, dz = (p - onehot)/P over the pixels that carry a
+ *      label in 0..classes-1; a pixel with any other label value (-1 by convention) is masked out
+ *      of the error map (Section 4.2's label masking): it adds nothing to the loss, its gradient is
+ *      zero, and P counts the unmasked pixels only (P = n*h*w without masking). ---- */
 double osk_softmax_loss(const double *z, const int32_t *labels, long n, long classes, long hw,
                         double *dz)
 {
-    double total = 0.0, P = (double)(n * hw);
+    double total = 0.0;
+    long kept = 0;
+    for (long q = 0; q < n * hw; ++q)
+        if (labels[q] >= 0 && labels[q] < classes) ++kept;
+    const double P = kept > 0 ? (double)kept : 1.0;
     for (long b = 0; b < n; ++b)
         for (long q = 0; q < hw; ++q) {
+            long lab = labels[b * hw + q];
+            if (lab < 0 || lab >= classes) {
+                if (dz)
+                    for (long c = 0; c < classes; ++c) dz[(b * classes + c) * hw + q] = 0.0;
+                continue;
+            }
             double m = z[(b * classes) * hw + q];
             for (long c = 1; c < classes; ++c) {
                 double v = z[(b * classes + c) * hw + q];
@@ -212,7 +225,6 @@ double osk_softmax_loss(const double *z, const int32_t *labels, long n, long cla
             }
             double sum = 0.0;
             for (long c = 0; c < classes; ++c) sum += exp(z[(b * classes + c) * hw + q] - m);
-            long lab = labels[b * hw + q];
             total -= z[(b * classes + lab) * hw + q] - m - log(sum);
             if (dz)
                 for (long c = 0; c < classes; ++c) {

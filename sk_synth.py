@@ -173,3 +173,16 @@ def usknet_params(c_in, classes, seed, base=64, bias_scale=0.0):
         bias = rng.standard_normal(f_out) * bias_scale
         out[name] = (w.astype(np.float32), bias.astype(np.float32))
     return out
+
+
+# ---- label masking (Section 4.2, the masking inequality) ----------------------------------------------
+
+def mask_labels_by_frequency(labels, classes, seed):
+    """Label map with pixels masked (-1) at random so that every label is left about equally often:
+    a pixel of label i is kept with probability min_j c_j / c_i (c = label frequencies in this map,
+    labels that do not occur left out of the minimum), so the rarest label is never masked."""
+    labels = np.asarray(labels)
+    c = np.bincount(labels.reshape(-1), minlength=classes).astype(np.float64) / labels.size
+    keep_p = np.where(c > 0, c[c > 0].min() / np.maximum(c, 1e-300), 1.0)
+    u = np.random.default_rng(seed).random(labels.shape)
+    return np.where(u < keep_p[labels], labels, -1).astype(np.int32)

@@ -336,6 +336,43 @@ def test_softmax_loss_closed_forms():
     assert abs(loss - ref.item()) < 1e-14
 
 
+def test_softmax_loss_with_masked_pixels():
+    # masked pixels (label -1): the loss is the plain loss of the unmasked subset, their gradient is zero,
+    # the normaliser is the number of unmasked pixels; the library's ignore_index is the same rule
+    z = rng(14).standard_normal((2, 3, 6, 7))
+    lab = rng(15).integers(0, 3, (2, 6, 7)).astype(np.int32)
+    masked = lab.copy()
+    masked[rng(16).random(lab.shape) < 0.4] = -1
+    keep = masked >= 0
+    loss, dz = L.softmax_loss(z, masked)
+    p = L.softmax(z)
+    pick = np.take_along_axis(p, lab[:, None].astype(np.int64), 1)[:, 0]
+    assert abs(loss + np.log(pick[keep]).mean()) < 1e-14
+    onehot = np.eye(3)[lab].transpose(0, 3, 1, 2)
+    expect = (p - onehot) / keep.sum() * keep[:, None]
+    assert np.abs(dz - expect).max() < 1e-16
+    assert (dz[np.broadcast_to(~keep[:, None], dz.shape)] == 0).all()
+    ref = F.cross_entropy(torch.from_numpy(z), torch.from_numpy(masked).long(), ignore_index=-1)
+    assert abs(loss - ref.item()) < 1e-14
+    # nothing masked: the rule reduces to the mean over all pixels
+    assert L.softmax_loss(z, lab)[0] == L.softmax_loss(z, np.where(keep, lab, lab))[0]
+    # everything masked: zero loss, zero gradient
+    loss0, dz0 = L.softmax_loss(z, np.full_like(lab, -1))
+    assert loss0 == 0.0 and not dz0.any()
+
+
+def test_label_masking_balances_the_histogram():
+    # Section 4.2: after masking, every label that occurs is left about equally often and the rarest
+    # one is never masked
+    lab = (rng(17).random((4, 200, 200)) < 0.15).astype(np.int32) + (rng(18).random((4, 200, 200)) < 0.02)
+    masked = S.mask_labels_by_frequency(lab, 3, 19)
+    before = np.bincount(lab.reshape(-1), minlength=3)
+    after = np.bincount(masked[masked >= 0], minlength=3)
+    assert ((masked == lab) | (masked == -1)).all()
+    assert after[before.argmin()] == before.min()
+    assert after.max() / after.min() < 1.15
+
+
 # ------------------------------------------------------------------ backward passes
 def _fd(f, x, eps=1e-6):
     g = np.zeros_like(x)
