@@ -147,9 +147,11 @@ sk_status sknet_forward(sknet_t *net, const float *image_dev, float *prob_dev, v
 
 /* Softmax loss and exact gradients of every conv weight and bias, after a forward on a
  * training plan (SK_ESTATE otherwise).  labels_dev: DEVICE int32 [n][h_out][w_out], values in
- * [0, n_classes).  loss_dev: DEVICE fp32 scalar = -(1/P) * sum over the P = n*h_out*w_out pixels
- * of log p_label (Section 4.3: accumulated over all pixels, then normalised).  Pool gradients go
- * to the recorded maximum; ReLU passes gradient where its output is > 0. */
+ * [0, n_classes), or any other value (-1 by convention) for a pixel that is masked out of the error
+ * map (Section 4.2's label masking: no loss, zero gradient).  loss_dev: DEVICE fp32 scalar =
+ * -(1/P) * sum over the P labelled pixels of log p_label (Section 4.3: accumulated over all error
+ * pixels, then normalised; P = n*h_out*w_out without masking; everything masked: loss 0, gradients 0).
+ * Pool gradients go to the recorded maximum; ReLU passes gradient where its output is > 0. */
 sk_status sknet_backward(sknet_t *net, const int32_t *labels_dev, float *loss_dev, void *hip_stream);
 
 /* SGD on the fp32 master weights with the gradients of the last backward:

@@ -231,11 +231,14 @@ hipError_t launch_softmax_f32(const float *z, float *p, int n, int classes, int 
 constexpr int LOSS_BLOCK = 256;
 constexpr int LOSS_MAX_BLOCKS = 1024;
 
-int softmax_loss_partials(long pixels)
+static int loss_blocks(long pixels)
 {
     long b = (pixels + LOSS_BLOCK - 1) / LOSS_BLOCK;
     return (int)(b < LOSS_MAX_BLOCKS ? (b < 1 ? 1 : b) : LOSS_MAX_BLOCKS);
 }
+
+// floats of scratch the loss needs: one partial sum and one partial count of labelled pixels per workgroup
+int softmax_loss_partials(long pixels) { return 2 * loss_blocks(pixels); }
 
 __device__ __forceinline__ float block_sum(float v, float *sh)
 {
@@ -250,24 +253,66 @@ __device__ __forceinline__ float block_sum(float v, float *sh)
     return r;   // valid on thread 0
 }
 
-__global__ void softmax_loss_f32_kernel(const float *z, const int32_t *labels, float *dz, float *partial,
+// A pixel whose label lies outside 0..classes-1 (-1 by convention) is masked out of the error map
+// (Section 4.2's label masking): no loss, zero gradient, and the normaliser P counts the labelled
+// pixels only.  P must be known before the first gradient is written, so the labelled pixels are
+// counted first (integer partial counts, one per workgroup), and every workgroup of the loss kernel
+// adds up those few counts for itself.
+__global__ void label_count_kernel(const int32_t *labels, long total, int classes, int *counts)
+{
+    __shared__ int sh[LOSS_BLOCK / 64];
+    int local = 0;
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
+        const int lab = labels[q];
+        local += (lab >= 0 && lab < classes) ? 1 : 0;
+    }
+    for (int off = 32; off > 0; off >>= 1) local += __shfl_down(local, off, 64);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = local;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int s = 0;
+        for (int w = 0; w < LOSS_BLOCK / 64; ++w) s += sh[w];
+        counts[blockIdx.x] = s;
+    }
+}
+
+// total of the partial counts, computed by the whole workgroup (exact: integers) and returned to every thread
+__device__ __forceinline__ long labelled_pixels(const int *counts, int nblocks)
+{
+    __shared__ long cnt_sh[LOSS_BLOCK / 64];
+    long local = 0;
+    for (int q = threadIdx.x; q < nblocks; q += blockDim.x) local += counts[q];
+    for (int off = 32; off > 0; off >>= 1) local += __shfl_down(local, off, 64);
+    if ((threadIdx.x & 63) == 0) cnt_sh[threadIdx.x >> 6] = local;
+    __syncthreads();
+    long kept = 0;
+    for (int w = 0; w < (int)(blockDim.x >> 6); ++w) kept += cnt_sh[w];
+    return kept;
+}
+
+__global__ void softmax_loss_f32_kernel(const float *z, const int32_t *labels, float *dz, float *partial, const int *counts,
                                         int n, int classes, int hw)
 {
     __shared__ float sh[LOSS_BLOCK / 64];
     const long total = (long)n * hw;
-    const float invP = 1.f / (float)total;
+    const long kept = labelled_pixels(counts, gridDim.x);
+    const float invP = 1.f / (float)(kept > 0 ? kept : 1);
     float local = 0.f;
     for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
         const long b = q / hw, pix = q - b * hw;
         const float *zp = z + b * classes * hw + pix;
+        float *gp = dz + b * classes * hw + pix;
+        const int lab = labels[q];
+        if (lab < 0 || lab >= classes) {
+            for (int c = 0; c < classes; ++c) gp[(long)c * hw] = 0.f;
+            continue;
+        }
         float m = zp[0];
         for (int c = 1; c < classes; ++c) m = fmaxf(m, zp[(long)c * hw]);
         float sum = 0.f;
         for (int c = 0; c < classes; ++c) sum += expf(zp[(long)c * hw] - m);
-        const int lab = labels[q];
         local -= zp[(long)lab * hw] - m - logf(sum);
         const float inv = 1.f / sum;
-        float *gp = dz + b * classes * hw + pix;
         for (int c = 0; c < classes; ++c)
             gp[(long)c * hw] = (expf(zp[(long)c * hw] - m) * inv - (c == lab ? 1.f : 0.f)) * invP;
     }
@@ -275,24 +320,26 @@ __global__ void softmax_loss_f32_kernel(const float *z, const int32_t *labels, f
     if (threadIdx.x == 0) partial[blockIdx.x] = s;
 }
 
-__global__ void loss_finish_kernel(const float *partial, int count, float scale, float *loss)
+__global__ void loss_finish_kernel(const float *partial, const int *counts, int count, float *loss)
 {
     __shared__ float sh[LOSS_BLOCK / 64];
     float v = 0.f;
     for (int q = threadIdx.x; q < count; q += blockDim.x) v += partial[q];
     const float s = block_sum(v, sh);
-    if (threadIdx.x == 0) *loss = s * scale;
+    const long kept = labelled_pixels(counts, count);
+    if (threadIdx.x == 0) *loss = s / (float)(kept > 0 ? kept : 1);
 }
 
 hipError_t launch_softmax_loss_f32(const float *z, const int32_t *labels, float *dz, float *loss,
                                    float *partial, int n, int classes, int hw, hipStream_t stream)
 {
     const long pixels = (long)n * hw;
-    const int blocks = softmax_loss_partials(pixels);
+    const int blocks = loss_blocks(pixels);
+    int *counts = reinterpret_cast<int *>(partial + blocks);
+    hipLaunchKernelGGL(label_count_kernel, dim3(blocks), dim3(LOSS_BLOCK), 0, stream, labels, pixels, classes, counts);
     hipLaunchKernelGGL(softmax_loss_f32_kernel, dim3(blocks), dim3(LOSS_BLOCK), 0, stream, z, labels, dz,
-                       partial, n, classes, hw);
-    hipLaunchKernelGGL(loss_finish_kernel, dim3(1), dim3(LOSS_BLOCK), 0, stream, partial, blocks,
-                       1.f / (float)pixels, loss);
+                       partial, counts, n, classes, hw);
+    hipLaunchKernelGGL(loss_finish_kernel, dim3(1), dim3(LOSS_BLOCK), 0, stream, partial, counts, blocks, loss);
     return hipGetLastError();
 }
 

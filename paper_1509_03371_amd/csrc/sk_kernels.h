@@ -132,8 +132,9 @@ hipError_t launch_maxpool_bwd_f32(const float *dy, const uint8_t *tap, const flo
                                   float *dx, int planes, int H, int W, int Ho, int Wo, int k, int d,
                                   hipStream_t stream);
 hipError_t launch_softmax_f32(const float *z, float *p, int n, int classes, int hw, hipStream_t stream);
-// loss = -(1/P) sum log p_label, dz = (p - onehot)/P, P = n*hw; partial must hold
-// softmax_loss_partials(n*hw) floats.
+// loss = -(1/P) sum log p_label, dz = (p - onehot)/P over the pixels whose label lies in 0..classes-1;
+// any other label value (-1 by convention) masks the pixel (no loss, zero gradient) and P counts the
+// labelled pixels only.  partial must hold softmax_loss_partials(n*hw) floats.
 int softmax_loss_partials(long pixels);
 hipError_t launch_softmax_loss_f32(const float *z, const int32_t *labels, float *dz, float *loss,
                                    float *partial, int n, int classes, int hw, hipStream_t stream);

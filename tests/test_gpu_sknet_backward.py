@@ -64,6 +64,32 @@ def test_tiny_net_training_step():
     train_step_compare(layers, 1, img, labels, ws, bs, lr=0.05, momentum=0.9, wd=1e-3, steps=2)
 
 
+def test_training_step_with_masked_labels():
+    # Section 4.2's label masking: pixels masked (-1) by inverse label frequency carry no error; the
+    # normaliser is the number of labelled pixels.  Three classes, two images, momentum SGD.
+    layers = [S.conv(8, 3, 1, relu=True), S.pool(2, 1, 1), S.conv(12, 3, 2, relu=True), S.conv(3, 1, 1, relu=False)]
+    ws, bs = S.he_normal_weights(layers, 2, 1200, bias_scale=0.1)
+    img = S.uniform_image(2, 2, 44, 70, 5)
+    raw = (np.random.default_rng(6).random((2, 44, 70)) < 0.2).astype(np.int32) + (np.random.default_rng(7).random((2, 44, 70)) < 0.05)
+    labels = S.mask_labels_by_frequency(raw, 3, 8)
+    assert (labels == -1).mean() > 0.3 and (labels >= 0).sum() > 100
+    train_step_compare(layers, 2, img, labels, ws, bs, lr=0.05, momentum=0.5, steps=2)
+
+
+def test_all_pixels_masked_gives_zero_loss_and_gradients():
+    layers = S.tiny_sknet_layers()
+    ws, bs = S.he_normal_weights(layers, 1, 1000, bias_scale=0.1)
+    net = make_net(layers, 1, ws, bs)
+    net.plan(1, 32, 40, pad=True, training=True)
+    net.forward(torch.from_numpy(S.uniform_image(1, 1, 32, 40, 3)).cuda())
+    loss = net.backward(torch.full((1, 32, 40), -1, dtype=torch.int32, device="cuda"))
+    assert float(loss.item()) == 0.0
+    for i in range(net.num_convs()):
+        dw, db = net.get_grad(i)
+        assert not dw.any() and not db.any()
+    net.close()
+
+
 def test_three_class_net_with_k3_and_ragged_sizes():
     layers = [S.conv(10, 3, 1), S.pool(2, 1), S.conv(20, 3, 2), S.pool(3, 2), S.conv(33, 2, 6), S.conv(3, 1, 1, relu=False)]
     ws, bs = S.he_normal_weights(layers, 3, 77, bias_scale=0.1)
