@@ -168,6 +168,36 @@ def mergecrop(a, b):
     return out
 
 
+def upconv2x2_bwd(x, wgt, dy):
+    """Gradients of upconv2x2: every output pixel (2y+a, 2x+b) of map o depends on input pixel
+    (y, x) of every map c through wgt[c,o,a,b] alone.  Returns (dx, dw, db)."""
+    x, wgt, dy = _f64(x), _f64(wgt), _f64(dy)
+    n, f_in, h, w = x.shape
+    f_out = wgt.shape[1]
+    assert dy.shape == (n, f_out, 2 * h, 2 * w)
+    dx = np.zeros_like(x)
+    dw = np.zeros_like(wgt)
+    for a in range(2):
+        for b in range(2):
+            g = dy[:, :, a::2, b::2]                                   # [n, f_out, h, w]
+            dx += np.einsum("co,noyx->ncyx", wgt[:, :, a, b], g)
+            dw[:, :, a, b] = np.einsum("ncyx,noyx->co", x, g)
+    return dx, dw, dy.sum(axis=(0, 2, 3))
+
+
+def mergecrop_bwd(g, fa, b_shape):
+    """Gradients of mergecrop: the first fa maps go to A; the rest go to the centre window of B,
+    the part of B that was cropped away gets none (Section 5.3.1)."""
+    g = _f64(g)
+    n, f, ha, wa = g.shape
+    _, fb, hb, wb = b_shape
+    assert f == fa + fb
+    oy, ox = (hb - ha) // 2, (wb - wa) // 2
+    db = np.zeros(b_shape)
+    db[:, :, oy:oy + ha, ox:ox + wa] = g[:, fa:]
+    return g[:, :fa].copy(), db
+
+
 def sgd(wgt, dw, vel, lr, momentum=0.0, weight_decay=0.0):
     """In place: g = dW + wd*W; V = mu*V + lr*g; W -= V.  vel may be None (mu = 0)."""
     assert wgt.dtype == np.float64 and wgt.flags.c_contiguous

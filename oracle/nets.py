@@ -173,3 +173,108 @@ def usknet_forward(image, params, base=64, keep=False):
     trace["logits"] = z
     prob = L.softmax(z)
     return (prob, trace) if keep else prob
+
+
+# ---------------------------------------------------------------------------------------------
+# Training pass of the U-Net and the USK-Net: the exact gradient of the (optionally masked) mean
+# softmax loss with respect to every parameter, the layers' own backward rules applied in reverse
+# order.  A map that feeds two layers (the skip connection: pooling and MergeCrop) receives the sum
+# of both gradients; MergeCrop sends nothing to the cropped-away border (Section 5.3.1).
+
+def _conv_fwd(x, p, d=1, relu=True):
+    return L.conv_sk(x, p[0], p[1], d=d, relu=relu)
+
+
+def _conv_bwd(x, y, g, p, d=1, relu=True, need_dx=True):
+    """Backward of conv (+ReLU): returns (dx or None, (dW, db))."""
+    if relu:
+        g = L.relu_bwd(y, g)
+    k = p[0].shape[2]
+    grads = L.conv_sk_bwd_weights(x, g, k, d)
+    dx = L.conv_sk_bwd_data(g, p[0], d, x.shape[2:]) if need_dx else None
+    return dx, grads
+
+
+def unet_backward(image, params, labels, depth=4):
+    """Returns (loss, {name: (dW, db)}) for the U-Net of unet_forward()."""
+    x0 = np.asarray(image, dtype=np.float64)
+    tape, skips = [], []
+    x = x0
+    for i in range(depth + 1):
+        a = _conv_fwd(x, params["down%da" % i])
+        b = _conv_fwd(a, params["down%db" % i])
+        tape.append(("down", i, x, a, b))
+        x = b
+        if i < depth:
+            skips.append(b)
+            pooled, am = L.maxpool_sk(b, 2, 1, 2)
+            tape.append(("pool", i, b, am))
+            x = pooled
+    for i in range(depth - 1, -1, -1):
+        up = L.upconv2x2(x, *params["up%d" % i])
+        m = L.mergecrop(up, skips[i])
+        a = _conv_fwd(m, params["dec%da" % i])
+        b = _conv_fwd(a, params["dec%db" % i])
+        tape.append(("up", i, x, up, m, a, b))
+        x = b
+    z = _conv_fwd(x, params["head"], relu=False)
+    loss, g = L.softmax_loss(z, labels)
+    grads = {}
+    g, grads["head"] = _conv_bwd(x, z, g, params["head"], relu=False)
+    gskip = [None] * depth
+    for rec in reversed(tape):
+        if rec[0] == "up":
+            _, i, xin, up, m, a, b = rec
+            g, grads["dec%db" % i] = _conv_bwd(a, b, g, params["dec%db" % i])
+            g, grads["dec%da" % i] = _conv_bwd(m, a, g, params["dec%da" % i])
+            g, gskip[i] = L.mergecrop_bwd(g, up.shape[1], skips[i].shape)
+            g, dw, db = L.upconv2x2_bwd(xin, params["up%d" % i][0], g)
+            grads["up%d" % i] = (dw, db)
+        elif rec[0] == "pool":
+            _, i, b, am = rec
+            g = L.maxpool_bwd(g, am, b.shape[2:]) + gskip[i]
+        else:
+            _, i, xin, a, b = rec
+            g, grads["down%db" % i] = _conv_bwd(a, b, g, params["down%db" % i])
+            g, grads["down%da" % i] = _conv_bwd(xin, a, g, params["down%da" % i], need_dx=i > 0)
+    return loss, grads
+
+
+def usknet_backward(image, params, labels, base=64):
+    """Returns (loss, {name: (dW, db)}) for the USK-Net of usknet_forward()."""
+    x0 = np.asarray(image, dtype=np.float64)
+    c1 = _conv_fwd(x0, params["conv1"])
+    c2 = _conv_fwd(c1, params["conv2"])
+    p1, am1 = L.maxpool_sk(c2, 2, 1, 2)
+    core = []                                   # (name, kind, d, input, output, argmax)
+    x = p1
+    for name, (kind, _, k, d, relu) in zip(USK_CORE_NAMES, usknet_core(base)):
+        if kind == "conv":
+            y = _conv_fwd(x, params[name], d=d, relu=relu)
+            core.append((name, kind, d, x, y, None))
+        else:
+            y, am = L.maxpool_sk(x, k, d, 1)
+            core.append((name, kind, d, x, y, am))
+        x = y
+    up = L.upconv2x2(x, *params["up1"])
+    m = L.mergecrop(up, c2)
+    c7 = _conv_fwd(m, params["conv7"])
+    c8 = _conv_fwd(c7, params["conv8"])
+    z = _conv_fwd(c8, params["ip3"], relu=False)
+    loss, g = L.softmax_loss(z, labels)
+    grads = {}
+    g, grads["ip3"] = _conv_bwd(c8, z, g, params["ip3"], relu=False)
+    g, grads["conv8"] = _conv_bwd(c7, c8, g, params["conv8"])
+    g, grads["conv7"] = _conv_bwd(m, c7, g, params["conv7"])
+    g, gskip = L.mergecrop_bwd(g, up.shape[1], c2.shape)
+    g, dw, db = L.upconv2x2_bwd(x, params["up1"][0], g)
+    grads["up1"] = (dw, db)
+    for name, kind, d, xin, y, am in reversed(core):
+        if kind == "conv":
+            g, grads[name] = _conv_bwd(xin, y, g, params[name], d=d)
+        else:
+            g = L.maxpool_bwd(g, am, xin.shape[2:])
+    g = L.maxpool_bwd(g, am1, c2.shape[2:]) + gskip
+    g, grads["conv2"] = _conv_bwd(c1, c2, g, params["conv2"])
+    _, grads["conv1"] = _conv_bwd(x0, c1, g, params["conv1"], need_dx=False)
+    return loss, grads

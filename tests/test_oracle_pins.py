@@ -563,3 +563,71 @@ def test_usknet_forward_table_sizes_and_torch_crosscheck(golden_rows):
     z = cv(x, "ip3")
     assert np.abs(tr["logits"] - z.numpy()).max() < 1e-11
     assert np.abs(prob - F.softmax(z, 1).numpy()).max() < 1e-13
+
+
+def _torch_grads(loss, tparams):
+    loss.backward()
+    return {k: (w.grad.numpy(), b.grad.numpy()) for k, (w, b) in tparams.items()}
+
+
+def test_unet_backward_matches_autograd():
+    # depth-2 U-Net on 44x44 with masked labels: every parameter gradient against the library's
+    # reverse-mode differentiation of the same composition
+    params = {k: (w.astype(np.float64), b.astype(np.float64))
+              for k, (w, b) in S.unet_params(2, 3, 80, depth=2, base=4, bias_scale=0.2).items()}
+    img = rng(81).random((2, 2, 44, 44))
+    lab = rng(82).integers(-1, 3, (2, 4, 4)).astype(np.int32)
+    loss, grads = nets.unet_backward(img, params, lab, depth=2)
+    tp = {k: (torch.from_numpy(w).requires_grad_(), torch.from_numpy(b).requires_grad_()) for k, (w, b) in params.items()}
+    x = torch.from_numpy(img)
+    skips = []
+    for i in range(3):
+        x = F.relu(F.conv2d(x, *tp["down%da" % i]))
+        x = F.relu(F.conv2d(x, *tp["down%db" % i]))
+        if i < 2:
+            skips.append(x)
+            x = F.max_pool2d(x, 2)
+    for i in (1, 0):
+        x = F.conv_transpose2d(x, *tp["up%d" % i], stride=2)
+        sk = skips[i]
+        o = (sk.shape[2] - x.shape[2]) // 2
+        x = torch.cat([x, sk[:, :, o:o + x.shape[2], o:o + x.shape[3]]], 1)
+        x = F.relu(F.conv2d(x, *tp["dec%da" % i]))
+        x = F.relu(F.conv2d(x, *tp["dec%db" % i]))
+    z = F.conv2d(x, *tp["head"])
+    tl = F.cross_entropy(z, torch.from_numpy(lab).long(), ignore_index=-1)
+    assert abs(loss - tl.item()) < 1e-13
+    ref = _torch_grads(tl, tp)
+    for k in params:
+        for got, want in zip(grads[k], ref[k]):
+            assert np.abs(got - want).max() <= 1e-12 * max(1.0, np.abs(want).max()), k
+
+
+def test_usknet_backward_matches_autograd():
+    base = 2
+    params = {k: (w.astype(np.float64), b.astype(np.float64))
+              for k, (w, b) in S.usknet_params(2, 3, 83, base=base, bias_scale=0.2).items()}
+    img = rng(84).random((1, 2, 190, 186))
+    ho, wo = 2 * ((190 - 4) // 2 - 86) - 4, 2 * ((186 - 4) // 2 - 86) - 4
+    lab = rng(85).integers(-1, 3, (1, ho, wo)).astype(np.int32)
+    loss, grads = nets.usknet_backward(img, params, lab, base=base)
+    tp = {k: (torch.from_numpy(w).requires_grad_(), torch.from_numpy(b).requires_grad_()) for k, (w, b) in params.items()}
+    cv = lambda x, name, d=1: F.conv2d(x, *tp[name], dilation=d)
+    x = F.relu(cv(F.relu(cv(torch.from_numpy(img), "conv1")), "conv2"))
+    skip = x
+    x = F.max_pool2d(x, 2)
+    for name, d in (("conv3", 1), ("conv4", 2), ("conv5", 4)):
+        x = F.max_pool2d(F.relu(cv(x, name, d)), 2, stride=1, dilation=d)
+    x = F.relu(cv(F.relu(cv(x, "ip1", 8)), "ip2"))
+    x = F.conv_transpose2d(x, *tp["up1"], stride=2)
+    oy, ox = (skip.shape[2] - x.shape[2]) // 2, (skip.shape[3] - x.shape[3]) // 2
+    x = torch.cat([x, skip[:, :, oy:oy + x.shape[2], ox:ox + x.shape[3]]], 1)
+    x = F.relu(cv(F.relu(cv(x, "conv7")), "conv8"))
+    z = cv(x, "ip3")
+    assert z.shape[2:] == (ho, wo)
+    tl = F.cross_entropy(z, torch.from_numpy(lab).long(), ignore_index=-1)
+    assert abs(loss - tl.item()) < 1e-13
+    ref = _torch_grads(tl, tp)
+    for k in params:
+        for got, want in zip(grads[k], ref[k]):
+            assert np.abs(got - want).max() <= 1e-12 * max(1.0, np.abs(want).max()), k
