@@ -212,6 +212,8 @@ sk_status usknet_create(int32_t c_in, int32_t n_classes, int32_t base_ch, sk_dty
  * W[c,o,a,b] = W1x1[o,c]).  shape4 (HOST) receives the four extents. */
 sk_status unet_num_params(const unet_t *net, int32_t *count);
 sk_status unet_param_shape(const unet_t *net, int32_t idx, int32_t *shape4);
+/* *kind (HOST) = 0 for a convolution ([f_out][f_in][k][k], f_out biases), 1 for an up-convolution ([f_in][f_out][2][2], f_out biases). */
+sk_status unet_param_kind(const unet_t *net, int32_t idx, int32_t *kind);
 sk_status unet_set_weights(unet_t *net, int32_t idx, const float *w_host, const float *b_host);
 
 /* Output size for an input of h_in x w_in (which already contains the context; 572 -> 388 in the
@@ -225,6 +227,23 @@ sk_status unet_plan(unet_t *net, int32_t n, int32_t h_in, int32_t w_in);
  * MergeCrop puts the up path's maps first, then the skip maps centre-cropped with offset
  * floor((w_skip - w_up)/2) (Section 5.3.1). */
 sk_status unet_forward(unet_t *net, const float *image_dev, float *prob_dev, void *hip_stream);
+
+/* Training pass (fp32 storage only, else SK_EUNSUPPORTED; U-Net and USK-Net handles alike).
+ * unet_plan_training: as unet_plan, and also allocates a gradient buffer per activation, the pools'
+ *   winner codes and the gradient scratch; unet_forward then records what the backward pass needs.
+ * unet_backward: after a forward on a training plan (SK_ESTATE otherwise).  labels_dev: DEVICE int32
+ *   [n][h_out][w_out], values in [0, n_classes) or -1 for a masked pixel; loss_dev: DEVICE fp32 scalar,
+ *   both as in sknet_backward (on a training plan unet_forward keeps a copy of its image for this).
+ *   Computes the exact gradient of the loss for every parameter: MergeCrop sends the up
+ *   path's gradient to the up-convolution and the skip maps' gradient to the centre window of the skip
+ *   map (nothing to the cropped border, Section 5.3.1); a skip map sums the gradients of the two layers
+ *   it feeds; the up-convolution's gradient is that of a 1x1 convolution to the four interleaved
+ *   sub-images.  Deterministic.
+ * unet_get_grad: gradient of parameter idx in the layout of unet_set_weights (HOST; either may be null);
+ *   synchronises. */
+sk_status unet_plan_training(unet_t *net, int32_t n, int32_t h_in, int32_t w_in);
+sk_status unet_backward(unet_t *net, const int32_t *labels_dev, float *loss_dev, void *hip_stream);
+sk_status unet_get_grad(unet_t *net, int32_t idx, float *dw_host, float *db_host);
 
 /* Output of named stage (HOST fp32 NCHW): "down{i}", "up{i}", "dec{i}", "logits". *dims3 = maps,h,w. */
 sk_status unet_get_activation(unet_t *net, const char *stage, float *nchw_host, int32_t *dims3);

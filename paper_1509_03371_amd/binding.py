@@ -68,6 +68,10 @@ _SIGS = {
     "unet_forward": [_vp, _vp, _vp, _vp],
     "unet_get_activation": [_vp, C.c_char_p, _fp, _ip],
     "usknet_create": [_i32, _i32, _i32, _i32, C.POINTER(_vp)],
+    "unet_plan_training": [_vp, _i32, _i32, _i32],
+    "unet_backward": [_vp, _vp, _vp, _vp],
+    "unet_get_grad": [_vp, _i32, _fp, _fp],
+    "unet_param_kind": [_vp, _i32, _ip],
     "sk_probe_mfma": [_i32, _i32, _i32, _vp, C.POINTER(C.c_double)],
     "sk_probe_copy": [_vp, _vp, C.c_uint64, _i32, _vp, C.POINTER(C.c_double)],
 }
@@ -347,9 +351,29 @@ class UNet:
         _check(lib.unet_output_size(self._h, h_in, w_in, C.byref(ho), C.byref(wo)))
         return ho.value, wo.value
 
-    def plan(self, n, h_in, w_in):
-        _check(lib.unet_plan(self._h, n, h_in, w_in))
+    def plan(self, n, h_in, w_in, training=False):
+        _check((lib.unet_plan_training if training else lib.unet_plan)(self._h, n, h_in, w_in))
         self._plan = (n, h_in, w_in)
+
+    def backward(self, labels, loss=None, stream=None):
+        """labels: int32 CUDA tensor [n, h_out, w_out] (-1 = masked pixel); returns the loss (1-element CUDA tensor)."""
+        n, h, w = self._plan
+        ho, wo = self.output_size(h, w)
+        if tuple(labels.shape) != (n, ho, wo):
+            raise ValueError("labels shape %s does not match the plan" % (tuple(labels.shape),))
+        if loss is None:
+            loss = torch.zeros(1, dtype=torch.float32, device=labels.device)
+        _check(lib.unet_backward(self._h, _dev_ptr(labels, torch.int32, "labels"), _dev_ptr(loss, torch.float32, "loss"), _stream(stream)))
+        return loss
+
+    def get_grad(self, idx):
+        shape = self.param_shape(idx)
+        kind = C.c_int32()
+        _check(lib.unet_param_kind(self._h, idx, C.byref(kind)))
+        dw = np.empty(shape, np.float32)
+        db = np.empty((shape[1] if kind.value == 1 else shape[0],), np.float32)
+        _check(lib.unet_get_grad(self._h, idx, dw.ctypes.data_as(_fp), db.ctypes.data_as(_fp)))
+        return dw, db
 
     def forward(self, image, prob=None, stream=None):
         n, h, w = self._plan

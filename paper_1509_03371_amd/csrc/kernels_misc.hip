@@ -425,6 +425,84 @@ hipError_t launch_relu_mask_f32(float *g, const float *act, long count, hipStrea
     return hipGetLastError();
 }
 
+// ---- backward pieces of the U-Net / USK-Net (Sections 3.4, 5.3.1) ---------------------------------------
+// Pool with stride s = k at d = 1: the windows do not overlap, so input sample (u, v) belongs to the one
+// window (u / k, v / k) and receives its dY if the recorded tap is (u % k, v % k).  Samples right of /
+// below the last window receive nothing.  accumulate adds to what dX holds (a map that also feeds a
+// skip connection).
+__global__ void maxpool_sk_eq_s_bwd_f32_kernel(const float *dy, const uint8_t *tap, float *dx, int H, int W, int Ho, int Wo,
+                                               int k, int accumulate)
+{
+    const int v = blockIdx.x * blockDim.x + threadIdx.x, u = blockIdx.y;
+    if (v >= W) return;
+    const long p = blockIdx.z;
+    const int yy = u / k, xx = v / k;
+    float g = 0.f;
+    if (yy < Ho && xx < Wo) {
+        const long q = (p * Ho + yy) * Wo + xx;
+        if (tap[q] == (uint8_t)((u - yy * k) * k + (v - xx * k))) g = dy[q];
+    }
+    const long o = (p * H + u) * W + v;
+    dx[o] = accumulate ? dx[o] + g : g;
+}
+
+hipError_t launch_maxpool_stride_bwd_f32(const float *dy, const uint8_t *tap, float *dx, int planes, int H, int W, int Ho, int Wo,
+                                         int k, int accumulate, hipStream_t stream)
+{
+    hipLaunchKernelGGL(maxpool_sk_eq_s_bwd_f32_kernel, dim3((W + 255) / 256, H, planes), dim3(256), 0, stream, dy, tap, dx, H, W, Ho,
+                       Wo, k, accumulate);
+    return hipGetLastError();
+}
+
+// out[b][t*maps + o][y][x] = in[b][o][2y + a][2x + c], t = 2a + c: the four interleaved sub-images of the
+// first `maps` maps of a tensor with in_maps maps and 2h x 2w pixels, stacked as 4*maps maps of h x w (the
+// gradient of a 2x2 stride-2 up-convolution seen as a 1x1 convolution with four times the output maps).
+__global__ void space_to_depth2_f32_kernel(const float *in, float *out, int n, int in_maps, int maps, int h, int w)
+{
+    const long total = (long)n * 4 * maps * h * w;
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
+        const int x = (int)(q % w);
+        long r = q / w;
+        const int y = (int)(r % h); r /= h;
+        const int o = (int)(r % maps); r /= maps;
+        const int t = (int)(r % 4);
+        const long b = r / 4;
+        out[q] = in[((b * in_maps + o) * (2L * h) + 2 * y + (t >> 1)) * (2L * w) + 2 * x + (t & 1)];
+    }
+}
+
+hipError_t launch_space_to_depth2_f32(const float *in, float *out, int n, int in_maps, int maps, int h, int w, hipStream_t stream)
+{
+    const long total = (long)n * 4 * maps * h * w;
+    hipLaunchKernelGGL(space_to_depth2_f32_kernel, dim3(grid_for(total, 256, 8192)), dim3(256), 0, stream, in, out, n, in_maps, maps, h, w);
+    return hipGetLastError();
+}
+
+// out[b][c][y + oy][x + ox] = in[b][c_off + c][y][x] for c < maps (MergeCrop backward into the skip map:
+// the cropped-away border keeps whatever out held -- the caller clears it first)
+__global__ void place_f32_kernel(const float *in, float *out, int n, int in_maps, int c_off, int maps, int hi, int wi, int ho, int wo,
+                                 int oy, int ox)
+{
+    const long total = (long)n * maps * hi * wi;
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
+        const int x = (int)(q % wi);
+        long r = q / wi;
+        const int y = (int)(r % hi); r /= hi;
+        const int c = (int)(r % maps);
+        const long b = r / maps;
+        out[((b * maps + c) * ho + y + oy) * wo + x + ox] = in[((b * in_maps + c_off + c) * hi + y) * wi + x];
+    }
+}
+
+hipError_t launch_place_f32(const float *in, float *out, int n, int in_maps, int c_off, int maps, int hi, int wi, int ho, int wo,
+                            int oy, int ox, hipStream_t stream)
+{
+    const long total = (long)n * maps * hi * wi;
+    hipLaunchKernelGGL(place_f32_kernel, dim3(grid_for(total, 256, 8192)), dim3(256), 0, stream, in, out, n, in_maps, c_off, maps, hi, wi,
+                       ho, wo, oy, ox);
+    return hipGetLastError();
+}
+
 __global__ void fill_f32_kernel(float *p, float v, long count)
 {
     for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < count; q += (long)gridDim.x * blockDim.x) p[q] = v;

@@ -450,12 +450,26 @@ static void wgrad_tiling(int c_out, int c_in, int k, int &MTo, int &NTk, int &MB
     NB = NTk >= 48 ? 12 : (NTk > 4 ? 4 : 1);
 }
 
+// Private copies of a gradient.  A small gradient (one tile group: the 48x768 of the BASELINE nets)
+// takes one copy per resident workgroup; a large one is split over tile groups (blockIdx.y), which
+// already spread it over the GPU, so it gets proportionally fewer copies -- 512 copies of a
+// 1024 x 9216 gradient would be 19 GB to write and to sum.
+static int wgrad_tile_groups(int MTo, int NTk, int MB, int NB)
+{
+    return ((MTo + MB - 1) / MB) * ((NTk + 4 * NB - 1) / (4 * NB));
+}
+static int wgrad_max_copies(int groups)
+{
+    const int c = (WG_MAX_BLOCKS + groups - 1) / groups;
+    return c < 1 ? 1 : c;
+}
+
 size_t wgrad_f32_scratch_floats(int c_out, int c_in, int k)
 {
     int MTo, NTk, MB, NB;
     wgrad_tiling(c_out, c_in, k, MTo, NTk, MB, NB);
     // private dW copies, then the bias partials (8 * ceil(c_out/8) maps x BG_SLICES)
-    return (size_t)WG_MAX_BLOCKS * MTo * 16 * NTk * 16 + (size_t)(c_out + 7) / 8 * 8 * BG_SLICES;
+    return (size_t)wgrad_max_copies(wgrad_tile_groups(MTo, NTk, MB, NB)) * MTo * 16 * NTk * 16 + (size_t)(c_out + 7) / 8 * 8 * BG_SLICES;
 }
 
 template <int MB, int NB, int DT>
@@ -528,7 +542,10 @@ static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, floa
     const long per_cu = (long)(160 * 1024) / (long)(smem > 1 ? smem : 1);
     long resident = (long)cus * (per_cu < 1 ? 1 : (per_cu > 2 ? 2 : per_cu));
     if (resident > WG_MAX_BLOCKS) resident = WG_MAX_BLOCKS;
-    const int blocks = a.total_segs < resident ? a.total_segs : (int)resident;
+    const int groups = wgrad_tile_groups(a.MTo, a.NTk, MB, NB), max_copies = wgrad_max_copies(groups);
+    long copies = (resident + groups - 1) / groups;
+    if (copies > max_copies) copies = max_copies;
+    const int blocks = a.total_segs < copies ? a.total_segs : (int)copies;
     hipError_t e = hipErrorInvalidValue;
     if constexpr (DT != 0) {
         if (h_path) {
@@ -548,7 +565,7 @@ static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, floa
     if (e != hipSuccess) return e;
     // stage 1 of the bias gradient into the partials behind the dW copies, then one kernel that sums
     // the copies and the partials
-    float *bias_part = scratch + (size_t)WG_MAX_BLOCKS * a.MTo * 16 * a.NTk * 16;
+    float *bias_part = scratch + (size_t)max_copies * a.MTo * 16 * a.NTk * 16;
     if (db) {
         const long plane = (long)a.Ho * a.Wo;
         if constexpr (DT == 0) {

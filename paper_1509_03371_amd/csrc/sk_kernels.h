@@ -159,6 +159,13 @@ hipError_t launch_crop_copy_f32(const float *in, float *out, int n, int maps, in
 hipError_t launch_tap_to_index(const uint8_t *tap, int32_t *idx, int planes, int Ho, int Wo, int W,
                                int k, int d, int s, hipStream_t stream);
 hipError_t launch_relu_mask_f32(float *g, const float *act, long count, hipStream_t stream);
+// backward pieces of the U-Net / USK-Net (see kernels_misc.hip): pool with s = k, d = 1; the four interleaved
+// sub-images of a 2h x 2w tensor as 4*maps maps of h x w; placing a tensor into a window of a larger one
+hipError_t launch_maxpool_stride_bwd_f32(const float *dy, const uint8_t *tap, float *dx, int planes, int H, int W, int Ho, int Wo,
+                                         int k, int accumulate, hipStream_t stream);
+hipError_t launch_space_to_depth2_f32(const float *in, float *out, int n, int in_maps, int maps, int h, int w, hipStream_t stream);
+hipError_t launch_place_f32(const float *in, float *out, int n, int in_maps, int c_off, int maps, int hi, int wi, int ho, int wo,
+                            int oy, int ox, hipStream_t stream);
 hipError_t launch_fill_f32(float *p, float v, long count, hipStream_t stream);
 
 }  // namespace sk

@@ -4,7 +4,10 @@
 // crop-and-place copy of the skip maps.  The USK-Net (Section 3.5 and its configuration table) is
 // the same engine with another layer list: one contracting step, the SK layer sequence at d = 1, 2,
 // 4, 8 on the half-resolution maps, one expanding step.  See include/sknet.h for the contract.
+#include <algorithm>
+#include <map>
 #include <new>
+#include <set>
 
 #include "sk_host.h"
 
@@ -17,6 +20,9 @@ struct UpParams {
     std::vector<float> w, b;        // host master [c_in][c_out][2][2], [c_out]
     float *w_dev = nullptr;         // same layout on the device
     ConvParams tap[4];              // per (a, b): a 1x1 convolution with weight W1[o][c] = w[c][o][a][b]
+    // training: the four taps as ONE 1x1 convolution with 4*c_out output maps (map t*c_out + o = tap t of
+    // map o, t = 2a + b); its data- and weight-gradient kernels serve the up-convolution's backward
+    ConvParams cat;
 };
 
 struct Stage {
@@ -38,6 +44,11 @@ struct unet {
     std::vector<ConvParams> convs;
     std::vector<UpParams> ups;
     // plan
+    bool training = false, backward_done = false;
+    float *image_copy = nullptr;                       // training: the image of the last forward pass (the first layer's weight gradient reads it)
+    std::map<const float *, float *> grad_of;          // training: gradient buffer of every activation buffer
+    std::vector<uint8_t *> taps;                       // training: winner codes, one entry per op (pools only)
+    float *loss_partial = nullptr, *wgrad_scratch = nullptr, *s2d = nullptr;
     bool planned = false, forward_done = false;
     int n = 0, h_in = 0, w_in = 0;
     std::vector<float *> buffers;            // every device activation buffer, for release
@@ -66,14 +77,21 @@ struct unet {
         buffers.clear();
         free_dev(unpack_tmp);
         unpack_tmp_floats = 0;
+        for (auto &kv : grad_of) { float *g = kv.second; free_dev(g); }
+        grad_of.clear();
+        for (auto &t : taps)
+            if (t) { (void)hipFree(t); t = nullptr; }
+        taps.clear();
+        free_dev(loss_partial); free_dev(wgrad_scratch); free_dev(s2d); free_dev(image_copy);
         ops.clear();
         stages.clear();
         for (auto &c : convs) release_conv(c);
         for (auto &u : ups) {
             free_dev(u.w_dev);
             for (auto &t : u.tap) release_conv(t);
+            release_conv(u.cat);
         }
-        planned = forward_done = false;
+        planned = forward_done = backward_done = false;
     }
 };
 
@@ -139,6 +157,13 @@ sk_status upload_up(UpParams &u, int dtype)
             t.b = u.b;
             SK_TRY(upload_conv(t, false, nullptr, dtype));
         }
+    if (u.cat.w_dev) {                 // training plan: the stacked form (bias unused: gradients only)
+        u.cat.w.resize((size_t)4 * u.c_out * u.c_in);
+        for (int t = 0; t < 4; ++t)
+            std::memcpy(u.cat.w.data() + (size_t)t * u.c_out * u.c_in, u.tap[t].w.data(), sizeof(float) * u.c_out * u.c_in);
+        u.cat.b.assign((size_t)4 * u.c_out, 0.f);
+        SK_TRY(upload_conv(u.cat, true, nullptr, dtype));
+    }
     return SK_OK;
 }
 
@@ -256,6 +281,14 @@ sk_status unet_param_shape(const unet_t *net, int32_t idx, int32_t *shape4)
     return SK_OK;
 }
 
+sk_status unet_param_kind(const unet_t *net, int32_t idx, int32_t *kind)
+{
+    SK_TRY(check(net));
+    if (!kind || idx < 0 || idx >= (int)net->params.size()) return fail(SK_EINVAL, "unet_param_kind: bad index");
+    *kind = net->params[idx].kind;
+    return SK_OK;
+}
+
 sk_status unet_set_weights(unet_t *net, int32_t idx, const float *w_host, const float *b_host)
 {
     SK_TRY(check(net));
@@ -282,14 +315,15 @@ sk_status unet_output_size(const unet_t *net, int32_t h_in, int32_t w_in, int32_
     return walk_sizes(net, h_in, w_in, h_out, w_out);
 }
 
-sk_status unet_plan(unet_t *net, int32_t n, int32_t h_in, int32_t w_in)
+static sk_status plan_impl(unet_t *net, int32_t n, int32_t h_in, int32_t w_in, bool training)
 {
     SK_TRY(check(net));
     if (n < 1) return fail(SK_EINVAL, "unet_plan: n must be >= 1");
+    if (training && net->dtype != SK_F32) return fail(SK_EUNSUPPORTED, "unet_plan_training: the backward pass is built for fp32 storage only");
     int ho, wo;
     SK_TRY(walk_sizes(net, h_in, w_in, &ho, &wo));
     net->release_plan();
-    net->n = n; net->h_in = h_in; net->w_in = w_in;
+    net->n = n; net->h_in = h_in; net->w_in = w_in; net->training = training;
     sk_status st = SK_OK;
     const bool half = net->dtype != SK_F32;
     // activation buffers: fp32 NCHW, or the 16-bit octet layout (sized in floats either way)
@@ -426,8 +460,8 @@ sk_status unet_plan(unet_t *net, int32_t n, int32_t h_in, int32_t w_in)
     for (auto &c : net->convs) {
         if (st != SK_OK) break;
         if (half && (net->arch != 0 || !sk::conv_h_supported(c.k, 1))) st = fail(SK_EUNSUPPORTED, "U-Net: kernel size %d is not built for 16-bit storage", c.k);
-        if (st == SK_OK) st = alloc_conv(c, false, net->dtype);
-        if (st == SK_OK) st = upload_conv(c, false, nullptr, net->dtype);
+        if (st == SK_OK) st = alloc_conv(c, training, net->dtype);
+        if (st == SK_OK) st = upload_conv(c, training, nullptr, net->dtype);
     }
     for (auto &u : net->ups) {
         if (st != SK_OK) break;
@@ -435,9 +469,49 @@ sk_status unet_plan(unet_t *net, int32_t n, int32_t h_in, int32_t w_in)
             t.c_in = u.c_in; t.c_out = u.c_out; t.k = 1;
             if (st == SK_OK) st = alloc_conv(t, false, net->dtype);
         }
+        if (training) {
+            u.cat.c_in = u.c_in; u.cat.c_out = 4 * u.c_out; u.cat.k = 1;
+            u.cat.w.assign((size_t)4 * u.c_out * u.c_in, 0.f);
+            u.cat.b.assign((size_t)4 * u.c_out, 0.f);
+            if (st == SK_OK) st = alloc_conv(u.cat, true, net->dtype);
+        }
         if (st == SK_OK) st = upload_up(u, net->dtype);
     }
     if (st == SK_OK && half) st = alloc_f(&net->unpack_tmp, net->unpack_tmp_floats);
+    if (st == SK_OK && training) {
+        // a gradient buffer per activation buffer, winner codes per pool, scratch of the loss and the weight gradients
+        for (float *bufp : net->buffers) {
+            if (st != SK_OK) break;
+            long floats = 0;
+            for (const auto &op : net->ops)
+                if (op.dst == bufp) floats = std::max(floats, op.out.count(n));
+            float *g = nullptr;
+            st = alloc_f(&g, floats);
+            if (g) net->grad_of[bufp] = g;
+        }
+        net->taps.assign(net->ops.size(), nullptr);
+        size_t scratch = 0;
+        long s2d_floats = 0;
+        for (size_t i = 0; i < net->ops.size() && st == SK_OK; ++i) {
+            const auto &op = net->ops[i];
+            if (op.kind == 1) {
+                if (op.s != 1 && !(op.s == op.k && op.d == 1)) st = fail(SK_EUNSUPPORTED, "training: pool needs s = 1, or s = k with d = 1");
+                hipError_t e = st == SK_OK ? hipMalloc(reinterpret_cast<void **>(&net->taps[i]), (size_t)op.out.count(n)) : hipSuccess;
+                if (e != hipSuccess) st = fail(SK_ENOMEM, "plan: hipMalloc of a pool mask failed: %s", hipGetErrorString(e));
+            } else if (op.kind == 0) {
+                const ConvParams &c = net->convs[op.param];
+                scratch = std::max(scratch, sk::wgrad_f32_scratch_floats(c.c_out, c.c_in, c.k));
+            } else if (op.kind == 2) {
+                const UpParams &u = net->ups[op.param];
+                scratch = std::max(scratch, sk::wgrad_f32_scratch_floats(4 * u.c_out, u.c_in, 1));
+                s2d_floats = std::max(s2d_floats, (long)n * 4 * u.c_out * op.in.h * op.in.w);
+            }
+        }
+        if (st == SK_OK) st = alloc_f(&net->wgrad_scratch, (long)scratch);
+        if (st == SK_OK) st = alloc_f(&net->s2d, s2d_floats);
+        if (st == SK_OK) st = alloc_f(&net->image_copy, (long)n * net->c_in * h_in * w_in);
+        if (st == SK_OK) st = alloc_f(&net->loss_partial, sk::softmax_loss_partials((long)n * net->out_dims.h * net->out_dims.w));
+    }
     if (st != SK_OK) {
         std::string keep = g_last_error;
         net->release_plan();
@@ -448,6 +522,10 @@ sk_status unet_plan(unet_t *net, int32_t n, int32_t h_in, int32_t w_in)
     return SK_OK;
 }
 
+sk_status unet_plan(unet_t *net, int32_t n, int32_t h_in, int32_t w_in) { return plan_impl(net, n, h_in, w_in, false); }
+
+sk_status unet_plan_training(unet_t *net, int32_t n, int32_t h_in, int32_t w_in) { return plan_impl(net, n, h_in, w_in, true); }
+
 sk_status unet_forward(unet_t *net, const float *image_dev, float *prob_dev, void *hip_stream)
 {
     SK_TRY(check(net));
@@ -457,7 +535,8 @@ sk_status unet_forward(unet_t *net, const float *image_dev, float *prob_dev, voi
     net->last_stream = stream;
     const int n = net->n;
     const int dt = net->dtype;
-    for (const auto &op : net->ops) {
+    for (size_t opi = 0; opi < net->ops.size(); ++opi) {
+        const auto &op = net->ops[opi];
         const float *src = op.src ? op.src : image_dev;
         if (dt != SK_F32) {
             // 16-bit storage: the same sequence on the octet layout
@@ -491,7 +570,8 @@ sk_status unet_forward(unet_t *net, const float *image_dev, float *prob_dev, voi
             sk::ConvF32Args a = conv_args(c, src, n, op.in, op.d, op.relu, op.dst, op.out);
             SK_HIP(sk::launch_conv_f32(a, stream));
         } else if (op.kind == 1) {
-            SK_HIP(sk::launch_maxpool_f32(src, op.dst, nullptr, n * op.in.c, op.in.h, op.in.w, op.out.h, op.out.w, op.k, op.d, op.s, stream));
+            SK_HIP(sk::launch_maxpool_f32(src, op.dst, net->training ? net->taps[opi] : nullptr, n * op.in.c, op.in.h, op.in.w, op.out.h, op.out.w,
+                                          op.k, op.d, op.s, stream));
         } else if (op.kind == 2) {
             const UpParams &u = net->ups[op.param];
             for (int t = 0; t < 4; ++t) {
@@ -507,7 +587,124 @@ sk_status unet_forward(unet_t *net, const float *image_dev, float *prob_dev, voi
         }
     }
     SK_HIP(sk::launch_softmax_f32(net->logits, prob_dev, n, net->out_dims.c, net->out_dims.h * net->out_dims.w, stream));
+    if (net->training)
+        SK_HIP(hipMemcpyAsync(net->image_copy, image_dev, sizeof(float) * (size_t)n * net->c_in * net->h_in * net->w_in,
+                              hipMemcpyDeviceToDevice, stream));
     net->forward_done = true;
+    net->backward_done = false;
+    return SK_OK;
+}
+
+// Exact gradient of the (optionally masked) mean softmax loss with respect to every parameter: the
+// forward ops in reverse order.  Conv: ReLU mask, weight/bias gradient, data gradient (the forward
+// kernel with flipped, transposed weights and zero padding).  Pool: to the recorded winner.
+// Up-convolution: the gradient's four interleaved sub-images stacked as 4*c_out maps turn it into a 1x1
+// convolution, whose weight and data gradients are the up-convolution's.  MergeCrop: the up path's maps
+// go back to the up-convolution, the skip maps into the centre window of the skip gradient (zero
+// elsewhere); the skip map also feeds a pool, whose gradient is added.
+sk_status unet_backward(unet_t *net, const int32_t *labels_dev, float *loss_dev, void *hip_stream)
+{
+    SK_TRY(check(net));
+    if (!net->planned || !net->training) return fail(SK_ESTATE, "unet_backward: needs a training plan (unet_plan_training)");
+    if (!net->forward_done) return fail(SK_ESTATE, "unet_backward: no forward pass yet");
+    if (!labels_dev || !loss_dev) return fail(SK_EINVAL, "unet_backward: null buffer");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    net->last_stream = stream;
+    const int n = net->n;
+    const Dims &o = net->out_dims;
+    SK_HIP(sk::launch_softmax_loss_f32(net->logits, labels_dev, net->grad_of[net->logits], loss_dev, net->loss_partial, n, o.c,
+                                       o.h * o.w, stream));
+    std::set<const float *> written;          // gradient buffers that already hold a contribution
+    written.insert(net->logits);
+    for (size_t opi = net->ops.size(); opi-- > 0;) {
+        const auto &op = net->ops[opi];
+        float *gsrc = op.src ? net->grad_of[op.src] : nullptr;
+        if (op.kind == 0) {
+            ConvParams &c = net->convs[op.param];
+            float *g = net->grad_of[op.dst];
+            if (op.relu) SK_HIP(sk::launch_relu_mask_f32(g, op.dst, op.out.count(n), stream));
+            const float *x = op.src ? op.src : net->image_copy;
+            SK_HIP(sk::launch_wgrad_f32(x, g, c.dw, c.db, net->wgrad_scratch, n, op.in.c, op.in.h, op.in.w, c.c_out, c.k, op.d, stream));
+            if (!op.src) continue;                 // the image needs no gradient
+            if (written.count(op.src)) return fail(SK_EUNSUPPORTED, "unet_backward: a map that feeds a convolution and another layer");
+            sk::ConvF32Args a{};
+            a.x = g; a.wp = c.wp_bwd; a.bias = nullptr; a.mask = nullptr; a.y = gsrc;
+            a.n = n; a.c_in = op.out.c; a.H = op.out.h; a.W = op.out.w;
+            a.c_out = op.in.c; a.n_pad = c.n_pad_bwd;
+            a.k = c.k; a.d = op.d; a.in_off = (c.k - 1) * op.d;
+            a.Ho = op.in.h; a.Wo = op.in.w; a.relu = 0;
+            a.out_maps = op.in.c; a.o_off = 0; a.OH = op.in.h; a.OW = op.in.w;
+            a.oy_mul = 1; a.oy_off = 0; a.ox_mul = 1; a.ox_off = 0;
+            SK_HIP(sk::launch_conv_f32(a, stream));
+            written.insert(op.src);
+        } else if (op.kind == 1) {
+            const float *g = net->grad_of[op.dst];
+            const int acc = written.count(op.src) ? 1 : 0;
+            if (op.s == 1) {
+                if (acc) return fail(SK_EUNSUPPORTED, "unet_backward: a map that feeds a stride-1 pool and another layer");
+                SK_HIP(sk::launch_maxpool_bwd_f32(g, net->taps[opi], nullptr, gsrc, n * op.in.c, op.in.h, op.in.w, op.out.h, op.out.w,
+                                                  op.k, op.d, stream));
+            } else {
+                SK_HIP(sk::launch_maxpool_stride_bwd_f32(g, net->taps[opi], gsrc, n * op.in.c, op.in.h, op.in.w, op.out.h, op.out.w,
+                                                         op.k, acc, stream));
+            }
+            written.insert(op.src);
+        } else if (op.kind == 2) {
+            UpParams &u = net->ups[op.param];
+            const float *gm = net->grad_of[op.dst];       // gradient of the merged buffer: the up path is its first c_out maps
+            SK_HIP(sk::launch_space_to_depth2_f32(gm, net->s2d, n, op.out.c, u.c_out, op.in.h, op.in.w, stream));
+            SK_HIP(sk::launch_wgrad_f32(op.src, net->s2d, u.cat.dw, u.cat.db, net->wgrad_scratch, n, u.c_in, op.in.h, op.in.w,
+                                        4 * u.c_out, 1, 1, stream));
+            if (written.count(op.src)) return fail(SK_EUNSUPPORTED, "unet_backward: a map that feeds an up-convolution and another layer");
+            sk::ConvF32Args a{};
+            a.x = net->s2d; a.wp = u.cat.wp_bwd; a.bias = nullptr; a.mask = nullptr; a.y = gsrc;
+            a.n = n; a.c_in = 4 * u.c_out; a.H = op.in.h; a.W = op.in.w;
+            a.c_out = u.c_in; a.n_pad = u.cat.n_pad_bwd;
+            a.k = 1; a.d = 1; a.in_off = 0;
+            a.Ho = op.in.h; a.Wo = op.in.w; a.relu = 0;
+            a.out_maps = u.c_in; a.o_off = 0; a.OH = op.in.h; a.OW = op.in.w;
+            a.oy_mul = 1; a.oy_off = 0; a.ox_mul = 1; a.ox_off = 0;
+            SK_HIP(sk::launch_conv_f32(a, stream));
+            written.insert(op.src);
+        } else if (op.kind == 3) {
+            const float *gm = net->grad_of[op.dst];
+            if (written.count(op.src)) return fail(SK_EUNSUPPORTED, "unet_backward: MergeCrop must be the last consumer of its skip map");
+            SK_HIP(sk::launch_fill_f32(gsrc, 0.f, (long)n * op.src_maps * op.in.h * op.in.w, stream));
+            SK_HIP(sk::launch_place_f32(gm, gsrc, n, op.out.c, op.o_off, op.src_maps, op.out.h, op.out.w, op.in.h, op.in.w, op.crop,
+                                        (op.in.w - op.out.w) / 2, stream));
+            written.insert(op.src);
+        }
+    }
+    net->backward_done = true;
+    return SK_OK;
+}
+
+sk_status unet_get_grad(unet_t *net, int32_t idx, float *dw_host, float *db_host)
+{
+    SK_TRY(check(net));
+    if (idx < 0 || idx >= (int)net->params.size()) return fail(SK_EINVAL, "unet_get_grad: bad index");
+    if (!net->backward_done) return fail(SK_ESTATE, "unet_get_grad: no backward pass yet");
+    SK_HIP(hipStreamSynchronize(net->last_stream));
+    const auto &p = net->params[idx];
+    if (p.kind == 0) {
+        ConvParams &c = net->convs[p.idx];
+        if (dw_host) SK_HIP(hipMemcpy(dw_host, c.dw, sizeof(float) * c.wcount(), hipMemcpyDeviceToHost));
+        if (db_host) SK_HIP(hipMemcpy(db_host, c.db, sizeof(float) * c.c_out, hipMemcpyDeviceToHost));
+        return SK_OK;
+    }
+    // up-convolution: the stacked 1x1 gradient [t*c_out + o][c] back to [c][o][a][b]; the bias is shared by the four taps
+    UpParams &u = net->ups[p.idx];
+    std::vector<float> dw((size_t)4 * u.c_out * u.c_in), db((size_t)4 * u.c_out);
+    SK_HIP(hipMemcpy(dw.data(), u.cat.dw, sizeof(float) * dw.size(), hipMemcpyDeviceToHost));
+    SK_HIP(hipMemcpy(db.data(), u.cat.db, sizeof(float) * db.size(), hipMemcpyDeviceToHost));
+    if (dw_host)
+        for (int c = 0; c < u.c_in; ++c)
+            for (int o2 = 0; o2 < u.c_out; ++o2)
+                for (int t = 0; t < 4; ++t)
+                    dw_host[((size_t)c * u.c_out + o2) * 4 + t] = dw[((size_t)t * u.c_out + o2) * u.c_in + c];
+    if (db_host)
+        for (int o2 = 0; o2 < u.c_out; ++o2)
+            db_host[o2] = (db[o2] + db[u.c_out + o2]) + (db[2 * u.c_out + o2] + db[3 * u.c_out + o2]);
     return SK_OK;
 }
 
