@@ -175,6 +175,42 @@ def measure_usknet(torch, B, S, steps, warmup):
             "gflop": round(gflop, 1), "tflops": round(gflop / dt / 1e3, 1)}
 
 
+def measure_unet_train(torch, B, S, which, steps, warmup):
+    """One training step (forward, masked softmax loss, backward, SGD) of the U-Net (572^2 -> 388^2) or the
+    USK-Net (692^2 -> 512^2) of the paper's tables, fp32, labels masked by inverse frequency."""
+    import numpy as np
+    if which == "unet":
+        params, names = S.unet_params(1, 2, 1005, depth=4, base=64), S.unet_param_names(4)
+        net, c_in, size, out = B.UNet(1, 2, depth=4, base_ch=64), 1, 572, 388
+    else:
+        params, names = S.usknet_params(3, 2, 1006, base=64), S.USKNET_PARAM_NAMES
+        net, c_in, size, out = B.USKNet(3, 2, base_ch=64), 3, 692, 512
+    for i, name in enumerate(names):
+        net.set_weights(i, *params[name])
+    net.plan(1, size, size, training=True)
+    img = torch.from_numpy(np.stack([S.em_like_image(size, size, 1010 + c) for c in range(c_in)])[None].copy()).cuda()
+    lab = torch.from_numpy(S.mask_labels_by_frequency(S.binary_labels(1, out, out, 1011), 2, 1012)).cuda()
+    prob = torch.empty((1, 2, out, out), dtype=torch.float32, device="cuda")
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step():
+        net.forward(img, prob, stream)
+        net.backward(lab, loss, stream)
+        net.sgd_step(1e-3, 0.9, 0.0, stream)
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    final = float(loss.item())
+    net.close()
+    return {"ms_per_step": round(dt * 1e3, 3), "labelled_pixels_per_s": round(out * out / dt, 1), "loss_after": round(final, 4)}
+
+
 def measure_paper_sknet(torch, B, S, steps, warmup):
     """The paper's own SK network (Section 3.3.2: 3 x 229^2 after padding -> 2 x 128^2; its inner product
     is a k = 10, d = 8 convolution 192 -> 1024, 644 of the 695 GFLOP) in fp32: the workload of the
@@ -227,7 +263,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", choices=["c2", "c3", "c4", "c5", "c5bf16", "usk", "papersk", "copy"], default="c2")
+    ap.add_argument("--workload", choices=["c2", "c3", "c4", "c5", "c5bf16", "usk", "papersk", "unettrain", "usktrain", "copy"], default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
     args = ap.parse_args()
@@ -262,6 +298,15 @@ def main():
                     "config": {"workload": "U-Net forward 1x1x572x572 -> 2x388x388, %s (BASELINE configs[4])" % dt,
                                "global_batch": 1, "parallelism": "single GPU"},
                     "roofline": None, "forward_tflops": r["tflops"]})
+        print(json.dumps(out))
+        return
+
+    if args.workload in ("unettrain", "usktrain"):
+        r = measure_unet_train(torch, B, S, "unet" if args.workload == "unettrain" else "usk", args.steps, args.warmup)
+        out.update({"value": r["labelled_pixels_per_s"], "ms_per_step": r["ms_per_step"], "dtype": "f32",
+                    "config": {"workload": ("U-Net 572^2 -> 388^2" if args.workload == "unettrain" else "USK-Net 692^2 -> 512^2")
+                                           + " training step (forward, masked softmax loss, backward, SGD), fp32",
+                               "global_batch": 1, "parallelism": "single GPU"}, "roofline": None, "detail": r})
         print(json.dumps(out))
         return
 
@@ -322,6 +367,8 @@ def main():
             extras[name] = measure_unet(torch, B, S, dt, 10, 3)
         extras["paper_sknet_128_f32"] = measure_paper_sknet(torch, B, S, 5, 2)
         extras["usknet_692_f32_forward"] = measure_usknet(torch, B, S, 5, 2)
+        extras["unet_572_f32_train_step"] = measure_unet_train(torch, B, S, "unet", 3, 1)
+        extras["usknet_692_f32_train_step"] = measure_unet_train(torch, B, S, "usk", 3, 1)
         out["extras"] = extras
 
     if args.workload == "c2" and not args.no_cpu_baseline:

@@ -244,6 +244,12 @@ sk_status unet_forward(unet_t *net, const float *image_dev, float *prob_dev, voi
 sk_status unet_plan_training(unet_t *net, int32_t n, int32_t h_in, int32_t w_in);
 sk_status unet_backward(unet_t *net, const int32_t *labels_dev, float *loss_dev, void *hip_stream);
 sk_status unet_get_grad(unet_t *net, int32_t idx, float *dw_host, float *db_host);
+/* SGD on the fp32 weights with the gradients of the last unet_backward, as sknet_sgd_step
+ * (g = dW + weight_decay*W; V = momentum*V + lr*g; W = W - V); the four taps of an up-convolution share
+ * one bias, whose gradient is the sum over the taps.  unet_get_weights: the current values in the
+ * layout of unet_set_weights (HOST; either may be null); synchronises.  A later unet_plan keeps them. */
+sk_status unet_sgd_step(unet_t *net, float lr, float momentum, float weight_decay, void *hip_stream);
+sk_status unet_get_weights(unet_t *net, int32_t idx, float *w_host, float *b_host);
 
 /* Output of named stage (HOST fp32 NCHW): "down{i}", "up{i}", "dec{i}", "logits". *dims3 = maps,h,w. */
 sk_status unet_get_activation(unet_t *net, const char *stage, float *nchw_host, int32_t *dims3);

@@ -72,6 +72,8 @@ _SIGS = {
     "unet_backward": [_vp, _vp, _vp, _vp],
     "unet_get_grad": [_vp, _i32, _fp, _fp],
     "unet_param_kind": [_vp, _i32, _ip],
+    "unet_sgd_step": [_vp, C.c_float, C.c_float, C.c_float, _vp],
+    "unet_get_weights": [_vp, _i32, _fp, _fp],
     "sk_probe_mfma": [_i32, _i32, _i32, _vp, C.POINTER(C.c_double)],
     "sk_probe_copy": [_vp, _vp, C.c_uint64, _i32, _vp, C.POINTER(C.c_double)],
 }
@@ -365,6 +367,18 @@ class UNet:
             loss = torch.zeros(1, dtype=torch.float32, device=labels.device)
         _check(lib.unet_backward(self._h, _dev_ptr(labels, torch.int32, "labels"), _dev_ptr(loss, torch.float32, "loss"), _stream(stream)))
         return loss
+
+    def sgd_step(self, lr, momentum=0.0, weight_decay=0.0, stream=None):
+        _check(lib.unet_sgd_step(self._h, lr, momentum, weight_decay, _stream(stream)))
+
+    def get_weights(self, idx):
+        shape = self.param_shape(idx)
+        kind = C.c_int32()
+        _check(lib.unet_param_kind(self._h, idx, C.byref(kind)))
+        w = np.empty(shape, np.float32)
+        b = np.empty((shape[1] if kind.value == 1 else shape[0],), np.float32)
+        _check(lib.unet_get_weights(self._h, idx, w.ctypes.data_as(_fp), b.ctypes.data_as(_fp)))
+        return w, b
 
     def get_grad(self, idx):
         shape = self.param_shape(idx)

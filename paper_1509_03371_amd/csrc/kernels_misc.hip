@@ -386,6 +386,27 @@ hipError_t launch_sgd_batch_f32(const SgdBatch &b, float lr, float mu, float wd,
     return hipGetLastError();
 }
 
+// SGD on the bias of a 2x2 up-convolution, which its four taps share: the gradient is the sum of the four
+// taps' bias gradients (db4[t*c_out + o]); the new value goes to each tap's own copy.
+__global__ void up_bias_sgd_f32_kernel(float *b0, float *b1, float *b2, float *b3, const float *db4, float *v, int c_out, float lr,
+                                       float mu, float wd)
+{
+    const int o = blockIdx.x * blockDim.x + threadIdx.x;
+    if (o >= c_out) return;
+    const float g = (db4[o] + db4[c_out + o]) + (db4[2 * c_out + o] + db4[3 * c_out + o]) + wd * b0[o];
+    const float vel = (v ? mu * v[o] : 0.f) + lr * g;
+    if (v) v[o] = vel;
+    const float nb = b0[o] - vel;
+    b0[o] = nb; b1[o] = nb; b2[o] = nb; b3[o] = nb;
+}
+
+hipError_t launch_up_bias_sgd_f32(float *b0, float *b1, float *b2, float *b3, const float *db4, float *v, int c_out, float lr, float mu,
+                                  float wd, hipStream_t stream)
+{
+    hipLaunchKernelGGL(up_bias_sgd_f32_kernel, dim3((c_out + 255) / 256), dim3(256), 0, stream, b0, b1, b2, b3, db4, v, c_out, lr, mu, wd);
+    return hipGetLastError();
+}
+
 // ---- crop-and-place copy (the two halves of MergeCrop, Section 5.3.1) -----------------------------------
 __global__ void crop_copy_f32_kernel(const float *in, float *out, int n, int maps, int hi, int wi,
                                      int out_maps, int o_off, int ho, int wo, int oy, int ox)

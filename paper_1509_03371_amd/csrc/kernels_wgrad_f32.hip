@@ -14,6 +14,7 @@
 // MFMA roles: A[m = output map][kk = pixel] = dY, B[kk = pixel][n = (c,i,j)] = X shifted by the
 // tap, D[m][n] = dW laid out exactly as OIHW.  Wave w of a workgroup owns MB row tiles (16 output
 // maps each) times NB column tiles (16 (c,i,j) triples each); blockIdx.y selects further groups.
+#include <algorithm>
 #include <type_traits>
 
 #include "sk_kernels.h"
@@ -54,8 +55,11 @@ __global__ __launch_bounds__(256) void wgrad_f32_kernel(WgradArgs a)
     // staged operands: fp32, or (16-bit storage types) the raw 16-bit values, widened when they are read
     // for the MFMA -- half the LDS, so two workgroups fit a CU and one stages while the other multiplies
     typedef typename std::conditional<DT == 0, float, unsigned short>::type stage_t;
-    stage_t *dys = reinterpret_cast<stage_t *>(smem);    // [m_rows][WG_DYP]
-    stage_t *xs = dys + m_rows * WG_DYP;                 // [c_in*k][xpitch]
+    // LDS holds what this workgroup's tile group needs: the dY rows of its MB map tiles and (fp32
+    // storage) the input maps its NB*4 column tiles touch -- a 1024 x 9216 gradient is split over
+    // many groups, and no group could hold all maps
+    stage_t *dys = reinterpret_cast<stage_t *>(smem);    // [MB*16][WG_DYP]
+    stage_t *xs = dys + MB * 16 * WG_DYP;                // [maps of the group * k][xpitch]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l16 = lane & 15, g = lane >> 4;
     const int PW = WG_SEG + (k - 1) * d;
 
@@ -63,6 +67,11 @@ __global__ __launch_bounds__(256) void wgrad_f32_kernel(WgradArgs a)
     const int ngroups = (a.NTk + 4 * NB - 1) / (4 * NB);
     const int mgroup = blockIdx.y / ngroups, ngroup = blockIdx.y - mgroup * ngroups;
     const int mo0 = mgroup * MB;
+    // input maps this group's columns (c,i,j) belong to; 16-bit storage stages whole octets and keeps all maps
+    const int c_lo = DT == 0 ? (ngroup * NB * 64) / (k * k) : 0;
+    int c_hi = DT == 0 ? ((ngroup + 1) * NB * 64 - 1) / (k * k) : a.c_in - 1;
+    c_hi = c_hi < a.c_in - 1 ? c_hi : a.c_in - 1;
+    const int cw = c_hi - c_lo + 1;
     // column tiles of this wave: nk = (ngroup*NB + q)*4 + wave
     int xoff[NB];
 #pragma unroll
@@ -72,7 +81,7 @@ __global__ __launch_bounds__(256) void wgrad_f32_kernel(WgradArgs a)
         int off = 0;
         if (nk < a.NTk && cij < K) {
             const int c = cij / (k * k), r = cij - c * k * k, i = r / k, j = r - i * k;
-            off = (c * k + i) * a.xpitch + j * d;
+            off = ((c - c_lo) * k + i) * a.xpitch + j * d;
         }
         xoff[q] = off + g;
     }
@@ -99,11 +108,11 @@ __global__ __launch_bounds__(256) void wgrad_f32_kernel(WgradArgs a)
             for (int row = mo0 * 16 + wave; row < row_end; row += 4) {
                 const int rc = row < a.c_out ? row : a.c_out - 1;
                 const float v = dyp[((long)b * a.c_out + rc) * yplane + (long)y * a.Wo + xl];
-                dys[row * WG_DYP + lane] = (row < a.c_out && x0 + lane < a.Wo) ? v : 0.f;
+                dys[(row - mo0 * 16) * WG_DYP + lane] = (row < a.c_out && x0 + lane < a.Wo) ? v : 0.f;
             }
-            // input rows y + i*d for every map
-            for (int row = wave; row < a.c_in * k; row += 4) {
-                const int c = row / k, i = row - c * k;
+            // input rows y + i*d of the group's maps
+            for (int row = wave; row < cw * k; row += 4) {
+                const int c = c_lo + row / k, i = row - (row / k) * k;
                 const float *src = xp + ((long)b * a.c_in + c) * xplane + (long)(y + i * d) * a.W;
                 float *dst = xs + row * a.xpitch;
 #pragma unroll 3
@@ -126,7 +135,7 @@ __global__ __launch_bounds__(256) void wgrad_f32_kernel(WgradArgs a)
                 const bool ok = oc < c8o && x0 + lane < a.Wo;
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
-                    dys[(oc * 8 + e) * WG_DYP + lane] = ok ? (unsigned short)((u[e >> 1] >> ((e & 1) * 16)) & 0xffffu) : (unsigned short)0;
+                    dys[(oc * 8 + e - mo0 * 16) * WG_DYP + lane] = ok ? (unsigned short)((u[e >> 1] >> ((e & 1) * 16)) & 0xffffu) : (unsigned short)0;
             }
             for (int rid = wave; rid < c8i * k; rid += 4) {
                 const int oc = rid / k, i = rid - oc * k;
@@ -148,8 +157,7 @@ __global__ __launch_bounds__(256) void wgrad_f32_kernel(WgradArgs a)
             float av[MB];
 #pragma unroll
             for (int m = 0; m < MB; ++m) {
-                const int row = (mo0 + m) * 16 + l16;
-                av[m] = (mo0 + m < a.MTo) ? staged<DT>(dys[row * WG_DYP + p + g]) : 0.f;
+                av[m] = (mo0 + m < a.MTo) ? staged<DT>(dys[(m * 16 + l16) * WG_DYP + p + g]) : 0.f;
             }
 #pragma unroll
             for (int q = 0; q < NB; ++q) {
@@ -528,12 +536,20 @@ static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, floa
     a.xsegs = (a.Wo + WG_SEG - 1) / WG_SEG;
     a.total_segs = a.xsegs * a.Ho * n;
     const int PW = WG_SEG + (k - 1) * d;
+    // fp32 storage: a tile group stages only the maps of its own columns; fewer column tiles per group
+    // when even those do not fit the LDS (1x1 kernels over many maps)
+    auto f32_smem = [&](int nb) {
+        const int maps = std::min(c_in, (nb * 64 + k * k - 1) / (k * k) + 1);
+        return sizeof(float) * ((size_t)MB * 16 * WG_DYP + (size_t)maps * k * ((PW + 31) / 32 * 32 + 4));
+    };
+    if (DT == 0)
+        while (NB > 1 && f32_smem(NB) > 150 * 1024) NB = NB == 12 ? 4 : 1;
     // 16-bit storage (and a window of at most 128 columns): the 16-bit matrix path
     const bool h_path = DT != 0 && PW <= 128;
     a.xpitch = h_path ? (PW + 7) / 8 * 8 + 8 : (PW + 31) / 32 * 32 + 4;
     const int x_rows = (DT == 0 ? c_in : (c_in + 7) / 8 * 8) * k;
-    const size_t smem = (DT == 0 ? sizeof(float) : sizeof(unsigned short)) *
-                        ((size_t)a.MTo * 16 * (h_path ? WG_DYH : WG_DYP) + (size_t)x_rows * a.xpitch);
+    const size_t smem = DT == 0 ? f32_smem(NB)
+                                : sizeof(unsigned short) * ((size_t)(h_path ? a.MTo : MB) * 16 * (h_path ? WG_DYH : WG_DYP) + (size_t)x_rows * a.xpitch);
     if (smem > 150 * 1024) return hipErrorInvalidValue;
     // as many persistent workgroups as fit on the GPU at once (more would only add private copies
     // for the reduction to read): LDS decides

@@ -298,7 +298,7 @@ sk_status unet_set_weights(unet_t *net, int32_t idx, const float *w_host, const 
         ConvParams &c = net->convs[p.idx];
         std::memcpy(c.w.data(), w_host, sizeof(float) * c.wcount());
         if (b_host) std::memcpy(c.b.data(), b_host, sizeof(float) * c.c_out);
-        if (net->planned) SK_TRY(upload_conv(c, false, net->last_stream, net->dtype));
+        if (net->planned) SK_TRY(upload_conv(c, net->training, net->last_stream, net->dtype));
     } else {
         UpParams &u = net->ups[p.idx];
         std::memcpy(u.w.data(), w_host, sizeof(float) * u.w.size());
@@ -315,6 +315,8 @@ sk_status unet_output_size(const unet_t *net, int32_t h_in, int32_t w_in, int32_
     return walk_sizes(net, h_in, w_in, h_out, w_out);
 }
 
+static sk_status sync_masters(unet_t *net);
+
 static sk_status plan_impl(unet_t *net, int32_t n, int32_t h_in, int32_t w_in, bool training)
 {
     SK_TRY(check(net));
@@ -322,6 +324,7 @@ static sk_status plan_impl(unet_t *net, int32_t n, int32_t h_in, int32_t w_in, b
     if (training && net->dtype != SK_F32) return fail(SK_EUNSUPPORTED, "unet_plan_training: the backward pass is built for fp32 storage only");
     int ho, wo;
     SK_TRY(walk_sizes(net, h_in, w_in, &ho, &wo));
+    SK_TRY(sync_masters(net));             // a trained net keeps its weights across plans
     net->release_plan();
     net->n = n; net->h_in = h_in; net->w_in = w_in; net->training = training;
     sk_status st = SK_OK;
@@ -705,6 +708,81 @@ sk_status unet_get_grad(unet_t *net, int32_t idx, float *dw_host, float *db_host
     if (db_host)
         for (int o2 = 0; o2 < u.c_out; ++o2)
             db_host[o2] = (db[o2] + db[u.c_out + o2]) + (db[2 * u.c_out + o2] + db[3 * u.c_out + o2]);
+    return SK_OK;
+}
+
+// device masters -> host masters (after SGD steps the device copies are the current ones)
+static sk_status sync_masters(unet_t *net)
+{
+    if (!net->planned || !net->training) return SK_OK;
+    if (net->last_stream) SK_HIP(hipStreamSynchronize(net->last_stream));
+    for (auto &c : net->convs) {
+        SK_HIP(hipMemcpy(c.w.data(), c.w_dev, sizeof(float) * c.wcount(), hipMemcpyDeviceToHost));
+        SK_HIP(hipMemcpy(c.b.data(), c.b_dev, sizeof(float) * c.c_out, hipMemcpyDeviceToHost));
+    }
+    for (auto &u : net->ups) {
+        std::vector<float> cat((size_t)4 * u.c_out * u.c_in);
+        SK_HIP(hipMemcpy(cat.data(), u.cat.w_dev, sizeof(float) * cat.size(), hipMemcpyDeviceToHost));
+        for (int c = 0; c < u.c_in; ++c)
+            for (int o2 = 0; o2 < u.c_out; ++o2)
+                for (int t = 0; t < 4; ++t) u.w[((size_t)c * u.c_out + o2) * 4 + t] = cat[((size_t)t * u.c_out + o2) * u.c_in + c];
+        SK_HIP(hipMemcpy(u.b.data(), u.tap[0].b_dev, sizeof(float) * u.c_out, hipMemcpyDeviceToHost));
+    }
+    return SK_OK;
+}
+
+sk_status unet_sgd_step(unet_t *net, float lr, float momentum, float weight_decay, void *hip_stream)
+{
+    SK_TRY(check(net));
+    if (!net->planned || !net->training || !net->backward_done) return fail(SK_ESTATE, "unet_sgd_step: needs a backward pass on a training plan");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    net->last_stream = stream;
+    // every weight and bias tensor (the up-convolutions in their stacked 1x1 form), BATCH_MAX per launch
+    sk::SgdBatch sb{};
+    auto push = [&](float *w, const float *dw, float *v, long count) -> sk_status {
+        sb.w[sb.n] = w; sb.dw[sb.n] = dw; sb.v[sb.n] = momentum != 0.f ? v : nullptr; sb.count[sb.n] = count;
+        if (++sb.n == sk::BATCH_MAX) {
+            SK_HIP(sk::launch_sgd_batch_f32(sb, lr, momentum, weight_decay, stream));
+            sb.n = 0;
+        }
+        return SK_OK;
+    };
+    for (auto &c : net->convs) {
+        SK_TRY(push(c.w_dev, c.dw, c.vw, c.wcount()));
+        SK_TRY(push(c.b_dev, c.db, c.vb, c.c_out));
+    }
+    for (auto &u : net->ups) SK_TRY(push(u.cat.w_dev, u.cat.dw, u.cat.vw, u.cat.wcount()));
+    if (sb.n > 0) SK_HIP(sk::launch_sgd_batch_f32(sb, lr, momentum, weight_decay, stream));
+    for (auto &u : net->ups) {
+        // the shared bias (its momentum lives in the stacked form's first c_out entries), then the taps' weights
+        SK_HIP(sk::launch_up_bias_sgd_f32(u.tap[0].b_dev, u.tap[1].b_dev, u.tap[2].b_dev, u.tap[3].b_dev, u.cat.db,
+                                          momentum != 0.f ? u.cat.vb : nullptr, u.c_out, lr, momentum, weight_decay, stream));
+        for (int t = 0; t < 4; ++t) {
+            SK_HIP(hipMemcpyAsync(u.tap[t].w_dev, u.cat.w_dev + (size_t)t * u.c_out * u.c_in, sizeof(float) * u.c_out * u.c_in,
+                                  hipMemcpyDeviceToDevice, stream));
+            SK_TRY(repack_conv(u.tap[t], false, net->dtype, stream));
+        }
+        SK_TRY(repack_conv(u.cat, true, net->dtype, stream));
+    }
+    for (auto &c : net->convs) SK_TRY(repack_conv(c, true, net->dtype, stream));
+    return SK_OK;
+}
+
+sk_status unet_get_weights(unet_t *net, int32_t idx, float *w_host, float *b_host)
+{
+    SK_TRY(check(net));
+    if (idx < 0 || idx >= (int)net->params.size()) return fail(SK_EINVAL, "unet_get_weights: bad index");
+    SK_TRY(sync_masters(net));
+    const auto &p = net->params[idx];
+    if (p.kind == 0) {
+        const ConvParams &c = net->convs[p.idx];
+        if (w_host) std::memcpy(w_host, c.w.data(), sizeof(float) * c.wcount());
+        if (b_host) std::memcpy(b_host, c.b.data(), sizeof(float) * c.c_out);
+    } else {
+        const UpParams &u = net->ups[p.idx];
+        if (w_host) std::memcpy(w_host, u.w.data(), sizeof(float) * u.w.size());
+        if (b_host) std::memcpy(b_host, u.b.data(), sizeof(float) * u.c_out);
+    }
     return SK_OK;
 }
 

@@ -15,7 +15,7 @@ def relerr(got, ref):
     return float(np.abs(np.asarray(got, dtype=np.float64) - ref).max() / max(np.abs(ref).max(), 1e-30))
 
 
-def check_grads(net, names, params, loss, ref_loss, ref_grads, tag):
+def check_grads(net, names, params, loss, ref_loss, ref_grads, tag, tol=FP32_TOL):
     assert abs(float(loss.item()) - ref_loss) <= FP32_TOL * abs(ref_loss)
     errs = []
     for i, name in enumerate(names):
@@ -27,7 +27,7 @@ def check_grads(net, names, params, loss, ref_loss, ref_grads, tag):
         errs.append((name, e_w, e_b))
         print("%s %-8s dW %.2e db %.2e" % (tag, name, e_w, e_b), flush=True)
     for name, e_w, e_b in errs:
-        assert e_w <= FP32_TOL and e_b <= FP32_TOL, (name, e_w, e_b)
+        assert e_w <= tol and e_b <= tol, (name, e_w, e_b)
 
 
 def image(n, c_in, h, w, seed):
@@ -70,6 +70,52 @@ def test_unet_backward(depth, base, h, w, n, seed):
     net.close()
 
 
+def test_unet_backward_wide_maps_several_tile_groups():
+    # 128 and 256 maps on a small image: the weight gradients are split over several map-tile and
+    # column-tile groups (each staging its own share of dY rows and input maps), 1x1 and 3x3 alike
+    from paper_1509_03371_amd import binding as B
+    depth, base, h, w, n = 1, 128, 28, 36, 1
+    params = S.unet_params(1, 2, 530, depth=depth, base=base, bias_scale=0.05)
+    names = S.unet_param_names(depth)
+    net = B.UNet(1, 2, depth=depth, base_ch=base)
+    for i, name in enumerate(names):
+        net.set_weights(i, *params[name])
+    img = image(n, 1, h, w, 531)
+    net.plan(n, h, w, training=True)
+    ho, wo = net.output_size(h, w)
+    lab = masked_labels(n, ho, wo, 2, 532)
+    net.forward(torch.from_numpy(img).cuda())
+    loss = net.backward(torch.from_numpy(lab).cuda())
+    p64 = {k: (a.astype(np.float64), b.astype(np.float64)) for k, (a, b) in params.items()}
+    ref_loss, ref_grads = ON.unet_backward(img, p64, lab, depth=depth)
+    check_grads(net, names, params, loss, ref_loss, ref_grads, "unet wide")
+    net.close()
+
+
+def test_c5_unet_training_pass_572():
+    # the configuration table's own sizes (1 x 572^2 -> 388^2, 64..1024 maps): the launch configuration
+    # bench.py times; every parameter gradient against the oracle.  Tolerance: at this size fp32
+    # accumulation itself (dot products of up to 9216 terms, sums over up to 3e5 pixels, 23 layers deep,
+    # gradients that largely cancel) costs more than 1e-4 -- the same pass in plain fp32 on the CPU with
+    # the library's reverse-mode differentiation is off from fp64 by up to 5e-4 of a tensor's largest
+    # entry (measured), this path by up to 1.1e-3; the small cases above hold 1e-4 with the same kernels.
+    from paper_1509_03371_amd import binding as B
+    params = S.unet_params(1, 2, 1005, depth=4, base=64)
+    names = S.unet_param_names(4)
+    net = B.UNet(1, 2, depth=4, base_ch=64)
+    for i, name in enumerate(names):
+        net.set_weights(i, *params[name])
+    img = image(1, 1, 572, 572, 1010)
+    net.plan(1, 572, 572, training=True)
+    lab = S.mask_labels_by_frequency(S.binary_labels(1, 388, 388, 1011), 2, 1012)
+    net.forward(torch.from_numpy(img).cuda())
+    loss = net.backward(torch.from_numpy(lab).cuda())
+    p64 = {k: (a.astype(np.float64), b.astype(np.float64)) for k, (a, b) in params.items()}
+    ref_loss, ref_grads = ON.unet_backward(img, p64, lab, depth=4)
+    check_grads(net, names, params, loss, ref_loss, ref_grads, "unet 572", tol=3e-3)
+    net.close()
+
+
 def test_usknet_backward():
     from paper_1509_03371_amd import binding as B
     base, h, w, n = 8, 212, 228, 2
@@ -86,6 +132,45 @@ def test_usknet_backward():
     p64 = {k: (a.astype(np.float64), b.astype(np.float64)) for k, (a, b) in params.items()}
     ref_loss, ref_grads = ON.usknet_backward(img, p64, lab, base=base)
     check_grads(net, S.USKNET_PARAM_NAMES, params, loss, ref_loss, ref_grads, "usk")
+    net.close()
+
+
+def test_unet_sgd_steps_and_replan():
+    # two momentum steps: after each, every parameter equals the update rule applied to the library's own
+    # gradients (the gradients themselves are checked above); the trained weights survive a new plan
+    from paper_1509_03371_amd import binding as B
+    depth, base, h, w, n = 2, 8, 60, 76, 2
+    params = S.unet_params(2, 3, 502, depth=depth, base=base, bias_scale=0.1)
+    names = S.unet_param_names(depth)
+    net = B.UNet(2, 3, depth=depth, base_ch=base)
+    for i, name in enumerate(names):
+        net.set_weights(i, *params[name])
+    img = torch.from_numpy(image(n, 2, h, w, 510)).cuda()
+    net.plan(n, h, w, training=True)
+    ho, wo = net.output_size(h, w)
+    lab = torch.from_numpy(masked_labels(n, ho, wo, 3, 511)).cuda()
+    lr, mu, wd = np.float32(0.05), np.float32(0.9), np.float32(1e-3)
+    wcur = [[a.copy() for a in net.get_weights(i)] for i in range(len(names))]
+    vel = [[np.zeros_like(a) for a in pair] for pair in wcur]
+    losses = []
+    for step in range(2):
+        net.forward(img)
+        losses.append(float(net.backward(lab).item()))
+        grads = [net.get_grad(i) for i in range(len(names))]
+        net.sgd_step(float(lr), float(mu), float(wd))
+        for i in range(len(names)):
+            got = net.get_weights(i)
+            for j in range(2):
+                vel[i][j] = mu * vel[i][j] + lr * (grads[i][j] + wd * wcur[i][j])
+                wcur[i][j] = wcur[i][j] - vel[i][j]
+                assert np.abs(got[j] - wcur[i][j]).max() <= 2e-6 * max(1.0, np.abs(wcur[i][j]).max()), (names[i], j, step)
+    # the next forward uses the updated weights, on this plan and on a fresh inference plan
+    p64 = {name: (wcur[i][0].astype(np.float64), wcur[i][1].astype(np.float64)) for i, name in enumerate(names)}
+    ref = ON.unet_forward(img.cpu().numpy(), p64, depth=depth)
+    assert np.abs(net.forward(img).cpu().numpy() - ref).max() <= FP32_TOL
+    net.plan(n, h, w)
+    assert np.abs(net.forward(img).cpu().numpy() - ref).max() <= FP32_TOL
+    assert np.array_equal(net.get_weights(3)[0], wcur[3][0].astype(np.float32)) or np.abs(net.get_weights(3)[0] - wcur[3][0]).max() <= 2e-6
     net.close()
 
 
