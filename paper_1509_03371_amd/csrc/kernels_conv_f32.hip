@@ -509,13 +509,11 @@ static hipError_t launch_conv_f32_nt(const ConvF32Args &a, hipStream_t stream)
         return launch_conv_f32_pf_t<NT, 1, 4, 4, 2>(a, stream);
     }
     // the large kernels of the USK-Net (6x6 at d = 1, 8x8 at d = 8) and of the paper's SK-Net (10x10 at
-    // d = 8, a 73-pixel window: three column groups); forward only, one chunk of four maps holds
+    // d = 8, a 73-pixel window: three column groups, forward only); one chunk of four maps holds
     // 4*k*k K values and its weight slab fills most of the LDS, so one workgroup per CU
-    if (a.in_off == 0) {
-        if (a.k == 6 && halo <= 64) return launch_conv_f32_pf_z<NT, 2, 6, 4, 2, false>(a, stream);
-        if (a.k == 8 && halo <= 64) return launch_conv_f32_pf_z<NT, 1, 8, 4, 2, false>(a, stream);
-        if (a.k == 10 && halo <= 128) return launch_conv_f32_pf_z<NT, 1, 10, 4, 3, false>(a, stream);
-    }
+    if (a.k == 6 && halo <= 64) return launch_conv_f32_pf_t<NT, 2, 6, 4, 2>(a, stream);        // forward and data gradient (USK-Net training)
+    if (a.k == 8 && halo <= 64) return launch_conv_f32_pf_t<NT, 1, 8, 4, 2>(a, stream);
+    if (a.k == 10 && halo <= 128 && a.in_off == 0) return launch_conv_f32_pf_z<NT, 1, 10, 4, 3, false>(a, stream);
     return launch_conv_f32_t<NT, 2>(a, stream);
 }
 

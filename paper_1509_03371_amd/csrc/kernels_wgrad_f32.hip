@@ -110,16 +110,33 @@ __global__ __launch_bounds__(256) void wgrad_f32_kernel(WgradArgs a)
                 const float v = dyp[((long)b * a.c_out + rc) * yplane + (long)y * a.Wo + xl];
                 dys[(row - mo0 * 16) * WG_DYP + lane] = (row < a.c_out && x0 + lane < a.Wo) ? v : 0.f;
             }
-            // input rows y + i*d of the group's maps
-            for (int row = wave; row < cw * k; row += 4) {
-                const int c = c_lo + row / k, i = row - (row / k) * k;
-                const float *src = xp + ((long)b * a.c_in + c) * xplane + (long)(y + i * d) * a.W;
-                float *dst = xs + row * a.xpitch;
-#pragma unroll 3
-                for (int xc = lane; xc < PW; xc += 64) {
-                    const int gx = x0 + xc < a.W ? x0 + xc : a.W - 1;
-                    const float v = src[gx];
-                    dst[xc] = (x0 + xc < a.W) ? v : 0.f;
+            // input rows y + i*d of the group's maps, eight rows per wave at a time: all their loads are
+            // issued before the first value is written to LDS (one row after the other, each load's
+            // latency is paid in full -- with hundreds of rows per segment that was most of the kernel)
+            constexpr int SU = 8, SV = 3;                        // rows per batch, 64-column groups per row (PW <= 192)
+            for (int row0 = wave; row0 < cw * k; row0 += 4 * SU) {
+                float v[SU][SV];
+#pragma unroll
+                for (int u = 0; u < SU; ++u) {
+                    int row = row0 + 4 * u;
+                    row = row < cw * k ? row : cw * k - 1;
+                    const int c = c_lo + row / k, i = row - (row / k) * k;
+                    const float *src = xp + ((long)b * a.c_in + c) * xplane + (long)(y + i * d) * a.W;
+#pragma unroll
+                    for (int sv = 0; sv < SV; ++sv) {
+                        const int xc = lane + 64 * sv;
+                        v[u][sv] = src[x0 + xc < a.W ? x0 + xc : a.W - 1];
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < SU; ++u) {
+                    const int row = row0 + 4 * u;
+                    if (row >= cw * k) break;                    // uniform
+#pragma unroll
+                    for (int sv = 0; sv < SV; ++sv) {
+                        const int xc = lane + 64 * sv;
+                        if (xc < PW) xs[row * a.xpitch + xc] = (x0 + xc < a.W) ? v[u][sv] : 0.f;
+                    }
                 }
             }
         } else {
@@ -542,6 +559,7 @@ static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, floa
         const int maps = std::min(c_in, (nb * 64 + k * k - 1) / (k * k) + 1);
         return sizeof(float) * ((size_t)MB * 16 * WG_DYP + (size_t)maps * k * ((PW + 31) / 32 * 32 + 4));
     };
+    if (DT == 0 && PW > 192) return hipErrorInvalidValue;            // the staging loop covers three 64-column groups per row
     if (DT == 0)
         while (NB > 1 && f32_smem(NB) > 150 * 1024) NB = NB == 12 ? 4 : 1;
     // 16-bit storage (and a window of at most 128 columns): the 16-bit matrix path
