@@ -29,8 +29,8 @@ METRIC = "labelled pixels/sec SK-Net fwd (and fwd+bwd) 1 GPU; conv % MFMA peak"
 # read for stream_copy_kernel on 1 GiB (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); the runs and their
 # figures are in profiles/sknet_c{2,3}_forward_hbm_traffic_pmc.txt and
 # profiles/stream_copy_1gib_pmc_calibration.txt.  KiB: (fetch x 2, write).
-TRAFFIC_KIB = {"c2": (2.0 * (35737.6 + 34232.2 + 30812.6) / 3, (78928.0 + 70746.1 + 58095.5) / 3),
-               "c3": (2.0 * (481764.7 + 475194.9 + 454771.8) / 3, (869381.1 + 845296.9 + 798768.0) / 3)}
+TRAFFIC_KIB = {"c2": (2.0 * (35718.7 + 34222.3 + 30790.5) / 3, (77704.1 + 70509.3 + 58015.5) / 3),
+               "c3": (2.0 * (480107.9 + 473247.5 + 454780.7) / 3, (870648.4 + 846171.7 + 798768.0) / 3)}
 
 
 def build_net(B, S, dtype, n, H, W, training):
