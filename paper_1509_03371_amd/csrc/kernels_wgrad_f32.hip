@@ -92,6 +92,73 @@ __global__ __launch_bounds__(256) void wgrad_f32_kernel(WgradArgs a)
         for (int q = 0; q < NB; ++q) acc[m][q] = floatx4{0.f, 0.f, 0.f, 0.f};
 
     const long xplane = (long)a.H * a.W, yplane = (long)a.Ho * a.Wo;
+    // fp32 storage: the loads of a segment are issued in batches (every load of a batch before its first
+    // value is written to LDS: one row after the other, each load's latency is paid in full, and with
+    // hundreds of rows per segment that was most of the kernel), and the first batch of the NEXT segment
+    // -- this wave's dY rows and SU input rows -- is issued before the MFMA loop and held in registers.
+    constexpr int SU = 16, SV = 3;            // input rows per wave and batch, 64-column groups per row (PW <= 192)
+    constexpr int DYU = 4 * MB;               // dY rows per wave
+    float pdy[DT == 0 ? DYU : 1], px[DT == 0 ? SU : 1][DT == 0 ? SV : 1];
+    const int xrows = cw * k;
+    auto load_dy = [&](int b, int y, int x0) {
+        const float *dyp = static_cast<const float *>(a.dy);
+        const int xl = x0 + lane < a.Wo ? x0 + lane : a.Wo - 1;
+#pragma unroll
+        for (int u = 0; u < DYU; ++u) {
+            const int row = mo0 * 16 + wave + 4 * u;
+            const int rc = row < a.c_out ? row : a.c_out - 1;
+            pdy[u] = dyp[((long)b * a.c_out + rc) * yplane + (long)y * a.Wo + xl];
+        }
+    };
+    auto store_dy = [&](int x0) {
+#pragma unroll
+        for (int u = 0; u < DYU; ++u) {
+            const int row = mo0 * 16 + wave + 4 * u;            // < (mo0 + MB) * 16
+            dys[(row - mo0 * 16) * WG_DYP + lane] = (row < a.c_out && x0 + lane < a.Wo) ? pdy[u] : 0.f;
+        }
+    };
+    auto load_x = [&](int bat, int b, int y, int x0) {
+        const float *xp = static_cast<const float *>(a.x);
+#pragma unroll
+        for (int u = 0; u < SU; ++u) {
+            int row = wave + 4 * (bat * SU + u);
+            row = row < xrows ? row : xrows - 1;
+            const int c = c_lo + row / k, i = row - (row / k) * k;
+            const float *src = xp + ((long)b * a.c_in + c) * xplane + (long)(y + i * d) * a.W;
+#pragma unroll
+            for (int sv = 0; sv < SV; ++sv) {
+                const int xc = lane + 64 * sv;
+                px[u][sv] = src[x0 + xc < a.W ? x0 + xc : a.W - 1];
+            }
+        }
+    };
+    auto store_x = [&](int bat, int x0) {
+#pragma unroll
+        for (int u = 0; u < SU; ++u) {
+            const int row = wave + 4 * (bat * SU + u);
+            if (row >= xrows) break;                             // uniform
+#pragma unroll
+            for (int sv = 0; sv < SV; ++sv) {
+                const int xc = lane + 64 * sv;
+                if (xc < PW) xs[row * a.xpitch + xc] = (x0 + xc < a.W) ? px[u][sv] : 0.f;
+            }
+        }
+    };
+    auto locate = [&](int seg, int &b, int &y, int &x0) {
+        const int xs_i = seg % a.xsegs, t = seg / a.xsegs;
+        y = t % a.Ho;
+        b = t / a.Ho;
+        x0 = xs_i * WG_SEG;
+    };
+    const int nbat = (xrows + 4 * SU - 1) / (4 * SU);
+    int pb = 0, py = 0, px0 = 0;              // position of the segment whose first batch is in registers
+    if constexpr (DT == 0) {
+        if ((int)blockIdx.x < a.total_segs) {
+            locate(blockIdx.x, pb, py, px0);
+            load_dy(pb, py, px0);
+            load_x(0, pb, py, px0);
+        }
+    }
     for (int seg = blockIdx.x; seg < a.total_segs; seg += gridDim.x) {
         const int xs_i = seg % a.xsegs;
         const int t = seg / a.xsegs;
@@ -99,45 +166,11 @@ __global__ __launch_bounds__(256) void wgrad_f32_kernel(WgradArgs a)
         const int x0 = xs_i * WG_SEG;
         __syncthreads();
         if constexpr (DT == 0) {
-            const float *dyp = static_cast<const float *>(a.dy), *xp = static_cast<const float *>(a.x);
-            // dY rows of this segment (zero beyond the map and for padded output maps)
-            const int xl = x0 + lane < a.Wo ? x0 + lane : a.Wo - 1;
-            // only the rows of this workgroup's map group (several groups: each reads its own part of dY)
-            const int row_end = (mo0 + MB) * 16 < m_rows ? (mo0 + MB) * 16 : m_rows;
-#pragma unroll 4
-            for (int row = mo0 * 16 + wave; row < row_end; row += 4) {
-                const int rc = row < a.c_out ? row : a.c_out - 1;
-                const float v = dyp[((long)b * a.c_out + rc) * yplane + (long)y * a.Wo + xl];
-                dys[(row - mo0 * 16) * WG_DYP + lane] = (row < a.c_out && x0 + lane < a.Wo) ? v : 0.f;
-            }
-            // input rows y + i*d of the group's maps, eight rows per wave at a time: all their loads are
-            // issued before the first value is written to LDS (one row after the other, each load's
-            // latency is paid in full -- with hundreds of rows per segment that was most of the kernel)
-            constexpr int SU = 8, SV = 3;                        // rows per batch, 64-column groups per row (PW <= 192)
-            for (int row0 = wave; row0 < cw * k; row0 += 4 * SU) {
-                float v[SU][SV];
-#pragma unroll
-                for (int u = 0; u < SU; ++u) {
-                    int row = row0 + 4 * u;
-                    row = row < cw * k ? row : cw * k - 1;
-                    const int c = c_lo + row / k, i = row - (row / k) * k;
-                    const float *src = xp + ((long)b * a.c_in + c) * xplane + (long)(y + i * d) * a.W;
-#pragma unroll
-                    for (int sv = 0; sv < SV; ++sv) {
-                        const int xc = lane + 64 * sv;
-                        v[u][sv] = src[x0 + xc < a.W ? x0 + xc : a.W - 1];
-                    }
-                }
-#pragma unroll
-                for (int u = 0; u < SU; ++u) {
-                    const int row = row0 + 4 * u;
-                    if (row >= cw * k) break;                    // uniform
-#pragma unroll
-                    for (int sv = 0; sv < SV; ++sv) {
-                        const int xc = lane + 64 * sv;
-                        if (xc < PW) xs[row * a.xpitch + xc] = (x0 + xc < a.W) ? v[u][sv] : 0.f;
-                    }
-                }
+            store_dy(x0);
+            store_x(0, x0);
+            for (int bat = 1; bat < nbat; ++bat) {
+                load_x(bat, b, y, x0);
+                store_x(bat, x0);
             }
         } else {
             // 16-bit octet layout: one 16-byte load brings 8 maps of a pixel; widen to fp32 in LDS
@@ -169,6 +202,14 @@ __global__ __launch_bounds__(256) void wgrad_f32_kernel(WgradArgs a)
             }
         }
         __syncthreads();
+        if constexpr (DT == 0) {
+            const int nseg = seg + gridDim.x;
+            if (nseg < a.total_segs) {                           // in flight while this segment is multiplied
+                locate(nseg, pb, py, px0);
+                load_dy(pb, py, px0);
+                load_x(0, pb, py, px0);
+            }
+        }
 #pragma unroll 2
         for (int p = 0; p < WG_SEG; p += 4) {
             float av[MB];
