@@ -120,3 +120,31 @@ def test_unet_host_logic(golden_rows):
     # free parameters of the table's convolutions: the up step's 1x1 conv f -> f/2 has f*f/2 weights
     total += sum(params[n][0].size // 4 for n in names if n.startswith("up"))
     assert round(total / 1e6) == 29
+
+
+def test_usknet_handle_host_logic(golden_rows):
+    # parameter shapes, the table's 692 -> 512, and the refusals; no GPU call is made
+    net = B.USKNet(3, 2, base_ch=64)
+    want = S.usknet_params(3, 2, 1, base=64)
+    assert net.num_params() == len(S.USKNET_PARAM_NAMES)
+    for i, name in enumerate(S.USKNET_PARAM_NAMES):
+        assert net.param_shape(i) == want[name][0].shape, name
+    rows = {r[0]: int(r[2]) for r in golden_rows("usknet_table.txt")}
+    assert net.output_size(rows["data"], rows["data"]) == (rows["ip3"], rows["ip3"])
+    assert net.output_size(182, 190) == (2, 10)
+    for bad in ((181, 182), (180, 180), (3, 3)):
+        with pytest.raises(B.SknetError) as e:
+            net.output_size(*bad)
+        assert e.value.status_name == "SK_ESHAPE"
+    net.close()
+    with pytest.raises(B.SknetError) as e:
+        B.USKNet(3, 2, base_ch=64, dtype="f16")
+    assert e.value.status_name == "SK_EUNSUPPORTED"
+
+
+def test_unet_training_plan_is_fp32_only():
+    net = B.UNet(1, 2, depth=2, base_ch=8, dtype="bf16")
+    with pytest.raises(B.SknetError) as e:
+        net.plan(1, 60, 60, training=True)      # refused before anything is allocated
+    assert e.value.status_name == "SK_EUNSUPPORTED"
+    net.close()
