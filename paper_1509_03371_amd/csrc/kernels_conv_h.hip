@@ -334,7 +334,8 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
             nxt = decode(t);
         }
         prefetch(nxt, nch);
-        compute(buf);
+        // a wave whose 16 columns lie right of the image (narrow maps: most waves of a 128-column tile) multiplies nothing
+        if (__builtin_amdgcn_readfirstlane((int)(cur.x0 + (tid >> 6) * 16 < a.Wo))) compute(buf);
         // Explicit vmcnt(0): every prefetched register is consumed below, some only by part of the
         // lanes; without it the compiler would carry "load pending" states around the loop and wait
         // (also for the stores of the epilogue) before it reuses those registers.  The stores of the
@@ -350,7 +351,7 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
         cur = nxt;
         buf ^= 1;
     }
-    compute(buf);
+    if (__builtin_amdgcn_readfirstlane((int)(cur.x0 + (tid >> 6) * 16 < a.Wo))) compute(buf);
     epilogue(cur);
 }
 
