@@ -399,35 +399,48 @@ __global__ __launch_bounds__(256) void conv_f32_pf_kernel(ConvF32Args a, int til
         commit(chunk);
         __syncthreads();
         if (chunk + 1 < nchunks) prefetch(chunk + 1);
-        // K loop with the operand fragments of step s+1 fetched from LDS while the MFMAs of step s run
-        float av[2][NT], bv[2][RW][4];
-        auto fetch = [&](int sidx, int buf) {
-            int ko = klane + kthread + kconst(sidx);
-            if constexpr (KTAB) ko = ktab[sidx % SPM] + kthread + (sidx / SPM) * RR * PITCH;
-            else if constexpr (!KSPLIT) ko = kreg[sidx] + kthread;
+        // K loop with the operand fragments of step s+1 fetched from LDS while the MFMAs of step s run.
+        // XN = 16-column groups of the tile that hold output columns: a tile at the right border of the
+        // map (or a map narrower than 33 columns: the deep U-Net levels) multiplies only its first two.
+        auto kloop = [&](auto xn) {
+            constexpr int XN = decltype(xn)::value;
+            float av[2][NT], bv[2][RW][XN];
+            auto fetch = [&](int sidx, int buf) {
+                int ko = klane + kthread + kconst(sidx);
+                if constexpr (KTAB) ko = ktab[sidx % SPM] + kthread + (sidx / SPM) * RR * PITCH;
+                else if constexpr (!KSPLIT) ko = kreg[sidx] + kthread;
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) av[buf][nt] = ws[(4 * sidx + g) * WN + nt * 16 + l16];
+                for (int nt = 0; nt < NT; ++nt) av[buf][nt] = ws[(4 * sidx + g) * WN + nt * 16 + l16];
 #pragma unroll
-            for (int rw = 0; rw < RW; ++rw)
+                for (int rw = 0; rw < RW; ++rw)
 #pragma unroll
-                for (int xt = 0; xt < 4; ++xt) bv[buf][rw][xt] = xs[ko + rw * PITCH + xt * 16];
+                    for (int xt = 0; xt < XN; ++xt) bv[buf][rw][xt] = xs[ko + rw * PITCH + xt * 16];
+            };
+            fetch(0, 0);
+#pragma unroll
+            for (int sidx = 0; sidx < KC / 4; ++sidx) {
+                const int cur = sidx & 1;
+                if (sidx + 1 < KC / 4) fetch(sidx + 1, cur ^ 1);
+                // the scheduler otherwise sinks each LDS read to just before its first use and the wave
+                // waits out the LDS latency several times per step
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int rw = 0; rw < RW; ++rw)
+#pragma unroll
+                    for (int xt = 0; xt < XN; ++xt)
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt)
+                            acc[rw][xt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[cur][nt], bv[cur][rw][xt], acc[rw][xt][nt], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         };
-        fetch(0, 0);
-#pragma unroll
-        for (int sidx = 0; sidx < KC / 4; ++sidx) {
-            const int cur = sidx & 1;
-            if (sidx + 1 < KC / 4) fetch(sidx + 1, cur ^ 1);
-            // the scheduler otherwise sinks each LDS read to just before its first use and the wave
-            // waits out the LDS latency several times per step
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int rw = 0; rw < RW; ++rw)
-#pragma unroll
-                for (int xt = 0; xt < 4; ++xt)
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt)
-                        acc[rw][xt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[cur][nt], bv[cur][rw][xt], acc[rw][xt][nt], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
+        // (only the small-map instantiation carries both loops: a second copy costs the large-map kernels
+        // registers -- 153 -> 210, a workgroup less per CU)
+        if constexpr (KS == 3 && CC == 16) {
+            if (a.Wo - x0 <= 32) kloop(std::integral_constant<int, 2>{});
+            else kloop(std::integral_constant<int, 4>{});
+        } else {
+            kloop(std::integral_constant<int, 4>{});
         }
     }
 
