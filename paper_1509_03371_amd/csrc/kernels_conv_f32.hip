@@ -92,7 +92,36 @@ __device__ __forceinline__ void store_outputs(const ConvF32Args &a, floatx4 (&ac
             }
         }
     };
-    if (a.mask) store_tiles(std::true_type{});
+    // the four taps of an up-convolution stacked as GEMM maps: each 16-map tile belongs to one tap, which
+    // moves its maps back by tap*tap_maps and its pixels to the tap's place in the 2x2 block (no mask here)
+    auto store_taps = [&]() {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const int o0 = o_first + nt * 16;
+            const int tap = o0 / a.tap_maps, om = o0 - tap * a.tap_maps;
+#pragma unroll
+            for (int rw = 0; rw < RW; ++rw) {
+                const int oy = oy_first + rw * d;
+                if (oy >= a.Ho) continue;
+                const long rowbase = (((long)b * a.out_maps + a.o_off + om) * a.OH + (long)oy * a.oy_mul + (tap >> 1)) * a.OW + (tap & 1);
+#pragma unroll
+                for (int xt = 0; xt < 4; ++xt) {
+                    const int ox = ox_first + xt * 16;
+                    if (ox >= a.Wo) continue;
+                    const long pbase = rowbase + (long)ox * a.ox_mul;
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4) {
+                        if (o0 + r4 >= a.c_out) continue;
+                        float v = acc[rw][xt][nt][r4] + bia[nt][r4];
+                        if (a.relu) v = v > 0.f ? v : 0.f;
+                        a.y[pbase + r4 * oplane] = v;
+                    }
+                }
+            }
+        }
+    };
+    if (a.tap_maps > 0) store_taps();
+    else if (a.mask) store_tiles(std::true_type{});
     else store_tiles(std::false_type{});
 }
 
@@ -619,6 +648,8 @@ static hipError_t launch_conv_c1_f32(const ConvF32Args &a, hipStream_t stream)
 hipError_t launch_conv_f32(const ConvF32Args &a, hipStream_t stream)
 {
     if (a.n_pad % 16 != 0 || a.c_out > a.n_pad || a.k < 1 || a.d < 1 || a.Ho < 1 || a.Wo < 1)
+        return hipErrorInvalidValue;
+    if (a.tap_maps != 0 && (a.tap_maps < 16 || a.tap_maps % 16 != 0 || a.c_out != 4 * a.tap_maps || a.mask || a.oy_mul != 2 || a.ox_mul != 2))
         return hipErrorInvalidValue;
     // a single input map, plain forward placement (contiguous NCHW output, no mask)
     if (a.c_in == 1 && a.in_off == 0 && !a.mask && a.OH == a.Ho && a.OW == a.Wo && a.oy_mul == 1 && a.ox_mul == 1 &&

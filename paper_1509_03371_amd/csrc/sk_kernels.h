@@ -26,6 +26,9 @@ struct ConvF32Args {
     int Ho, Wo;
     int relu;
     int out_maps, o_off, OH, OW, oy_mul, oy_off, ox_mul, ox_off;
+    // tap_maps > 0 (a multiple of 16): GEMM map o is tap t = o / tap_maps of real map o % tap_maps and is stored at
+    // (y*oy_mul + t/2, x*ox_mul + t%2) -- the four taps of a 2x2 stride-2 up-convolution as one 1x1 convolution
+    int tap_maps;
 };
 hipError_t launch_conv_f32(const ConvF32Args &a, hipStream_t stream);
 

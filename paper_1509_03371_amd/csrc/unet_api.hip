@@ -157,12 +157,14 @@ sk_status upload_up(UpParams &u, int dtype)
             t.b = u.b;
             SK_TRY(upload_conv(t, false, nullptr, dtype));
         }
-    if (u.cat.w_dev) {                 // training plan: the stacked form (bias unused: gradients only)
+    if (u.cat.w_dev) {                 // the stacked form: one launch in the fp32 forward pass, and the backward pass
         u.cat.w.resize((size_t)4 * u.c_out * u.c_in);
-        for (int t = 0; t < 4; ++t)
+        u.cat.b.resize((size_t)4 * u.c_out);
+        for (int t = 0; t < 4; ++t) {
             std::memcpy(u.cat.w.data() + (size_t)t * u.c_out * u.c_in, u.tap[t].w.data(), sizeof(float) * u.c_out * u.c_in);
-        u.cat.b.assign((size_t)4 * u.c_out, 0.f);
-        SK_TRY(upload_conv(u.cat, true, nullptr, dtype));
+            std::memcpy(u.cat.b.data() + (size_t)t * u.c_out, u.b.data(), sizeof(float) * u.c_out);
+        }
+        SK_TRY(upload_conv(u.cat, u.cat.wp_bwd != nullptr, nullptr, dtype));
     }
     return SK_OK;
 }
@@ -472,11 +474,11 @@ static sk_status plan_impl(unet_t *net, int32_t n, int32_t h_in, int32_t w_in, b
             t.c_in = u.c_in; t.c_out = u.c_out; t.k = 1;
             if (st == SK_OK) st = alloc_conv(t, false, net->dtype);
         }
-        if (training) {
+        if (!half) {
             u.cat.c_in = u.c_in; u.cat.c_out = 4 * u.c_out; u.cat.k = 1;
             u.cat.w.assign((size_t)4 * u.c_out * u.c_in, 0.f);
             u.cat.b.assign((size_t)4 * u.c_out, 0.f);
-            if (st == SK_OK) st = alloc_conv(u.cat, true, net->dtype);
+            if (st == SK_OK) st = alloc_conv(u.cat, training, net->dtype);
         }
         if (st == SK_OK) st = upload_up(u, net->dtype);
     }
@@ -577,12 +579,21 @@ sk_status unet_forward(unet_t *net, const float *image_dev, float *prob_dev, voi
                                           op.k, op.d, op.s, stream));
         } else if (op.kind == 2) {
             const UpParams &u = net->ups[op.param];
-            for (int t = 0; t < 4; ++t) {
-                Dims lowres = {u.c_out, op.in.h, op.in.w};
-                sk::ConvF32Args a = conv_args(u.tap[t], src, n, op.in, 1, 0, op.dst, lowres);
+            if (u.c_out % 16 == 0) {
+                // one 1x1 convolution to 4*c_out maps; the epilogue puts tap t of map o at (2y + t/2, 2x + t%2)
+                Dims lowres = {4 * u.c_out, op.in.h, op.in.w};
+                sk::ConvF32Args a = conv_args(u.cat, src, n, op.in, 1, 0, op.dst, lowres);
                 a.out_maps = op.out.c; a.OH = op.out.h; a.OW = op.out.w;
-                a.oy_mul = 2; a.oy_off = t / 2; a.ox_mul = 2; a.ox_off = t % 2;
+                a.oy_mul = 2; a.oy_off = 0; a.ox_mul = 2; a.ox_off = 0; a.tap_maps = u.c_out;
                 SK_HIP(sk::launch_conv_f32(a, stream));
+            } else {
+                for (int t = 0; t < 4; ++t) {
+                    Dims lowres = {u.c_out, op.in.h, op.in.w};
+                    sk::ConvF32Args a = conv_args(u.tap[t], src, n, op.in, 1, 0, op.dst, lowres);
+                    a.out_maps = op.out.c; a.OH = op.out.h; a.OW = op.out.w;
+                    a.oy_mul = 2; a.oy_off = t / 2; a.ox_mul = 2; a.ox_off = t % 2;
+                    SK_HIP(sk::launch_conv_f32(a, stream));
+                }
             }
         } else {
             SK_HIP(sk::launch_crop_copy_f32(src, op.dst, n, op.src_maps, op.in.h, op.in.w, op.out.c, op.o_off,
@@ -758,6 +769,7 @@ sk_status unet_sgd_step(unet_t *net, float lr, float momentum, float weight_deca
         SK_HIP(sk::launch_up_bias_sgd_f32(u.tap[0].b_dev, u.tap[1].b_dev, u.tap[2].b_dev, u.tap[3].b_dev, u.cat.db,
                                           momentum != 0.f ? u.cat.vb : nullptr, u.c_out, lr, momentum, weight_decay, stream));
         for (int t = 0; t < 4; ++t) {
+            SK_HIP(hipMemcpyAsync(u.cat.b_dev + (size_t)t * u.c_out, u.tap[0].b_dev, sizeof(float) * u.c_out, hipMemcpyDeviceToDevice, stream));
             SK_HIP(hipMemcpyAsync(u.tap[t].w_dev, u.cat.w_dev + (size_t)t * u.c_out * u.c_in, sizeof(float) * u.c_out * u.c_in,
                                   hipMemcpyDeviceToDevice, stream));
             SK_TRY(repack_conv(u.tap[t], false, net->dtype, stream));
