@@ -294,6 +294,12 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
                         if (colok && o + r4 < a.c_out) *reinterpret_cast<float *>(ybase + (o + r4) * plane_bytes + yoff) = v[r4];
                 } else {
                     const int o8 = mtile * 2 + (g >> 1);
+                    // stacked up-convolution taps: the tile's tap moves its octets back and its pixel inside the 2x2 block
+                    int tapadj = 0;
+                    if (a.tap_maps > 0) {
+                        const int tap = mtile * 16 / a.tap_maps;
+                        tapadj = (tap >> 1) * row_bytes + (tap & 1) * 16 - tap * (a.tap_maps / 8) * plane_bytes;
+                    }
                     unsigned short h[4];
 #pragma unroll
                     for (int r4 = 0; r4 < 4; ++r4) h[r4] = H<DT>::cvt(v[r4]);
@@ -307,7 +313,7 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
                         if (!pos16(m[1] >> 16)) hi &= 0x0000ffffu;
                         packed = uint2v{lo, hi};
                     }
-                    if (colok && o8 < a.c8_out) *reinterpret_cast<uint2v *>(ybase + o8 * plane_bytes + yoff) = packed;
+                    if (colok && o8 < a.c8_out) *reinterpret_cast<uint2v *>(ybase + o8 * plane_bytes + yoff + tapadj) = packed;
                 }
             }
         }
@@ -602,7 +608,14 @@ __global__ __launch_bounds__(CH_THREADS + 64 * NP) void conv_h_ring_kernel(ConvH
         for (int mt = 0; mt < MT; ++mt) {
             const int mtile = p.mg * MT + mt;
             if (a.out_f32) voff[mt] = (unsigned)((mtile * 16 + 4 * g) * plane_bytes + (oxc * a.ox_mul + a.ox_off) * 4);
-            else voff[mt] = (unsigned)((mtile * 2 + (g >> 1)) * plane_bytes + (oxc * a.ox_mul + a.ox_off) * 16 + (g & 1) * 8);
+            else {
+                int off = (mtile * 2 + (g >> 1)) * plane_bytes + (oxc * a.ox_mul + a.ox_off) * 16 + (g & 1) * 8;
+                if (a.tap_maps > 0) {        // stacked up-convolution taps (see ConvHArgs)
+                    const int tap = mtile * 16 / a.tap_maps;
+                    off += (tap >> 1) * row_bytes + (tap & 1) * 16 - tap * (a.tap_maps / 8) * plane_bytes;
+                }
+                voff[mt] = (unsigned)off;
+            }
         }
         uint2v mk[HAS_MASK ? R : 1][HAS_MASK ? MT : 1];
         if constexpr (HAS_MASK) {
@@ -1039,6 +1052,9 @@ bool conv_h_supported(int k, int d, int gemm_m)
 hipError_t launch_conv_h(const ConvHArgs &a, hipStream_t stream)
 {
     if (!conv_h_supported(a.k, a.d) || a.Ho < 1 || a.Wo < 1 || a.c8_in < 1 || a.c_out < 1) return hipErrorInvalidValue;
+    if (a.tap_maps != 0 && (a.tap_maps < 16 || a.tap_maps % 16 != 0 || a.c_out != 4 * a.tap_maps || a.mask || a.out_f32 || a.oy_mul != 2 ||
+                            a.ox_mul != 2 || a.k != 1))
+        return hipErrorInvalidValue;
     // the packed weights were laid out for this many map tiles per group (0 = the default choice)
     const int mt = a.mt > 0 ? a.mt : conv_h_mt(a.c_out, a.k);
     if (mt > 4 || (a.k == 3 && mt > 3)) return hipErrorInvalidValue;

@@ -59,6 +59,7 @@ struct ConvHArgs {
     int relu, out_f32;
     int c8_out_total, o8_off, OH, OW, oy_mul, oy_off, ox_mul, ox_off;
     int mt;               // map tiles per workgroup the weights were packed for; 0 = default for (c_out, k)
+    int tap_maps;         // > 0 (multiple of 16): GEMM map o = tap o / tap_maps of real map o % tap_maps, stored at (y*oy_mul + tap/2, x*ox_mul + tap%2)
     // filled in by the launcher
     int m_tiles, mgroups, nchunks, xtiles, tiles_hi, tiles_lo, rem, ytiles_total, total_tiles;
     const void *zeros;    // >= 16 bytes of zeros in device memory

@@ -459,6 +459,7 @@ static sk_status plan_impl(unet_t *net, int32_t n, int32_t h_in, int32_t w_in, b
                 c.mt16 = sk::conv_h_pick_mt(c.c_out, c.k, n, op.out.h, op.out.w);
             } else if (op.kind == 2) {
                 for (auto &t : net->ups[op.param].tap) t.mt16 = sk::conv_h_pick_mt(net->ups[op.param].c_out, 1, n, op.in.h, op.in.w);
+                net->ups[op.param].cat.mt16 = sk::conv_h_pick_mt(4 * net->ups[op.param].c_out, 1, n, op.in.h, op.in.w);
             }
         }
     }
@@ -474,7 +475,7 @@ static sk_status plan_impl(unet_t *net, int32_t n, int32_t h_in, int32_t w_in, b
             t.c_in = u.c_in; t.c_out = u.c_out; t.k = 1;
             if (st == SK_OK) st = alloc_conv(t, false, net->dtype);
         }
-        if (!half) {
+        {
             u.cat.c_in = u.c_in; u.cat.c_out = 4 * u.c_out; u.cat.k = 1;
             u.cat.w.assign((size_t)4 * u.c_out * u.c_in, 0.f);
             u.cat.b.assign((size_t)4 * u.c_out, 0.f);
@@ -557,12 +558,21 @@ sk_status unet_forward(unet_t *net, const float *image_dev, float *prob_dev, voi
                                             op.out.h, op.out.w, op.k, op.d, op.s, stream));
             } else if (op.kind == 2) {
                 const UpParams &u = net->ups[op.param];
-                for (int t = 0; t < 4; ++t) {
-                    Dims lowres = {u.c_out, op.in.h, op.in.w};
-                    sk::ConvHArgs a = conv_h_args(u.tap[t], dt, src, n, op.in, 1, 0, op.dst, lowres, false);
+                if (u.c_out % 16 == 0) {
+                    // one 1x1 convolution to 4*c_out maps; the epilogue puts tap t of map o at (2y + t/2, 2x + t%2)
+                    Dims lowres = {4 * u.c_out, op.in.h, op.in.w};
+                    sk::ConvHArgs a = conv_h_args(u.cat, dt, src, n, op.in, 1, 0, op.dst, lowres, false);
                     a.c8_out_total = (op.out.c + 7) / 8; a.o8_off = 0; a.OH = op.out.h; a.OW = op.out.w;
-                    a.oy_mul = 2; a.oy_off = t / 2; a.ox_mul = 2; a.ox_off = t % 2;
+                    a.oy_mul = 2; a.oy_off = 0; a.ox_mul = 2; a.ox_off = 0; a.tap_maps = u.c_out;
                     SK_HIP(sk::launch_conv_h(a, stream));
+                } else {
+                    for (int t = 0; t < 4; ++t) {
+                        Dims lowres = {u.c_out, op.in.h, op.in.w};
+                        sk::ConvHArgs a = conv_h_args(u.tap[t], dt, src, n, op.in, 1, 0, op.dst, lowres, false);
+                        a.c8_out_total = (op.out.c + 7) / 8; a.o8_off = 0; a.OH = op.out.h; a.OW = op.out.w;
+                        a.oy_mul = 2; a.oy_off = t / 2; a.ox_mul = 2; a.ox_off = t % 2;
+                        SK_HIP(sk::launch_conv_h(a, stream));
+                    }
                 }
             } else {
                 SK_HIP(sk::launch_crop_copy_h(src, op.dst, n, op.src_maps / 8, op.in.h, op.in.w, (op.out.c + 7) / 8, op.o_off / 8,
