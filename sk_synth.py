@@ -67,6 +67,55 @@ def he_normal_weights(layers, c_in, seed, bias_scale=0.0):
     return ws, bs
 
 
+def sknet3d_layers(classes=2, maps=(16, 32, 128, 64)):
+    """A 3-D SK net in the manner of Section 5.2.2 (the 2-D layer sequence with 3-D kernels and fewer maps,
+    sized for memory): the Algorithm-1 conversion of the sliding-window net conv k3, pool 2, conv k3, pool 2,
+    inner product, inner product, classes on an 18^3 patch.  Context 17 per axis."""
+    a, b, c, e = maps
+    return [conv(a, 3, 1), pool(2, 1), conv(b, 3, 2), pool(2, 2), conv(c, 3, 4), conv(e, 1, 1),
+            conv(classes, 1, 1, relu=False)]
+
+
+def sw3d_layers(classes=2, maps=(16, 32, 128, 64)):
+    """The sliding-window net that sknet3d_layers() converts; patch 18 per axis."""
+    a, b, c, e = maps
+    return [{"type": "conv", "f_out": a, "k": 3, "relu": True}, {"type": "pool", "k": 2, "s": 2},
+            {"type": "conv", "f_out": b, "k": 3, "relu": True}, {"type": "pool", "k": 2, "s": 2},
+            {"type": "ip", "f_out": c, "relu": True}, {"type": "ip", "f_out": e, "relu": True},
+            {"type": "ip", "f_out": classes, "relu": False}]
+
+
+def he_normal_weights3d(layers, c_in, seed, bias_scale=0.0):
+    """As he_normal_weights for kernels [f_out, f_in, k, k, k] (standard deviation sqrt(2/(f_in k^3)))."""
+    rng = np.random.default_rng(seed)
+    ws, bs, f_in = [], [], c_in
+    for l in layers:
+        if l["type"] != "conv":
+            continue
+        k, f_out = l["k"], l["f_out"]
+        w = rng.standard_normal((f_out, f_in, k, k, k)) * np.sqrt(2.0 / (f_in * k ** 3))
+        b = rng.standard_normal(f_out) * bias_scale
+        ws.append(w.astype(np.float32))
+        bs.append(b.astype(np.float32))
+        f_in = f_out
+    return ws, bs
+
+
+def uniform_volume(c, dz, h, w, seed):
+    return np.random.default_rng(seed).random((c, dz, h, w), dtype=np.float32)
+
+
+def em_like_volume(dz, h, w, seed):
+    """A stack of dz sections [1, dz, h, w]: consecutive sections are one slowly changing texture (blurred
+    along the stack as well), each crossed by its own dark curves as in em_like_image."""
+    rng = np.random.default_rng(seed)
+    base = ndimage.gaussian_filter(rng.random((dz, h, w)), (1.5, 2.0, 2.0), mode="reflect", truncate=4.0)
+    base = (base - base.min()) / (base.max() - base.min())
+    marks = np.stack([em_like_image(h, w, seed + 1 + z) for z in range(dz)])
+    vol = 0.5 * base + 0.5 * marks
+    return vol[None].astype(np.float32)
+
+
 def uniform_image(n, c, h, w, seed):
     return np.random.default_rng(seed).random((n, c, h, w), dtype=np.float32)
 
