@@ -8,6 +8,7 @@ A step is one such pass over one synthetic image that is resident in HBM before 
 --workload c3 : the same net in bf16 (fp32 accumulate) on 8 images of 1024x1024 (configs[2])
 --workload c4 : one bf16 training step at 512x512 (configs[3]): forward, softmax loss, backward, SGD
 --workload c5 / c5bf16 : U-Net forward on one 572x572 image (configs[4]) in fp32 / bf16
+--workload sk3d : 3-D SK net forward on a stack of 81 sections of 145x145 (Section 5.2.2), fp32
 --workload copy : only the streaming-copy probe on 2 x 1 GiB (the known-size kernel that the HBM
                   byte counters of a profiler run are calibrated against)
 The default run also appends short c3 / c4 measurements under "extras" (skip with --no-extras).
@@ -241,6 +242,41 @@ def measure_paper_sknet(torch, B, S, steps, warmup):
             "paper_pixels_per_s": {"W9100 OpenCL": 59513, "GTX 980 CUDA": 85460}}
 
 
+def measure_sknet3d(torch, B, S, steps, warmup):
+    """3-D SK net forward (Section 5.2.2): the Algorithm-1 conversion of an 18^3 sliding-window net
+    (conv k3, pool, conv k3, pool, inner products 128 and 64; context 17) on a stack of 81 synthetic
+    145 x 145 sections -> 64 x 128 x 128 labelled voxels, fp32."""
+    import numpy as np
+    layers = S.sknet3d_layers(classes=2)
+    ws, bs = S.he_normal_weights3d(layers, 1, 1100)
+    net = B.SKNet3D(layers, 1, 2)
+    for i, (w, b) in enumerate(zip(ws, bs)):
+        net.set_weights(i, w, b)
+    dz, h, w = 81, 145, 145
+    net.plan(dz, h, w)
+    shapes = net.infer_shapes(dz, h, w)
+    vol = torch.from_numpy(np.ascontiguousarray(S.em_like_volume(dz, h, w, 1101).transpose(1, 0, 2, 3))).cuda()
+    prob = torch.empty(net.out_shape(), dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+    for _ in range(warmup):
+        net.forward(vol, prob, stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        net.forward(vol, prob, stream)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    net.close()
+    gflop, f_in = 0.0, 1
+    for lay, (c, d_, h_, w_) in zip(layers, shapes[1:]):
+        if lay["type"] == "conv":
+            gflop += 2e-9 * f_in * lay["k"] ** 3 * c * d_ * h_ * w_       # Section 5.5's count with k^3 taps
+            f_in = c
+    voxels = shapes[-1][1] * shapes[-1][2] * shapes[-1][3]
+    return {"ms_per_step": round(dt * 1e3, 4), "labelled_voxels_per_s": round(voxels / dt, 1),
+            "gflop": round(gflop, 1), "tflops": round(gflop / dt / 1e3, 1)}
+
+
 def measured_peaks(torch, B):
     """What this GPU sustains on a bare MFMA issue loop and on a streaming copy (not the method)."""
     src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)   # 1 GiB each
@@ -263,7 +299,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", choices=["c2", "c3", "c4", "c5", "c5bf16", "usk", "papersk", "unettrain", "usktrain", "copy"], default="c2")
+    ap.add_argument("--workload", choices=["c2", "c3", "c4", "c5", "c5bf16", "usk", "papersk", "sk3d", "unettrain", "usktrain", "copy"], default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
     args = ap.parse_args()
@@ -310,8 +346,11 @@ def main():
         print(json.dumps(out))
         return
 
-    if args.workload in ("usk", "papersk"):
-        if args.workload == "usk":
+    if args.workload in ("usk", "papersk", "sk3d"):
+        if args.workload == "sk3d":
+            r = measure_sknet3d(torch, B, S, args.steps, args.warmup)
+            px, what = r["labelled_voxels_per_s"], "3-D SK net forward, 81x145x145 -> 2x64x128x128 (context 17), fp32; value = labelled voxels per second"
+        elif args.workload == "usk":
             r = measure_usknet(torch, B, S, args.steps, args.warmup)
             px, what = r["labelled_pixels_per_s"], "USK-Net forward 1x3x692x692 -> 2x512x512, fp32 (the paper's USK configuration table)"
         else:
@@ -367,6 +406,7 @@ def main():
             extras[name] = measure_unet(torch, B, S, dt, 10, 3)
         extras["paper_sknet_128_f32"] = measure_paper_sknet(torch, B, S, 5, 2)
         extras["usknet_692_f32_forward"] = measure_usknet(torch, B, S, 5, 2)
+        extras["sknet3d_81x145x145_f32_forward"] = measure_sknet3d(torch, B, S, 5, 2)
         extras["unet_572_f32_train_step"] = measure_unet_train(torch, B, S, "unet", 3, 1)
         extras["usknet_692_f32_train_step"] = measure_unet_train(torch, B, S, "usk", 3, 1)
         out["extras"] = extras

@@ -32,6 +32,7 @@ extern "C" {
 
 typedef struct sknet sknet_t; /* opaque */
 typedef struct unet unet_t;   /* opaque */
+typedef struct sknet3d sknet3d_t; /* opaque */
 
 typedef enum {
     SK_OK = 0,
@@ -253,6 +254,45 @@ sk_status unet_get_weights(unet_t *net, int32_t idx, float *w_host, float *b_hos
 
 /* Output of named stage (HOST fp32 NCHW): "down{i}", "up{i}", "dec{i}", "logits". *dims3 = maps,h,w. */
 sk_status unet_get_activation(unet_t *net, const char *stage, float *nchw_host, int32_t *dims3);
+
+/* ---------------------------------------------------------------- 3-D SK net forward */
+
+/* SK net on volumes (Section 5.2.2: the convolution and max-pool layers with one more spatial axis; the
+ * paper's N-dimensional layers, three dimensions here).  The layers are sk_layer entries whose k, d and s
+ * act on depth, height and width alike:
+ *   SK_CONV    : Y[o,z,y,x] = b[o] + sum_{c,a,i,j} W[o,c,a,i,j] X[c, z+a*d, y+i*d, x+j*d], optional ReLU;
+ *   SK_MAXPOOL : Y[c,z,y,x] = max_{a,i,j<k} X[c, s*z+a*d, s*y+i*d, s*x+j*d]  (s = 1, or s = k with d = 1);
+ * every layer shrinks each axis by (k-1)*d (Algorithm 1 holds per axis); a per-voxel softmax over the maps
+ * of the last layer follows.  fp32 only, one volume per call, no padding: the caller's volume contains the
+ * context v, the output is (dz - v) x (h - v) x (w - v).  Create is host only; errors as sknet_create.
+ *
+ * Layout of every volume that crosses this interface (input, probabilities, activations): SLICE-MAJOR,
+ * [depth][maps][height][width] fp32 -- a stack of multi-map 2-D sections; for one input map that is the
+ * plain [depth][height][width] image stack.  Weights are [f_out][f_in][k][k][k] (depth, height, width taps). */
+sk_status sknet3d_create(const sk_layer *layers, int32_t n_layers, int32_t c_in, int32_t n_classes, sknet3d_t **out);
+void sknet3d_destroy(sknet3d_t *net);
+/* *v = sum of (k-1)*d over the layers (SK_ESHAPE if a pool has s != 1). */
+sk_status sknet3d_context(const sknet3d_t *net, int32_t *v);
+/* dims4 (HOST) receives (n_layers + 1) quadruples {maps, depth, height, width}: entry 0 the input volume,
+ * entry i the output of layer i-1.  SK_ESHAPE if a map would vanish or a down-sampling pool meets a size
+ * that k does not divide. */
+sk_status sknet3d_infer_shapes(const sknet3d_t *net, int32_t dz, int32_t h, int32_t w, int32_t *dims4);
+sk_status sknet3d_num_convs(const sknet3d_t *net, int32_t *count);
+/* shape5 (HOST) = {f_out, f_in, k, k, k} */
+sk_status sknet3d_conv_shape(const sknet3d_t *net, int32_t conv_idx, int32_t *shape5);
+/* w_host: HOST fp32 [f_out][f_in][k][k][k]; b_host: HOST fp32 [f_out] or NULL = keep.  Before or after a
+ * plan (after: the device copies are refreshed synchronously). */
+sk_status sknet3d_set_weights(sknet3d_t *net, int32_t conv_idx, const float *w_host, const float *b_host);
+/* Fix the volume size and allocate the workspaces on the current HIP device (hipMalloc).  mode 0: inference,
+ * a trailing "1x1x1 conv + ReLU, 1x1x1 conv, softmax" may run as one kernel (then sknet3d_get_activation
+ * reports SK_ESTATE for those two layers); mode 2: every layer's output is kept.  May be called again. */
+sk_status sknet3d_plan(sknet3d_t *net, int32_t dz, int32_t h, int32_t w, int32_t mode);
+/* volume_dev: DEVICE fp32 [dz][c_in][h][w]; prob_dev: DEVICE fp32 [dz-v][n_classes][h-v][w-v] (for nets with
+ * down-sampling pools: the sizes sknet3d_infer_shapes reports).  The volume must stay valid until the
+ * enqueued work has run.  SK_ESTATE without a plan. */
+sk_status sknet3d_forward(sknet3d_t *net, const float *volume_dev, float *prob_dev, void *hip_stream);
+/* Output of layer layer_idx (HOST fp32 [depth][maps][height][width]); synchronises. */
+sk_status sknet3d_get_activation(sknet3d_t *net, int32_t layer_idx, float *dchw_host);
 
 /* Machine probes for the benchmark (Section 6 of the paper times kernels against each device's
  * peak; these two calls measure the peaks of the device at hand).  Neither runs any step of the method.

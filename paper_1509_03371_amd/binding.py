@@ -74,6 +74,15 @@ _SIGS = {
     "unet_param_kind": [_vp, _i32, _ip],
     "unet_sgd_step": [_vp, C.c_float, C.c_float, C.c_float, _vp],
     "unet_get_weights": [_vp, _i32, _fp, _fp],
+    "sknet3d_create": [C.POINTER(SkLayer), _i32, _i32, _i32, C.POINTER(_vp)],
+    "sknet3d_context": [_vp, _ip],
+    "sknet3d_infer_shapes": [_vp, _i32, _i32, _i32, _ip],
+    "sknet3d_num_convs": [_vp, _ip],
+    "sknet3d_conv_shape": [_vp, _i32, _ip],
+    "sknet3d_set_weights": [_vp, _i32, _fp, _fp],
+    "sknet3d_plan": [_vp, _i32, _i32, _i32, _i32],
+    "sknet3d_forward": [_vp, _vp, _vp, _vp],
+    "sknet3d_get_activation": [_vp, _i32, _fp],
     "sk_probe_mfma": [_i32, _i32, _i32, _vp, C.POINTER(C.c_double)],
     "sk_probe_copy": [_vp, _vp, C.c_uint64, _i32, _vp, C.POINTER(C.c_double)],
 }
@@ -85,12 +94,14 @@ lib.sknet_destroy.argtypes = [_vp]
 lib.sknet_destroy.restype = None
 lib.unet_destroy.argtypes = [_vp]
 lib.unet_destroy.restype = None
+lib.sknet3d_destroy.argtypes = [_vp]
+lib.sknet3d_destroy.restype = None
 lib.sknet_last_error.argtypes = []
 lib.sknet_last_error.restype = C.c_char_p
 lib.sknet_conv_flops.argtypes = [C.c_int64] * 4
 lib.sknet_conv_flops.restype = C.c_int64
 
-EXPORTED = sorted(list(_SIGS) + ["sknet_destroy", "unet_destroy", "sknet_last_error", "sknet_conv_flops"])
+EXPORTED = sorted(list(_SIGS) + ["sknet_destroy", "unet_destroy", "sknet3d_destroy", "sknet_last_error", "sknet_conv_flops"])
 
 
 def _check(status):
@@ -416,3 +427,89 @@ class USKNet(UNet):
 
     def _create(self, c_in, n_classes, depth, base_ch, dtype):
         _check(lib.usknet_create(c_in, n_classes, base_ch, DTYPES[dtype], C.byref(self._h)))
+
+
+class SKNet3D:
+    """Owner of one sknet3d_t handle; methods are the C entry points without the `sknet3d_` prefix.
+    Volumes are slice-major: [depth][maps][height][width]."""
+
+    def __init__(self, layers, c_in, n_classes):
+        self.layers = list(layers)
+        self._h = _vp()
+        _check(lib.sknet3d_create(layers_to_c(layers), len(layers), c_in, n_classes, C.byref(self._h)))
+        self.c_in, self.n_classes = c_in, n_classes
+        self._plan = None
+
+    def close(self):
+        if self._h:
+            lib.sknet3d_destroy(self._h)
+            self._h = _vp()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def context(self):
+        v = C.c_int32()
+        _check(lib.sknet3d_context(self._h, C.byref(v)))
+        return v.value
+
+    def infer_shapes(self, dz, h, w):
+        """[(maps, depth, height, width)] for the input volume and every layer's output."""
+        out = (C.c_int32 * (4 * (len(self.layers) + 1)))()
+        _check(lib.sknet3d_infer_shapes(self._h, dz, h, w, out))
+        return [tuple(out[4 * i:4 * i + 4]) for i in range(len(self.layers) + 1)]
+
+    def num_convs(self):
+        c = C.c_int32()
+        _check(lib.sknet3d_num_convs(self._h, C.byref(c)))
+        return c.value
+
+    def conv_shape(self, conv_idx):
+        s = (C.c_int32 * 5)()
+        _check(lib.sknet3d_conv_shape(self._h, conv_idx, s))
+        return tuple(s)
+
+    def set_weights(self, conv_idx, w, b=None):
+        shape = self.conv_shape(conv_idx)
+        w, wp = _f32(w)
+        if w.shape != shape:
+            raise ValueError("conv %d expects weights %s, got %s" % (conv_idx, shape, w.shape))
+        if b is not None:
+            b, bp = _f32(b)
+            if b.shape != (shape[0],):
+                raise ValueError("conv %d expects %d biases" % (conv_idx, shape[0]))
+        else:
+            bp = None
+        _check(lib.sknet3d_set_weights(self._h, conv_idx, wp, bp))
+
+    def plan(self, dz, h, w, keep=False):
+        _check(lib.sknet3d_plan(self._h, dz, h, w, 2 if keep else 0))
+        self._plan = (dz, h, w)
+        self._shapes = self.infer_shapes(dz, h, w)
+
+    def out_shape(self):
+        """(depth, classes, height, width) of the probabilities."""
+        c, dz, h, w = self._shapes[-1]
+        return (dz, c, h, w)
+
+    def forward(self, volume, prob=None, stream=None):
+        dz, h, w = self._plan
+        if tuple(volume.shape) != (dz, self.c_in, h, w):
+            raise ValueError("volume shape %s does not match the plan %s" % (tuple(volume.shape), (dz, self.c_in, h, w)))
+        if prob is None:
+            prob = torch.empty(self.out_shape(), dtype=torch.float32, device=volume.device)
+        elif tuple(prob.shape) != self.out_shape():
+            raise ValueError("prob shape %s does not match %s" % (tuple(prob.shape), self.out_shape()))
+        _check(lib.sknet3d_forward(self._h, _dev_ptr(volume, torch.float32, "volume"),
+                                   _dev_ptr(prob, torch.float32, "prob"), _stream(stream)))
+        return prob
+
+    def get_activation(self, layer_idx):
+        """Output of layer layer_idx as a numpy array [depth, maps, height, width]."""
+        c, dz, h, w = self._shapes[layer_idx + 1]
+        out = np.empty((dz, c, h, w), np.float32)
+        _check(lib.sknet3d_get_activation(self._h, layer_idx, out.ctypes.data_as(_fp)))
+        return out

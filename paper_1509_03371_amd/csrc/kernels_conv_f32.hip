@@ -54,7 +54,9 @@ __device__ __forceinline__ void store_outputs(const ConvF32Args &a, floatx4 (&ac
     __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0): the bias is in registers from here on
     __builtin_amdgcn_sched_barrier(0);
     const long oplane = (long)a.OH * a.OW;
-    auto store_tiles = [&](auto masked) {
+    // mode 0: plain store; 1: ReLU-derivative mask; 2: the value already in y is added before bias and ReLU
+    auto store_tiles = [&](auto mode) {
+        constexpr int MODE = decltype(mode)::value;
 #pragma unroll
         for (int rw = 0; rw < RW; ++rw) {
             const int oy = oy_first + rw * d;
@@ -66,7 +68,8 @@ __device__ __forceinline__ void store_outputs(const ConvF32Args &a, floatx4 (&ac
                 if (ox >= a.Wo) continue;
                 const long pbase = rowbase + (long)ox * a.ox_mul;
                 float mk[NT][4];
-                if constexpr (decltype(masked)::value) {
+                if constexpr (MODE != 0) {
+                    const float *side = MODE == 1 ? a.mask : a.y;
 #pragma unroll
                     for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
@@ -74,7 +77,7 @@ __device__ __forceinline__ void store_outputs(const ConvF32Args &a, floatx4 (&ac
                             // maps beyond c_out are never stored; their mask address is clamped to
                             // map 0 of the same pixel so that the load stays inside the tensor
                             const int oo = nt * 16 + r4;
-                            mk[nt][r4] = a.mask[pbase + (o_first + oo < a.c_out ? oo : -o_first) * oplane];
+                            mk[nt][r4] = side[pbase + (o_first + oo < a.c_out ? oo : -o_first) * oplane];
                         }
                 }
 #pragma unroll
@@ -84,8 +87,9 @@ __device__ __forceinline__ void store_outputs(const ConvF32Args &a, floatx4 (&ac
                         const int oo = nt * 16 + r4;
                         if (o_first + oo >= a.c_out) continue;
                         float v = acc[rw][xt][nt][r4] + bia[nt][r4];
+                        if constexpr (MODE == 2) v += mk[nt][r4];
                         if (a.relu) v = v > 0.f ? v : 0.f;
-                        if constexpr (decltype(masked)::value)
+                        if constexpr (MODE == 1)
                             if (!(mk[nt][r4] > 0.f)) v = 0.f;
                         a.y[pbase + oo * oplane] = v;
                     }
@@ -121,8 +125,9 @@ __device__ __forceinline__ void store_outputs(const ConvF32Args &a, floatx4 (&ac
         }
     };
     if (a.tap_maps > 0) store_taps();
-    else if (a.mask) store_tiles(std::true_type{});
-    else store_tiles(std::false_type{});
+    else if (a.mask) store_tiles(std::integral_constant<int, 1>{});
+    else if (a.accumulate) store_tiles(std::integral_constant<int, 2>{});
+    else store_tiles(std::integral_constant<int, 0>{});
 }
 
 template <int NT, int RW>
@@ -171,7 +176,7 @@ __global__ __launch_bounds__(256) void conv_f32_kernel(ConvF32Args a, int tiles_
             for (int nt = 0; nt < NT; ++nt) acc[rw][xt][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
 
     const long plane = (long)a.H * a.W;
-    const float *xb = a.x + (long)b * a.c_in * plane;
+    const float *xb = a.x + (long)b * (a.x_bstride ? a.x_bstride : (long)a.c_in * plane);
     const int c_pad = (a.c_in + CONV_CC - 1) / CONV_CC * CONV_CC;
 
     for (int c0 = 0; c0 < c_pad; c0 += CONV_CC) {
@@ -345,7 +350,7 @@ __global__ __launch_bounds__(256) void conv_f32_pf_kernel(ConvF32Args a, int til
             for (int nt = 0; nt < NT; ++nt) acc[rw][xt][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
 
     const long plane = (long)a.H * a.W;
-    const float *xb = a.x + (long)b * a.c_in * plane;
+    const float *xb = a.x + (long)b * (a.x_bstride ? a.x_bstride : (long)a.c_in * plane);
     const int nchunks = (a.c_in + CC - 1) / CC;
     const int gy0 = py + d * (ty * R) - a.in_off;       // input row of tile row 0
     const int gx0 = x0 - a.in_off + lane;                // input column of this lane, column group 0
@@ -651,8 +656,10 @@ hipError_t launch_conv_f32(const ConvF32Args &a, hipStream_t stream)
         return hipErrorInvalidValue;
     if (a.tap_maps != 0 && (a.tap_maps < 16 || a.tap_maps % 16 != 0 || a.c_out != 4 * a.tap_maps || a.mask || a.oy_mul != 2 || a.ox_mul != 2))
         return hipErrorInvalidValue;
+    if (a.accumulate && (a.mask || a.tap_maps != 0)) return hipErrorInvalidValue;
+    if (a.x_bstride < 0) return hipErrorInvalidValue;
     // a single input map, plain forward placement (contiguous NCHW output, no mask)
-    if (a.c_in == 1 && a.in_off == 0 && !a.mask && a.OH == a.Ho && a.OW == a.Wo && a.oy_mul == 1 && a.ox_mul == 1 &&
+    if (a.c_in == 1 && a.in_off == 0 && !a.mask && !a.accumulate && a.x_bstride == 0 && a.OH == a.Ho && a.OW == a.Wo && a.oy_mul == 1 && a.ox_mul == 1 &&
         a.oy_off == 0 && a.ox_off == 0 && a.Ho == a.H - (a.k - 1) * a.d && a.Wo == a.W - (a.k - 1) * a.d && a.n_pad <= 512) {
         if (a.k == 3) return launch_conv_c1_f32<3>(a, stream);
         if (a.k == 4) return launch_conv_c1_f32<4>(a, stream);

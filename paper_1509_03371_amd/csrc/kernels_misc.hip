@@ -147,6 +147,86 @@ hipError_t launch_maxpool_f32(const float *x, float *y, uint8_t *tap, int planes
     return hipGetLastError();
 }
 
+// ---- 3-D max pooling with kernel stride d and layer stride s on the slice-major layout (Section 5.2.2) ----
+// X[D][C][H][W] -> Y[Do][C][Ho][Wo], Y[z,c,y,x] = max_{a,i,j<k} X[s*z + a*d, c, s*y + i*d, s*x + j*d].
+// grid: x = (output slice, column block), y = output row, z = map
+__global__ void __launch_bounds__(256) maxpool3d_f32_kernel(const float *__restrict__ x, float *__restrict__ y, int C, int H, int W,
+                                                            int Ho, int Wo, int k, int d, int s, int xblocks)
+{
+    const int zo = blockIdx.x / xblocks, xb = blockIdx.x - zo * xblocks;
+    const int xx = xb * 256 + threadIdx.x, yy = blockIdx.y, c = blockIdx.z;
+    if (xx >= Wo) return;
+    const long plane = (long)H * W;
+    const float *src = x + (((long)s * zo * C + c) * H + (long)s * yy) * W + (long)s * xx;
+    float best = src[0];
+    for (int a = 0; a < k; ++a) {
+        const float *sl = src + (long)a * d * C * plane;
+        for (int i = 0; i < k; ++i)
+            for (int j = 0; j < k; ++j) {
+                const float v = sl[(long)i * d * W + j * d];
+                best = v > best ? v : best;
+            }
+    }
+    y[(((long)zo * C + c) * Ho + yy) * Wo + xx] = best;
+}
+
+// k = 2, s = 1 (the SK pools of a converted net): a thread owns one output column of one map and walks down
+// the slices z0, z0 + d, z0 + 2d, ... of one residue class mod d.  The 2x2 in-slice maximum q[z] of slice z
+// serves the windows of the outputs z - d and z, so each is formed once: four loads per output, not eight.
+// grid: x = (residue class and chain segment, column block), y = output row, z = map
+__global__ void __launch_bounds__(256) maxpool3d_k2_chain_f32_kernel(const float *__restrict__ x, float *__restrict__ y, int C,
+                                                                     int H, int W, int Do, int Ho, int Wo, int d, int M,
+                                                                     int nseg, int xblocks)
+{
+    const int chain = blockIdx.x / xblocks, xb = blockIdx.x - chain * xblocks;
+    const int phase = chain / nseg, seg = chain - phase * nseg;
+    const int xx = xb * 256 + threadIdx.x, yy = blockIdx.y, c = blockIdx.z;
+    if (xx >= Wo || phase >= Do) return;
+    const int links = (Do - phase + d - 1) / d;
+    const int m0 = seg * M, m1 = min(links, m0 + M);
+    if (m0 >= m1) return;
+    const long plane = (long)H * W, zstep = (long)d * C * plane, ostep = (long)d * C * Ho * Wo;
+    const float *src = x + (((long)(phase + m0 * d) * C + c) * H + yy) * W + xx;
+    float *dst = y + (((long)(phase + m0 * d) * C + c) * Ho + yy) * Wo + xx;
+    const long dn = (long)d * W;
+    auto quad = [&](const float *p) {
+        const float a = p[0], b = p[d], e = p[dn], f = p[dn + d];
+        const float ab = b > a ? b : a, ef = f > e ? f : e;
+        return ef > ab ? ef : ab;
+    };
+    float q = quad(src);
+    for (int m = m0; m < m1; ++m) {
+        src += zstep;
+        const float q2 = quad(src);
+        *dst = q2 > q ? q2 : q;
+        dst += ostep;
+        q = q2;
+    }
+}
+
+hipError_t launch_maxpool3d_f32(const float *x, float *y, int C, int D, int H, int W, int Do, int Ho, int Wo, int k, int d, int s,
+                                hipStream_t stream)
+{
+    if (C < 1 || C > 65535 || Ho < 1 || Ho > 65535 || Do < 1 || Wo < 1) return hipErrorInvalidValue;
+    if ((long)s * (Do - 1) + (long)(k - 1) * d >= D || (long)s * (Ho - 1) + (long)(k - 1) * d >= H ||
+        (long)s * (Wo - 1) + (long)(k - 1) * d >= W)
+        return hipErrorInvalidValue;
+    const int xblocks = (Wo + 255) / 256;
+    if (k == 2 && s == 1) {
+        const int M = 16, links = (Do + d - 1) / d, nseg = (links + M - 1) / M;
+        const long gx = (long)d * nseg * xblocks;
+        if (gx <= 0x7fffffffL) {
+            hipLaunchKernelGGL(maxpool3d_k2_chain_f32_kernel, dim3((unsigned)gx, Ho, C), dim3(256), 0, stream, x, y, C, H, W, Do, Ho,
+                               Wo, d, M, nseg, xblocks);
+            return hipGetLastError();
+        }
+    }
+    if ((long)Do * xblocks > 0x7fffffffL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(maxpool3d_f32_kernel, dim3((unsigned)(Do * xblocks), Ho, C), dim3(256), 0, stream, x, y, C, H, W, Ho, Wo, k, d,
+                       s, xblocks);
+    return hipGetLastError();
+}
+
 // Gather form of the pool gradient: input sample (u, v) can only have won the windows whose
 // output sits at (u - i*d, v - j*d); it collects dY from those whose recorded tap is (i, j).
 // No atomics, so the result does not depend on scheduling.

@@ -29,6 +29,12 @@ struct ConvF32Args {
     // tap_maps > 0 (a multiple of 16): GEMM map o is tap t = o / tap_maps of real map o % tap_maps and is stored at
     // (y*oy_mul + t/2, x*ox_mul + t%2) -- the four taps of a 2x2 stride-2 up-convolution as one 1x1 convolution
     int tap_maps;
+    // accumulate != 0: the value that y holds is added to the sum before bias and ReLU (a convolution split into
+    // several launches over parts of its input maps); not with mask or tap_maps
+    int accumulate;
+    // distance in floats between the inputs of consecutive images; 0 = c_in*H*W (images may overlap: a 3-D
+    // convolution reads a window of consecutive slices as the maps of one image)
+    long x_bstride;
 };
 hipError_t launch_conv_f32(const ConvF32Args &a, hipStream_t stream);
 
@@ -135,6 +141,9 @@ hipError_t launch_maxpool_f32(const float *x, float *y, uint8_t *tap, int planes
 hipError_t launch_maxpool_bwd_f32(const float *dy, const uint8_t *tap, const float *relu_src,
                                   float *dx, int planes, int H, int W, int Ho, int Wo, int k, int d,
                                   hipStream_t stream);
+// 3-D pool on the slice-major layout X[D][C][H][W] -> Y[Do][C][Ho][Wo]; k, d, s act on the three axes alike
+hipError_t launch_maxpool3d_f32(const float *x, float *y, int C, int D, int H, int W, int Do, int Ho, int Wo, int k, int d, int s,
+                                hipStream_t stream);
 hipError_t launch_softmax_f32(const float *z, float *p, int n, int classes, int hw, hipStream_t stream);
 // loss = -(1/P) sum log p_label, dz = (p - onehot)/P over the pixels whose label lies in 0..classes-1;
 // any other label value (-1 by convention) masks the pixel (no loss, zero gradient) and P counts the

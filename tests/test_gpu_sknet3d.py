@@ -1,0 +1,134 @@
+"""GPU parity: 3-D SK net forward (Section 5.2.2) through the C ABI against the fp64 CPU oracle.
+The library's volumes are slice-major [depth][maps][height][width]; the oracle's are [maps][depth][height][width]."""
+import numpy as np
+import pytest
+import torch
+
+import sk_synth as S
+from oracle import nd as OND
+
+pytestmark = pytest.mark.gpu
+
+FP32_TOL = 1e-4     # fp32 storage and fp32 MFMA accumulation against fp64, relative to the layer's largest value
+
+
+def relerr(got, ref):
+    return float(np.abs(got.astype(np.float64) - ref).max() / max(np.abs(ref).max(), 1e-30))
+
+
+def make_net(layers, c_in, classes, seed, bias_scale=0.1):
+    from paper_1509_03371_amd import binding as B
+    ws, bs = S.he_normal_weights3d(layers, c_in, seed, bias_scale=bias_scale)
+    net = B.SKNet3D(layers, c_in, classes)
+    assert net.num_convs() == len(ws)
+    for i, (w, b) in enumerate(zip(ws, bs)):
+        assert net.conv_shape(i) == w.shape
+        net.set_weights(i, w, b)
+    return net, ws, bs
+
+
+def check_layers(layers, c_in, classes, size, seed, tol=FP32_TOL):
+    """Every layer's output and the probabilities of a plan that keeps them, against the oracle."""
+    net, ws, bs = make_net(layers, c_in, classes, seed)
+    dz, h, w = size
+    vol = S.uniform_volume(c_in, dz, h, w, seed + 1) - 0.3
+    net.plan(dz, h, w, keep=True)
+    shapes = net.infer_shapes(dz, h, w)
+    dev = torch.from_numpy(np.ascontiguousarray(vol.transpose(1, 0, 2, 3))).cuda()
+    prob = net.forward(dev).cpu().numpy()
+    ref, acts = OND.sknet3d_forward(vol, layers, ws, bs, keep=True)
+    for i in range(len(layers)):
+        got = net.get_activation(i).transpose(1, 0, 2, 3)
+        assert got.shape == acts[i + 1].shape == shapes[i + 1], i
+        e = relerr(got, acts[i + 1])
+        print("sk3d layer %d %s %s rel err %.3e" % (i, layers[i]["type"], got.shape, e), flush=True)
+        if layers[i]["type"] == "pool":
+            # a pool only selects: its output equals the maximum of the library's own input exactly
+            src = vol if i == 0 else net.get_activation(i - 1).transpose(1, 0, 2, 3)
+            np.testing.assert_array_equal(got, OND.maxpool_sk3d(src, layers[i]["k"], layers[i]["d"], layers[i].get("s", 1)).astype(np.float32))
+        assert e <= tol, (i, e)
+    assert np.abs(prob.transpose(1, 0, 2, 3) - ref).max() <= tol
+    net.close()
+    return prob
+
+
+def test_converted_net_layer_by_layer_ragged_volume():
+    # the Algorithm-1 conversion of the 18^3 sliding-window net (context 17): d = 1 (one launch with k*C maps),
+    # d = 2 and 4 (a launch per depth tap, accumulated); output 5 x 21 x 70 spans two column tiles with a ragged tail
+    layers = S.sknet3d_layers(classes=3, maps=(8, 12, 24, 20))
+    prob = check_layers(layers, 2, 3, (22, 38, 87), 500)
+    assert prob.shape == (5, 3, 21, 70)
+
+
+def test_single_input_map_and_odd_map_counts():
+    layers = [S.conv(5, 2, 1), S.pool(2, 1), S.conv(7, 2, 2), S.pool(2, 2), S.conv(9, 3, 4), S.conv(2, 1, 1, relu=False)]
+    prob = check_layers(layers, 1, 2, (17, 30, 41), 510)
+    assert prob.shape == (3, 2, 16, 27)
+
+
+def test_general_pools_and_downsampling_pool():
+    # a 3^3 pool with kernel stride 2 and a down-sampling pool (s = k) take the general kernel
+    layers = [S.conv(6, 3, 1), S.pool(3, 2), S.conv(8, 2, 1), S.pool(2, 1, 2), S.conv(4, 2, 1), S.conv(2, 1, 1, relu=False)]
+    prob = check_layers(layers, 2, 2, (15, 21, 27), 520)
+    assert prob.shape == (3, 2, 6, 9)
+
+
+def test_fused_head_plan_matches_oracle():
+    # an inference plan runs "1x1x1 conv + ReLU, 1x1x1 conv, softmax" as one kernel
+    from paper_1509_03371_amd import binding as B
+    layers = S.sknet3d_layers(classes=2, maps=(8, 16, 32, 24))
+    net, ws, bs = make_net(layers, 1, 2, 530)
+    vol = S.em_like_volume(25, 49, 60, 531)
+    net.plan(25, 49, 60)
+    prob = net.forward(torch.from_numpy(np.ascontiguousarray(vol.transpose(1, 0, 2, 3))).cuda()).cpu().numpy()
+    ref = OND.sknet3d_forward(vol, layers, ws, bs)
+    assert prob.shape == (8, 2, 32, 43)
+    assert np.abs(prob.transpose(1, 0, 2, 3) - ref).max() <= FP32_TOL
+    with pytest.raises(B.SknetError) as e:
+        net.get_activation(len(layers) - 1)
+    assert e.value.status_name == "SK_ESTATE"
+    assert relerr(net.get_activation(4).transpose(1, 0, 2, 3), OND.sknet3d_forward(vol, layers, ws, bs, keep=True)[1][5]) <= FP32_TOL
+    # new weights after the plan reach the device copies, the packed head included
+    ws2, bs2 = S.he_normal_weights3d(layers, 1, 532, bias_scale=0.1)
+    for i, (w, b) in enumerate(zip(ws2, bs2)):
+        net.set_weights(i, w, b)
+    prob2 = net.forward(torch.from_numpy(np.ascontiguousarray(vol.transpose(1, 0, 2, 3))).cuda()).cpu().numpy()
+    assert np.abs(prob2.transpose(1, 0, 2, 3) - OND.sknet3d_forward(vol, layers, ws2, bs2)).max() <= FP32_TOL
+    net.close()
+
+
+def test_benchmark_volume_sampled_against_oracle():
+    # the benchmark's configuration and launch shapes (81 x 145 x 145 in, 64 x 128 x 128 out); the oracle
+    # recomputes 2 x 2 x 2 output blocks from their own (2 + v)^3 input windows, corners and interior
+    layers = S.sknet3d_layers(classes=2)
+    net, ws, bs = make_net(layers, 1, 2, 1100, bias_scale=0.0)
+    v = net.context()
+    assert v == 17
+    dz, h, w = 64 + v, 128 + v, 128 + v
+    vol = S.em_like_volume(dz, h, w, 1101)
+    net.plan(dz, h, w)
+    prob = net.forward(torch.from_numpy(np.ascontiguousarray(vol.transpose(1, 0, 2, 3))).cuda()).cpu().numpy()
+    assert prob.shape == (64, 2, 128, 128)
+    assert np.abs(prob.sum(axis=1) - 1.0).max() <= 1e-5
+    for (z, y, x) in [(0, 0, 0), (62, 126, 126), (31, 64, 63), (5, 126, 17), (62, 0, 100)]:
+        ref = OND.sknet3d_forward(vol[:, z:z + 2 + v, y:y + 2 + v, x:x + 2 + v], layers, ws, bs)
+        got = prob[z:z + 2, :, y:y + 2, x:x + 2].transpose(1, 0, 2, 3)
+        assert np.abs(got - ref).max() <= FP32_TOL, (z, y, x)
+    net.close()
+
+
+def test_errors_reach_the_caller():
+    from paper_1509_03371_amd import binding as B
+    layers = S.sknet3d_layers(classes=2, maps=(4, 4, 8, 4))
+    net, _, _ = make_net(layers, 1, 2, 540)
+    vol = torch.zeros((20, 1, 20, 20), device="cuda")
+    with pytest.raises(B.SknetError) as e:
+        B._check(B.lib.sknet3d_forward(net._h, B.C.c_void_p(vol.data_ptr()), B.C.c_void_p(vol.data_ptr()), None))
+    assert e.value.status_name == "SK_ESTATE"
+    with pytest.raises(B.SknetError) as e:
+        net.plan(17, 40, 40)          # depth 17 leaves no output slice
+    assert e.value.status_name == "SK_ESHAPE"
+    net.plan(20, 20, 20)
+    with pytest.raises(ValueError):
+        net.forward(torch.zeros((20, 1, 20, 21), device="cuda"))
+    net.close()

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "sknet.h")).read()
-    declared = set(re.findall(r"\b((?:sknet|unet|usknet|sk_probe)_[a-z_0-9]+)\s*\(", header))
+    declared = set(re.findall(r"\b((?:sknet3d|sknet|unet|usknet|sk_probe)_[a-z_0-9]+)\s*\(", header))
     assert declared, "no declarations found"
     for name in declared:
         assert hasattr(B.lib, name), name
@@ -148,3 +148,35 @@ def test_unet_training_plan_is_fp32_only():
         net.plan(1, 60, 60, training=True)      # refused before anything is allocated
     assert e.value.status_name == "SK_EUNSUPPORTED"
     net.close()
+
+
+def test_sknet3d_handle_host_logic():
+    # shapes, context and refusals of the 3-D handle; no GPU call is made
+    layers = S.sknet3d_layers(classes=2)
+    net = B.SKNet3D(layers, 1, 2)
+    assert net.context() == 17 and net.num_convs() == 5
+    assert net.conv_shape(0) == (16, 1, 3, 3, 3) and net.conv_shape(2) == (128, 32, 3, 3, 3) and net.conv_shape(4) == (2, 64, 1, 1, 1)
+    shapes = net.infer_shapes(81, 145, 100)
+    assert shapes[0] == (1, 81, 145, 100) and shapes[1] == (16, 79, 143, 98) and shapes[2] == (16, 78, 142, 97)
+    assert shapes[3] == (32, 74, 138, 93) and shapes[4] == (32, 72, 136, 91) and shapes[-1] == (2, 64, 128, 83)
+    with pytest.raises(B.SknetError) as e:
+        net.infer_shapes(81, 17, 145)
+    assert e.value.status_name == "SK_ESHAPE"
+    with pytest.raises(ValueError):
+        net.set_weights(0, np.zeros((16, 1, 3, 3), np.float32))
+    net.close()
+    with pytest.raises(B.SknetError) as e:
+        B.SKNet3D(layers, 1, 3)                  # the last layer has 2 maps
+    assert e.value.status_name == "SK_ESHAPE"
+    with pytest.raises(B.SknetError) as e:
+        B.SKNet3D([S.pool(2, 2, 2), S.conv(2, 1, 1, relu=False)], 1, 2)   # a down-sampling pool with d != 1
+    assert e.value.status_name == "SK_ESHAPE"
+    down = B.SKNet3D([S.conv(4, 3, 1), S.pool(2, 1, 2), S.conv(2, 1, 1, relu=False)], 1, 2)
+    assert down.infer_shapes(10, 12, 14)[-1] == (2, 4, 5, 6)
+    with pytest.raises(B.SknetError) as e:
+        down.infer_shapes(11, 12, 14)
+    assert e.value.status_name == "SK_ESHAPE"
+    with pytest.raises(B.SknetError) as e:
+        down.context()
+    assert e.value.status_name == "SK_ESHAPE"
+    down.close()
