@@ -231,6 +231,7 @@ static hipError_t launch_conv_f32_t(const ConvF32Args &a, hipStream_t stream)
 {
     constexpr int R = 4 * RW, WN = NT * 16;
     const int k = a.k, d = a.d;
+    if (a.grp_maps != 0) return hipErrorInvalidValue;       // grouped input maps: only the kernels below
     const int RR = R + k - 1, PW = CONV_TX + (k - 1) * d;
     const int KC = CONV_CC * k * k;
     const size_t smem = sizeof(float) * ((size_t)CONV_CC * RR * PW + (size_t)KC * WN) + sizeof(int) * KC;
@@ -390,12 +391,17 @@ __global__ __launch_bounds__(256) void conv_f32_pf_kernel(ConvF32Args a, int til
         woff[u] = 4u * (unsigned)(r * a.n_pad + col);
     }
     const int xs_thread = wave * RR * PITCH + lane;
+    // input maps in groups of grp_maps (a multiple of CC) with grp_skip more floats between groups: chunks are
+    // prefetched in order, so the skip that applies is kept as a running sum instead of a division per chunk
+    const int grp_chunks = a.grp_maps > 0 ? a.grp_maps / CC : 0x7fffffff;
+    int pf_left = grp_chunks;
+    long pf_skip = 0;
     auto prefetch = [&](int chunk) {
 #pragma unroll
         for (int cw = 0; cw < CPW; ++cw) {
             int c = chunk * CC + wave + 4 * cw;
             c = c < a.c_in ? c : a.c_in - 1;
-            const float *src = xb + (long)c * plane;
+            const float *src = xb + pf_skip + (long)c * plane;
 #pragma unroll
             for (int t = 0; t < RR; ++t) {
                 const char *row = reinterpret_cast<const char *>(src + roff[t]);
@@ -406,6 +412,10 @@ __global__ __launch_bounds__(256) void conv_f32_pf_kernel(ConvF32Args a, int til
         const char *slab = reinterpret_cast<const char *>(a.wp + (long)chunk * KC * a.n_pad);
 #pragma unroll
         for (int u = 0; u < WV4; ++u) wr[u] = *reinterpret_cast<const floatx4 *>(slab + woff[u]);
+        if (--pf_left == 0) {
+            pf_left = grp_chunks;
+            pf_skip += a.grp_skip;
+        }
     };
     auto commit = [&](int chunk) {
 #pragma unroll
@@ -487,6 +497,7 @@ static hipError_t launch_conv_f32_pf_z(const ConvF32Args &a, hipStream_t stream)
 {
     constexpr int R = 4 * RW, WN = NT * 16, RR = R + KS - 1, KC = CC * KS * KS, PITCH = 64 * NCG;
     if (CONV_TX + (KS - 1) * a.d > PITCH) return hipErrorInvalidValue;
+    if (a.grp_maps != 0 && (a.grp_maps < 0 || a.grp_maps % CC != 0 || a.c_in % a.grp_maps != 0 || a.grp_skip < 0)) return hipErrorInvalidValue;
     if ((long)a.H * a.W >= (1L << 29)) return hipErrorInvalidValue;     // 32-bit byte offsets inside a map
     if ((long)KC * a.n_pad >= (1L << 29)) return hipErrorInvalidValue;  // and inside a weight slab
     const size_t smem = sizeof(float) * ((size_t)CC * RR * PITCH + (size_t)KC * WN);
@@ -650,6 +661,14 @@ static hipError_t launch_conv_c1_f32(const ConvF32Args &a, hipStream_t stream)
     return hipGetLastError();
 }
 
+// grp_maps is accepted for the kernel sizes with a prefetching specialisation when it is a multiple of the
+// largest K chunk (16 maps)
+bool conv_f32_groups_supported(int k, int d, int grp_maps)
+{
+    const int halo = (k - 1) * d;
+    return grp_maps > 0 && grp_maps % 16 == 0 && (k == 1 || ((k == 3 || k == 4 || k == 6 || k == 8) && halo <= 64));
+}
+
 hipError_t launch_conv_f32(const ConvF32Args &a, hipStream_t stream)
 {
     if (a.n_pad % 16 != 0 || a.c_out > a.n_pad || a.k < 1 || a.d < 1 || a.Ho < 1 || a.Wo < 1)
@@ -659,7 +678,7 @@ hipError_t launch_conv_f32(const ConvF32Args &a, hipStream_t stream)
     if (a.accumulate && (a.mask || a.tap_maps != 0)) return hipErrorInvalidValue;
     if (a.x_bstride < 0) return hipErrorInvalidValue;
     // a single input map, plain forward placement (contiguous NCHW output, no mask)
-    if (a.c_in == 1 && a.in_off == 0 && !a.mask && !a.accumulate && a.x_bstride == 0 && a.OH == a.Ho && a.OW == a.Wo && a.oy_mul == 1 && a.ox_mul == 1 &&
+    if (a.c_in == 1 && a.in_off == 0 && !a.mask && !a.accumulate && a.x_bstride == 0 && a.grp_maps == 0 && a.OH == a.Ho && a.OW == a.Wo && a.oy_mul == 1 && a.ox_mul == 1 &&
         a.oy_off == 0 && a.ox_off == 0 && a.Ho == a.H - (a.k - 1) * a.d && a.Wo == a.W - (a.k - 1) * a.d && a.n_pad <= 512) {
         if (a.k == 3) return launch_conv_c1_f32<3>(a, stream);
         if (a.k == 4) return launch_conv_c1_f32<4>(a, stream);

@@ -35,7 +35,13 @@ struct ConvF32Args {
     // distance in floats between the inputs of consecutive images; 0 = c_in*H*W (images may overlap: a 3-D
     // convolution reads a window of consecutive slices as the maps of one image)
     long x_bstride;
+    // grp_maps > 0: the input maps of an image come in groups of grp_maps consecutive planes with grp_skip more
+    // floats between one group and the next (the depth taps of a 3-D convolution with kernel stride > 1: a tap's
+    // maps are one slice, the next tap's slice lies d slices on); see conv_f32_groups_supported
+    int grp_maps;
+    long grp_skip;
 };
+bool conv_f32_groups_supported(int k, int d, int grp_maps);
 hipError_t launch_conv_f32(const ConvF32Args &a, hipStream_t stream);
 
 // Pack OIHW fp32 master weights [c_out][c_in][k][k] into the K-major layout launch_conv_f32 reads.

@@ -6,8 +6,9 @@
 // (depth tap a, map c) pairs, found in slice z + a*d.  The output slices form the "images" of one 2-D launch
 // (consecutive output slices read overlapping windows of input slices, so the image stride is one slice):
 //   d = 1 or k = 1: the k tapped slices are adjacent in memory, i.e. one 2-D convolution with k*C input maps;
-//   d > 1: one launch per depth tap, each adding to what the previous ones left in the output, the last one
-//          applying bias and ReLU.
+//   d > 1, C a multiple of 16: still one launch; the kernel steps over the d - 1 slices between two taps;
+//   d > 1 otherwise: one launch per depth tap, each adding to what the previous ones left in the output, the
+//          last one applying bias and ReLU.
 // The 2-D kernels are used unchanged; nothing here is a separate 3-D multiplication.
 #include <hip/hip_runtime.h>
 
@@ -134,6 +135,10 @@ sk_status run_layer3(sknet3d *net, int li, hipStream_t stream)
         a.bias = last ? run.p.b_dev : nullptr;
         a.accumulate = r > 0 ? 1 : 0;
         a.x_bstride = slice;
+        if (run.len > 1 && l.d > 1) {
+            a.grp_maps = in.c;
+            a.grp_skip = (long)(l.d - 1) * slice;
+        }
         SK_HIP(sk::launch_conv_f32(a, stream));
     }
     return SK_OK;
@@ -172,7 +177,9 @@ sk_status sknet3d_create(const sk_layer *layers, int32_t n_layers, int32_t c_in,
             c.c_in = maps; c.c_out = l.c_out; c.k = l.k; c.d = l.d;
             c.w.assign((size_t)c.wcount(), 0.f);
             c.b.assign((size_t)c.c_out, 0.f);
-            const bool adjacent = l.d == 1 || l.k == 1;   // tapped slices adjacent in memory: one run
+            // one run when the tapped slices are adjacent in memory, or the kernel can step over the d - 1
+            // slices between two taps
+            const bool adjacent = l.d == 1 || l.k == 1 || sk::conv_f32_groups_supported(l.k, l.d, maps);
             for (int a0 = 0; a0 < l.k; a0 += adjacent ? l.k : 1) {
                 TapRun r;
                 r.a0 = a0; r.len = adjacent ? l.k : 1;

@@ -60,6 +60,13 @@ def test_converted_net_layer_by_layer_ragged_volume():
     assert prob.shape == (5, 3, 21, 70)
 
 
+def test_depth_taps_in_one_launch_for_multiples_of_sixteen_maps():
+    # 16 and 32 input maps at d = 2 and 4: the kernel steps over the slices between two depth taps
+    layers = [S.conv(16, 3, 1), S.pool(2, 1), S.conv(32, 3, 2), S.pool(2, 2), S.conv(24, 4, 4), S.conv(2, 1, 1, relu=False)]
+    prob = check_layers(layers, 1, 2, (24, 29, 83), 505)
+    assert prob.shape == (3, 2, 8, 62)
+
+
 def test_single_input_map_and_odd_map_counts():
     layers = [S.conv(5, 2, 1), S.pool(2, 1), S.conv(7, 2, 2), S.pool(2, 2), S.conv(9, 3, 4), S.conv(2, 1, 1, relu=False)]
     prob = check_layers(layers, 1, 2, (17, 30, 41), 510)
