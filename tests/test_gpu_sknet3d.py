@@ -36,7 +36,7 @@ def check_layers(layers, c_in, classes, size, seed, tol=FP32_TOL):
     shapes = net.infer_shapes(dz, h, w)
     dev = torch.from_numpy(np.ascontiguousarray(vol.transpose(1, 0, 2, 3))).cuda()
     prob = net.forward(dev).cpu().numpy()
-    ref, acts = OND.sknet3d_forward(vol, layers, ws, bs, keep=True)
+    ref, acts, _ = OND.sknet3d_forward(vol, layers, ws, bs, keep=True)
     for i in range(len(layers)):
         got = net.get_activation(i).transpose(1, 0, 2, 3)
         assert got.shape == acts[i + 1].shape == shapes[i + 1], i

@@ -106,7 +106,7 @@ def test_sk3d_equals_sliding_window_voxel_by_voxel():
     bs = [b.astype(np.float64) for b in bs]
     out = (2, 3, 2)
     vol = np.random.default_rng(12).standard_normal((2, out[0] + v, out[1] + v, out[2] + v))
-    prob, acts = nd.sknet3d_forward(vol, sk, ws, bs, keep=True)
+    prob, acts, _ = nd.sknet3d_forward(vol, sk, ws, bs, keep=True)
     scores = acts[-1]
     assert scores.shape == (2,) + out
     for z in range(out[0]):
@@ -125,3 +125,75 @@ def test_size_errors():
         nd.conv_sk3d(np.zeros((1, 4, 9, 9)), np.zeros((1, 1, 3, 3, 3)), None, d=2)
     with pytest.raises(ValueError):
         nd.maxpool_sk3d(np.zeros((1, 9, 2, 9)), 2, 2)
+
+
+def test_pool3d_argmax_points_at_the_first_maximum():
+    rng = np.random.default_rng(8)
+    x = rng.integers(0, 3, size=(2, 7, 8, 9)).astype(np.float64)      # many ties
+    k, d = 2, 2
+    y, arg = nd.maxpool_sk3d(x, k, d, want_argmax=True)
+    flat = x.reshape(2, -1)
+    np.testing.assert_array_equal(np.take_along_axis(flat, arg.reshape(2, -1), axis=1).reshape(y.shape), y)
+    # brute force: the first tap in (a, i, j) order that attains the maximum
+    for (m, z, yy, xx) in [(0, 0, 0, 0), (1, 4, 5, 6), (0, 2, 3, 1), (1, 1, 0, 6)]:
+        taps = [((z + a * d) * 8 + yy + i * d) * 9 + xx + j * d for a in range(k) for i in range(k) for j in range(k)]
+        vals = [flat[m, t] for t in taps]
+        assert arg[m, z, yy, xx] == taps[int(np.argmax(vals))]       # np.argmax returns the first maximum
+    # a constant volume: every window's first tap wins
+    _, arg0 = nd.maxpool_sk3d(np.ones((1, 5, 5, 5)), 2, 1, want_argmax=True)
+    assert arg0[0, 1, 2, 3] == (1 * 5 + 2) * 5 + 3
+
+
+def _torch_net(vol, layers, ws, bs):
+    x, wi = vol[None], 0
+    for lay in layers:
+        if lay["type"] == "conv":
+            x = F.conv3d(x, ws[wi], bs[wi], dilation=lay["d"])
+            if lay.get("relu", False):
+                x = F.relu(x)
+            wi += 1
+        else:
+            x = F.max_pool3d(x, kernel_size=lay["k"], stride=lay.get("s", 1), dilation=lay["d"])
+    return x[0]
+
+
+def test_net_backward_matches_reverse_mode_differentiation_and_finite_differences():
+    layers = S.sknet3d_layers(classes=3, maps=(3, 4, 5, 4))
+    ws, bs = S.he_normal_weights3d(layers, 2, seed=21, bias_scale=0.1)
+    ws = [w.astype(np.float64) for w in ws]
+    bs = [b.astype(np.float64) for b in bs]
+    vol = np.random.default_rng(22).standard_normal((2, 19, 20, 21))
+    labels = np.random.default_rng(23).integers(-1, 3, size=(2, 3, 4))       # some voxels masked
+    prob, acts, argmaxes = nd.sknet3d_forward(vol, layers, ws, bs, keep=True)
+    loss, dws, dbs = nd.sknet3d_backward(layers, ws, acts, argmaxes, labels)
+    tw = [torch.from_numpy(w).requires_grad_(True) for w in ws]
+    tb = [torch.from_numpy(b).requires_grad_(True) for b in bs]
+    z = _torch_net(torch.from_numpy(vol), layers, tw, tb)
+    lab = torch.from_numpy(labels)
+    ref = F.cross_entropy(z[None], lab[None].long(), ignore_index=-1, reduction="mean")
+    ref.backward()
+    assert abs(loss - ref.item()) <= 1e-12 * max(1.0, abs(ref.item()))
+    for i in range(len(ws)):
+        np.testing.assert_allclose(dws[i], tw[i].grad.numpy(), rtol=1e-9, atol=1e-12)
+        np.testing.assert_allclose(dbs[i], tb[i].grad.numpy(), rtol=1e-9, atol=1e-12)
+    # central difference on one weight of the dilated middle convolution
+    idx, eps = (2, 1, 2, 0, 1), 1e-6
+    vals = []
+    for sgn in (1, -1):
+        w2 = [w.copy() for w in ws]
+        w2[1][idx] += sgn * eps
+        _, a2, _ = nd.sknet3d_forward(vol, layers, w2, bs, keep=True)
+        vals.append(nd.softmax_loss3d(a2[-1], labels)[0])
+    assert abs((vals[0] - vals[1]) / (2 * eps) - dws[1][idx]) <= 1e-6 * max(1.0, abs(dws[1][idx]))
+
+
+def test_loss3d_all_masked_and_closed_form():
+    z = np.zeros((4, 2, 2, 2))
+    loss, dz = nd.softmax_loss3d(z, np.full((2, 2, 2), -1))
+    assert loss == 0.0 and not dz.any()
+    lab = np.zeros((2, 2, 2), dtype=np.int64)
+    lab[0, 0, 0] = -1
+    loss, dz = nd.softmax_loss3d(z, lab)
+    assert abs(loss - np.log(4.0)) <= 1e-15                   # uniform scores: -log(1/4) whatever the count
+    np.testing.assert_allclose(dz[:, 1, 1, 1], np.array([0.25 - 1, 0.25, 0.25, 0.25]) / 7)
+    assert not dz[:, 0, 0, 0].any()
