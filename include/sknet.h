@@ -263,7 +263,7 @@ sk_status unet_get_activation(unet_t *net, const char *stage, float *nchw_host, 
  *   SK_CONV    : Y[o,z,y,x] = b[o] + sum_{c,a,i,j} W[o,c,a,i,j] X[c, z+a*d, y+i*d, x+j*d], optional ReLU;
  *   SK_MAXPOOL : Y[c,z,y,x] = max_{a,i,j<k} X[c, s*z+a*d, s*y+i*d, s*x+j*d]  (s = 1, or s = k with d = 1);
  * every layer shrinks each axis by (k-1)*d (Algorithm 1 holds per axis); a per-voxel softmax over the maps
- * of the last layer follows.  fp32 only, one volume per call, no padding: the caller's volume contains the
+ * of the last layer follows (forward; sknet3d_backward adds the training pass).  fp32 only, one volume per call, no padding: the caller's volume contains the
  * context v, the output is (dz - v) x (h - v) x (w - v).  Create is host only; errors as sknet_create.
  *
  * Layout of every volume that crosses this interface (input, probabilities, activations): SLICE-MAJOR,
@@ -285,14 +285,31 @@ sk_status sknet3d_conv_shape(const sknet3d_t *net, int32_t conv_idx, int32_t *sh
 sk_status sknet3d_set_weights(sknet3d_t *net, int32_t conv_idx, const float *w_host, const float *b_host);
 /* Fix the volume size and allocate the workspaces on the current HIP device (hipMalloc).  mode 0: inference,
  * a trailing "1x1x1 conv + ReLU, 1x1x1 conv, softmax" may run as one kernel (then sknet3d_get_activation
- * reports SK_ESTATE for those two layers); mode 2: every layer's output is kept.  May be called again. */
+ * reports SK_ESTATE for those two layers); mode 2: every layer's output is kept; mode 1: training -- every
+ * activation and the pools' winners are kept, gradient buffers allocated (pools must have s = 1 and k <= 6,
+ * else SK_EUNSUPPORTED).  May be called again; the current weights are kept. */
 sk_status sknet3d_plan(sknet3d_t *net, int32_t dz, int32_t h, int32_t w, int32_t mode);
 /* volume_dev: DEVICE fp32 [dz][c_in][h][w]; prob_dev: DEVICE fp32 [dz-v][n_classes][h-v][w-v] (for nets with
- * down-sampling pools: the sizes sknet3d_infer_shapes reports).  The volume must stay valid until the
- * enqueued work has run.  SK_ESTATE without a plan. */
+ * down-sampling pools: the sizes sknet3d_infer_shapes reports).  On an inference plan the volume must stay
+ * valid until the enqueued work has run; a training plan copies it.  SK_ESTATE without a plan. */
 sk_status sknet3d_forward(sknet3d_t *net, const float *volume_dev, float *prob_dev, void *hip_stream);
-/* Output of layer layer_idx (HOST fp32 [depth][maps][height][width]); synchronises. */
+/* Softmax loss and the exact gradient of every weight and bias, after a forward on a training plan (SK_ESTATE
+ * otherwise).  labels_dev: DEVICE int32 [dz-v][h-v][w-v], values in [0, n_classes) or -1 for a masked voxel;
+ * loss_dev: DEVICE fp32 scalar; both as in sknet_backward with voxels for pixels (Sections 4.2, 4.3).  The
+ * gradient of a pool goes to the recorded winner (first maximum in the order depth, row, column tap), ReLU
+ * passes gradient where its output is > 0.  Deterministic. */
+sk_status sknet3d_backward(sknet3d_t *net, const int32_t *labels_dev, float *loss_dev, void *hip_stream);
+/* SGD on the fp32 weights with the gradients of the last backward, as sknet_sgd_step. */
+sk_status sknet3d_sgd_step(sknet3d_t *net, float lr, float momentum, float weight_decay, void *hip_stream);
+/* Parity accessors; each synchronises the stream of the last call first.  get_grad / get_weights: HOST fp32
+ * [f_out][f_in][k][k][k] and [f_out] (either may be NULL).  get_activation: output of layer layer_idx, HOST fp32
+ * [depth][maps][height][width].  get_pool_argmax: for max pool number pool_idx (0-based among pools) of a
+ * training plan, per output element ([depth][maps][height][width], int32) the flat offset
+ * (z_in*H_in + y_in)*W_in + x_in of the winning sample inside its map's input volume. */
+sk_status sknet3d_get_grad(sknet3d_t *net, int32_t conv_idx, float *dw_host, float *db_host);
+sk_status sknet3d_get_weights(sknet3d_t *net, int32_t conv_idx, float *w_host, float *b_host);
 sk_status sknet3d_get_activation(sknet3d_t *net, int32_t layer_idx, float *dchw_host);
+sk_status sknet3d_get_pool_argmax(sknet3d_t *net, int32_t pool_idx, int32_t *idx_host);
 
 /* Machine probes for the benchmark (Section 6 of the paper times kernels against each device's
  * peak; these two calls measure the peaks of the device at hand).  Neither runs any step of the method.

@@ -83,6 +83,11 @@ _SIGS = {
     "sknet3d_plan": [_vp, _i32, _i32, _i32, _i32],
     "sknet3d_forward": [_vp, _vp, _vp, _vp],
     "sknet3d_get_activation": [_vp, _i32, _fp],
+    "sknet3d_backward": [_vp, _vp, _vp, _vp],
+    "sknet3d_sgd_step": [_vp, C.c_float, C.c_float, C.c_float, _vp],
+    "sknet3d_get_grad": [_vp, _i32, _fp, _fp],
+    "sknet3d_get_weights": [_vp, _i32, _fp, _fp],
+    "sknet3d_get_pool_argmax": [_vp, _i32, _ip],
     "sk_probe_mfma": [_i32, _i32, _i32, _vp, C.POINTER(C.c_double)],
     "sk_probe_copy": [_vp, _vp, C.c_uint64, _i32, _vp, C.POINTER(C.c_double)],
 }
@@ -485,8 +490,9 @@ class SKNet3D:
             bp = None
         _check(lib.sknet3d_set_weights(self._h, conv_idx, wp, bp))
 
-    def plan(self, dz, h, w, keep=False):
-        _check(lib.sknet3d_plan(self._h, dz, h, w, 2 if keep else 0))
+    def plan(self, dz, h, w, keep=False, training=False):
+        """mode 1 if training, else 2 if keep (inference, every layer kept), else 0 (inference, fused head)."""
+        _check(lib.sknet3d_plan(self._h, dz, h, w, 1 if training else (2 if keep else 0)))
         self._plan = (dz, h, w)
         self._shapes = self.infer_shapes(dz, h, w)
 
@@ -512,4 +518,39 @@ class SKNet3D:
         c, dz, h, w = self._shapes[layer_idx + 1]
         out = np.empty((dz, c, h, w), np.float32)
         _check(lib.sknet3d_get_activation(self._h, layer_idx, out.ctypes.data_as(_fp)))
+        return out
+
+    def backward(self, labels, loss=None, stream=None):
+        dz, _, h, w = self.out_shape()
+        if tuple(labels.shape) != (dz, h, w):
+            raise ValueError("labels shape %s does not match %s" % (tuple(labels.shape), (dz, h, w)))
+        if loss is None:
+            loss = torch.empty((), dtype=torch.float32, device=labels.device)
+        _check(lib.sknet3d_backward(self._h, _dev_ptr(labels, torch.int32, "labels"), _dev_ptr(loss, torch.float32, "loss"),
+                                    _stream(stream)))
+        return loss
+
+    def sgd_step(self, lr, momentum=0.0, weight_decay=0.0, stream=None):
+        _check(lib.sknet3d_sgd_step(self._h, lr, momentum, weight_decay, _stream(stream)))
+
+    def get_grad(self, conv_idx):
+        shape = self.conv_shape(conv_idx)
+        dw = np.empty(shape, np.float32)
+        db = np.empty(shape[0], np.float32)
+        _check(lib.sknet3d_get_grad(self._h, conv_idx, dw.ctypes.data_as(_fp), db.ctypes.data_as(_fp)))
+        return dw, db
+
+    def get_weights(self, conv_idx):
+        shape = self.conv_shape(conv_idx)
+        w = np.empty(shape, np.float32)
+        b = np.empty(shape[0], np.float32)
+        _check(lib.sknet3d_get_weights(self._h, conv_idx, w.ctypes.data_as(_fp), b.ctypes.data_as(_fp)))
+        return w, b
+
+    def get_pool_argmax(self, pool_idx):
+        """Winner offsets of max pool number pool_idx as int32 [depth, maps, height, width]."""
+        pools = [i for i, l in enumerate(self.layers) if l["type"] == "pool"]
+        c, dz, h, w = self._shapes[pools[pool_idx] + 1]
+        out = np.empty((dz, c, h, w), np.int32)
+        _check(lib.sknet3d_get_pool_argmax(self._h, pool_idx, out.ctypes.data_as(_ip)))
         return out

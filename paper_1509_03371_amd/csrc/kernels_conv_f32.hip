@@ -721,6 +721,41 @@ __global__ void pack_weights_f32_kernel(const float *w, float *wp, int c_out, in
     pack_weights_f32_body(w, wp, c_out, c_in, k, flip_transpose, rows, n_pad);
 }
 
+// Packings of a 3-D kernel W3[c_out][C][k][k][k] (depth, row, column taps) for the 2-D convolution that treats
+// depth taps as input maps; al runs over the len taps of the launch:
+// flip_transpose = 0 (forward, taps a0 + al):       Wp[((al*C + c)*k + i)*k + j][o]     = W3[o][c][a0 + al][i][j]
+// flip_transpose = 1 (data gradient: every axis flipped, map roles swapped; taps k-1-(a0 + al)):
+//                                                   Wp[((al*c_out + o)*k + i)*k + j][c] = W3[o][c][k-1-a0-al][k-1-i][k-1-j]
+// Rows and columns beyond the real extents are zero.
+__global__ void pack_weights3d_f32_kernel(const float *w3, float *wp, int c_out, int C, int k, int a0, int len, int flip_transpose,
+                                          int rows, int n_pad)
+{
+    const long total = (long)rows * n_pad;
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
+        const int col = (int)(q % n_pad), row = (int)(q / n_pad);
+        const int j = row % k, i = (row / k) % k, m = row / (k * k);
+        float v = 0.f;
+        if (!flip_transpose) {
+            const int al = m / C, c = m - al * C;
+            if (al < len && col < c_out) v = w3[((((long)col * C + c) * k + a0 + al) * k + i) * k + j];
+        } else {
+            const int al = m / c_out, o = m - al * c_out;
+            if (al < len && col < C) v = w3[((((long)o * C + col) * k + (k - 1 - a0 - al)) * k + (k - 1 - i)) * k + (k - 1 - j)];
+        }
+        wp[q] = v;
+    }
+}
+
+hipError_t launch_pack_weights3d_f32(const float *w3, float *wp, int c_out, int C, int k, int a0, int len, int flip_transpose, int rows,
+                                     int n_pad, hipStream_t stream)
+{
+    const long total = (long)rows * n_pad;
+    const int blocks = (int)((total + 255) / 256 < 1024 ? (total + 255) / 256 : 1024);
+    hipLaunchKernelGGL(pack_weights3d_f32_kernel, dim3(blocks), dim3(256), 0, stream, w3, wp, c_out, C, k, a0, len, flip_transpose, rows,
+                       n_pad);
+    return hipGetLastError();
+}
+
 struct PackF32Jobs { PackF32Job job[BATCH_MAX]; };
 __global__ void pack_weights_f32_batch_kernel(PackF32Jobs b)
 {

@@ -149,9 +149,11 @@ hipError_t launch_maxpool_f32(const float *x, float *y, uint8_t *tap, int planes
 
 // ---- 3-D max pooling with kernel stride d and layer stride s on the slice-major layout (Section 5.2.2) ----
 // X[D][C][H][W] -> Y[Do][C][Ho][Wo], Y[z,c,y,x] = max_{a,i,j<k} X[s*z + a*d, c, s*y + i*d, s*x + j*d].
+// Taps are scanned in the order (a, i, j) and only a strictly greater value replaces the incumbent, so the
+// first maximum wins; tap (optional, laid out like y) receives the winner's code (a*k + i)*k + j.
 // grid: x = (output slice, column block), y = output row, z = map
-__global__ void __launch_bounds__(256) maxpool3d_f32_kernel(const float *__restrict__ x, float *__restrict__ y, int C, int H, int W,
-                                                            int Ho, int Wo, int k, int d, int s, int xblocks)
+__global__ void __launch_bounds__(256) maxpool3d_f32_kernel(const float *__restrict__ x, float *__restrict__ y, uint8_t *__restrict__ tap,
+                                                            int C, int H, int W, int Ho, int Wo, int k, int d, int s, int xblocks)
 {
     const int zo = blockIdx.x / xblocks, xb = blockIdx.x - zo * xblocks;
     const int xx = xb * 256 + threadIdx.x, yy = blockIdx.y, c = blockIdx.z;
@@ -159,24 +161,33 @@ __global__ void __launch_bounds__(256) maxpool3d_f32_kernel(const float *__restr
     const long plane = (long)H * W;
     const float *src = x + (((long)s * zo * C + c) * H + (long)s * yy) * W + (long)s * xx;
     float best = src[0];
+    int code = 0;
     for (int a = 0; a < k; ++a) {
         const float *sl = src + (long)a * d * C * plane;
         for (int i = 0; i < k; ++i)
             for (int j = 0; j < k; ++j) {
                 const float v = sl[(long)i * d * W + j * d];
-                best = v > best ? v : best;
+                if (v > best) {
+                    best = v;
+                    code = (a * k + i) * k + j;
+                }
             }
     }
-    y[(((long)zo * C + c) * Ho + yy) * Wo + xx] = best;
+    const long q = (((long)zo * C + c) * Ho + yy) * Wo + xx;
+    y[q] = best;
+    if (tap) tap[q] = (uint8_t)code;
 }
 
 // k = 2, s = 1 (the SK pools of a converted net): a thread owns one output column of one map and walks down
 // the slices z0, z0 + d, z0 + 2d, ... of one residue class mod d.  The 2x2 in-slice maximum q[z] of slice z
 // serves the windows of the outputs z - d and z, so each is formed once: four loads per output, not eight.
+// Winner codes follow the (a, i, j) scan: 0..3 inside slice z, 4..7 inside slice z + d, which only wins
+// when strictly greater.
 // grid: x = (residue class and chain segment, column block), y = output row, z = map
-__global__ void __launch_bounds__(256) maxpool3d_k2_chain_f32_kernel(const float *__restrict__ x, float *__restrict__ y, int C,
-                                                                     int H, int W, int Do, int Ho, int Wo, int d, int M,
-                                                                     int nseg, int xblocks)
+template <bool TAP>
+__global__ void __launch_bounds__(256) maxpool3d_k2_chain_f32_kernel(const float *__restrict__ x, float *__restrict__ y,
+                                                                     uint8_t *__restrict__ tap, int C, int H, int W, int Do, int Ho,
+                                                                     int Wo, int d, int M, int nseg, int xblocks)
 {
     const int chain = blockIdx.x / xblocks, xb = blockIdx.x - chain * xblocks;
     const int phase = chain / nseg, seg = chain - phase * nseg;
@@ -187,27 +198,41 @@ __global__ void __launch_bounds__(256) maxpool3d_k2_chain_f32_kernel(const float
     if (m0 >= m1) return;
     const long plane = (long)H * W, zstep = (long)d * C * plane, ostep = (long)d * C * Ho * Wo;
     const float *src = x + (((long)(phase + m0 * d) * C + c) * H + yy) * W + xx;
-    float *dst = y + (((long)(phase + m0 * d) * C + c) * Ho + yy) * Wo + xx;
+    const long o0 = (((long)(phase + m0 * d) * C + c) * Ho + yy) * Wo + xx;
+    float *dst = y + o0;
+    uint8_t *tdst = TAP ? tap + o0 : nullptr;
     const long dn = (long)d * W;
-    auto quad = [&](const float *p) {
+    int qc = 0;
+    auto quad = [&](const float *p, int &code) {
         const float a = p[0], b = p[d], e = p[dn], f = p[dn + d];
-        const float ab = b > a ? b : a, ef = f > e ? f : e;
-        return ef > ab ? ef : ab;
+        float best = a;
+        code = 0;
+        if (b > best) { best = b; code = 1; }
+        if (e > best) { best = e; code = 2; }
+        if (f > best) { best = f; code = 3; }
+        return best;
     };
-    float q = quad(src);
+    float q = quad(src, qc);
     for (int m = m0; m < m1; ++m) {
         src += zstep;
-        const float q2 = quad(src);
-        *dst = q2 > q ? q2 : q;
+        int qc2;
+        const float q2 = quad(src, qc2);
+        const bool lower = q2 > q;
+        *dst = lower ? q2 : q;
+        if (TAP) {
+            *tdst = (uint8_t)(lower ? 4 + qc2 : qc);
+            tdst += ostep;
+        }
         dst += ostep;
         q = q2;
+        qc = qc2;
     }
 }
 
-hipError_t launch_maxpool3d_f32(const float *x, float *y, int C, int D, int H, int W, int Do, int Ho, int Wo, int k, int d, int s,
-                                hipStream_t stream)
+hipError_t launch_maxpool3d_f32(const float *x, float *y, uint8_t *tap, int C, int D, int H, int W, int Do, int Ho, int Wo, int k,
+                                int d, int s, hipStream_t stream)
 {
-    if (C < 1 || C > 65535 || Ho < 1 || Ho > 65535 || Do < 1 || Wo < 1) return hipErrorInvalidValue;
+    if (C < 1 || C > 65535 || Ho < 1 || Ho > 65535 || Do < 1 || Wo < 1 || k < 1 || (tap && k > 6)) return hipErrorInvalidValue;
     if ((long)s * (Do - 1) + (long)(k - 1) * d >= D || (long)s * (Ho - 1) + (long)(k - 1) * d >= H ||
         (long)s * (Wo - 1) + (long)(k - 1) * d >= W)
         return hipErrorInvalidValue;
@@ -216,14 +241,103 @@ hipError_t launch_maxpool3d_f32(const float *x, float *y, int C, int D, int H, i
         const int M = 16, links = (Do + d - 1) / d, nseg = (links + M - 1) / M;
         const long gx = (long)d * nseg * xblocks;
         if (gx <= 0x7fffffffL) {
-            hipLaunchKernelGGL(maxpool3d_k2_chain_f32_kernel, dim3((unsigned)gx, Ho, C), dim3(256), 0, stream, x, y, C, H, W, Do, Ho,
-                               Wo, d, M, nseg, xblocks);
+            if (tap)
+                hipLaunchKernelGGL(maxpool3d_k2_chain_f32_kernel<true>, dim3((unsigned)gx, Ho, C), dim3(256), 0, stream, x, y, tap, C, H, W,
+                                   Do, Ho, Wo, d, M, nseg, xblocks);
+            else
+                hipLaunchKernelGGL(maxpool3d_k2_chain_f32_kernel<false>, dim3((unsigned)gx, Ho, C), dim3(256), 0, stream, x, y, tap, C, H, W,
+                                   Do, Ho, Wo, d, M, nseg, xblocks);
             return hipGetLastError();
         }
     }
     if ((long)Do * xblocks > 0x7fffffffL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(maxpool3d_f32_kernel, dim3((unsigned)(Do * xblocks), Ho, C), dim3(256), 0, stream, x, y, C, H, W, Ho, Wo, k, d,
-                       s, xblocks);
+    hipLaunchKernelGGL(maxpool3d_f32_kernel, dim3((unsigned)(Do * xblocks), Ho, C), dim3(256), 0, stream, x, y, tap, C, H, W, Ho, Wo, k,
+                       d, s, xblocks);
+    return hipGetLastError();
+}
+
+// Gather form of the 3-D pool gradient (s = 1): input sample (z, u, v) can only have won the windows whose
+// output sits at (z - a*d, u - i*d, v - j*d); it collects dY from those whose recorded code is (a*k + i)*k + j.
+// relu_src (optional, laid out like dx): the result is zeroed where relu_src <= 0.  No atomics.
+// grid: x = (input slice, column block), y = input row, z = map
+__global__ void __launch_bounds__(256) maxpool3d_bwd_f32_kernel(const float *__restrict__ dy, const uint8_t *__restrict__ tap,
+                                                                const float *__restrict__ relu_src, float *__restrict__ dx, int C,
+                                                                int H, int W, int Do, int Ho, int Wo, int k, int d, int xblocks)
+{
+    const int z = blockIdx.x / xblocks, xb = blockIdx.x - z * xblocks;
+    const int v = xb * 256 + threadIdx.x, u = blockIdx.y, c = blockIdx.z;
+    if (v >= W) return;
+    float sum = 0.f;
+    for (int a = 0; a < k; ++a) {
+        const int zo = z - a * d;
+        if (zo < 0 || zo >= Do) continue;
+        for (int i = 0; i < k; ++i) {
+            const int yo = u - i * d;
+            if (yo < 0 || yo >= Ho) continue;
+            for (int j = 0; j < k; ++j) {
+                const int xo = v - j * d;
+                if (xo < 0 || xo >= Wo) continue;
+                const long q = (((long)zo * C + c) * Ho + yo) * Wo + xo;
+                if (tap[q] == (uint8_t)((a * k + i) * k + j)) sum += dy[q];
+            }
+        }
+    }
+    const long p = (((long)z * C + c) * H + u) * W + v;
+    if (relu_src && !(relu_src[p] > 0.f)) sum = 0.f;
+    dx[p] = sum;
+}
+
+hipError_t launch_maxpool3d_bwd_f32(const float *dy, const uint8_t *tap, const float *relu_src, float *dx, int C, int D, int H, int W,
+                                    int Do, int Ho, int Wo, int k, int d, hipStream_t stream)
+{
+    if (C < 1 || C > 65535 || H < 1 || H > 65535 || k < 1 || k > 6) return hipErrorInvalidValue;
+    if (Do != D - (k - 1) * d || Ho != H - (k - 1) * d || Wo != W - (k - 1) * d || Do < 1 || Ho < 1 || Wo < 1) return hipErrorInvalidValue;
+    const int xblocks = (W + 255) / 256;
+    if ((long)D * xblocks > 0x7fffffffL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(maxpool3d_bwd_f32_kernel, dim3((unsigned)(D * xblocks), H, C), dim3(256), 0, stream, dy, tap, relu_src, dx, C, H, W,
+                       Do, Ho, Wo, k, d, xblocks);
+    return hipGetLastError();
+}
+
+// winner codes of a 3-D pool -> flat offsets ((z_in*H + y_in)*W + x_in) inside the map's input volume
+__global__ void tap3d_to_index_kernel(const uint8_t *tap, int32_t *idx, int C, int Do, int Ho, int Wo, int H, int W, int k, int d, int s,
+                                      long total)
+{
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
+        const int xo = (int)(q % Wo);
+        long t = q / Wo;
+        const int yo = (int)(t % Ho);
+        t /= Ho;
+        const int zo = (int)(t / C);
+        const int code = tap[q];
+        const int j = code % k, i = (code / k) % k, a = code / (k * k);
+        idx[q] = (int32_t)((((long)s * zo + a * d) * H + s * yo + i * d) * W + s * xo + j * d);
+    }
+}
+
+hipError_t launch_tap3d_to_index(const uint8_t *tap, int32_t *idx, int C, int Do, int Ho, int Wo, int H, int W, int k, int d, int s,
+                                 hipStream_t stream)
+{
+    const long total = (long)C * Do * Ho * Wo;
+    hipLaunchKernelGGL(tap3d_to_index_kernel, dim3(grid_for(total)), dim3(256), 0, stream, tap, idx, C, Do, Ho, Wo, H, W, k, d, s, total);
+    return hipGetLastError();
+}
+
+// dst[(m*k + a)*kk + r] = src[m*kk + r]: the gradient of depth tap a, [maps][k][k], into the 3-D gradient [maps][k][k][k]
+__global__ void place_tap_f32_kernel(const float *src, float *dst, long maps, int k, int a)
+{
+    const int kk = k * k;
+    const long total = maps * kk;
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
+        const long m = q / kk;
+        const int r = (int)(q - m * kk);
+        dst[(m * k + a) * kk + r] = src[q];
+    }
+}
+
+hipError_t launch_place_tap_f32(const float *src, float *dst, long maps, int k, int a, hipStream_t stream)
+{
+    hipLaunchKernelGGL(place_tap_f32_kernel, dim3(grid_for(maps * k * k)), dim3(256), 0, stream, src, dst, maps, k, a);
     return hipGetLastError();
 }
 

@@ -147,9 +147,20 @@ hipError_t launch_maxpool_f32(const float *x, float *y, uint8_t *tap, int planes
 hipError_t launch_maxpool_bwd_f32(const float *dy, const uint8_t *tap, const float *relu_src,
                                   float *dx, int planes, int H, int W, int Ho, int Wo, int k, int d,
                                   hipStream_t stream);
-// 3-D pool on the slice-major layout X[D][C][H][W] -> Y[Do][C][Ho][Wo]; k, d, s act on the three axes alike
-hipError_t launch_maxpool3d_f32(const float *x, float *y, int C, int D, int H, int W, int Do, int Ho, int Wo, int k, int d, int s,
-                                hipStream_t stream);
+// 3-D pool on the slice-major layout X[D][C][H][W] -> Y[Do][C][Ho][Wo]; k, d, s act on the three axes alike;
+// tap (optional, k <= 6) receives the winner's code (a*k + i)*k + j, first maximum in (a, i, j) order
+hipError_t launch_maxpool3d_f32(const float *x, float *y, uint8_t *tap, int C, int D, int H, int W, int Do, int Ho, int Wo, int k,
+                                int d, int s, hipStream_t stream);
+// gradient of the s = 1 pool from its winner codes; relu_src (optional, like dx) zeroes the result where it is <= 0
+hipError_t launch_maxpool3d_bwd_f32(const float *dy, const uint8_t *tap, const float *relu_src, float *dx, int C, int D, int H, int W,
+                                    int Do, int Ho, int Wo, int k, int d, hipStream_t stream);
+hipError_t launch_tap3d_to_index(const uint8_t *tap, int32_t *idx, int C, int Do, int Ho, int Wo, int H, int W, int k, int d, int s,
+                                 hipStream_t stream);
+// dst[(m*k + a)*k*k + r] = src[m*k*k + r] for m < maps, r < k*k
+hipError_t launch_place_tap_f32(const float *src, float *dst, long maps, int k, int a, hipStream_t stream);
+// packings of a 3-D kernel [c_out][C][k][k][k] for launch_conv_f32 (see kernels_conv_f32.hip)
+hipError_t launch_pack_weights3d_f32(const float *w3, float *wp, int c_out, int C, int k, int a0, int len, int flip_transpose, int rows,
+                                     int n_pad, hipStream_t stream);
 hipError_t launch_softmax_f32(const float *z, float *p, int n, int classes, int hw, hipStream_t stream);
 // loss = -(1/P) sum log p_label, dz = (p - onehot)/P over the pixels whose label lies in 0..classes-1;
 // any other label value (-1 by convention) masks the pixel (no loss, zero gradient) and P counts the

@@ -1,5 +1,6 @@
-// 3-D SK net forward (Section 5.2.2's N-dimensional layers, three dimensions): handle, shape inference,
-// planning and the launch sequence.  See include/sknet.h for the contract of every entry point.
+// 3-D SK net (Section 5.2.2's N-dimensional layers, three dimensions): handle, shape inference, planning and
+// the launch sequences of the forward and training passes.  See include/sknet.h for the contract of every
+// entry point.
 //
 // Volumes live slice-major, [D][C][H][W]: a stack of D multi-map 2-D slices.  With that layout a 3-D
 // convolution with kernel stride d is a 2-D SK convolution per output slice z whose input maps are the
@@ -9,6 +10,11 @@
 //   d > 1, C a multiple of 16: still one launch; the kernel steps over the d - 1 slices between two taps;
 //   d > 1 otherwise: one launch per depth tap, each adding to what the previous ones left in the output, the
 //          last one applying bias and ReLU.
+// The data gradient is the same convolution with every axis of the kernel flipped and the map roles swapped,
+// applied to the output gradient padded with zeros: rows and columns are padded by the 2-D kernel's own zero
+// padding, the (k-1)*d zero slices before and after are real memory (the gradient of a convolution's output is
+// written into the interior of a buffer whose border slices are cleared).  The weight gradient of depth tap a
+// is the 2-D weight gradient between the output gradient and the input slices shifted by a*d.
 // The 2-D kernels are used unchanged; nothing here is a separate 3-D multiplication.
 #include <hip/hip_runtime.h>
 
@@ -22,35 +28,93 @@ namespace {
 
 struct Dims3 {
     int c = 0, dz = 0, h = 0, w = 0;
-    long count() const { return (long)c * dz * h * w; }
+    long slice() const { return (long)c * h * w; }
+    long count() const { return slice() * dz; }
 };
 
-// the depth taps [a0, a0 + len) of one 3-D convolution as a 2-D convolution with len*C input maps
+// the depth taps [a0, a0 + len) of one 3-D convolution as a 2-D convolution with len * (maps per slice) input maps
 struct TapRun {
-    int a0 = 0, len = 0;
-    ConvParams p;
+    int a0 = 0, len = 0, rows = 0;
+    float *wp = nullptr;
 };
 
 struct Conv3 {
     int c_in = 0, c_out = 0, k = 1, d = 1;
-    std::vector<float> w, b;   // host master, [c_out][c_in][k][k][k] and [c_out]
-    std::vector<TapRun> runs;
+    int n_pad = 0, n_pad_bwd = 0;
+    std::vector<float> w, b;           // host master, [c_out][c_in][k][k][k] and [c_out]
+    float *w_dev = nullptr, *b_dev = nullptr;   // device master (b_dev: n_pad entries, zero padded)
+    std::vector<TapRun> fwd, bwd;      // bwd: runs over the flipped taps, for the data gradient
+    float *dw = nullptr, *db = nullptr, *vw = nullptr, *vb = nullptr, *dw_tap = nullptr;
     long wcount() const { return (long)c_out * c_in * k * k * k; }
 };
 
-// 2-D weights of a run: map (a - a0)*C + c of the 2-D convolution is depth tap a of map c
-void fill_run_weights(const Conv3 &cv, TapRun &r, bool last)
+std::vector<TapRun> make_runs(int k, int d, int maps)
 {
-    const int k = cv.k, C = cv.c_in;
-    ConvParams &p = r.p;
-    p.w.assign((size_t)p.wcount(), 0.f);
-    for (int o = 0; o < cv.c_out; ++o)
-        for (int a = 0; a < r.len; ++a)
-            for (int c = 0; c < C; ++c)
-                std::memcpy(&p.w[(((size_t)o * p.c_in) + (size_t)a * C + c) * k * k],
-                            &cv.w[((((size_t)o * C + c) * k) + r.a0 + a) * k * k], sizeof(float) * k * k);
-    p.b.assign((size_t)cv.c_out, 0.f);
-    if (last) p.b = cv.b;
+    // one run when the tapped slices are adjacent in memory, or the kernel can step over the d - 1 slices
+    // between two taps
+    const bool merged = d == 1 || k == 1 || sk::conv_f32_groups_supported(k, d, maps);
+    std::vector<TapRun> runs;
+    for (int a0 = 0; a0 < k; a0 += merged ? k : 1) {
+        TapRun r;
+        r.a0 = a0; r.len = merged ? k : 1;
+        r.rows = round_up(r.len * maps, 16) * k * k;
+        runs.push_back(r);
+    }
+    return runs;
+}
+
+void release_conv3(Conv3 &c)
+{
+    free_dev(c.w_dev); free_dev(c.b_dev);
+    for (auto &r : c.fwd) free_dev(r.wp);
+    for (auto &r : c.bwd) free_dev(r.wp);
+    c.bwd.clear();
+    free_dev(c.dw); free_dev(c.db); free_dev(c.vw); free_dev(c.vb); free_dev(c.dw_tap);
+}
+
+// rebuild the packed forms from the device master (asynchronous)
+sk_status repack_conv3(Conv3 &c, hipStream_t stream)
+{
+    for (auto &r : c.fwd)
+        SK_HIP(sk::launch_pack_weights3d_f32(c.w_dev, r.wp, c.c_out, c.c_in, c.k, r.a0, r.len, 0, r.rows, c.n_pad, stream));
+    for (auto &r : c.bwd)
+        SK_HIP(sk::launch_pack_weights3d_f32(c.w_dev, r.wp, c.c_out, c.c_in, c.k, r.a0, r.len, 1, r.rows, c.n_pad_bwd, stream));
+    return SK_OK;
+}
+
+sk_status upload_conv3(Conv3 &c, hipStream_t stream)
+{
+    SK_HIP(hipMemcpyAsync(c.w_dev, c.w.data(), sizeof(float) * c.wcount(), hipMemcpyHostToDevice, stream));
+    std::vector<float> bp(c.n_pad, 0.f);
+    std::memcpy(bp.data(), c.b.data(), sizeof(float) * c.c_out);
+    SK_HIP(hipMemcpyAsync(c.b_dev, bp.data(), sizeof(float) * c.n_pad, hipMemcpyHostToDevice, stream));
+    SK_TRY(repack_conv3(c, stream));
+    SK_HIP(hipStreamSynchronize(stream));
+    return SK_OK;
+}
+
+sk_status alloc_conv3(Conv3 &c, bool training, bool needs_dgrad)
+{
+    release_conv3(c);
+    c.n_pad = round_up(c.c_out, 16);
+    c.n_pad_bwd = round_up(c.c_in, 16);
+    SK_TRY(alloc_f(&c.w_dev, c.wcount()));
+    SK_TRY(alloc_f(&c.b_dev, c.n_pad));
+    for (auto &r : c.fwd) SK_TRY(alloc_f(&r.wp, (long)r.rows * c.n_pad));
+    if (training) {
+        if (needs_dgrad) {
+            c.bwd = make_runs(c.k, c.d, c.c_out);
+            for (auto &r : c.bwd) SK_TRY(alloc_f(&r.wp, (long)r.rows * c.n_pad_bwd));
+        }
+        SK_TRY(alloc_f(&c.dw, c.wcount()));
+        SK_TRY(alloc_f(&c.db, c.c_out));
+        SK_TRY(alloc_f(&c.vw, c.wcount()));
+        SK_TRY(alloc_f(&c.vb, c.c_out));
+        SK_TRY(alloc_f(&c.dw_tap, (long)c.c_out * c.c_in * c.k * c.k));
+        SK_HIP(hipMemset(c.vw, 0, sizeof(float) * c.wcount()));
+        SK_HIP(hipMemset(c.vb, 0, sizeof(float) * c.c_out));
+    }
+    return SK_OK;
 }
 
 }  // namespace
@@ -60,12 +124,14 @@ struct sknet3d {
     int c_in = 0, n_classes = 0;
     std::vector<Conv3> convs;
     std::vector<int> conv_of_layer;
-    bool planned = false, forward_done = false;
+    bool planned = false, training = false, forward_done = false, backward_done = false;
     int dz = 0, h = 0, w = 0;
     std::vector<Dims3> dims;       // dims[0] the volume, dims[i+1] the output of layer i
-    std::vector<float *> act;      // act[0] unused (the caller's volume is read in place)
+    std::vector<float *> act;      // act[0]: the training plan's copy of the volume, else unused
+    std::vector<uint8_t *> tap;    // per layer: winner codes of the pools of a training plan
     bool fuse_head = false;        // last two 1x1x1 convolutions + softmax as one kernel
     float *head_w1p = nullptr;
+    float *gbuf[2] = {nullptr, nullptr}, *loss_partial = nullptr, *wgrad_scratch = nullptr;
     hipStream_t last_stream = nullptr;
     const float *last_volume = nullptr;
 
@@ -73,10 +139,14 @@ struct sknet3d {
     {
         for (auto &p : act) free_dev(p);
         act.clear();
-        free_dev(head_w1p);
-        for (auto &c : convs)
-            for (auto &r : c.runs) release_conv(r.p);
-        planned = forward_done = false;
+        for (auto &t : tap) {
+            if (t) (void)hipFree(t);
+            t = nullptr;
+        }
+        tap.clear();
+        free_dev(head_w1p); free_dev(gbuf[0]); free_dev(gbuf[1]); free_dev(loss_partial); free_dev(wgrad_scratch);
+        for (auto &c : convs) release_conv3(c);
+        planned = training = forward_done = backward_done = false;
         fuse_head = false;
     }
 };
@@ -113,6 +183,35 @@ sk_status infer3(const sknet3d *net, int dz, int h, int w, std::vector<Dims3> &d
     return SK_OK;
 }
 
+// the launches of one 3-D convolution (forward, or data gradient on the zero-padded output gradient):
+// x: first slice of the input, [*][maps][H][W]; y: [n_img][out_maps][OH][OW]
+sk_status run_conv3(const std::vector<TapRun> &runs, const float *x, float *y, const float *bias, const float *mask, int n_img,
+                    int maps, int H, int W, int out_maps, int n_pad, int k, int d, int in_off, int OH, int OW, int relu,
+                    hipStream_t stream)
+{
+    const long slice = (long)maps * H * W;
+    for (size_t r = 0; r < runs.size(); ++r) {
+        const TapRun &run = runs[r];
+        const bool last = r + 1 == runs.size();
+        sk::ConvF32Args a{};
+        a.x = x + (long)run.a0 * d * slice; a.wp = run.wp; a.bias = last ? bias : nullptr; a.mask = mask; a.y = y;
+        a.n = n_img; a.c_in = run.len * maps; a.H = H; a.W = W;
+        a.c_out = out_maps; a.n_pad = n_pad;
+        a.k = k; a.d = d; a.in_off = in_off;
+        a.Ho = OH; a.Wo = OW; a.relu = last ? relu : 0;
+        a.out_maps = out_maps; a.o_off = 0; a.OH = OH; a.OW = OW;
+        a.oy_mul = 1; a.oy_off = 0; a.ox_mul = 1; a.ox_off = 0;
+        a.accumulate = r > 0 ? 1 : 0;
+        a.x_bstride = slice;
+        if (run.len > 1 && d > 1) {
+            a.grp_maps = maps;
+            a.grp_skip = (long)(d - 1) * slice;
+        }
+        SK_HIP(sk::launch_conv_f32(a, stream));
+    }
+    return SK_OK;
+}
+
 sk_status run_layer3(sknet3d *net, int li, hipStream_t stream)
 {
     const sk_layer &l = net->layers[li];
@@ -120,28 +219,18 @@ sk_status run_layer3(sknet3d *net, int li, hipStream_t stream)
     const float *x = li == 0 ? net->last_volume : net->act[li];
     float *y = net->act[li + 1];
     if (l.kind == SK_MAXPOOL) {
-        SK_HIP(sk::launch_maxpool3d_f32(x, y, in.c, in.dz, in.h, in.w, out.dz, out.h, out.w, l.k, l.d, l.s, stream));
+        SK_HIP(sk::launch_maxpool3d_f32(x, y, net->tap[li], in.c, in.dz, in.h, in.w, out.dz, out.h, out.w, l.k, l.d, l.s, stream));
         return SK_OK;
     }
-    Conv3 &cv = net->convs[net->conv_of_layer[li]];
-    const long slice = (long)in.c * in.h * in.w;
-    for (size_t r = 0; r < cv.runs.size(); ++r) {
-        const TapRun &run = cv.runs[r];
-        const bool last = r + 1 == cv.runs.size();
-        Dims in2, out2;
-        in2.c = run.len * in.c; in2.h = in.h; in2.w = in.w;
-        out2.c = out.c; out2.h = out.h; out2.w = out.w;
-        sk::ConvF32Args a = conv_args(run.p, x + (long)run.a0 * l.d * slice, out.dz, in2, l.d, last ? l.relu : 0, y, out2);
-        a.bias = last ? run.p.b_dev : nullptr;
-        a.accumulate = r > 0 ? 1 : 0;
-        a.x_bstride = slice;
-        if (run.len > 1 && l.d > 1) {
-            a.grp_maps = in.c;
-            a.grp_skip = (long)(l.d - 1) * slice;
-        }
-        SK_HIP(sk::launch_conv_f32(a, stream));
-    }
-    return SK_OK;
+    const Conv3 &cv = net->convs[net->conv_of_layer[li]];
+    return run_conv3(cv.fwd, x, y, cv.b_dev, nullptr, out.dz, in.c, in.h, in.w, out.c, cv.n_pad, l.k, l.d, 0, out.h, out.w, l.relu, stream);
+}
+
+// zero slices that surround the gradient of layer li's output while it serves as the input of li's data gradient
+int grad_pad(const sknet3d *net, int li)
+{
+    const sk_layer &l = net->layers[li];
+    return (l.kind == SK_CONV && li > 0) ? (l.k - 1) * l.d : 0;
 }
 
 }  // namespace
@@ -177,16 +266,7 @@ sk_status sknet3d_create(const sk_layer *layers, int32_t n_layers, int32_t c_in,
             c.c_in = maps; c.c_out = l.c_out; c.k = l.k; c.d = l.d;
             c.w.assign((size_t)c.wcount(), 0.f);
             c.b.assign((size_t)c.c_out, 0.f);
-            // one run when the tapped slices are adjacent in memory, or the kernel can step over the d - 1
-            // slices between two taps
-            const bool adjacent = l.d == 1 || l.k == 1 || sk::conv_f32_groups_supported(l.k, l.d, maps);
-            for (int a0 = 0; a0 < l.k; a0 += adjacent ? l.k : 1) {
-                TapRun r;
-                r.a0 = a0; r.len = adjacent ? l.k : 1;
-                r.p.c_in = r.len * maps; r.p.c_out = l.c_out; r.p.k = l.k;
-                c.runs.push_back(std::move(r));
-            }
-            for (size_t r = 0; r < c.runs.size(); ++r) fill_run_weights(c, c.runs[r], r + 1 == c.runs.size());
+            c.fwd = make_runs(l.k, l.d, maps);
             net->conv_of_layer.push_back((int)net->convs.size());
             net->convs.push_back(std::move(c));
             maps = l.c_out;
@@ -258,47 +338,89 @@ sk_status sknet3d_set_weights(sknet3d_t *net, int32_t conv_idx, const float *w_h
     Conv3 &c = net->convs[conv_idx];
     std::memcpy(c.w.data(), w_host, sizeof(float) * c.wcount());
     if (b_host) std::memcpy(c.b.data(), b_host, sizeof(float) * c.c_out);
-    for (size_t r = 0; r < c.runs.size(); ++r) {
-        fill_run_weights(c, c.runs[r], r + 1 == c.runs.size());
-        if (net->planned) SK_TRY(upload_conv(c.runs[r].p, false, nullptr));
-    }
-    if (net->planned && net->fuse_head && conv_idx == (int)net->convs.size() - 2) {
-        ConvParams &c1 = c.runs[0].p;
-        SK_HIP(sk::launch_pack_head_w1(c1.w_dev, net->head_w1p, SK_F32, c1.c_out, c1.c_in, nullptr));
+    if (!net->planned) return SK_OK;
+    if (net->last_stream) SK_HIP(hipStreamSynchronize(net->last_stream));
+    if (!b_host)   // keep the device's current biases (an SGD step may have changed them)
+        SK_HIP(hipMemcpy(c.b.data(), c.b_dev, sizeof(float) * c.c_out, hipMemcpyDeviceToHost));
+    SK_TRY(upload_conv3(c, nullptr));
+    if (net->fuse_head && conv_idx == (int)net->convs.size() - 2) {
+        SK_HIP(sk::launch_pack_head_w1(c.w_dev, net->head_w1p, SK_F32, c.c_out, c.c_in, nullptr));
         SK_HIP(hipStreamSynchronize(nullptr));
     }
+    return SK_OK;
+}
+
+sk_status sknet3d_get_weights(sknet3d_t *net, int32_t conv_idx, float *w_host, float *b_host)
+{
+    SK_TRY(check3(net));
+    if (conv_idx < 0 || conv_idx >= (int)net->convs.size()) return fail(SK_EINVAL, "get_weights: bad index");
+    Conv3 &c = net->convs[conv_idx];
+    if (net->planned) {   // the device holds the current values
+        if (net->last_stream) SK_HIP(hipStreamSynchronize(net->last_stream));
+        SK_HIP(hipMemcpy(c.w.data(), c.w_dev, sizeof(float) * c.wcount(), hipMemcpyDeviceToHost));
+        SK_HIP(hipMemcpy(c.b.data(), c.b_dev, sizeof(float) * c.c_out, hipMemcpyDeviceToHost));
+    }
+    if (w_host) std::memcpy(w_host, c.w.data(), sizeof(float) * c.wcount());
+    if (b_host) std::memcpy(b_host, c.b.data(), sizeof(float) * c.c_out);
     return SK_OK;
 }
 
 sk_status sknet3d_plan(sknet3d_t *net, int32_t dz, int32_t h, int32_t w, int32_t mode)
 {
     SK_TRY(check3(net));
-    if (mode != 0 && mode != 2) return fail(SK_EINVAL, "plan: mode must be 0 (inference) or 2 (inference, every layer kept)");
+    if (mode < 0 || mode > 2) return fail(SK_EINVAL, "plan: mode must be 0 (inference), 1 (training) or 2 (inference, every layer kept)");
+    const bool training = mode == 1;
     std::vector<Dims3> dims;
     SK_TRY(infer3(net, dz, h, w, dims));
     const int L = (int)net->layers.size();
     for (int i = 0; i <= L; ++i)
         if (dims[i].dz > 65535 || dims[i].h > 65535 || dims[i].count() >= (1L << 40))
             return fail(SK_EUNSUPPORTED, "plan: volume too large");
+    if (training)
+        for (int i = 0; i < L; ++i) {
+            const sk_layer &l = net->layers[i];
+            if (l.kind == SK_MAXPOOL && l.s != 1) return fail(SK_EUNSUPPORTED, "plan: training needs pools with s = 1 (layer %d)", i);
+            if (l.kind == SK_MAXPOOL && l.k > 6) return fail(SK_EUNSUPPORTED, "plan: training needs pools with k <= 6 (layer %d)", i);
+        }
+    // keep the host masters (a planned net's masters may have been updated on the device)
+    if (net->planned)
+        for (int i = 0; i < (int)net->convs.size(); ++i) SK_TRY(sknet3d_get_weights(net, i, nullptr, nullptr));
     net->release_plan();
     net->dz = dz; net->h = h; net->w = w;
     net->dims = dims;
     net->act.assign(L + 1, nullptr);
+    net->tap.assign(L, nullptr);
     net->fuse_head = mode == 0 && L >= 2 && net->layers[L - 2].kind == SK_CONV && net->layers[L - 1].kind == SK_CONV &&
                      net->layers[L - 2].k == 1 && net->layers[L - 1].k == 1 && net->layers[L - 2].relu && !net->layers[L - 1].relu &&
                      sk::head_supported(SK_F32, dims[L - 2].c, net->layers[L - 2].c_out, net->layers[L - 1].c_out);
     sk_status st = SK_OK;
-    for (int i = 1; i <= L && st == SK_OK; ++i) {
+    long max_grad = 0;   // largest gradient buffer: an activation plus the zero slices around it
+    size_t scratch = 0;
+    for (int i = training ? 0 : 1; i <= L && st == SK_OK; ++i) {
         if (net->fuse_head && i >= L - 1) continue;
         st = alloc_f(&net->act[i], dims[i].count());
     }
-    for (auto &c : net->convs)
-        for (auto &r : c.runs) {
-            if (st == SK_OK) st = alloc_conv(r.p, false);
-            if (st == SK_OK) st = upload_conv(r.p, false, nullptr);
+    for (int i = 0; i < L && st == SK_OK && training; ++i) {
+        const sk_layer &l = net->layers[i];
+        const long padded = dims[i + 1].count() + 2L * grad_pad(net, i) * dims[i + 1].slice();
+        if (padded > max_grad) max_grad = padded;
+        if (dims[i].count() > max_grad) max_grad = dims[i].count();
+        if (l.kind == SK_MAXPOOL) {
+            hipError_t e = hipMalloc(reinterpret_cast<void **>(&net->tap[i]), (size_t)dims[i + 1].count());
+            if (e != hipSuccess) st = fail(SK_ENOMEM, "plan: winner codes: %s", hipGetErrorString(e));
+        } else {
+            const size_t s = sk::wgrad_f32_scratch_floats(l.c_out, dims[i].c, l.k);
+            if (s > scratch) scratch = s;
         }
+    }
+    for (int i = 0; i < L && st == SK_OK; ++i) {
+        if (net->layers[i].kind != SK_CONV) continue;
+        Conv3 &c = net->convs[net->conv_of_layer[i]];
+        st = alloc_conv3(c, training, i > 0);
+        if (st == SK_OK) st = upload_conv3(c, nullptr);
+    }
     if (st == SK_OK && net->fuse_head) {
-        ConvParams &c1 = net->convs[net->conv_of_layer[L - 2]].runs[0].p;
+        Conv3 &c1 = net->convs[net->conv_of_layer[L - 2]];
         st = alloc_f(&net->head_w1p, (sk::head_w1_packed_bytes(SK_F32, c1.c_in, c1.c_out) + 3) / 4);
         if (st == SK_OK) {
             hipError_t e = sk::launch_pack_head_w1(c1.w_dev, net->head_w1p, SK_F32, c1.c_out, c1.c_in, nullptr);
@@ -306,11 +428,18 @@ sk_status sknet3d_plan(sknet3d_t *net, int32_t dz, int32_t h, int32_t w, int32_t
             if (e != hipSuccess) st = fail(SK_EDEVICE, "plan: packing the head weights failed: %s", hipGetErrorString(e));
         }
     }
+    if (st == SK_OK && training) {
+        st = alloc_f(&net->gbuf[0], max_grad);
+        if (st == SK_OK) st = alloc_f(&net->gbuf[1], max_grad);
+        if (st == SK_OK) st = alloc_f(&net->loss_partial, sk::softmax_loss_partials(dims[L].count() / dims[L].c));
+        if (st == SK_OK) st = alloc_f(&net->wgrad_scratch, (long)scratch);
+    }
     if (st != SK_OK) {
         net->release_plan();
         return st;
     }
     net->planned = true;
+    net->training = training;
     return SK_OK;
 }
 
@@ -322,11 +451,15 @@ sk_status sknet3d_forward(sknet3d_t *net, const float *volume_dev, float *prob_d
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     net->last_stream = stream;
     net->last_volume = volume_dev;
+    if (net->training) {   // the backward pass reads the volume again: keep a copy
+        SK_HIP(hipMemcpyAsync(net->act[0], volume_dev, sizeof(float) * net->dims[0].count(), hipMemcpyDeviceToDevice, stream));
+        net->last_volume = net->act[0];
+    }
     const int L = (int)net->layers.size();
     for (int i = 0; i < (net->fuse_head ? L - 2 : L); ++i) SK_TRY(run_layer3(net, i, stream));
     const Dims3 &o = net->dims[L];
     if (net->fuse_head) {
-        const ConvParams &c1 = net->convs[net->conv_of_layer[L - 2]].runs[0].p, &c2 = net->convs[net->conv_of_layer[L - 1]].runs[0].p;
+        const Conv3 &c1 = net->convs[net->conv_of_layer[L - 2]], &c2 = net->convs[net->conv_of_layer[L - 1]];
         const Dims3 &in = net->dims[L - 2];
         sk::HeadArgs a{};
         a.x = L - 2 == 0 ? volume_dev : net->act[L - 2];
@@ -338,6 +471,90 @@ sk_status sknet3d_forward(sknet3d_t *net, const float *volume_dev, float *prob_d
         SK_HIP(sk::launch_softmax_f32(net->act[L], prob_dev, o.dz, o.c, o.h * o.w, stream));
     }
     net->forward_done = true;
+    net->backward_done = false;
+    return SK_OK;
+}
+
+sk_status sknet3d_backward(sknet3d_t *net, const int32_t *labels_dev, float *loss_dev, void *hip_stream)
+{
+    SK_TRY(check3(net));
+    if (!net->planned || !net->training) return fail(SK_ESTATE, "backward: needs a training plan");
+    if (!net->forward_done) return fail(SK_ESTATE, "backward: run sknet3d_forward first");
+    if (!labels_dev || !loss_dev) return fail(SK_EINVAL, "backward: null buffer");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    net->last_stream = stream;
+    const int L = (int)net->layers.size();
+    const Dims3 &o = net->dims[L];
+    float *gcur = net->gbuf[0], *gnext = net->gbuf[1];
+    {
+        float *dz = gcur + (long)grad_pad(net, L - 1) * o.slice();
+        SK_HIP(sk::launch_softmax_loss_f32(net->act[L], labels_dev, dz, loss_dev, net->loss_partial, o.dz, o.c, o.h * o.w, stream));
+        if (net->layers[L - 1].kind == SK_CONV && net->layers[L - 1].relu) SK_HIP(sk::launch_relu_mask_f32(dz, net->act[L], o.count(), stream));
+    }
+    for (int li = L - 1; li >= 0; --li) {
+        const sk_layer &l = net->layers[li];
+        const Dims3 &in = net->dims[li], &out = net->dims[li + 1];
+        const int pad = grad_pad(net, li);
+        const float *g = gcur + (long)pad * out.slice();       // gradient of this layer's output
+        // ReLU of the layer below acts on this layer's input
+        const float *relu_src = (li > 0 && net->layers[li - 1].kind == SK_CONV && net->layers[li - 1].relu) ? net->act[li] : nullptr;
+        float *dst = li > 0 ? gnext + (long)grad_pad(net, li - 1) * in.slice() : nullptr;
+        if (l.kind == SK_CONV) {
+            Conv3 &c = net->convs[net->conv_of_layer[li]];
+            for (int a = 0; a < l.k; ++a) {   // depth tap a: the input slices shifted by a*d against the output gradient
+                SK_HIP(sk::launch_wgrad_f32(net->act[li] + (long)a * l.d * in.slice(), g, c.dw_tap, a + 1 == l.k ? c.db : nullptr,
+                                            net->wgrad_scratch, out.dz, in.c, in.h, in.w, c.c_out, l.k, l.d, stream));
+                SK_HIP(sk::launch_place_tap_f32(c.dw_tap, c.dw, (long)c.c_out * c.c_in, l.k, a, stream));
+            }
+            if (li == 0) break;   // nothing below needs the volume's gradient
+            if (pad > 0) {
+                SK_HIP(sk::launch_fill_f32(gcur, 0.f, (long)pad * out.slice(), stream));
+                SK_HIP(sk::launch_fill_f32(gcur + (long)(pad + out.dz) * out.slice(), 0.f, (long)pad * out.slice(), stream));
+            }
+            const bool one = c.bwd.size() == 1;
+            SK_TRY(run_conv3(c.bwd, gcur, dst, nullptr, one ? relu_src : nullptr, in.dz, out.c, out.h, out.w, in.c, c.n_pad_bwd, l.k,
+                             l.d, (l.k - 1) * l.d, in.h, in.w, 0, stream));
+            if (!one && relu_src) SK_HIP(sk::launch_relu_mask_f32(dst, relu_src, in.count(), stream));
+        } else {
+            if (li == 0) break;
+            SK_HIP(sk::launch_maxpool3d_bwd_f32(g, net->tap[li], relu_src, dst, in.c, in.dz, in.h, in.w, out.dz, out.h, out.w, l.k, l.d,
+                                                stream));
+        }
+        float *t = gcur; gcur = gnext; gnext = t;
+    }
+    net->backward_done = true;
+    return SK_OK;
+}
+
+sk_status sknet3d_sgd_step(sknet3d_t *net, float lr, float momentum, float weight_decay, void *hip_stream)
+{
+    SK_TRY(check3(net));
+    if (!net->planned || !net->training || !net->backward_done) return fail(SK_ESTATE, "sgd_step: needs a backward pass on a training plan");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    net->last_stream = stream;
+    sk::SgdBatch sb{};
+    for (auto &c : net->convs) {
+        if (sb.n + 2 > sk::BATCH_MAX) {
+            SK_HIP(sk::launch_sgd_batch_f32(sb, lr, momentum, weight_decay, stream));
+            sb = sk::SgdBatch{};
+        }
+        sb.w[sb.n] = c.w_dev; sb.dw[sb.n] = c.dw; sb.v[sb.n] = momentum != 0.f ? c.vw : nullptr; sb.count[sb.n] = c.wcount(); ++sb.n;
+        sb.w[sb.n] = c.b_dev; sb.dw[sb.n] = c.db; sb.v[sb.n] = momentum != 0.f ? c.vb : nullptr; sb.count[sb.n] = c.c_out; ++sb.n;
+    }
+    if (sb.n > 0) SK_HIP(sk::launch_sgd_batch_f32(sb, lr, momentum, weight_decay, stream));
+    for (auto &c : net->convs) SK_TRY(repack_conv3(c, stream));
+    return SK_OK;
+}
+
+sk_status sknet3d_get_grad(sknet3d_t *net, int32_t conv_idx, float *dw_host, float *db_host)
+{
+    SK_TRY(check3(net));
+    if (conv_idx < 0 || conv_idx >= (int)net->convs.size()) return fail(SK_EINVAL, "get_grad: bad index");
+    if (!net->backward_done) return fail(SK_ESTATE, "get_grad: no backward pass yet");
+    Conv3 &c = net->convs[conv_idx];
+    SK_HIP(hipStreamSynchronize(net->last_stream));
+    if (dw_host) SK_HIP(hipMemcpy(dw_host, c.dw, sizeof(float) * c.wcount(), hipMemcpyDeviceToHost));
+    if (db_host) SK_HIP(hipMemcpy(db_host, c.db, sizeof(float) * c.c_out, hipMemcpyDeviceToHost));
     return SK_OK;
 }
 
@@ -350,6 +567,28 @@ sk_status sknet3d_get_activation(sknet3d_t *net, int32_t layer_idx, float *dchw_
         return fail(SK_ESTATE, "get_activation: this plan fuses the last two layers; plan with mode 2 to keep them");
     SK_HIP(hipStreamSynchronize(net->last_stream));
     SK_HIP(hipMemcpy(dchw_host, net->act[layer_idx + 1], sizeof(float) * net->dims[layer_idx + 1].count(), hipMemcpyDeviceToHost));
+    return SK_OK;
+}
+
+sk_status sknet3d_get_pool_argmax(sknet3d_t *net, int32_t pool_idx, int32_t *idx_host)
+{
+    SK_TRY(check3(net));
+    if (!idx_host || pool_idx < 0) return fail(SK_EINVAL, "get_pool_argmax: bad arguments");
+    if (!net->planned || !net->training || !net->forward_done) return fail(SK_ESTATE, "get_pool_argmax: needs a forward pass on a training plan");
+    int li = -1, seen = 0;
+    for (int i = 0; i < (int)net->layers.size(); ++i)
+        if (net->layers[i].kind == SK_MAXPOOL && seen++ == pool_idx) li = i;
+    if (li < 0) return fail(SK_EINVAL, "get_pool_argmax: the net has no pool number %d", pool_idx);
+    const sk_layer &l = net->layers[li];
+    const Dims3 &in = net->dims[li], &out = net->dims[li + 1];
+    if ((long)in.dz * in.h * in.w > 0x7fffffffL) return fail(SK_EUNSUPPORTED, "get_pool_argmax: offsets exceed 32 bits");
+    int32_t *tmp = nullptr;
+    SK_HIP(hipMalloc(reinterpret_cast<void **>(&tmp), sizeof(int32_t) * (size_t)out.count()));
+    hipError_t e = sk::launch_tap3d_to_index(net->tap[li], tmp, out.c, out.dz, out.h, out.w, in.h, in.w, l.k, l.d, l.s, net->last_stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(net->last_stream);
+    if (e == hipSuccess) e = hipMemcpy(idx_host, tmp, sizeof(int32_t) * (size_t)out.count(), hipMemcpyDeviceToHost);
+    (void)hipFree(tmp);
+    if (e != hipSuccess) return fail(SK_EDEVICE, "get_pool_argmax: %s", hipGetErrorString(e));
     return SK_OK;
 }
 
