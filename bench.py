@@ -8,7 +8,7 @@ A step is one such pass over one synthetic image that is resident in HBM before 
 --workload c3 : the same net in bf16 (fp32 accumulate) on 8 images of 1024x1024 (configs[2])
 --workload c4 : one bf16 training step at 512x512 (configs[3]): forward, softmax loss, backward, SGD
 --workload c5 / c5bf16 : U-Net forward on one 572x572 image (configs[4]) in fp32 / bf16
---workload sk3d : 3-D SK net forward on a stack of 81 sections of 145x145 (Section 5.2.2), fp32
+--workload sk3d / sk3dtrain : 3-D SK net on a stack of 81 sections of 145x145 (Section 5.2.2), fp32: forward / training step
 --workload copy : only the streaming-copy probe on 2 x 1 GiB (the known-size kernel that the HBM
                   byte counters of a profiler run are calibrated against)
 The default run also appends short c3 / c4 measurements under "extras" (skip with --no-extras).
@@ -277,6 +277,43 @@ def measure_sknet3d(torch, B, S, steps, warmup):
             "gflop": round(gflop, 1), "tflops": round(gflop / dt / 1e3, 1)}
 
 
+def measure_sknet3d_train(torch, B, S, steps, warmup):
+    """One training step of the 3-D SK net of measure_sknet3d on the same volume: forward on a training plan,
+    masked softmax loss, backward, SGD."""
+    import numpy as np
+    layers = S.sknet3d_layers(classes=2)
+    ws, bs = S.he_normal_weights3d(layers, 1, 1100)
+    net = B.SKNet3D(layers, 1, 2)
+    for i, (w, b) in enumerate(zip(ws, bs)):
+        net.set_weights(i, w, b)
+    dz, h, w = 81, 145, 145
+    net.plan(dz, h, w, training=True)
+    od, _, oh, ow = net.out_shape()
+    vol = torch.from_numpy(np.ascontiguousarray(S.em_like_volume(dz, h, w, 1101).transpose(1, 0, 2, 3))).cuda()
+    lab = S.binary_labels(od, oh, ow, 1102)
+    labels = torch.from_numpy(S.mask_labels_by_frequency(lab, 2, 1103)).cuda()
+    prob = torch.empty(net.out_shape(), dtype=torch.float32, device="cuda")
+    loss = torch.empty((), dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step():
+        net.forward(vol, prob, stream)
+        net.backward(labels, loss, stream)
+        net.sgd_step(1e-3, 0.9, 0.0, stream)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    final = float(loss.cpu())
+    net.close()
+    return {"ms_per_step": round(dt * 1e3, 3), "labelled_voxels_per_s": round(od * oh * ow / dt, 1), "loss_after": round(final, 4)}
+
+
 def measured_peaks(torch, B):
     """What this GPU sustains on a bare MFMA issue loop and on a streaming copy (not the method)."""
     src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)   # 1 GiB each
@@ -299,7 +336,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", choices=["c2", "c3", "c4", "c5", "c5bf16", "usk", "papersk", "sk3d", "unettrain", "usktrain", "copy"], default="c2")
+    ap.add_argument("--workload", choices=["c2", "c3", "c4", "c5", "c5bf16", "usk", "papersk", "sk3d", "sk3dtrain", "unettrain", "usktrain", "copy"], default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
     args = ap.parse_args()
@@ -346,8 +383,11 @@ def main():
         print(json.dumps(out))
         return
 
-    if args.workload in ("usk", "papersk", "sk3d"):
-        if args.workload == "sk3d":
+    if args.workload in ("usk", "papersk", "sk3d", "sk3dtrain"):
+        if args.workload == "sk3dtrain":
+            r = measure_sknet3d_train(torch, B, S, args.steps, args.warmup)
+            px, what = r["labelled_voxels_per_s"], "3-D SK net training step, 81x145x145 -> 64x128x128 labels, fp32: forward, masked softmax loss, backward, SGD; value = labelled voxels per second"
+        elif args.workload == "sk3d":
             r = measure_sknet3d(torch, B, S, args.steps, args.warmup)
             px, what = r["labelled_voxels_per_s"], "3-D SK net forward, 81x145x145 -> 2x64x128x128 (context 17), fp32; value = labelled voxels per second"
         elif args.workload == "usk":
@@ -407,6 +447,7 @@ def main():
         extras["paper_sknet_128_f32"] = measure_paper_sknet(torch, B, S, 5, 2)
         extras["usknet_692_f32_forward"] = measure_usknet(torch, B, S, 5, 2)
         extras["sknet3d_81x145x145_f32_forward"] = measure_sknet3d(torch, B, S, 5, 2)
+        extras["sknet3d_81x145x145_f32_train_step"] = measure_sknet3d_train(torch, B, S, 3, 1)
         extras["unet_572_f32_train_step"] = measure_unet_train(torch, B, S, "unet", 3, 1)
         extras["usknet_692_f32_train_step"] = measure_unet_train(torch, B, S, "usk", 3, 1)
         out["extras"] = extras

@@ -69,6 +69,14 @@ def test_gradients_sixteen_map_multiples_one_launch():
     net.close()
 
 
+def test_gradients_benchmark_net_map_counts():
+    # the benchmark's net (16 / 32 / 128 / 64 maps, context 17) on a volume the oracle finishes in seconds:
+    # the same kernels and launch forms as bench.py's training step, several column tiles and a ragged tail
+    layers = S.sknet3d_layers(classes=2)
+    net, *_ = run_training(layers, 1, 2, (25, 40, 150), 650)
+    net.close()
+
+
 def test_gradients_converted_net_unmasked_and_wider_pool():
     layers = [S.conv(8, 3, 1), S.pool(3, 1), S.conv(12, 2, 3), S.conv(10, 1, 1), S.conv(2, 1, 1, relu=False)]
     net, *_ = run_training(layers, 1, 2, (12, 20, 70), 620, masked=False)
