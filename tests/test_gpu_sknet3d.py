@@ -80,6 +80,24 @@ def test_general_pools_and_downsampling_pool():
     assert prob.shape == (3, 2, 6, 9)
 
 
+def test_smallest_volume_single_output_voxel():
+    # exactly context + 1 per axis: one labelled voxel, every layer's tiles are ragged
+    layers = S.sknet3d_layers(classes=2, maps=(6, 8, 16, 8))
+    prob = check_layers(layers, 3, 2, (18, 18, 18), 550)
+    assert prob.shape == (1, 2, 1, 1)
+
+
+def test_pool_first_pointwise_net_and_wide_kernel():
+    # a pool as the first layer (reads the caller's volume), 1x1x1 convolutions only after it; then a 5^3 kernel
+    # (the generic convolution kernel, a launch per depth tap at d = 2)
+    layers = [S.pool(2, 1), S.conv(7, 1, 1), S.conv(3, 1, 1, relu=False)]
+    prob = check_layers(layers, 4, 3, (6, 9, 70), 551)
+    assert prob.shape == (5, 3, 8, 69)
+    layers = [S.conv(6, 5, 1), S.conv(4, 5, 2), S.conv(2, 1, 1, relu=False)]
+    prob = check_layers(layers, 2, 2, (15, 20, 30), 552)
+    assert prob.shape == (3, 2, 8, 18)
+
+
 def test_fused_head_plan_matches_oracle():
     # an inference plan runs "1x1x1 conv + ReLU, 1x1x1 conv, softmax" as one kernel
     from paper_1509_03371_amd import binding as B
