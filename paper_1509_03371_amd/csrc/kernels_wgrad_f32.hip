@@ -509,12 +509,33 @@ __global__ void __launch_bounds__(256) bias_grad_kernel(const float *__restrict_
     if (threadIdx.x == 0) part[(long)o * slices + sl] = sh[0] + sh[1] + sh[2] + sh[3];
 }
 
-static void wgrad_tiling(int c_out, int c_in, int k, int &MTo, int &NTk, int &MB, int &NB)
+// Tiles per workgroup: MB map tiles x 4*NB column tiles (NB per wave).  Tiles beyond the gradient's extent are
+// multiplied like the others, so the counts are chosen to leave few of them.
+static void wgrad_tiling(int c_out, int c_in, int k, bool f32, int &MTo, int &NTk, int &MB, int &NB)
 {
     MTo = (c_out + 15) / 16;
     NTk = (c_in * k * k + 15) / 16;
     MB = MTo == 1 ? 1 : (MTo % 3 == 0 ? 3 : 4);
     NB = NTk >= 48 ? 12 : (NTk > 4 ? 4 : 1);
+    if (!f32) return;
+    // fp32 storage (MFMA 16x16x4: the multiplications are a large share of the time): fewer map tiles per
+    // workgroup where that saves a quarter or more of the padded tiles (2 for 32 maps, 3 for 80); a smaller gain
+    // does not pay for the lower reuse of the staged input rows (13 map tiles: 4.09 ms with 4, 4.21 ms with 2)
+    if (MTo > 1) {
+        const int pad0 = (MTo + MB - 1) / MB * MB;
+        int best = MB, pad = pad0;
+        for (int cand = 4; cand >= 2; --cand) {
+            const int p = (MTo + cand - 1) / cand * cand;
+            if (4 * p <= 3 * pad0 && p < pad) { pad = p; best = cand; }
+        }
+        MB = best;
+    }
+    // column tiles: groups of at most 16, all of the same size (18 tiles are 2 x 12 slots, not 16 + 16; 36 are
+    // 3 x 12); with three map tiles and 48 or more column tiles one group of 48 stays (the 48-map SK-Net)
+    if (!(MB == 3 && NTk >= 48) && NTk > 4) {
+        const int ngroups = (NTk + 15) / 16, per = (NTk + ngroups - 1) / ngroups;
+        NB = (per + 3) / 4;
+    }
 }
 
 // Private copies of a gradient.  A small gradient (one tile group: the 48x768 of the BASELINE nets)
@@ -533,10 +554,14 @@ static int wgrad_max_copies(int groups)
 
 size_t wgrad_f32_scratch_floats(int c_out, int c_in, int k)
 {
+    // private dW copies (the larger of what the fp32 and the 16-bit tiling ask for), then the bias partials
+    // (8 * ceil(c_out/8) maps x BG_SLICES)
     int MTo, NTk, MB, NB;
-    wgrad_tiling(c_out, c_in, k, MTo, NTk, MB, NB);
-    // private dW copies, then the bias partials (8 * ceil(c_out/8) maps x BG_SLICES)
-    return (size_t)wgrad_max_copies(wgrad_tile_groups(MTo, NTk, MB, NB)) * MTo * 16 * NTk * 16 + (size_t)(c_out + 7) / 8 * 8 * BG_SLICES;
+    wgrad_tiling(c_out, c_in, k, false, MTo, NTk, MB, NB);
+    int copies = wgrad_max_copies(wgrad_tile_groups(MTo, NTk, MB, NB));
+    wgrad_tiling(c_out, c_in, k, true, MTo, NTk, MB, NB);
+    copies = std::max(copies, wgrad_max_copies(wgrad_tile_groups(MTo, NTk, MB, NB)));
+    return (size_t)copies * MTo * 16 * NTk * 16 + (size_t)(c_out + 7) / 8 * 8 * BG_SLICES;
 }
 
 template <int MB, int NB, int DT>
@@ -591,13 +616,12 @@ static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, floa
     a.Ho = H - (k - 1) * d; a.Wo = W - (k - 1) * d;
     if (a.Ho < 1 || a.Wo < 1) return hipErrorInvalidValue;
     int MB, NB;
-    wgrad_tiling(c_out, c_in, k, a.MTo, a.NTk, MB, NB);
-    // fp32 storage, four map tiles: 16 column tiles per workgroup keep the kernel within half the register file,
-    // so two workgroups share a CU and one stages while the other multiplies; with 48 column tiles (192
-    // accumulator registers) only one fits.  Measured on the training steps: U-Net 22.4 -> 20.1 ms, USK-Net
+    wgrad_tiling(c_out, c_in, k, DT == 0, a.MTo, a.NTk, MB, NB);
+    // fp32 storage: at most 16 column tiles per workgroup keep the kernel within half the register file, so two
+    // workgroups share a CU and one stages while the other multiplies; with 48 column tiles (192 accumulator
+    // registers at four map tiles) only one fits.  Measured on the training steps: U-Net 22.4 -> 20.1 ms, USK-Net
     // 49.3 -> 41.8 ms.  (More tile groups mean fewer private copies, so the scratch sized for 48 still suffices;
     // with three map tiles the single 48-tile group stays faster: 4.09 against 4.38 ms on the 48-map SK-Net.)
-    if (DT == 0 && NB == 12 && MB == 4) NB = 4;
     a.xsegs = (a.Wo + WG_SEG - 1) / WG_SEG;
     a.total_segs = a.xsegs * a.Ho * n;
     const int PW = WG_SEG + (k - 1) * d;
@@ -609,7 +633,7 @@ static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, floa
     };
     if (DT == 0 && PW > 192) return hipErrorInvalidValue;            // the staging loop covers three 64-column groups per row
     if (DT == 0)
-        while (NB > 1 && f32_smem(NB) > 150 * 1024) NB = NB == 12 ? 4 : 1;
+        while (NB > 1 && f32_smem(NB) > 150 * 1024) NB = NB == 12 ? 4 : NB - 1;
     // 16-bit storage (and a window of at most 128 columns): the 16-bit matrix path
     const bool h_path = DT != 0 && PW <= 128;
     a.xpitch = h_path ? (PW + 7) / 8 * 8 + 8 : (PW + 31) / 32 * 32 + 4;
@@ -642,6 +666,12 @@ static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, floa
         SK_WG_CASE(1, 1) SK_WG_CASE(1, 4) SK_WG_CASE(1, 12)
         SK_WG_CASE(3, 1) SK_WG_CASE(3, 4) SK_WG_CASE(3, 12)
         SK_WG_CASE(4, 1) SK_WG_CASE(4, 4) SK_WG_CASE(4, 12)
+        if constexpr (DT == 0) {   // the tile counts only the fp32 tiling asks for
+            SK_WG_CASE(1, 2) SK_WG_CASE(1, 3)
+            SK_WG_CASE(2, 1) SK_WG_CASE(2, 2) SK_WG_CASE(2, 3) SK_WG_CASE(2, 4)
+            SK_WG_CASE(3, 2) SK_WG_CASE(3, 3)
+            SK_WG_CASE(4, 2) SK_WG_CASE(4, 3)
+        }
 #undef SK_WG_CASE
     }
     if (e != hipSuccess) return e;
