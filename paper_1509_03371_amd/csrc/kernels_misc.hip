@@ -183,16 +183,18 @@ __global__ void __launch_bounds__(256) maxpool3d_f32_kernel(const float *__restr
 // serves the windows of the outputs z - d and z, so each is formed once: four loads per output, not eight.
 // Winner codes follow the (a, i, j) scan: 0..3 inside slice z, 4..7 inside slice z + d, which only wins
 // when strictly greater.
-// grid: x = (residue class and chain segment, column block), y = output row, z = map
+// A workgroup takes 256 consecutive positions of the Ho x Wo plane (rows of 136 outputs would leave half of a
+// 256-thread row block idle).  grid: x = (residue class and chain segment, plane block), y = map
 template <bool TAP>
 __global__ void __launch_bounds__(256) maxpool3d_k2_chain_f32_kernel(const float *__restrict__ x, float *__restrict__ y,
                                                                      uint8_t *__restrict__ tap, int C, int H, int W, int Do, int Ho,
-                                                                     int Wo, int d, int M, int nseg, int xblocks)
+                                                                     int Wo, int d, int M, int nseg, int pblocks)
 {
-    const int chain = blockIdx.x / xblocks, xb = blockIdx.x - chain * xblocks;
+    const int chain = blockIdx.x / pblocks, pb = blockIdx.x - chain * pblocks;
     const int phase = chain / nseg, seg = chain - phase * nseg;
-    const int xx = xb * 256 + threadIdx.x, yy = blockIdx.y, c = blockIdx.z;
-    if (xx >= Wo || phase >= Do) return;
+    const int pos = pb * 256 + threadIdx.x, c = blockIdx.y;
+    if (pos >= Ho * Wo || phase >= Do) return;
+    const int yy = pos / Wo, xx = pos - yy * Wo;
     const int links = (Do - phase + d - 1) / d;
     const int m0 = seg * M, m1 = min(links, m0 + M);
     if (m0 >= m1) return;
@@ -239,14 +241,15 @@ hipError_t launch_maxpool3d_f32(const float *x, float *y, uint8_t *tap, int C, i
     const int xblocks = (Wo + 255) / 256;
     if (k == 2 && s == 1) {
         const int M = 16, links = (Do + d - 1) / d, nseg = (links + M - 1) / M;
-        const long gx = (long)d * nseg * xblocks;
-        if (gx <= 0x7fffffffL) {
+        const long plane = (long)Ho * Wo, pblocks = (plane + 255) / 256;
+        const long gx = (long)d * nseg * pblocks;
+        if (gx <= 0x7fffffffL && plane <= 0x7fffffffL) {
             if (tap)
-                hipLaunchKernelGGL(maxpool3d_k2_chain_f32_kernel<true>, dim3((unsigned)gx, Ho, C), dim3(256), 0, stream, x, y, tap, C, H, W,
-                                   Do, Ho, Wo, d, M, nseg, xblocks);
+                hipLaunchKernelGGL(maxpool3d_k2_chain_f32_kernel<true>, dim3((unsigned)gx, C), dim3(256), 0, stream, x, y, tap, C, H, W,
+                                   Do, Ho, Wo, d, M, nseg, (int)pblocks);
             else
-                hipLaunchKernelGGL(maxpool3d_k2_chain_f32_kernel<false>, dim3((unsigned)gx, Ho, C), dim3(256), 0, stream, x, y, tap, C, H, W,
-                                   Do, Ho, Wo, d, M, nseg, xblocks);
+                hipLaunchKernelGGL(maxpool3d_k2_chain_f32_kernel<false>, dim3((unsigned)gx, C), dim3(256), 0, stream, x, y, tap, C, H, W,
+                                   Do, Ho, Wo, d, M, nseg, (int)pblocks);
             return hipGetLastError();
         }
     }
@@ -259,14 +262,15 @@ hipError_t launch_maxpool3d_f32(const float *x, float *y, uint8_t *tap, int C, i
 // Gather form of the 3-D pool gradient (s = 1): input sample (z, u, v) can only have won the windows whose
 // output sits at (z - a*d, u - i*d, v - j*d); it collects dY from those whose recorded code is (a*k + i)*k + j.
 // relu_src (optional, laid out like dx): the result is zeroed where relu_src <= 0.  No atomics.
-// grid: x = (input slice, column block), y = input row, z = map
+// grid: x = (input slice, block of 256 consecutive positions of the H x W plane), y = map
 __global__ void __launch_bounds__(256) maxpool3d_bwd_f32_kernel(const float *__restrict__ dy, const uint8_t *__restrict__ tap,
                                                                 const float *__restrict__ relu_src, float *__restrict__ dx, int C,
-                                                                int H, int W, int Do, int Ho, int Wo, int k, int d, int xblocks)
+                                                                int H, int W, int Do, int Ho, int Wo, int k, int d, int pblocks)
 {
-    const int z = blockIdx.x / xblocks, xb = blockIdx.x - z * xblocks;
-    const int v = xb * 256 + threadIdx.x, u = blockIdx.y, c = blockIdx.z;
-    if (v >= W) return;
+    const int z = blockIdx.x / pblocks, pb = blockIdx.x - z * pblocks;
+    const int pos = pb * 256 + threadIdx.x, c = blockIdx.y;
+    if (pos >= H * W) return;
+    const int u = pos / W, v = pos - u * W;
     float sum = 0.f;
     for (int a = 0; a < k; ++a) {
         const int zo = z - a * d;
@@ -292,10 +296,10 @@ hipError_t launch_maxpool3d_bwd_f32(const float *dy, const uint8_t *tap, const f
 {
     if (C < 1 || C > 65535 || H < 1 || H > 65535 || k < 1 || k > 6) return hipErrorInvalidValue;
     if (Do != D - (k - 1) * d || Ho != H - (k - 1) * d || Wo != W - (k - 1) * d || Do < 1 || Ho < 1 || Wo < 1) return hipErrorInvalidValue;
-    const int xblocks = (W + 255) / 256;
-    if ((long)D * xblocks > 0x7fffffffL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(maxpool3d_bwd_f32_kernel, dim3((unsigned)(D * xblocks), H, C), dim3(256), 0, stream, dy, tap, relu_src, dx, C, H, W,
-                       Do, Ho, Wo, k, d, xblocks);
+    const long pblocks = ((long)H * W + 255) / 256;
+    if ((long)H * W > 0x7fffffffL || (long)D * pblocks > 0x7fffffffL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(maxpool3d_bwd_f32_kernel, dim3((unsigned)(D * pblocks), C), dim3(256), 0, stream, dy, tap, relu_src, dx, C, H, W,
+                       Do, Ho, Wo, k, d, (int)pblocks);
     return hipGetLastError();
 }
 
