@@ -33,7 +33,7 @@ constexpr int CONV_CC = 4;    // input maps per K chunk
 // load awaited between stores makes that wait cover every store before it.  The bias is therefore
 // fetched in one batch and awaited once; the store loop without a mask then contains no load at
 // all, and the masked variant fetches the masks of a whole pixel tile before its first store.
-template <int NT, int RW>
+template <int NT, int RW, int XN = 4>
 __device__ __forceinline__ void store_outputs(const ConvF32Args &a, floatx4 (&acc)[RW][4][NT], int b, int o_first,
                                               int oy_first, int d, int ox_first)
 {
@@ -63,7 +63,7 @@ __device__ __forceinline__ void store_outputs(const ConvF32Args &a, floatx4 (&ac
             if (oy >= a.Ho) continue;
             const long rowbase = (((long)b * a.out_maps + a.o_off + o_first) * a.OH + (long)oy * a.oy_mul + a.oy_off) * a.OW + a.ox_off;
 #pragma unroll
-            for (int xt = 0; xt < 4; ++xt) {
+            for (int xt = 0; xt < XN; ++xt) {
                 const int ox = ox_first + xt * 16;
                 if (ox >= a.Wo) continue;
                 const long pbase = rowbase + (long)ox * a.ox_mul;
@@ -109,7 +109,7 @@ __device__ __forceinline__ void store_outputs(const ConvF32Args &a, floatx4 (&ac
                 if (oy >= a.Ho) continue;
                 const long rowbase = (((long)b * a.out_maps + a.o_off + om) * a.OH + (long)oy * a.oy_mul + (tap >> 1)) * a.OW + (tap & 1);
 #pragma unroll
-                for (int xt = 0; xt < 4; ++xt) {
+                for (int xt = 0; xt < XN; ++xt) {
                     const int ox = ox_first + xt * 16;
                     if (ox >= a.Wo) continue;
                     const long pbase = rowbase + (long)ox * a.ox_mul;
@@ -261,9 +261,13 @@ static hipError_t launch_conv_f32_t(const ConvF32Args &a, hipStream_t stream)
 // flight; they are written to LDS after the loop.  Wave w stages input maps c0 + w, c0 + w + 4, ...
 // of the chunk (CC/4 maps, RR rows each, NCG groups of 64 columns), so every count is a compile-time
 // constant and the prefetched values stay in registers.
-template <int NT, int RW, int KS, int CC, int NCG, bool PADZ>
+// XNT = 16-column groups of a tile that are multiplied and stored.  A launch covers the gx column tiles from
+// bx0 on: the last column tile of a map whose width is no multiple of 64 can run as a launch of its own with
+// XNT = 1 or 2 (a test inside the K loop breaks its schedule, and a second K loop inside one kernel costs the
+// registers of a workgroup per CU: both measured).
+template <int NT, int RW, int KS, int CC, int NCG, bool PADZ, int XNT = 4>
 __global__ __launch_bounds__(256) void conv_f32_pf_kernel(ConvF32Args a, int tiles_hi, int tiles_lo,
-                                                          int rem, int nblocks, int gx, int gy, int total_tiles)
+                                                          int rem, int nblocks, int gx, int gy, int total_tiles, int bx0)
 {
     extern __shared__ float smem[];
     constexpr int R = 4 * RW, WN = NT * 16, RR = R + KS - 1, KK2 = KS * KS, KC = CC * KK2, CPW = CC / 4;
@@ -340,7 +344,7 @@ __global__ __launch_bounds__(256) void conv_f32_pf_kernel(ConvF32Args a, int til
         ty = b2 % tiles_lo;
     }
     const int b = bz / nblocks, nb = bz - b * nblocks;
-    const int x0 = bx * CONV_TX;
+    const int x0 = (bx0 + bx) * CONV_TX;
 
     floatx4 acc[RW][4][NT];
 #pragma unroll
@@ -484,12 +488,42 @@ __global__ __launch_bounds__(256) void conv_f32_pf_kernel(ConvF32Args a, int til
             if (a.Wo - x0 <= 32) kloop(std::integral_constant<int, 2>{});
             else kloop(std::integral_constant<int, 4>{});
         } else {
-            kloop(std::integral_constant<int, 4>{});
+            kloop(std::integral_constant<int, XNT>{});
         }
     }
 
-    store_outputs<NT, RW>(a, acc, b, nb * WN + 4 * g, py + d * (ty * R + wave * RW), d, x0 + l16);
+    store_outputs<NT, RW, XNT>(a, acc, b, nb * WN + 4 * g, py + d * (ty * R + wave * RW), d, x0 + l16);
     }
+}
+
+// one launch over the gxl column tiles from bx0 on
+template <int NT, int RW, int KS, int CC, int NCG, bool PADZ, int XNT>
+static hipError_t launch_conv_f32_pf_part(const ConvF32Args &a, size_t smem, int tiles_hi, int tiles_lo, int rem, int nblocks, int gxl,
+                                          int gy, int bx0, hipStream_t stream)
+{
+    static bool attr_set = false;
+    if (smem > 48 * 1024 && !attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_f32_pf_kernel<NT, RW, KS, CC, NCG, PADZ, XNT>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const long total = (long)gxl * gy * a.n * nblocks;
+    if (gxl <= 0 || gy <= 0 || total <= 0 || total > 0x7fffffffL) return hipErrorInvalidValue;
+    static int slots = 0;                  // workgroups of this kernel that are resident at once
+    if (slots == 0) {
+        int dev = 0, cus = 0, per_cu = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e == hipSuccess)
+            e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, conv_f32_pf_kernel<NT, RW, KS, CC, NCG, PADZ, XNT>, 256, smem);
+        if (e != hipSuccess) return e;
+        slots = cus * (per_cu > 0 ? per_cu : 1);
+    }
+    const int blocks = (int)(total < slots ? total : slots);
+    hipLaunchKernelGGL((conv_f32_pf_kernel<NT, RW, KS, CC, NCG, PADZ, XNT>), dim3(blocks), dim3(256), smem, stream, a, tiles_hi,
+                       tiles_lo > 0 ? tiles_lo : 1, rem, nblocks, gxl, gy, (int)total, bx0);
+    return hipGetLastError();
 }
 
 template <int NT, int RW, int KS, int CC, int NCG, bool PADZ>
@@ -502,34 +536,25 @@ static hipError_t launch_conv_f32_pf_z(const ConvF32Args &a, hipStream_t stream)
     if ((long)KC * a.n_pad >= (1L << 29)) return hipErrorInvalidValue;  // and inside a weight slab
     const size_t smem = sizeof(float) * ((size_t)CC * RR * PITCH + (size_t)KC * WN);
     if (smem > 150 * 1024) return hipErrorInvalidValue;
-    static bool attr_set = false;
-    if (smem > 48 * 1024 && !attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_f32_pf_kernel<NT, RW, KS, CC, NCG, PADZ>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
     const int q = a.Ho / a.d, rem = a.Ho % a.d;
     const int tiles_hi = (q + 1 + R - 1) / R, tiles_lo = (q + R - 1) / R;
     const int gy = rem * tiles_hi + (a.d - rem) * tiles_lo;
     const int nblocks = (a.n_pad / 16 + NT - 1) / NT;
     const int gx = (a.Wo + CONV_TX - 1) / CONV_TX;
-    const long total = (long)gx * gy * a.n * nblocks;
-    if (gx <= 0 || gy <= 0 || total <= 0 || total > 0x7fffffffL) return hipErrorInvalidValue;
-    static int slots = 0;                  // workgroups of this kernel that are resident at once
-    if (slots == 0) {
-        int dev = 0, cus = 0, per_cu = 0;
-        hipError_t e = hipGetDevice(&dev);
-        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e == hipSuccess)
-            e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, conv_f32_pf_kernel<NT, RW, KS, CC, NCG, PADZ>, 256, smem);
-        if (e != hipSuccess) return e;
-        slots = cus * (per_cu > 0 ? per_cu : 1);
+    // The last column tile of a map whose width is no multiple of 64 holds output columns in only some of its
+    // four 16-column groups.  Where that column alone has enough tiles to fill the GPU several times (batches of
+    // slices of a 3-D volume, many-map layers), it runs as a launch of its own that multiplies one or two groups.
+    if constexpr ((KS == 3 && CC == 4) || KS == 8) {
+        const int groups = (a.Wo - (gx - 1) * CONV_TX + 15) / 16;
+        const long column = (long)gy * a.n * nblocks;
+        if (gx >= 2 && groups <= 2 && column >= 512) {
+            hipError_t e = launch_conv_f32_pf_part<NT, RW, KS, CC, NCG, PADZ, 4>(a, smem, tiles_hi, tiles_lo, rem, nblocks, gx - 1, gy, 0, stream);
+            if (e != hipSuccess) return e;
+            if (groups == 1) return launch_conv_f32_pf_part<NT, RW, KS, CC, NCG, PADZ, 1>(a, smem, tiles_hi, tiles_lo, rem, nblocks, 1, gy, gx - 1, stream);
+            return launch_conv_f32_pf_part<NT, RW, KS, CC, NCG, PADZ, 2>(a, smem, tiles_hi, tiles_lo, rem, nblocks, 1, gy, gx - 1, stream);
+        }
     }
-    const int blocks = (int)(total < slots ? total : slots);
-    hipLaunchKernelGGL((conv_f32_pf_kernel<NT, RW, KS, CC, NCG, PADZ>), dim3(blocks), dim3(256), smem, stream, a, tiles_hi,
-                       tiles_lo > 0 ? tiles_lo : 1, rem, nblocks, gx, gy, (int)total);
-    return hipGetLastError();
+    return launch_conv_f32_pf_part<NT, RW, KS, CC, NCG, PADZ, 4>(a, smem, tiles_hi, tiles_lo, rem, nblocks, gx, gy, 0, stream);
 }
 
 template <int NT, int RW, int KS, int CC, int NCG>
