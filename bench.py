@@ -30,8 +30,8 @@ METRIC = "labelled pixels/sec SK-Net fwd (and fwd+bwd) 1 GPU; conv % MFMA peak"
 # read for stream_copy_kernel on 1 GiB (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); the runs and their
 # figures are in profiles/sknet_c{2,3}_forward_hbm_traffic_pmc.txt and
 # profiles/stream_copy_1gib_pmc_calibration.txt.  KiB: (fetch x 2, write).
-TRAFFIC_KIB = {"c2": (2.0 * (35718.7 + 34222.3 + 30790.5) / 3, (77704.1 + 70509.3 + 58015.5) / 3),
-               "c3": (2.0 * (480107.9 + 473247.5 + 454780.7) / 3, (870648.4 + 846171.7 + 798768.0) / 3)}
+TRAFFIC_KIB = {"c2": (2.0 * (35765.2 + 34265.0 + 30821.7) / 3, (78827.5 + 71135.3 + 58340.2) / 3),
+               "c3": (2.0 * (479830.4 + 473130.7 + 454601.8) / 3, (870701.7 + 846215.4 + 798768.0) / 3)}
 
 
 def build_net(B, S, dtype, n, H, W, training):
@@ -416,7 +416,7 @@ def main():
                          "traffic_unit": "bytes beyond L2 per launch (read + written), from profiles/",
                          "algorithmic_bytes": int(r["conv_alg_bytes"]),
                          "kernel": "48->48 k4 SK convolutions at d=2,4,8 (%s)"
-                                   % ("conv_f32_pf_kernel<3,1,4,4,2,false>" if dtype == "f32" else "conv_h_ring_kernel<bf16,4,3,MAP4,8,false,3,true,4>")},
+                                   % ("conv_f32_pf_kernel<3,1,4,4,2,false,4>" if dtype == "f32" else "conv_h_ring_kernel<bf16,4,3,MAP4,8,false,3,true,4>")},
             "forward_tflops": round(r["forward_tflops"], 2),
             "pool_gbs": round(r["pool_gbs"], 1), "pool_frac_of_hbm_peak": round(r["pool_gbs"] / HBM_PEAK_GBS, 4),
             "step_ms": r["step_ms"],
