@@ -77,6 +77,16 @@ def test_gradients_benchmark_net_map_counts():
     net.close()
 
 
+@pytest.mark.parametrize("width", [88, 74])
+def test_ragged_last_column_tile_as_its_own_launch(width):
+    # 42 slices x 14 row tiles: the last column of the tile grid has more than 512 tiles, and the maps are 86 / 84
+    # (width 88: two 16-column groups) or 72 / 70 wide (width 74: one group), so forward, data gradient (with the
+    # ReLU mask fused) and their narrow launches all run; compared with the oracle like every other case
+    layers = [S.conv(16, 3, 1), S.conv(8, 3, 1), S.conv(2, 1, 1, relu=False)]
+    net, *_ = run_training(layers, 1, 2, (44, 108, width), 660 + width)
+    net.close()
+
+
 def test_gradients_converted_net_unmasked_and_wider_pool():
     layers = [S.conv(8, 3, 1), S.pool(3, 1), S.conv(12, 2, 3), S.conv(10, 1, 1), S.conv(2, 1, 1, relu=False)]
     net, *_ = run_training(layers, 1, 2, (12, 20, 70), 620, masked=False)
