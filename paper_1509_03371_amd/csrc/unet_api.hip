@@ -774,6 +774,20 @@ sk_status unet_sgd_step(unet_t *net, float lr, float momentum, float weight_deca
     }
     for (auto &u : net->ups) SK_TRY(push(u.cat.w_dev, u.cat.dw, u.cat.vw, u.cat.wcount()));
     if (sb.n > 0) SK_HIP(sk::launch_sgd_batch_f32(sb, lr, momentum, weight_decay, stream));
+    // the packed forms of every tensor, BATCH_MAX per launch (training plans are fp32)
+    sk::PackF32Job jobs[sk::BATCH_MAX];
+    int nj = 0;
+    auto pack = [&](const ConvParams &c, bool bwd) -> sk_status {
+        for (int f = 0; f < (bwd && c.wp_bwd ? 2 : 1); ++f) {
+            jobs[nj++] = f == 0 ? sk::PackF32Job{c.w_dev, c.wp_fwd, c.c_out, c.c_in, c.k, 0, c.rows_fwd, c.n_pad}
+                                : sk::PackF32Job{c.w_dev, c.wp_bwd, c.c_out, c.c_in, c.k, 1, c.rows_bwd, c.n_pad_bwd};
+            if (nj == sk::BATCH_MAX) {
+                SK_HIP(sk::launch_pack_weights_f32_batch(jobs, nj, stream));
+                nj = 0;
+            }
+        }
+        return SK_OK;
+    };
     for (auto &u : net->ups) {
         // the shared bias (its momentum lives in the stacked form's first c_out entries), then the taps' weights
         SK_HIP(sk::launch_up_bias_sgd_f32(u.tap[0].b_dev, u.tap[1].b_dev, u.tap[2].b_dev, u.tap[3].b_dev, u.cat.db,
@@ -782,11 +796,14 @@ sk_status unet_sgd_step(unet_t *net, float lr, float momentum, float weight_deca
             SK_HIP(hipMemcpyAsync(u.cat.b_dev + (size_t)t * u.c_out, u.tap[0].b_dev, sizeof(float) * u.c_out, hipMemcpyDeviceToDevice, stream));
             SK_HIP(hipMemcpyAsync(u.tap[t].w_dev, u.cat.w_dev + (size_t)t * u.c_out * u.c_in, sizeof(float) * u.c_out * u.c_in,
                                   hipMemcpyDeviceToDevice, stream));
-            SK_TRY(repack_conv(u.tap[t], false, net->dtype, stream));
         }
-        SK_TRY(repack_conv(u.cat, true, net->dtype, stream));
     }
-    for (auto &c : net->convs) SK_TRY(repack_conv(c, true, net->dtype, stream));
+    for (auto &u : net->ups) {
+        for (int t = 0; t < 4; ++t) SK_TRY(pack(u.tap[t], false));
+        SK_TRY(pack(u.cat, true));
+    }
+    for (auto &c : net->convs) SK_TRY(pack(c, true));
+    if (nj > 0) SK_HIP(sk::launch_pack_weights_f32_batch(jobs, nj, stream));
     return SK_OK;
 }
 
