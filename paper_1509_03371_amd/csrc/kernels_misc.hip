@@ -339,6 +339,26 @@ __global__ void place_tap_f32_kernel(const float *src, float *dst, long maps, in
     }
 }
 
+__global__ void place_taps_f32_kernel(const float *src, float *dst, int c_out, int C, int k)
+{
+    const int kk = k * k;
+    const long total = (long)c_out * C * k * kk;
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
+        const int r = (int)(q % kk);
+        long t = q / kk;
+        const int c = (int)(t % C);
+        t /= C;
+        const int a = (int)(t % k), o = (int)(t / k);
+        dst[(((long)o * C + c) * k + a) * kk + r] = src[q];
+    }
+}
+
+hipError_t launch_place_taps_f32(const float *src, float *dst, int c_out, int C, int k, hipStream_t stream)
+{
+    hipLaunchKernelGGL(place_taps_f32_kernel, dim3(grid_for((long)c_out * C * k * k * k)), dim3(256), 0, stream, src, dst, c_out, C, k);
+    return hipGetLastError();
+}
+
 hipError_t launch_place_tap_f32(const float *src, float *dst, long maps, int k, int a, hipStream_t stream)
 {
     hipLaunchKernelGGL(place_tap_f32_kernel, dim3(grid_for(maps * k * k)), dim3(256), 0, stream, src, dst, maps, k, a);

@@ -44,6 +44,11 @@ struct WgradArgs {
     int MTo, NTk;          // 16-wide tiles over output maps / over (c,i,j)
     int xsegs, total_segs;
     int xpitch;            // LDS pitch of an input row
+    // fp32 storage only: distance in floats between the inputs of consecutive images (0 = c_in*H*W), and input maps
+    // in groups of 2^grp_shift consecutive planes with grp_skip more floats between groups (the depth taps of a 3-D
+    // convolution: see launch_conv_f32); grp_shift = 31: no groups
+    long x_bstride, grp_skip;
+    int grp_shift;
 };
 
 template <int MB, int NB, int DT>
@@ -125,7 +130,7 @@ __global__ __launch_bounds__(256, (DT == 0 && MB * NB <= 16) ? 2 : 1) void wgrad
             int row = wave + 4 * (bat * SU + u);
             row = row < xrows ? row : xrows - 1;
             const int c = c_lo + row / k, i = row - (row / k) * k;
-            const float *src = xp + ((long)b * a.c_in + c) * xplane + (long)(y + i * d) * a.W;
+            const float *src = xp + (long)b * a.x_bstride + (long)c * xplane + (long)(c >> a.grp_shift) * a.grp_skip + (long)(y + i * d) * a.W;
 #pragma unroll
             for (int sv = 0; sv < SV; ++sv) {
                 const int xc = lane + 64 * sv;
@@ -608,9 +613,19 @@ static hipError_t launch_wgrad_h_rb(const WgradArgs &a, int MB, int NB, size_t s
 
 template <int DT>
 static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, float *db, float *scratch, int n, int c_in, int H,
-                                  int W, int c_out, int k, int d, hipStream_t stream)
+                                  int W, int c_out, int k, int d, hipStream_t stream, long x_bstride = 0, int grp_maps = 0,
+                                  long grp_skip = 0)
 {
     WgradArgs a;
+    a.x_bstride = x_bstride ? x_bstride : (long)c_in * H * W;
+    a.grp_shift = 31; a.grp_skip = 0;
+    if (grp_maps > 0) {
+        if (DT != 0 || (grp_maps & (grp_maps - 1)) != 0 || c_in % grp_maps != 0 || grp_skip < 0) return hipErrorInvalidValue;
+        a.grp_shift = __builtin_ctz((unsigned)grp_maps);
+        a.grp_skip = grp_skip;
+    } else if (DT != 0 && x_bstride != 0) {
+        return hipErrorInvalidValue;
+    }
     a.x = x; a.dy = dy; a.scratch = scratch;
     a.n = n; a.c_in = c_in; a.H = H; a.W = W; a.c_out = c_out; a.k = k; a.d = d;
     a.Ho = H - (k - 1) * d; a.Wo = W - (k - 1) * d;
@@ -702,6 +717,12 @@ hipError_t launch_wgrad_f32(const float *x, const float *dy, float *dw, float *d
                             hipStream_t stream)
 {
     return launch_wgrad_dt<0>(x, dy, dw, db, scratch, n, c_in, H, W, c_out, k, d, stream);
+}
+
+hipError_t launch_wgrad_f32_grouped(const float *x, const float *dy, float *dw, float *db, float *scratch, int n, int c_in, int H,
+                                    int W, int c_out, int k, int d, long x_bstride, int grp_maps, long grp_skip, hipStream_t stream)
+{
+    return launch_wgrad_dt<0>(x, dy, dw, db, scratch, n, c_in, H, W, c_out, k, d, stream, x_bstride, grp_maps, grp_skip);
 }
 
 // same gradient from 16-bit octet-layout activations (dtype 1 = bf16, 2 = fp16): the operands are

@@ -133,6 +133,11 @@ hipError_t launch_wgrad_f32(const float *x, const float *dy, float *dw, float *d
                             int n, int c_in, int H, int W, int c_out, int k, int d,
                             hipStream_t stream);
 
+// the same with the input addressed as launch_conv_f32 addresses it: images x_bstride floats apart (0 = c_in*H*W),
+// the c_in maps in groups of grp_maps (a power of two, or 0 = none) with grp_skip more floats between groups
+hipError_t launch_wgrad_f32_grouped(const float *x, const float *dy, float *dw, float *db, float *scratch, int n, int c_in, int H,
+                                    int W, int c_out, int k, int d, long x_bstride, int grp_maps, long grp_skip, hipStream_t stream);
+
 hipError_t launch_wgrad_h(const void *x, const void *dy, float *dw, float *db, float *scratch, int dtype,
                           int n, int c_in, int H, int W, int c_out, int k, int d, hipStream_t stream);
 
@@ -158,6 +163,8 @@ hipError_t launch_tap3d_to_index(const uint8_t *tap, int32_t *idx, int C, int Do
                                  hipStream_t stream);
 // dst[(m*k + a)*k*k + r] = src[m*k*k + r] for m < maps, r < k*k
 hipError_t launch_place_tap_f32(const float *src, float *dst, long maps, int k, int a, hipStream_t stream);
+// dst[((o*C + c)*k + a)*k*k + r] = src[((o*k + a)*C + c)*k*k + r]: a gradient whose input maps are (depth tap, map) pairs
+hipError_t launch_place_taps_f32(const float *src, float *dst, int c_out, int C, int k, hipStream_t stream);
 // packings of a 3-D kernel [c_out][C][k][k][k] for launch_conv_f32 (see kernels_conv_f32.hip)
 hipError_t launch_pack_weights3d_f32(const float *w3, float *wp, int c_out, int C, int k, int a0, int len, int flip_transpose, int rows,
                                      int n_pad, hipStream_t stream);

@@ -18,6 +18,7 @@
 // The 2-D kernels are used unchanged; nothing here is a separate 3-D multiplication.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <new>
 
 #include "sk_host.h"
@@ -45,6 +46,9 @@ struct Conv3 {
     float *w_dev = nullptr, *b_dev = nullptr;   // device master (b_dev: n_pad entries, zero padded)
     std::vector<TapRun> fwd, bwd;      // bwd: runs over the flipped taps, for the data gradient
     float *dw = nullptr, *db = nullptr, *vw = nullptr, *vb = nullptr, *dw_tap = nullptr;
+    // weight gradient of all depth taps in one launch: k > 1 and (d = 1, the tapped slices adjacent, or a power-of-two
+    // map count, which the kernel's grouped addressing needs)
+    bool wgrad_merged = false;
     long wcount() const { return (long)c_out * c_in * k * k * k; }
 };
 
@@ -110,7 +114,8 @@ sk_status alloc_conv3(Conv3 &c, bool training, bool needs_dgrad)
         SK_TRY(alloc_f(&c.db, c.c_out));
         SK_TRY(alloc_f(&c.vw, c.wcount()));
         SK_TRY(alloc_f(&c.vb, c.c_out));
-        SK_TRY(alloc_f(&c.dw_tap, (long)c.c_out * c.c_in * c.k * c.k));
+        c.wgrad_merged = c.k > 1 && (c.d == 1 || (c.c_in & (c.c_in - 1)) == 0);
+        SK_TRY(alloc_f(&c.dw_tap, (long)c.c_out * c.c_in * c.k * c.k * (c.wgrad_merged ? c.k : 1)));
         SK_HIP(hipMemset(c.vw, 0, sizeof(float) * c.wcount()));
         SK_HIP(hipMemset(c.vb, 0, sizeof(float) * c.c_out));
     }
@@ -409,7 +414,8 @@ sk_status sknet3d_plan(sknet3d_t *net, int32_t dz, int32_t h, int32_t w, int32_t
             hipError_t e = hipMalloc(reinterpret_cast<void **>(&net->tap[i]), (size_t)dims[i + 1].count());
             if (e != hipSuccess) st = fail(SK_ENOMEM, "plan: winner codes: %s", hipGetErrorString(e));
         } else {
-            const size_t s = sk::wgrad_f32_scratch_floats(l.c_out, dims[i].c, l.k);
+            // one launch over all depth taps (k * C input maps) or one per tap: the larger need
+            const size_t s = std::max(sk::wgrad_f32_scratch_floats(l.c_out, dims[i].c, l.k), sk::wgrad_f32_scratch_floats(l.c_out, l.k * dims[i].c, l.k));
             if (s > scratch) scratch = s;
         }
     }
@@ -501,10 +507,17 @@ sk_status sknet3d_backward(sknet3d_t *net, const int32_t *labels_dev, float *los
         float *dst = li > 0 ? gnext + (long)grad_pad(net, li - 1) * in.slice() : nullptr;
         if (l.kind == SK_CONV) {
             Conv3 &c = net->convs[net->conv_of_layer[li]];
-            for (int a = 0; a < l.k; ++a) {   // depth tap a: the input slices shifted by a*d against the output gradient
-                SK_HIP(sk::launch_wgrad_f32(net->act[li] + (long)a * l.d * in.slice(), g, c.dw_tap, a + 1 == l.k ? c.db : nullptr,
-                                            net->wgrad_scratch, out.dz, in.c, in.h, in.w, c.c_out, l.k, l.d, stream));
-                SK_HIP(sk::launch_place_tap_f32(c.dw_tap, c.dw, (long)c.c_out * c.c_in, l.k, a, stream));
+            if (c.wgrad_merged) {
+                // all depth taps in one launch: the (tap, map) pairs are the input maps, as in the forward pass
+                SK_HIP(sk::launch_wgrad_f32_grouped(net->act[li], g, c.dw_tap, c.db, net->wgrad_scratch, out.dz, l.k * in.c, in.h, in.w,
+                                                    c.c_out, l.k, l.d, in.slice(), l.d > 1 ? in.c : 0, (long)(l.d - 1) * in.slice(), stream));
+                SK_HIP(sk::launch_place_taps_f32(c.dw_tap, c.dw, c.c_out, c.c_in, l.k, stream));
+            } else {
+                for (int a = 0; a < l.k; ++a) {   // depth tap a: the input slices shifted by a*d against the output gradient
+                    SK_HIP(sk::launch_wgrad_f32(net->act[li] + (long)a * l.d * in.slice(), g, c.dw_tap, a + 1 == l.k ? c.db : nullptr,
+                                                net->wgrad_scratch, out.dz, in.c, in.h, in.w, c.c_out, l.k, l.d, stream));
+                    SK_HIP(sk::launch_place_tap_f32(c.dw_tap, c.dw, (long)c.c_out * c.c_in, l.k, a, stream));
+                }
             }
             if (li == 0) break;   // nothing below needs the volume's gradient
             if (pad > 0) {
