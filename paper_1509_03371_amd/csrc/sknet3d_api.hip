@@ -14,7 +14,8 @@
 // applied to the output gradient padded with zeros: rows and columns are padded by the 2-D kernel's own zero
 // padding, the (k-1)*d zero slices before and after are real memory (the gradient of a convolution's output is
 // written into the interior of a buffer whose border slices are cleared).  The weight gradient of depth tap a
-// is the 2-D weight gradient between the output gradient and the input slices shifted by a*d.
+// is the 2-D weight gradient between the output gradient and the input slices shifted by a*d; with a power-of-two
+// map count (or d = 1) all taps are one launch over the k*C (tap, map) input maps, else one launch per tap.
 // The 2-D kernels are used unchanged; nothing here is a separate 3-D multiplication.
 #include <hip/hip_runtime.h>
 
