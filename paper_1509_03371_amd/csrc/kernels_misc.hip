@@ -262,7 +262,11 @@ hipError_t launch_maxpool3d_f32(const float *x, float *y, uint8_t *tap, int C, i
 // Gather form of the 3-D pool gradient (s = 1): input sample (z, u, v) can only have won the windows whose
 // output sits at (z - a*d, u - i*d, v - j*d); it collects dY from those whose recorded code is (a*k + i)*k + j.
 // relu_src (optional, laid out like dx): the result is zeroed where relu_src <= 0.  No atomics.
+// K > 0: compile-time kernel size; the K^3 winner codes and gradients are then fetched unconditionally (addresses
+// of windows outside the output clamped to element 0) so that all loads are in flight together instead of one
+// dependent load per branch.  K = 0: any k, plain loops.
 // grid: x = (input slice, block of 256 consecutive positions of the H x W plane), y = map
+template <int K>
 __global__ void __launch_bounds__(256) maxpool3d_bwd_f32_kernel(const float *__restrict__ dy, const uint8_t *__restrict__ tap,
                                                                 const float *__restrict__ relu_src, float *__restrict__ dx, int C,
                                                                 int H, int W, int Do, int Ho, int Wo, int k, int d, int pblocks)
@@ -272,17 +276,37 @@ __global__ void __launch_bounds__(256) maxpool3d_bwd_f32_kernel(const float *__r
     if (pos >= H * W) return;
     const int u = pos / W, v = pos - u * W;
     float sum = 0.f;
-    for (int a = 0; a < k; ++a) {
-        const int zo = z - a * d;
-        if (zo < 0 || zo >= Do) continue;
-        for (int i = 0; i < k; ++i) {
-            const int yo = u - i * d;
-            if (yo < 0 || yo >= Ho) continue;
-            for (int j = 0; j < k; ++j) {
-                const int xo = v - j * d;
-                if (xo < 0 || xo >= Wo) continue;
-                const long q = (((long)zo * C + c) * Ho + yo) * Wo + xo;
-                if (tap[q] == (uint8_t)((a * k + i) * k + j)) sum += dy[q];
+    if constexpr (K > 0) {
+        long q[K * K * K];
+        bool ok[K * K * K];
+#pragma unroll
+        for (int t = 0; t < K * K * K; ++t) {
+            const int a = t / (K * K), i = (t / K) % K, j = t % K;
+            const int zo = z - a * d, yo = u - i * d, xo = v - j * d;
+            ok[t] = zo >= 0 && zo < Do && yo >= 0 && yo < Ho && xo >= 0 && xo < Wo;
+            q[t] = ok[t] ? (((long)zo * C + c) * Ho + yo) * Wo + xo : 0;
+        }
+        uint8_t code[K * K * K];
+        float g[K * K * K];
+#pragma unroll
+        for (int t = 0; t < K * K * K; ++t) code[t] = tap[q[t]];
+#pragma unroll
+        for (int t = 0; t < K * K * K; ++t) g[t] = dy[q[t]];
+#pragma unroll
+        for (int t = 0; t < K * K * K; ++t) sum += (ok[t] && code[t] == (uint8_t)t) ? g[t] : 0.f;
+    } else {
+        for (int a = 0; a < k; ++a) {
+            const int zo = z - a * d;
+            if (zo < 0 || zo >= Do) continue;
+            for (int i = 0; i < k; ++i) {
+                const int yo = u - i * d;
+                if (yo < 0 || yo >= Ho) continue;
+                for (int j = 0; j < k; ++j) {
+                    const int xo = v - j * d;
+                    if (xo < 0 || xo >= Wo) continue;
+                    const long qq = (((long)zo * C + c) * Ho + yo) * Wo + xo;
+                    if (tap[qq] == (uint8_t)((a * k + i) * k + j)) sum += dy[qq];
+                }
             }
         }
     }
@@ -298,8 +322,12 @@ hipError_t launch_maxpool3d_bwd_f32(const float *dy, const uint8_t *tap, const f
     if (Do != D - (k - 1) * d || Ho != H - (k - 1) * d || Wo != W - (k - 1) * d || Do < 1 || Ho < 1 || Wo < 1) return hipErrorInvalidValue;
     const long pblocks = ((long)H * W + 255) / 256;
     if ((long)H * W > 0x7fffffffL || (long)D * pblocks > 0x7fffffffL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(maxpool3d_bwd_f32_kernel, dim3((unsigned)(D * pblocks), C), dim3(256), 0, stream, dy, tap, relu_src, dx, C, H, W,
-                       Do, Ho, Wo, k, d, (int)pblocks);
+    if (k == 2)
+        hipLaunchKernelGGL(maxpool3d_bwd_f32_kernel<2>, dim3((unsigned)(D * pblocks), C), dim3(256), 0, stream, dy, tap, relu_src, dx, C,
+                           H, W, Do, Ho, Wo, k, d, (int)pblocks);
+    else
+        hipLaunchKernelGGL(maxpool3d_bwd_f32_kernel<0>, dim3((unsigned)(D * pblocks), C), dim3(256), 0, stream, dy, tap, relu_src, dx, C,
+                           H, W, Do, Ho, Wo, k, d, (int)pblocks);
     return hipGetLastError();
 }
 
