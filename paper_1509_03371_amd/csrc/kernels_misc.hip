@@ -396,21 +396,43 @@ hipError_t launch_place_tap_f32(const float *src, float *dst, long maps, int k, 
 // Gather form of the pool gradient: input sample (u, v) can only have won the windows whose
 // output sits at (u - i*d, v - j*d); it collects dY from those whose recorded tap is (i, j).
 // No atomics, so the result does not depend on scheduling.
-__global__ void maxpool_bwd_f32_kernel(const float *dy, const uint8_t *tap, const float *relu_src,
-                                       float *dx, int H, int W, int Ho, int Wo, int k, int d)
+// K > 0: compile-time kernel size, the K*K codes and gradients fetched together (windows outside the output read
+// element 0 and are discarded); K = 0: any k
+template <int K>
+__global__ void maxpool_bwd_f32_kernel(const float *__restrict__ dy, const uint8_t *__restrict__ tap, const float *__restrict__ relu_src,
+                                       float *__restrict__ dx, int H, int W, int Ho, int Wo, int k, int d)
 {
     const int v = blockIdx.x * blockDim.x + threadIdx.x, u = blockIdx.y;
     if (v >= W) return;
     const long p = blockIdx.z;
     float acc = 0.f;
-    for (int i = 0; i < k; ++i) {
-        const int yy = u - i * d;
-        if (yy < 0 || yy >= Ho) continue;
-        for (int j = 0; j < k; ++j) {
-            const int xx = v - j * d;
-            if (xx < 0 || xx >= Wo) continue;
-            const long o = (p * Ho + yy) * Wo + xx;
-            if (tap[o] == i * k + j) acc += dy[o];
+    if constexpr (K > 0) {
+        long o[K * K];
+        bool ok[K * K];
+#pragma unroll
+        for (int t = 0; t < K * K; ++t) {
+            const int yy = u - (t / K) * d, xx = v - (t % K) * d;
+            ok[t] = yy >= 0 && yy < Ho && xx >= 0 && xx < Wo;
+            o[t] = ok[t] ? (p * Ho + yy) * Wo + xx : 0;
+        }
+        uint8_t code[K * K];
+        float g[K * K];
+#pragma unroll
+        for (int t = 0; t < K * K; ++t) code[t] = tap[o[t]];
+#pragma unroll
+        for (int t = 0; t < K * K; ++t) g[t] = dy[o[t]];
+#pragma unroll
+        for (int t = 0; t < K * K; ++t) acc += (ok[t] && code[t] == (uint8_t)t) ? g[t] : 0.f;
+    } else {
+        for (int i = 0; i < k; ++i) {
+            const int yy = u - i * d;
+            if (yy < 0 || yy >= Ho) continue;
+            for (int j = 0; j < k; ++j) {
+                const int xx = v - j * d;
+                if (xx < 0 || xx >= Wo) continue;
+                const long o = (p * Ho + yy) * Wo + xx;
+                if (tap[o] == i * k + j) acc += dy[o];
+            }
         }
     }
     const long q = (p * H + u) * W + v;
@@ -423,8 +445,9 @@ hipError_t launch_maxpool_bwd_f32(const float *dy, const uint8_t *tap, const flo
                                   hipStream_t stream)
 {
     if (H > 65535 || planes > 65535) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(maxpool_bwd_f32_kernel, dim3((W + 255) / 256, H, planes), dim3(256), 0, stream, dy, tap,
-                       relu_src, dx, H, W, Ho, Wo, k, d);
+    const dim3 grid((W + 255) / 256, H, planes);
+    if (k == 2) hipLaunchKernelGGL(maxpool_bwd_f32_kernel<2>, grid, dim3(256), 0, stream, dy, tap, relu_src, dx, H, W, Ho, Wo, k, d);
+    else hipLaunchKernelGGL(maxpool_bwd_f32_kernel<0>, grid, dim3(256), 0, stream, dy, tap, relu_src, dx, H, W, Ho, Wo, k, d);
     return hipGetLastError();
 }
 
