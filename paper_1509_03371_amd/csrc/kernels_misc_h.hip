@@ -289,9 +289,11 @@ hipError_t launch_crop_copy_h(const void *src, void *dst, int n, int c8, int Hs,
 // Gather form of the pool gradient (s = 1): input unit (u, v) collects, per map, dY of the windows
 // whose recorded winner it is.  Sums are formed in fp32 and rounded once.  relu_src (optional,
 // same shape as dx) zeroes the result where the layer below produced a non-positive value.
-template <int DT>
-__global__ void maxpool_bwd_h_kernel(const uint4v *dy, const uint2v *tap, const uint4v *relu_src, uint4v *dx,
-                                     int H, int W, int Ho, int Wo, int k, int d)
+// K > 0: compile-time kernel size, the K*K code and gradient octets fetched together (windows outside the
+// output read unit 0 and are discarded); K = 0: any k.
+template <int DT, int K>
+__global__ void maxpool_bwd_h_kernel(const uint4v *__restrict__ dy, const uint2v *__restrict__ tap, const uint4v *__restrict__ relu_src,
+                                     uint4v *__restrict__ dx, int H, int W, int Ho, int Wo, int k, int d)
 {
     const int v = blockIdx.x * blockDim.x + threadIdx.x, u = blockIdx.y;
     if (v >= W) return;
@@ -299,6 +301,29 @@ __global__ void maxpool_bwd_h_kernel(const uint4v *dy, const uint2v *tap, const 
     float acc[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+    if constexpr (K > 0) {
+        long o[K * K];
+        bool ok[K * K];
+#pragma unroll
+        for (int t = 0; t < K * K; ++t) {
+            const int yy = u - (t / K) * d, xx = v - (t % K) * d;
+            ok[t] = yy >= 0 && yy < Ho && xx >= 0 && xx < Wo;
+            o[t] = ok[t] ? (p * Ho + yy) * Wo + xx : 0;
+        }
+        uint2v c[K * K];
+        uint4v g[K * K];
+#pragma unroll
+        for (int t = 0; t < K * K; ++t) c[t] = tap[o[t]];
+#pragma unroll
+        for (int t = 0; t < K * K; ++t) g[t] = dy[o[t]];
+#pragma unroll
+        for (int t = 0; t < K * K; ++t)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const unsigned code = (c[t][e >> 2] >> ((e & 3) * 8)) & 0xffu;
+                acc[e] += (ok[t] && code == (unsigned)t) ? up16<DT>(elem16(g[t], e)) : 0.f;
+            }
+    } else
     for (int i = 0; i < k; ++i) {
         const int yy = u - i * d;
         if (yy < 0 || yy >= Ho) continue;
@@ -334,14 +359,13 @@ hipError_t launch_maxpool_bwd_h(const void *dy, const void *tap, const void *rel
 {
     if (H > 65535 || planes8 > 65535) return hipErrorInvalidValue;
     const dim3 grid((W + 255) / 256, H, (unsigned)planes8);
-    if (dtype == 1)
-        hipLaunchKernelGGL(maxpool_bwd_h_kernel<1>, grid, dim3(256), 0, stream, static_cast<const uint4v *>(dy),
-                           static_cast<const uint2v *>(tap), static_cast<const uint4v *>(relu_src), static_cast<uint4v *>(dx),
-                           H, W, Ho, Wo, k, d);
-    else
-        hipLaunchKernelGGL(maxpool_bwd_h_kernel<2>, grid, dim3(256), 0, stream, static_cast<const uint4v *>(dy),
-                           static_cast<const uint2v *>(tap), static_cast<const uint4v *>(relu_src), static_cast<uint4v *>(dx),
-                           H, W, Ho, Wo, k, d);
+    const uint4v *g = static_cast<const uint4v *>(dy), *rs = static_cast<const uint4v *>(relu_src);
+    const uint2v *tp = static_cast<const uint2v *>(tap);
+    uint4v *out = static_cast<uint4v *>(dx);
+    if (dtype == 1 && k == 2) hipLaunchKernelGGL((maxpool_bwd_h_kernel<1, 2>), grid, dim3(256), 0, stream, g, tp, rs, out, H, W, Ho, Wo, k, d);
+    else if (dtype == 1) hipLaunchKernelGGL((maxpool_bwd_h_kernel<1, 0>), grid, dim3(256), 0, stream, g, tp, rs, out, H, W, Ho, Wo, k, d);
+    else if (k == 2) hipLaunchKernelGGL((maxpool_bwd_h_kernel<2, 2>), grid, dim3(256), 0, stream, g, tp, rs, out, H, W, Ho, Wo, k, d);
+    else hipLaunchKernelGGL((maxpool_bwd_h_kernel<2, 0>), grid, dim3(256), 0, stream, g, tp, rs, out, H, W, Ho, Wo, k, d);
     return hipGetLastError();
 }
 
