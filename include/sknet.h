@@ -167,9 +167,17 @@ sk_status sknet_sgd_step(sknet_t *net, float lr, float momentum, float weight_de
  * get_pool_argmax: for max-pool number pool_idx (0-based among pools), per output element the
  *   flat offset (y*W_in + x) of the winning input sample inside its input plane, int32 NCHW
  *   (HOST).  Taps are scanned row-major and only a strictly greater value replaces the
- *   incumbent, so the first maximum wins.  Needs a training plan. */
+ *   incumbent, so the first maximum wins.  Needs a training plan.
+ * get_activation_grad: the error map of layer layer_idx (0-based), i.e. the gradient of the loss with respect
+ *   to that layer's output with the layer's own ReLU derivative applied (what its weight gradient and the
+ *   data gradient of the layer read; Section 1.6 calls it the blob's "diff"), fp32 NCHW (HOST), sized like the
+ *   layer's output.  Re-runs the backward pass of the last forward with labels_dev (DEVICE, as in
+ *   sknet_backward) from the loss down to that layer; this overwrites the weight gradients of the layers it
+ *   passes, so sknet_get_grad reports SK_ESTATE until the next sknet_backward.  Needs a forward pass on a
+ *   training plan.  Allocates and frees small temporaries. */
 sk_status sknet_get_grad(sknet_t *net, int32_t conv_idx, float *dw_host, float *db_host);
 sk_status sknet_get_activation(sknet_t *net, int32_t layer_idx, float *nchw_host);
+sk_status sknet_get_activation_grad(sknet_t *net, int32_t layer_idx, const int32_t *labels_dev, float *nchw_host);
 sk_status sknet_get_pool_argmax(sknet_t *net, int32_t pool_idx, int32_t *idx_host);
 
 /* Number of device steps of the planned forward pass (pad, one per layer or fused group, softmax), a short
@@ -235,14 +243,19 @@ sk_status unet_forward(unet_t *net, const float *image_dev, float *prob_dev, voi
  * unet_backward: after a forward on a training plan (SK_ESTATE otherwise).  labels_dev: DEVICE int32
  *   [n][h_out][w_out], values in [0, n_classes) or -1 for a masked pixel; loss_dev: DEVICE fp32 scalar,
  *   both as in sknet_backward (on a training plan unet_forward keeps a copy of its image for this).
- *   Computes the exact gradient of the loss for every parameter: MergeCrop sends the up
- *   path's gradient to the up-convolution and the skip maps' gradient to the centre window of the skip
- *   map (nothing to the cropped border, Section 5.3.1); a skip map sums the gradients of the two layers
- *   it feeds; the up-convolution's gradient is that of a 1x1 convolution to the four interleaved
- *   sub-images.  Deterministic.
+ *   Computes the gradient of the loss for every parameter by the layers' backward rules in reverse order.
+ *   MergeCrop (Section 5.3.1) copies the error maps back in the inverse direction; for these nets the
+ *   section enables that for input A (the up path) only, because B (the skip map) gets its differential
+ *   on another path, from the down-sampling pool.  That is the default.  unet_set_merge_backward(net, 1)
+ *   selects the exact derivative of the composite instead: the skip maps' part of MergeCrop's gradient
+ *   also goes to the centre window of the skip map (nothing to the cropped border) and is summed with
+ *   the pool's gradient; mode 0 restores the section's rule.  May be called at any time before
+ *   unet_backward; SK_EINVAL for another mode.  The up-convolution's gradient is that of a 1x1
+ *   convolution to the four interleaved sub-images.  Deterministic.
  * unet_get_grad: gradient of parameter idx in the layout of unet_set_weights (HOST; either may be null);
  *   synchronises. */
 sk_status unet_plan_training(unet_t *net, int32_t n, int32_t h_in, int32_t w_in);
+sk_status unet_set_merge_backward(unet_t *net, int32_t mode);
 sk_status unet_backward(unet_t *net, const int32_t *labels_dev, float *loss_dev, void *hip_stream);
 sk_status unet_get_grad(unet_t *net, int32_t idx, float *dw_host, float *db_host);
 /* SGD on the fp32 weights with the gradients of the last unet_backward, as sknet_sgd_step

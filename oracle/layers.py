@@ -1,4 +1,5 @@
-"""numpy-facing wrappers of the C oracle (oracle/sk_oracle.c).  Argument marshalling only.
+"""numpy-facing wrappers of the C oracle (oracle/sk_oracle.c): argument marshalling, plus the
+backward rules of the up-convolution and of MergeCrop written out in numpy.
 
 All arrays are fp64, C-contiguous, NCHW.  TEST INFRASTRUCTURE ONLY.
 """
@@ -185,16 +186,21 @@ def upconv2x2_bwd(x, wgt, dy):
     return dx, dw, dy.sum(axis=(0, 2, 3))
 
 
-def mergecrop_bwd(g, fa, b_shape):
-    """Gradients of mergecrop: the first fa maps go to A; the rest go to the centre window of B,
-    the part of B that was cropped away gets none (Section 5.3.1)."""
+def mergecrop_bwd(g, fa, b_shape, into_b=False):
+    """Backward of mergecrop (Section 5.3.1): the error maps are copied back in the inverse direction.
+    The first fa maps go to A.  For the U- and USK-Net the section enables backwarding for input A only,
+    because B (the skip map) receives its differential on another path, from the down-sampling pool:
+    into_b=False returns zeros for B.  into_b=True is the exact derivative of the copy: the rest of
+    the maps go to the centre window of B, nothing to the part that was cropped away.
+    Returns (dA, dB)."""
     g = _f64(g)
     n, f, ha, wa = g.shape
     _, fb, hb, wb = b_shape
     assert f == fa + fb
     oy, ox = (hb - ha) // 2, (wb - wa) // 2
     db = np.zeros(b_shape)
-    db[:, :, oy:oy + ha, ox:ox + wa] = g[:, fa:]
+    if into_b:
+        db[:, :, oy:oy + ha, ox:ox + wa] = g[:, fa:]
     return g[:, :fa].copy(), db
 
 

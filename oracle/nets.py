@@ -41,10 +41,14 @@ def sknet_forward(image, sk_layers, weights, biases, pad=True, pad_mode=0, keep=
     return prob
 
 
-def sknet_backward(sk_layers, weights, acts, argmaxes, labels):
+def sknet_backward(sk_layers, weights, acts, argmaxes, labels, diffs=None):
     """Exact gradient of the mean softmax loss w.r.t. every conv weight and bias.
-    acts/argmaxes come from sknet_forward(keep=True).  Returns (loss, dW list, db list, d_input)."""
+    acts/argmaxes come from sknet_forward(keep=True).  Returns (loss, dW list, db list, d_input).
+    diffs: an optional list that receives, per layer, the error map of that layer (the gradient of the
+    loss with respect to its output, after the layer's own ReLU derivative)."""
     loss, g = L.softmax_loss(acts[-1], labels)
+    if diffs is not None:
+        diffs[:] = [None] * len(sk_layers)
     conv_ids = [i for i, l in enumerate(sk_layers) if l["type"] == "conv"]
     dws, dbs = [None] * len(conv_ids), [None] * len(conv_ids)
     wi = len(conv_ids) - 1
@@ -54,10 +58,14 @@ def sknet_backward(sk_layers, weights, acts, argmaxes, labels):
         if lay["type"] == "conv":
             if lay.get("relu", False):
                 g = L.relu_bwd(y_out, g)
+            if diffs is not None:
+                diffs[li] = g
             dws[wi], dbs[wi] = L.conv_sk_bwd_weights(x_in, g, lay["k"], lay["d"])
             g = L.conv_sk_bwd_data(g, weights[wi], lay["d"], x_in.shape[2:])
             wi -= 1
         else:
+            if diffs is not None:
+                diffs[li] = g
             g = L.maxpool_bwd(g, argmaxes[li], x_in.shape[2:])
     return loss, dws, dbs, g
 
@@ -178,8 +186,11 @@ def usknet_forward(image, params, base=64, keep=False):
 # ---------------------------------------------------------------------------------------------
 # Training pass of the U-Net and the USK-Net: the exact gradient of the (optionally masked) mean
 # softmax loss with respect to every parameter, the layers' own backward rules applied in reverse
-# order.  A map that feeds two layers (the skip connection: pooling and MergeCrop) receives the sum
-# of both gradients; MergeCrop sends nothing to the cropped-away border (Section 5.3.1).
+# order.  The skip map feeds two layers, the pool and MergeCrop.  Section 5.3.1 enables MergeCrop's
+# backward for its input A (the up path) only: the skip map then takes its gradient from the pool
+# alone (merge_into_b=False, the section's rule).  merge_into_b=True is the exact derivative of the
+# composite instead: MergeCrop also copies its skip maps' gradient into the centre window of the skip
+# map (nothing into the cropped-away border) and the skip map sums both contributions.
 
 def _conv_fwd(x, p, d=1, relu=True):
     return L.conv_sk(x, p[0], p[1], d=d, relu=relu)
@@ -195,7 +206,7 @@ def _conv_bwd(x, y, g, p, d=1, relu=True, need_dx=True):
     return dx, grads
 
 
-def unet_backward(image, params, labels, depth=4):
+def unet_backward(image, params, labels, depth=4, merge_into_b=False):
     """Returns (loss, {name: (dW, db)}) for the U-Net of unet_forward()."""
     x0 = np.asarray(image, dtype=np.float64)
     tape, skips = [], []
@@ -227,7 +238,7 @@ def unet_backward(image, params, labels, depth=4):
             _, i, xin, up, m, a, b = rec
             g, grads["dec%db" % i] = _conv_bwd(a, b, g, params["dec%db" % i])
             g, grads["dec%da" % i] = _conv_bwd(m, a, g, params["dec%da" % i])
-            g, gskip[i] = L.mergecrop_bwd(g, up.shape[1], skips[i].shape)
+            g, gskip[i] = L.mergecrop_bwd(g, up.shape[1], skips[i].shape, merge_into_b)
             g, dw, db = L.upconv2x2_bwd(xin, params["up%d" % i][0], g)
             grads["up%d" % i] = (dw, db)
         elif rec[0] == "pool":
@@ -240,7 +251,7 @@ def unet_backward(image, params, labels, depth=4):
     return loss, grads
 
 
-def usknet_backward(image, params, labels, base=64):
+def usknet_backward(image, params, labels, base=64, merge_into_b=False):
     """Returns (loss, {name: (dW, db)}) for the USK-Net of usknet_forward()."""
     x0 = np.asarray(image, dtype=np.float64)
     c1 = _conv_fwd(x0, params["conv1"])
@@ -266,7 +277,7 @@ def usknet_backward(image, params, labels, base=64):
     g, grads["ip3"] = _conv_bwd(c8, z, g, params["ip3"], relu=False)
     g, grads["conv8"] = _conv_bwd(c7, c8, g, params["conv8"])
     g, grads["conv7"] = _conv_bwd(m, c7, g, params["conv7"])
-    g, gskip = L.mergecrop_bwd(g, up.shape[1], c2.shape)
+    g, gskip = L.mergecrop_bwd(g, up.shape[1], c2.shape, merge_into_b)
     g, dw, db = L.upconv2x2_bwd(x, params["up1"][0], g)
     grads["up1"] = (dw, db)
     for name, kind, d, xin, y, am in reversed(core):

@@ -54,6 +54,7 @@ _SIGS = {
     "sknet_backward": [_vp, _vp, _vp, _vp],
     "sknet_sgd_step": [_vp, C.c_float, C.c_float, C.c_float, _vp],
     "sknet_get_grad": [_vp, _i32, _fp, _fp],
+    "sknet_get_activation_grad": [_vp, _i32, _vp, _fp],
     "sknet_get_activation": [_vp, _i32, _fp],
     "sknet_get_pool_argmax": [_vp, _i32, _ip],
     "sknet_num_steps": [_vp, _ip],
@@ -69,6 +70,7 @@ _SIGS = {
     "unet_get_activation": [_vp, C.c_char_p, _fp, _ip],
     "usknet_create": [_i32, _i32, _i32, _i32, C.POINTER(_vp)],
     "unet_plan_training": [_vp, _i32, _i32, _i32],
+    "unet_set_merge_backward": [_vp, _i32],
     "unet_backward": [_vp, _vp, _vp, _vp],
     "unet_get_grad": [_vp, _i32, _fp, _fp],
     "unet_param_kind": [_vp, _i32, _ip],
@@ -298,6 +300,13 @@ class SKNet:
         _check(lib.sknet_get_activation(self._h, layer_idx, out.ctypes.data_as(_fp)))
         return out
 
+    def get_activation_grad(self, layer_idx, labels):
+        """Error map of layer layer_idx (fp32 NCHW numpy), recomputed from the last forward with labels."""
+        c, h, w = self._shapes[layer_idx + 1]
+        out = np.empty((self._plan[0], c, h, w), np.float32)
+        _check(lib.sknet_get_activation_grad(self._h, layer_idx, _dev_ptr(labels, torch.int32, "labels"), out.ctypes.data_as(_fp)))
+        return out
+
     def get_pool_argmax(self, pool_idx):
         li = [i for i, l in enumerate(self.layers) if l["type"] == "pool"][pool_idx]
         c, h, w = self._shapes[li + 1]
@@ -372,6 +381,10 @@ class UNet:
     def plan(self, n, h_in, w_in, training=False):
         _check((lib.unet_plan_training if training else lib.unet_plan)(self._h, n, h_in, w_in))
         self._plan = (n, h_in, w_in)
+
+    def set_merge_backward(self, mode):
+        """0: MergeCrop backwards into the up path only (default); 1: into the skip map as well."""
+        _check(lib.unet_set_merge_backward(self._h, int(mode)))
 
     def backward(self, labels, loss=None, stream=None):
         """labels: int32 CUDA tensor [n, h_out, w_out] (-1 = masked pixel); returns the loss (1-element CUDA tensor)."""

@@ -909,26 +909,6 @@ static int device_cus()
     return cus;
 }
 
-// a few KB of zeros in device memory, read in place of samples outside the image; one page per
-// device, allocated on first use and kept until the process ends
-static const void *zero_page()
-{
-    constexpr int kMaxDevices = 64;
-    static void *pages[kMaxDevices] = {};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
-    if (!pages[dev]) {
-        void *page = nullptr;
-        if (hipMalloc(&page, 4096) != hipSuccess) return nullptr;
-        if (hipMemset(page, 0, 4096) != hipSuccess) {
-            (void)hipFree(page);
-            return nullptr;
-        }
-        pages[dev] = page;
-    }
-    return pages[dev];
-}
-
 // LDS bytes of the ring kernel: S stages (+ resident weights) + bias + y-tile table
 template <int KS, int MT, bool MAP4, int R, int S, bool RESW>
 static size_t ring_smem(int d, int c_out, int c8_in, int Ho)
@@ -955,8 +935,7 @@ static hipError_t launch_conv_h_ring_m(ConvHArgs a, hipStream_t stream)
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    a.zeros = zero_page();
-    if (!a.zeros) return hipErrorOutOfMemory;
+    if (!a.zeros) return hipErrorInvalidValue;                     // the caller's page of zeros (allocated with its plan)
     a.m_tiles = (a.c_out + 15) / 16;
     a.mgroups = (a.m_tiles + MT - 1) / MT;
     a.nchunks = (a.c8_in + OC - 1) / OC;

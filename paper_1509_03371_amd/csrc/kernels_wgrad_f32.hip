@@ -611,10 +611,19 @@ static hipError_t launch_wgrad_h_rb(const WgradArgs &a, int MB, int NB, size_t s
     return e;
 }
 
+// floats of one private copy of a gradient, and of its bias partials
+static size_t wgrad_copy_floats(int c_out, int c_in, int k)
+{
+    return (size_t)((c_out + 15) / 16 * 16) * (size_t)((c_in * k * k + 15) / 16 * 16);
+}
+static size_t wgrad_bias_floats(int c_out) { return (size_t)(c_out + 7) / 8 * 8 * BG_SLICES; }
+
+size_t wgrad_min_scratch_floats(int c_out, int c_in, int k) { return wgrad_copy_floats(c_out, c_in, k) + wgrad_bias_floats(c_out); }
+
 template <int DT>
 static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, float *db, float *scratch, int n, int c_in, int H,
                                   int W, int c_out, int k, int d, hipStream_t stream, long x_bstride = 0, int grp_maps = 0,
-                                  long grp_skip = 0)
+                                  long grp_skip = 0, size_t scratch_cap = 0)
 {
     WgradArgs a;
     a.x_bstride = x_bstride ? x_bstride : (long)c_in * H * W;
@@ -663,7 +672,15 @@ static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, floa
     const long per_cu = (long)(160 * 1024) / (long)(smem > 1 ? smem : 1);
     long resident = (long)cus * (per_cu < 1 ? 1 : (per_cu > 2 ? 2 : per_cu));
     if (resident > WG_MAX_BLOCKS) resident = WG_MAX_BLOCKS;
-    const int groups = wgrad_tile_groups(a.MTo, a.NTk, MB, NB), max_copies = wgrad_max_copies(groups);
+    const int groups = wgrad_tile_groups(a.MTo, a.NTk, MB, NB);
+    int max_copies = wgrad_max_copies(groups);
+    if (scratch_cap > 0) {
+        // a scratch buffer of a given size: as many private copies as it holds (fewer workgroups, same sums)
+        const size_t per = wgrad_copy_floats(c_out, c_in, k), bias = wgrad_bias_floats(c_out);
+        if (scratch_cap < per + bias) return hipErrorInvalidValue;
+        const size_t fit = (scratch_cap - bias) / per;
+        if (fit < (size_t)max_copies) max_copies = (int)fit;
+    }
     long copies = (resident + groups - 1) / groups;
     if (copies > max_copies) copies = max_copies;
     const int blocks = a.total_segs < copies ? a.total_segs : (int)copies;
@@ -714,9 +731,9 @@ static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, floa
 
 hipError_t launch_wgrad_f32(const float *x, const float *dy, float *dw, float *db, float *scratch,
                             int n, int c_in, int H, int W, int c_out, int k, int d,
-                            hipStream_t stream)
+                            hipStream_t stream, size_t scratch_cap)
 {
-    return launch_wgrad_dt<0>(x, dy, dw, db, scratch, n, c_in, H, W, c_out, k, d, stream);
+    return launch_wgrad_dt<0>(x, dy, dw, db, scratch, n, c_in, H, W, c_out, k, d, stream, 0, 0, 0, scratch_cap);
 }
 
 hipError_t launch_wgrad_f32_grouped(const float *x, const float *dy, float *dw, float *db, float *scratch, int n, int c_in, int H,
@@ -728,10 +745,10 @@ hipError_t launch_wgrad_f32_grouped(const float *x, const float *dy, float *dw, 
 // same gradient from 16-bit octet-layout activations (dtype 1 = bf16, 2 = fp16): the operands are
 // staged as they are and widened to fp32 when read, the contraction runs on the fp32 MFMA path
 hipError_t launch_wgrad_h(const void *x, const void *dy, float *dw, float *db, float *scratch, int dtype,
-                          int n, int c_in, int H, int W, int c_out, int k, int d, hipStream_t stream)
+                          int n, int c_in, int H, int W, int c_out, int k, int d, hipStream_t stream, size_t scratch_cap)
 {
-    return dtype == 1 ? launch_wgrad_dt<1>(x, dy, dw, db, scratch, n, c_in, H, W, c_out, k, d, stream)
-                      : launch_wgrad_dt<2>(x, dy, dw, db, scratch, n, c_in, H, W, c_out, k, d, stream);
+    return dtype == 1 ? launch_wgrad_dt<1>(x, dy, dw, db, scratch, n, c_in, H, W, c_out, k, d, stream, 0, 0, 0, scratch_cap)
+                      : launch_wgrad_dt<2>(x, dy, dw, db, scratch, n, c_in, H, W, c_out, k, d, stream, 0, 0, 0, scratch_cap);
 }
 
 }  // namespace sk

@@ -140,10 +140,43 @@ inline sk_status alloc_conv(ConvParams &c, bool training, int dtype = SK_F32)
 // element counts on the 16-bit octet layout, expressed in floats (what alloc_f takes)
 inline long octet_floats(int n, const Dims &d) { return (long)n * ((d.c + 7) / 8) * d.h * d.w * 4; }
 
+// One pass of a freshly planned net over zero inputs on the null stream, so that whatever a first launch sets
+// up (kernel attributes, code loading) has happened when the plan call returns: forward and backward then only
+// enqueue kernels, also when the caller records its very first call into a HIP graph.  fwd(image, prob) and
+// bwd(labels, loss) run the planned passes; bwd is skipped when label_count is 0.
+template <class Fwd, class Bwd>
+inline sk_status warm_up(long image_floats, long prob_floats, long label_count, Fwd fwd, Bwd bwd)
+{
+    float *img = nullptr, *prob = nullptr, *lab = nullptr, *loss = nullptr;
+    sk_status st = alloc_f(&img, image_floats);
+    if (st == SK_OK) st = alloc_f(&prob, prob_floats);
+    if (st == SK_OK && label_count > 0) st = alloc_f(&lab, label_count);
+    if (st == SK_OK && label_count > 0) st = alloc_f(&loss, 1);
+    hipError_t e = hipSuccess;
+    if (st == SK_OK) e = hipMemset(img, 0, sizeof(float) * (size_t)image_floats);
+    if (st == SK_OK && e == hipSuccess && lab) e = hipMemset(lab, 0, sizeof(int32_t) * (size_t)label_count);   // every pixel of class 0
+    if (st == SK_OK && e != hipSuccess) st = fail(SK_EDEVICE, "plan: clearing the warm-up buffers failed: %s", hipGetErrorString(e));
+    if (st == SK_OK) st = fwd(img, prob);
+    if (st == SK_OK && lab) st = bwd(reinterpret_cast<const int32_t *>(lab), loss);
+    e = hipDeviceSynchronize();
+    if (st == SK_OK && e != hipSuccess) st = fail(SK_EDEVICE, "plan: the warm-up pass failed: %s", hipGetErrorString(e));
+    free_dev(img); free_dev(prob); free_dev(lab); free_dev(loss);
+    return st;
+}
+
+// the page of zeros the 16-bit convolution reads for samples outside the image; part of a plan
+inline sk_status alloc_zero_page(float **p)
+{
+    SK_TRY(alloc_f(p, sk::CONV_H_ZERO_BYTES / 4));
+    SK_HIP(hipMemset(*p, 0, sk::CONV_H_ZERO_BYTES));
+    return SK_OK;
+}
+
 inline sk::ConvHArgs conv_h_args(const ConvParams &c, int dtype, const void *x, int n, const Dims &in, int d, int relu,
-                                 void *y, const Dims &out, bool out_f32)
+                                 void *y, const Dims &out, bool out_f32, const void *zeros)
 {
     sk::ConvHArgs a{};
+    a.zeros = zeros;
     a.x = x; a.wp = c.wp16_fwd; a.bias = c.b_dev; a.mask = nullptr; a.y = y; a.dtype = dtype;
     a.n = n; a.c8_in = (in.c + 7) / 8; a.H = in.h; a.W = in.w;
     a.c_out = c.c_out; a.c8_out = (c.c_out + 7) / 8;

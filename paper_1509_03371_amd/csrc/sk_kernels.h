@@ -72,10 +72,12 @@ struct ConvHArgs {
     int c8_out_total, o8_off, OH, OW, oy_mul, oy_off, ox_mul, ox_off;
     int mt;               // map tiles per workgroup the weights were packed for; 0 = default for (c_out, k)
     int tap_maps;         // > 0 (multiple of 16): GEMM map o = tap o / tap_maps of real map o % tap_maps, stored at (y*oy_mul + tap/2, x*ox_mul + tap%2)
+    const void *zeros;    // CONV_H_ZERO_BYTES of zeros in device memory, read in place of samples outside the image (the launcher
+                          // allocates nothing: the owner of the plan provides the page)
     // filled in by the launcher
     int m_tiles, mgroups, nchunks, xtiles, tiles_hi, tiles_lo, rem, ytiles_total, total_tiles;
-    const void *zeros;    // >= 16 bytes of zeros in device memory
 };
+constexpr int CONV_H_ZERO_BYTES = 4096;
 bool conv_h_supported(int k, int d);
 // ... and for a GEMM with gemm_m output maps (c_out forward, c_in for the data gradient) the tile fits the LDS
 bool conv_h_supported(int k, int d, int gemm_m);
@@ -127,11 +129,14 @@ hipError_t launch_head_fused(HeadArgs a, hipStream_t stream);
 
 // ---- weight / bias gradient of the SK convolution (fp32) ---------------------------------------
 // dW[o][c][i][j] = sum_{b,y,x} dY[b,o,y,x] * X[b,c,y+i*d,x+j*d];  db[o] = sum dY[b,o,:,:].
-// scratch must hold wgrad_scratch_floats(...) floats; the result is deterministic.
+// scratch must hold wgrad_f32_scratch_floats(...) floats (scratch_cap = 0), or scratch_cap floats with
+// scratch_cap >= wgrad_min_scratch_floats(...): the kernel then takes as many private copies of the gradient
+// as that holds.  The result is deterministic for a given scratch size.
 size_t wgrad_f32_scratch_floats(int c_out, int c_in, int k);
+size_t wgrad_min_scratch_floats(int c_out, int c_in, int k);
 hipError_t launch_wgrad_f32(const float *x, const float *dy, float *dw, float *db, float *scratch,
                             int n, int c_in, int H, int W, int c_out, int k, int d,
-                            hipStream_t stream);
+                            hipStream_t stream, size_t scratch_cap = 0);
 
 // the same with the input addressed as launch_conv_f32 addresses it: images x_bstride floats apart (0 = c_in*H*W),
 // the c_in maps in groups of grp_maps (a power of two, or 0 = none) with grp_skip more floats between groups
@@ -139,7 +144,7 @@ hipError_t launch_wgrad_f32_grouped(const float *x, const float *dy, float *dw, 
                                     int W, int c_out, int k, int d, long x_bstride, int grp_maps, long grp_skip, hipStream_t stream);
 
 hipError_t launch_wgrad_h(const void *x, const void *dy, float *dw, float *db, float *scratch, int dtype,
-                          int n, int c_in, int H, int W, int c_out, int k, int d, hipStream_t stream);
+                          int n, int c_in, int H, int W, int c_out, int k, int d, hipStream_t stream, size_t scratch_cap = 0);
 
 // ---- HBM-bound layers ---------------------------------------------------------------------------
 hipError_t launch_mirror_pad_f32(const float *in, float *out, int planes, int h, int w, int top,

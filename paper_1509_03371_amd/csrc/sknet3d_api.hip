@@ -447,7 +447,13 @@ sk_status sknet3d_plan(sknet3d_t *net, int32_t dz, int32_t h, int32_t w, int32_t
     }
     net->planned = true;
     net->training = training;
-    return SK_OK;
+    st = warm_up(dims[0].count(), dims[L].count(), training ? dims[L].count() / dims[L].c : 0,
+                 [&](const float *vol, float *prob) { return sknet3d_forward(net, vol, prob, nullptr); },
+                 [&](const int32_t *lab, float *loss) { return sknet3d_backward(net, lab, loss, nullptr); });
+    net->forward_done = net->backward_done = false;
+    net->last_volume = nullptr;
+    if (st != SK_OK) net->release_plan();
+    return st;
 }
 
 sk_status sknet3d_forward(sknet3d_t *net, const float *volume_dev, float *prob_dev, void *hip_stream)

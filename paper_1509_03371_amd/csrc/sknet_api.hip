@@ -30,6 +30,7 @@ struct sknet {
     float *head_w1p = nullptr;
     float *logits_f32 = nullptr;      // 16-bit nets: fp32 logits when the last layer is a pool; else alias of act[L]
     float *dz_f32 = nullptr;          // 16-bit training: fp32 gradient of the logits before it is packed
+    float *zero_page = nullptr;       // 16-bit nets: zeros the convolution reads for samples outside the image
     bool half() const { return dtype != SK_F32; }
     bool forward_done = false, backward_done = false;
     hipStream_t last_stream = nullptr;
@@ -46,7 +47,7 @@ struct sknet {
         }
         tap.clear();
         free_dev(gbuf[0]); free_dev(gbuf[1]); free_dev(loss_partial); free_dev(wgrad_scratch);
-        free_dev(logits_f32); free_dev(dz_f32); free_dev(head_w1p);
+        free_dev(logits_f32); free_dev(dz_f32); free_dev(head_w1p); free_dev(zero_page);
         steps.clear();
         fuse_head = false;
         for (auto &c : convs) release_conv(c);
@@ -145,7 +146,7 @@ sk_status run_forward_step(sknet *net, int step_idx, hipStream_t stream)
             const ConvParams &c = net->convs[net->conv_of_layer[li]];
             if (half) {
                 sk::ConvHArgs a = conv_h_args(c, net->dtype, net->act[li], net->n, in, l.d, l.relu, net->act[li + 1], out,
-                                              li == L - 1);   // the last conv writes fp32 logits
+                                              li == L - 1, net->zero_page);   // the last conv writes fp32 logits
                 SK_HIP(sk::launch_conv_h(a, stream));
             } else {
                 sk::ConvF32Args a = conv_args(c, net->act[li], net->n, in, l.d, l.relu, net->act[li + 1], out);
@@ -189,39 +190,56 @@ int64_t sknet_conv_flops(int64_t f_in, int64_t f_out, int64_t k, int64_t w_out)
     return f_out * w_out * w_out * (2 * f_in * k * k - 1);
 }
 
+// Algorithm 1 (Section 3.3.1) in two passes.  Pass 1 walks the patch-sized maps of the sliding-window net and
+// applies the algorithm's checks; what it records per layer is the map size in front of the layer and the
+// product of the pooling strides met since the last inner product -- the kernel stride the layer must take so
+// that its taps fall on the samples the sliding-window layer would have seen.  Pass 2 writes the SK layers
+// and checks that a full-patch input survives them (every SK layer shrinks its map by (k-1)*d).
 sk_status sknet_convert_sw(const sw_layer *sw, int32_t n, int32_t w0_sw, sk_layer *sk_out, int32_t *n_out)
 {
     if (!sw || !sk_out || !n_out || n < 1 || w0_sw < 1) return fail(SK_EINVAL, "convert_sw: bad arguments");
-    int d_temp = 1, w_sw = w0_sw, w_sk = w0_sw, written = 0;
+    std::vector<int> patch_before(n), stride_product(n);
+    int patch = w0_sw, pooled = 1;
     for (int i = 0; i < n; ++i) {
         const sw_layer &l = sw[i];
-        sk_layer o{};
-        if (l.kind == 0) {                       // convolution keeps k, takes the current kernel stride
+        patch_before[i] = patch;
+        stride_product[i] = pooled;
+        switch (l.kind) {
+        case 0:
             if (l.k < 1) return fail(SK_ESHAPE, "layer %d: k < 1", i);
-            o.kind = SK_CONV; o.c_out = l.c_out; o.k = l.k; o.d = d_temp; o.s = 1; o.relu = l.relu;
-            w_sk -= (l.k - 1) * d_temp;
-            w_sw -= l.k - 1;
-        } else if (l.kind == 1) {                // down-sampling pool becomes a stride-1 SK pool
-            if (l.k < 1 || w_sw % l.k != 0 || l.k != l.s)
-                return fail(SK_ESHAPE, "layer %d: pooling needs w mod k = 0 and k = s (w=%d k=%d s=%d)", i, w_sw, l.k, l.s);
-            o.kind = SK_MAXPOOL; o.k = l.k; o.d = d_temp; o.s = 1;
-            w_sk -= (l.k - 1) * d_temp;
-            w_sw /= l.k;
-            d_temp *= l.k;
-        } else if (l.kind == 2) {                // inner product spans the whole remaining map
-            o.kind = SK_CONV; o.c_out = l.c_out; o.k = w_sw; o.d = d_temp; o.s = 1; o.relu = l.relu;
-            w_sk -= (w_sw - 1) * d_temp;
-            w_sw = 1;
-            d_temp = 1;
-        } else {
+            patch -= l.k - 1;
+            break;
+        case 1:
+            if (l.k < 1 || l.k != l.s || patch % l.k != 0)
+                return fail(SK_ESHAPE, "layer %d: pooling needs w mod k = 0 and k = s (w=%d k=%d s=%d)", i, patch, l.k, l.s);
+            patch /= l.k;
+            pooled *= l.k;
+            break;
+        case 2:            // the inner product consumes the whole patch; behind it every map is 1 x 1 again
+            patch = 1;
+            pooled = 1;
+            break;
+        default:
             if (l.k > 1) return fail(SK_ESHAPE, "layer %d: only element-wise layers (k = 1) convert unchanged", i);
-            continue;
         }
-        if (w_sk < 1 || w_sw < 1) return fail(SK_ESHAPE, "layer %d: map shrinks below one pixel", i);
-        sk_out[written++] = o;
+        if (patch < 1) return fail(SK_ESHAPE, "layer %d: map shrinks below one pixel", i);
     }
-    if (d_temp != 1) return fail(SK_ESHAPE, "kernel stride is %d after the last layer; it must be 1", d_temp);
-    *n_out = written;
+    if (pooled != 1) return fail(SK_ESHAPE, "kernel stride is %d after the last layer; it must be 1", pooled);
+    int dense = w0_sw, count = 0;
+    for (int i = 0; i < n; ++i) {
+        const sw_layer &l = sw[i];
+        if (l.kind > 2 || l.kind < 0) continue;                      // element-wise layers are not SK layers
+        sk_layer o{};
+        o.kind = l.kind == 1 ? SK_MAXPOOL : SK_CONV;
+        o.k = l.kind == 2 ? patch_before[i] : l.k;                   // an inner product is a convolution over the whole map
+        o.d = stride_product[i];
+        o.s = 1;
+        if (o.kind == SK_CONV) { o.c_out = l.c_out; o.relu = l.relu; }
+        dense -= (o.k - 1) * o.d;
+        if (dense < 1) return fail(SK_ESHAPE, "layer %d: map shrinks below one pixel", i);
+        sk_out[count++] = o;
+    }
+    *n_out = count;
     return SK_OK;
 }
 
@@ -408,6 +426,7 @@ sk_status sknet_plan(sknet_t *net, int32_t n, int32_t h, int32_t w, int32_t pad,
         if (count > max_count) max_count = count;
     }
     if (st == SK_OK && half && net->layers[L - 1].kind != SK_CONV) st = alloc_f(&net->logits_f32, dims[L].count(n));
+    if (st == SK_OK && half) st = alloc_zero_page(&net->zero_page);
     size_t scratch = 0;
     for (int i = 0; i < L && st == SK_OK; ++i) {
         const sk_layer &l = net->layers[i];
@@ -449,7 +468,17 @@ sk_status sknet_plan(sknet_t *net, int32_t n, int32_t h, int32_t w, int32_t pad,
     }
     net->planned = true;
     net->last_stream = nullptr;
-    return SK_OK;
+    st = warm_up((long)n * net->c_in * h * w, dims[L].count(n), training ? (long)n * dims[L].h * dims[L].w : 0,
+                 [&](const float *img, float *prob) { return sknet_forward(net, img, prob, nullptr); },
+                 [&](const int32_t *lab, float *loss) { return sknet_backward(net, lab, loss, nullptr); });
+    net->forward_done = net->backward_done = false;
+    net->last_image = nullptr; net->last_prob = nullptr;
+    if (st != SK_OK) {
+        std::string keep = g_last_error;
+        net->release_plan();
+        g_last_error = keep;
+    }
+    return st;
 }
 
 sk_status sknet_forward(sknet_t *net, const float *image_dev, float *prob_dev, void *hip_stream)
@@ -467,14 +496,17 @@ sk_status sknet_forward(sknet_t *net, const float *image_dev, float *prob_dev, v
     return SK_OK;
 }
 
-sk_status sknet_backward(sknet_t *net, const int32_t *labels_dev, float *loss_dev, void *hip_stream)
+// The backward pass from the loss down to layer stop_layer (0 = all of it).  With stop_layer > 0 the walk
+// ends before layer stop_layer's own step and *grad_at_stop receives the buffer that holds the gradient of
+// the loss with respect to that layer's output (after the layer's own ReLU mask), in the storage layout
+// of the activations; the weight gradients of the layers below are then not computed.
+//
+// The partial results of the pass -- the loss kernel's per-workgroup sums and counts, the private copies of
+// each weight gradient and the bias partials -- go to loss_partial and wgrad_scratch; wgrad_cap = 0: the
+// plan's own buffer (sized for the fastest launch), else the floats wgrad_scratch holds.
+static sk_status backward_impl(sknet_t *net, const int32_t *labels_dev, float *loss_dev, hipStream_t stream, int stop_layer,
+                               float **grad_at_stop, float *loss_partial, float *wgrad_scratch, size_t wgrad_cap)
 {
-    SK_TRY(check_net(net));
-    if (!net->planned || !net->training) return fail(SK_ESTATE, "backward: needs a training plan");
-    if (!net->forward_done) return fail(SK_ESTATE, "backward: run sknet_forward first");
-    if (!labels_dev || !loss_dev) return fail(SK_EINVAL, "backward: null buffer");
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    net->last_stream = stream;
     const int L = (int)net->layers.size(), n = net->n;
     const Dims &o = net->dims[L];
     float *gcur = net->gbuf[0], *gnext = net->gbuf[1];
@@ -483,12 +515,16 @@ sk_status sknet_backward(sknet_t *net, const int32_t *labels_dev, float *loss_de
     {
         const float *logits = (half && net->layers[L - 1].kind != SK_CONV) ? net->logits_f32 : net->act[L];
         float *dz = half ? net->dz_f32 : gcur;
-        SK_HIP(sk::launch_softmax_loss_f32(logits, labels_dev, dz, loss_dev, net->loss_partial, n, o.c, o.h * o.w, stream));
+        SK_HIP(sk::launch_softmax_loss_f32(logits, labels_dev, dz, loss_dev, loss_partial, n, o.c, o.h * o.w, stream));
         if (net->layers[L - 1].kind == SK_CONV && net->layers[L - 1].relu)
             SK_HIP(sk::launch_relu_mask_f32(dz, net->act[L], o.count(n), stream));
         if (half) SK_HIP(sk::launch_pad_pack_h(dz, gcur, dt, n, o.c, o.h, o.w, 0, 0, o.h, o.w, 0, stream));
     }
     for (int li = L - 1; li >= 0; --li) {
+        if (grad_at_stop && li == stop_layer) {
+            *grad_at_stop = gcur;
+            return SK_OK;
+        }
         const sk_layer &l = net->layers[li];
         const Dims &in = net->dims[li], &out = net->dims[li + 1];
         // ReLU of the layer below acts on this layer's input: fuse its mask into whatever
@@ -498,15 +534,15 @@ sk_status sknet_backward(sknet_t *net, const int32_t *labels_dev, float *loss_de
         if (l.kind == SK_CONV) {
             ConvParams &c = net->convs[net->conv_of_layer[li]];
             if (half)
-                SK_HIP(sk::launch_wgrad_h(net->act[li], gcur, c.dw, c.db, net->wgrad_scratch, dt, n, in.c, in.h, in.w,
-                                          c.c_out, c.k, l.d, stream));
+                SK_HIP(sk::launch_wgrad_h(net->act[li], gcur, c.dw, c.db, wgrad_scratch, dt, n, in.c, in.h, in.w,
+                                          c.c_out, c.k, l.d, stream, wgrad_cap));
             else
-                SK_HIP(sk::launch_wgrad_f32(net->act[li], gcur, c.dw, c.db, net->wgrad_scratch, n, in.c, in.h, in.w,
-                                            c.c_out, c.k, l.d, stream));
+                SK_HIP(sk::launch_wgrad_f32(net->act[li], gcur, c.dw, c.db, wgrad_scratch, n, in.c, in.h, in.w,
+                                            c.c_out, c.k, l.d, stream, wgrad_cap));
             if (li == 0) break;   // nothing below needs the image gradient
             if (half) {
                 sk::ConvHArgs a{};
-                a.x = gcur; a.wp = c.wp16_bwd; a.bias = nullptr; a.mask = relu_src; a.y = gnext; a.dtype = dt;
+                a.x = gcur; a.wp = c.wp16_bwd; a.bias = nullptr; a.mask = relu_src; a.y = gnext; a.dtype = dt; a.zeros = net->zero_page;
                 a.n = n; a.c8_in = (out.c + 7) / 8; a.H = out.h; a.W = out.w;
                 a.c_out = in.c; a.c8_out = (in.c + 7) / 8;
                 a.k = c.k; a.d = l.d; a.in_off = (c.k - 1) * l.d; a.Ho = in.h; a.Wo = in.w; a.relu = 0; a.out_f32 = 0;
@@ -535,7 +571,49 @@ sk_status sknet_backward(sknet_t *net, const int32_t *labels_dev, float *loss_de
         }
         float *t = gcur; gcur = gnext; gnext = t;
     }
+    return SK_OK;
+}
+
+sk_status sknet_backward(sknet_t *net, const int32_t *labels_dev, float *loss_dev, void *hip_stream)
+{
+    SK_TRY(check_net(net));
+    if (!net->planned || !net->training) return fail(SK_ESTATE, "backward: needs a training plan");
+    if (!net->forward_done) return fail(SK_ESTATE, "backward: run sknet_forward first");
+    if (!labels_dev || !loss_dev) return fail(SK_EINVAL, "backward: null buffer");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    net->last_stream = stream;
+    SK_TRY(backward_impl(net, labels_dev, loss_dev, stream, 0, nullptr, net->loss_partial, net->wgrad_scratch, 0));
     net->backward_done = true;
+    return SK_OK;
+}
+
+sk_status sknet_get_activation_grad(sknet_t *net, int32_t layer_idx, const int32_t *labels_dev, float *nchw_host)
+{
+    SK_TRY(check_net(net));
+    const int L = (int)net->layers.size();
+    if (!nchw_host || !labels_dev || layer_idx < 0 || layer_idx >= L) return fail(SK_EINVAL, "get_activation_grad: bad arguments");
+    if (!net->planned || !net->training || !net->forward_done)
+        return fail(SK_ESTATE, "get_activation_grad: needs a forward pass on a training plan");
+    hipStream_t stream = net->last_stream;
+    float *loss = nullptr, *g = nullptr, *tmp = nullptr;
+    SK_TRY(alloc_f(&loss, 1));
+    // the walk overwrites the weight gradients of the layers it passes: a later get_grad needs a new backward
+    net->backward_done = false;
+    sk_status st = backward_impl(net, labels_dev, loss, stream, layer_idx, &g, net->loss_partial, net->wgrad_scratch, 0);
+    const Dims &dm = net->dims[layer_idx + 1];
+    const long count = dm.count(net->n);
+    hipError_t e = hipSuccess;
+    if (st == SK_OK && layer_idx == L - 1 && net->half()) g = net->dz_f32;   // the logits' gradient is kept in fp32 beside its packed copy
+    const bool f32 = !net->half() || layer_idx == L - 1;
+    if (st == SK_OK && !f32) {
+        st = alloc_f(&tmp, count);
+        if (st == SK_OK) e = sk::launch_unpack_h(g, tmp, net->dtype, net->n, dm.c, dm.h, dm.w, stream);
+    }
+    if (st == SK_OK && e == hipSuccess) e = hipStreamSynchronize(stream);
+    if (st == SK_OK && e == hipSuccess) e = hipMemcpy(nchw_host, f32 ? g : tmp, sizeof(float) * (size_t)count, hipMemcpyDeviceToHost);
+    free_dev(loss); free_dev(tmp);
+    if (st != SK_OK) return st;
+    if (e != hipSuccess) return fail(SK_EDEVICE, "get_activation_grad: %s", hipGetErrorString(e));
     return SK_OK;
 }
 

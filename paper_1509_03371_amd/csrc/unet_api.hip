@@ -45,6 +45,7 @@ struct unet {
     std::vector<UpParams> ups;
     // plan
     bool training = false, backward_done = false;
+    int merge_backward = 0;                            // MergeCrop's backward: 0 = into the up path only, 1 = into the skip map as well
     float *image_copy = nullptr;                       // training: the image of the last forward pass (the first layer's weight gradient reads it)
     std::map<const float *, float *> grad_of;          // training: gradient buffer of every activation buffer
     std::vector<uint8_t *> taps;                       // training: winner codes, one entry per op (pools only)
@@ -66,6 +67,7 @@ struct unet {
     std::vector<Op> ops;
     std::vector<Stage> stages;
     float *logits = nullptr;                 // fp32 NCHW in every storage type
+    float *zero_page = nullptr;              // 16-bit types: zeros the convolution reads for samples outside the image
     float *unpack_tmp = nullptr;             // 16-bit types: fp32 staging for unet_get_activation
     long unpack_tmp_floats = 0;
     Dims out_dims;
@@ -75,7 +77,7 @@ struct unet {
     {
         for (auto &p : buffers) free_dev(p);
         buffers.clear();
-        free_dev(unpack_tmp);
+        free_dev(unpack_tmp); free_dev(zero_page);
         unpack_tmp_floats = 0;
         for (auto &kv : grad_of) { float *g = kv.second; free_dev(g); }
         grad_of.clear();
@@ -484,6 +486,7 @@ static sk_status plan_impl(unet_t *net, int32_t n, int32_t h_in, int32_t w_in, b
         if (st == SK_OK) st = upload_up(u, net->dtype);
     }
     if (st == SK_OK && half) st = alloc_f(&net->unpack_tmp, net->unpack_tmp_floats);
+    if (st == SK_OK && half) st = alloc_zero_page(&net->zero_page);
     if (st == SK_OK && training) {
         // a gradient buffer per activation buffer, winner codes per pool, scratch of the loss and the weight gradients
         for (float *bufp : net->buffers) {
@@ -525,6 +528,23 @@ static sk_status plan_impl(unet_t *net, int32_t n, int32_t h_in, int32_t w_in, b
         return st;
     }
     net->planned = true;
+    st = warm_up((long)n * net->c_in * h_in * w_in, net->out_dims.count(n), training ? (long)n * net->out_dims.h * net->out_dims.w : 0,
+                 [&](const float *img, float *prob) { return unet_forward(net, img, prob, nullptr); },
+                 [&](const int32_t *lab, float *loss) { return unet_backward(net, lab, loss, nullptr); });
+    net->forward_done = net->backward_done = false;
+    if (st != SK_OK) {
+        std::string keep = g_last_error;
+        net->release_plan();
+        g_last_error = keep;
+    }
+    return st;
+}
+
+sk_status unet_set_merge_backward(unet_t *net, int32_t mode)
+{
+    SK_TRY(check(net));
+    if (mode != 0 && mode != 1) return fail(SK_EINVAL, "unet_set_merge_backward: mode must be 0 (up path only) or 1 (skip map as well)");
+    net->merge_backward = mode;
     return SK_OK;
 }
 
@@ -551,7 +571,7 @@ sk_status unet_forward(unet_t *net, const float *image_dev, float *prob_dev, voi
             } else if (op.kind == 0) {
                 const ConvParams &c = net->convs[op.param];
                 const bool to_logits = op.dst == net->logits;     // the last conv leaves fp32 NCHW
-                sk::ConvHArgs a = conv_h_args(c, dt, src, n, op.in, op.d, op.relu, op.dst, op.out, to_logits);
+                sk::ConvHArgs a = conv_h_args(c, dt, src, n, op.in, op.d, op.relu, op.dst, op.out, to_logits, net->zero_page);
                 SK_HIP(sk::launch_conv_h(a, stream));
             } else if (op.kind == 1) {
                 SK_HIP(sk::launch_maxpool_h(src, op.dst, nullptr, dt, (long)n * ((op.in.c + 7) / 8), op.in.h, op.in.w,
@@ -561,14 +581,14 @@ sk_status unet_forward(unet_t *net, const float *image_dev, float *prob_dev, voi
                 if (u.c_out % 16 == 0) {
                     // one 1x1 convolution to 4*c_out maps; the epilogue puts tap t of map o at (2y + t/2, 2x + t%2)
                     Dims lowres = {4 * u.c_out, op.in.h, op.in.w};
-                    sk::ConvHArgs a = conv_h_args(u.cat, dt, src, n, op.in, 1, 0, op.dst, lowres, false);
+                    sk::ConvHArgs a = conv_h_args(u.cat, dt, src, n, op.in, 1, 0, op.dst, lowres, false, net->zero_page);
                     a.c8_out_total = (op.out.c + 7) / 8; a.o8_off = 0; a.OH = op.out.h; a.OW = op.out.w;
                     a.oy_mul = 2; a.oy_off = 0; a.ox_mul = 2; a.ox_off = 0; a.tap_maps = u.c_out;
                     SK_HIP(sk::launch_conv_h(a, stream));
                 } else {
                     for (int t = 0; t < 4; ++t) {
                         Dims lowres = {u.c_out, op.in.h, op.in.w};
-                        sk::ConvHArgs a = conv_h_args(u.tap[t], dt, src, n, op.in, 1, 0, op.dst, lowres, false);
+                        sk::ConvHArgs a = conv_h_args(u.tap[t], dt, src, n, op.in, 1, 0, op.dst, lowres, false, net->zero_page);
                         a.c8_out_total = (op.out.c + 7) / 8; a.o8_off = 0; a.OH = op.out.h; a.OW = op.out.w;
                         a.oy_mul = 2; a.oy_off = t / 2; a.ox_mul = 2; a.ox_off = t % 2;
                         SK_HIP(sk::launch_conv_h(a, stream));
@@ -619,13 +639,15 @@ sk_status unet_forward(unet_t *net, const float *image_dev, float *prob_dev, voi
     return SK_OK;
 }
 
-// Exact gradient of the (optionally masked) mean softmax loss with respect to every parameter: the
+// Gradient of the (optionally masked) mean softmax loss with respect to every parameter: the
 // forward ops in reverse order.  Conv: ReLU mask, weight/bias gradient, data gradient (the forward
 // kernel with flipped, transposed weights and zero padding).  Pool: to the recorded winner.
 // Up-convolution: the gradient's four interleaved sub-images stacked as 4*c_out maps turn it into a 1x1
-// convolution, whose weight and data gradients are the up-convolution's.  MergeCrop: the up path's maps
-// go back to the up-convolution, the skip maps into the centre window of the skip gradient (zero
-// elsewhere); the skip map also feeds a pool, whose gradient is added.
+// convolution, whose weight and data gradients are the up-convolution's.  MergeCrop (Section 5.3.1):
+// the up path's maps go back to the up-convolution; the skip map takes its gradient from the pool it
+// also feeds and nothing from MergeCrop (merge_backward 0, the section's rule for these nets), or
+// (merge_backward 1, the exact derivative) MergeCrop's skip maps are also copied into the centre
+// window of the skip gradient, zero elsewhere, and the pool's gradient is added to them.
 sk_status unet_backward(unet_t *net, const int32_t *labels_dev, float *loss_dev, void *hip_stream)
 {
     SK_TRY(check(net));
@@ -691,6 +713,7 @@ sk_status unet_backward(unet_t *net, const int32_t *labels_dev, float *loss_dev,
             SK_HIP(sk::launch_conv_f32(a, stream));
             written.insert(op.src);
         } else if (op.kind == 3) {
+            if (!net->merge_backward) continue;    // backwarding enabled for the up path only
             const float *gm = net->grad_of[op.dst];
             if (written.count(op.src)) return fail(SK_EUNSUPPORTED, "unet_backward: MergeCrop must be the last consumer of its skip map");
             SK_HIP(sk::launch_fill_f32(gsrc, 0.f, (long)n * op.src_maps * op.in.h * op.in.w, stream));

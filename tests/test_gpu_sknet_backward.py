@@ -108,6 +108,65 @@ def test_pool_backward_bit_exact_routing():
     train_step_compare(layers, 4, img, labels, ws, bs)
 
 
+def compare_error_maps(layers, c_in, img, labels, ws, bs, dtype, tol, tag):
+    """Error map of every layer (sknet_get_activation_grad) against the oracle's, every element."""
+    n, _, h, w = img.shape
+    net = make_net(layers, c_in, ws, bs, dtype=dtype)
+    net.plan(n, h, w, pad=True, training=True)
+    tlab = torch.from_numpy(labels).cuda()
+    net.forward(torch.from_numpy(img).cuda())
+    ow, ob = [x.astype(np.float64) for x in ws], [x.astype(np.float64) for x in bs]
+    _, acts, ams = ON.sknet_forward(img, layers, ow, ob, keep=True)
+    diffs = []
+    ON.sknet_backward(layers, ow, acts, ams, labels, diffs=diffs)
+    for li in range(len(layers) - 1, -1, -1):
+        got = net.get_activation_grad(li, tlab)
+        ref = diffs[li]
+        assert got.shape == ref.shape and np.abs(ref).max() > 0, li
+        e = relerr(got, ref)
+        edge = max(relerr(got[:, :, :8], ref[:, :, :8]), relerr(got[:, :, -8:], ref[:, :, -8:]),
+                   relerr(got[:, :, :, :8], ref[:, :, :, :8]), relerr(got[:, :, :, -8:], ref[:, :, :, -8:]))
+        print(tag, dtype, "layer", li, layers[li]["type"], "error map rel err %.3e (8-wide borders %.3e)" % (e, edge), flush=True)
+        assert e <= tol, (li, e)
+    with pytest.raises(Exception):
+        net.get_grad(0)                    # the partial walks overwrote gradients: a new backward is needed
+    net.backward(tlab)
+    net.get_grad(0)
+    net.close()
+
+
+@pytest.mark.parametrize("dtype,tol", [("f32", FP32_TOL), ("f16", 5e-3), ("bf16", 2e-2)])
+def test_data_gradient_error_maps_borders_included(dtype, tol):
+    """The data gradient of the dilated convolutions compared directly, element by element, not through
+    the weight gradients of the layers below: the error map of every layer of a chain of 4x4 convolutions at
+    d = 1, 2, 4, 8, including the (k-1)d-wide border that only partial sums reach.  The chain has no ReLU and
+    no pool, so no decision can fall differently in the two precisions and the maps are held to the
+    tolerance of the arithmetic.  Two images, non-square, masked labels."""
+    layers = [S.conv(16, 1, 1, relu=False)] + [S.conv(16, 4, d, relu=False) for d in (1, 2, 4, 8)] + [S.conv(2, 1, 1, relu=False)]
+    ws, bs = S.he_normal_weights(layers, 3, 21, bias_scale=0.1)
+    n, h, w = 2, 50, 150
+    img = np.ascontiguousarray(S.em_like_batch(n, h, w, 22).repeat(3, 1) * np.array([1.0, 0.5, -0.7], np.float32)[None, :, None, None])
+    labels = S.binary_labels(n, h, w, 23)
+    labels[0, :5, :] = -1
+    compare_error_maps(layers, 3, img, labels, ws, bs, dtype, tol, "dgrad")
+
+
+@pytest.mark.parametrize("dtype,tol", [("f32", FP32_TOL), ("f16", 5e-3), ("bf16", 2e-2)])
+def test_pool_scatter_error_maps_with_ties(dtype, tol):
+    """The pool gradient compared directly: identity 1x1 convolution + ReLU, then SK pools at d = 1, 2, 4, 8,
+    then a 1x1 convolution to the classes.  The image holds multiples of 1/16 (exact in every storage type,
+    many ties, negative values and zeros for the fused ReLU mask), so both sides pool identical numbers and
+    pick identical winners; the error maps then differ by the arithmetic of the head alone."""
+    layers = [S.conv(8, 1, 1, relu=True)] + [S.pool(2, d) for d in (1, 2, 4, 8)] + [S.conv(3, 1, 1, relu=False)]
+    ws, bs = S.he_normal_weights(layers, 8, 31, bias_scale=0.1)
+    ws[0] = np.eye(8, dtype=np.float32).reshape(8, 8, 1, 1)
+    bs[0] = np.zeros(8, np.float32)
+    n, h, w = 2, 45, 140
+    img = (np.random.default_rng(32).integers(-16, 48, (n, 8, h, w)) / 16.0).astype(np.float32)
+    labels = np.random.default_rng(33).integers(-1, 3, (n, h, w)).astype(np.int32)
+    compare_error_maps(layers, 8, img, labels, ws, bs, dtype, tol, "pool")
+
+
 def test_c4_sknet_training_step_512():
     layers = S.sknet_layers()
     ws, bs = S.he_normal_weights(layers, 1, 1001)

@@ -42,8 +42,11 @@ def masked_labels(n, h, w, classes, seed, masked=0.25):
     return lab
 
 
+@pytest.mark.parametrize("merge_into_b", [0, 1])
 @pytest.mark.parametrize("depth,base,h,w,n,seed", [(2, 8, 60, 76, 2, 502), (1, 8, 28, 36, 1, 601), (3, 4, 108, 92, 1, 503)])
-def test_unet_backward(depth, base, h, w, n, seed):
+def test_unet_backward(depth, base, h, w, n, seed, merge_into_b):
+    # merge_into_b = 0: MergeCrop backwards into the up path only (Section 5.3.1's rule, the default);
+    # 1: the exact derivative, the skip map sums MergeCrop's and the pool's gradients
     from paper_1509_03371_amd import binding as B
     params = S.unet_params(2, 3, seed, depth=depth, base=base, bias_scale=0.1)
     names = S.unet_param_names(depth)
@@ -52,14 +55,19 @@ def test_unet_backward(depth, base, h, w, n, seed):
         net.set_weights(i, *params[name])
     img = image(n, 2, h, w, 510)
     net.plan(n, h, w, training=True)
+    if merge_into_b:
+        net.set_merge_backward(1)
     ho, wo = net.output_size(h, w)
     lab = masked_labels(n, ho, wo, 3, 511)
     prob = net.forward(torch.from_numpy(img).cuda()).cpu().numpy()
     loss = net.backward(torch.from_numpy(lab).cuda())
     p64 = {k: (a.astype(np.float64), b.astype(np.float64)) for k, (a, b) in params.items()}
     assert np.abs(prob - ON.unet_forward(img, p64, depth=depth)).max() <= FP32_TOL
-    ref_loss, ref_grads = ON.unet_backward(img, p64, lab, depth=depth)
-    check_grads(net, names, params, loss, ref_loss, ref_grads, "unet d%d" % depth)
+    ref_loss, ref_grads = ON.unet_backward(img, p64, lab, depth=depth, merge_into_b=bool(merge_into_b))
+    if depth == 2:      # the two rules differ: the other rule's contracting-path gradients must not pass
+        _, other = ON.unet_backward(img, p64, lab, depth=depth, merge_into_b=not merge_into_b)
+        assert relerr(other["down0a"][0], ref_grads["down0a"][0]) > 1e-2
+    check_grads(net, names, params, loss, ref_loss, ref_grads, "unet d%d m%d" % (depth, merge_into_b))
     # a second pass on the same plan (gradient buffers are reused) gives the same gradients
     net.forward(torch.from_numpy(img).cuda())
     net.backward(torch.from_numpy(lab).cuda())
@@ -94,11 +102,11 @@ def test_unet_backward_wide_maps_several_tile_groups():
 
 def test_c5_unet_training_pass_572():
     # the configuration table's own sizes (1 x 572^2 -> 388^2, 64..1024 maps): the launch configuration
-    # bench.py times; every parameter gradient against the oracle.  Tolerance: at this size fp32
-    # accumulation itself (dot products of up to 9216 terms, sums over up to 3e5 pixels, 23 layers deep,
-    # gradients that largely cancel) costs more than 1e-4 -- the same pass in plain fp32 on the CPU with
-    # the library's reverse-mode differentiation is off from fp64 by up to 5e-4 of a tensor's largest
-    # entry (measured), this path by up to 1.1e-3; the small cases above hold 1e-4 with the same kernels.
+    # bench.py times; every parameter gradient against the oracle.  Tolerance 2e-3, not 1e-4: at this size
+    # (1.2e8 ReLU and pool decisions) a few decisions fall differently in fp32 and fp64, and each moves one
+    # whole pixel's term of gradient sums that largely cancel.  tests/test_fp32_decision_floor.py measures
+    # that on the CPU: the library's own fp32 pass is off from fp64 by 6.7e-4 with its own decisions and by
+    # 1.3e-5 with fp64's.  The small cases above hold 1e-4 with the same kernels.
     from paper_1509_03371_amd import binding as B
     params = S.unet_params(1, 2, 1005, depth=4, base=64)
     names = S.unet_param_names(4)
@@ -112,11 +120,12 @@ def test_c5_unet_training_pass_572():
     loss = net.backward(torch.from_numpy(lab).cuda())
     p64 = {k: (a.astype(np.float64), b.astype(np.float64)) for k, (a, b) in params.items()}
     ref_loss, ref_grads = ON.unet_backward(img, p64, lab, depth=4)
-    check_grads(net, names, params, loss, ref_loss, ref_grads, "unet 572", tol=3e-3)
+    check_grads(net, names, params, loss, ref_loss, ref_grads, "unet 572", tol=2e-3)
     net.close()
 
 
-def test_usknet_backward():
+@pytest.mark.parametrize("merge_into_b", [0, 1])
+def test_usknet_backward(merge_into_b):
     from paper_1509_03371_amd import binding as B
     base, h, w, n = 8, 212, 228, 2
     params = S.usknet_params(2, 3, 520, base=base, bias_scale=0.1)
@@ -125,13 +134,14 @@ def test_usknet_backward():
         net.set_weights(i, *params[name])
     img = image(n, 2, h, w, 521)
     net.plan(n, h, w, training=True)
+    net.set_merge_backward(merge_into_b)
     ho, wo = net.output_size(h, w)
     lab = masked_labels(n, ho, wo, 3, 522)
     net.forward(torch.from_numpy(img).cuda())
     loss = net.backward(torch.from_numpy(lab).cuda())
     p64 = {k: (a.astype(np.float64), b.astype(np.float64)) for k, (a, b) in params.items()}
-    ref_loss, ref_grads = ON.usknet_backward(img, p64, lab, base=base)
-    check_grads(net, S.USKNET_PARAM_NAMES, params, loss, ref_loss, ref_grads, "usk")
+    ref_loss, ref_grads = ON.usknet_backward(img, p64, lab, base=base, merge_into_b=bool(merge_into_b))
+    check_grads(net, S.USKNET_PARAM_NAMES, params, loss, ref_loss, ref_grads, "usk m%d" % merge_into_b)
     net.close()
 
 

@@ -503,6 +503,14 @@ def test_mergecrop_order_and_offsets():
     b = rng(56).standard_normal((1, 3, 8, 12))
     out = L.mergecrop(a, b)
     assert np.array_equal(out[:, :2], a) and np.array_equal(out[:, 2:], b[:, :, 2:6, 3:9])
+    # backward: the copy's adjoint (<mergecrop(a, b), g> = <a, dA> + <b, dB>) when B takes gradient, and
+    # Section 5.3.1's rule for the U- and USK-Net (A only: B gets nothing from this layer)
+    g = rng(57).standard_normal(out.shape)
+    da, db = L.mergecrop_bwd(g, 2, b.shape, into_b=True)
+    assert abs((out * g).sum() - (a * da).sum() - (b * db).sum()) < 1e-12
+    assert np.count_nonzero(db) == 3 * 4 * 6 and np.array_equal(db[:, :, 2:6, 3:9], g[:, 2:])
+    da2, db2 = L.mergecrop_bwd(g, 2, b.shape)
+    assert np.array_equal(da2, g[:, :2]) and not db2.any()
 
 
 def test_unet_small_forward_shape_and_torch_crosscheck():
@@ -570,14 +578,17 @@ def _torch_grads(loss, tparams):
     return {k: (w.grad.numpy(), b.grad.numpy()) for k, (w, b) in tparams.items()}
 
 
-def test_unet_backward_matches_autograd():
+@pytest.mark.parametrize("merge_into_b", [False, True])
+def test_unet_backward_matches_autograd(merge_into_b):
     # depth-2 U-Net on 44x44 with masked labels: every parameter gradient against the library's
-    # reverse-mode differentiation of the same composition
+    # reverse-mode differentiation of the same composition.  merge_into_b=False is Section 5.3.1's rule
+    # (MergeCrop backwards into the up path only): the skip map enters the concatenation as a constant;
+    # merge_into_b=True is the exact derivative of the whole composite.
     params = {k: (w.astype(np.float64), b.astype(np.float64))
               for k, (w, b) in S.unet_params(2, 3, 80, depth=2, base=4, bias_scale=0.2).items()}
     img = rng(81).random((2, 2, 44, 44))
     lab = rng(82).integers(-1, 3, (2, 4, 4)).astype(np.int32)
-    loss, grads = nets.unet_backward(img, params, lab, depth=2)
+    loss, grads = nets.unet_backward(img, params, lab, depth=2, merge_into_b=merge_into_b)
     tp = {k: (torch.from_numpy(w).requires_grad_(), torch.from_numpy(b).requires_grad_()) for k, (w, b) in params.items()}
     x = torch.from_numpy(img)
     skips = []
@@ -589,7 +600,7 @@ def test_unet_backward_matches_autograd():
             x = F.max_pool2d(x, 2)
     for i in (1, 0):
         x = F.conv_transpose2d(x, *tp["up%d" % i], stride=2)
-        sk = skips[i]
+        sk = skips[i] if merge_into_b else skips[i].detach()
         o = (sk.shape[2] - x.shape[2]) // 2
         x = torch.cat([x, sk[:, :, o:o + x.shape[2], o:o + x.shape[3]]], 1)
         x = F.relu(F.conv2d(x, *tp["dec%da" % i]))
@@ -603,14 +614,15 @@ def test_unet_backward_matches_autograd():
             assert np.abs(got - want).max() <= 1e-12 * max(1.0, np.abs(want).max()), k
 
 
-def test_usknet_backward_matches_autograd():
+@pytest.mark.parametrize("merge_into_b", [False, True])
+def test_usknet_backward_matches_autograd(merge_into_b):
     base = 2
     params = {k: (w.astype(np.float64), b.astype(np.float64))
               for k, (w, b) in S.usknet_params(2, 3, 83, base=base, bias_scale=0.2).items()}
     img = rng(84).random((1, 2, 190, 186))
     ho, wo = 2 * ((190 - 4) // 2 - 86) - 4, 2 * ((186 - 4) // 2 - 86) - 4
     lab = rng(85).integers(-1, 3, (1, ho, wo)).astype(np.int32)
-    loss, grads = nets.usknet_backward(img, params, lab, base=base)
+    loss, grads = nets.usknet_backward(img, params, lab, base=base, merge_into_b=merge_into_b)
     tp = {k: (torch.from_numpy(w).requires_grad_(), torch.from_numpy(b).requires_grad_()) for k, (w, b) in params.items()}
     cv = lambda x, name, d=1: F.conv2d(x, *tp[name], dilation=d)
     x = F.relu(cv(F.relu(cv(torch.from_numpy(img), "conv1")), "conv2"))
@@ -621,6 +633,8 @@ def test_usknet_backward_matches_autograd():
     x = F.relu(cv(F.relu(cv(x, "ip1", 8)), "ip2"))
     x = F.conv_transpose2d(x, *tp["up1"], stride=2)
     oy, ox = (skip.shape[2] - x.shape[2]) // 2, (skip.shape[3] - x.shape[3]) // 2
+    if not merge_into_b:
+        skip = skip.detach()
     x = torch.cat([x, skip[:, :, oy:oy + x.shape[2], ox:ox + x.shape[3]]], 1)
     x = F.relu(cv(F.relu(cv(x, "conv7")), "conv8"))
     z = cv(x, "ip3")
