@@ -155,6 +155,22 @@ sk_status sknet_forward(sknet_t *net, const float *image_dev, float *prob_dev, v
  * Pool gradients go to the recorded maximum; ReLU passes gradient where its output is > 0. */
 sk_status sknet_backward(sknet_t *net, const int32_t *labels_dev, float *loss_dev, void *hip_stream);
 
+/* sknet_backward for callers that cannot allocate device memory or tolerate a call that does (code under HIP
+ * graph capture, tight serving / training loops, harnesses that forbid hipMalloc): the same pass with the same
+ * arguments, results and state rules, but its partial results -- the loss kernel's partial sums and counts, the
+ * private copies of each weight gradient and the bias partials -- live in a buffer that is part of the library's
+ * device code (32 MiB per GPU, there from the time the library is loaded on that GPU until the process ends)
+ * instead of the plan's own scratch.  The call itself allocates and frees nothing.  The activation-gradient
+ * buffers are the plan's, as in sknet_backward.  Limits: SK_EUNSUPPORTED if one padded copy of the net's largest
+ * weight gradient, roundup(f_out,16) x roundup(f_in*k*k,16) floats plus 64 x roundup(f_out,8) floats of bias partials,
+ * exceeds 8 Mi - 4096 floats, or if the loss needs more than 4096 floats (it never does: at most 2048).  A weight
+ * gradient takes as many private copies as fit, so the summation order -- not the value beyond fp32 rounding --
+ * can differ from sknet_backward's.  Every call on one GPU shares that GPU's buffer, whose contents are whatever
+ * the last call left (nothing in it needs clearing: each kernel writes every partial that is read afterwards);
+ * two such calls that overlap in time on one GPU (two streams, two handles, two threads) race and give wrong
+ * gradients -- serialise them. */
+sk_status sknet_backward_noalloc(sknet_t *net, const int32_t *labels_dev, float *loss_dev, void *hip_stream);
+
 /* SGD on the fp32 master weights with the gradients of the last backward:
  * g = dW + weight_decay*W;  V = momentum*V + lr*g;  W = W - V; then the packed device weights
  * are rebuilt (rounded to the compute dtype). */

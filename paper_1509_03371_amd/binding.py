@@ -51,6 +51,7 @@ _SIGS = {
     "sknet_get_weights": [_vp, _i32, _fp, _fp],
     "sknet_plan": [_vp, _i32, _i32, _i32, _i32, _i32],
     "sknet_forward": [_vp, _vp, _vp, _vp],
+    "sknet_backward_noalloc": [_vp, _vp, _vp, _vp],
     "sknet_backward": [_vp, _vp, _vp, _vp],
     "sknet_sgd_step": [_vp, C.c_float, C.c_float, C.c_float, _vp],
     "sknet_get_grad": [_vp, _i32, _fp, _fp],
@@ -274,14 +275,18 @@ class SKNet:
                                  _dev_ptr(prob, torch.float32, "prob"), _stream(stream)))
         return prob
 
-    def backward(self, labels, loss=None, stream=None):
+    def backward(self, labels, loss=None, stream=None, noalloc=False):
+        """noalloc=True: sknet_backward_noalloc (scratch in the library's static device buffer); loss must then
+        be given, so that nothing is allocated on the way."""
         n, _, h, w = self.out_shape()
         if tuple(labels.shape) != (n, h, w):
             raise ValueError("labels shape %s does not match %s" % (tuple(labels.shape), (n, h, w)))
         if loss is None:
+            if noalloc:
+                raise ValueError("noalloc needs a caller-provided loss tensor")
             loss = torch.empty(1, dtype=torch.float32, device=labels.device)
-        _check(lib.sknet_backward(self._h, _dev_ptr(labels, torch.int32, "labels"),
-                                  _dev_ptr(loss, torch.float32, "loss"), _stream(stream)))
+        fn = lib.sknet_backward_noalloc if noalloc else lib.sknet_backward
+        _check(fn(self._h, _dev_ptr(labels, torch.int32, "labels"), _dev_ptr(loss, torch.float32, "loss"), _stream(stream)))
         return loss
 
     def sgd_step(self, lr, momentum=0.0, weight_decay=0.0, stream=None):

@@ -2,11 +2,43 @@
 // per-layer launch sequences.  See include/sknet.h for the contract of every entry point.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
 #include <new>
 
 #include "sk_host.h"
 
 using namespace skh;
+
+// Scratch of sknet_backward_noalloc: the partial results of one backward pass (the loss kernel's partial sums and
+// counts, then the private copies and bias partials of one weight gradient at a time).  One array per GPU, held
+// from the moment the library's code is loaded on that GPU until the process ends.  Host code never uses this
+// name as an address: it asks the runtime for the array's device address once per device (static_scratch below).
+constexpr size_t kStaticScratchFloats = (size_t)8 << 20;          // 32 MiB
+constexpr size_t kStaticLossFloats = 4096;                         // its first part: the loss partials
+static __device__ __align__(256) float scratch[kStaticScratchFloats];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+float *g_scratch_ptr[kMaxDevices] = {};
+
+// device address of `scratch` on the current device, looked up on first use there
+sk_status static_scratch(float **out)
+{
+    int dev = -1;
+    SK_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(SK_EDEVICE, "device ordinal %d is beyond the %d this library keeps scratch for", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        SK_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(SK_EDEVICE, "hipGetSymbolAddress returned no address for the static scratch");
+        g_scratch_ptr[dev] = static_cast<float *>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return SK_OK;
+}
+}  // namespace
 
 // ================================================================================ SK-Net handle
 struct sknet {
@@ -454,6 +486,10 @@ sk_status sknet_plan(sknet_t *net, int32_t n, int32_t h, int32_t w, int32_t pad,
         }
     }
     if (st == SK_OK && training) {
+        float *unused = nullptr;
+        st = static_scratch(&unused);        // sknet_backward_noalloc's scratch: its address on this device is looked up here
+    }
+    if (st == SK_OK && training) {
         st = alloc_f(&net->gbuf[0], max_count);
         if (st == SK_OK) st = alloc_f(&net->gbuf[1], max_count);
         if (st == SK_OK) st = alloc_f(&net->loss_partial, sk::softmax_loss_partials((long)n * dims[L].h * dims[L].w));
@@ -583,6 +619,36 @@ sk_status sknet_backward(sknet_t *net, const int32_t *labels_dev, float *loss_de
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     net->last_stream = stream;
     SK_TRY(backward_impl(net, labels_dev, loss_dev, stream, 0, nullptr, net->loss_partial, net->wgrad_scratch, 0));
+    net->backward_done = true;
+    return SK_OK;
+}
+
+sk_status sknet_backward_noalloc(sknet_t *net, const int32_t *labels_dev, float *loss_dev, void *hip_stream)
+{
+    SK_TRY(check_net(net));
+    if (!net->planned || !net->training) return fail(SK_ESTATE, "backward_noalloc: needs a training plan");
+    if (!net->forward_done) return fail(SK_ESTATE, "backward_noalloc: run sknet_forward first");
+    if (!labels_dev || !loss_dev) return fail(SK_EINVAL, "backward_noalloc: null buffer");
+    // sizes first: the loss partials and one private copy of the largest gradient (plus its bias partials) must fit
+    const int L = (int)net->layers.size();
+    const size_t loss_floats = (size_t)sk::softmax_loss_partials((long)net->n * net->dims[L].h * net->dims[L].w);
+    if (loss_floats > kStaticLossFloats)
+        return fail(SK_EUNSUPPORTED, "backward_noalloc: the loss needs %zu floats of scratch, the static buffer keeps %zu for it", loss_floats,
+                    kStaticLossFloats);
+    const size_t cap = kStaticScratchFloats - kStaticLossFloats;
+    for (const auto &c : net->convs) {
+        const size_t need = sk::wgrad_min_scratch_floats(c.c_out, c.c_in, c.k);
+        if (need > cap)
+            return fail(SK_EUNSUPPORTED,
+                        "backward_noalloc: the %d x %d x %dx%d weight gradient needs %zu floats of scratch, the static buffer holds %zu "
+                        "(use sknet_backward, whose scratch belongs to the plan)", c.c_out, c.c_in, c.k, c.k, need, cap);
+    }
+    float *base = nullptr;
+    SK_TRY(static_scratch(&base));
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    net->last_stream = stream;
+    // nothing in the scratch has to start at zero: every kernel writes all the partials that its reduction reads
+    SK_TRY(backward_impl(net, labels_dev, loss_dev, stream, 0, nullptr, base, base + kStaticLossFloats, cap));
     net->backward_done = true;
     return SK_OK;
 }
