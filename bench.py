@@ -70,30 +70,43 @@ def measure_forward(torch, B, S, dtype, n, H, W, steps, warmup, first_seed, kern
     step_ms, conv_flops, conv_ms, total_flops = {}, 0.0, 0.0, 0.0
     conv_bytes, conv_launches = 0.0, 0
     pool_bytes, pool_ms = 0.0, 0.0
+    f_in_of = {}
     f_in = 1
+    for li, l in enumerate(layers):
+        f_in_of[li] = f_in
+        if l["type"] == "conv":
+            f_in = l["f_out"]
+    import re
     for step in range(net.num_steps()):
         ms = net.time_step(step, kernel_iters, stream)
-        step_ms[net.step_name(step)] = round(ms, 5)
-        if 1 <= step <= len(layers):
-            l = layers[step - 1]
-            c, ho, wo = shapes[step]
-            if l["type"] == "conv":
-                fl = 2.0 * f_in * l["k"] ** 2 * l["f_out"] * ho * wo * n
-                total_flops += fl
-                if f_in == 48 and l["f_out"] == 48:      # the dominant kernel: 48 -> 48, k4, dilated
-                    conv_flops += fl
-                    conv_ms += ms
-                    hi, wi = shapes[step - 1][1:]
-                    conv_bytes += esize * n * 48.0 * (hi * wi + ho * wo)   # every input and output element once
-                    conv_launches += 1
-                f_in = l["f_out"]
-            else:                                         # pool: one element read + one written
-                pool_bytes += 2.0 * esize * n * c * ho * wo
-                pool_ms += ms
+        name = net.step_name(step)
+        step_ms[name] = round(ms, 5)
+        m = re.match(r"(conv|pool)(\d+)_", name)
+        if not m:
+            continue
+        li = int(m.group(2))
+        l = layers[li]
+        c, ho, wo = shapes[li + 1]
+        if m.group(1) == "conv":
+            fl = 2.0 * f_in_of[li] * l["k"] ** 2 * l["f_out"] * ho * wo * n
+            total_flops += fl
+            if f_in_of[li] == 48 and l["f_out"] == 48:      # the dominant kernel: 48 -> 48, k4, dilated
+                conv_flops += fl
+                conv_ms += ms
+                hi, wi = shapes[li][1:]
+                conv_bytes += esize * n * 48.0 * (hi * wi + ho * wo)   # every input and output element once
+                conv_launches += 1
+        else:                                         # pool as a layer of its own: one element read + one written
+            pool_bytes += 2.0 * esize * n * c * ho * wo
+            pool_ms += ms
+    for li, l in enumerate(layers):                   # the 1x1 convolutions of a fused head
+        if l["type"] == "conv" and not any(k.startswith("conv%d_" % li) for k in step_ms):
+            c, ho, wo = shapes[li + 1]
+            total_flops += 2.0 * f_in_of[li] * l["k"] ** 2 * l["f_out"] * ho * wo * n
     res = {
         "ms_per_step": ms_per_step, "pixels_per_s": n * H * W * steps / dt, "step_ms": step_ms,
         "conv_tflops": conv_flops / (conv_ms * 1e-3) / 1e12, "forward_tflops": total_flops / (ms_per_step * 1e-3) / 1e12,
-        "pool_gbs": pool_bytes / (pool_ms * 1e-3) / 1e9, "conv_alg_bytes": conv_bytes / max(conv_launches, 1), "layers": layers, "ws": ws, "bs": bs, "img": img,
+        "pool_gbs": (pool_bytes / (pool_ms * 1e-3) / 1e9) if pool_ms > 0 else None, "conv_alg_bytes": conv_bytes / max(conv_launches, 1), "layers": layers, "ws": ws, "bs": bs, "img": img,
     }
     net.close()
     return res
@@ -418,7 +431,8 @@ def main():
                          "kernel": "48->48 k4 SK convolutions at d=2,4,8 (%s)"
                                    % ("conv_f32_pf_kernel<3,1,4,4,2,false,4>" if dtype == "f32" else "conv_h_ring_kernel<bf16,4,3,MAP4,8,false,3,true,4>")},
             "forward_tflops": round(r["forward_tflops"], 2),
-            "pool_gbs": round(r["pool_gbs"], 1), "pool_frac_of_hbm_peak": round(r["pool_gbs"] / HBM_PEAK_GBS, 4),
+            "pool_gbs": None if r["pool_gbs"] is None else round(r["pool_gbs"], 1),
+            "pool_frac_of_hbm_peak": None if r["pool_gbs"] is None else round(r["pool_gbs"] / HBM_PEAK_GBS, 4),
             "step_ms": r["step_ms"],
             "measured_peaks": measured_peaks(torch, B),
         })
@@ -437,7 +451,8 @@ def main():
         extras["c3_bf16_forward_8x1024"] = {
             "pixels_per_s": round(r3["pixels_per_s"], 1), "ms_per_step": round(r3["ms_per_step"], 4),
             "conv_tflops": round(r3["conv_tflops"], 1), "conv_frac_of_bf16_mfma_peak": round(r3["conv_tflops"] / 2500.0, 4),
-            "pool_gbs": round(r3["pool_gbs"], 1), "pool_frac_of_hbm_peak": round(r3["pool_gbs"] / HBM_PEAK_GBS, 4),
+            "pool_gbs": None if r3["pool_gbs"] is None else round(r3["pool_gbs"], 1),
+            "pool_frac_of_hbm_peak": None if r3["pool_gbs"] is None else round(r3["pool_gbs"] / HBM_PEAK_GBS, 4),
             "step_ms": r3["step_ms"]}
         for name, dt in (("c4_bf16_train_512", "bf16"), ("c4_as_f32_train_512", "f32")):
             rt = measure_train(torch, B, S, dt, 1, 512, 512, 20, 3, 2)

@@ -63,6 +63,19 @@ template <> struct H<2> {
     static __device__ __forceinline__ float up(unsigned short u) { return (float)__builtin_bit_cast(_Float16, u); }
 };
 
+// element-wise maximum of two pairs / two octets of unsigned 16-bit values (the order of non-negative bf16 and
+// fp16 numbers is the unsigned order of their bit patterns)
+__device__ __forceinline__ unsigned pk_max_u16(unsigned x, unsigned y)
+{
+    unsigned r;
+    asm("v_pk_max_u16 %0, %1, %2" : "=v"(r) : "v"(x), "v"(y));
+    return r;
+}
+__device__ __forceinline__ uint4v max_u16x8(uint4v x, uint4v y)
+{
+    return uint4v{pk_max_u16(x[0], y[0]), pk_max_u16(x[1], y[1]), pk_max_u16(x[2], y[2]), pk_max_u16(x[3], y[3])};
+}
+
 // positive (> 0) test on a 16-bit float bit pattern (both formats: sign bit clear, magnitude non-zero)
 __device__ __forceinline__ bool pos16(unsigned v) { return (v & 0x8000u) == 0 && (v & 0x7fffu) != 0; }
 
@@ -373,9 +386,16 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
 // or store instruction can sit in that queue for hundreds of cycles when HBM is the limit, and a
 // wave that waits there issues no MFMA; with the loads on waves of their own the multiplying waves
 // lose that time only for their stores.
-template <int DT, int KS, int MT, bool MAP4, int R, bool HAS_MASK, int S, bool RESW, int NP>
+// VPOOL (with producer waves only): the layer's ReLU output is max-pooled over the kernel-stride neighbour
+// BELOW before it is stored (the vertical half of the SK pool k = 2 at this layer's d; rows of a tile lie d
+// apart, so that neighbour is the wave's own next accumulator row).  Tiles are then walked down the columns
+// of the tile grid in contiguous runs, and the last row of a tile is carried in registers to the next one.
+// a.hd > 0 (producer waves only): the input was written by such a launch with kernel stride hd; the producer
+// waves finish its pool on the way in, tile[x] = max(in[x], in[x + hd]), in place in the LDS stage.
+template <int DT, int KS, int MT, bool MAP4, int R, bool HAS_MASK, int S, bool RESW, int NP, bool VPOOL = false>
 __global__ __launch_bounds__(CH_THREADS + 64 * NP) void conv_h_ring_kernel(ConvHArgs a)
 {
+    static_assert(!VPOOL || (NP > 0 && !HAS_MASK && (R % 2 == 0)), "vertical pooling runs in the producer-wave variant");
     constexpr int NTHREADS = CH_THREADS + 64 * NP;
     constexpr int LW = NP > 0 ? NP : CH_WAVES;                 // waves that share a chunk's loads
     extern __shared__ uint4v lds[];
@@ -390,7 +410,12 @@ __global__ __launch_bounds__(CH_THREADS + 64 * NP) void conv_h_ring_kernel(ConvH
     constexpr int VUE = KS == 1 ? 2 : 3;                       // 64-unit column groups per staged row
 
     const int d = a.d;
-    const int PW = CH_TX + (KS - 1) * d;
+    const int hd = NP > 0 ? a.hd : 0;                          // the input's pending horizontal pool distance
+    // rows from one row tile to the next: R, or (VPOOL on a launch with few tiles per workgroup) R - 1, so that every
+    // tile holds the row below its last pooled row itself and nothing is carried from tile to tile
+    const int ypitch = VPOOL ? a.ypitch : R;
+    const int PWL = CH_TX + (KS - 1) * d;                      // tile width the multiplication reads
+    const int PW = PWL + hd;                                   // staged row pitch: hd raw columns more
     const int tile_units = ROWS * PW;
     // RESW: the weights of every chunk stay in LDS for the whole kernel (one map group only) and the
     // ring stages hold input tiles only; otherwise each stage also carries its chunk's weight slab
@@ -431,15 +456,31 @@ __global__ __launch_bounds__(CH_THREADS + 64 * NP) void conv_h_ring_kernel(ConvH
     };
     auto cursor_at = [&](int t) {
         Cursor c;
-        c.xt = t % a.xtiles;
-        const int rest = t / a.xtiles;
-        c.yt = rest % a.ytiles_total;
-        c.mb = rest / a.ytiles_total;
+        if constexpr (VPOOL) {                       // y tiles fastest: consecutive tiles go down one column of tiles
+            c.yt = t % a.ytiles_total;
+            const int rest = t / a.ytiles_total;
+            c.xt = rest % a.xtiles;
+            c.mb = rest / a.xtiles;
+        } else {
+            c.xt = t % a.xtiles;
+            const int rest = t / a.xtiles;
+            c.yt = rest % a.ytiles_total;
+            c.mb = rest / a.ytiles_total;
+        }
         return c;
     };
     const int step_x = nslots % a.xtiles, step_y = (nslots / a.xtiles) % a.ytiles_total,
               step_mb = nslots / a.xtiles / a.ytiles_total;
     auto advance = [&](Cursor &c) {
+        if constexpr (VPOOL) {                       // the next tile of a contiguous run
+            int carry = ++c.yt >= a.ytiles_total;
+            c.yt -= carry ? a.ytiles_total : 0;
+            c.xt += carry;
+            carry = c.xt >= a.xtiles;
+            c.xt -= carry ? a.xtiles : 0;
+            c.mb += carry;
+            return;
+        }
         c.xt += step_x;
         int carry = c.xt >= a.xtiles;
         c.xt -= carry ? a.xtiles : 0;
@@ -473,7 +514,8 @@ __global__ __launch_bounds__(CH_THREADS + 64 * NP) void conv_h_ring_kernel(ConvH
     // they multiply, the last four after: while one wave of a SIMD sits in the memory pipeline's
     // queue, the other one keeps the matrix unit busy.
     const bool late_issue = wave >= CH_WAVES / 2;
-    const long plane_bytes_in = (long)a.H * a.W * 16;
+    const int Wmem = a.W + hd;                                 // columns of an input row in memory
+    const long plane_bytes_in = (long)a.H * Wmem * 16;
     const char *zeros = reinterpret_cast<const char *>(a.zeros);
 
     // Loads of chunk `ch` of the tile at `p` into ring stage `st`.  Exactly L load instructions for
@@ -483,14 +525,14 @@ __global__ __launch_bounds__(CH_THREADS + 64 * NP) void conv_h_ring_kernel(ConvH
     // Inside the image the address is a scalar row base plus a per-lane 32-bit column offset.
     auto issue = [&](const TilePos &p, int ch, int st) {
         uint4v *dst = lds + st * stage_units;
-        const int gy0 = p.py + d * (p.ty * R) - a.in_off;
+        const int gy0 = p.py + d * (p.ty * ypitch) - a.in_off;
         const int gx0 = p.x0 - a.in_off + lane;
         unsigned coff[VUE];
         bool cok[VUE];
 #pragma unroll
         for (int v = 0; v < VUE; ++v) {
             const int gx = gx0 + 64 * v;
-            cok[v] = gx >= 0 && gx < a.W;
+            cok[v] = gx >= 0 && gx < Wmem;
             coff[v] = (unsigned)(cok[v] ? gx : 0) * 16u;
         }
 #pragma unroll
@@ -502,7 +544,7 @@ __global__ __launch_bounds__(CH_THREADS + 64 * NP) void conv_h_ring_kernel(ConvH
             const int gy = gy0 + r * d;
             const bool rowok = o < a.c8_in && gy >= 0 && gy < a.H;
             const char *rowbase = reinterpret_cast<const char *>(a.x) + ((long)p.b * a.c8_in + (rowok ? o : 0)) * plane_bytes_in +
-                                  (long)(rowok ? gy : 0) * a.W * 16;
+                                  (long)(rowok ? gy : 0) * Wmem * 16;
 #pragma unroll
             for (int v = 0; v < VUE; ++v) {
                 const int xc = lane + 64 * v;
@@ -528,6 +570,36 @@ __global__ __launch_bounds__(CH_THREADS + 64 * NP) void conv_h_ring_kernel(ConvH
             if (blk >= WBLK) break;                              // uniform
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(wsrc + (unsigned)(blk * 1024 + lane * 16)),
                                              (__attribute__((address_space(3))) void *)(dst + tile_units + blk * 64), 16, 0, 0);
+        }
+    };
+
+    // Horizontal half of the pending pool, in place in ring stage st, on the rows this producer wave loaded
+    // itself (so its own vmcnt wait covers them): unit x of a row becomes max(unit x, unit x + hd) for the PWL
+    // units the multiplication reads.  The values are ReLU outputs (>= +0), for which the unsigned 16-bit order
+    // of the bit patterns is the numerical order in both storage types.  A row is read completely before any
+    // of it is written, because unit x + hd is itself overwritten as unit x' = x + hd.
+    auto hmax_in_place = [&](int st) {
+        uint4v *base = lds + st * stage_units;
+#pragma unroll
+        for (int u = 0; u < RU; ++u) {
+            const int rid = lw + LW * u;
+            if (rid >= ROWS) break;                              // uniform
+            uint4v *row = base + rid * PW;
+            uint4v va[VUE], vb[VUE];
+#pragma unroll
+            for (int v = 0; v < VUE; ++v) {
+                const int xc = lane + 64 * v;
+                if (xc < PWL) {
+                    va[v] = row[xc];
+                    vb[v] = row[xc + hd];
+                }
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+            for (int v = 0; v < VUE; ++v) {
+                const int xc = lane + 64 * v;
+                if (xc < PWL) row[xc] = max_u16x8(va[v], vb[v]);
+            }
         }
     };
 
@@ -621,7 +693,7 @@ __global__ __launch_bounds__(CH_THREADS + 64 * NP) void conv_h_ring_kernel(ConvH
         if constexpr (HAS_MASK) {
 #pragma unroll
             for (int y = 0; y < R; ++y) {
-                const int oy = p.py + d * (p.ty * R + y);
+                const int oy = p.py + d * (p.ty * ypitch + y);
                 if (oy >= a.Ho) continue;
                 const char *rowp = mask_base + (long)(oy * a.oy_mul + a.oy_off) * row_bytes;
 #pragma unroll
@@ -636,7 +708,7 @@ __global__ __launch_bounds__(CH_THREADS + 64 * NP) void conv_h_ring_kernel(ConvH
         }
 #pragma unroll
         for (int y = 0; y < R; ++y) {
-            const int oy = p.py + d * (p.ty * R + y);
+            const int oy = p.py + d * (p.ty * ypitch + y);
             char *rowp = img_base + (long)(oy * a.oy_mul + a.oy_off) * row_bytes;
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
@@ -727,16 +799,88 @@ __global__ __launch_bounds__(CH_THREADS + 64 * NP) void conv_h_ring_kernel(ConvH
                 const auto s1 = __builtin_amdgcn_permlane16_swap(hi[0], hi[1], false, false);
                 // even group: {own row y half, neighbour's row y half}; odd group: {neighbour's row y+1 half, own}
                 const uint4v octet = uint4v{s0[0], s1[0], s0[1], s1[1]};
-                const int oy = p.py + d * (p.ty * R + y + (g & 1));
+                const int oy = p.py + d * (p.ty * ypitch + y + (g & 1));
                 if (octet_ok && oy < a.Ho)
                     *reinterpret_cast<uint4v *>(img_base + (long)(oy * a.oy_mul + a.oy_off) * row_bytes + voff) = octet;
             }
         }
     };
 
+    // Epilogue with the vertical half of the SK pool (VPOOL): bias, ReLU, conversion as in epilogue16, then pooled
+    // row j - 1 of the tile = max(conv row j - 1, conv row j), j = 0..R-1, where conv row -1 is the last row of the
+    // tile above, carried in `carry` (have_carry: there is such a tile and this wave multiplied it).  Pooled rows
+    // are stored in pairs like the rows of epilogue16.  store = false (the extra tile in front of a run that
+    // starts inside a column of tiles) only leaves its last row behind.  The ReLU is a signed-integer max on the
+    // fp32 bit pattern (negative values and -0 become +0), after which the packed unsigned 16-bit max is the
+    // numerical max.
+    unsigned carry[VPOOL ? MT : 1][2] = {};
+    auto epilogue_vpool = [&](const TilePos &p, bool have_carry, bool store) {
+        auto pkmax = [](unsigned x, unsigned y) { return pk_max_u16(x, y); };
+        const int ox = p.x0 + wave * 16 + l16;
+        const bool colok = ox < a.Wo;
+        const int row_bytes = a.OW * 16, plane_bytes = a.OH * row_bytes;   // < 2^31 (checked by the launcher)
+        const int oxc = colok ? ox : 0;
+        char *img_base = reinterpret_cast<char *>(a.y) + ((long)p.b * a.c8_out_total + a.o8_off) * plane_bytes;
+        const int Hp = a.Ho - d;                                           // pooled rows
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const int mtile = p.mg * MT + mt;
+            float bia[4];
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) bia[r4] = bias_lds[mtile * 16 + 4 * g + r4];
+            const bool octet_ok = store && colok && mtile < a.m_tiles && mtile * 2 + (g >> 1) < a.c8_out;
+            const unsigned voff = (unsigned)((mtile * 2 + (g >> 1)) * plane_bytes + oxc * 16);
+            unsigned prev_lo = carry[mt][0], prev_hi = carry[mt][1];
+#pragma unroll
+            for (int y = 0; y < R; y += 2) {
+                unsigned lo[2], hi[2];          // this lane's half octet of pooled rows y - 1 and y
+#pragma unroll
+                for (int yy = 0; yy < 2; ++yy) {
+                    floatx4 v = acc[y + yy][mt];
+                    unsigned short h[4];
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4) {
+                        const int bits = __float_as_int(v[r4] + bia[r4]);
+                        h[r4] = H<DT>::cvt(__int_as_float(bits > 0 ? bits : 0));
+                    }
+                    const unsigned cl = (unsigned)h[0] | ((unsigned)h[1] << 16), chh = (unsigned)h[2] | ((unsigned)h[3] << 16);
+                    lo[yy] = pkmax(prev_lo, cl);
+                    hi[yy] = pkmax(prev_hi, chh);
+                    prev_lo = cl;
+                    prev_hi = chh;
+                }
+                const auto s0 = __builtin_amdgcn_permlane16_swap(lo[0], lo[1], false, false);
+                const auto s1 = __builtin_amdgcn_permlane16_swap(hi[0], hi[1], false, false);
+                const uint4v octet = uint4v{s0[0], s1[0], s0[1], s1[1]};
+                // even lane groups own pooled row y - 1, odd ones pooled row y (tile-local; -1 is the carried row's)
+                const int j = y - 1 + (g & 1);
+                const int oy = p.py + d * (p.ty * ypitch + j);
+                if (octet_ok && (j >= 0 || have_carry) && oy < Hp)
+                    *reinterpret_cast<uint4v *>(img_base + (long)oy * row_bytes + voff) = octet;
+            }
+            carry[mt][0] = prev_lo;
+            carry[mt][1] = prev_hi;
+        }
+    };
+
+    // This workgroup's tiles: every nslots-th tile of its XCD's eighth of the list, or (VPOOL) a contiguous run of
+    // that eighth -- with the tile above its first one in front when the run starts inside a column of tiles.
     int t = t_begin + slot;
-    if (t >= t_end) return;
-    const int my_tiles = (t_end - t + nslots - 1) / nslots;
+    int my_tiles = 0;
+    bool lead_in = false;
+    if constexpr (VPOOL) {
+        const long len = t_end - t_begin;
+        const int r0 = t_begin + (int)(len * slot / nslots), r1 = t_begin + (int)(len * (slot + 1) / nslots);
+        if (r0 >= r1) return;
+        const int yt0 = r0 % a.ytiles_total;             // its row tile inside its row phase (as in the ypos table)
+        const int ty0 = yt0 < a.rem * a.tiles_hi ? yt0 % a.tiles_hi : (yt0 - a.rem * a.tiles_hi) % a.tiles_lo;
+        lead_in = ty0 > 0 && ypitch == R;
+        t = r0 - (lead_in ? 1 : 0);
+        my_tiles = r1 - t;
+    } else {
+        if (t >= t_end) return;
+        my_tiles = (t_end - t + nslots - 1) / nslots;
+    }
     const int total_chunks = my_tiles * a.nchunks;
     block_sync_lds();                                   // ypos / bias tables are in place
 
@@ -770,6 +914,7 @@ __global__ __launch_bounds__(CH_THREADS + 64 * NP) void conv_h_ring_kernel(ConvH
                 __builtin_amdgcn_sched_barrier(0);
                 wait_vmcnt_at_most(allow);
                 __builtin_amdgcn_sched_barrier(0);
+                if (hd > 0) hmax_in_place(q % S);          // chunk q has landed: finish the input's pool on this wave's rows
                 block_sync_lds();
                 if (issued < total_chunks) issue_next();
             }
@@ -797,7 +942,8 @@ __global__ __launch_bounds__(CH_THREADS + 64 * NP) void conv_h_ring_kernel(ConvH
                     compute(st, ch);
                     st = st + 1 == S ? 0 : st + 1;
                 }
-                if (HAS_MASK || a.out_f32 || (R & 1)) epilogue(cur);
+                if constexpr (VPOOL) epilogue_vpool(cur, ypitch == R && cur.ty > 0 && ctile > 0, !(lead_in && ctile == 0));
+                else if (HAS_MASK || a.out_f32 || (R & 1)) epilogue(cur);
                 else epilogue16(cur);
             }
             if (ctile + 1 < my_tiles) {
@@ -911,10 +1057,10 @@ static int device_cus()
 
 // LDS bytes of the ring kernel: S stages (+ resident weights) + bias + y-tile table
 template <int KS, int MT, bool MAP4, int R, int S, bool RESW>
-static size_t ring_smem(int d, int c_out, int c8_in, int Ho)
+static size_t ring_smem(int d, int c_out, int c8_in, int Ho, int hd = 0)
 {
     constexpr int RR = R + KS - 1, OC = MAP4 ? 1 : 4, CS = MAP4 ? 1 : KS;
-    const int PW = CH_TX + (KS - 1) * d;
+    const int PW = CH_TX + (KS - 1) * d + hd;
     const size_t tile = (size_t)OC * RR * PW, slab = (size_t)CS * KS * MT * 64;
     const int nchunks = (c8_in + OC - 1) / OC;
     const int m_tiles_all = ((c_out + 15) / 16 + MT - 1) / MT * MT;
@@ -922,15 +1068,20 @@ static size_t ring_smem(int d, int c_out, int c8_in, int Ho)
     return units * 16 + (size_t)m_tiles_all * 64 + (size_t)(Ho / R + 2 * d + 2) * 4;
 }
 
-template <int DT, int KS, int MT, bool MAP4, int R, bool HAS_MASK, int S, bool RESW, int NP = 0>
+template <int DT, int KS, int MT, bool MAP4, int R, bool HAS_MASK, int S, bool RESW, int NP = 0, bool VPOOL = false>
 static hipError_t launch_conv_h_ring_m(ConvHArgs a, hipStream_t stream)
 {
     constexpr int OC = MAP4 ? 1 : 4;
-    const size_t smem = ring_smem<KS, MT, MAP4, R, S, RESW>(a.d, a.c_out, a.c8_in, a.Ho);
+    if (NP == 0 && a.hd != 0) return hipErrorInvalidValue;         // the pending pool is finished by producer waves
+    if (a.hd != 0 && (a.in_off != 0 || a.hd < 1 || CH_TX + (KS - 1) * a.d + a.hd > 64 * (KS == 1 ? 2 : 3))) return hipErrorInvalidValue;
+    if (VPOOL && (!a.relu || a.out_f32 || a.tap_maps != 0 || a.oy_mul != 1 || a.ox_mul != 1 || a.oy_off != 0 || a.ox_off != 0 ||
+                  a.OH != a.Ho - a.d || a.OW != a.Wo || a.Ho <= a.d))
+        return hipErrorInvalidValue;
+    const size_t smem = ring_smem<KS, MT, MAP4, R, S, RESW>(a.d, a.c_out, a.c8_in, a.Ho, a.hd);
     if (smem > 160 * 1024) return hipErrorInvalidValue;            // callers check the size first
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_h_ring_kernel<DT, KS, MT, MAP4, R, HAS_MASK, S, RESW, NP>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_h_ring_kernel<DT, KS, MT, MAP4, R, HAS_MASK, S, RESW, NP, VPOOL>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
@@ -942,8 +1093,19 @@ static hipError_t launch_conv_h_ring_m(ConvHArgs a, hipStream_t stream)
     a.xtiles = (a.Wo + CH_TX - 1) / CH_TX;
     const int q = a.Ho / a.d;
     a.rem = a.Ho % a.d;
+    a.ypitch = R;
     a.tiles_hi = (q + 1 + R - 1) / R;
     a.tiles_lo = (q + R - 1) / R;
+    if (VPOOL) {
+        // carried rows pay one extra tile per workgroup (the tile above its run): worth it from about eight tiles per
+        // workgroup; below that, tiles that overlap by one row (R - 1 pooled rows each) cost less
+        const long per_wg = (long)a.xtiles * (a.rem * a.tiles_hi + (a.d - a.rem) * a.tiles_lo) * a.n / (device_cus() / 8 * 8);
+        if (per_wg < 8) {
+            a.ypitch = R - 1;
+            a.tiles_hi = q >= 1 ? (q + R - 2) / (R - 1) : 1;         // q + 1 rows: q pooled rows
+            a.tiles_lo = q >= 2 ? (q - 1 + R - 2) / (R - 1) : 1;     // q rows: q - 1 pooled rows
+        }
+    }
     a.ytiles_total = a.rem * a.tiles_hi + (a.d - a.rem) * a.tiles_lo;
     if (a.tiles_lo < 1) a.tiles_lo = 1;
     if (RESW && a.mgroups != 1) return hipErrorInvalidValue;
@@ -953,7 +1115,7 @@ static hipError_t launch_conv_h_ring_m(ConvHArgs a, hipStream_t stream)
     a.total_tiles = (int)total;
     int blocks = device_cus() / 8 * 8;
     if (total < blocks) blocks = (int)((total + 7) / 8 * 8);
-    hipLaunchKernelGGL((conv_h_ring_kernel<DT, KS, MT, MAP4, R, HAS_MASK, S, RESW, NP>), dim3(blocks), dim3(CH_THREADS + 64 * NP), smem, stream, a);
+    hipLaunchKernelGGL((conv_h_ring_kernel<DT, KS, MT, MAP4, R, HAS_MASK, S, RESW, NP, VPOOL>), dim3(blocks), dim3(CH_THREADS + 64 * NP), smem, stream, a);
     return hipGetLastError();
 }
 
@@ -971,12 +1133,17 @@ template <int DT, int KS, int MT, bool MAP4, int R>
 static hipError_t launch_conv_h_ring_or_staged(const ConvHArgs &a, hipStream_t stream)
 {
     const bool one_group = ((a.c_out + 15) / 16 + MT - 1) / MT == 1;
-    if (one_group && ring_smem<KS, MT, MAP4, R, 3, true>(a.d, a.c_out, a.c8_in, a.Ho) <= 160 * 1024) {
+    if (one_group && ring_smem<KS, MT, MAP4, R, 3, true>(a.d, a.c_out, a.c8_in, a.Ho, a.hd) <= 160 * 1024) {
         // the forward 4x4 convolution of the benchmark nets: loads on four waves of their own (three waves per SIMD)
         if constexpr (KS == 4 && MAP4 && R == 8)
-            if (!a.mask) return launch_conv_h_ring_m<DT, KS, MT, MAP4, R, false, 3, true, 4>(a, stream);
+            if (!a.mask) {
+                if (a.vpool) return launch_conv_h_ring_m<DT, KS, MT, MAP4, R, false, 3, true, 4, true>(a, stream);
+                return launch_conv_h_ring_m<DT, KS, MT, MAP4, R, false, 3, true, 4>(a, stream);
+            }
+        if (a.vpool || a.hd) return hipErrorInvalidValue;
         return launch_conv_h_ring_mask<DT, KS, MT, MAP4, R, 3, true>(a, stream);
     }
+    if (a.vpool || a.hd) return hipErrorInvalidValue;              // callers ask conv_h_pool_fusable first
     if (ring_smem<KS, MT, MAP4, R, 4, false>(a.d, a.c_out, a.c8_in, a.Ho) <= 160 * 1024)
         return launch_conv_h_ring_mask<DT, KS, MT, MAP4, R, 4, false>(a, stream);
     return launch_conv_h_t<DT, KS, MT, MAP4, R>(a, stream);
@@ -1009,6 +1176,18 @@ int conv_h_mt(int c_out, int k)
     return pad3 <= pad4 ? 3 : 4;
 }
 
+// Can this forward layer run in the producer-wave kernel, which is the one that stores its output pooled
+// vertically (vpool) and finishes a pending horizontal pool of its input (hd)?
+bool conv_h_pool_fusable(int k, int d, int c_out, int c8_in, int Ho, int hd)
+{
+    if (k != 4 || c_out < 1 || c_out > 48 || d < 1 || hd < 0 || Ho < 1) return false;
+    if (CH_TX + 3 * d + hd > 64 * 3) return false;
+    const int mt = conv_h_mt(c_out, k);
+    if (mt == 1) return ring_smem<4, 1, true, 8, 3, true>(d, c_out, c8_in, Ho, hd) <= 160 * 1024;
+    if (mt == 2) return ring_smem<4, 2, true, 8, 3, true>(d, c_out, c8_in, Ho, hd) <= 160 * 1024;
+    return ring_smem<4, 3, true, 8, 3, true>(d, c_out, c8_in, Ho, hd) <= 160 * 1024;
+}
+
 bool conv_h_supported(int k, int d)
 {
     return (k >= 1 && k <= 4) && CH_TX + (k - 1) * d <= 64 * CH_VU;
@@ -1031,6 +1210,8 @@ bool conv_h_supported(int k, int d, int gemm_m)
 hipError_t launch_conv_h(const ConvHArgs &a, hipStream_t stream)
 {
     if (!conv_h_supported(a.k, a.d) || a.Ho < 1 || a.Wo < 1 || a.c8_in < 1 || a.c_out < 1) return hipErrorInvalidValue;
+    if ((a.vpool || a.hd) && (a.mt > 0 && a.mt != conv_h_mt(a.c_out, a.k))) return hipErrorInvalidValue;
+    if ((a.vpool || a.hd) && !conv_h_pool_fusable(a.k, a.d, a.c_out, a.c8_in, a.Ho, a.hd)) return hipErrorInvalidValue;
     if (a.tap_maps != 0 && (a.tap_maps < 16 || a.tap_maps % 16 != 0 || a.c_out != 4 * a.tap_maps || a.mask || a.out_f32 || a.oy_mul != 2 ||
                             a.ox_mul != 2 || a.k != 1))
         return hipErrorInvalidValue;

@@ -181,11 +181,24 @@ __global__ __launch_bounds__(HEAD_THREADS, 2) void head_fused_kernel(HeadArgs a)
 // the hidden layer.  Hidden tiles are processed in groups of at most GT so that four pixel tiles
 // (64 pixels) share each W1 fragment read from LDS; the pixels of the next pass are loaded while
 // the current one is multiplied.
-template <int DT, int HT, int KSTEPS>
+// PEND > 0: the input still lacks the horizontal half of an SK pool at kernel stride PEND (see ConvHArgs::vpool): its
+// rows hold W + PEND samples and pixel (y, x) is max(X[y][x], X[y][x + PEND]).  The kernel then walks the samples
+// in memory order (all W + PEND of a row: the partner of sample q is sample q + PEND whatever the row), loads a
+// fifth pixel tile per pass and takes the partner from the lanes PEND further on -- a row shift inside the tile,
+// and the first lanes of the next tile -- instead of loading everything twice.  Samples with x >= W are computed
+// and dropped.  The values are ReLU outputs, so the unsigned 16-bit order of the bit patterns is the numerical order.
+template <unsigned CTRL>
+__device__ __forceinline__ unsigned dpp_row_move(unsigned v)
+{
+    return (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);   // lanes shifted in from outside the row read 0
+}
+
+template <int DT, int HT, int KSTEPS, int PEND = 0>
 __global__ __launch_bounds__(HEAD_THREADS, 2) void head_fused_h_kernel(HeadArgs a)
 {
     extern __shared__ float smem[];
     constexpr int NTP = 4, GT = 6, HP = (HT + 1) / 2;   // GT even: tile pairs never straddle two groups
+    constexpr int NTL = PEND > 0 ? NTP + 1 : NTP;       // pixel tiles loaded per pass
     uint4v *w1 = reinterpret_cast<uint4v *>(smem);               // [HT][KSTEPS][64]
     uint4v *w2f = w1 + HT * KSTEPS * 64;                         // [HP][64]
     float *b1 = reinterpret_cast<float *>(w2f + HP * 64);        // [HT*16]
@@ -209,7 +222,10 @@ __global__ __launch_bounds__(HEAD_THREADS, 2) void head_fused_h_kernel(HeadArgs 
     if (tid < 4) b2[tid] = tid < a.classes ? a.b2[tid] : 0.f;
     __syncthreads();
 
-    const int plane = a.H * a.W, total = a.n * plane;          // fit 32 bits (checked by the launcher)
+    // samples per image as the kernel walks them: the W + PEND samples of every row in memory
+    const int Wm = a.W + PEND;
+    const int plane = a.H * Wm, total = a.n * plane;            // fit 32 bits (checked by the launcher)
+    const int out_plane = a.H * a.W;
     const int groups = (total + 16 * NTP - 1) / (16 * NTP);
     const int wave_id = blockIdx.x * (HEAD_THREADS / 64) + wave, wave_cnt = gridDim.x * (HEAD_THREADS / 64);
     const int c8 = (a.c_in + 7) / 8;
@@ -217,12 +233,12 @@ __global__ __launch_bounds__(HEAD_THREADS, 2) void head_fused_h_kernel(HeadArgs 
 
     // one division per pass: pixel tile pt + 1 starts 16 pixels after tile pt and may wrap into the
     // following image(s)
-    auto load_pixels = [&](int grp, uint4v (&bv)[KSTEPS][NTP]) {
+    auto load_pixels = [&](int grp, uint4v (&bv)[KSTEPS][NTL]) {
         int p = grp * (16 * NTP) + l16;
         p = p < total ? p : total - 1;
         int img = p / plane, pix = p - img * plane;
 #pragma unroll
-        for (int pt = 0; pt < NTP; ++pt) {
+        for (int pt = 0; pt < NTL; ++pt) {
             const long base = (long)img * c8 * plane + pix;
 #pragma unroll
             for (int ks = 0; ks < KSTEPS; ++ks) {
@@ -233,6 +249,26 @@ __global__ __launch_bounds__(HEAD_THREADS, 2) void head_fused_h_kernel(HeadArgs 
             pix += 16;                                           // next tile; clamp at the very end
             while (pix >= plane && img + 1 < a.n) { pix -= plane; ++img; }
             if (pix >= plane) pix = plane - 1;
+        }
+    };
+    // PEND: tile pt becomes the maximum of itself, itself shifted down by PEND lanes inside each row of 16 lanes,
+    // and the next tile shifted up by 16 - PEND
+    auto finish_pool = [&](uint4v (&bv)[KSTEPS][NTL]) {
+        if constexpr (PEND > 0) {
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ++ks)
+#pragma unroll
+                for (int pt = 0; pt < NTP; ++pt)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        unsigned v = bv[ks][pt][e];
+                        const unsigned own = PEND < 16 ? dpp_row_move<0x100 + (PEND < 16 ? PEND : 1)>(v) : 0u;                  // row_shl: lane l reads lane l + PEND
+                        const unsigned nxt = PEND < 16 ? dpp_row_move<0x110 + (PEND < 16 ? 16 - PEND : 1)>(bv[ks][pt + 1][e])   // row_shr: lane l reads lane l - (16 - PEND)
+                                                       : bv[ks][pt + 1][e];
+                        asm("v_pk_max_u16 %0, %1, %2" : "=v"(v) : "v"(v), "v"(own));
+                        asm("v_pk_max_u16 %0, %1, %2" : "=v"(v) : "v"(v), "v"(nxt));
+                        bv[ks][pt][e] = v;
+                    }
         }
     };
     auto mfma = [](uint4v av, uint4v bvv, floatx4 c) {
@@ -248,11 +284,12 @@ __global__ __launch_bounds__(HEAD_THREADS, 2) void head_fused_h_kernel(HeadArgs 
         else return __builtin_bit_cast(unsigned, __builtin_convertvector(r, halfx2));
     };
 
-    uint4v bv[KSTEPS][NTP], nx[KSTEPS][NTP];
+    uint4v bv[KSTEPS][NTL], nx[KSTEPS][NTL];
     if (wave_id < groups) load_pixels(wave_id, bv);
     for (int grp = wave_id; grp < groups; grp += wave_cnt) {
         const int nxt = grp + wave_cnt;
         load_pixels(nxt < groups ? nxt : grp, nx);               // in flight during this pass
+        finish_pool(bv);
         floatx4 z[NTP];
         {
             const floatx4 zb = g == 0 ? *reinterpret_cast<const floatx4 *>(b2) : floatx4{0.f, 0.f, 0.f, 0.f};
@@ -315,8 +352,15 @@ __global__ __launch_bounds__(HEAD_THREADS, 2) void head_fused_h_kernel(HeadArgs 
                 }
             }
             const int p = grp * (16 * NTP) + lane;
-            if (p < total) {
-                const int img = p / plane, pix = p - img * plane;
+            const int img = p / plane;
+            int pix = p - img * plane;
+            bool keep = p < total;
+            if constexpr (PEND > 0) {                             // memory sample -> output pixel; the PEND extra samples of a row are dropped
+                const int yy = pix / Wm, xx = pix - yy * Wm;
+                keep = keep && xx < a.W;
+                pix = yy * a.W + xx;
+            }
+            if (keep) {
                 float m = zc[0];
 #pragma unroll
                 for (int c = 1; c < 4; ++c)
@@ -328,16 +372,16 @@ __global__ __launch_bounds__(HEAD_THREADS, 2) void head_fused_h_kernel(HeadArgs 
                     sum += e[c];
                 }
                 const float inv = __frcp_rn(sum);
-                float *dst = a.prob + (long)img * a.classes * plane + pix;
+                float *dst = a.prob + (long)img * a.classes * out_plane + pix;
 #pragma unroll
                 for (int c = 0; c < 4; ++c)
-                    if (c < a.classes) dst[(long)c * plane] = e[c] * inv;
+                    if (c < a.classes) dst[(long)c * out_plane] = e[c] * inv;
             }
         }
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks)
 #pragma unroll
-            for (int pt = 0; pt < NTP; ++pt) bv[ks][pt] = nx[ks][pt];
+            for (int pt = 0; pt < NTL; ++pt) bv[ks][pt] = nx[ks][pt];
     }
 }
 
@@ -426,25 +470,41 @@ static hipError_t launch_head_cl(const HeadArgs &a, hipStream_t stream)
     }
 }
 
-template <int DT, int HT, int KSTEPS>
-static hipError_t launch_head_h_t(const HeadArgs &a, hipStream_t stream)
+template <int DT, int HT, int KSTEPS, int PEND>
+static hipError_t launch_head_h_p(const HeadArgs &a, hipStream_t stream)
 {
     constexpr int HP = (HT + 1) / 2;
     const size_t smem = (size_t)(HT * KSTEPS + HP) * 1024 + (size_t)(HT * 16 + 4) * 4;
     static bool attr_set = false;
     if (smem > 48 * 1024 && !attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&head_fused_h_kernel<DT, HT, KSTEPS>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&head_fused_h_kernel<DT, HT, KSTEPS, PEND>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const long total = (long)a.n * a.H * a.W;
+    const long total = (long)a.n * a.H * (a.W + PEND);
+    if (total >= 0x7fffffffL - 64) return hipErrorInvalidValue;
     const long groups = (total + 63) / 64;
     long blocks = (groups + 3) / 4;
     if (blocks > 512) blocks = 512;       // two workgroups per CU, persistent over the pixel groups
     if (blocks < 1) blocks = 1;
-    hipLaunchKernelGGL((head_fused_h_kernel<DT, HT, KSTEPS>), dim3((int)blocks), dim3(HEAD_THREADS), smem, stream, a);
+    hipLaunchKernelGGL((head_fused_h_kernel<DT, HT, KSTEPS, PEND>), dim3((int)blocks), dim3(HEAD_THREADS), smem, stream, a);
     return hipGetLastError();
+}
+
+// the pending pool distances of SK nets are the kernel strides of their convolutions: powers of two up to 16
+template <int DT, int HT, int KSTEPS>
+static hipError_t launch_head_h_t(const HeadArgs &a, hipStream_t stream)
+{
+    switch (a.hd) {
+    case 0: return launch_head_h_p<DT, HT, KSTEPS, 0>(a, stream);
+    case 1: return launch_head_h_p<DT, HT, KSTEPS, 1>(a, stream);
+    case 2: return launch_head_h_p<DT, HT, KSTEPS, 2>(a, stream);
+    case 4: return launch_head_h_p<DT, HT, KSTEPS, 4>(a, stream);
+    case 8: return launch_head_h_p<DT, HT, KSTEPS, 8>(a, stream);
+    case 16: return launch_head_h_p<DT, HT, KSTEPS, 16>(a, stream);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 // the MFMA-only 16-bit kernel covers up to 4 classes and up to 64 input maps
@@ -479,10 +539,17 @@ static hipError_t launch_head_dt(const HeadArgs &a, hipStream_t stream)
     return launch_head_cl<DT, 8>(a, stream);
 }
 
+bool head_takes_pending_pool(int dtype, int c_in, int classes, int hd)
+{
+    // the MFMA-only 16-bit kernel, instantiated for the kernel strides of the SK nets
+    return dtype != 0 && classes <= 4 && head_ksteps(dtype, c_in) <= 2 && (hd == 1 || hd == 2 || hd == 4 || hd == 8 || hd == 16);
+}
+
 hipError_t launch_head_fused(HeadArgs a, hipStream_t stream)
 {
     if (!head_supported(a.dtype, a.c_in, a.hidden, a.classes)) return hipErrorInvalidValue;
     if ((long)a.n * a.H * a.W >= 0x7fffffffL - 64) return hipErrorInvalidValue;
+    if (a.hd < 0 || (a.hd > 0 && !head_takes_pending_pool(a.dtype, a.c_in, a.classes, a.hd))) return hipErrorInvalidValue;
     a.ksteps = head_ksteps(a.dtype, a.c_in);
     if (a.dtype == 0) return launch_head_dt<0>(a, stream);
     if (a.dtype == 1) return launch_head_dt<1>(a, stream);

@@ -72,13 +72,19 @@ struct ConvHArgs {
     int c8_out_total, o8_off, OH, OW, oy_mul, oy_off, ox_mul, ox_off;
     int mt;               // map tiles per workgroup the weights were packed for; 0 = default for (c_out, k)
     int tap_maps;         // > 0 (multiple of 16): GEMM map o = tap o / tap_maps of real map o % tap_maps, stored at (y*oy_mul + tap/2, x*ox_mul + tap%2)
+    // SK pool k = 2, s = 1 fused across two launches (inference): vpool != 0: this layer's output (ReLU required) is
+    // stored as max(Y[y], Y[y + d]), Ho - d rows of Wo columns (OH = Ho - d, OW = Wo); hd > 0: the input was stored that way
+    // by a layer with kernel stride hd and has W + hd columns per row in memory, of which this launch reads
+    // max(X[x], X[x + hd]) for x < W.  Both only where conv_h_pool_fusable() says so.
+    int vpool, hd;
     const void *zeros;    // CONV_H_ZERO_BYTES of zeros in device memory, read in place of samples outside the image (the launcher
                           // allocates nothing: the owner of the plan provides the page)
     // filled in by the launcher
-    int m_tiles, mgroups, nchunks, xtiles, tiles_hi, tiles_lo, rem, ytiles_total, total_tiles;
+    int m_tiles, mgroups, nchunks, xtiles, tiles_hi, tiles_lo, rem, ytiles_total, total_tiles, ypitch;
 };
 constexpr int CONV_H_ZERO_BYTES = 4096;
 bool conv_h_supported(int k, int d);
+bool conv_h_pool_fusable(int k, int d, int c_out, int c8_in, int Ho, int hd);
 // ... and for a GEMM with gemm_m output maps (c_out forward, c_in for the data gradient) the tile fits the LDS
 bool conv_h_supported(int k, int d, int gemm_m);
 hipError_t launch_conv_h(const ConvHArgs &a, hipStream_t stream);
@@ -120,9 +126,11 @@ struct HeadArgs {
     const float *b2;      // [classes]
     float *prob;          // fp32 NCHW [n][classes][H][W]
     int dtype, n, c_in, H, W, hidden, classes;
+    int hd;               // > 0: the input lacks the horizontal half of an SK pool at kernel stride hd (rows of W + hd samples)
     int ksteps;           // filled in by the launcher
 };
 bool head_supported(int dtype, int c_in, int hidden, int classes);
+bool head_takes_pending_pool(int dtype, int c_in, int classes, int hd);
 long head_w1_packed_bytes(int dtype, int c_in, int hidden);
 hipError_t launch_pack_head_w1(const float *w1, void *out, int dtype, int hidden, int c_in, hipStream_t stream);
 hipError_t launch_head_fused(HeadArgs a, hipStream_t stream);

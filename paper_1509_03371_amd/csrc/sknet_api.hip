@@ -59,6 +59,18 @@ struct sknet {
     struct Step { int kind, arg; };
     std::vector<Step> steps;
     bool fuse_head = false;           // inference plans: last two 1x1 convs + softmax run as one kernel
+    // 16-bit inference plans: an SK pool (k = 2, s = 1, the d of the convolution in front of it) runs inside its two
+    // neighbours -- the convolution stores max(Y[y], Y[y + d]) (vpool[layer] = 1, its buffer then holds H - d rows of
+    // W columns), the layer after the pool reads max(X[x], X[x + d]) (pending[layer] = d; the fused head: pending_head)
+    std::vector<int> vpool, pending;
+    int pending_head = 0;
+    bool kept(int layer) const        // is the output of `layer` in memory in the form the layer defines?
+    {
+        if (fuse_head && layer >= (int)layers.size() - 2) return false;
+        if (vpool.empty()) return true;
+        if (vpool[layer]) return false;
+        return !(layer > 0 && vpool[layer - 1]);
+    }
     float *head_w1p = nullptr;
     float *logits_f32 = nullptr;      // 16-bit nets: fp32 logits when the last layer is a pool; else alias of act[L]
     float *dz_f32 = nullptr;          // 16-bit training: fp32 gradient of the logits before it is packed
@@ -81,6 +93,7 @@ struct sknet {
         free_dev(gbuf[0]); free_dev(gbuf[1]); free_dev(loss_partial); free_dev(wgrad_scratch);
         free_dev(logits_f32); free_dev(dz_f32); free_dev(head_w1p); free_dev(zero_page);
         steps.clear();
+        vpool.clear(); pending.clear(); pending_head = 0;
         fuse_head = false;
         for (auto &c : convs) release_conv(c);
         planned = forward_done = backward_done = false;
@@ -149,7 +162,9 @@ sk_status run_forward_step(sknet *net, int step_idx, hipStream_t stream)
         const ConvParams &c1 = net->convs[net->conv_of_layer[L - 2]], &c2 = net->convs[net->conv_of_layer[L - 1]];
         const Dims &in = net->dims[L - 2];
         sk::HeadArgs a{};
-        a.x = net->act[L - 2]; a.w1p = net->head_w1p; a.b1 = c1.b_dev; a.w2 = c2.w_dev; a.b2 = c2.b_dev;
+        a.x = net->pending_head ? net->act[L - 3] : net->act[L - 2];    // a pending pool: the buffer of the convolution before it
+        a.hd = net->pending_head;
+        a.w1p = net->head_w1p; a.b1 = c1.b_dev; a.w2 = c2.w_dev; a.b2 = c2.b_dev;
         a.prob = net->last_prob; a.dtype = net->dtype; a.n = net->n; a.c_in = in.c; a.H = in.h; a.W = in.w;
         a.hidden = c1.c_out; a.classes = c2.c_out;
         SK_HIP(sk::launch_head_fused(a, stream));
@@ -177,8 +192,14 @@ sk_status run_forward_step(sknet *net, int step_idx, hipStream_t stream)
         if (l.kind == SK_CONV) {
             const ConvParams &c = net->convs[net->conv_of_layer[li]];
             if (half) {
-                sk::ConvHArgs a = conv_h_args(c, net->dtype, net->act[li], net->n, in, l.d, l.relu, net->act[li + 1], out,
+                const int hd = net->pending[li];
+                sk::ConvHArgs a = conv_h_args(c, net->dtype, hd ? net->act[li - 1] : net->act[li], net->n, in, l.d, l.relu, net->act[li + 1], out,
                                               li == L - 1, net->zero_page);   // the last conv writes fp32 logits
+                a.hd = hd;
+                if (net->vpool[li]) {
+                    a.vpool = 1;
+                    a.OH = out.h - l.d;
+                }
                 SK_HIP(sk::launch_conv_h(a, stream));
             } else {
                 sk::ConvF32Args a = conv_args(c, net->act[li], net->n, in, l.d, l.relu, net->act[li + 1], out);
@@ -446,12 +467,42 @@ sk_status sknet_plan(sknet_t *net, int32_t n, int32_t h, int32_t w, int32_t pad,
         net->layers[L - 2].k == 1 && net->layers[L - 1].k == 1 && net->layers[L - 2].relu && !net->layers[L - 1].relu &&
         sk::head_supported(net->dtype, dims[L - 2].c, net->layers[L - 2].c_out, net->layers[L - 1].c_out))
         net->fuse_head = true;
+    net->vpool.assign(L, 0);
+    net->pending.assign(L, 0);
+    net->pending_head = 0;
+    if (mode == 0 && half) {
+        // walk forward; `carry` is the pool distance the next layer still has to apply to its input
+        int carry = 0;
+        for (int i = 0; i < L; ++i) {
+            const sk_layer &l = net->layers[i];
+            if (l.kind != SK_CONV) { carry = 0; continue; }
+            net->pending[i] = carry;
+            carry = 0;
+            if (net->fuse_head && i >= L - 2) continue;
+            if (i + 2 >= L || !l.relu) continue;
+            const sk_layer &pl = net->layers[i + 1], &nl = net->layers[i + 2];
+            if (pl.kind != SK_MAXPOOL || pl.k != 2 || pl.s != 1 || pl.d != l.d || nl.kind != SK_CONV) continue;
+            const bool self_ok = sk::conv_h_pool_fusable(l.k, l.d, l.c_out, (dims[i].c + 7) / 8, dims[i + 1].h, net->pending[i]);
+            bool next_ok;
+            if (net->fuse_head && i + 2 == L - 2)
+                next_ok = sk::head_takes_pending_pool(net->dtype, dims[L - 2].c, net->layers[L - 1].c_out, l.d);
+            else
+                next_ok = sk::conv_h_pool_fusable(nl.k, nl.d, nl.c_out, (dims[i + 2].c + 7) / 8, dims[i + 3].h, l.d);
+            if (!self_ok || !next_ok) continue;
+            net->vpool[i] = 1;
+            carry = l.d;
+            if (net->fuse_head && i + 2 == L - 2) net->pending_head = l.d;
+            ++i;                                       // the pool is spoken for
+        }
+    }
     net->steps.clear();
     net->steps.push_back({0, 0});
-    for (int i = 0; i < (net->fuse_head ? L - 2 : L); ++i) net->steps.push_back({1, i});
+    for (int i = 0; i < (net->fuse_head ? L - 2 : L); ++i)
+        if (!(i > 0 && net->vpool[i - 1])) net->steps.push_back({1, i});
     net->steps.push_back({net->fuse_head ? 3 : 2, 0});
     for (int i = 0; i <= L && st == SK_OK; ++i) {
         if (net->fuse_head && i >= L - 1) continue;   // hidden maps and logits never leave the head kernel
+        if (i >= 2 && net->vpool[i - 2]) continue;    // the output of a pool that runs inside its neighbours
         const bool f32 = (i == 0) ? !half : stored_f32(net, i - 1);
         const long count = f32 ? dims[i].count(n) : octet_floats(n, dims[i]);
         st = alloc_f(&net->act[i], count);
@@ -739,8 +790,8 @@ sk_status sknet_get_activation(sknet_t *net, int32_t layer_idx, float *nchw_host
     SK_TRY(check_net(net));
     if (!nchw_host || layer_idx < -1 || layer_idx >= (int)net->layers.size()) return fail(SK_EINVAL, "get_activation: bad arguments");
     if (!net->forward_done) return fail(SK_ESTATE, "get_activation: no forward pass yet");
-    if (net->fuse_head && layer_idx >= (int)net->layers.size() - 2)
-        return fail(SK_ESTATE, "get_activation: this plan fuses the last two layers; plan with mode 2 to keep them");
+    if (layer_idx >= 0 && !net->kept(layer_idx))
+        return fail(SK_ESTATE, "get_activation: this plan fuses layer %d with its neighbours; plan with mode 2 to keep every layer", layer_idx);
     SK_HIP(hipStreamSynchronize(net->last_stream));
     const int i = layer_idx + 1;
     const Dims &dm = net->dims[i];
@@ -803,7 +854,8 @@ sk_status sknet_step_name(const sknet_t *net, int32_t step, char *name, int32_t 
     else if (st.kind == 3) snprintf(name, cap, "head_fused");
     else {
         const sk_layer &l = net->layers[st.arg];
-        if (l.kind == SK_CONV) snprintf(name, cap, "conv%d_k%d_d%d_o%d", st.arg, l.k, l.d, l.c_out);
+        if (l.kind == SK_CONV)
+            snprintf(name, cap, "conv%d_k%d_d%d_o%d%s%s", st.arg, l.k, l.d, l.c_out, net->pending[st.arg] ? "_hpool" : "", net->vpool[st.arg] ? "_vpool" : "");
         else snprintf(name, cap, "pool%d_k%d_d%d_s%d", st.arg, l.k, l.d, l.s);
     }
     return SK_OK;

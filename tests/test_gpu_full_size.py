@@ -24,33 +24,61 @@ def make_net(layers, ws, bs, dtype):
     return net
 
 
-def test_c3_bf16_forward_8x1024_sampled_windows():
+def sample_windows(n, H, win, rng):
+    """Per image: the four corners (mirror padding), four windows that straddle tile seams of the 16-bit
+    convolution's tiling (columns 128k, rows 64k: every row-tile boundary 8*d of d = 1, 2, 4, 8 passes there)
+    and two random places."""
+    places = []
+    for b in range(n):
+        places += [(b, 0, 0), (b, 0, H - win), (b, H - win, 0), (b, H - win, H - win)]
+        for _ in range(4):
+            kx, ky = int(rng.integers(1, H // 128)), int(rng.integers(1, H // 64))
+            places.append((b, 64 * ky - win // 2, 128 * kx - win // 2))
+        places += [(b, int(rng.integers(0, H - win)), int(rng.integers(0, H - win))) for _ in range(2)]
+    return places
+
+
+@pytest.mark.parametrize("dtype,n", [("bf16", 8), ("f16", 2)])
+def test_c3_forward_1024_sampled_windows(dtype, n):
+    """The inference plan bench.py times (fused layers: probabilities only) and a plan that keeps every
+    layer, whose fp32 logits carry the 2e-2 relative bound; both against oracle windows."""
     layers = S.sknet_layers()
     ws, bs = S.he_normal_weights(layers, 1, 1001)
-    n, H = 8, 1024
+    H = 1024
     img = S.em_like_batch(n, H, H, 3)
-    net = make_net(layers, ws, bs, "bf16")
+    timg = torch.from_numpy(img).cuda()
+    net = make_net(layers, ws, bs, dtype)
     net.plan(n, H, H, pad=True)                      # inference plan, as timed by bench.py
-    prob = net.forward(torch.from_numpy(img).cuda()).cpu().numpy()
+    prob = net.forward(timg).cpu().numpy()
     assert prob.shape == (n, 2, H, H)
     assert np.isfinite(prob).all()
     assert np.abs(prob.sum(1) - 1).max() < 1e-5
-    v = net.context()
-    half = v // 2
-    rng = np.random.default_rng(99)
-    win = 24
-    # corners (mirror padding), tile seams of the 128-column / 8-row tiling, and random places
-    places = [(0, 0, 0), (7, H - win, H - win), (3, 0, H - win), (5, 500, 120), (2, 1000, 250)]
-    places += [(int(rng.integers(0, n)), int(rng.integers(0, H - win)), int(rng.integers(0, H - win))) for _ in range(7)]
-    worst = 0.0
-    for b, y0, x0 in places:
-        padded = OL.mirror_pad(img[b:b + 1], half, half, half, half)
-        crop = padded[:, :, y0:y0 + win + v, x0:x0 + win + v]
-        ref = ON.sknet_forward(crop, layers, ws, bs, pad=False)
-        err = np.abs(prob[b:b + 1, :, y0:y0 + win, x0:x0 + win] - ref).max()
-        worst = max(worst, err)
-        assert err <= HALF_TOL, (b, y0, x0, err)
+    net.plan(n, H, H, pad=True, keep=True)           # every layer kept: the logits are an output
+    prob_keep = net.forward(timg).cpu().numpy()
+    logits = net.get_activation(len(layers) - 1)
     net.close()
+    v = 60
+    half = v // 2
+    win = 24
+    places = sample_windows(n, H, win, np.random.default_rng(99))
+    assert len(places) >= 10 * n
+    padded = {}
+    refs = []
+    for b, y0, x0 in places:
+        if b not in padded:
+            padded[b] = OL.mirror_pad(img[b:b + 1], half, half, half, half)
+        crop = padded[b][:, :, y0:y0 + win + v, x0:x0 + win + v]
+        ref_prob, acts, _ = ON.sknet_forward(crop, layers, ws, bs, pad=False, keep=True)
+        refs.append((ref_prob, acts[-1]))
+    zmax = max(np.abs(z).max() for _, z in refs)
+    worst_z = worst_p = 0.0
+    for (b, y0, x0), (ref_prob, ref_z) in zip(places, refs):
+        ez = np.abs(logits[b:b + 1, :, y0:y0 + win, x0:x0 + win] - ref_z).max() / zmax
+        ep = max(np.abs(prob[b:b + 1, :, y0:y0 + win, x0:x0 + win] - ref_prob).max(),
+                 np.abs(prob_keep[b:b + 1, :, y0:y0 + win, x0:x0 + win] - ref_prob).max())
+        worst_z, worst_p = max(worst_z, ez), max(worst_p, ep)
+        assert ez <= HALF_TOL and ep <= HALF_TOL, (b, y0, x0, ez, ep)
+    print(dtype, "%d windows: logits rel err %.3e, probabilities abs err %.3e" % (len(places), worst_z, worst_p), flush=True)
 
 
 def test_c4_bf16_training_step_512():
@@ -83,17 +111,3 @@ def test_c4_bf16_training_step_512():
         w1, b1 = net.get_weights(i)
         assert np.abs(w1 - (before[i][0] - np.float32(0.01) * grads[i][0])).max() <= 1e-7
     net.close()
-
-
-def test_c3_fp16_matches_bf16_within_tolerance_on_one_image():
-    """The fp16 instantiation of the same kernels at 1024^2 (one image): against the bf16 result."""
-    layers = S.sknet_layers()
-    ws, bs = S.he_normal_weights(layers, 1, 1001)
-    img = S.em_like_batch(1, 1024, 1024, 3)
-    out = {}
-    for dt in ("bf16", "f16"):
-        net = make_net(layers, ws, bs, dt)
-        net.plan(1, 1024, 1024, pad=True)
-        out[dt] = net.forward(torch.from_numpy(img).cuda()).cpu().numpy()
-        net.close()
-    assert np.abs(out["bf16"] - out["f16"]).max() <= 2 * HALF_TOL
