@@ -49,6 +49,9 @@ struct WgradArgs {
     // convolution: see launch_conv_f32); grp_shift = 31: no groups
     long x_bstride, grp_skip;
     int grp_shift;
+    // 16-bit matrix path: bias_part != nullptr makes the kernel sum dY over the pixels as well (one more MFMA per map tile
+    // against a fragment of ones) and write bias_part[map * gridDim.x + blockIdx.x]
+    float *bias_part;
 };
 
 template <int MB, int NB, int DT>
@@ -329,6 +332,11 @@ __global__ __launch_bounds__(256) void wgrad_h_kernel(WgradArgs a)
     for (int m = 0; m < MB; ++m)
 #pragma unroll
         for (int q = 0; q < NB; ++q) acc[m][q] = floatx4{0.f, 0.f, 0.f, 0.f};
+    // bias gradient: map tile m of this workgroup is summed by wave m (MB <= 4) in the column group 0 blocks
+    const bool sum_dy = a.bias_part != nullptr && ngroup == 0 && wave < MB && mo0 + wave < a.MTo;
+    floatx4 bacc = floatx4{0.f, 0.f, 0.f, 0.f};
+    const unsigned one2 = DT == 1 ? 0x3F803F80u : 0x3C003C00u;      // two ones in the storage type
+    const uint4v ones = uint4v{one2, one2, one2, one2};
 
     const long xplane = (long)a.H * a.W, yplane = (long)a.Ho * a.Wo;
     const uint4v *dyp = static_cast<const uint4v *>(a.dy), *xp = static_cast<const uint4v *>(a.x);
@@ -432,6 +440,19 @@ __global__ __launch_bounds__(256) void wgrad_h_kernel(WgradArgs a)
 #pragma unroll
                 for (int m = 0; m < MB; ++m) acc[m][q] = mfma32<DT>(av[m], bv, acc[m][q]);
             }
+            if (sum_dy) {                                        // wave-uniform
+                uint4v aw = av[0];
+#pragma unroll
+                for (int m = 1; m < MB; ++m) aw = wave == m ? av[m] : aw;
+                bacc = mfma32<DT>(aw, ones, bacc);
+            }
+        }
+    }
+    if (sum_dy && l16 == 0) {                                   // every column of bacc holds the same sums
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+            const int o = (mo0 + wave) * 16 + 4 * g + r4;
+            if (o < a.c_out) a.bias_part[(long)o * gridDim.x + blockIdx.x] = bacc[r4];
         }
     }
     const long ncols = (long)a.NTk * 16;
@@ -557,6 +578,10 @@ static int wgrad_max_copies(int groups)
     return c < 1 ? 1 : c;
 }
 
+// floats of the bias partials: one per map and per slice (the slices of bias_grad_kernel, or one per workgroup
+// of the 16-bit kernel, which sums dY itself)
+static size_t wgrad_bias_floats(int c_out) { return (size_t)(c_out + 15) / 16 * 16 * (WG_MAX_BLOCKS > BG_SLICES ? WG_MAX_BLOCKS : BG_SLICES); }
+
 size_t wgrad_f32_scratch_floats(int c_out, int c_in, int k)
 {
     // private dW copies (the larger of what the fp32 and the 16-bit tiling ask for), then the bias partials
@@ -566,7 +591,7 @@ size_t wgrad_f32_scratch_floats(int c_out, int c_in, int k)
     int copies = wgrad_max_copies(wgrad_tile_groups(MTo, NTk, MB, NB));
     wgrad_tiling(c_out, c_in, k, true, MTo, NTk, MB, NB);
     copies = std::max(copies, wgrad_max_copies(wgrad_tile_groups(MTo, NTk, MB, NB)));
-    return (size_t)copies * MTo * 16 * NTk * 16 + (size_t)(c_out + 7) / 8 * 8 * BG_SLICES;
+    return (size_t)copies * MTo * 16 * NTk * 16 + wgrad_bias_floats(c_out);
 }
 
 template <int MB, int NB, int DT>
@@ -616,7 +641,6 @@ static size_t wgrad_copy_floats(int c_out, int c_in, int k)
 {
     return (size_t)((c_out + 15) / 16 * 16) * (size_t)((c_in * k * k + 15) / 16 * 16);
 }
-static size_t wgrad_bias_floats(int c_out) { return (size_t)(c_out + 7) / 8 * 8 * BG_SLICES; }
 
 size_t wgrad_min_scratch_floats(int c_out, int c_in, int k) { return wgrad_copy_floats(c_out, c_in, k) + wgrad_bias_floats(c_out); }
 
@@ -635,7 +659,7 @@ static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, floa
     } else if (DT != 0 && x_bstride != 0) {
         return hipErrorInvalidValue;
     }
-    a.x = x; a.dy = dy; a.scratch = scratch;
+    a.x = x; a.dy = dy; a.scratch = scratch; a.bias_part = nullptr;
     a.n = n; a.c_in = c_in; a.H = H; a.W = W; a.c_out = c_out; a.k = k; a.d = d;
     a.Ho = H - (k - 1) * d; a.Wo = W - (k - 1) * d;
     if (a.Ho < 1 || a.Wo < 1) return hipErrorInvalidValue;
@@ -671,6 +695,9 @@ static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, floa
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
     const long per_cu = (long)(160 * 1024) / (long)(smem > 1 ? smem : 1);
     long resident = (long)cus * (per_cu < 1 ? 1 : (per_cu > 2 ? 2 : per_cu));
+    // 16-bit path, few segments per workgroup (one 512^2 image): the private copies -- written once per workgroup, read
+    // once by the reduction -- cost more than a second workgroup per CU hides (measured 96 + 12 -> 87 + 7 us per layer)
+    if (h_path && wgrad_tile_groups(a.MTo, a.NTk, MB, NB) == 1 && a.NTk >= 48 && a.total_segs < 24L * 2 * cus && resident > cus) resident = cus;
     if (resident > WG_MAX_BLOCKS) resident = WG_MAX_BLOCKS;
     const int groups = wgrad_tile_groups(a.MTo, a.NTk, MB, NB);
     int max_copies = wgrad_max_copies(groups);
@@ -684,6 +711,9 @@ static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, floa
     long copies = (resident + groups - 1) / groups;
     if (copies > max_copies) copies = max_copies;
     const int blocks = a.total_segs < copies ? a.total_segs : (int)copies;
+    float *bias_part = scratch + (size_t)max_copies * a.MTo * 16 * a.NTk * 16;
+    const bool bias_in_kernel = db && h_path && MB <= 4;
+    if (bias_in_kernel) a.bias_part = bias_part;
     hipError_t e = hipErrorInvalidValue;
     if constexpr (DT != 0) {
         if (h_path) {
@@ -709,8 +739,7 @@ static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, floa
     if (e != hipSuccess) return e;
     // stage 1 of the bias gradient into the partials behind the dW copies, then one kernel that sums
     // the copies and the partials
-    float *bias_part = scratch + (size_t)max_copies * a.MTo * 16 * a.NTk * 16;
-    if (db) {
+    if (db && !bias_in_kernel) {
         const long plane = (long)a.Ho * a.Wo;
         if constexpr (DT == 0) {
             hipLaunchKernelGGL(bias_grad_kernel, dim3(BG_SLICES, c_out), dim3(256), 0, stream, static_cast<const float *>(dy), bias_part,
@@ -725,7 +754,7 @@ static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, floa
     const long total = (long)c_out * K;
     const int dw_blocks = (int)((total + RED_ELEMS - 1) / RED_ELEMS), db_blocks = db ? (c_out + RED_ELEMS - 1) / RED_ELEMS : 0;
     hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(dw_blocks + db_blocks), dim3(256), 0, stream, scratch, dw, blocks, c_out, K,
-                       a.MTo * 16, a.NTk * 16, dw_blocks, bias_part, db, BG_SLICES);
+                       a.MTo * 16, a.NTk * 16, dw_blocks, bias_part, db, bias_in_kernel ? blocks : BG_SLICES);
     return hipGetLastError();
 }
 
