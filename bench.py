@@ -161,10 +161,10 @@ def measure_unet(torch, B, S, dtype, steps, warmup):
             "tflops": round(gflop / dt / 1e3, 1)}
 
 
-def measure_usknet(torch, B, S, steps, warmup):
-    """USK-Net forward of the paper's USK configuration table (3 x 692^2 -> 2 x 512^2), fp32."""
+def measure_usknet(torch, B, S, steps, warmup, dtype="f32"):
+    """USK-Net forward of the paper's USK configuration table (3 x 692^2 -> 2 x 512^2)."""
     params = S.usknet_params(3, 2, 1006, base=64)
-    net = B.USKNet(3, 2, base_ch=64)
+    net = B.USKNet(3, 2, base_ch=64, dtype=dtype)
     for i, name in enumerate(S.USKNET_PARAM_NAMES):
         net.set_weights(i, *params[name])
     net.plan(1, 692, 692)
@@ -225,13 +225,13 @@ def measure_unet_train(torch, B, S, which, steps, warmup):
     return {"ms_per_step": round(dt * 1e3, 3), "labelled_pixels_per_s": round(out * out / dt, 1), "loss_after": round(final, 4)}
 
 
-def measure_paper_sknet(torch, B, S, steps, warmup):
+def measure_paper_sknet(torch, B, S, steps, warmup, dtype="f32"):
     """The paper's own SK network (Section 3.3.2: 3 x 229^2 after padding -> 2 x 128^2; its inner product
-    is a k = 10, d = 8 convolution 192 -> 1024, 644 of the 695 GFLOP) in fp32: the workload of the
+    is a k = 10, d = 8 convolution 192 -> 1024, 644 of the 695 GFLOP): the workload of the
     paper's label-throughput and layer-efficiency tables."""
     layers = S.paper_sknet_layers()
     ws, bs = S.he_normal_weights(layers, 3, 1003)
-    net = B.SKNet(layers, 3, 2, dtype="f32")
+    net = B.SKNet(layers, 3, 2, dtype=dtype)
     for i, (w, b) in enumerate(zip(ws, bs)):
         net.set_weights(i, w, b)
     net.plan(1, 128, 128, pad=True)
@@ -252,6 +252,7 @@ def measure_paper_sknet(torch, B, S, steps, warmup):
     return {"ms_per_step": round(dt * 1e3, 3), "pixels_per_s": round(128 * 128 / dt, 1),
             "forward_tflops": round(694.6 / dt / 1e3, 1), name + "_ms": round(ip1_ms, 3),
             name + "_tflops": round(644.23 / ip1_ms, 1),
+            name + "_frac_of_mfma_peak": round(644.23 / ip1_ms / PEAK_TFLOPS[dtype], 4),
             "paper_pixels_per_s": {"W9100 OpenCL": 59513, "GTX 980 CUDA": 85460}}
 
 
@@ -349,7 +350,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", choices=["c2", "c3", "c4", "c5", "c5bf16", "usk", "papersk", "sk3d", "sk3dtrain", "unettrain", "usktrain", "copy"], default="c2")
+    ap.add_argument("--workload", choices=["c2", "c3", "c4", "c5", "c5bf16", "usk", "uskbf16", "papersk", "paperskbf16", "sk3d", "sk3dtrain", "unettrain", "usktrain",
+                                           "copy"], default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
     args = ap.parse_args()
@@ -396,20 +398,21 @@ def main():
         print(json.dumps(out))
         return
 
-    if args.workload in ("usk", "papersk", "sk3d", "sk3dtrain"):
+    if args.workload in ("usk", "uskbf16", "papersk", "paperskbf16", "sk3d", "sk3dtrain"):
+        wdt = "bf16" if args.workload.endswith("bf16") else "f32"
         if args.workload == "sk3dtrain":
             r = measure_sknet3d_train(torch, B, S, args.steps, args.warmup)
             px, what = r["labelled_voxels_per_s"], "3-D SK net training step, 81x145x145 -> 64x128x128 labels, fp32: forward, masked softmax loss, backward, SGD; value = labelled voxels per second"
         elif args.workload == "sk3d":
             r = measure_sknet3d(torch, B, S, args.steps, args.warmup)
             px, what = r["labelled_voxels_per_s"], "3-D SK net forward, 81x145x145 -> 2x64x128x128 (context 17), fp32; value = labelled voxels per second"
-        elif args.workload == "usk":
-            r = measure_usknet(torch, B, S, args.steps, args.warmup)
-            px, what = r["labelled_pixels_per_s"], "USK-Net forward 1x3x692x692 -> 2x512x512, fp32 (the paper's USK configuration table)"
+        elif args.workload in ("usk", "uskbf16"):
+            r = measure_usknet(torch, B, S, args.steps, args.warmup, wdt)
+            px, what = r["labelled_pixels_per_s"], "USK-Net forward 1x3x692x692 -> 2x512x512, %s (the paper's USK configuration table)" % wdt
         else:
-            r = measure_paper_sknet(torch, B, S, args.steps, args.warmup)
-            px, what = r["pixels_per_s"], "the paper's SK-Net forward, 3x128x128 -> 2x128x128 (padded to 229), fp32"
-        out.update({"value": px, "ms_per_step": r["ms_per_step"], "dtype": "f32",
+            r = measure_paper_sknet(torch, B, S, args.steps, args.warmup, wdt)
+            px, what = r["pixels_per_s"], "the paper's SK-Net forward, 3x128x128 -> 2x128x128 (padded to 229), %s" % wdt
+        out.update({"value": px, "ms_per_step": r["ms_per_step"], "dtype": wdt,
                     "config": {"workload": what, "global_batch": 1, "parallelism": "single GPU"}, "roofline": None, "detail": r})
         print(json.dumps(out))
         return
@@ -460,7 +463,9 @@ def main():
         for name, dt in (("c5_unet_572_f32", "f32"), ("c5_unet_572_bf16", "bf16")):
             extras[name] = measure_unet(torch, B, S, dt, 10, 3)
         extras["paper_sknet_128_f32"] = measure_paper_sknet(torch, B, S, 5, 2)
+        extras["paper_sknet_128_bf16"] = measure_paper_sknet(torch, B, S, 5, 2, "bf16")
         extras["usknet_692_f32_forward"] = measure_usknet(torch, B, S, 5, 2)
+        extras["usknet_692_bf16_forward"] = measure_usknet(torch, B, S, 5, 2, "bf16")
         extras["sknet3d_81x145x145_f32_forward"] = measure_sknet3d(torch, B, S, 5, 2)
         extras["sknet3d_81x145x145_f32_train_step"] = measure_sknet3d_train(torch, B, S, 3, 1)
         extras["unet_572_f32_train_step"] = measure_unet_train(torch, B, S, "unet", 3, 1)

@@ -13,7 +13,9 @@
 // 16-byte unit and 16 lanes write 256 contiguous bytes.
 //
 // How the 32 K values of one MFMA are chosen ("column step"):
-//   MAP4 (k = 4): the four lane groups take the four kernel columns j = g of one input octet.
+//   MAP4 (k >= 4): the four lane groups take four consecutive kernel columns j = 4*cs + g of one input octet
+//                  (ceil(k/4) column steps; columns j >= k carry zero weights and read the staged tile
+//                  (k - 1) < j columns further right, which is why the tile is staged that wide).
 //   otherwise   : the four lane groups take four input octets at one kernel column j.
 // Either way a B fragment is tied to one INPUT row r of the staged tile and is reused for every
 // kernel row i (output row y = r - i) and every output-map tile: the rows of a tile lie d apart
@@ -106,20 +108,21 @@ struct TilePos {
     int b, mg, py, ty, x0;
 };
 
-template <int DT, int KS, int MT, bool MAP4, int R, bool HAS_MASK>
+template <int DT, int KS, int MT, bool MAP4, int R, bool HAS_MASK, int VU = CH_VU>
 __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
 {
     extern __shared__ uint4v lds[];
     constexpr int RR = R + KS - 1;
     constexpr int OC = MAP4 ? 1 : 4;            // input octets per chunk
-    constexpr int CS = MAP4 ? 1 : KS;           // column steps per chunk
+    constexpr int CS = MAP4 ? (KS + 3) / 4 : KS; // column steps per chunk
+    constexpr int TAPW = MAP4 ? 4 * CS : KS;    // kernel columns the tile is staged for
     constexpr int ROWS = OC * RR;               // staged tile rows per chunk
     constexpr int RU = (ROWS + CH_WAVES - 1) / CH_WAVES;
     constexpr int WUNITS = CS * KS * MT * 64;   // 16-byte units of the weight slab of one chunk
     constexpr int WU = (WUNITS + CH_THREADS - 1) / CH_THREADS;
 
     const int d = a.d;
-    const int PW = CH_TX + (KS - 1) * d;        // tile width in 16-byte units
+    const int PW = CH_TX + (TAPW - 1) * d;      // tile width in 16-byte units
     const int tile_units = ROWS * PW;
     const int stage_units = tile_units + WUNITS;
 
@@ -152,7 +155,7 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
 
     // chunk-invariant column bookkeeping of this lane
     const long plane = (long)a.H * a.W;
-    uint4v xr[RU][CH_VU];
+    uint4v xr[RU][VU];
     uint4v wr[WU];
 
     auto prefetch = [&](const TilePos &p, int ch) {
@@ -169,7 +172,7 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
             gy = gy < 0 ? 0 : (gy >= a.H ? a.H - 1 : gy);
             const uint4v *row = reinterpret_cast<const uint4v *>(a.x) + ((long)p.b * a.c8_in + o) * plane + (long)gy * a.W;
 #pragma unroll
-            for (int v = 0; v < CH_VU; ++v) {
+            for (int v = 0; v < VU; ++v) {
                 int gx = gx0 + lane + 64 * v;
                 gx = gx < 0 ? 0 : (gx >= a.W ? a.W - 1 : gx);
                 xr[u][v] = row[gx];
@@ -196,7 +199,7 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
                 const int gy = gy0 + r * d;
                 const bool rowok = (ch * OC + oc < a.c8_in) && gy >= 0 && gy < a.H;
 #pragma unroll
-                for (int v = 0; v < CH_VU; ++v) {
+                for (int v = 0; v < VU; ++v) {
                     const int xc = lane + 64 * v, gx = gx0 + xc;
                     if (xc < PW) dst[rid * PW + xc] = (rowok && gx >= 0 && gx < a.W) ? xr[u][v] : zero;
                 }
@@ -225,7 +228,7 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
             for (int i = 0; i < KS; ++i)
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) afr[i][mt] = wl[((cs * KS + i) * MT + mt) * 64 + lane];
-            const int off = (MAP4 ? g * d : g * RR * PW + cs * d) + wave * 16 + l16;
+            const int off = (MAP4 ? (4 * cs + g) * d : g * RR * PW + cs * d) + wave * 16 + l16;
             uint4v bcur = tile[off];
 #pragma unroll
             for (int r = 0; r < RR; ++r) {
@@ -402,6 +405,7 @@ __global__ __launch_bounds__(CH_THREADS + 64 * NP) void conv_h_ring_kernel(ConvH
     constexpr int RR = R + KS - 1;
     constexpr int OC = MAP4 ? 1 : 4;
     constexpr int CS = MAP4 ? 1 : KS;
+    static_assert(!MAP4 || KS == 4, "the ring kernel maps the four lane groups to the four columns of a 4x4 kernel");
     constexpr int ROWS = OC * RR;
     constexpr int RU = (ROWS + LW - 1) / LW;
     constexpr int WUNITS = CS * KS * MT * 64;
@@ -993,19 +997,20 @@ __global__ __launch_bounds__(CH_THREADS + 64 * NP) void conv_h_ring_kernel(ConvH
     }
 }
 
-template <int DT, int KS, int MT, bool MAP4, int R, bool HAS_MASK>
+template <int DT, int KS, int MT, bool MAP4, int R, bool HAS_MASK, int VU = CH_VU>
 static hipError_t launch_conv_h_m(ConvHArgs a, hipStream_t stream)
 {
-    constexpr int RR = R + KS - 1, OC = MAP4 ? 1 : 4, CS = MAP4 ? 1 : KS;
-    const int PW = CH_TX + (KS - 1) * a.d;
-    if (PW > 64 * CH_VU) return hipErrorInvalidValue;
+    constexpr int RR = R + KS - 1, OC = MAP4 ? 1 : 4, CS = MAP4 ? (KS + 3) / 4 : KS, TAPW = MAP4 ? 4 * CS : KS;
+    const int PW = CH_TX + (TAPW - 1) * a.d;
+    if (PW > 64 * VU) return hipErrorInvalidValue;
+    if (a.vpool || a.hd) return hipErrorInvalidValue;
     const size_t stage = (size_t)OC * RR * PW + (size_t)CS * KS * MT * 64;
     const int m_tiles_all = ((a.c_out + 15) / 16 + MT - 1) / MT * MT;
     const size_t smem = 2 * stage * 16 + (size_t)m_tiles_all * 16 * sizeof(float);
     if (smem > 160 * 1024) return hipErrorInvalidValue;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_h_kernel<DT, KS, MT, MAP4, R, HAS_MASK>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_h_kernel<DT, KS, MT, MAP4, R, HAS_MASK, VU>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
@@ -1033,15 +1038,26 @@ static hipError_t launch_conv_h_m(ConvHArgs a, hipStream_t stream)
     }
     int blocks = cus / 8 * 8;               // one workgroup per CU, a multiple of the 8 XCDs
     if (total < blocks) blocks = (int)((total + 7) / 8 * 8);
-    hipLaunchKernelGGL((conv_h_kernel<DT, KS, MT, MAP4, R, HAS_MASK>), dim3(blocks), dim3(CH_THREADS), smem, stream, a);
+    hipLaunchKernelGGL((conv_h_kernel<DT, KS, MT, MAP4, R, HAS_MASK, VU>), dim3(blocks), dim3(CH_THREADS), smem, stream, a);
     return hipGetLastError();
 }
 
-template <int DT, int KS, int MT, bool MAP4, int R>
+template <int DT, int KS, int MT, bool MAP4, int R, int VU = CH_VU>
 static hipError_t launch_conv_h_t(const ConvHArgs &a, hipStream_t stream)
 {
-    if (a.mask) return launch_conv_h_m<DT, KS, MT, MAP4, R, true>(a, stream);
-    return launch_conv_h_m<DT, KS, MT, MAP4, R, false>(a, stream);
+    if (a.mask) return launch_conv_h_m<DT, KS, MT, MAP4, R, true, VU>(a, stream);
+    return launch_conv_h_m<DT, KS, MT, MAP4, R, false, VU>(a, stream);
+}
+
+// kernels larger than 4x4: the register-staged kernel with the lane groups on four consecutive kernel columns, four
+// output rows per tile, forward only; tiles wider than 192 units (10x10 at d = 8) stage a fourth column group per row
+template <int DT, int KS, int MT>
+static hipError_t launch_conv_h_big(const ConvHArgs &a, hipStream_t stream)
+{
+    if (a.mask) return hipErrorInvalidValue;
+    constexpr int TAPW = 4 * ((KS + 3) / 4);
+    if (CH_TX + (TAPW - 1) * a.d > 64 * CH_VU) return launch_conv_h_m<DT, KS, MT, true, 4, false, 4>(a, stream);
+    return launch_conv_h_m<DT, KS, MT, true, 4, false, CH_VU>(a, stream);
 }
 
 static int device_cus()
@@ -1161,6 +1177,11 @@ static hipError_t launch_conv_h_mt(const ConvHArgs &a, hipStream_t stream)
     case 4:
         if constexpr (MT <= 3) return launch_conv_h_ring_or_staged<DT, 4, MT, true, 8>(a, stream);
         else return launch_conv_h_ring_or_staged<DT, 4, MT, true, 4>(a, stream);
+    case 5: if constexpr (MT <= 3) return launch_conv_h_big<DT, 5, MT>(a, stream); else return hipErrorInvalidValue;
+    case 6: if constexpr (MT <= 3) return launch_conv_h_big<DT, 6, MT>(a, stream); else return hipErrorInvalidValue;
+    case 7: if constexpr (MT <= 3) return launch_conv_h_big<DT, 7, MT>(a, stream); else return hipErrorInvalidValue;
+    case 8: if constexpr (MT <= 2) return launch_conv_h_big<DT, 8, MT>(a, stream); else return hipErrorInvalidValue;
+    case 10: if constexpr (MT <= 2) return launch_conv_h_big<DT, 10, MT>(a, stream); else return hipErrorInvalidValue;
     default: return hipErrorInvalidValue;
     }
 }
@@ -1170,7 +1191,12 @@ static hipError_t launch_conv_h_mt(const ConvHArgs &a, hipStream_t stream)
 int conv_h_mt(int c_out, int k)
 {
     const int tiles = (c_out + 15) / 16;
+    // kernels beyond 4x4: the weight slab of a chunk is ceil(k/4)*k KB per map tile and shares the LDS with a tile of
+    // k + 3 rows, twice (two stages)
+    if (k >= 9) return 1;
+    if (k >= 8) return tiles < 2 ? tiles : 2;
     if (tiles <= 2) return tiles;
+    if (k >= 5) return 3;
     const int pad3 = (tiles + 2) / 3 * 3, pad4 = (tiles + 3) / 4 * 4;
     if (k == 3) return 3;
     return pad3 <= pad4 ? 3 : 4;
@@ -1188,9 +1214,14 @@ bool conv_h_pool_fusable(int k, int d, int c_out, int c8_in, int Ho, int hd)
     return ring_smem<4, 3, true, 8, 3, true>(d, c_out, c8_in, Ho, hd) <= 160 * 1024;
 }
 
+// widest staged tile: the 4x4 and smaller kernels three 64-unit groups per row, the larger ones (register-staged
+// kernel only) four
+static int conv_h_tile_width(int k, int d) { return CH_TX + ((k >= 4 ? 4 * ((k + 3) / 4) : k) - 1) * d; }
+
 bool conv_h_supported(int k, int d)
 {
-    return (k >= 1 && k <= 4) && CH_TX + (k - 1) * d <= 64 * CH_VU;
+    if (k >= 1 && k <= 4) return conv_h_tile_width(k, d) <= 64 * CH_VU;
+    return (k == 5 || k == 6 || k == 7 || k == 8 || k == 10) && d >= 1 && conv_h_tile_width(k, d) <= 64 * 4;
 }
 
 // ... and the two-stage tile of the register-staged kernel (what every shape can fall back to) fits
@@ -1199,9 +1230,9 @@ bool conv_h_supported(int k, int d, int gemm_m)
 {
     if (!conv_h_supported(k, d) || gemm_m < 1) return false;
     const int mt = conv_h_mt(gemm_m, k);
-    const bool map4 = k == 4;
-    const int R = map4 && mt <= 3 ? 8 : 4, RR = R + k - 1, OC = map4 ? 1 : 4, CS = map4 ? 1 : k;
-    const long PW = CH_TX + (k - 1) * d;
+    const bool map4 = k >= 4;
+    const int R = k == 4 && mt <= 3 ? 8 : 4, RR = R + k - 1, OC = map4 ? 1 : 4, CS = map4 ? (k + 3) / 4 : k;
+    const long PW = conv_h_tile_width(k, d);
     const long stage = OC * RR * PW + (long)CS * k * mt * 64;
     const long m_tiles_all = ((gemm_m + 15) / 16 + mt - 1) / mt * mt;
     return 2 * stage * 16 + m_tiles_all * 64 <= 160 * 1024;
@@ -1218,6 +1249,7 @@ hipError_t launch_conv_h(const ConvHArgs &a, hipStream_t stream)
     // the packed weights were laid out for this many map tiles per group (0 = the default choice)
     const int mt = a.mt > 0 ? a.mt : conv_h_mt(a.c_out, a.k);
     if (mt > 4 || (a.k == 3 && mt > 3)) return hipErrorInvalidValue;
+    if (a.k > 4 && !conv_h_supported(a.k, a.d, a.c_out)) return hipErrorInvalidValue;
     if (a.dtype == 1) {
         switch (mt) {
         case 1: return launch_conv_h_mt<1, 1>(a, stream);
@@ -1241,7 +1273,7 @@ hipError_t launch_conv_h(const ConvHArgs &a, hipStream_t stream)
 // Weight packing for conv_h_kernel.  The packed array is a sequence of 1 KB MFMA A fragments,
 //   [mgroup][chunk][column step cs][kernel row i][m-tile mt][lane group g][l16][e = 0..7]
 // with element = W[o][c][i][j] (forward) where o = (mgroup*MT + mt)*16 + l16 and
-//   MAP4 (k = 4): c = chunk*8 + e,            j = g
+//   MAP4 (k >= 4): c = chunk*8 + e,           j = 4*cs + g (zero for j >= k)
 //   otherwise   : c = (chunk*4 + g)*8 + e,    j = cs
 // flip_transpose = 1 builds the data-gradient operator instead: the roles of input and output maps
 // are swapped and both taps are mirrored (element = W[c][o][k-1-i][k-1-j]).
@@ -1250,7 +1282,7 @@ template <int DT>
 __device__ __forceinline__ void pack_weights_h_body(const float *w, unsigned short *wp, int c_out, int c_in, int k, int flip_transpose,
                                                     int mt_per_group, int map4, int gemm_m, int gemm_c8, long total)
 {
-    const int OC = map4 ? 1 : 4, CS = map4 ? 1 : k;
+    const int OC = map4 ? 1 : 4, CS = map4 ? (k + 3) / 4 : k;
     const int nchunks = (gemm_c8 + OC - 1) / OC;
     for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
         long r = q;
@@ -1264,9 +1296,9 @@ __device__ __forceinline__ void pack_weights_h_body(const float *w, unsigned sho
         const int mg = (int)r;
         const int m = (mg * mt_per_group + mt) * 16 + l16;          // GEMM output map
         const int c = map4 ? ch * 8 + e : (ch * 4 + g) * 8 + e;     // GEMM input map
-        const int j = map4 ? g : cs;
+        const int j = map4 ? 4 * cs + g : cs;
         float v = 0.f;
-        if (m < gemm_m && c < gemm_c8 * 8) {
+        if (m < gemm_m && c < gemm_c8 * 8 && j < k) {
             if (!flip_transpose) {
                 if (m < c_out && c < c_in) v = w[(((long)m * c_in + c) * k + i) * k + j];
             } else {
@@ -1310,8 +1342,8 @@ long packed_h_elems(int gemm_m, int gemm_c8, int k, int mt)
 {
     if (mt <= 0) mt = conv_h_mt(gemm_m, k);
     const int m_tiles = (gemm_m + 15) / 16, mgroups = (m_tiles + mt - 1) / mt;
-    const bool map4 = k == 4;
-    const int OC = map4 ? 1 : 4, CS = map4 ? 1 : k;
+    const bool map4 = k >= 4;
+    const int OC = map4 ? 1 : 4, CS = map4 ? (k + 3) / 4 : k;
     const int nchunks = (gemm_c8 + OC - 1) / OC;
     return (long)mgroups * nchunks * CS * k * mt * 512;
 }
@@ -1326,10 +1358,10 @@ hipError_t launch_pack_weights_h(const float *w_oihw, void *wp, int dtype, int c
     const int blocks = (int)((total + 255) / 256 < 2048 ? (total + 255) / 256 : 2048);
     if (dtype == 1)
         hipLaunchKernelGGL(pack_weights_h_kernel<1>, dim3(blocks), dim3(256), 0, stream, w_oihw,
-                           static_cast<unsigned short *>(wp), c_out, c_in, k, flip_transpose, mt, k == 4 ? 1 : 0, gemm_m, gemm_c8, total);
+                           static_cast<unsigned short *>(wp), c_out, c_in, k, flip_transpose, mt, k >= 4 ? 1 : 0, gemm_m, gemm_c8, total);
     else
         hipLaunchKernelGGL(pack_weights_h_kernel<2>, dim3(blocks), dim3(256), 0, stream, w_oihw,
-                           static_cast<unsigned short *>(wp), c_out, c_in, k, flip_transpose, mt, k == 4 ? 1 : 0, gemm_m, gemm_c8, total);
+                           static_cast<unsigned short *>(wp), c_out, c_in, k, flip_transpose, mt, k >= 4 ? 1 : 0, gemm_m, gemm_c8, total);
     return hipGetLastError();
 }
 
@@ -1346,7 +1378,7 @@ hipError_t launch_pack_weights_h_batch(const PackHJob *jobs, int n, int dtype, h
         o.gemm_m = j.flip_transpose ? j.c_in : j.c_out;
         o.gemm_c8 = ((j.flip_transpose ? j.c_out : j.c_in) + 7) / 8;
         o.mt = j.mt > 0 ? j.mt : conv_h_mt(o.gemm_m, j.k);
-        o.map4 = j.k == 4 ? 1 : 0;
+        o.map4 = j.k >= 4 ? 1 : 0;
         o.total = packed_h_elems(o.gemm_m, o.gemm_c8, j.k, o.mt);
         most = o.total > most ? o.total : most;
     }

@@ -319,7 +319,7 @@ sk_status sknet_create(const sk_layer *layers, int32_t n_layers, int32_t c_in, i
         else if (l.kind == SK_MAXPOOL && !(l.s == 1 || (l.s == l.k && l.d == 1)))
             bad = fail(SK_ESHAPE, "layer %d: pool needs s = 1, or s = k with d = 1", i);
         else if (dtype != SK_F32 && l.kind == SK_CONV && !sk::conv_h_supported(l.k, l.d))
-            bad = fail(SK_EUNSUPPORTED, "layer %d: 16-bit convolutions need k <= 4 and (k-1)*d <= 64", i);
+            bad = fail(SK_EUNSUPPORTED, "layer %d: 16-bit convolutions are built for k = 1..8 and 10, with a staged tile of at most 192 columns (k <= 4) or 256 (larger k)", i);
         else if (dtype != SK_F32 && l.kind == SK_CONV && !sk::conv_h_supported(l.k, l.d, l.c_out))
             bad = fail(SK_EUNSUPPORTED, "layer %d: a 16-bit %dx%d convolution to %d maps at d = %d does not fit the LDS tile", i, l.k, l.k, l.c_out, l.d);
         if (bad != SK_OK) {
@@ -445,6 +445,10 @@ sk_status sknet_plan(sknet_t *net, int32_t n, int32_t h, int32_t w, int32_t pad,
         for (int i = 0; i < L; ++i)
             if (net->layers[i].kind == SK_MAXPOOL && net->layers[i].s != 1)
                 return fail(SK_EUNSUPPORTED, "plan: training through a down-sampling pool is not built");
+    if (training && net->dtype != SK_F32)
+        for (int i = 0; i < L; ++i)
+            if (net->layers[i].kind == SK_CONV && net->layers[i].k > 4)
+                return fail(SK_EUNSUPPORTED, "plan: the 16-bit kernels for k > 4 (layer %d: %dx%d) are forward only; train in fp32", i, net->layers[i].k, net->layers[i].k);
     if (training && net->dtype != SK_F32)
         for (int i = 1; i < L; ++i)      // data gradients: the GEMM's output maps are the layer's input maps (the first layer needs none)
             if (net->layers[i].kind == SK_CONV && !sk::conv_h_supported(net->layers[i].k, net->layers[i].d, dims[i].c))

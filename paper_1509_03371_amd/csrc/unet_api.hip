@@ -222,7 +222,9 @@ sk_status usknet_create(int32_t c_in, int32_t n_classes, int32_t base_ch, sk_dty
     if (!out) return fail(SK_EINVAL, "usknet_create: out is null");
     *out = nullptr;
     if (c_in < 1 || n_classes < 1 || base_ch < 1) return fail(SK_EINVAL, "usknet_create: bad arguments");
-    if (dtype != SK_F32) return fail(SK_EUNSUPPORTED, "usknet_create: only fp32 storage is built (its 6x6 and 8x8 kernels have no 16-bit variant)");
+    if (dtype != SK_F32 && dtype != SK_BF16 && dtype != SK_F16) return fail(SK_EINVAL, "usknet_create: unknown dtype %d", (int)dtype);
+    if (dtype != SK_F32 && base_ch % 8 != 0)
+        return fail(SK_EUNSUPPORTED, "usknet_create: the 16-bit layout keeps maps in groups of 8, base_ch must be a multiple of 8");
     unet *net = new (std::nothrow) unet;
     if (!net) return fail(SK_ENOMEM, "usknet_create: out of host memory");
     net->arch = 1; net->c_in = c_in; net->n_classes = n_classes; net->depth = 1; net->base = base_ch; net->dtype = dtype;
@@ -465,9 +467,13 @@ static sk_status plan_impl(unet_t *net, int32_t n, int32_t h_in, int32_t w_in, b
             }
         }
     }
+    if (half)
+        for (const auto &op : net->ops)
+            if (st == SK_OK && op.kind == 0 && !sk::conv_h_supported(net->convs[op.param].k, op.d, net->convs[op.param].c_out))
+                st = fail(SK_EUNSUPPORTED, "a %dx%d convolution at d = %d to %d maps is not built for 16-bit storage", net->convs[op.param].k,
+                          net->convs[op.param].k, op.d, net->convs[op.param].c_out);
     for (auto &c : net->convs) {
         if (st != SK_OK) break;
-        if (half && (net->arch != 0 || !sk::conv_h_supported(c.k, 1))) st = fail(SK_EUNSUPPORTED, "U-Net: kernel size %d is not built for 16-bit storage", c.k);
         if (st == SK_OK) st = alloc_conv(c, training, net->dtype);
         if (st == SK_OK) st = upload_conv(c, training, nullptr, net->dtype);
     }

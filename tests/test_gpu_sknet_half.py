@@ -32,6 +32,10 @@ def make_net(layers, c_in, ws, bs, dtype):
     (4, 1, 1, 48, 70, 150), (4, 2, 48, 48, 41, 131), (4, 8, 48, 48, 57, 300), (4, 4, 48, 48, 100, 129),
     (3, 1, 64, 128, 20, 23), (1, 1, 48, 200, 19, 70), (1, 1, 200, 2, 19, 140), (3, 4, 3, 5, 30, 40),
     (2, 3, 5, 7, 9, 200), (4, 8, 6, 4, 25, 25), (4, 2, 20, 72, 30, 135), (3, 2, 40, 48, 33, 260),
+    # kernels beyond 4x4 (the paper's SK-Net: 7x7, 5x5 d2, 10x10 d8; the USK-Net: 6x6, 8x8 d8): lane groups on four
+    # consecutive kernel columns, the columns past the kernel carry zero weights; ragged maps, several map blocks
+    (5, 2, 8, 16, 33, 29), (5, 2, 48, 128, 40, 150), (6, 1, 10, 40, 30, 75), (6, 3, 5, 70, 40, 90), (7, 1, 3, 48, 25, 140),
+    (8, 8, 12, 130, 70, 140), (8, 2, 3, 16, 33, 29), (10, 8, 6, 50, 90, 160), (10, 2, 4, 20, 30, 24), (10, 8, 24, 40, 80, 210),
 ])
 def test_conv_layer_shapes_half(dtype, k, d, c_in, c_out, h, w):
     dt = "f16" if dtype == "fp16" else dtype
@@ -181,6 +185,27 @@ def test_weight_gradient_kernel_strides_half(dtype, c_in, spec, h, w):
         assert np.abs(db - dbs[i]).max() <= tol * max(np.abs(dbs[i]).max(), np.abs(dws[i]).max()), ("db", i)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_paper_sknet_configuration_forward_half(dtype):
+    # the network of Section 3.3.2's SK table (k = 7, 5 d2, 3 d4 and the k = 10, d = 8 inner product 192 -> 1024,
+    # context 101) in 16-bit storage: every layer and the fp32 logits against the oracle
+    layers = S.paper_sknet_layers()
+    ws, bs = S.he_normal_weights(layers, 3, 1003, bias_scale=0.05)
+    img = S.uniform_image(1, 3, 60, 68, 11)
+    net = make_net(layers, 3, ws, bs, dtype)
+    net.plan(1, 60, 68, pad=True, keep=True)
+    prob = net.forward(torch.from_numpy(img).cuda()).cpu().numpy()
+    ref_prob, acts, _ = ON.sknet_forward(img, layers, ws, bs, keep=True)
+    for li in range(len(layers)):
+        e = relerr(net.get_activation(li), acts[li + 1])
+        print(dtype, "paper SK-Net layer", li, layers[li]["type"], "rel err %.3e" % e, flush=True)
+        assert e <= HALF_TOL, (li, layers[li], e)
+    assert np.abs(prob - ref_prob).max() <= HALF_TOL
+    net.plan(1, 60, 68, pad=True)
+    assert np.abs(net.forward(torch.from_numpy(img).cuda()).cpu().numpy() - ref_prob).max() <= HALF_TOL
+    net.close()
+
+
 def test_unsupported_kernel_size_is_reported():
     from paper_1509_03371_amd import binding as B
     with pytest.raises(B.SknetError) as e:
@@ -188,5 +213,13 @@ def test_unsupported_kernel_size_is_reported():
     assert e.value.status_name == "SK_EUNSUPPORTED"
     B.SKNet([S.conv(32, 3, 8, relu=True), S.conv(2, 1, 1, relu=False)], 1, 2, dtype="bf16").close()  # two map tiles fit
     with pytest.raises(B.SknetError) as e:
-        B.SKNet([S.conv(2, 5, 2, relu=False)], 1, 2, dtype="bf16")
+        B.SKNet([S.conv(2, 9, 2, relu=False)], 1, 2, dtype="bf16")                                 # no 9x9 instantiation
     assert e.value.status_name == "SK_EUNSUPPORTED"
+    with pytest.raises(B.SknetError) as e:
+        B.SKNet([S.conv(2, 10, 12, relu=False)], 1, 2, dtype="bf16")                               # 128 + 11*12 columns: beyond the staged tile
+    assert e.value.status_name == "SK_EUNSUPPORTED"
+    net = B.SKNet([S.conv(8, 6, 1, relu=True), S.conv(2, 1, 1, relu=False)], 1, 2, dtype="bf16")
+    with pytest.raises(B.SknetError) as e:
+        net.plan(1, 40, 40, pad=True, training=True)                                               # large kernels: forward only
+    assert e.value.status_name == "SK_EUNSUPPORTED"
+    net.close()
