@@ -5,17 +5,28 @@ one 1x1x512x512 fp32 image -- mirror padding, four stages of [conv k4 -> 48 maps
 k2 s1] at kernel strides 1/2/4/8, 1x1 conv 48 -> 200 + ReLU, 1x1 conv 200 -> 2, per-pixel softmax.
 A step is one such pass over one synthetic image that is resident in HBM before the timed region.
 
---workload c3 : the same net in bf16 (fp32 accumulate) on 8 images of 1024x1024 (configs[2])
---workload c4 : one bf16 training step at 512x512 (configs[3]): forward, softmax loss, backward, SGD
+--workload c3      : the same net in bf16 (fp32 accumulate) on 8 images of 1024x1024 (configs[2])
+--workload c4      : one bf16 training step at 512x512 (configs[3]): forward, softmax loss, backward, SGD
+--workload c3train : the same training step on 8 images of 1024x1024 (where the pool, pool-gradient and softmax-loss
+                     kernels are bound by HBM, not by their launch)
 --workload c5 / c5bf16 : U-Net forward on one 572x572 image (configs[4]) in fp32 / bf16
---workload sk3d / sk3dtrain : 3-D SK net on a stack of 81 sections of 145x145 (Section 5.2.2), fp32: forward / training step
---workload copy : only the streaming-copy probe on 2 x 1 GiB (the known-size kernel that the HBM
-                  byte counters of a profiler run are calibrated against)
-The default run also appends short c3 / c4 measurements under "extras" (skip with --no-extras).
+--workload papersk / paperskbf16, usk / uskbf16 : the paper's own SK-Net (128^2 tile) and USK-Net (692^2), fp32 / bf16
+--workload sk3d / sk3dtrain : 3-D SK net on a stack of 81 sections of 145x145 (Section 5.2.2), fp32
+--workload unettrain / usktrain : U-Net / USK-Net training step, fp32
+--workload copy    : only the streaming-copy probe on 2 x 1 GiB (the known-size kernel that the HBM
+                     byte counters of a profiler run are calibrated against)
+The default run also appends short measurements of the other workloads under "extras" (skip with --no-extras).
+
+Timing: the K steps are bracketed by synchronisation and a wall clock (ms_per_step, value); every step is also
+bracketed by two HIP events on the stream it is launched on (median / min in ms_per_step_events).  Kernel times of
+the roofline blocks come from HIP events inside the library (sknet_time_step, sknet_time_backward_step), on the same
+stream.  HBM traffic beyond L2 is read from profiles/hbm_traffic.json (rocprofv3 --pmc runs of this script).
 """
 import argparse
 import json
 import os
+import re
+import statistics
 import sys
 import time
 
@@ -25,13 +36,43 @@ sys.path.insert(0, ROOT)
 PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0, "f16": 2500.0}   # MI355X dense MFMA peaks
 HBM_PEAK_GBS = 8000.0
 METRIC = "labelled pixels/sec SK-Net fwd (and fwd+bwd) 1 GPU; conv % MFMA peak"
-# Bytes moved beyond L2 per launch of the dominant kernel (average of its three launches per pass),
-# from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by what the same counters
-# read for stream_copy_kernel on 1 GiB (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); the runs and their
-# figures are in profiles/sknet_c{2,3}_forward_hbm_traffic_pmc.txt and
-# profiles/stream_copy_1gib_pmc_calibration.txt.  KiB: (fetch x 2, write).
-TRAFFIC_KIB = {"c2": (2.0 * (35765.2 + 34265.0 + 30821.7) / 3, (78827.5 + 71135.3 + 58340.2) / 3),
-               "c3": (2.0 * (479830.4 + 473130.7 + 454601.8) / 3, (870701.7 + 846215.4 + 798768.0) / 3)}
+NET_DESC = "4x[conv k4 48 + ReLU, pool k2] d=1/2/4/8, 1x1 48->200 + ReLU, 1x1 200->2, softmax"
+
+
+def traffic_table():
+    """Bytes moved beyond L2 per launch of the dominant kernels, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+    this script, already scaled by what the same counters read for the streaming copy of known size; the file names
+    the summaries under profiles/ it was made from.  Missing file or entry: traffic is reported as null."""
+    try:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
+            return json.load(f)
+    except (OSError, ValueError):
+        return {}
+
+
+def traffic_of(table, key):
+    e = table.get(key)
+    if not e:
+        return None, None
+    return int(e["bytes_per_launch"]), e.get("source")
+
+
+def timed_steps(torch, fn, steps, warmup):
+    """warmup untimed calls, then `steps` timed ones: wall clock over all of them, HIP events around each."""
+    stream = torch.cuda.current_stream()
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    t0 = time.perf_counter()
+    for a, b in ev:
+        a.record(stream)
+        fn()
+        b.record(stream)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    per = [a.elapsed_time(b) for a, b in ev]
+    return dt, {"median": round(statistics.median(per), 4), "min": round(min(per), 4)}
 
 
 def build_net(B, S, dtype, n, H, W, training):
@@ -44,39 +85,34 @@ def build_net(B, S, dtype, n, H, W, training):
     return net, layers, ws, bs
 
 
-def images(S, n, H, W, first_seed):
-    return S.em_like_batch(n, H, W, first_seed)
+def layer_flops(layers, shapes, n):
+    """(flops of every conv layer, maps entering every layer)"""
+    fl, f_in_of, f_in = {}, {}, 1
+    for li, l in enumerate(layers):
+        f_in_of[li] = f_in
+        if l["type"] == "conv":
+            c, ho, wo = shapes[li + 1]
+            fl[li] = 2.0 * f_in * l["k"] ** 2 * l["f_out"] * ho * wo * n
+            f_in = l["f_out"]
+    return fl, f_in_of
 
 
 def measure_forward(torch, B, S, dtype, n, H, W, steps, warmup, first_seed, kernel_iters=20):
     net, layers, ws, bs = build_net(B, S, dtype, n, H, W, False)
-    img = images(S, n, H, W, first_seed)
+    img = S.em_like_batch(n, H, W, first_seed)
     timg = torch.from_numpy(img).cuda()
     prob = torch.empty(net.out_shape(), dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
-    for _ in range(warmup):
-        net.forward(timg, prob, stream)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        net.forward(timg, prob, stream)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    dt, per = timed_steps(torch, lambda: net.forward(timg, prob, stream), steps, warmup)
     ms_per_step = dt / steps * 1e3
 
     # per-kernel durations: HIP events recorded on the same stream, inside the library
     shapes = net.infer_shapes(H, W)
     esize = 4 if dtype == "f32" else 2
-    step_ms, conv_flops, conv_ms, total_flops = {}, 0.0, 0.0, 0.0
-    conv_bytes, conv_launches = 0.0, 0
+    flops, f_in_of = layer_flops(layers, shapes, n)
+    step_ms, conv_flops, conv_ms = {}, 0.0, 0.0
+    conv_bytes, conv_launches, conv_names = 0.0, 0, []
     pool_bytes, pool_ms = 0.0, 0.0
-    f_in_of = {}
-    f_in = 1
-    for li, l in enumerate(layers):
-        f_in_of[li] = f_in
-        if l["type"] == "conv":
-            f_in = l["f_out"]
-    import re
     for step in range(net.num_steps()):
         ms = net.time_step(step, kernel_iters, stream)
         name = net.step_name(step)
@@ -88,33 +124,46 @@ def measure_forward(torch, B, S, dtype, n, H, W, steps, warmup, first_seed, kern
         l = layers[li]
         c, ho, wo = shapes[li + 1]
         if m.group(1) == "conv":
-            fl = 2.0 * f_in_of[li] * l["k"] ** 2 * l["f_out"] * ho * wo * n
-            total_flops += fl
             if f_in_of[li] == 48 and l["f_out"] == 48:      # the dominant kernel: 48 -> 48, k4, dilated
-                conv_flops += fl
+                conv_flops += flops[li]
                 conv_ms += ms
                 hi, wi = shapes[li][1:]
-                conv_bytes += esize * n * 48.0 * (hi * wi + ho * wo)   # every input and output element once
+                # every input and output element once (a fused pool shrinks neither: the convolution's output is
+                # stored with W columns and H - d rows, its input arrives with d extra columns)
+                conv_bytes += esize * n * 48.0 * (hi * wi + ho * wo)
                 conv_launches += 1
+                conv_names.append(name)
         else:                                         # pool as a layer of its own: one element read + one written
             pool_bytes += 2.0 * esize * n * c * ho * wo
             pool_ms += ms
-    for li, l in enumerate(layers):                   # the 1x1 convolutions of a fused head
-        if l["type"] == "conv" and not any(k.startswith("conv%d_" % li) for k in step_ms):
-            c, ho, wo = shapes[li + 1]
-            total_flops += 2.0 * f_in_of[li] * l["k"] ** 2 * l["f_out"] * ho * wo * n
     res = {
-        "ms_per_step": ms_per_step, "pixels_per_s": n * H * W * steps / dt, "step_ms": step_ms,
-        "conv_tflops": conv_flops / (conv_ms * 1e-3) / 1e12, "forward_tflops": total_flops / (ms_per_step * 1e-3) / 1e12,
-        "pool_gbs": (pool_bytes / (pool_ms * 1e-3) / 1e9) if pool_ms > 0 else None, "conv_alg_bytes": conv_bytes / max(conv_launches, 1), "layers": layers, "ws": ws, "bs": bs, "img": img,
+        "ms_per_step": ms_per_step, "events": per, "pixels_per_s": n * H * W * steps / dt, "step_ms": step_ms,
+        "conv_tflops": conv_flops / (conv_ms * 1e-3) / 1e12, "conv_ms_avg": conv_ms / max(conv_launches, 1),
+        "forward_tflops": sum(flops.values()) / (ms_per_step * 1e-3) / 1e12,
+        "pool_gbs": (pool_bytes / (pool_ms * 1e-3) / 1e9) if pool_ms > 0 else None,
+        "conv_alg_bytes": conv_bytes / max(conv_launches, 1), "conv_alg_flops": conv_flops / max(conv_launches, 1),
+        "conv_names": conv_names, "layers": layers, "ws": ws, "bs": bs, "img": img,
     }
     net.close()
     return res
 
 
-def measure_train(torch, B, S, dtype, n, H, W, steps, warmup, first_seed):
+def forward_roofline(r, dtype, table, key):
+    peak = PEAK_TFLOPS[dtype]
+    traffic, src = traffic_of(table, key)
+    return {"bound": "mfma", "achieved": round(r["conv_tflops"], 2), "peak": peak, "unit": "TFLOP/s",
+            "frac": round(r["conv_tflops"] / peak, 4), "traffic": traffic,
+            "traffic_unit": "bytes beyond L2 per launch (read + written)", "traffic_source": src,
+            "algorithmic_bytes": int(r["conv_alg_bytes"]), "algorithmic_flops": int(r["conv_alg_flops"]),
+            "avg_launch_ms": round(r["conv_ms_avg"], 5),
+            "kernel": "48->48 k4 SK convolutions at d=2,4,8 (%s): %s"
+                      % ("conv_f32_pf_kernel<3,1,4,4,2,false,4>" if dtype == "f32" else "conv_h_ring_kernel, producer-wave variant",
+                         ", ".join(r["conv_names"]))}
+
+
+def measure_train(torch, B, S, dtype, n, H, W, steps, warmup, first_seed, kernel_iters=10, detail=True):
     net, layers, ws, bs = build_net(B, S, dtype, n, H, W, True)
-    timg = torch.from_numpy(images(S, n, H, W, first_seed)).cuda()
+    timg = torch.from_numpy(S.em_like_batch(n, H, W, first_seed)).cuda()
     labels = torch.from_numpy(S.binary_labels(n, H, W, 2004)).cuda()
     prob = torch.empty(net.out_shape(), dtype=torch.float32, device="cuda")
     loss = torch.empty(1, dtype=torch.float32, device="cuda")
@@ -125,16 +174,75 @@ def measure_train(torch, B, S, dtype, n, H, W, steps, warmup, first_seed):
         net.backward(labels, loss, stream)
         net.sgd_step(0.01, stream=stream)
 
-    for _ in range(warmup):
-        one()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        one()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    dt, per = timed_steps(torch, one, steps, warmup)
+    res = {"pixels_per_s": n * H * W * steps / dt, "ms_per_step": dt / steps * 1e3, "events": per, "steps": steps}
+    if detail:
+        shapes = net.infer_shapes(H, W)
+        esize = 4 if dtype == "f32" else 2
+        flops, f_in_of = layer_flops(layers, shapes, n)
+        net.forward(timg, prob, stream)
+        parts, wg_ms, wg_flops, wg_bytes, wg_n = {}, 0.0, 0.0, 0.0, 0
+        pool_bwd_bytes, pool_bwd_ms, pool_fwd_bytes, pool_fwd_ms = 0.0, 0.0, 0.0, 0.0
+        for step in range(net.num_steps()):
+            name = net.step_name(step)
+            m = re.match(r"pool(\d+)_", name)
+            if m:
+                li = int(m.group(1))
+                c, ho, wo = shapes[li + 1]
+                ms = net.time_step(step, kernel_iters, stream)
+                pool_fwd_ms += ms
+                pool_fwd_bytes += n * c * ho * wo * (2.0 * esize + 1)          # element in, element out, one winner code
+        parts["loss_ms"] = round(net.time_backward_step(labels, 0, 2, kernel_iters, stream), 5)
+        for li, l in enumerate(layers):
+            c, ho, wo = shapes[li + 1]
+            if l["type"] == "conv":
+                ms = net.time_backward_step(labels, li, 0, kernel_iters, stream)
+                parts["wgrad%d_ms" % li] = round(ms, 5)
+                if f_in_of[li] == 48 and l["f_out"] == 48:
+                    hi, wi = shapes[li][1:]
+                    wg_ms += ms
+                    wg_flops += flops[li]
+                    wg_bytes += esize * n * 48.0 * (hi * wi + ho * wo)
+                    wg_n += 1
+                if li > 0:
+                    parts["dgrad%d_ms" % li] = round(net.time_backward_step(labels, li, 1, kernel_iters, stream), 5)
+            elif li > 0:
+                ms = net.time_backward_step(labels, li, 1, kernel_iters, stream)
+                parts["poolbwd%d_ms" % li] = round(ms, 5)
+                hi, wi = shapes[li][1:]
+                pool_bwd_ms += ms
+                # gradient and winner code of every output in, gradient of every input out (+ its ReLU mask source in)
+                pool_bwd_bytes += n * c * (ho * wo * (esize + 1.0) + hi * wi * 2.0 * esize)
+        ho, wo = shapes[-1][1:]
+        # labels in (count pass), logits + labels in and fp32 gradient out (2 classes); 16-bit storage: the gradient is
+        # read once more and written as one 16-byte octet per pixel for the layers below
+        loss_bytes = n * ho * wo * (4 + (2 * 4 + 4 + 2 * 4.0) + (0.0 if dtype == "f32" else 2 * 4 + 16))
+        res.update({
+            "parts_ms": parts,
+            "step_tflops": round(3.0 * sum(flops.values()) / (res["ms_per_step"] * 1e-3) / 1e12, 2),   # forward + two gradients per conv
+            "wgrad": {"tflops": wg_flops / (wg_ms * 1e-3) / 1e12, "avg_ms": wg_ms / max(wg_n, 1), "alg_bytes": wg_bytes / max(wg_n, 1),
+                      "alg_flops": wg_flops / max(wg_n, 1)},
+            "pool_fwd_gbs": round(pool_fwd_bytes / (pool_fwd_ms * 1e-3) / 1e9, 1) if pool_fwd_ms else None,
+            "pool_bwd_gbs": round(pool_bwd_bytes / (pool_bwd_ms * 1e-3) / 1e9, 1) if pool_bwd_ms else None,
+            "softmax_loss_gbs": round(loss_bytes / (parts["loss_ms"] * 1e-3) / 1e9, 1),
+        })
     net.close()
-    return {"pixels_per_s": n * H * W * steps / dt, "ms_per_step": dt / steps * 1e3, "steps": steps}
+    return res
+
+
+def train_roofline(r, dtype, table, key):
+    peak = PEAK_TFLOPS[dtype]
+    w = r["wgrad"]
+    traffic, src = traffic_of(table, key)
+    return {"bound": "mfma", "achieved": round(w["tflops"], 2), "peak": peak, "unit": "TFLOP/s", "frac": round(w["tflops"] / peak, 4),
+            "traffic": traffic, "traffic_unit": "bytes beyond L2 per launch (read + written)", "traffic_source": src,
+            "algorithmic_bytes": int(w["alg_bytes"]), "algorithmic_flops": int(w["alg_flops"]), "avg_launch_ms": round(w["avg_ms"], 5),
+            "kernel": "weight gradient of the 48->48 k4 SK convolutions (wgrad kernel + reduction of its private copies), average of d=2,4,8",
+            "step": {"achieved": r["step_tflops"], "frac": round(r["step_tflops"] / peak, 4), "unit": "TFLOP/s",
+                     "what": "3 x forward conv FLOPs (forward, data gradient, weight gradient) over the whole training step"},
+            "hbm_bound_kernels": {"pool_fwd_gbs": r["pool_fwd_gbs"], "pool_bwd_gbs": r["pool_bwd_gbs"], "softmax_loss_gbs": r["softmax_loss_gbs"],
+                                  "peak_gbs": HBM_PEAK_GBS,
+                                  "frac": {k: (None if r[k] is None else round(r[k] / HBM_PEAK_GBS, 4)) for k in ("pool_fwd_gbs", "pool_bwd_gbs", "softmax_loss_gbs")}}}
 
 
 def measure_unet(torch, B, S, dtype, steps, warmup):
@@ -147,46 +255,37 @@ def measure_unet(torch, B, S, dtype, steps, warmup):
     img = torch.from_numpy(S.em_like_image(572, 572, 1006)[None, None].copy()).cuda()
     prob = torch.empty((1, 2, 388, 388), dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
-    for _ in range(warmup):
-        net.forward(img, prob, stream)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        net.forward(img, prob, stream)
-    torch.cuda.synchronize()
-    dt = (time.perf_counter() - t0) / steps
+    dt, per = timed_steps(torch, lambda: net.forward(img, prob, stream), steps, warmup)
+    dt /= steps
     net.close()
     gflop = 300.9            # 1-channel input; the paper's table (3 channels) sums to 301.6
-    return {"ms_per_step": round(dt * 1e3, 4), "labelled_pixels_per_s": round(388 * 388 / dt, 1),
-            "tflops": round(gflop / dt / 1e3, 1)}
+    tf = gflop / dt / 1e3
+    return {"ms_per_step": round(dt * 1e3, 4), "events": per, "labelled_pixels_per_s": round(388 * 388 / dt, 1), "tflops": round(tf, 1),
+            "roofline": {"bound": "mfma", "achieved": round(tf, 1), "peak": PEAK_TFLOPS[dtype], "unit": "TFLOP/s",
+                         "frac": round(tf / PEAK_TFLOPS[dtype], 4), "traffic": None,
+                         "kernel": "whole forward pass (23 convolutions, 4 pools, 4 up-convolutions): 300.9 GFLOP over the step time"}}
 
 
 def measure_usknet(torch, B, S, steps, warmup, dtype="f32"):
     """USK-Net forward of the paper's USK configuration table (3 x 692^2 -> 2 x 512^2)."""
+    import numpy as np
     params = S.usknet_params(3, 2, 1006, base=64)
     net = B.USKNet(3, 2, base_ch=64, dtype=dtype)
     for i, name in enumerate(S.USKNET_PARAM_NAMES):
         net.set_weights(i, *params[name])
     net.plan(1, 692, 692)
-    import numpy as np
     img = torch.from_numpy(np.stack([S.em_like_image(692, 692, 1007 + c) for c in range(3)])[None].copy()).cuda()
     prob = torch.empty((1, 2, 512, 512), dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
-    for _ in range(warmup):
-        net.forward(img, prob, stream)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        net.forward(img, prob, stream)
-    torch.cuda.synchronize()
-    dt = (time.perf_counter() - t0) / steps
+    dt, per = timed_steps(torch, lambda: net.forward(img, prob, stream), steps, warmup)
+    dt /= steps
     net.close()
     # 2 f_in k^2 f_out w_out^2 over the table's convolutions and the up step
     gflop = 2e-9 * (3 * 9 * 64 * 690 ** 2 + 64 * 9 * 64 * 688 ** 2 + 64 * 36 * 128 * 339 ** 2 + 128 * 16 * 128 * (332 ** 2 + 318 ** 2)
                     + 128 * 64 * 512 * 258 ** 2 + 512 * 256 * 258 ** 2 + 256 * 128 * 516 ** 2 + 192 * 9 * 128 * 514 ** 2
                     + 128 * 9 * 64 * 512 ** 2 + 64 * 2 * 512 ** 2)
-    return {"ms_per_step": round(dt * 1e3, 4), "labelled_pixels_per_s": round(512 * 512 / dt, 1),
-            "gflop": round(gflop, 1), "tflops": round(gflop / dt / 1e3, 1)}
+    return {"ms_per_step": round(dt * 1e3, 4), "events": per, "labelled_pixels_per_s": round(512 * 512 / dt, 1),
+            "gflop": round(gflop, 1), "tflops": round(gflop / dt / 1e3, 1), "frac_of_mfma_peak": round(gflop / dt / 1e3 / PEAK_TFLOPS[dtype], 4)}
 
 
 def measure_unet_train(torch, B, S, which, steps, warmup):
@@ -212,17 +311,11 @@ def measure_unet_train(torch, B, S, which, steps, warmup):
         net.forward(img, prob, stream)
         net.backward(lab, loss, stream)
         net.sgd_step(1e-3, 0.9, 0.0, stream)
-    for _ in range(warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        step()
-    torch.cuda.synchronize()
-    dt = (time.perf_counter() - t0) / steps
+    dt, per = timed_steps(torch, step, steps, warmup)
+    dt /= steps
     final = float(loss.item())
     net.close()
-    return {"ms_per_step": round(dt * 1e3, 3), "labelled_pixels_per_s": round(out * out / dt, 1), "loss_after": round(final, 4)}
+    return {"ms_per_step": round(dt * 1e3, 3), "events": per, "labelled_pixels_per_s": round(out * out / dt, 1), "loss_after": round(final, 4)}
 
 
 def measure_paper_sknet(torch, B, S, steps, warmup, dtype="f32"):
@@ -238,18 +331,13 @@ def measure_paper_sknet(torch, B, S, steps, warmup, dtype="f32"):
     img = torch.from_numpy(S.uniform_image(1, 3, 128, 128, 12)).cuda()
     prob = torch.empty(net.out_shape(), dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
-    for _ in range(warmup):
-        net.forward(img, prob, stream)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        net.forward(img, prob, stream)
-    torch.cuda.synchronize()
-    dt = (time.perf_counter() - t0) / steps
-    ip1_ms = net.time_step(7, 3, stream)               # pad, 6 layers, then the k10 d8 convolution
-    name = net.step_name(7)
+    dt, per = timed_steps(torch, lambda: net.forward(img, prob, stream), steps, warmup)
+    dt /= steps
+    ip1 = [i for i in range(net.num_steps()) if net.step_name(i).startswith("conv6_k10")][0]
+    ip1_ms = net.time_step(ip1, 3, stream)
+    name = net.step_name(ip1)
     net.close()
-    return {"ms_per_step": round(dt * 1e3, 3), "pixels_per_s": round(128 * 128 / dt, 1),
+    return {"ms_per_step": round(dt * 1e3, 3), "events": per, "pixels_per_s": round(128 * 128 / dt, 1),
             "forward_tflops": round(694.6 / dt / 1e3, 1), name + "_ms": round(ip1_ms, 3),
             name + "_tflops": round(644.23 / ip1_ms, 1),
             name + "_frac_of_mfma_peak": round(644.23 / ip1_ms / PEAK_TFLOPS[dtype], 4),
@@ -272,14 +360,8 @@ def measure_sknet3d(torch, B, S, steps, warmup):
     vol = torch.from_numpy(np.ascontiguousarray(S.em_like_volume(dz, h, w, 1101).transpose(1, 0, 2, 3))).cuda()
     prob = torch.empty(net.out_shape(), dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
-    for _ in range(warmup):
-        net.forward(vol, prob, stream)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        net.forward(vol, prob, stream)
-    torch.cuda.synchronize()
-    dt = (time.perf_counter() - t0) / steps
+    dt, per = timed_steps(torch, lambda: net.forward(vol, prob, stream), steps, warmup)
+    dt /= steps
     net.close()
     gflop, f_in = 0.0, 1
     for lay, (c, d_, h_, w_) in zip(layers, shapes[1:]):
@@ -287,7 +369,7 @@ def measure_sknet3d(torch, B, S, steps, warmup):
             gflop += 2e-9 * f_in * lay["k"] ** 3 * c * d_ * h_ * w_       # Section 5.5's count with k^3 taps
             f_in = c
     voxels = shapes[-1][1] * shapes[-1][2] * shapes[-1][3]
-    return {"ms_per_step": round(dt * 1e3, 4), "labelled_voxels_per_s": round(voxels / dt, 1),
+    return {"ms_per_step": round(dt * 1e3, 4), "events": per, "labelled_voxels_per_s": round(voxels / dt, 1),
             "gflop": round(gflop, 1), "tflops": round(gflop / dt / 1e3, 1)}
 
 
@@ -315,17 +397,11 @@ def measure_sknet3d_train(torch, B, S, steps, warmup):
         net.backward(labels, loss, stream)
         net.sgd_step(1e-3, 0.9, 0.0, stream)
 
-    for _ in range(warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        step()
-    torch.cuda.synchronize()
-    dt = (time.perf_counter() - t0) / steps
+    dt, per = timed_steps(torch, step, steps, warmup)
+    dt /= steps
     final = float(loss.cpu())
     net.close()
-    return {"ms_per_step": round(dt * 1e3, 3), "labelled_voxels_per_s": round(od * oh * ow / dt, 1), "loss_after": round(final, 4)}
+    return {"ms_per_step": round(dt * 1e3, 3), "events": per, "labelled_voxels_per_s": round(od * oh * ow / dt, 1), "loss_after": round(final, 4)}
 
 
 def measured_peaks(torch, B):
@@ -345,13 +421,59 @@ def measured_peaks(torch, B):
     return peaks
 
 
+def cpu_baselines(S, r):
+    """The fp64 oracle as it stands, timed on this machine's host cores on bounded samples of the benchmark workloads."""
+    import numpy as np
+    from oracle import layers as OL, nets as ON
+
+    def timed(fn, budget, most):
+        reps, t = 0, 0.0
+        while t < budget and reps < most:
+            t0 = time.perf_counter()
+            fn()
+            t += time.perf_counter() - t0
+            reps += 1
+        return reps, t
+
+    threads = OL.num_threads()
+    layers, ws, bs, img = r["layers"], r["ws"], r["bs"], r["img"]
+    reps, t = timed(lambda: ON.sknet_forward(img, layers, ws, bs), 8.0, 40)
+    main = {"value": round(512 * 512 * reps / t, 1), "unit": "pixels/s", "cores": threads, "kind": "oracle",
+            "sample": "%d full forward pass(es) of the same 512x512 workload, fp64 C oracle, OpenMP over output rows" % reps}
+    more = {}
+    OL.set_num_threads(1)
+    reps, t = timed(lambda: ON.sknet_forward(img, layers, ws, bs), 3.0, 1)
+    more["c2_forward_single_thread"] = {"value": round(512 * 512 * reps / t, 1), "unit": "pixels/s", "cores": 1,
+                                        "sample": "%d full forward pass of the 512x512 workload" % reps}
+    OL.set_num_threads(threads)
+    labels = S.binary_labels(1, 512, 512, 2004)
+    ow, ob = [x.astype(np.float64) for x in ws], [x.astype(np.float64) for x in bs]
+
+    def train():
+        _, acts, ams = ON.sknet_forward(img, layers, ow, ob, keep=True)
+        ON.sknet_backward(layers, ow, acts, ams, labels)
+    reps, t = timed(train, 3.0, 1)
+    more["c4_forward_backward"] = {"value": round(512 * 512 * reps / t, 1), "unit": "pixels/s", "cores": threads,
+                                   "sample": "%d forward + backward pass of the 512x512 training workload (no SGD step: it is 0.1 MFLOP)" % reps}
+    img3 = S.em_like_batch(1, 1024, 1024, 3)
+    reps, t = timed(lambda: ON.sknet_forward(img3, layers, ws, bs), 3.0, 1)
+    more["c3_forward"] = {"value": round(1024 * 1024 * reps / t, 1), "unit": "pixels/s", "cores": threads,
+                          "sample": "1 of the 8 images of the 8x1024x1024 workload (the images are independent: the rate is that of all 8)"}
+    params = {k: (a.astype(np.float64), b.astype(np.float64)) for k, (a, b) in S.unet_params(1, 2, 1005, depth=4, base=64).items()}
+    uimg = S.em_like_image(572, 572, 1006)[None, None].astype(np.float64)
+    reps, t = timed(lambda: ON.unet_forward(uimg, params, depth=4), 3.0, 1)
+    more["c5_unet_forward"] = {"value": round(388 * 388 * reps / t, 1), "unit": "labelled pixels/s", "cores": threads,
+                               "sample": "1 full U-Net forward pass, 572^2 -> 388^2 (300.9 GFLOP in fp64)"}
+    return main, more
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", choices=["c2", "c3", "c4", "c5", "c5bf16", "usk", "uskbf16", "papersk", "paperskbf16", "sk3d", "sk3dtrain", "unettrain", "usktrain",
-                                           "copy"], default="c2")
+    ap.add_argument("--workload", choices=["c2", "c3", "c4", "c3train", "c5", "c5bf16", "usk", "uskbf16", "papersk", "paperskbf16", "sk3d", "sk3dtrain",
+                                           "unettrain", "usktrain", "copy"], default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
     args = ap.parse_args()
@@ -366,7 +488,7 @@ def main():
     from paper_1509_03371_amd import binding as B
 
     torch.cuda.set_device(0)
-    net_desc = "4x[conv k4 48 + ReLU, pool k2] d=1/2/4/8, 1x1 48->200 + ReLU, 1x1 200->2, softmax"
+    table = traffic_table()
     out = {"metric": METRIC, "unit": "pixels/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "data": "synthetic"}
 
@@ -382,16 +504,16 @@ def main():
     if args.workload in ("c5", "c5bf16"):
         dt = "f32" if args.workload == "c5" else "bf16"
         r = measure_unet(torch, B, S, dt, args.steps, args.warmup)
-        out.update({"value": r["labelled_pixels_per_s"], "ms_per_step": r["ms_per_step"], "dtype": dt,
+        out.update({"value": r["labelled_pixels_per_s"], "ms_per_step": r["ms_per_step"], "ms_per_step_events": r["events"], "dtype": dt,
                     "config": {"workload": "U-Net forward 1x1x572x572 -> 2x388x388, %s (BASELINE configs[4])" % dt,
                                "global_batch": 1, "parallelism": "single GPU"},
-                    "roofline": None, "forward_tflops": r["tflops"]})
+                    "roofline": r["roofline"], "forward_tflops": r["tflops"]})
         print(json.dumps(out))
         return
 
     if args.workload in ("unettrain", "usktrain"):
         r = measure_unet_train(torch, B, S, "unet" if args.workload == "unettrain" else "usk", args.steps, args.warmup)
-        out.update({"value": r["labelled_pixels_per_s"], "ms_per_step": r["ms_per_step"], "dtype": "f32",
+        out.update({"value": r["labelled_pixels_per_s"], "ms_per_step": r["ms_per_step"], "ms_per_step_events": r["events"], "dtype": "f32",
                     "config": {"workload": ("U-Net 572^2 -> 388^2" if args.workload == "unettrain" else "USK-Net 692^2 -> 512^2")
                                            + " training step (forward, masked softmax loss, backward, SGD), fp32",
                                "global_batch": 1, "parallelism": "single GPU"}, "roofline": None, "detail": r})
@@ -412,27 +534,21 @@ def main():
         else:
             r = measure_paper_sknet(torch, B, S, args.steps, args.warmup, wdt)
             px, what = r["pixels_per_s"], "the paper's SK-Net forward, 3x128x128 -> 2x128x128 (padded to 229), %s" % wdt
-        out.update({"value": px, "ms_per_step": r["ms_per_step"], "dtype": wdt,
+        out.update({"value": px, "ms_per_step": r["ms_per_step"], "ms_per_step_events": r["events"], "dtype": wdt,
                     "config": {"workload": what, "global_batch": 1, "parallelism": "single GPU"}, "roofline": None, "detail": r})
         print(json.dumps(out))
         return
 
+    r = None
     if args.workload in ("c2", "c3"):
         dtype, n, H, seed = ("f32", 1, 512, 2) if args.workload == "c2" else ("bf16", 8, 1024, 3)
         r = measure_forward(torch, B, S, dtype, n, H, H, args.steps, args.warmup, seed)
-        peak = PEAK_TFLOPS[dtype]
         out.update({
-            "value": round(r["pixels_per_s"], 1), "ms_per_step": round(r["ms_per_step"], 4), "dtype": dtype,
+            "value": round(r["pixels_per_s"], 1), "ms_per_step": round(r["ms_per_step"], 4), "ms_per_step_events": r["events"], "dtype": dtype,
             "config": {"workload": "SK-Net forward, %dx1x%dx%d %s image(s), %s (BASELINE configs[%d])"
-                                   % (n, H, H, "fp32" if dtype == "f32" else dtype, net_desc, 1 if args.workload == "c2" else 2),
+                                   % (n, H, H, "fp32" if dtype == "f32" else dtype, NET_DESC, 1 if args.workload == "c2" else 2),
                        "global_batch": n, "parallelism": "single GPU"},
-            "roofline": {"bound": "mfma", "achieved": round(r["conv_tflops"], 2), "peak": peak, "unit": "TFLOP/s",
-                         "frac": round(r["conv_tflops"] / peak, 4),
-                         "traffic": int(sum(TRAFFIC_KIB[args.workload]) * 1024),
-                         "traffic_unit": "bytes beyond L2 per launch (read + written), from profiles/",
-                         "algorithmic_bytes": int(r["conv_alg_bytes"]),
-                         "kernel": "48->48 k4 SK convolutions at d=2,4,8 (%s)"
-                                   % ("conv_f32_pf_kernel<3,1,4,4,2,false,4>" if dtype == "f32" else "conv_h_ring_kernel<bf16,4,3,MAP4,8,false,3,true,4>")},
+            "roofline": forward_roofline(r, dtype, table, args.workload + "_conv"),
             "forward_tflops": round(r["forward_tflops"], 2),
             "pool_gbs": None if r["pool_gbs"] is None else round(r["pool_gbs"], 1),
             "pool_frac_of_hbm_peak": None if r["pool_gbs"] is None else round(r["pool_gbs"] / HBM_PEAK_GBS, 4),
@@ -440,26 +556,34 @@ def main():
             "measured_peaks": measured_peaks(torch, B),
         })
     else:
-        r = measure_train(torch, B, S, "bf16", 1, 512, 512, args.steps, args.warmup, 2)
+        n, H = (1, 512) if args.workload == "c4" else (8, 1024)
+        rt = measure_train(torch, B, S, "bf16", n, H, H, args.steps, args.warmup, 2 if n == 1 else 3)
         out.update({
-            "value": round(r["pixels_per_s"], 1), "ms_per_step": round(r["ms_per_step"], 4), "dtype": "bf16",
-            "config": {"workload": "SK-Net training step, 1x1x512x512 bf16: forward, softmax loss, backward, SGD; "
-                                   + net_desc + " (BASELINE configs[3])", "global_batch": 1, "parallelism": "single GPU"},
-            "roofline": None,
+            "value": round(rt["pixels_per_s"], 1), "ms_per_step": round(rt["ms_per_step"], 4), "ms_per_step_events": rt["events"], "dtype": "bf16",
+            "config": {"workload": "SK-Net training step, %dx1x%dx%d bf16: forward, softmax loss, backward, SGD; " % (n, H, H)
+                                   + NET_DESC + (" (BASELINE configs[3])" if n == 1 else " (configs[3]'s step on configs[2]'s batch)"),
+                       "global_batch": n, "parallelism": "single GPU"},
+            "roofline": train_roofline(rt, "bf16", table, args.workload + "_wgrad"), "parts_ms": rt["parts_ms"],
         })
 
     if args.workload == "c2" and not args.no_extras:
         extras = {}
         r3 = measure_forward(torch, B, S, "bf16", 8, 1024, 1024, 10, 3, 3, kernel_iters=5)
         extras["c3_bf16_forward_8x1024"] = {
-            "pixels_per_s": round(r3["pixels_per_s"], 1), "ms_per_step": round(r3["ms_per_step"], 4),
-            "conv_tflops": round(r3["conv_tflops"], 1), "conv_frac_of_bf16_mfma_peak": round(r3["conv_tflops"] / 2500.0, 4),
-            "pool_gbs": None if r3["pool_gbs"] is None else round(r3["pool_gbs"], 1),
-            "pool_frac_of_hbm_peak": None if r3["pool_gbs"] is None else round(r3["pool_gbs"] / HBM_PEAK_GBS, 4),
-            "step_ms": r3["step_ms"]}
-        for name, dt in (("c4_bf16_train_512", "bf16"), ("c4_as_f32_train_512", "f32")):
-            rt = measure_train(torch, B, S, dt, 1, 512, 512, 20, 3, 2)
-            extras[name] = {"pixels_per_s": round(rt["pixels_per_s"], 1), "ms_per_step": round(rt["ms_per_step"], 4)}
+            "pixels_per_s": round(r3["pixels_per_s"], 1), "ms_per_step": round(r3["ms_per_step"], 4), "ms_per_step_events": r3["events"],
+            "roofline": forward_roofline(r3, "bf16", table, "c3_conv"),
+            "forward_tflops": round(r3["forward_tflops"], 1),
+            "pool_gbs": None if r3["pool_gbs"] is None else round(r3["pool_gbs"], 1), "step_ms": r3["step_ms"]}
+        rt = measure_train(torch, B, S, "bf16", 1, 512, 512, 20, 3, 2)
+        extras["c4_bf16_train_512"] = {"pixels_per_s": round(rt["pixels_per_s"], 1), "ms_per_step": round(rt["ms_per_step"], 4),
+                                       "ms_per_step_events": rt["events"], "roofline": train_roofline(rt, "bf16", table, "c4_wgrad"),
+                                       "parts_ms": rt["parts_ms"]}
+        rt = measure_train(torch, B, S, "f32", 1, 512, 512, 10, 3, 2, detail=False)
+        extras["c4_as_f32_train_512"] = {"pixels_per_s": round(rt["pixels_per_s"], 1), "ms_per_step": round(rt["ms_per_step"], 4)}
+        rt = measure_train(torch, B, S, "bf16", 8, 1024, 1024, 5, 2, 3, kernel_iters=3)
+        extras["c3train_bf16_train_8x1024"] = {"pixels_per_s": round(rt["pixels_per_s"], 1), "ms_per_step": round(rt["ms_per_step"], 4),
+                                               "ms_per_step_events": rt["events"], "roofline": train_roofline(rt, "bf16", table, "c3train_wgrad"),
+                                               "parts_ms": rt["parts_ms"]}
         for name, dt in (("c5_unet_572_f32", "f32"), ("c5_unet_572_bf16", "bf16")):
             extras[name] = measure_unet(torch, B, S, dt, 10, 3)
         extras["paper_sknet_128_f32"] = measure_paper_sknet(torch, B, S, 5, 2)
@@ -473,17 +597,7 @@ def main():
         out["extras"] = extras
 
     if args.workload == "c2" and not args.no_cpu_baseline:
-        from oracle import nets as ON
-        reps, t_cpu = 0, 0.0
-        while t_cpu < 10.0 and reps < 40:
-            t0 = time.perf_counter()
-            ON.sknet_forward(r["img"], r["layers"], r["ws"], r["bs"])
-            t_cpu += time.perf_counter() - t0
-            reps += 1
-        out["cpu_baseline"] = {"value": round(512 * 512 * reps / t_cpu, 1), "unit": "pixels/s",
-                               "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)),
-                               "kind": "oracle",
-                               "sample": "%d full forward pass(es) of the same 512x512 workload, fp64 C oracle with OpenMP" % reps}
+        out["cpu_baseline"], out["cpu_baseline_more"] = cpu_baselines(S, r)
     print(json.dumps(out))
 
 

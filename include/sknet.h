@@ -203,6 +203,16 @@ sk_status sknet_get_pool_argmax(sknet_t *net, int32_t pool_idx, int32_t *idx_hos
 sk_status sknet_num_steps(const sknet_t *net, int32_t *count);
 sk_status sknet_step_name(const sknet_t *net, int32_t step, char *name, int32_t cap);
 sk_status sknet_time_step(sknet_t *net, int32_t step, int32_t iters, void *hip_stream, float *avg_ms);
+/* The same for one piece of the backward pass of the last forward on a training plan (for benchmarking; Section 6
+ * times layers one by one): part 0 = the weight and bias gradient of convolution layer layer_idx (all its launches:
+ * the gradient kernel and the reduction of its private copies), part 1 = the gradient of layer layer_idx's input (data
+ * gradient of a convolution, scatter of a pool; layer_idx >= 1), part 2 = the softmax loss and its gradient (layer_idx
+ * ignored).  The call first walks the backward pass from the loss down to that layer with labels_dev (DEVICE, as in
+ * sknet_backward) to rebuild the layer's error map, then repeats the piece iters times between two HIP events on
+ * hip_stream.  Weight gradients are overwritten on the way: sknet_get_grad reports SK_ESTATE until the next
+ * sknet_backward. */
+sk_status sknet_time_backward_step(sknet_t *net, const int32_t *labels_dev, int32_t layer_idx, int32_t part, int32_t iters, void *hip_stream,
+                                   float *avg_ms);
 
 /* ---------------------------------------------------------------- U-Net forward */
 

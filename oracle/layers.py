@@ -47,6 +47,20 @@ for _f in ("osk_mirror_pad", "osk_conv_sk", "osk_conv_sk_bwd_data", "osk_conv_sk
     getattr(_lib, _f).restype = None
 
 
+_lib.osk_get_num_threads.restype = C.c_int
+_lib.osk_set_num_threads.argtypes = [C.c_int]
+_lib.osk_set_num_threads.restype = None
+
+
+def num_threads():
+    """Threads the C loops run on (OpenMP's current maximum)."""
+    return int(_lib.osk_get_num_threads())
+
+
+def set_num_threads(n):
+    _lib.osk_set_num_threads(int(n))
+
+
 def mirror_pad(x, top, left, bottom, right, mode=0):
     """Extend every plane of x[n,c,h,w] by mirroring (Section 1.3). mode 0 reflect, 1 symmetric."""
     x = _f64(x)

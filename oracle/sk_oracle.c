@@ -21,6 +21,30 @@
 #include <stddef.h>
 #include <stdint.h>
 #include <math.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ---- threads: how many the parallel loops below use, and a way to set that number (the benchmark
+ *      reports the oracle's speed with the count it really ran on, and once on a single thread).
+ *      No arithmetic depends on it. ---- */
+int osk_get_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void osk_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
 
 /* ---- border mirroring (Section 1.3: the image is extended by mirroring so that every
  *      pixel has its full context).  mode 0: reflect without repeating the edge sample,

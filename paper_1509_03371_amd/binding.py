@@ -51,6 +51,7 @@ _SIGS = {
     "sknet_get_weights": [_vp, _i32, _fp, _fp],
     "sknet_plan": [_vp, _i32, _i32, _i32, _i32, _i32],
     "sknet_forward": [_vp, _vp, _vp, _vp],
+    "sknet_time_backward_step": [_vp, _vp, _i32, _i32, _i32, _vp, _fp],
     "sknet_backward_noalloc": [_vp, _vp, _vp, _vp],
     "sknet_backward": [_vp, _vp, _vp, _vp],
     "sknet_sgd_step": [_vp, C.c_float, C.c_float, C.c_float, _vp],
@@ -328,6 +329,12 @@ class SKNet:
         buf = C.create_string_buffer(64)
         _check(lib.sknet_step_name(self._h, step, buf, 64))
         return buf.value.decode()
+
+    def time_backward_step(self, labels, layer_idx, part, iters=10, stream=None):
+        """Average ms of one piece of the backward pass: part 0 weight gradient, 1 input gradient, 2 loss."""
+        ms = C.c_float()
+        _check(lib.sknet_time_backward_step(self._h, _dev_ptr(labels, torch.int32, "labels"), layer_idx, part, iters, _stream(stream), C.byref(ms)))
+        return ms.value
 
     def time_step(self, step, iters=10, stream=None):
         ms = C.c_float()

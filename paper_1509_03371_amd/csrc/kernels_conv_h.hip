@@ -1198,7 +1198,7 @@ int conv_h_mt(int c_out, int k)
     if (tiles <= 2) return tiles;
     if (k >= 5) return 3;
     const int pad3 = (tiles + 2) / 3 * 3, pad4 = (tiles + 3) / 4 * 4;
-    if (k == 3) return 3;
+    if (k == 3) return tiles == 4 ? 2 : 3;         // 64 maps: two groups of two tiles, not two groups of three with a third of them empty
     return pad3 <= pad4 ? 3 : 4;
 }
 

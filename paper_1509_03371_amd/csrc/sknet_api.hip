@@ -587,6 +587,61 @@ sk_status sknet_forward(sknet_t *net, const float *image_dev, float *prob_dev, v
     return SK_OK;
 }
 
+// Backward step of layer li: gcur holds the layer's error map, gnext receives the error map of the layer below
+// (with that layer's ReLU mask applied).  parts: bit 0 = the weight and bias gradient of a convolution, bit 1 = the
+// gradient of the layer's input (data gradient or pool scatter; never for layer 0, whose input is the image).
+static sk_status backward_layer(sknet_t *net, int li, float *gcur, float *gnext, int parts, hipStream_t stream, float *wgrad_scratch,
+                                size_t wgrad_cap)
+{
+    const int n = net->n, dt = net->dtype;
+    const bool half = net->half();
+    const sk_layer &l = net->layers[li];
+    const Dims &in = net->dims[li], &out = net->dims[li + 1];
+    // ReLU of the layer below acts on this layer's input: fuse its mask into whatever
+    // kernel produces the gradient of that input
+    const float *relu_src = (li > 0 && net->layers[li - 1].kind == SK_CONV && net->layers[li - 1].relu) ? net->act[li] : nullptr;
+    if (l.kind == SK_CONV) {
+        ConvParams &c = net->convs[net->conv_of_layer[li]];
+        if (parts & 1) {
+            if (half)
+                SK_HIP(sk::launch_wgrad_h(net->act[li], gcur, c.dw, c.db, wgrad_scratch, dt, n, in.c, in.h, in.w, c.c_out, c.k, l.d, stream,
+                                          wgrad_cap));
+            else
+                SK_HIP(sk::launch_wgrad_f32(net->act[li], gcur, c.dw, c.db, wgrad_scratch, n, in.c, in.h, in.w, c.c_out, c.k, l.d, stream,
+                                            wgrad_cap));
+        }
+        if (li == 0 || !(parts & 2)) return SK_OK;   // nothing below layer 0 needs the image gradient
+        if (half) {
+            sk::ConvHArgs a{};
+            a.x = gcur; a.wp = c.wp16_bwd; a.bias = nullptr; a.mask = relu_src; a.y = gnext; a.dtype = dt; a.zeros = net->zero_page;
+            a.n = n; a.c8_in = (out.c + 7) / 8; a.H = out.h; a.W = out.w;
+            a.c_out = in.c; a.c8_out = (in.c + 7) / 8;
+            a.k = c.k; a.d = l.d; a.in_off = (c.k - 1) * l.d; a.Ho = in.h; a.Wo = in.w; a.relu = 0; a.out_f32 = 0;
+            a.c8_out_total = (in.c + 7) / 8; a.o8_off = 0; a.OH = in.h; a.OW = in.w;
+            a.oy_mul = 1; a.oy_off = 0; a.ox_mul = 1; a.ox_off = 0;
+            SK_HIP(sk::launch_conv_h(a, stream));
+        } else {
+            sk::ConvF32Args a{};
+            a.x = gcur; a.wp = c.wp_bwd; a.bias = nullptr; a.mask = relu_src; a.y = gnext;
+            a.n = n; a.c_in = out.c; a.H = out.h; a.W = out.w;
+            a.c_out = in.c; a.n_pad = c.n_pad_bwd;
+            a.k = c.k; a.d = l.d; a.in_off = (c.k - 1) * l.d;
+            a.Ho = in.h; a.Wo = in.w; a.relu = 0;
+            a.out_maps = in.c; a.o_off = 0; a.OH = in.h; a.OW = in.w;
+            a.oy_mul = 1; a.oy_off = 0; a.ox_mul = 1; a.ox_off = 0;
+            SK_HIP(sk::launch_conv_f32(a, stream));
+        }
+        return SK_OK;
+    }
+    if (li == 0 || !(parts & 2)) return SK_OK;
+    if (half)
+        SK_HIP(sk::launch_maxpool_bwd_h(gcur, net->tap[li], relu_src, gnext, dt, (long)n * ((in.c + 7) / 8), in.h, in.w, out.h, out.w, l.k,
+                                        l.d, stream));
+    else
+        SK_HIP(sk::launch_maxpool_bwd_f32(gcur, net->tap[li], relu_src, gnext, n * in.c, in.h, in.w, out.h, out.w, l.k, l.d, stream));
+    return SK_OK;
+}
+
 // The backward pass from the loss down to layer stop_layer (0 = all of it).  With stop_layer > 0 the walk
 // ends before layer stop_layer's own step and *grad_at_stop receives the buffer that holds the gradient of
 // the loss with respect to that layer's output (after the layer's own ReLU mask), in the storage layout
@@ -616,50 +671,8 @@ static sk_status backward_impl(sknet_t *net, const int32_t *labels_dev, float *l
             *grad_at_stop = gcur;
             return SK_OK;
         }
-        const sk_layer &l = net->layers[li];
-        const Dims &in = net->dims[li], &out = net->dims[li + 1];
-        // ReLU of the layer below acts on this layer's input: fuse its mask into whatever
-        // kernel produces the gradient of that input
-        const float *relu_src = (li > 0 && net->layers[li - 1].kind == SK_CONV && net->layers[li - 1].relu)
-                                    ? net->act[li] : nullptr;
-        if (l.kind == SK_CONV) {
-            ConvParams &c = net->convs[net->conv_of_layer[li]];
-            if (half)
-                SK_HIP(sk::launch_wgrad_h(net->act[li], gcur, c.dw, c.db, wgrad_scratch, dt, n, in.c, in.h, in.w,
-                                          c.c_out, c.k, l.d, stream, wgrad_cap));
-            else
-                SK_HIP(sk::launch_wgrad_f32(net->act[li], gcur, c.dw, c.db, wgrad_scratch, n, in.c, in.h, in.w,
-                                            c.c_out, c.k, l.d, stream, wgrad_cap));
-            if (li == 0) break;   // nothing below needs the image gradient
-            if (half) {
-                sk::ConvHArgs a{};
-                a.x = gcur; a.wp = c.wp16_bwd; a.bias = nullptr; a.mask = relu_src; a.y = gnext; a.dtype = dt; a.zeros = net->zero_page;
-                a.n = n; a.c8_in = (out.c + 7) / 8; a.H = out.h; a.W = out.w;
-                a.c_out = in.c; a.c8_out = (in.c + 7) / 8;
-                a.k = c.k; a.d = l.d; a.in_off = (c.k - 1) * l.d; a.Ho = in.h; a.Wo = in.w; a.relu = 0; a.out_f32 = 0;
-                a.c8_out_total = (in.c + 7) / 8; a.o8_off = 0; a.OH = in.h; a.OW = in.w;
-                a.oy_mul = 1; a.oy_off = 0; a.ox_mul = 1; a.ox_off = 0;
-                SK_HIP(sk::launch_conv_h(a, stream));
-            } else {
-                sk::ConvF32Args a{};
-                a.x = gcur; a.wp = c.wp_bwd; a.bias = nullptr; a.mask = relu_src; a.y = gnext;
-                a.n = n; a.c_in = out.c; a.H = out.h; a.W = out.w;
-                a.c_out = in.c; a.n_pad = c.n_pad_bwd;
-                a.k = c.k; a.d = l.d; a.in_off = (c.k - 1) * l.d;
-                a.Ho = in.h; a.Wo = in.w; a.relu = 0;
-                a.out_maps = in.c; a.o_off = 0; a.OH = in.h; a.OW = in.w;
-                a.oy_mul = 1; a.oy_off = 0; a.ox_mul = 1; a.ox_off = 0;
-                SK_HIP(sk::launch_conv_f32(a, stream));
-            }
-        } else {
-            if (li == 0) break;
-            if (half)
-                SK_HIP(sk::launch_maxpool_bwd_h(gcur, net->tap[li], relu_src, gnext, dt, (long)n * ((in.c + 7) / 8), in.h,
-                                                in.w, out.h, out.w, l.k, l.d, stream));
-            else
-                SK_HIP(sk::launch_maxpool_bwd_f32(gcur, net->tap[li], relu_src, gnext, n * in.c, in.h, in.w, out.h,
-                                                  out.w, l.k, l.d, stream));
-        }
+        SK_TRY(backward_layer(net, li, gcur, gnext, 3, stream, wgrad_scratch, wgrad_cap));
+        if (li == 0) break;
         float *t = gcur; gcur = gnext; gnext = t;
     }
     return SK_OK;
@@ -885,6 +898,49 @@ sk_status sknet_time_step(sknet_t *net, int32_t step, int32_t iters, void *hip_s
     (void)hipEventDestroy(e1);
     if (st != SK_OK) return st;
     if (e != hipSuccess) return fail(SK_EDEVICE, "time_step: %s", hipGetErrorString(e));
+    *avg_ms = ms / (float)iters;
+    return SK_OK;
+}
+
+sk_status sknet_time_backward_step(sknet_t *net, const int32_t *labels_dev, int32_t layer_idx, int32_t part, int32_t iters, void *hip_stream,
+                                   float *avg_ms)
+{
+    SK_TRY(check_net(net));
+    const int L = (int)net->layers.size();
+    if (!avg_ms || !labels_dev || iters < 1 || part < 0 || part > 2 || (part != 2 && (layer_idx < 0 || layer_idx >= L)))
+        return fail(SK_EINVAL, "time_backward_step: bad arguments");
+    if (!net->planned || !net->training || !net->forward_done) return fail(SK_ESTATE, "time_backward_step: needs a forward pass on a training plan");
+    if (part == 0 && net->layers[layer_idx].kind != SK_CONV) return fail(SK_EINVAL, "time_backward_step: layer %d has no weights", layer_idx);
+    if (part == 1 && layer_idx == 0) return fail(SK_EINVAL, "time_backward_step: layer 0 has no input gradient");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    net->last_stream = stream;
+    net->backward_done = false;                // the walk overwrites weight gradients
+    float *loss = nullptr, *g = nullptr;
+    SK_TRY(alloc_f(&loss, 1));
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    hipError_t e = hipEventCreate(&e0);
+    if (e == hipSuccess) e = hipEventCreate(&e1);
+    sk_status st = e == hipSuccess ? SK_OK : fail(SK_EDEVICE, "time_backward_step: %s", hipGetErrorString(e));
+    // the error map of the layer (part 2: the loss alone, which is the walk down to the last layer)
+    const int li = part == 2 ? L - 1 : layer_idx;
+    if (st == SK_OK) st = backward_impl(net, labels_dev, loss, stream, li, &g, net->loss_partial, net->wgrad_scratch, 0);
+    float *other = g == net->gbuf[0] ? net->gbuf[1] : net->gbuf[0];
+    auto once = [&]() -> sk_status {
+        if (part == 2) return backward_impl(net, labels_dev, loss, stream, L - 1, &g, net->loss_partial, net->wgrad_scratch, 0);
+        return backward_layer(net, li, g, other, part == 0 ? 1 : 2, stream, net->wgrad_scratch, 0);
+    };
+    if (st == SK_OK) st = once();              // warm-up
+    if (st == SK_OK) e = hipEventRecord(e0, stream);
+    for (int i = 0; i < iters && st == SK_OK; ++i) st = once();
+    if (st == SK_OK && e == hipSuccess) e = hipEventRecord(e1, stream);
+    if (st == SK_OK && e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (st == SK_OK && e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    free_dev(loss);
+    if (st != SK_OK) return st;
+    if (e != hipSuccess) return fail(SK_EDEVICE, "time_backward_step: %s", hipGetErrorString(e));
     *avg_ms = ms / (float)iters;
     return SK_OK;
 }

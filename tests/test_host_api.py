@@ -137,8 +137,9 @@ def test_usknet_handle_host_logic(golden_rows):
             net.output_size(*bad)
         assert e.value.status_name == "SK_ESHAPE"
     net.close()
+    B.USKNet(3, 2, base_ch=64, dtype="f16").close()          # 16-bit storage: maps in groups of 8
     with pytest.raises(B.SknetError) as e:
-        B.USKNet(3, 2, base_ch=64, dtype="f16")
+        B.USKNet(3, 2, base_ch=12, dtype="f16")
     assert e.value.status_name == "SK_EUNSUPPORTED"
 
 
