@@ -394,7 +394,8 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
 // apart, so that neighbour is the wave's own next accumulator row).  Tiles are then walked down the columns
 // of the tile grid in contiguous runs, and the last row of a tile is carried in registers to the next one.
 // a.hd > 0 (producer waves only): the input was written by such a launch with kernel stride hd; the producer
-// waves finish its pool on the way in, tile[x] = max(in[x], in[x + hd]), in place in the LDS stage.
+// waves finish its pool on the way in, tile[x] = max(in[x], in[x + hd]), in registers between the global loads and
+// the LDS write.
 template <int DT, int KS, int MT, bool MAP4, int R, bool HAS_MASK, int S, bool RESW, int NP, bool VPOOL = false>
 __global__ __launch_bounds__(CH_THREADS + 64 * NP) void conv_h_ring_kernel(ConvHArgs a)
 {
@@ -419,7 +420,7 @@ __global__ __launch_bounds__(CH_THREADS + 64 * NP) void conv_h_ring_kernel(ConvH
     // tile holds the row below its last pooled row itself and nothing is carried from tile to tile
     const int ypitch = VPOOL ? a.ypitch : R;
     const int PWL = CH_TX + (KS - 1) * d;                      // tile width the multiplication reads
-    const int PW = PWL + hd;                                   // staged row pitch: hd raw columns more
+    const int PW = PWL;                                        // staged row pitch
     const int tile_units = ROWS * PW;
     // RESW: the weights of every chunk stay in LDS for the whole kernel (one map group only) and the
     // ring stages hold input tiles only; otherwise each stage also carries its chunk's weight slab
@@ -574,36 +575,6 @@ __global__ __launch_bounds__(CH_THREADS + 64 * NP) void conv_h_ring_kernel(ConvH
             if (blk >= WBLK) break;                              // uniform
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(wsrc + (unsigned)(blk * 1024 + lane * 16)),
                                              (__attribute__((address_space(3))) void *)(dst + tile_units + blk * 64), 16, 0, 0);
-        }
-    };
-
-    // Horizontal half of the pending pool, in place in ring stage st, on the rows this producer wave loaded
-    // itself (so its own vmcnt wait covers them): unit x of a row becomes max(unit x, unit x + hd) for the PWL
-    // units the multiplication reads.  The values are ReLU outputs (>= +0), for which the unsigned 16-bit order
-    // of the bit patterns is the numerical order in both storage types.  A row is read completely before any
-    // of it is written, because unit x + hd is itself overwritten as unit x' = x + hd.
-    auto hmax_in_place = [&](int st) {
-        uint4v *base = lds + st * stage_units;
-#pragma unroll
-        for (int u = 0; u < RU; ++u) {
-            const int rid = lw + LW * u;
-            if (rid >= ROWS) break;                              // uniform
-            uint4v *row = base + rid * PW;
-            uint4v va[VUE], vb[VUE];
-#pragma unroll
-            for (int v = 0; v < VUE; ++v) {
-                const int xc = lane + 64 * v;
-                if (xc < PWL) {
-                    va[v] = row[xc];
-                    vb[v] = row[xc + hd];
-                }
-            }
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#pragma unroll
-            for (int v = 0; v < VUE; ++v) {
-                const int xc = lane + 64 * v;
-                if (xc < PWL) row[xc] = max_u16x8(va[v], vb[v]);
-            }
         }
     };
 
@@ -892,8 +863,10 @@ __global__ __launch_bounds__(CH_THREADS + 64 * NP) void conv_h_ring_kernel(ConvH
     Cursor icur = cursor_at(t), ccur = icur;
     TilePos ipos = position(icur);
     int ich = 0, issued = 0, itiles = 0;
-    auto issue_next = [&]() {
-        issue(ipos, ich, issued % S);
+    // the next chunk in this workgroup's order: its tile position and its chunk number inside the tile
+    auto take_next = [&](TilePos &p, int &ch) {
+        p = ipos;
+        ch = ich;
         ++issued;
         if (++ich == a.nchunks) {
             ich = 0;
@@ -903,14 +876,112 @@ __global__ __launch_bounds__(CH_THREADS + 64 * NP) void conv_h_ring_kernel(ConvH
             }
         }
     };
+    auto issue_next = [&]() {
+        TilePos p;
+        int ch;
+        const int st = issued % S;
+        take_next(p, ch);
+        issue(p, ch, st);
+    };
+    // (a pending pool of the input is finished in registers on the way into LDS: see the producer branch below)
+    if (!(NP > 0 && hd > 0)) {
 #pragma unroll
-    for (int j = 0; j < S - 1; ++j)
-        if (j < total_chunks && lw >= 0) issue_next();
+        for (int j = 0; j < S - 1; ++j)
+            if (j < total_chunks && lw >= 0) issue_next();
+    }
 
     if constexpr (NP > 0) {
         // Every wave meets the same barrier once per chunk.  A producer arrives when its loads of
         // chunk q have landed and then refills the stage that was multiplied in the previous
         // iteration; a multiplying wave arrives when it is done with chunk q - 1.
+        if (wave >= CH_WAVES && hd > 0) {
+            // The input lacks the horizontal half of its pool: unit x of the tile is max(X[x], X[x + hd]).  The producer
+            // waves load both operands into registers (two chunks in flight, in two register sets), take the maximum
+            // and write the result into the ring stage -- one LDS write per unit, where loading the raw row straight
+            // into LDS and pooling it in place cost the direct write, two reads and a write.  Chunk c is loaded
+            // after barrier c - 3, written after barrier c - 1 (its stage was multiplied before barrier c - 2) and
+            // multiplied after barrier c.  The values are ReLU outputs (>= +0): the unsigned 16-bit order of the
+            // bit patterns is their numerical order.
+            const int my_rows = (ROWS - lw + LW - 1) / LW;         // tile rows this wave stages
+            const int Lr = 2 * my_rows * VUE;                      // its loads per chunk
+            uint4v rA[RU][VUE][2], rB[RU][VUE][2];
+            TilePos pA = ipos, pB = ipos;
+            int cA = 0, cB = 0;
+            auto gload = [&](uint4v (&r)[RU][VUE][2], const TilePos &p, int ch) {
+                const int gy0 = p.py + d * (p.ty * ypitch), gx0 = p.x0 + lane;
+#pragma unroll
+                for (int u = 0; u < RU; ++u) {
+                    const int rid = lw + LW * u;
+                    if (rid >= ROWS) break;                          // uniform: this wave has no further row
+                    const int oc = rid / RR, rr = rid - oc * RR;
+                    int o = ch * OC + oc, gy = gy0 + rr * d;
+                    o = o < a.c8_in ? o : a.c8_in - 1;
+                    gy = gy < a.H ? gy : a.H - 1;
+                    const uint4v *row = reinterpret_cast<const uint4v *>(reinterpret_cast<const char *>(a.x) + ((long)p.b * a.c8_in + o) * plane_bytes_in +
+                                                                         (long)gy * Wmem * 16);
+#pragma unroll
+                    for (int v = 0; v < VUE; ++v) {
+                        int gx = gx0 + 64 * v;
+                        gx = gx < a.W ? gx : a.W - 1;                // clamped: what lies outside is replaced by zero when it is stored
+                        r[u][v][0] = row[gx];
+                        r[u][v][1] = row[gx + hd];
+                    }
+                }
+            };
+            auto gstore = [&](uint4v (&r)[RU][VUE][2], const TilePos &p, int ch, int st) {
+                uint4v *dst = lds + st * stage_units;
+                const int gy0 = p.py + d * (p.ty * ypitch), gx0 = p.x0 + lane;
+#pragma unroll
+                for (int u = 0; u < RU; ++u) {
+                    const int rid = lw + LW * u;
+                    if (rid >= ROWS) break;
+                    const int oc = rid / RR, rr = rid - oc * RR;
+                    const bool rowok = ch * OC + oc < a.c8_in && gy0 + rr * d < a.H;
+#pragma unroll
+                    for (int v = 0; v < VUE; ++v) {
+                        const int xc = lane + 64 * v;
+                        uint4v m = max_u16x8(r[u][v][0], r[u][v][1]);
+                        if (!(rowok && gx0 + 64 * v < a.W)) m = uint4v{0u, 0u, 0u, 0u};
+                        if (xc < PWL) dst[rid * PW + xc] = m;
+                    }
+                }
+            };
+            // chunk c (c >= 1), right after barrier c - 1: from its register set into its stage, then chunk c + 2 into the set
+            auto step = [&](uint4v (&r)[RU][VUE][2], TilePos &p, int &ch, int c) {
+                if (c >= total_chunks) return;
+                __builtin_amdgcn_sched_barrier(0);
+                wait_vmcnt_at_most(c + 1 < total_chunks ? Lr : 0);   // the loads of chunk c + 1 are younger and may be in flight
+                __builtin_amdgcn_sched_barrier(0);
+                gstore(r, p, ch, c % S);
+                if (c + 2 < total_chunks) {
+                    take_next(p, ch);
+                    gload(r, p, ch);
+                }
+            };
+            take_next(pA, cA);
+            gload(rA, pA, cA);                                       // chunk 0
+            if (total_chunks > 1) {
+                take_next(pB, cB);
+                gload(rB, pB, cB);                                   // chunk 1
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            wait_vmcnt_at_most(total_chunks > 1 ? Lr : 0);
+            __builtin_amdgcn_sched_barrier(0);
+            gstore(rA, pA, cA, 0);
+            if (total_chunks > 2) {
+                take_next(pA, cA);
+                gload(rA, pA, cA);                                   // chunk 2
+            }
+            for (int q = 0; q < total_chunks; q += 2) {
+                block_sync_lds();                                    // barrier q: chunk q is in LDS
+                step(rB, pB, cB, q + 1);
+                if (q + 1 < total_chunks) {
+                    block_sync_lds();                                // barrier q + 1
+                    step(rA, pA, cA, q + 2);
+                }
+            }
+            return;
+        }
         if (wave >= CH_WAVES) {
             for (int q = 0; q < total_chunks; ++q) {
                 int allow = (issued - q - 1) * L;          // loads of younger chunks may still be in flight
@@ -918,7 +989,6 @@ __global__ __launch_bounds__(CH_THREADS + 64 * NP) void conv_h_ring_kernel(ConvH
                 __builtin_amdgcn_sched_barrier(0);
                 wait_vmcnt_at_most(allow);
                 __builtin_amdgcn_sched_barrier(0);
-                if (hd > 0) hmax_in_place(q % S);          // chunk q has landed: finish the input's pool on this wave's rows
                 block_sync_lds();
                 if (issued < total_chunks) issue_next();
             }
@@ -1076,7 +1146,8 @@ template <int KS, int MT, bool MAP4, int R, int S, bool RESW>
 static size_t ring_smem(int d, int c_out, int c8_in, int Ho, int hd = 0)
 {
     constexpr int RR = R + KS - 1, OC = MAP4 ? 1 : 4, CS = MAP4 ? 1 : KS;
-    const int PW = CH_TX + (KS - 1) * d + hd;
+    const int PW = CH_TX + (KS - 1) * d;                       // (a pending pool of the input is finished before the tile is staged)
+    (void)hd;
     const size_t tile = (size_t)OC * RR * PW, slab = (size_t)CS * KS * MT * 64;
     const int nchunks = (c8_in + OC - 1) / OC;
     const int m_tiles_all = ((c_out + 15) / 16 + MT - 1) / MT * MT;
