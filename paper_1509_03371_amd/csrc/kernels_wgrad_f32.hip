@@ -591,7 +591,8 @@ size_t wgrad_f32_scratch_floats(int c_out, int c_in, int k)
     int copies = wgrad_max_copies(wgrad_tile_groups(MTo, NTk, MB, NB));
     wgrad_tiling(c_out, c_in, k, true, MTo, NTk, MB, NB);
     copies = std::max(copies, wgrad_max_copies(wgrad_tile_groups(MTo, NTk, MB, NB)));
-    return (size_t)copies * MTo * 16 * NTk * 16 + wgrad_bias_floats(c_out);
+    const size_t segs = (size_t)copies * MTo * 16 * NTk * 16 + wgrad_bias_floats(c_out);
+    return std::max(segs, wgrad_rows_h_supported(c_in, c_out, k, 1) ? wgrad_rows_h_scratch_floats(c_in, c_out) : (size_t)0);
 }
 
 template <int MB, int NB, int DT>
@@ -774,8 +775,11 @@ hipError_t launch_wgrad_f32_grouped(const float *x, const float *dy, float *dw, 
 // same gradient from 16-bit octet-layout activations (dtype 1 = bf16, 2 = fp16): the operands are
 // staged as they are and widened to fp32 when read, the contraction runs on the fp32 MFMA path
 hipError_t launch_wgrad_h(const void *x, const void *dy, float *dw, float *db, float *scratch, int dtype,
-                          int n, int c_in, int H, int W, int c_out, int k, int d, hipStream_t stream, size_t scratch_cap)
+                          int n, int c_in, int H, int W, int c_out, int k, int d, hipStream_t stream, size_t scratch_cap, const void *zeros)
 {
+    if (zeros && (dtype == 1 || dtype == 2) && wgrad_rows_h_supported(c_in, c_out, k, d))
+        return launch_wgrad_rows_h(x, dy, zeros, dw, db, scratch, scratch_cap ? scratch_cap : wgrad_f32_scratch_floats(c_out, c_in, k), dtype, n,
+                                   c_in, H, W, c_out, d, stream);
     return dtype == 1 ? launch_wgrad_dt<1>(x, dy, dw, db, scratch, n, c_in, H, W, c_out, k, d, stream, 0, 0, 0, scratch_cap)
                       : launch_wgrad_dt<2>(x, dy, dw, db, scratch, n, c_in, H, W, c_out, k, d, stream, 0, 0, 0, scratch_cap);
 }

@@ -151,8 +151,16 @@ hipError_t launch_wgrad_f32(const float *x, const float *dy, float *dw, float *d
 hipError_t launch_wgrad_f32_grouped(const float *x, const float *dy, float *dw, float *db, float *scratch, int n, int c_in, int H,
                                     int W, int c_out, int k, int d, long x_bstride, int grp_maps, long grp_skip, hipStream_t stream);
 
+// zeros: at least 1 KB of zeros in device memory (the row-streaming form of the 4x4 gradient reads the gradient rows
+// beyond the image from there); nullptr keeps every shape on the segment kernel
 hipError_t launch_wgrad_h(const void *x, const void *dy, float *dw, float *db, float *scratch, int dtype,
-                          int n, int c_in, int H, int W, int c_out, int k, int d, hipStream_t stream, size_t scratch_cap = 0);
+                          int n, int c_in, int H, int W, int c_out, int k, int d, hipStream_t stream, size_t scratch_cap = 0,
+                          const void *zeros = nullptr);
+// 16-bit storage, 4x4 kernels up to 48 -> 48 maps: rows streamed through an LDS ring, operands transposed by the LDS read
+bool wgrad_rows_h_supported(int c_in, int c_out, int k, int d);
+size_t wgrad_rows_h_scratch_floats(int c_in, int c_out);
+hipError_t launch_wgrad_rows_h(const void *x, const void *dy, const void *zeros, float *dw, float *db, float *scratch, size_t scratch_floats,
+                               int dtype, int n, int c_in, int H, int W, int c_out, int d, hipStream_t stream);
 
 // ---- HBM-bound layers ---------------------------------------------------------------------------
 hipError_t launch_mirror_pad_f32(const float *in, float *out, int planes, int h, int w, int top,

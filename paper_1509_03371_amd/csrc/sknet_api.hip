@@ -605,7 +605,7 @@ static sk_status backward_layer(sknet_t *net, int li, float *gcur, float *gnext,
         if (parts & 1) {
             if (half)
                 SK_HIP(sk::launch_wgrad_h(net->act[li], gcur, c.dw, c.db, wgrad_scratch, dt, n, in.c, in.h, in.w, c.c_out, c.k, l.d, stream,
-                                          wgrad_cap));
+                                          wgrad_cap, net->zero_page));
             else
                 SK_HIP(sk::launch_wgrad_f32(net->act[li], gcur, c.dw, c.db, wgrad_scratch, n, in.c, in.h, in.w, c.c_out, c.k, l.d, stream,
                                             wgrad_cap));
