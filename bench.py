@@ -81,7 +81,8 @@ def build_net(B, S, dtype, n, H, W, training):
     net = B.SKNet(layers, 1, 2, dtype=dtype)
     for i, (w, b) in enumerate(zip(ws, bs)):
         net.set_weights(i, w, b)
-    net.plan(n, H, W, pad=True, training=training)
+    # 16-bit training: the head (48 -> 200 -> 2) and the loss as one kernel in each direction (plan mode 3)
+    net.plan(n, H, W, pad=True, training=training, fused_head=training and dtype != "f32")
     return net, layers, ws, bs
 
 
@@ -193,7 +194,12 @@ def measure_train(torch, B, S, dtype, n, H, W, steps, warmup, first_seed, kernel
                 pool_fwd_ms += ms
                 pool_fwd_bytes += n * c * ho * wo * (2.0 * esize + 1)          # element in, element out, one winner code
         parts["loss_ms"] = round(net.time_backward_step(labels, 0, 2, kernel_iters, stream), 5)
+        head_fused = dtype != "f32"                                      # its two layers have no steps of their own
+        if head_fused:
+            parts["head_loss_backward_ms"] = parts.pop("loss_ms")
         for li, l in enumerate(layers):
+            if head_fused and li >= len(layers) - 2:
+                continue
             c, ho, wo = shapes[li + 1]
             if l["type"] == "conv":
                 ms = net.time_backward_step(labels, li, 0, kernel_iters, stream)
@@ -217,6 +223,8 @@ def measure_train(torch, B, S, dtype, n, H, W, steps, warmup, first_seed, kernel
         # labels in (count pass), logits + labels in and fp32 gradient out (2 classes); 16-bit storage: the gradient is
         # read once more and written as one 16-byte octet per pixel for the layers below
         loss_bytes = n * ho * wo * (4 + (2 * 4 + 4 + 2 * 4.0) + (0.0 if dtype == "f32" else 2 * 4 + 16))
+        if head_fused:                                                   # labels twice, the head's input in, its gradient out
+            loss_bytes = n * ho * wo * (2 * 4 + 2.0 * esize * f_in_of[len(layers) - 2])
         res.update({
             "parts_ms": parts,
             "step_tflops": round(3.0 * sum(flops.values()) / (res["ms_per_step"] * 1e-3) / 1e12, 2),   # forward + two gradients per conv
@@ -224,7 +232,7 @@ def measure_train(torch, B, S, dtype, n, H, W, steps, warmup, first_seed, kernel
                       "alg_flops": wg_flops / max(wg_n, 1)},
             "pool_fwd_gbs": round(pool_fwd_bytes / (pool_fwd_ms * 1e-3) / 1e9, 1) if pool_fwd_ms else None,
             "pool_bwd_gbs": round(pool_bwd_bytes / (pool_bwd_ms * 1e-3) / 1e9, 1) if pool_bwd_ms else None,
-            "softmax_loss_gbs": round(loss_bytes / (parts["loss_ms"] * 1e-3) / 1e9, 1),
+            "softmax_loss_gbs": round(loss_bytes / (parts["head_loss_backward_ms" if head_fused else "loss_ms"] * 1e-3) / 1e9, 1),
         })
     net.close()
     return res
@@ -560,7 +568,7 @@ def main():
         rt = measure_train(torch, B, S, "bf16", n, H, H, args.steps, args.warmup, 2 if n == 1 else 3)
         out.update({
             "value": round(rt["pixels_per_s"], 1), "ms_per_step": round(rt["ms_per_step"], 4), "ms_per_step_events": rt["events"], "dtype": "bf16",
-            "config": {"workload": "SK-Net training step, %dx1x%dx%d bf16: forward, softmax loss, backward, SGD; " % (n, H, H)
+            "config": {"workload": "SK-Net training step, %dx1x%dx%d bf16: forward, softmax loss, backward, SGD (head and loss one kernel per direction); " % (n, H, H)
                                    + NET_DESC + (" (BASELINE configs[3])" if n == 1 else " (configs[3]'s step on configs[2]'s batch)"),
                        "global_batch": n, "parallelism": "single GPU"},
             "roofline": train_roofline(rt, "bf16", table, args.workload + "_wgrad"), "parts_ms": rt["parts_ms"],

@@ -137,7 +137,12 @@ sk_status sknet_get_weights(sknet_t *net, int32_t conv_idx, float *w_host, float
  *          softmax" runs as one kernel whose hidden maps and logits never reach memory; then
  *          sknet_get_activation reports SK_ESTATE for those two layers);
  * mode 1 = training: every activation and the pool winners are kept, gradient buffers allocated;
- * mode 2 = inference with every layer's output kept in memory (for parity checks).
+ * mode 2 = inference with every layer's output kept in memory (for parity checks);
+ * mode 3 = training as mode 1, but a trailing "1x1 conv + ReLU, 1x1 conv" and the softmax loss (Sections 4.2, 4.3)
+ *          run as one kernel in each direction: the hidden maps, the logits and their gradients never reach memory
+ *          (the backward kernel recomputes the hidden maps from the head's input).  16-bit storage, at most 48
+ *          input maps, 208 hidden maps and 4 classes, a pool in front of the head; SK_EUNSUPPORTED otherwise.
+ *          sknet_get_activation and sknet_get_activation_grad report SK_ESTATE / SK_EUNSUPPORTED for those two layers.
  * May be called again to change the size or mode.  SK_ESHAPE as in sknet_infer_shapes. */
 sk_status sknet_plan(sknet_t *net, int32_t n, int32_t h, int32_t w, int32_t pad, int32_t mode);
 

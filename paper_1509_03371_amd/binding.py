@@ -252,9 +252,10 @@ class SKNet:
         _check(lib.sknet_get_weights(self._h, conv_idx, w.ctypes.data_as(_fp), b.ctypes.data_as(_fp)))
         return w, b
 
-    def plan(self, n, h, w, pad=True, training=False, keep=False):
-        """mode 1 if training, else 2 if keep (inference, every layer kept), else 0 (inference, fused)."""
-        mode = 1 if training else (2 if keep else 0)
+    def plan(self, n, h, w, pad=True, training=False, keep=False, fused_head=False):
+        """mode 1 if training (3 with fused_head: the head and the loss as one kernel in each direction),
+        else 2 if keep (inference, every layer kept), else 0 (inference, fused)."""
+        mode = (3 if fused_head else 1) if training else (2 if keep else 0)
         _check(lib.sknet_plan(self._h, n, h, w, int(pad), mode))
         self._plan = (n, h, w, bool(pad), bool(training))
         self._shapes = self.infer_shapes(h, w, pad)

@@ -599,6 +599,14 @@ __global__ void loss_finish_kernel(const float *partial, const int *counts, int 
     if (threadIdx.x == 0) *loss = s / (float)(kept > 0 ? kept : 1);
 }
 
+hipError_t launch_label_count(const int32_t *labels, long pixels, int classes, int *counts, int *ncounts, hipStream_t stream)
+{
+    const int blocks = loss_blocks(pixels);
+    hipLaunchKernelGGL(label_count_kernel, dim3(blocks), dim3(LOSS_BLOCK), 0, stream, labels, pixels, classes, counts);
+    *ncounts = blocks;
+    return hipGetLastError();
+}
+
 hipError_t launch_softmax_loss_f32(const float *z, const int32_t *labels, float *dz, float *loss,
                                    float *partial, int n, int classes, int hw, hipStream_t stream)
 {

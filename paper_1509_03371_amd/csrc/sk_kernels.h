@@ -135,6 +135,25 @@ long head_w1_packed_bytes(int dtype, int c_in, int hidden);
 hipError_t launch_pack_head_w1(const float *w1, void *out, int dtype, int hidden, int c_in, hipStream_t stream);
 hipError_t launch_head_fused(HeadArgs a, hipStream_t stream);
 
+// Backward pass of the same head with the softmax loss in one kernel (16-bit storage): nothing but x is read and
+// nothing but dx, the two layers' weight / bias gradients and the loss is written.
+struct HeadTrainArgs {
+    const void *x;            // input maps, 16-bit octet layout [n][ceil(c_in/8)][plane][8]
+    const void *w1p;          // first conv's weights packed by launch_pack_head_w1
+    const float *w1;          // the same weights, fp32 [hidden][c_in]
+    const float *b1, *w2, *b2;
+    const int32_t *labels;    // [n][plane]; outside 0..classes-1: masked
+    const int *counts;        // partial counts of the labelled pixels (launch_label_count)
+    int ncounts;
+    void *dx;                 // gradient of the loss with respect to x, layout of x (nullptr: not wanted)
+    float *scratch;           // head_train_scratch_floats(...) floats, or fewer (fewer workgroups)
+    float *dw1, *db1, *dw2, *db2, *loss;
+    int dtype, n, c_in, plane, hidden, classes;
+};
+bool head_train_supported(int dtype, int c_in, int hidden, int classes);
+size_t head_train_scratch_floats(int c_in, int hidden);
+hipError_t launch_head_train_bwd(HeadTrainArgs a, size_t scratch_floats, hipStream_t stream);
+
 // ---- weight / bias gradient of the SK convolution (fp32) ---------------------------------------
 // dW[o][c][i][j] = sum_{b,y,x} dY[b,o,y,x] * X[b,c,y+i*d,x+j*d];  db[o] = sum dY[b,o,:,:].
 // scratch must hold wgrad_f32_scratch_floats(...) floats (scratch_cap = 0), or scratch_cap floats with
@@ -194,6 +213,8 @@ hipError_t launch_softmax_f32(const float *z, float *p, int n, int classes, int 
 // any other label value (-1 by convention) masks the pixel (no loss, zero gradient) and P counts the
 // labelled pixels only.  partial must hold softmax_loss_partials(n*hw) floats.
 int softmax_loss_partials(long pixels);
+// counts[0..*ncounts) = partial counts of the pixels whose label lies in 0..classes-1 (counts: softmax_loss_partials(pixels) ints)
+hipError_t launch_label_count(const int32_t *labels, long pixels, int classes, int *counts, int *ncounts, hipStream_t stream);
 hipError_t launch_softmax_loss_f32(const float *z, const int32_t *labels, float *dz, float *loss,
                                    float *partial, int n, int classes, int hw, hipStream_t stream);
 // g = dw + wd*w; v = mu*v + lr*g; w -= v   (v may be nullptr when mu = 0)

@@ -435,8 +435,9 @@ sk_status sknet_plan(sknet_t *net, int32_t n, int32_t h, int32_t w, int32_t pad,
 {
     SK_TRY(check_net(net));
     if (n < 1) return fail(SK_EINVAL, "plan: n must be >= 1");
-    if (mode < 0 || mode > 2) return fail(SK_EINVAL, "plan: mode must be 0 (inference), 1 (training) or 2 (inference, every layer kept)");
-    const int training = mode == 1;
+    if (mode < 0 || mode > 3)
+        return fail(SK_EINVAL, "plan: mode must be 0 (inference), 1 (training), 2 (inference, every layer kept) or 3 (training, head in one kernel)");
+    const int training = mode == 1 || mode == 3;
     std::vector<Dims> dims;
     int pt = 0, pl = 0;
     SK_TRY(infer(net, h, w, pad, dims, &pt, &pl));
@@ -471,6 +472,17 @@ sk_status sknet_plan(sknet_t *net, int32_t n, int32_t h, int32_t w, int32_t pad,
         net->layers[L - 2].k == 1 && net->layers[L - 1].k == 1 && net->layers[L - 2].relu && !net->layers[L - 1].relu &&
         sk::head_supported(net->dtype, dims[L - 2].c, net->layers[L - 2].c_out, net->layers[L - 1].c_out))
         net->fuse_head = true;
+    if (mode == 3) {
+        // the two 1x1 layers and the loss run as one kernel in both directions: their hidden maps are never stored
+        const bool shape_ok = L >= 2 && net->layers[L - 2].kind == SK_CONV && net->layers[L - 1].kind == SK_CONV && net->layers[L - 2].k == 1 &&
+                              net->layers[L - 1].k == 1 && net->layers[L - 2].relu && !net->layers[L - 1].relu;
+        if (!shape_ok || !half || !sk::head_train_supported(net->dtype, dims[L - 2].c, net->layers[L - 2].c_out, net->layers[L - 1].c_out))
+            return fail(SK_EUNSUPPORTED, "plan: mode 3 needs 16-bit storage and a net that ends in 1x1 conv + ReLU, 1x1 conv with at most 48 input maps, "
+                                         "208 hidden maps and 4 classes");
+        if (L >= 3 && net->layers[L - 3].kind == SK_CONV && net->layers[L - 3].relu)
+            return fail(SK_EUNSUPPORTED, "plan: mode 3 needs a pool (or a convolution without ReLU) in front of the head");
+        net->fuse_head = true;
+    }
     net->vpool.assign(L, 0);
     net->pending.assign(L, 0);
     net->pending_head = 0;
@@ -531,6 +543,7 @@ sk_status sknet_plan(sknet_t *net, int32_t n, int32_t h, int32_t w, int32_t pad,
             if (s > scratch) scratch = s;
         }
     }
+    if (training && net->fuse_head) scratch = std::max(scratch, sk::head_train_scratch_floats(dims[L - 2].c, net->layers[L - 2].c_out));
     if (st == SK_OK && net->fuse_head) {
         ConvParams &c1 = net->convs[net->conv_of_layer[L - 2]];
         st = alloc_f(&net->head_w1p, (sk::head_w1_packed_bytes(net->dtype, c1.c_in, c1.c_out) + 3) / 4);
@@ -658,7 +671,23 @@ static sk_status backward_impl(sknet_t *net, const int32_t *labels_dev, float *l
     float *gcur = net->gbuf[0], *gnext = net->gbuf[1];
     const bool half = net->half();
     const int dt = net->dtype;
-    {
+    int top = L - 1;                                   // the layer the walk starts at
+    if (net->fuse_head) {
+        // loss, both 1x1 layers' gradients and the gradient of the head's input in one kernel
+        if (grad_at_stop && stop_layer > L - 3) return fail(SK_EUNSUPPORTED, "this plan keeps no gradient inside the head (plan with mode 1)");
+        const ConvParams &c1 = net->convs[net->conv_of_layer[L - 2]], &c2 = net->convs[net->conv_of_layer[L - 1]];
+        const Dims &in = net->dims[L - 2];
+        const long pixels = (long)n * o.h * o.w;
+        int *counts = reinterpret_cast<int *>(loss_partial);
+        sk::HeadTrainArgs a{};
+        SK_HIP(sk::launch_label_count(labels_dev, pixels, o.c, counts, &a.ncounts, stream));
+        a.x = net->act[L - 2]; a.w1p = net->head_w1p; a.w1 = c1.w_dev; a.b1 = c1.b_dev; a.w2 = c2.w_dev; a.b2 = c2.b_dev;
+        a.labels = labels_dev; a.counts = counts; a.dx = L > 2 ? gcur : nullptr; a.scratch = wgrad_scratch;
+        a.dw1 = c1.dw; a.db1 = c1.db; a.dw2 = c2.dw; a.db2 = c2.db; a.loss = loss_dev;
+        a.dtype = dt; a.n = n; a.c_in = in.c; a.plane = in.h * in.w; a.hidden = c1.c_out; a.classes = c2.c_out;
+        SK_HIP(sk::launch_head_train_bwd(a, wgrad_cap ? wgrad_cap : sk::head_train_scratch_floats(in.c, c1.c_out), stream));
+        top = L - 3;
+    } else {
         const float *logits = (half && net->layers[L - 1].kind != SK_CONV) ? net->logits_f32 : net->act[L];
         float *dz = half ? net->dz_f32 : gcur;
         SK_HIP(sk::launch_softmax_loss_f32(logits, labels_dev, dz, loss_dev, loss_partial, n, o.c, o.h * o.w, stream));
@@ -666,7 +695,7 @@ static sk_status backward_impl(sknet_t *net, const int32_t *labels_dev, float *l
             SK_HIP(sk::launch_relu_mask_f32(dz, net->act[L], o.count(n), stream));
         if (half) SK_HIP(sk::launch_pad_pack_h(dz, gcur, dt, n, o.c, o.h, o.w, 0, 0, o.h, o.w, 0, stream));
     }
-    for (int li = L - 1; li >= 0; --li) {
+    for (int li = top; li >= 0; --li) {
         if (grad_at_stop && li == stop_layer) {
             *grad_at_stop = gcur;
             return SK_OK;
@@ -704,6 +733,8 @@ sk_status sknet_backward_noalloc(sknet_t *net, const int32_t *labels_dev, float 
         return fail(SK_EUNSUPPORTED, "backward_noalloc: the loss needs %zu floats of scratch, the static buffer keeps %zu for it", loss_floats,
                     kStaticLossFloats);
     const size_t cap = kStaticScratchFloats - kStaticLossFloats;
+    if (net->fuse_head && sk::head_train_scratch_floats(net->dims[L - 2].c, net->layers[L - 2].c_out) / 512 > cap)
+        return fail(SK_EUNSUPPORTED, "backward_noalloc: the head's sums do not fit the static buffer");
     for (const auto &c : net->convs) {
         const size_t need = sk::wgrad_min_scratch_floats(c.c_out, c.c_in, c.k);
         if (need > cap)
@@ -787,6 +818,10 @@ sk_status sknet_sgd_step(sknet_t *net, float lr, float momentum, float weight_de
     SK_HIP(sk::launch_sgd_batch_f32(sb, lr, momentum, weight_decay, stream));
     if (net->dtype == SK_F32) SK_HIP(sk::launch_pack_weights_f32_batch(pf, np, stream));
     else SK_HIP(sk::launch_pack_weights_h_batch(ph, np, net->dtype, stream));
+    if (net->fuse_head) {
+        const ConvParams &c1 = net->convs[net->conv_of_layer[(int)net->layers.size() - 2]];
+        SK_HIP(sk::launch_pack_head_w1(c1.w_dev, net->head_w1p, net->dtype, c1.c_out, c1.c_in, stream));
+    }
     return SK_OK;
 }
 
@@ -922,11 +957,11 @@ sk_status sknet_time_backward_step(sknet_t *net, const int32_t *labels_dev, int3
     if (e == hipSuccess) e = hipEventCreate(&e1);
     sk_status st = e == hipSuccess ? SK_OK : fail(SK_EDEVICE, "time_backward_step: %s", hipGetErrorString(e));
     // the error map of the layer (part 2: the loss alone, which is the walk down to the last layer)
-    const int li = part == 2 ? L - 1 : layer_idx;
+    const int li = part == 2 ? (net->fuse_head ? L - 3 : L - 1) : layer_idx;     // (a head in one kernel: the loss part is that kernel)
     if (st == SK_OK) st = backward_impl(net, labels_dev, loss, stream, li, &g, net->loss_partial, net->wgrad_scratch, 0);
     float *other = g == net->gbuf[0] ? net->gbuf[1] : net->gbuf[0];
     auto once = [&]() -> sk_status {
-        if (part == 2) return backward_impl(net, labels_dev, loss, stream, L - 1, &g, net->loss_partial, net->wgrad_scratch, 0);
+        if (part == 2) return backward_impl(net, labels_dev, loss, stream, li, &g, net->loss_partial, net->wgrad_scratch, 0);
         return backward_layer(net, li, g, other, part == 0 ? 1 : 2, stream, net->wgrad_scratch, 0);
     };
     if (st == SK_OK) st = once();              // warm-up

@@ -154,6 +154,11 @@ def test_training_step_half(dtype):
     (9, [(24, 4, 6), (2, 1, 1)], 50, 90),                    # d = 6: 4-byte reads
     (3, [(16, 3, 12), (20, 2, 4), (2, 1, 1)], 60, 100),      # d = 12 and 4: 8-byte reads
     (4, [(8, 4, 1), (72, 4, 8), (2, 1, 1)], 45, 140),        # d = 8: 16-byte reads; 72 maps = several map tiles
+    # 4x4 layers of at most 48 maps take the row-streaming kernel: strips of 64 columns (65 = one full, one of width 1),
+    # input-map tiles of 16 (20 maps = one and a quarter), the widest kernel stride it stages (3d = 63), two chained layers
+    (20, [(48, 4, 3), (2, 1, 1)], 70, 65),
+    (48, [(5, 4, 21), (2, 1, 1)], 90, 63),
+    (1, [(16, 4, 1), (40, 4, 2), (3, 1, 1)], 33, 129),
 ])
 def test_weight_gradient_kernel_strides_half(dtype, c_in, spec, h, w):
     """The 16-bit weight gradient reads its input fragments at the alignment the kernel stride allows:
