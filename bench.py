@@ -223,8 +223,11 @@ def measure_train(torch, B, S, dtype, n, H, W, steps, warmup, first_seed, kernel
         # labels in (count pass), logits + labels in and fp32 gradient out (2 classes); 16-bit storage: the gradient is
         # read once more and written as one 16-byte octet per pixel for the layers below
         loss_bytes = n * ho * wo * (4 + (2 * 4 + 4 + 2 * 4.0) + (0.0 if dtype == "f32" else 2 * 4 + 16))
-        if head_fused:                                                   # labels twice, the head's input in, its gradient out
-            loss_bytes = n * ho * wo * (2 * 4 + 2.0 * esize * f_in_of[len(layers) - 2])
+        head_flops = None
+        if head_fused:
+            # one kernel: h and z recomputed, dx = W1^T dh, dW1 = dh x^T, dW2 = dz h^T (2 FLOP per multiply-add)
+            f1, hid, cls = f_in_of[len(layers) - 2], layers[-2]["f_out"], layers[-1]["f_out"]
+            head_flops = n * ho * wo * 2.0 * (3 * f1 * hid + 2 * hid * cls)
         res.update({
             "parts_ms": parts,
             "step_tflops": round(3.0 * sum(flops.values()) / (res["ms_per_step"] * 1e-3) / 1e12, 2),   # forward + two gradients per conv
@@ -232,7 +235,8 @@ def measure_train(torch, B, S, dtype, n, H, W, steps, warmup, first_seed, kernel
                       "alg_flops": wg_flops / max(wg_n, 1)},
             "pool_fwd_gbs": round(pool_fwd_bytes / (pool_fwd_ms * 1e-3) / 1e9, 1) if pool_fwd_ms else None,
             "pool_bwd_gbs": round(pool_bwd_bytes / (pool_bwd_ms * 1e-3) / 1e9, 1) if pool_bwd_ms else None,
-            "softmax_loss_gbs": round(loss_bytes / (parts["head_loss_backward_ms" if head_fused else "loss_ms"] * 1e-3) / 1e9, 1),
+            "softmax_loss_gbs": None if head_fused else round(loss_bytes / (parts["loss_ms"] * 1e-3) / 1e9, 1),
+            "head_backward_tflops": round(head_flops / (parts["head_loss_backward_ms"] * 1e-3) / 1e12, 1) if head_fused else None,
         })
     net.close()
     return res
@@ -249,7 +253,7 @@ def train_roofline(r, dtype, table, key):
             "step": {"achieved": r["step_tflops"], "frac": round(r["step_tflops"] / peak, 4), "unit": "TFLOP/s",
                      "what": "3 x forward conv FLOPs (forward, data gradient, weight gradient) over the whole training step"},
             "hbm_bound_kernels": {"pool_fwd_gbs": r["pool_fwd_gbs"], "pool_bwd_gbs": r["pool_bwd_gbs"], "softmax_loss_gbs": r["softmax_loss_gbs"],
-                                  "peak_gbs": HBM_PEAK_GBS,
+                                  "peak_gbs": HBM_PEAK_GBS, "head_and_loss_backward_tflops": r.get("head_backward_tflops"),
                                   "frac": {k: (None if r[k] is None else round(r[k] / HBM_PEAK_GBS, 4)) for k in ("pool_fwd_gbs", "pool_bwd_gbs", "softmax_loss_gbs")}}}
 
 
