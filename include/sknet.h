@@ -101,8 +101,10 @@ const char *sknet_last_error(void);
  * n_classes must equal the map count of the last layer.  pad_mode: 0 = reflect (edge sample not
  * repeated), 1 = symmetric (edge sample repeated).  Conv weights start as zeros.
  * SK_EINVAL for bad arguments, SK_ESHAPE for k < 1, d < 1, a pool whose s is neither 1 nor k
- * (or s = k with d != 1), SK_EUNSUPPORTED for k > 15, and for SK_BF16 / SK_F16 nets a conv with
- * k > 4 or (k-1)*d > 64 (the 16-bit kernels stage at most 192 columns per tile row). */
+ * (or s = k with d != 1), SK_EUNSUPPORTED for k > 15, and for SK_BF16 / SK_F16 nets a conv whose
+ * kernel the 16-bit path has no variant for: k <= 4 needs (k-1)*d <= 64; k = 5, 6, 7, 8 and 10 (the
+ * sizes of the paper's SK and USK configuration tables) need a staged row 128 + (4*ceil(k/4) - 1)*d
+ * of at most 256 pixels; k = 9 and k > 10 are fp32 only.  (Training plans in 16-bit storage: k <= 4.) */
 sk_status sknet_create(const sk_layer *layers, int32_t n_layers, int32_t c_in, int32_t n_classes,
                        sk_dtype dtype, int32_t pad_mode, sknet_t **out);
 void sknet_destroy(sknet_t *net);
@@ -167,7 +169,7 @@ sk_status sknet_backward(sknet_t *net, const int32_t *labels_dev, float *loss_de
  * device code (32 MiB per GPU, there from the time the library is loaded on that GPU until the process ends)
  * instead of the plan's own scratch.  The call itself allocates and frees nothing.  The activation-gradient
  * buffers are the plan's, as in sknet_backward.  Limits: SK_EUNSUPPORTED if one padded copy of the net's largest
- * weight gradient, roundup(f_out,16) x roundup(f_in*k*k,16) floats plus 64 x roundup(f_out,8) floats of bias partials,
+ * weight gradient, roundup(f_out,16) x roundup(f_in*k*k,16) floats plus 512 x roundup(f_out,16) floats of bias partials,
  * exceeds 8 Mi - 4096 floats, or if the loss needs more than 4096 floats (it never does: at most 2048).  A weight
  * gradient takes as many private copies as fit, so the summation order -- not the value beyond fp32 rounding --
  * can differ from sknet_backward's.  Every call on one GPU shares that GPU's buffer, whose contents are whatever
@@ -241,8 +243,8 @@ void unet_destroy(unet_t *net);
  * 2, 1 times base_ch along the path.  692 x 692 in -> 512 x 512 out.  Parameter order: "conv1",
  * "conv2", "conv3", "conv4", "conv5", "ip1", "ip2", "up1" ([4b][2b][2][2]), "conv7", "conv8",
  * "ip3".  Stages for unet_get_activation: "conv2", "pool1", "conv3", "pool2", "conv4", "pool3",
- * "conv5", "pool4", "ip1", "ip2", "up1", "conv8", "logits".  dtype: SK_F32 only (the 6x6 and 8x8
- * kernels have no 16-bit variant: SK_EUNSUPPORTED).  Host only. */
+ * "conv5", "pool4", "ip1", "ip2", "up1", "conv8", "logits".  dtype: SK_F32, or SK_BF16 / SK_F16 for the
+ * forward pass (base_ch a multiple of 8; training plans are fp32).  Host only. */
 sk_status usknet_create(int32_t c_in, int32_t n_classes, int32_t base_ch, sk_dtype dtype, unet_t **out);
 
 /* Parameter tensors, in forward order: per level i = 0..depth "down{i}a", "down{i}b"; then per
