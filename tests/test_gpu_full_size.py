@@ -81,13 +81,16 @@ def test_c3_forward_1024_sampled_windows(dtype, n):
     print(dtype, "%d windows: logits rel err %.3e, probabilities abs err %.3e" % (len(places), worst_z, worst_p), flush=True)
 
 
-def test_c4_bf16_training_step_512():
+@pytest.mark.parametrize("fused_head,n,size", [(False, 1, 512), (True, 1, 512), (True, 2, 1024)])
+def test_c4_bf16_training_step_512(fused_head, n, size):
+    """The training step at the benchmark's sizes and in its plan modes: layer by layer (mode 1), and with the head
+    and the loss as one kernel per direction (mode 3, what bench.py times), also on 1024^2 images."""
     layers = S.sknet_layers()
     ws, bs = S.he_normal_weights(layers, 1, 1001)
-    img = S.em_like_batch(1, 512, 512, 2)
-    labels = S.binary_labels(1, 512, 512, 2004)
+    img = S.em_like_batch(n, size, size, 2)
+    labels = S.binary_labels(n, size, size, 2004)
     net = make_net(layers, ws, bs, "bf16")
-    net.plan(1, 512, 512, pad=True, training=True)
+    net.plan(n, size, size, pad=True, training=True, fused_head=fused_head)
     timg, tlab = torch.from_numpy(img).cuda(), torch.from_numpy(labels).cuda()
     prob = net.forward(timg).cpu().numpy()
     loss = net.backward(tlab)
@@ -96,8 +99,9 @@ def test_c4_bf16_training_step_512():
     ref_prob, acts, ams = ON.sknet_forward(img, layers, ow, ob, keep=True)
     ref_loss, dws, dbs, _ = ON.sknet_backward(layers, ow, acts, ams, labels)
     assert np.abs(prob - ref_prob).max() <= HALF_TOL
-    logits = net.get_activation(len(layers) - 1)
-    assert np.abs(logits - acts[-1]).max() <= HALF_TOL * np.abs(acts[-1]).max()
+    if not fused_head:                                   # the one-kernel head keeps no logits
+        logits = net.get_activation(len(layers) - 1)
+        assert np.abs(logits - acts[-1]).max() <= HALF_TOL * np.abs(acts[-1]).max()
     assert abs(loss.item() - ref_loss) <= HALF_TOL * abs(ref_loss)
     for i in range(net.num_convs()):
         dw, db = net.get_grad(i)
