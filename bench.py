@@ -11,7 +11,7 @@ A step is one such pass over one synthetic image that is resident in HBM before 
                      kernels are bound by HBM, not by their launch)
 --workload c5 / c5bf16 : U-Net forward on one 572x572 image (configs[4]) in fp32 / bf16
 --workload papersk / paperskbf16, usk / uskbf16 : the paper's own SK-Net (128^2 tile) and USK-Net (692^2), fp32 / bf16
---workload sk3d / sk3dtrain : 3-D SK net on a stack of 81 sections of 145x145 (Section 5.2.2), fp32
+--workload sk3d / sk3dbf16 / sk3dtrain : 3-D SK net on a stack of 81 sections of 145x145 (Section 5.2.2), fp32 (bf16: forward)
 --workload unettrain / usktrain : U-Net / USK-Net training step, fp32
 --workload copy    : only the streaming-copy probe on 2 x 1 GiB (the known-size kernel that the HBM
                      byte counters of a profiler run are calibrated against)
@@ -356,14 +356,14 @@ def measure_paper_sknet(torch, B, S, steps, warmup, dtype="f32"):
             "paper_pixels_per_s": {"W9100 OpenCL": 59513, "GTX 980 CUDA": 85460}}
 
 
-def measure_sknet3d(torch, B, S, steps, warmup):
+def measure_sknet3d(torch, B, S, steps, warmup, dtype="f32"):
     """3-D SK net forward (Section 5.2.2): the Algorithm-1 conversion of an 18^3 sliding-window net
     (conv k3, pool, conv k3, pool, inner products 128 and 64; context 17) on a stack of 81 synthetic
-    145 x 145 sections -> 64 x 128 x 128 labelled voxels, fp32."""
+    145 x 145 sections -> 64 x 128 x 128 labelled voxels, fp32 or 16-bit storage."""
     import numpy as np
     layers = S.sknet3d_layers(classes=2)
     ws, bs = S.he_normal_weights3d(layers, 1, 1100)
-    net = B.SKNet3D(layers, 1, 2)
+    net = B.SKNet3D(layers, 1, 2, dtype=dtype)
     for i, (w, b) in enumerate(zip(ws, bs)):
         net.set_weights(i, w, b)
     dz, h, w = 81, 145, 145
@@ -484,7 +484,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", choices=["c2", "c3", "c4", "c3train", "c5", "c5bf16", "usk", "uskbf16", "papersk", "paperskbf16", "sk3d", "sk3dtrain",
+    ap.add_argument("--workload", choices=["c2", "c3", "c4", "c3train", "c5", "c5bf16", "usk", "uskbf16", "papersk", "paperskbf16", "sk3d", "sk3dbf16", "sk3dtrain",
                                            "unettrain", "usktrain", "copy"], default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
@@ -532,14 +532,14 @@ def main():
         print(json.dumps(out))
         return
 
-    if args.workload in ("usk", "uskbf16", "papersk", "paperskbf16", "sk3d", "sk3dtrain"):
+    if args.workload in ("usk", "uskbf16", "papersk", "paperskbf16", "sk3d", "sk3dbf16", "sk3dtrain"):
         wdt = "bf16" if args.workload.endswith("bf16") else "f32"
         if args.workload == "sk3dtrain":
             r = measure_sknet3d_train(torch, B, S, args.steps, args.warmup)
             px, what = r["labelled_voxels_per_s"], "3-D SK net training step, 81x145x145 -> 64x128x128 labels, fp32: forward, masked softmax loss, backward, SGD; value = labelled voxels per second"
-        elif args.workload == "sk3d":
-            r = measure_sknet3d(torch, B, S, args.steps, args.warmup)
-            px, what = r["labelled_voxels_per_s"], "3-D SK net forward, 81x145x145 -> 2x64x128x128 (context 17), fp32; value = labelled voxels per second"
+        elif args.workload in ("sk3d", "sk3dbf16"):
+            r = measure_sknet3d(torch, B, S, args.steps, args.warmup, wdt)
+            px, what = r["labelled_voxels_per_s"], "3-D SK net forward, 81x145x145 -> 2x64x128x128 (context 17), %s; value = labelled voxels per second" % wdt
         elif args.workload in ("usk", "uskbf16"):
             r = measure_usknet(torch, B, S, args.steps, args.warmup, wdt)
             px, what = r["labelled_pixels_per_s"], "USK-Net forward 1x3x692x692 -> 2x512x512, %s (the paper's USK configuration table)" % wdt
@@ -603,6 +603,7 @@ def main():
         extras["usknet_692_f32_forward"] = measure_usknet(torch, B, S, 5, 2)
         extras["usknet_692_bf16_forward"] = measure_usknet(torch, B, S, 5, 2, "bf16")
         extras["sknet3d_81x145x145_f32_forward"] = measure_sknet3d(torch, B, S, 5, 2)
+        extras["sknet3d_81x145x145_bf16_forward"] = measure_sknet3d(torch, B, S, 5, 2, "bf16")
         extras["sknet3d_81x145x145_f32_train_step"] = measure_sknet3d_train(torch, B, S, 3, 1)
         extras["unet_572_f32_train_step"] = measure_unet_train(torch, B, S, "unet", 3, 1)
         extras["usknet_692_f32_train_step"] = measure_unet_train(torch, B, S, "usk", 3, 1)

@@ -309,13 +309,19 @@ sk_status unet_get_activation(unet_t *net, const char *stage, float *nchw_host, 
  *   SK_CONV    : Y[o,z,y,x] = b[o] + sum_{c,a,i,j} W[o,c,a,i,j] X[c, z+a*d, y+i*d, x+j*d], optional ReLU;
  *   SK_MAXPOOL : Y[c,z,y,x] = max_{a,i,j<k} X[c, s*z+a*d, s*y+i*d, s*x+j*d]  (s = 1, or s = k with d = 1);
  * every layer shrinks each axis by (k-1)*d (Algorithm 1 holds per axis); a per-voxel softmax over the maps
- * of the last layer follows (forward; sknet3d_backward adds the training pass).  fp32 only, one volume per call, no padding: the caller's volume contains the
+ * of the last layer follows (forward; sknet3d_backward adds the training pass).  One volume per call, no padding: the caller's volume contains the
  * context v, the output is (dz - v) x (h - v) x (w - v).  Create is host only; errors as sknet_create.
  *
  * Layout of every volume that crosses this interface (input, probabilities, activations): SLICE-MAJOR,
  * [depth][maps][height][width] fp32 -- a stack of multi-map 2-D sections; for one input map that is the
  * plain [depth][height][width] image stack.  Weights are [f_out][f_in][k][k][k] (depth, height, width taps). */
 sk_status sknet3d_create(const sk_layer *layers, int32_t n_layers, int32_t c_in, int32_t n_classes, sknet3d_t **out);
+/* The same with the storage type of the activations: SK_F32 (what sknet3d_create builds), or SK_BF16 / SK_F16 for
+ * the forward pass (inference plans, modes 0 and 2): activations in the 16-bit slice-major octet layout inside the
+ * library, fp32 accumulation, fp32 volumes and probabilities at this interface as before; the net must end in a
+ * convolution.  SK_EUNSUPPORTED for a convolution the 16-bit kernels have no variant for (see sknet_create);
+ * sknet3d_plan refuses a training plan for such a net. */
+sk_status sknet3d_create_dtype(const sk_layer *layers, int32_t n_layers, int32_t c_in, int32_t n_classes, sk_dtype dtype, sknet3d_t **out);
 void sknet3d_destroy(sknet3d_t *net);
 /* *v = sum of (k-1)*d over the layers (SK_ESHAPE if a pool has s != 1). */
 sk_status sknet3d_context(const sknet3d_t *net, int32_t *v);

@@ -79,6 +79,7 @@ _SIGS = {
     "unet_sgd_step": [_vp, C.c_float, C.c_float, C.c_float, _vp],
     "unet_get_weights": [_vp, _i32, _fp, _fp],
     "sknet3d_create": [C.POINTER(SkLayer), _i32, _i32, _i32, C.POINTER(_vp)],
+    "sknet3d_create_dtype": [C.POINTER(SkLayer), _i32, _i32, _i32, _i32, C.POINTER(_vp)],
     "sknet3d_context": [_vp, _ip],
     "sknet3d_infer_shapes": [_vp, _i32, _i32, _i32, _ip],
     "sknet3d_num_convs": [_vp, _ip],
@@ -464,10 +465,10 @@ class SKNet3D:
     """Owner of one sknet3d_t handle; methods are the C entry points without the `sknet3d_` prefix.
     Volumes are slice-major: [depth][maps][height][width]."""
 
-    def __init__(self, layers, c_in, n_classes):
+    def __init__(self, layers, c_in, n_classes, dtype="f32"):
         self.layers = list(layers)
         self._h = _vp()
-        _check(lib.sknet3d_create(layers_to_c(layers), len(layers), c_in, n_classes, C.byref(self._h)))
+        _check(lib.sknet3d_create_dtype(layers_to_c(layers), len(layers), c_in, n_classes, DTYPES[dtype], C.byref(self._h)))
         self.c_in, self.n_classes = c_in, n_classes
         self._plan = None
 

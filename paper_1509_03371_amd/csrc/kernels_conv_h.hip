@@ -155,6 +155,9 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
 
     // chunk-invariant column bookkeeping of this lane
     const long plane = (long)a.H * a.W;
+    // octet plane of input octet o of image b (slices of a volume as images: overlapping images, octets in groups)
+    const int xb8 = a.xb8 > 0 ? a.xb8 : a.c8_in;
+    auto in_plane = [&](int b, int o) -> long { return (long)b * xb8 + o + (a.grp8 > 0 ? (o / a.grp8) * a.skip8 : 0); };
     uint4v xr[RU][VU];
     uint4v wr[WU];
 
@@ -170,7 +173,7 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
             o = o < a.c8_in ? o : a.c8_in - 1;
             int gy = gy0 + r * d;
             gy = gy < 0 ? 0 : (gy >= a.H ? a.H - 1 : gy);
-            const uint4v *row = reinterpret_cast<const uint4v *>(a.x) + ((long)p.b * a.c8_in + o) * plane + (long)gy * a.W;
+            const uint4v *row = reinterpret_cast<const uint4v *>(a.x) + in_plane(p.b, o) * plane + (long)gy * a.W;
 #pragma unroll
             for (int v = 0; v < VU; ++v) {
                 int gx = gx0 + lane + 64 * v;
@@ -522,6 +525,9 @@ __global__ __launch_bounds__(CH_THREADS + 64 * NP) void conv_h_ring_kernel(ConvH
     const int Wmem = a.W + hd;                                 // columns of an input row in memory
     const long plane_bytes_in = (long)a.H * Wmem * 16;
     const char *zeros = reinterpret_cast<const char *>(a.zeros);
+    // octet plane of input octet o of image b (slices of a volume as images: overlapping images, octets in groups)
+    const int xb8 = a.xb8 > 0 ? a.xb8 : a.c8_in;
+    auto in_plane = [&](int b, int o) -> long { return (long)b * xb8 + o + (a.grp8 > 0 ? (o / a.grp8) * a.skip8 : 0); };
 
     // Loads of chunk `ch` of the tile at `p` into ring stage `st`.  Exactly L load instructions for
     // this wave, whatever the position (the pipeline counts them): a row or a 64-column group that lies
@@ -548,7 +554,7 @@ __global__ __launch_bounds__(CH_THREADS + 64 * NP) void conv_h_ring_kernel(ConvH
             const int o = ch * OC + oc;
             const int gy = gy0 + r * d;
             const bool rowok = o < a.c8_in && gy >= 0 && gy < a.H;
-            const char *rowbase = reinterpret_cast<const char *>(a.x) + ((long)p.b * a.c8_in + (rowok ? o : 0)) * plane_bytes_in +
+            const char *rowbase = reinterpret_cast<const char *>(a.x) + in_plane(p.b, rowok ? o : 0) * plane_bytes_in +
                                   (long)(rowok ? gy : 0) * Wmem * 16;
 #pragma unroll
             for (int v = 0; v < VUE; ++v) {
@@ -917,7 +923,7 @@ __global__ __launch_bounds__(CH_THREADS + 64 * NP) void conv_h_ring_kernel(ConvH
                     int o = ch * OC + oc, gy = gy0 + rr * d;
                     o = o < a.c8_in ? o : a.c8_in - 1;
                     gy = gy < a.H ? gy : a.H - 1;
-                    const uint4v *row = reinterpret_cast<const uint4v *>(reinterpret_cast<const char *>(a.x) + ((long)p.b * a.c8_in + o) * plane_bytes_in +
+                    const uint4v *row = reinterpret_cast<const uint4v *>(reinterpret_cast<const char *>(a.x) + in_plane(p.b, o) * plane_bytes_in +
                                                                          (long)gy * Wmem * 16);
 #pragma unroll
                     for (int v = 0; v < VUE; ++v) {
@@ -1312,6 +1318,8 @@ bool conv_h_supported(int k, int d, int gemm_m)
 hipError_t launch_conv_h(const ConvHArgs &a, hipStream_t stream)
 {
     if (!conv_h_supported(a.k, a.d) || a.Ho < 1 || a.Wo < 1 || a.c8_in < 1 || a.c_out < 1) return hipErrorInvalidValue;
+    if (a.xb8 < 0 || a.grp8 < 0 || a.skip8 < 0 || (a.grp8 > 0 && a.c8_in % a.grp8 != 0) || (a.grp8 == 0 && a.skip8 != 0)) return hipErrorInvalidValue;
+    if ((a.xb8 || a.grp8) && (a.vpool || a.hd || a.in_off)) return hipErrorInvalidValue;      // slices as images: plain forward launches only
     if ((a.vpool || a.hd) && (a.mt > 0 && a.mt != conv_h_mt(a.c_out, a.k))) return hipErrorInvalidValue;
     if ((a.vpool || a.hd) && !conv_h_pool_fusable(a.k, a.d, a.c_out, a.c8_in, a.Ho, a.hd)) return hipErrorInvalidValue;
     if (a.tap_maps != 0 && (a.tap_maps < 16 || a.tap_maps % 16 != 0 || a.c_out != 4 * a.tap_maps || a.mask || a.out_f32 || a.oy_mul != 2 ||

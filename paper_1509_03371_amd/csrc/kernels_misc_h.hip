@@ -262,6 +262,58 @@ hipError_t launch_maxpool_h(const void *x, void *y, void *tap, int dtype, long p
     return hipGetLastError();
 }
 
+// ---- 3-D max pooling on the slice-major octet layout [D][C8][H][W][8] (Section 5.2.2) -----------------------
+// Y[z][o8][y][x] = max over the k^3 taps X[s z + a d][o8][s y + i d][s x + j d]; forward only (no winner codes).
+// grid: x = column blocks, y = output row, z = (output slice, octet)
+template <int DT>
+__global__ void maxpool3d_h_kernel(const uint4v *x, uint4v *y, int C8, int H, int W, int Ho, int Wo, int k, int d, int s)
+{
+    const int xx = blockIdx.x * blockDim.x + threadIdx.x, yy = blockIdx.y;
+    if (xx >= Wo) return;
+    const int zo = blockIdx.z / C8, o8 = blockIdx.z - zo * C8;
+    const long plane = (long)H * W;
+    const uint4v *src = x + ((long)s * zo * C8 + o8) * plane + (long)s * yy * W + (long)s * xx;
+    const uint4v first = src[0];
+    float best[8];
+    unsigned bits[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        bits[e] = elem16(first, e);
+        best[e] = up16<DT>(bits[e]);
+    }
+    for (int a = 0; a < k; ++a)
+        for (int i = 0; i < k; ++i)
+            for (int j = 0; j < k; ++j) {
+                const uint4v u = src[(long)a * d * C8 * plane + (long)i * d * W + j * d];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const unsigned b16 = elem16(u, e);
+                    const float v = up16<DT>(b16);
+                    if (v > best[e]) {
+                        best[e] = v;
+                        bits[e] = b16;
+                    }
+                }
+            }
+    y[((long)blockIdx.z * Ho + yy) * Wo + xx] =
+        uint4v{bits[0] | (bits[1] << 16), bits[2] | (bits[3] << 16), bits[4] | (bits[5] << 16), bits[6] | (bits[7] << 16)};
+}
+
+hipError_t launch_maxpool3d_h(const void *x, void *y, int dtype, int C, int D, int H, int W, int Do, int Ho, int Wo, int k, int d, int s,
+                              hipStream_t stream)
+{
+    const int C8 = (C + 7) / 8;
+    if (Ho > 65535 || (long)Do * C8 > 65535 || (dtype != 1 && dtype != 2) || D < 1) return hipErrorInvalidValue;
+    const dim3 grid((Wo + 255) / 256, Ho, (unsigned)(Do * C8));
+    if (dtype == 1)
+        hipLaunchKernelGGL(maxpool3d_h_kernel<1>, grid, dim3(256), 0, stream, static_cast<const uint4v *>(x), static_cast<uint4v *>(y), C8, H, W, Ho,
+                           Wo, k, d, s);
+    else
+        hipLaunchKernelGGL(maxpool3d_h_kernel<2>, grid, dim3(256), 0, stream, static_cast<const uint4v *>(x), static_cast<uint4v *>(y), C8, H, W, Ho,
+                           Wo, k, d, s);
+    return hipGetLastError();
+}
+
 // MergeCrop's second operand on octets (Section 5.3.1): dst[b][o8_off + o][y][x] = src[b][o][y + cy][x + cx]
 __global__ void crop_copy_h_kernel(const uint4v *__restrict__ src, uint4v *__restrict__ dst, int n, int c8, int Hs, int Ws,
                                    int c8_total, int o8_off, int H, int W, int cy, int cx)

@@ -79,6 +79,10 @@ struct ConvHArgs {
     int vpool, hd;
     const void *zeros;    // CONV_H_ZERO_BYTES of zeros in device memory, read in place of samples outside the image (the launcher
                           // allocates nothing: the owner of the plan provides the page)
+    // Slices of a volume as images (3-D layers on the slice-major layout): xb8 > 0: image b starts xb8 octet planes after
+    // image b - 1 (0: c8_in, images do not overlap); grp8 > 0: the c8_in input octets come in groups of grp8 with skip8 more
+    // octet planes between two groups (the d - 1 slices between two depth taps)
+    int xb8, grp8, skip8;
     // filled in by the launcher
     int m_tiles, mgroups, nchunks, xtiles, tiles_hi, tiles_lo, rem, ytiles_total, total_tiles, ypitch;
 };
@@ -194,6 +198,9 @@ hipError_t launch_maxpool_bwd_f32(const float *dy, const uint8_t *tap, const flo
                                   hipStream_t stream);
 // 3-D pool on the slice-major layout X[D][C][H][W] -> Y[Do][C][Ho][Wo]; k, d, s act on the three axes alike;
 // tap (optional, k <= 6) receives the winner's code (a*k + i)*k + j, first maximum in (a, i, j) order
+// the same on the 16-bit slice-major octet layout [D][ceil(C/8)][H][W][8], forward only
+hipError_t launch_maxpool3d_h(const void *x, void *y, int dtype, int C, int D, int H, int W, int Do, int Ho, int Wo, int k, int d, int s,
+                              hipStream_t stream);
 hipError_t launch_maxpool3d_f32(const float *x, float *y, uint8_t *tap, int C, int D, int H, int W, int Do, int Ho, int Wo, int k,
                                 int d, int s, hipStream_t stream);
 // gradient of the s = 1 pool from its winner codes; relu_src (optional, like dx) zeroes the result where it is <= 0

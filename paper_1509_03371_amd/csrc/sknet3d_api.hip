@@ -46,6 +46,7 @@ struct Conv3 {
     std::vector<float> w, b;           // host master, [c_out][c_in][k][k][k] and [c_out]
     float *w_dev = nullptr, *b_dev = nullptr;   // device master (b_dev: n_pad entries, zero padded)
     std::vector<TapRun> fwd, bwd;      // bwd: runs over the flipped taps, for the data gradient
+    void *wp16 = nullptr;              // 16-bit nets: the kernel as a 2-D convolution over k * 8*ceil(c_in/8) input maps, packed MFMA fragments
     float *dw = nullptr, *db = nullptr, *vw = nullptr, *vb = nullptr, *dw_tap = nullptr;
     // weight gradient of all depth taps in one launch: k > 1 and (d = 1, the tapped slices adjacent, or a power-of-two
     // map count, which the kernel's grouped addressing needs)
@@ -71,6 +72,7 @@ std::vector<TapRun> make_runs(int k, int d, int maps)
 void release_conv3(Conv3 &c)
 {
     free_dev(c.w_dev); free_dev(c.b_dev);
+    if (c.wp16) { (void)hipFree(c.wp16); c.wp16 = nullptr; }
     for (auto &r : c.fwd) free_dev(r.wp);
     for (auto &r : c.bwd) free_dev(r.wp);
     c.bwd.clear();
@@ -95,6 +97,27 @@ sk_status upload_conv3(Conv3 &c, hipStream_t stream)
     SK_HIP(hipMemcpyAsync(c.b_dev, bp.data(), sizeof(float) * c.n_pad, hipMemcpyHostToDevice, stream));
     SK_TRY(repack_conv3(c, stream));
     SK_HIP(hipStreamSynchronize(stream));
+    return SK_OK;
+}
+
+// 16-bit storage: depth tap a of input map c becomes input map a * 8*ceil(c_in/8) + c of a 2-D convolution (the maps an
+// octet pads are zero), packed as the 2-D 16-bit kernels want it
+sk_status upload_conv3_h(Conv3 &c, int dtype)
+{
+    const int c8 = (c.c_in + 7) / 8, cin2 = c.k * c8 * 8, kk = c.k * c.k;
+    std::vector<float> w2((size_t)c.c_out * cin2 * kk, 0.f);
+    for (int o = 0; o < c.c_out; ++o)
+        for (int ci = 0; ci < c.c_in; ++ci)
+            for (int a = 0; a < c.k; ++a)
+                std::memcpy(&w2[((size_t)o * cin2 + (size_t)a * c8 * 8 + ci) * kk], &c.w[(((size_t)o * c.c_in + ci) * c.k + a) * kk], sizeof(float) * kk);
+    float *tmp = nullptr;
+    SK_TRY(alloc_f(&tmp, (long)w2.size()));
+    hipError_t e = hipMemcpy(tmp, w2.data(), sizeof(float) * w2.size(), hipMemcpyHostToDevice);
+    if (!c.wp16 && e == hipSuccess) e = hipMalloc(&c.wp16, sizeof(unsigned short) * (size_t)sk::packed_h_elems(c.c_out, c.k * c8, c.k));
+    if (e == hipSuccess) e = sk::launch_pack_weights_h(tmp, c.wp16, dtype, c.c_out, cin2, c.k, 0, 0, nullptr);
+    if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
+    free_dev(tmp);
+    if (e != hipSuccess) return fail(SK_EDEVICE, "packing 16-bit weights: %s", hipGetErrorString(e));
     return SK_OK;
 }
 
@@ -127,7 +150,7 @@ sk_status alloc_conv3(Conv3 &c, bool training, bool needs_dgrad)
 
 struct sknet3d {
     std::vector<sk_layer> layers;
-    int c_in = 0, n_classes = 0;
+    int c_in = 0, n_classes = 0, dtype = SK_F32;
     std::vector<Conv3> convs;
     std::vector<int> conv_of_layer;
     bool planned = false, training = false, forward_done = false, backward_done = false;
@@ -136,9 +159,10 @@ struct sknet3d {
     std::vector<float *> act;      // act[0]: the training plan's copy of the volume, else unused
     std::vector<uint8_t *> tap;    // per layer: winner codes of the pools of a training plan
     bool fuse_head = false;        // last two 1x1x1 convolutions + softmax as one kernel
-    float *head_w1p = nullptr;
+    float *head_w1p = nullptr, *zero_page = nullptr;
     float *gbuf[2] = {nullptr, nullptr}, *loss_partial = nullptr, *wgrad_scratch = nullptr;
     hipStream_t last_stream = nullptr;
+    bool half() const { return dtype != SK_F32; }
     const float *last_volume = nullptr;
 
     void release_plan()
@@ -150,7 +174,7 @@ struct sknet3d {
             t = nullptr;
         }
         tap.clear();
-        free_dev(head_w1p); free_dev(gbuf[0]); free_dev(gbuf[1]); free_dev(loss_partial); free_dev(wgrad_scratch);
+        free_dev(head_w1p); free_dev(zero_page); free_dev(gbuf[0]); free_dev(gbuf[1]); free_dev(loss_partial); free_dev(wgrad_scratch);
         for (auto &c : convs) release_conv3(c);
         planned = training = forward_done = backward_done = false;
         fuse_head = false;
@@ -224,6 +248,30 @@ sk_status run_layer3(sknet3d *net, int li, hipStream_t stream)
     const Dims3 &in = net->dims[li], &out = net->dims[li + 1];
     const float *x = li == 0 ? net->last_volume : net->act[li];
     float *y = net->act[li + 1];
+    if (net->half()) {
+        // 16-bit storage, slice-major octet layout: act[0] holds the converted volume
+        const int dt = net->dtype, c8 = (in.c + 7) / 8;
+        if (l.kind == SK_MAXPOOL) {
+            SK_HIP(sk::launch_maxpool3d_h(net->act[li], y, dt, in.c, in.dz, in.h, in.w, out.dz, out.h, out.w, l.k, l.d, l.s, stream));
+            return SK_OK;
+        }
+        // one 2-D launch: the output slices are its images (one input slice apart), the (depth tap, octet) pairs its input octets
+        const Conv3 &cv = net->convs[net->conv_of_layer[li]];
+        const bool last = li == (int)net->layers.size() - 1;        // the last convolution leaves fp32 logits
+        sk::ConvHArgs a{};
+        a.zeros = net->zero_page;
+        a.x = net->act[li]; a.wp = cv.wp16; a.bias = cv.b_dev; a.mask = nullptr; a.y = y; a.dtype = dt;
+        a.n = out.dz; a.c8_in = l.k * c8; a.H = in.h; a.W = in.w;
+        a.c_out = out.c; a.c8_out = (out.c + 7) / 8;
+        a.k = l.k; a.d = l.d; a.in_off = 0; a.Ho = out.h; a.Wo = out.w; a.relu = l.relu; a.out_f32 = last ? 1 : 0;
+        a.c8_out_total = (out.c + 7) / 8; a.o8_off = 0; a.OH = out.h; a.OW = out.w;
+        a.oy_mul = 1; a.oy_off = 0; a.ox_mul = 1; a.ox_off = 0;
+        a.mt = 0;
+        a.xb8 = c8;
+        if (l.k > 1 && l.d > 1) { a.grp8 = c8; a.skip8 = (l.d - 1) * c8; }
+        SK_HIP(sk::launch_conv_h(a, stream));
+        return SK_OK;
+    }
     if (l.kind == SK_MAXPOOL) {
         SK_HIP(sk::launch_maxpool3d_f32(x, y, net->tap[li], in.c, in.dz, in.h, in.w, out.dz, out.h, out.w, l.k, l.d, l.s, stream));
         return SK_OK;
@@ -245,12 +293,18 @@ extern "C" {
 
 sk_status sknet3d_create(const sk_layer *layers, int32_t n_layers, int32_t c_in, int32_t n_classes, sknet3d_t **out)
 {
+    return sknet3d_create_dtype(layers, n_layers, c_in, n_classes, SK_F32, out);
+}
+
+sk_status sknet3d_create_dtype(const sk_layer *layers, int32_t n_layers, int32_t c_in, int32_t n_classes, sk_dtype dtype, sknet3d_t **out)
+{
     if (!out) return fail(SK_EINVAL, "create: out is null");
     *out = nullptr;
     if (!layers || n_layers < 1 || c_in < 1 || n_classes < 1) return fail(SK_EINVAL, "create: bad arguments");
+    if (dtype != SK_F32 && dtype != SK_BF16 && dtype != SK_F16) return fail(SK_EINVAL, "create: unknown dtype");
     sknet3d *net = new (std::nothrow) sknet3d;
     if (!net) return fail(SK_ENOMEM, "create: out of host memory");
-    net->c_in = c_in; net->n_classes = n_classes;
+    net->c_in = c_in; net->n_classes = n_classes; net->dtype = dtype;
     int maps = c_in;
     for (int i = 0; i < n_layers; ++i) {
         const sk_layer &l = layers[i];
@@ -262,6 +316,8 @@ sk_status sknet3d_create(const sk_layer *layers, int32_t n_layers, int32_t c_in,
         else if (l.kind == SK_MAXPOOL && !(l.s == 1 || (l.s == l.k && l.d == 1)))
             bad = fail(SK_ESHAPE, "layer %d: pool needs s = 1, or s = k with d = 1", i);
         else if (maps > 65535) bad = fail(SK_EUNSUPPORTED, "layer %d: more than 65535 maps", i);
+        else if (dtype != SK_F32 && l.kind == SK_CONV && !sk::conv_h_supported(l.k, l.d, l.c_out))
+            bad = fail(SK_EUNSUPPORTED, "layer %d: no 16-bit convolution kernel for k = %d, d = %d, %d maps", i, l.k, l.d, l.c_out);
         if (bad != SK_OK) {
             delete net;
             return bad;
@@ -349,8 +405,9 @@ sk_status sknet3d_set_weights(sknet3d_t *net, int32_t conv_idx, const float *w_h
     if (!b_host)   // keep the device's current biases (an SGD step may have changed them)
         SK_HIP(hipMemcpy(c.b.data(), c.b_dev, sizeof(float) * c.c_out, hipMemcpyDeviceToHost));
     SK_TRY(upload_conv3(c, nullptr));
+    if (net->half()) SK_TRY(upload_conv3_h(c, net->dtype));
     if (net->fuse_head && conv_idx == (int)net->convs.size() - 2) {
-        SK_HIP(sk::launch_pack_head_w1(c.w_dev, net->head_w1p, SK_F32, c.c_out, c.c_in, nullptr));
+        SK_HIP(sk::launch_pack_head_w1(c.w_dev, net->head_w1p, net->dtype, c.c_out, c.c_in, nullptr));
         SK_HIP(hipStreamSynchronize(nullptr));
     }
     return SK_OK;
@@ -376,9 +433,11 @@ sk_status sknet3d_plan(sknet3d_t *net, int32_t dz, int32_t h, int32_t w, int32_t
     SK_TRY(check3(net));
     if (mode < 0 || mode > 2) return fail(SK_EINVAL, "plan: mode must be 0 (inference), 1 (training) or 2 (inference, every layer kept)");
     const bool training = mode == 1;
+    if (training && net->half()) return fail(SK_EUNSUPPORTED, "plan: 3-D training runs in fp32 storage only");
     std::vector<Dims3> dims;
     SK_TRY(infer3(net, dz, h, w, dims));
     const int L = (int)net->layers.size();
+    const bool half = net->half();
     for (int i = 0; i <= L; ++i)
         if (dims[i].dz > 65535 || dims[i].h > 65535 || dims[i].count() >= (1L << 40))
             return fail(SK_EUNSUPPORTED, "plan: volume too large");
@@ -398,14 +457,17 @@ sk_status sknet3d_plan(sknet3d_t *net, int32_t dz, int32_t h, int32_t w, int32_t
     net->tap.assign(L, nullptr);
     net->fuse_head = mode == 0 && L >= 2 && net->layers[L - 2].kind == SK_CONV && net->layers[L - 1].kind == SK_CONV &&
                      net->layers[L - 2].k == 1 && net->layers[L - 1].k == 1 && net->layers[L - 2].relu && !net->layers[L - 1].relu &&
-                     sk::head_supported(SK_F32, dims[L - 2].c, net->layers[L - 2].c_out, net->layers[L - 1].c_out);
+                     sk::head_supported(net->dtype, dims[L - 2].c, net->layers[L - 2].c_out, net->layers[L - 1].c_out);
     sk_status st = SK_OK;
     long max_grad = 0;   // largest gradient buffer: an activation plus the zero slices around it
     size_t scratch = 0;
-    for (int i = training ? 0 : 1; i <= L && st == SK_OK; ++i) {
+    for (int i = (training || half) ? 0 : 1; i <= L && st == SK_OK; ++i) {
         if (net->fuse_head && i >= L - 1) continue;
-        st = alloc_f(&net->act[i], dims[i].count());
+        // 16-bit storage: octets (counted in floats), but for the logits of a last convolution, which stay fp32
+        const bool f32 = !half || (i == L && net->layers[L - 1].kind == SK_CONV);
+        st = alloc_f(&net->act[i], f32 ? dims[i].count() : (long)dims[i].dz * ((dims[i].c + 7) / 8) * dims[i].h * dims[i].w * 4);
     }
+    if (st == SK_OK && half) st = alloc_zero_page(&net->zero_page);
     for (int i = 0; i < L && st == SK_OK && training; ++i) {
         const sk_layer &l = net->layers[i];
         const long padded = dims[i + 1].count() + 2L * grad_pad(net, i) * dims[i + 1].slice();
@@ -425,12 +487,13 @@ sk_status sknet3d_plan(sknet3d_t *net, int32_t dz, int32_t h, int32_t w, int32_t
         Conv3 &c = net->convs[net->conv_of_layer[i]];
         st = alloc_conv3(c, training, i > 0);
         if (st == SK_OK) st = upload_conv3(c, nullptr);
+        if (st == SK_OK && half) st = upload_conv3_h(c, net->dtype);
     }
     if (st == SK_OK && net->fuse_head) {
         Conv3 &c1 = net->convs[net->conv_of_layer[L - 2]];
-        st = alloc_f(&net->head_w1p, (sk::head_w1_packed_bytes(SK_F32, c1.c_in, c1.c_out) + 3) / 4);
+        st = alloc_f(&net->head_w1p, (sk::head_w1_packed_bytes(net->dtype, c1.c_in, c1.c_out) + 3) / 4);
         if (st == SK_OK) {
-            hipError_t e = sk::launch_pack_head_w1(c1.w_dev, net->head_w1p, SK_F32, c1.c_out, c1.c_in, nullptr);
+            hipError_t e = sk::launch_pack_head_w1(c1.w_dev, net->head_w1p, net->dtype, c1.c_out, c1.c_in, nullptr);
             if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
             if (e != hipSuccess) st = fail(SK_EDEVICE, "plan: packing the head weights failed: %s", hipGetErrorString(e));
         }
@@ -469,18 +532,23 @@ sk_status sknet3d_forward(sknet3d_t *net, const float *volume_dev, float *prob_d
         net->last_volume = net->act[0];
     }
     const int L = (int)net->layers.size();
+    if (net->half()) {
+        const Dims3 &d0 = net->dims[0];
+        SK_HIP(sk::launch_pad_pack_h(volume_dev, net->act[0], net->dtype, d0.dz, d0.c, d0.h, d0.w, 0, 0, d0.h, d0.w, 0, stream));
+    }
     for (int i = 0; i < (net->fuse_head ? L - 2 : L); ++i) SK_TRY(run_layer3(net, i, stream));
     const Dims3 &o = net->dims[L];
     if (net->fuse_head) {
         const Conv3 &c1 = net->convs[net->conv_of_layer[L - 2]], &c2 = net->convs[net->conv_of_layer[L - 1]];
         const Dims3 &in = net->dims[L - 2];
         sk::HeadArgs a{};
-        a.x = L - 2 == 0 ? volume_dev : net->act[L - 2];
+        a.x = (L - 2 == 0 && !net->half()) ? volume_dev : net->act[L - 2];
         a.w1p = net->head_w1p; a.b1 = c1.b_dev; a.w2 = c2.w_dev; a.b2 = c2.b_dev;
-        a.prob = prob_dev; a.dtype = SK_F32; a.n = in.dz; a.c_in = in.c; a.H = in.h; a.W = in.w;
+        a.prob = prob_dev; a.dtype = net->dtype; a.n = in.dz; a.c_in = in.c; a.H = in.h; a.W = in.w;
         a.hidden = c1.c_out; a.classes = c2.c_out;
         SK_HIP(sk::launch_head_fused(a, stream));
     } else {
+        if (net->half() && net->layers[L - 1].kind != SK_CONV) return fail(SK_EUNSUPPORTED, "forward: a 16-bit 3-D net must end in a convolution");
         SK_HIP(sk::launch_softmax_f32(net->act[L], prob_dev, o.dz, o.c, o.h * o.w, stream));
     }
     net->forward_done = true;
@@ -585,8 +653,19 @@ sk_status sknet3d_get_activation(sknet3d_t *net, int32_t layer_idx, float *dchw_
     if (!net->forward_done) return fail(SK_ESTATE, "get_activation: no forward pass yet");
     if (net->fuse_head && layer_idx >= (int)net->layers.size() - 2)
         return fail(SK_ESTATE, "get_activation: this plan fuses the last two layers; plan with mode 2 to keep them");
+    const Dims3 &dm = net->dims[layer_idx + 1];
+    if (net->half() && !(layer_idx == (int)net->layers.size() - 1 && net->layers[layer_idx].kind == SK_CONV)) {
+        float *tmp = nullptr;
+        SK_TRY(alloc_f(&tmp, dm.count()));
+        hipError_t e = sk::launch_unpack_h(net->act[layer_idx + 1], tmp, net->dtype, dm.dz, dm.c, dm.h, dm.w, net->last_stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(net->last_stream);
+        if (e == hipSuccess) e = hipMemcpy(dchw_host, tmp, sizeof(float) * dm.count(), hipMemcpyDeviceToHost);
+        free_dev(tmp);
+        if (e != hipSuccess) return fail(SK_EDEVICE, "get_activation: %s", hipGetErrorString(e));
+        return SK_OK;
+    }
     SK_HIP(hipStreamSynchronize(net->last_stream));
-    SK_HIP(hipMemcpy(dchw_host, net->act[layer_idx + 1], sizeof(float) * net->dims[layer_idx + 1].count(), hipMemcpyDeviceToHost));
+    SK_HIP(hipMemcpy(dchw_host, net->act[layer_idx + 1], sizeof(float) * dm.count(), hipMemcpyDeviceToHost));
     return SK_OK;
 }
 
