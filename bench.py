@@ -145,6 +145,20 @@ def measure_forward(torch, B, S, dtype, n, H, W, steps, warmup, first_seed, kern
         "conv_alg_bytes": conv_bytes / max(conv_launches, 1), "conv_alg_flops": conv_flops / max(conv_launches, 1),
         "conv_names": conv_names, "layers": layers, "ws": ws, "bs": bs, "img": img,
     }
+    if dtype != "f32" and any("pool" in nm for nm in conv_names):
+        # the same layers as plain convolutions (a plan that keeps every layer: pools are launches of their own there),
+        # to tell the convolution's own speed from the pool work its fused form carries
+        net.plan(n, H, W, pad=True, keep=True)
+        net.forward(timg, prob, stream)
+        pf, pm, pn = 0.0, 0.0, 0
+        for step in range(net.num_steps()):
+            m = re.match(r"conv(\d+)_", net.step_name(step))
+            if m and f_in_of[int(m.group(1))] == 48 and layers[int(m.group(1))]["f_out"] == 48:
+                pm += net.time_step(step, kernel_iters, stream)
+                pf += flops[int(m.group(1))]
+                pn += 1
+        if pn:
+            res["conv_plain"] = {"avg_launch_ms": round(pm / pn, 5), "tflops": round(pf / (pm * 1e-3) / 1e12, 2)}
     net.close()
     return res
 
@@ -157,6 +171,9 @@ def forward_roofline(r, dtype, table, key):
             "traffic_unit": "bytes beyond L2 per launch (read + written)", "traffic_source": src,
             "algorithmic_bytes": int(r["conv_alg_bytes"]), "algorithmic_flops": int(r["conv_alg_flops"]),
             "avg_launch_ms": round(r["conv_ms_avg"], 5),
+            "same_layers_without_pool_work": (dict(r["conv_plain"], frac=round(r["conv_plain"]["tflops"] / peak, 4),
+                                                   what="the three layers in a plan that keeps the pools as launches (mode 2)")
+                                              if r.get("conv_plain") else None),
             "kernel": "48->48 k4 SK convolutions at d=2,4,8 (%s): %s"
                       % ("conv_f32_pf_kernel<3,1,4,4,2,false,4>" if dtype == "f32" else "conv_h_ring_kernel, producer-wave variant",
                          ", ".join(r["conv_names"]))}
