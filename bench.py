@@ -259,6 +259,34 @@ def measure_train(torch, B, S, dtype, n, H, W, steps, warmup, first_seed, kernel
     return res
 
 
+def measure_softmax_kernels(torch, B, S, dtype, n, H, W, kernel_iters=10):
+    """The stand-alone softmax and softmax-loss kernels (what a layer-by-layer plan runs; the fused plans of the
+    timed steps have them inside the head kernels): GB/s over their algorithmic bytes."""
+    layers = S.sknet_layers()
+    ws, bs = S.he_normal_weights(layers, 1, 1001)
+    net = B.SKNet(layers, 1, 2, dtype=dtype)
+    for i, (w, b) in enumerate(zip(ws, bs)):
+        net.set_weights(i, w, b)
+    net.plan(n, H, W, pad=True, training=True)
+    timg = torch.from_numpy(S.em_like_batch(n, H, W, 3)).cuda()
+    labels = torch.from_numpy(S.binary_labels(n, H, W, 2004)).cuda()
+    stream = torch.cuda.current_stream()
+    net.forward(timg, None, stream)
+    px, cls = n * H * W, 2
+    sm_ms = None
+    for step in range(net.num_steps()):
+        if net.step_name(step) == "softmax":
+            sm_ms = net.time_step(step, kernel_iters, stream)
+    loss_ms = net.time_backward_step(labels, 0, 2, kernel_iters, stream)
+    net.close()
+    # softmax: logits in, probabilities out.  loss: labels (count pass), logits + labels in, fp32 gradient out,
+    # and for 16-bit storage the gradient once more as one 16-byte octet per pixel
+    sm_bytes = px * 2.0 * 4 * cls
+    loss_bytes = px * (4 + 4 * cls + 4 + 4 * cls + (0 if dtype == "f32" else 16.0))
+    return {"softmax_ms": round(sm_ms, 5) if sm_ms else None, "softmax_gbs": round(sm_bytes / (sm_ms * 1e-3) / 1e9, 1) if sm_ms else None,
+            "softmax_loss_ms": round(loss_ms, 5), "softmax_loss_gbs": round(loss_bytes / (loss_ms * 1e-3) / 1e9, 1)}
+
+
 def train_roofline(r, dtype, table, key):
     peak = PEAK_TFLOPS[dtype]
     w = r["wgrad"]
@@ -594,6 +622,13 @@ def main():
                        "global_batch": n, "parallelism": "single GPU"},
             "roofline": train_roofline(rt, "bf16", table, args.workload + "_wgrad"), "parts_ms": rt["parts_ms"],
         })
+        sm = measure_softmax_kernels(torch, B, S, "bf16", n, H, H)
+        hb = out["roofline"]["hbm_bound_kernels"]
+        hb.update({"softmax_gbs": sm["softmax_gbs"], "softmax_loss_gbs": sm["softmax_loss_gbs"], "softmax_ms": sm["softmax_ms"],
+                   "softmax_loss_ms": sm["softmax_loss_ms"],
+                   "softmax_note": "stand-alone kernels of a layer-by-layer plan (mode 1) on the same images; the timed step has them inside the head kernels"})
+        hb["frac"].update({"softmax_gbs": round(sm["softmax_gbs"] / HBM_PEAK_GBS, 4) if sm["softmax_gbs"] else None,
+                           "softmax_loss_gbs": round(sm["softmax_loss_gbs"] / HBM_PEAK_GBS, 4)})
 
     if args.workload == "c2" and not args.no_extras:
         extras = {}

@@ -170,7 +170,7 @@ sk_status sknet_backward(sknet_t *net, const int32_t *labels_dev, float *loss_de
  * instead of the plan's own scratch.  The call itself allocates and frees nothing.  The activation-gradient
  * buffers are the plan's, as in sknet_backward.  Limits: SK_EUNSUPPORTED if one padded copy of the net's largest
  * weight gradient, roundup(f_out,16) x roundup(f_in*k*k,16) floats plus 512 x roundup(f_out,16) floats of bias partials,
- * exceeds 8 Mi - 4096 floats, or if the loss needs more than 4096 floats (it never does: at most 2048).  A weight
+ * exceeds 8 Mi - 4096 floats, or if the loss needs more than 4096 floats (it never does: at most 4096).  A weight
  * gradient takes as many private copies as fit, so the summation order -- not the value beyond fp32 rounding --
  * can differ from sknet_backward's.  Every call on one GPU shares that GPU's buffer, whose contents are whatever
  * the last call left (nothing in it needs clearing: each kernel writes every partial that is read afterwards);

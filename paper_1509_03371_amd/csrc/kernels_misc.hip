@@ -489,8 +489,51 @@ __global__ void softmax_f32_kernel(const float *z, float *p, int n, int classes,
     }
 }
 
+// Four consecutive pixels per thread (16-byte loads and stores), the exponentials kept in registers: the kernel
+// moves 8 bytes per pixel and class and does nothing else, so access width and instruction count are what it has.
+typedef float float4v __attribute__((ext_vector_type(4)));
+template <int CLS>
+__global__ void __launch_bounds__(256) softmax_f32_v4_kernel(const float *__restrict__ z, float *__restrict__ p, int n, int hw4)
+{
+    const long total = (long)n * hw4;
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
+        const long b = q / hw4, g4 = q - b * hw4;
+        const float4v *zp = reinterpret_cast<const float4v *>(z) + b * CLS * hw4 + g4;
+        float4v e[CLS];
+#pragma unroll
+        for (int c = 0; c < CLS; ++c) e[c] = zp[(long)c * hw4];
+        float4v m = e[0];
+#pragma unroll
+        for (int c = 1; c < CLS; ++c)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) m[t] = fmaxf(m[t], e[c][t]);
+        float4v sum = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < CLS; ++c)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                e[c][t] = expf(e[c][t] - m[t]);
+                sum[t] += e[c][t];
+            }
+        float4v inv;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) inv[t] = 1.f / sum[t];
+        float4v *pp = reinterpret_cast<float4v *>(p) + b * CLS * hw4 + g4;
+#pragma unroll
+        for (int c = 0; c < CLS; ++c) pp[(long)c * hw4] = e[c] * inv;
+    }
+}
+
 hipError_t launch_softmax_f32(const float *z, float *p, int n, int classes, int hw, hipStream_t stream)
 {
+    const bool vec = hw % 4 == 0 && classes >= 2 && classes <= 4 && (reinterpret_cast<uintptr_t>(z) | reinterpret_cast<uintptr_t>(p)) % 16 == 0;
+    if (vec) {
+        const dim3 grid(grid_for((long)n * (hw / 4)));
+        if (classes == 2) hipLaunchKernelGGL(softmax_f32_v4_kernel<2>, grid, dim3(256), 0, stream, z, p, n, hw / 4);
+        else if (classes == 3) hipLaunchKernelGGL(softmax_f32_v4_kernel<3>, grid, dim3(256), 0, stream, z, p, n, hw / 4);
+        else hipLaunchKernelGGL(softmax_f32_v4_kernel<4>, grid, dim3(256), 0, stream, z, p, n, hw / 4);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(softmax_f32_kernel, dim3(grid_for((long)n * hw)), dim3(256), 0, stream, z, p, n,
                        classes, hw);
     return hipGetLastError();
@@ -498,7 +541,7 @@ hipError_t launch_softmax_f32(const float *z, float *p, int n, int classes, int 
 
 // ---- softmax loss (Section 4.3): mean over all pixels of -log p_label, and its gradient ----------------
 constexpr int LOSS_BLOCK = 256;
-constexpr int LOSS_MAX_BLOCKS = 1024;
+constexpr int LOSS_MAX_BLOCKS = 2048;
 
 static int loss_blocks(long pixels)
 {
@@ -531,9 +574,19 @@ __global__ void label_count_kernel(const int32_t *labels, long total, int classe
 {
     __shared__ int sh[LOSS_BLOCK / 64];
     int local = 0;
-    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
-        const int lab = labels[q];
-        local += (lab >= 0 && lab < classes) ? 1 : 0;
+    if (total % 4 == 0 && reinterpret_cast<uintptr_t>(labels) % 16 == 0) {          // four labels per load
+        typedef int int4l __attribute__((ext_vector_type(4)));
+        const int4l *l4 = reinterpret_cast<const int4l *>(labels);
+        for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total / 4; q += (long)gridDim.x * blockDim.x) {
+            const int4l lab = l4[q];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) local += (lab[t] >= 0 && lab[t] < classes) ? 1 : 0;
+        }
+    } else {
+        for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
+            const int lab = labels[q];
+            local += (lab >= 0 && lab < classes) ? 1 : 0;
+        }
     }
     for (int off = 32; off > 0; off >>= 1) local += __shfl_down(local, off, 64);
     if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = local;
@@ -589,6 +642,67 @@ __global__ void softmax_loss_f32_kernel(const float *z, const int32_t *labels, f
     if (threadIdx.x == 0) partial[blockIdx.x] = s;
 }
 
+// The same, four consecutive pixels per thread, 16-byte accesses.  dz16 (optional): the gradient once more in the
+// 16-bit octet layout [n][1][hw][8] (classes 0..CLS-1 of a pixel in the first elements of its 16 bytes, zeros behind),
+// which is what the 16-bit layers below read -- written here instead of by a conversion pass over dz.
+typedef unsigned int uint4w __attribute__((ext_vector_type(4)));
+typedef int int4w __attribute__((ext_vector_type(4)));
+template <int CLS, int DT>
+__global__ void __launch_bounds__(LOSS_BLOCK) softmax_loss_f32_v4_kernel(const float *__restrict__ z, const int32_t *__restrict__ labels,
+                                                                          float *__restrict__ dz, uint4w *__restrict__ dz16,
+                                                                          float *__restrict__ partial, const int *__restrict__ counts, int n, int hw4)
+{
+    __shared__ float sh[LOSS_BLOCK / 64];
+    const long total = (long)n * hw4;
+    const long kept = labelled_pixels(counts, gridDim.x);
+    const float invP = 1.f / (float)(kept > 0 ? kept : 1);
+    float local = 0.f;
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
+        const long b = q / hw4, g4 = q - b * hw4;
+        const float4v *zp = reinterpret_cast<const float4v *>(z) + b * CLS * hw4 + g4;
+        const int4w lab = reinterpret_cast<const int4w *>(labels)[q];
+        float4v e[CLS];
+#pragma unroll
+        for (int c = 0; c < CLS; ++c) e[c] = zp[(long)c * hw4];
+        float4v g[CLS];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const bool ok = lab[t] >= 0 && lab[t] < CLS;
+            float m = e[0][t];
+#pragma unroll
+            for (int c = 1; c < CLS; ++c) m = fmaxf(m, e[c][t]);
+            float sum = 0.f, zl = 0.f, ex[CLS];
+#pragma unroll
+            for (int c = 0; c < CLS; ++c) {
+                ex[c] = expf(e[c][t] - m);
+                sum += ex[c];
+                zl = c == lab[t] ? e[c][t] : zl;
+            }
+            if (ok) local -= zl - m - logf(sum);
+            const float inv = 1.f / sum;
+#pragma unroll
+            for (int c = 0; c < CLS; ++c) g[c][t] = ok ? (ex[c] * inv - (c == lab[t] ? 1.f : 0.f)) * invP : 0.f;
+        }
+        float4v *gp = reinterpret_cast<float4v *>(dz) + b * CLS * hw4 + g4;
+#pragma unroll
+        for (int c = 0; c < CLS; ++c) gp[(long)c * hw4] = g[c];
+        if constexpr (DT != 0) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                unsigned short h[4] = {0, 0, 0, 0};
+#pragma unroll
+                for (int c = 0; c < CLS; ++c) {
+                    if constexpr (DT == 1) h[c] = __builtin_bit_cast(unsigned short, static_cast<__bf16>(g[c][t]));
+                    else h[c] = __builtin_bit_cast(unsigned short, static_cast<_Float16>(g[c][t]));
+                }
+                dz16[4 * q + t] = uint4w{(unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16), 0u, 0u};
+            }
+        }
+    }
+    const float s = block_sum(local, sh);
+    if (threadIdx.x == 0) partial[blockIdx.x] = s;
+}
+
 __global__ void loss_finish_kernel(const float *partial, const int *counts, int count, float *loss)
 {
     __shared__ float sh[LOSS_BLOCK / 64];
@@ -607,13 +721,35 @@ hipError_t launch_label_count(const int32_t *labels, long pixels, int classes, i
     return hipGetLastError();
 }
 
+template <int DT>
+static void launch_loss_v4(int classes, int blocks, hipStream_t stream, const float *z, const int32_t *labels, float *dz, void *dz16, float *partial,
+                           const int *counts, int n, int hw4)
+{
+    uint4w *o = static_cast<uint4w *>(dz16);
+    if (classes == 2) hipLaunchKernelGGL((softmax_loss_f32_v4_kernel<2, DT>), dim3(blocks), dim3(LOSS_BLOCK), 0, stream, z, labels, dz, o, partial, counts, n, hw4);
+    else if (classes == 3) hipLaunchKernelGGL((softmax_loss_f32_v4_kernel<3, DT>), dim3(blocks), dim3(LOSS_BLOCK), 0, stream, z, labels, dz, o, partial, counts, n, hw4);
+    else hipLaunchKernelGGL((softmax_loss_f32_v4_kernel<4, DT>), dim3(blocks), dim3(LOSS_BLOCK), 0, stream, z, labels, dz, o, partial, counts, n, hw4);
+}
+
+// can launch_softmax_loss_f32 write the 16-bit octet copy of the gradient itself?  (else the caller converts dz)
+bool softmax_loss_writes_octets(int classes, int hw) { return hw % 4 == 0 && classes >= 2 && classes <= 4; }
+
 hipError_t launch_softmax_loss_f32(const float *z, const int32_t *labels, float *dz, float *loss,
-                                   float *partial, int n, int classes, int hw, hipStream_t stream)
+                                   float *partial, int n, int classes, int hw, hipStream_t stream, void *dz16, int dtype16)
 {
     const long pixels = (long)n * hw;
     const int blocks = loss_blocks(pixels);
     int *counts = reinterpret_cast<int *>(partial + blocks);
     hipLaunchKernelGGL(label_count_kernel, dim3(blocks), dim3(LOSS_BLOCK), 0, stream, labels, pixels, classes, counts);
+    const bool aligned = (reinterpret_cast<uintptr_t>(z) | reinterpret_cast<uintptr_t>(dz) | reinterpret_cast<uintptr_t>(labels)) % 16 == 0;
+    if (dz16 && !(softmax_loss_writes_octets(classes, hw) && aligned && (dtype16 == 1 || dtype16 == 2))) return hipErrorInvalidValue;
+    if (softmax_loss_writes_octets(classes, hw) && aligned) {
+        if (!dz16) launch_loss_v4<0>(classes, blocks, stream, z, labels, dz, nullptr, partial, counts, n, hw / 4);
+        else if (dtype16 == 1) launch_loss_v4<1>(classes, blocks, stream, z, labels, dz, dz16, partial, counts, n, hw / 4);
+        else launch_loss_v4<2>(classes, blocks, stream, z, labels, dz, dz16, partial, counts, n, hw / 4);
+        hipLaunchKernelGGL(loss_finish_kernel, dim3(1), dim3(LOSS_BLOCK), 0, stream, partial, counts, blocks, loss);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(softmax_loss_f32_kernel, dim3(blocks), dim3(LOSS_BLOCK), 0, stream, z, labels, dz,
                        partial, counts, n, classes, hw);
     hipLaunchKernelGGL(loss_finish_kernel, dim3(1), dim3(LOSS_BLOCK), 0, stream, partial, counts, blocks, loss);

@@ -222,8 +222,11 @@ hipError_t launch_softmax_f32(const float *z, float *p, int n, int classes, int 
 int softmax_loss_partials(long pixels);
 // counts[0..*ncounts) = partial counts of the pixels whose label lies in 0..classes-1 (counts: softmax_loss_partials(pixels) ints)
 hipError_t launch_label_count(const int32_t *labels, long pixels, int classes, int *counts, int *ncounts, hipStream_t stream);
+// dz16 (optional, with dtype16 = 1 bf16 / 2 fp16): the gradient once more in the 16-bit octet layout [n][1][hw][8]; only where
+// softmax_loss_writes_octets(classes, hw) says so (hipErrorInvalidValue otherwise: convert dz instead)
+bool softmax_loss_writes_octets(int classes, int hw);
 hipError_t launch_softmax_loss_f32(const float *z, const int32_t *labels, float *dz, float *loss,
-                                   float *partial, int n, int classes, int hw, hipStream_t stream);
+                                   float *partial, int n, int classes, int hw, hipStream_t stream, void *dz16 = nullptr, int dtype16 = 0);
 // g = dw + wd*w; v = mu*v + lr*g; w -= v   (v may be nullptr when mu = 0)
 hipError_t launch_sgd_f32(float *w, const float *dw, float *v, long count, float lr, float mu,
                           float wd, hipStream_t stream);

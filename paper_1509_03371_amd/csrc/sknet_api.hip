@@ -690,10 +690,13 @@ static sk_status backward_impl(sknet_t *net, const int32_t *labels_dev, float *l
     } else {
         const float *logits = (half && net->layers[L - 1].kind != SK_CONV) ? net->logits_f32 : net->act[L];
         float *dz = half ? net->dz_f32 : gcur;
-        SK_HIP(sk::launch_softmax_loss_f32(logits, labels_dev, dz, loss_dev, loss_partial, n, o.c, o.h * o.w, stream));
-        if (net->layers[L - 1].kind == SK_CONV && net->layers[L - 1].relu)
-            SK_HIP(sk::launch_relu_mask_f32(dz, net->act[L], o.count(n), stream));
-        if (half) SK_HIP(sk::launch_pad_pack_h(dz, gcur, dt, n, o.c, o.h, o.w, 0, 0, o.h, o.w, 0, stream));
+        const bool masked = net->layers[L - 1].kind == SK_CONV && net->layers[L - 1].relu;
+        // 16-bit nets: the loss kernel also writes the gradient in the octet layout the layers below read (when it can)
+        const bool direct = half && !masked && sk::softmax_loss_writes_octets(o.c, o.h * o.w);
+        SK_HIP(sk::launch_softmax_loss_f32(logits, labels_dev, dz, loss_dev, loss_partial, n, o.c, o.h * o.w, stream, direct ? gcur : nullptr,
+                                           direct ? dt : 0));
+        if (masked) SK_HIP(sk::launch_relu_mask_f32(dz, net->act[L], o.count(n), stream));
+        if (half && !direct) SK_HIP(sk::launch_pad_pack_h(dz, gcur, dt, n, o.c, o.h, o.w, 0, 0, o.h, o.w, 0, stream));
     }
     for (int li = top; li >= 0; --li) {
         if (grad_at_stop && li == stop_layer) {
