@@ -12,7 +12,7 @@ A step is one such pass over one synthetic image that is resident in HBM before 
 --workload c5 / c5bf16 : U-Net forward on one 572x572 image (configs[4]) in fp32 / bf16
 --workload papersk / paperskbf16, usk / uskbf16 : the paper's own SK-Net (128^2 tile) and USK-Net (692^2), fp32 / bf16
 --workload sk3d / sk3dbf16 / sk3dtrain : 3-D SK net on a stack of 81 sections of 145x145 (Section 5.2.2), fp32 (bf16: forward)
---workload unettrain / usktrain : U-Net / USK-Net training step, fp32
+--workload unettrain / usktrain : U-Net / USK-Net training step, fp32 (unettrainbf16 / usktrainbf16: bf16 storage)
 --workload copy    : only the streaming-copy probe on 2 x 1 GiB (the known-size kernel that the HBM
                      byte counters of a profiler run are calibrated against)
 The default run also appends short measurements of the other workloads under "extras" (skip with --no-extras).
@@ -345,16 +345,17 @@ def measure_usknet(torch, B, S, steps, warmup, dtype="f32"):
             "gflop": round(gflop, 1), "tflops": round(gflop / dt / 1e3, 1), "frac_of_mfma_peak": round(gflop / dt / 1e3 / PEAK_TFLOPS[dtype], 4)}
 
 
-def measure_unet_train(torch, B, S, which, steps, warmup):
+def measure_unet_train(torch, B, S, which, steps, warmup, dtype="f32"):
     """One training step (forward, masked softmax loss, backward, SGD) of the U-Net (572^2 -> 388^2) or the
-    USK-Net (692^2 -> 512^2) of the paper's tables, fp32, labels masked by inverse frequency."""
+    USK-Net (692^2 -> 512^2) of the paper's tables, labels masked by inverse frequency; dtype = storage type of
+    activations and error maps."""
     import numpy as np
     if which == "unet":
         params, names = S.unet_params(1, 2, 1005, depth=4, base=64), S.unet_param_names(4)
-        net, c_in, size, out = B.UNet(1, 2, depth=4, base_ch=64), 1, 572, 388
+        net, c_in, size, out = B.UNet(1, 2, depth=4, base_ch=64, dtype=dtype), 1, 572, 388
     else:
         params, names = S.usknet_params(3, 2, 1006, base=64), S.USKNET_PARAM_NAMES
-        net, c_in, size, out = B.USKNet(3, 2, base_ch=64), 3, 692, 512
+        net, c_in, size, out = B.USKNet(3, 2, base_ch=64, dtype=dtype), 3, 692, 512
     for i, name in enumerate(names):
         net.set_weights(i, *params[name])
     net.plan(1, size, size, training=True)
@@ -530,7 +531,7 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", choices=["c2", "c3", "c4", "c3train", "c5", "c5bf16", "usk", "uskbf16", "papersk", "paperskbf16", "sk3d", "sk3dbf16", "sk3dtrain",
-                                           "unettrain", "usktrain", "copy"], default="c2")
+                                           "unettrain", "usktrain", "unettrainbf16", "usktrainbf16", "copy"], default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
     args = ap.parse_args()
@@ -568,11 +569,12 @@ def main():
         print(json.dumps(out))
         return
 
-    if args.workload in ("unettrain", "usktrain"):
-        r = measure_unet_train(torch, B, S, "unet" if args.workload == "unettrain" else "usk", args.steps, args.warmup)
-        out.update({"value": r["labelled_pixels_per_s"], "ms_per_step": r["ms_per_step"], "ms_per_step_events": r["events"], "dtype": "f32",
-                    "config": {"workload": ("U-Net 572^2 -> 388^2" if args.workload == "unettrain" else "USK-Net 692^2 -> 512^2")
-                                           + " training step (forward, masked softmax loss, backward, SGD), fp32",
+    if args.workload in ("unettrain", "usktrain", "unettrainbf16", "usktrainbf16"):
+        wdt = "bf16" if args.workload.endswith("bf16") else "f32"
+        r = measure_unet_train(torch, B, S, "unet" if args.workload.startswith("unet") else "usk", args.steps, args.warmup, wdt)
+        out.update({"value": r["labelled_pixels_per_s"], "ms_per_step": r["ms_per_step"], "ms_per_step_events": r["events"], "dtype": wdt,
+                    "config": {"workload": ("U-Net 572^2 -> 388^2" if args.workload.startswith("unet") else "USK-Net 692^2 -> 512^2")
+                                           + " training step (forward, masked softmax loss, backward, SGD), " + wdt,
                                "global_batch": 1, "parallelism": "single GPU"}, "roofline": None, "detail": r})
         print(json.dumps(out))
         return
@@ -659,6 +661,8 @@ def main():
         extras["sknet3d_81x145x145_f32_train_step"] = measure_sknet3d_train(torch, B, S, 3, 1)
         extras["unet_572_f32_train_step"] = measure_unet_train(torch, B, S, "unet", 3, 1)
         extras["usknet_692_f32_train_step"] = measure_unet_train(torch, B, S, "usk", 3, 1)
+        extras["unet_572_bf16_train_step"] = measure_unet_train(torch, B, S, "unet", 3, 1, "bf16")
+        extras["usknet_692_bf16_train_step"] = measure_unet_train(torch, B, S, "usk", 3, 1, "bf16")
         out["extras"] = extras
 
     if args.workload == "c2" and not args.no_cpu_baseline:

@@ -270,7 +270,9 @@ sk_status unet_plan(unet_t *net, int32_t n, int32_t h_in, int32_t w_in);
  * floor((w_skip - w_up)/2) (Section 5.3.1). */
 sk_status unet_forward(unet_t *net, const float *image_dev, float *prob_dev, void *hip_stream);
 
-/* Training pass (fp32 storage only, else SK_EUNSUPPORTED; U-Net and USK-Net handles alike).
+/* Training pass (U-Net and USK-Net handles alike; every storage type: with bf16 / fp16 the error maps are stored
+ * in that type too, sums and weight gradients are fp32 and the fp32 master weights take the update.  fp16 error
+ * maps carry the loss's factor 1 / (labelled pixels) unscaled and underflow on large images; bf16 does not).
  * unet_plan_training: as unet_plan, and also allocates a gradient buffer per activation, the pools'
  *   winner codes and the gradient scratch; unet_forward then records what the backward pass needs.
  * unet_backward: after a forward on a training plan (SK_ESTATE otherwise).  labels_dev: DEVICE int32

@@ -421,6 +421,114 @@ hipError_t launch_maxpool_bwd_h(const void *dy, const void *tap, const void *rel
     return hipGetLastError();
 }
 
+// Gradient of a pool with layer stride s = k at d = 1 (the U-Net pools, Section 3.4): the windows do not overlap, input
+// unit (u, v) belongs to window (u / k, v / k) and takes that window's dY where it is the recorded winner; units beyond
+// the last window get zero.  acc != 0: added to what dx holds (another consumer of the same map wrote first).  relu_src
+// as in the gather form above (applied to the sum).
+template <int DT>
+__global__ void maxpool_stride_bwd_h_kernel(const uint4v *__restrict__ dy, const uint2v *__restrict__ tap, const uint4v *__restrict__ relu_src,
+                                            uint4v *__restrict__ dx, int H, int W, int Ho, int Wo, int k, int acc)
+{
+    const int v = blockIdx.x * blockDim.x + threadIdx.x, u = blockIdx.y;
+    if (v >= W) return;
+    const long p = blockIdx.z;
+    const int yy = u / k, xx = v / k;
+    const unsigned want = (unsigned)((u - yy * k) * k + (v - xx * k));
+    const long q = (p * H + u) * W + v;
+    float a[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) a[e] = 0.f;
+    if (yy < Ho && xx < Wo) {
+        const long o = (p * Ho + yy) * Wo + xx;
+        const uint2v c = tap[o];
+        const uint4v g = dy[o];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const unsigned code = (c[e >> 2] >> ((e & 3) * 8)) & 0xffu;
+            if (code == want) a[e] = up16<DT>(elem16(g, e));
+        }
+    }
+    if (acc) {
+        const uint4v old = dx[q];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) a[e] += up16<DT>(elem16(old, e));
+    }
+    uint4v rs = uint4v{0u, 0u, 0u, 0u};
+    if (relu_src) rs = relu_src[q];
+    unsigned hv[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        float t = a[e];
+        if (relu_src && !(up16<DT>(elem16(rs, e)) > 0.f)) t = 0.f;
+        hv[e] = down16<DT>(t);
+    }
+    dx[q] = uint4v{hv[0] | (hv[1] << 16), hv[2] | (hv[3] << 16), hv[4] | (hv[5] << 16), hv[6] | (hv[7] << 16)};
+}
+
+hipError_t launch_maxpool_stride_bwd_h(const void *dy, const void *tap, const void *relu_src, void *dx, int dtype, long planes8, int H, int W,
+                                       int Ho, int Wo, int k, int acc, hipStream_t stream)
+{
+    if (H > 65535 || planes8 > 65535 || k < 1 || (dtype != 1 && dtype != 2) || Ho * k > H || Wo * k > W) return hipErrorInvalidValue;
+    const dim3 grid((W + 255) / 256, H, (unsigned)planes8);
+    const uint4v *g = static_cast<const uint4v *>(dy), *rs = static_cast<const uint4v *>(relu_src);
+    const uint2v *tp = static_cast<const uint2v *>(tap);
+    uint4v *out = static_cast<uint4v *>(dx);
+    if (dtype == 1) hipLaunchKernelGGL(maxpool_stride_bwd_h_kernel<1>, grid, dim3(256), 0, stream, g, tp, rs, out, H, W, Ho, Wo, k, acc);
+    else hipLaunchKernelGGL(maxpool_stride_bwd_h_kernel<2>, grid, dim3(256), 0, stream, g, tp, rs, out, H, W, Ho, Wo, k, acc);
+    return hipGetLastError();
+}
+
+// Backward of the 2x2 stride-2 up-convolution (Section 3.4), first step: the gradient of the merged buffer's first c8
+// octets (the up path; the buffer has c8_total octets of 2h x 2w) as four interleaved sub-images stacked along the maps:
+// out[b][t * c8 + o][y][x] = in[b][o][2y + t/2][2x + t%2].  Bits are moved, nothing is rounded.
+__global__ void space_to_depth2_h_kernel(const uint4v *__restrict__ in, uint4v *__restrict__ out, int n, int c8_total, int c8, int h, int w)
+{
+    const long plane = (long)h * w, total = (long)n * 4 * c8 * plane;
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
+        const long pix = q % plane, r = q / plane;
+        const int x = (int)(pix % w), y = (int)(pix / w);
+        const int o4 = (int)(r % (4 * c8)), t = o4 / c8, o = o4 - t * c8;
+        const long b = r / (4 * c8);
+        out[q] = in[((b * c8_total + o) * (2 * h) + 2 * y + (t >> 1)) * (2L * w) + 2 * x + (t & 1)];
+    }
+}
+
+hipError_t launch_space_to_depth2_h(const void *in, void *out, int n, int c8_total, int c8, int h, int w, hipStream_t stream)
+{
+    if (n < 1 || c8 < 1 || c8 > c8_total || h < 1 || w < 1) return hipErrorInvalidValue;
+    const long total = (long)n * 4 * c8 * h * w;
+    hipLaunchKernelGGL(space_to_depth2_h_kernel, dim3(grid_for(total)), dim3(256), 0, stream, static_cast<const uint4v *>(in),
+                       static_cast<uint4v *>(out), n, c8_total, c8, h, w);
+    return hipGetLastError();
+}
+
+// MergeCrop's backward into the skip map (Section 5.3.1, when enabled): dst [n][c8][Hd][Wd] takes octets o8_off .. of
+// src [n][c8_total][Hs][Ws] in its centre window (offset cy, cx) and zero elsewhere
+__global__ void place_h_kernel(const uint4v *__restrict__ src, uint4v *__restrict__ dst, int n, int c8, int Hd, int Wd, int c8_total,
+                               int o8_off, int Hs, int Ws, int cy, int cx)
+{
+    const long plane = (long)Hd * Wd, total = (long)n * c8 * plane;
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
+        const long pix = q % plane, r = q / plane;
+        const int x = (int)(pix % Wd) - cx, y = (int)(pix / Wd) - cy;
+        const int o = (int)(r % c8);
+        const long b = r / c8;
+        uint4v v = uint4v{0u, 0u, 0u, 0u};
+        if (x >= 0 && x < Ws && y >= 0 && y < Hs) v = src[((b * c8_total + o8_off + o) * Hs + y) * Ws + x];
+        dst[q] = v;
+    }
+}
+
+hipError_t launch_place_h(const void *src, void *dst, int n, int c8, int Hd, int Wd, int c8_total, int o8_off, int Hs, int Ws, int cy,
+                          int cx, hipStream_t stream)
+{
+    if (cy < 0 || cx < 0 || cy + Hs > Hd || cx + Ws > Wd || o8_off < 0 || o8_off + c8 > c8_total || n < 1) return hipErrorInvalidValue;
+    const long total = (long)n * c8 * Hd * Wd;
+    hipLaunchKernelGGL(place_h_kernel, dim3(grid_for(total)), dim3(256), 0, stream, static_cast<const uint4v *>(src), static_cast<uint4v *>(dst),
+                       n, c8, Hd, Wd, c8_total, o8_off, Hs, Ws, cy, cx);
+    return hipGetLastError();
+}
+
 // winner codes on the octet layout -> flat input offsets, int32 NCHW (for the parity accessor)
 __global__ void tap_to_index_h_kernel(const uint2v *tap, int32_t *idx, int n, int c, int Ho, int Wo, int W, int k, int d, int s)
 {

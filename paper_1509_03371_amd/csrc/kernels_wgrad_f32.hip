@@ -306,8 +306,9 @@ __global__ __launch_bounds__(256) void wgrad_h_kernel(WgradArgs a)
     extern __shared__ uint4v smem16[];
     const int k = a.k, d = a.d, K = a.c_in * k * k;
     const int m_rows = a.MTo * 16;
-    unsigned short *dys = reinterpret_cast<unsigned short *>(smem16);   // [m_rows][WG_DYH]
-    unsigned short *xs = dys + m_rows * WG_DYH;                          // [8*ceil(c_in/8)*k][xpitch]
+    // a tile group stages what it multiplies: the dY rows of its MB map tiles and the input octets its columns touch
+    unsigned short *dys = reinterpret_cast<unsigned short *>(smem16);   // [MB*16][WG_DYH]
+    unsigned short *xs = dys + MB * 16 * WG_DYH;                         // [8*(octets of the group)*k][xpitch]
     const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, g = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int PW = WG_SEG + (k - 1) * d;        // <= 64 * XV (checked by the launcher)
@@ -315,6 +316,11 @@ __global__ __launch_bounds__(256) void wgrad_h_kernel(WgradArgs a)
     const int ngroups = (a.NTk + 4 * NB - 1) / (4 * NB);
     const int mgroup = blockIdx.y / ngroups, ngroup = blockIdx.y - mgroup * ngroups;
     const int mo0 = mgroup * MB;
+    // input octets of this group's columns (c, i, j) = cij: [oc0, oc0 + noct)
+    const int cij_lo = ngroup * NB * 4 * 16;
+    int cij_hi = cij_lo + NB * 4 * 16 - 1;
+    cij_hi = cij_hi < K - 1 ? cij_hi : K - 1;
+    const int oc0 = cij_lo / (k * k) / 8, noct = cij_hi / (k * k) / 8 - oc0 + 1;
     int xoff[NB];
 #pragma unroll
     for (int q = 0; q < NB; ++q) {
@@ -323,7 +329,7 @@ __global__ __launch_bounds__(256) void wgrad_h_kernel(WgradArgs a)
         int off = 0;
         if (nk < a.NTk && cij < K) {
             const int c = cij / (k * k), r = cij - c * k * k, i = r / k, j = r - i * k;
-            off = (c * k + i) * a.xpitch + j * d;
+            off = ((c - oc0 * 8) * k + i) * a.xpitch + j * d;
         }
         xoff[q] = off + 8 * g;
     }
@@ -342,7 +348,7 @@ __global__ __launch_bounds__(256) void wgrad_h_kernel(WgradArgs a)
     const uint4v *dyp = static_cast<const uint4v *>(a.dy), *xp = static_cast<const uint4v *>(a.x);
     const int c8o = (a.c_out + 7) / 8, c8i = (a.c_in + 7) / 8;
     const int oc_end = (mo0 + MB) * 2 < a.MTo * 2 ? (mo0 + MB) * 2 : a.MTo * 2;
-    const int nrid = c8i * k;                                   // (input octet, kernel row) pairs to stage
+    const int nrid = noct * k;                                  // (input octet, kernel row) pairs to stage
     const int nbat = (nrid + 4 * XU - 1) / (4 * XU);
     const int kxp = k * a.xpitch;                               // LDS distance between the 8 maps of an octet
 
@@ -362,7 +368,9 @@ __global__ __launch_bounds__(256) void wgrad_h_kernel(WgradArgs a)
         for (int u = 0; u < XU; ++u) {
             const int rid = wave + 4 * (bat * XU + u);
             const int ridc = rid < nrid ? rid : nrid - 1;
-            const int oc = ridc / k, i = ridc - oc * k;
+            const int ocr = ridc / k, i = ridc - ocr * k;
+            int oc = oc0 + ocr;
+            oc = oc < c8i ? oc : c8i - 1;
             const uint4v *src = xp + ((long)b * c8i + oc) * xplane + (long)(y + i * d) * a.W;
 #pragma unroll
             for (int v = 0; v < XV; ++v) {
@@ -380,7 +388,7 @@ __global__ __launch_bounds__(256) void wgrad_h_kernel(WgradArgs a)
 #pragma unroll
         for (int t = 0; t < DYL; ++t) {
             const int oc = mo0 * 2 + wave + 4 * t;
-            if (oc < oc_end) scatter(dys + oc * 8 * WG_DYH + lane, WG_DYH, pdy[t], oc < c8o && x0 + lane < a.Wo);
+            if (oc < oc_end) scatter(dys + (oc - mo0 * 2) * 8 * WG_DYH + lane, WG_DYH, pdy[t], oc < c8o && x0 + lane < a.Wo);
         }
     };
     auto store_x = [&](int bat, int x0) {
@@ -388,12 +396,12 @@ __global__ __launch_bounds__(256) void wgrad_h_kernel(WgradArgs a)
         for (int u = 0; u < XU; ++u) {
             const int rid = wave + 4 * (bat * XU + u);
             if (rid >= nrid) continue;                          // uniform
-            const int oc = rid / k, i = rid - oc * k;
+            const int oc = rid / k, i = rid - oc * k;                 // octet relative to the group's first
             unsigned short *row = xs + (oc * 8 * k + i) * a.xpitch;
 #pragma unroll
             for (int v = 0; v < XV; ++v) {
                 const int xc = lane + 64 * v;
-                if (xc < PW) scatter(row + xc, kxp, px[u][v], x0 + xc < a.W);
+                if (xc < PW) scatter(row + xc, kxp, px[u][v], x0 + xc < a.W && oc0 + oc < c8i);
             }
         }
     };
@@ -430,7 +438,7 @@ __global__ __launch_bounds__(256) void wgrad_h_kernel(WgradArgs a)
             uint4v av[MB];
 #pragma unroll
             for (int m = 0; m < MB; ++m) {
-                const int row = (mo0 + m) * 16 + l16;
+                const int row = m * 16 + l16;
                 av[m] = uint4v{0u, 0u, 0u, 0u};
                 if (mo0 + m < a.MTo) av[m] = *reinterpret_cast<const uint4v *>(dys + row * WG_DYH + p + 8 * g);
             }
@@ -686,9 +694,19 @@ static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, floa
     // 16-bit storage (and a window of at most 128 columns): the 16-bit matrix path
     const bool h_path = DT != 0 && PW <= 128;
     a.xpitch = h_path ? (PW + 7) / 8 * 8 + 8 : (PW + 31) / 32 * 32 + 4;
-    const int x_rows = (DT == 0 ? c_in : (c_in + 7) / 8 * 8) * k;
+    // 16-bit matrix path: a tile group stages the input octets its columns touch (the most any group has)
+    int goct = (c_in + 7) / 8;
+    if (h_path) {
+        const int K = c_in * k * k, ngroups = (a.NTk + 4 * NB - 1) / (4 * NB);
+        goct = 1;
+        for (int gi = 0; gi < ngroups; ++gi) {
+            const int lo = gi * NB * 64, hi = std::min(lo + NB * 64 - 1, K - 1);
+            goct = std::max(goct, hi / (k * k) / 8 - lo / (k * k) / 8 + 1);
+        }
+    }
+    const int x_rows = (DT == 0 ? c_in : goct * 8) * k;
     const size_t smem = DT == 0 ? f32_smem(NB)
-                                : sizeof(unsigned short) * ((size_t)(h_path ? a.MTo : MB) * 16 * (h_path ? WG_DYH : WG_DYP) + (size_t)x_rows * a.xpitch);
+                                : sizeof(unsigned short) * ((size_t)MB * 16 * (h_path ? WG_DYH : WG_DYP) + (size_t)x_rows * a.xpitch);
     if (smem > 150 * 1024) return hipErrorInvalidValue;
     // as many persistent workgroups as fit on the GPU at once (more would only add private copies
     // for the reduction to read): LDS decides

@@ -116,6 +116,14 @@ hipError_t launch_crop_copy_h(const void *src, void *dst, int n, int c8, int Hs,
                               int H, int W, int cy, int cx, hipStream_t stream);
 hipError_t launch_maxpool_bwd_h(const void *dy, const void *tap, const void *relu_src, void *dx, int dtype,
                                 long planes8, int H, int W, int Ho, int Wo, int k, int d, hipStream_t stream);
+// pool with layer stride s = k at d = 1: dx (H x W) from dy and the winner codes (Ho x Wo); acc != 0 adds to dx
+hipError_t launch_maxpool_stride_bwd_h(const void *dy, const void *tap, const void *relu_src, void *dx, int dtype, long planes8, int H, int W,
+                                       int Ho, int Wo, int k, int acc, hipStream_t stream);
+// out[b][t*c8 + o][y][x] = in[b][o][2y + t/2][2x + t%2] for the first c8 of in's c8_total octets (in: 2h x 2w, out: h x w)
+hipError_t launch_space_to_depth2_h(const void *in, void *out, int n, int c8_total, int c8, int h, int w, hipStream_t stream);
+// dst [n][c8][Hd][Wd] = octets o8_off.. of src [n][c8_total][Hs][Ws] in the window at (cy, cx), zero elsewhere
+hipError_t launch_place_h(const void *src, void *dst, int n, int c8, int Hd, int Wd, int c8_total, int o8_off, int Hs, int Ws, int cy,
+                          int cx, hipStream_t stream);
 hipError_t launch_tap_to_index_h(const void *tap, int32_t *idx, int n, int c, int Ho, int Wo, int W, int k, int d, int s,
                                  hipStream_t stream);
 // stage 1 of the bias gradient: part[(map) * slices + slice] (8 * ceil(c/8) maps); see kernels_wgrad_f32.hip

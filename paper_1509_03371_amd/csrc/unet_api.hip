@@ -50,6 +50,8 @@ struct unet {
     std::map<const float *, float *> grad_of;          // training: gradient buffer of every activation buffer
     std::vector<uint8_t *> taps;                       // training: winner codes, one entry per op (pools only)
     float *loss_partial = nullptr, *wgrad_scratch = nullptr, *s2d = nullptr;
+    float *dz16 = nullptr;                             // 16-bit training: the loss gradient in the octet layout (the last conv's dY)
+    std::set<const float *> relu_out;                  // buffers written by a convolution with ReLU
     bool planned = false, forward_done = false;
     int n = 0, h_in = 0, w_in = 0;
     std::vector<float *> buffers;            // every device activation buffer, for release
@@ -84,7 +86,8 @@ struct unet {
         for (auto &t : taps)
             if (t) { (void)hipFree(t); t = nullptr; }
         taps.clear();
-        free_dev(loss_partial); free_dev(wgrad_scratch); free_dev(s2d); free_dev(image_copy);
+        free_dev(loss_partial); free_dev(wgrad_scratch); free_dev(s2d); free_dev(image_copy); free_dev(dz16);
+        relu_out.clear();
         ops.clear();
         stages.clear();
         for (auto &c : convs) release_conv(c);
@@ -166,7 +169,7 @@ sk_status upload_up(UpParams &u, int dtype)
             std::memcpy(u.cat.w.data() + (size_t)t * u.c_out * u.c_in, u.tap[t].w.data(), sizeof(float) * u.c_out * u.c_in);
             std::memcpy(u.cat.b.data() + (size_t)t * u.c_out, u.b.data(), sizeof(float) * u.c_out);
         }
-        SK_TRY(upload_conv(u.cat, u.cat.wp_bwd != nullptr, nullptr, dtype));
+        SK_TRY(upload_conv(u.cat, u.cat.wp_bwd != nullptr || u.cat.wp16_bwd != nullptr, nullptr, dtype));
     }
     return SK_OK;
 }
@@ -327,7 +330,6 @@ static sk_status plan_impl(unet_t *net, int32_t n, int32_t h_in, int32_t w_in, b
 {
     SK_TRY(check(net));
     if (n < 1) return fail(SK_EINVAL, "unet_plan: n must be >= 1");
-    if (training && net->dtype != SK_F32) return fail(SK_EUNSUPPORTED, "unet_plan_training: the backward pass is built for fp32 storage only");
     int ho, wo;
     SK_TRY(walk_sizes(net, h_in, w_in, &ho, &wo));
     SK_TRY(sync_masters(net));             // a trained net keeps its weights across plans
@@ -499,7 +501,7 @@ static sk_status plan_impl(unet_t *net, int32_t n, int32_t h_in, int32_t w_in, b
             if (st != SK_OK) break;
             long floats = 0;
             for (const auto &op : net->ops)
-                if (op.dst == bufp) floats = std::max(floats, op.out.count(n));
+                if (op.dst == bufp) floats = std::max(floats, half && bufp != net->logits ? octet_floats(n, op.out) : op.out.count(n));
             float *g = nullptr;
             st = alloc_f(&g, floats);
             if (g) net->grad_of[bufp] = g;
@@ -511,11 +513,17 @@ static sk_status plan_impl(unet_t *net, int32_t n, int32_t h_in, int32_t w_in, b
             const auto &op = net->ops[i];
             if (op.kind == 1) {
                 if (op.s != 1 && !(op.s == op.k && op.d == 1)) st = fail(SK_EUNSUPPORTED, "training: pool needs s = 1, or s = k with d = 1");
-                hipError_t e = st == SK_OK ? hipMalloc(reinterpret_cast<void **>(&net->taps[i]), (size_t)op.out.count(n)) : hipSuccess;
+                // one byte per element, in the layout of the pool's output
+                const size_t tap_bytes = half ? (size_t)octet_floats(n, op.out) * 2 : (size_t)op.out.count(n);
+                hipError_t e = st == SK_OK ? hipMalloc(reinterpret_cast<void **>(&net->taps[i]), tap_bytes) : hipSuccess;
                 if (e != hipSuccess) st = fail(SK_ENOMEM, "plan: hipMalloc of a pool mask failed: %s", hipGetErrorString(e));
             } else if (op.kind == 0) {
                 const ConvParams &c = net->convs[op.param];
                 scratch = std::max(scratch, sk::wgrad_f32_scratch_floats(c.c_out, c.c_in, c.k));
+                if (op.relu) net->relu_out.insert(op.dst);
+                if (half && op.src != net->ops[0].dst && !sk::conv_h_supported(c.k, op.d, c.c_in))
+                    st = fail(SK_EUNSUPPORTED, "training: the data gradient of a %dx%d convolution at d = %d to %d maps is not built for 16-bit storage",
+                              c.k, c.k, op.d, c.c_in);
             } else if (op.kind == 2) {
                 const UpParams &u = net->ups[op.param];
                 scratch = std::max(scratch, sk::wgrad_f32_scratch_floats(4 * u.c_out, u.c_in, 1));
@@ -525,6 +533,7 @@ static sk_status plan_impl(unet_t *net, int32_t n, int32_t h_in, int32_t w_in, b
         if (st == SK_OK) st = alloc_f(&net->wgrad_scratch, (long)scratch);
         if (st == SK_OK) st = alloc_f(&net->s2d, s2d_floats);
         if (st == SK_OK) st = alloc_f(&net->image_copy, (long)n * net->c_in * h_in * w_in);
+        if (st == SK_OK && half) st = alloc_f(&net->dz16, octet_floats(n, net->out_dims));
         if (st == SK_OK) st = alloc_f(&net->loss_partial, sk::softmax_loss_partials((long)n * net->out_dims.h * net->out_dims.w));
     }
     if (st != SK_OK) {
@@ -580,7 +589,7 @@ sk_status unet_forward(unet_t *net, const float *image_dev, float *prob_dev, voi
                 sk::ConvHArgs a = conv_h_args(c, dt, src, n, op.in, op.d, op.relu, op.dst, op.out, to_logits, net->zero_page);
                 SK_HIP(sk::launch_conv_h(a, stream));
             } else if (op.kind == 1) {
-                SK_HIP(sk::launch_maxpool_h(src, op.dst, nullptr, dt, (long)n * ((op.in.c + 7) / 8), op.in.h, op.in.w,
+                SK_HIP(sk::launch_maxpool_h(src, op.dst, net->training ? net->taps[opi] : nullptr, dt, (long)n * ((op.in.c + 7) / 8), op.in.h, op.in.w,
                                             op.out.h, op.out.w, op.k, op.d, op.s, stream));
             } else if (op.kind == 2) {
                 const UpParams &u = net->ups[op.param];
@@ -637,11 +646,86 @@ sk_status unet_forward(unet_t *net, const float *image_dev, float *prob_dev, voi
         }
     }
     SK_HIP(sk::launch_softmax_f32(net->logits, prob_dev, n, net->out_dims.c, net->out_dims.h * net->out_dims.w, stream));
-    if (net->training)
+    if (net->training && dt == SK_F32)          // (16-bit plans keep the image in their first buffer, in the octet layout)
         SK_HIP(hipMemcpyAsync(net->image_copy, image_dev, sizeof(float) * (size_t)n * net->c_in * net->h_in * net->w_in,
                               hipMemcpyDeviceToDevice, stream));
     net->forward_done = true;
     net->backward_done = false;
+    return SK_OK;
+}
+
+// The backward pass on the 16-bit octet layout: the same walk as the fp32 one below, with 16-bit error maps (fp32
+// sums inside every kernel, fp32 weight gradients).  The ReLU mask of a convolution's output is applied by whichever
+// kernel writes the last contribution to that map's gradient (data gradient, pool gradient or up-convolution gradient).
+static sk_status backward_h(unet_t *net, const int32_t *labels_dev, float *loss_dev, hipStream_t stream)
+{
+    const int n = net->n, dt = net->dtype;
+    const Dims &o = net->out_dims;
+    const bool direct = sk::softmax_loss_writes_octets(o.c, o.h * o.w);
+    SK_HIP(sk::launch_softmax_loss_f32(net->logits, labels_dev, net->grad_of[net->logits], loss_dev, net->loss_partial, n, o.c, o.h * o.w,
+                                       stream, direct ? net->dz16 : nullptr, direct ? dt : 0));
+    if (!direct) SK_HIP(sk::launch_pad_pack_h(net->grad_of[net->logits], net->dz16, dt, n, o.c, o.h, o.w, 0, 0, o.h, o.w, 0, stream));
+    std::set<const float *> written;          // gradient buffers that already hold a contribution
+    written.insert(net->logits);
+    const float *image16 = net->ops[0].dst;   // the image in the octet layout: needs no gradient
+    auto relu_of = [&](const float *buf) -> const float * { return net->relu_out.count(buf) ? buf : nullptr; };
+    for (size_t opi = net->ops.size(); opi-- > 1;) {
+        const auto &op = net->ops[opi];
+        float *gsrc = op.src != image16 ? net->grad_of[op.src] : nullptr;
+        if (op.kind == 0) {
+            ConvParams &c = net->convs[op.param];
+            const float *g = op.dst == net->logits ? net->dz16 : net->grad_of[op.dst];
+            SK_HIP(sk::launch_wgrad_h(op.src, g, c.dw, c.db, net->wgrad_scratch, dt, n, op.in.c, op.in.h, op.in.w, c.c_out, c.k, op.d, stream, 0,
+                                      net->zero_page));
+            if (!gsrc) continue;
+            if (written.count(op.src)) return fail(SK_EUNSUPPORTED, "unet_backward: a map that feeds a convolution and another layer");
+            sk::ConvHArgs a{};
+            a.x = g; a.wp = c.wp16_bwd; a.bias = nullptr; a.mask = relu_of(op.src); a.y = gsrc; a.dtype = dt; a.zeros = net->zero_page;
+            a.n = n; a.c8_in = (op.out.c + 7) / 8; a.H = op.out.h; a.W = op.out.w;
+            a.c_out = op.in.c; a.c8_out = (op.in.c + 7) / 8;
+            a.k = c.k; a.d = op.d; a.in_off = (c.k - 1) * op.d; a.Ho = op.in.h; a.Wo = op.in.w; a.relu = 0; a.out_f32 = 0;
+            a.c8_out_total = (op.in.c + 7) / 8; a.o8_off = 0; a.OH = op.in.h; a.OW = op.in.w;
+            a.oy_mul = 1; a.oy_off = 0; a.ox_mul = 1; a.ox_off = 0;
+            SK_HIP(sk::launch_conv_h(a, stream));
+            written.insert(op.src);
+        } else if (op.kind == 1) {
+            const float *g = net->grad_of[op.dst];
+            const int acc = written.count(op.src) ? 1 : 0;
+            const long planes8 = (long)n * ((op.in.c + 7) / 8);
+            if (op.s == 1) {
+                if (acc) return fail(SK_EUNSUPPORTED, "unet_backward: a map that feeds a stride-1 pool and another layer");
+                SK_HIP(sk::launch_maxpool_bwd_h(g, net->taps[opi], relu_of(op.src), gsrc, dt, planes8, op.in.h, op.in.w, op.out.h, op.out.w, op.k,
+                                                op.d, stream));
+            } else {
+                SK_HIP(sk::launch_maxpool_stride_bwd_h(g, net->taps[opi], relu_of(op.src), gsrc, dt, planes8, op.in.h, op.in.w, op.out.h, op.out.w,
+                                                       op.k, acc, stream));
+            }
+            written.insert(op.src);
+        } else if (op.kind == 2) {
+            UpParams &u = net->ups[op.param];
+            const float *gm = net->grad_of[op.dst];       // gradient of the merged buffer: the up path is its first c_out maps
+            SK_HIP(sk::launch_space_to_depth2_h(gm, net->s2d, n, (op.out.c + 7) / 8, u.c_out / 8, op.in.h, op.in.w, stream));
+            SK_HIP(sk::launch_wgrad_h(op.src, net->s2d, u.cat.dw, u.cat.db, net->wgrad_scratch, dt, n, u.c_in, op.in.h, op.in.w, 4 * u.c_out, 1, 1,
+                                      stream, 0, net->zero_page));
+            if (written.count(op.src)) return fail(SK_EUNSUPPORTED, "unet_backward: a map that feeds an up-convolution and another layer");
+            sk::ConvHArgs a{};
+            a.x = net->s2d; a.wp = u.cat.wp16_bwd; a.bias = nullptr; a.mask = relu_of(op.src); a.y = gsrc; a.dtype = dt; a.zeros = net->zero_page;
+            a.n = n; a.c8_in = 4 * u.c_out / 8; a.H = op.in.h; a.W = op.in.w;
+            a.c_out = u.c_in; a.c8_out = (u.c_in + 7) / 8;
+            a.k = 1; a.d = 1; a.in_off = 0; a.Ho = op.in.h; a.Wo = op.in.w; a.relu = 0; a.out_f32 = 0;
+            a.c8_out_total = (u.c_in + 7) / 8; a.o8_off = 0; a.OH = op.in.h; a.OW = op.in.w;
+            a.oy_mul = 1; a.oy_off = 0; a.ox_mul = 1; a.ox_off = 0;
+            SK_HIP(sk::launch_conv_h(a, stream));
+            written.insert(op.src);
+        } else if (op.kind == 3) {
+            if (!net->merge_backward) continue;    // backwarding enabled for the up path only
+            if (written.count(op.src)) return fail(SK_EUNSUPPORTED, "unet_backward: MergeCrop must be the last consumer of its skip map");
+            // (the pool that also reads the skip map adds its gradient afterwards and applies the map's ReLU mask to the sum)
+            SK_HIP(sk::launch_place_h(net->grad_of[op.dst], gsrc, n, op.src_maps / 8, op.in.h, op.in.w, (op.out.c + 7) / 8, op.o_off / 8,
+                                      op.out.h, op.out.w, op.crop, (op.in.w - op.out.w) / 2, stream));
+            written.insert(op.src);
+        }
+    }
     return SK_OK;
 }
 
@@ -664,6 +748,11 @@ sk_status unet_backward(unet_t *net, const int32_t *labels_dev, float *loss_dev,
     net->last_stream = stream;
     const int n = net->n;
     const Dims &o = net->out_dims;
+    if (net->dtype != SK_F32) {
+        SK_TRY(backward_h(net, labels_dev, loss_dev, stream));
+        net->backward_done = true;
+        return SK_OK;
+    }
     SK_HIP(sk::launch_softmax_loss_f32(net->logits, labels_dev, net->grad_of[net->logits], loss_dev, net->loss_partial, n, o.c,
                                        o.h * o.w, stream));
     std::set<const float *> written;          // gradient buffers that already hold a contribution
@@ -826,6 +915,29 @@ sk_status unet_sgd_step(unet_t *net, float lr, float momentum, float weight_deca
             SK_HIP(hipMemcpyAsync(u.tap[t].w_dev, u.cat.w_dev + (size_t)t * u.c_out * u.c_in, sizeof(float) * u.c_out * u.c_in,
                                   hipMemcpyDeviceToDevice, stream));
         }
+    }
+    if (net->dtype != SK_F32) {
+        // 16-bit plans: the forward and data-gradient packings in the storage type
+        sk::PackHJob hj[sk::BATCH_MAX];
+        int nh = 0;
+        auto pack_h = [&](const ConvParams &c, bool bwd) -> sk_status {
+            for (int f = 0; f < (bwd && c.wp16_bwd ? 2 : 1); ++f) {
+                hj[nh++] = f == 0 ? sk::PackHJob{c.w_dev, c.wp16_fwd, c.c_out, c.c_in, c.k, 0, c.mt16}
+                                  : sk::PackHJob{c.w_dev, c.wp16_bwd, c.c_out, c.c_in, c.k, 1, 0};
+                if (nh == sk::BATCH_MAX) {
+                    SK_HIP(sk::launch_pack_weights_h_batch(hj, nh, net->dtype, stream));
+                    nh = 0;
+                }
+            }
+            return SK_OK;
+        };
+        for (auto &u : net->ups) {
+            for (int t = 0; t < 4; ++t) SK_TRY(pack_h(u.tap[t], false));
+            SK_TRY(pack_h(u.cat, true));
+        }
+        for (auto &c : net->convs) SK_TRY(pack_h(c, true));
+        if (nh > 0) SK_HIP(sk::launch_pack_weights_h_batch(hj, nh, net->dtype, stream));
+        return SK_OK;
     }
     for (auto &u : net->ups) {
         for (int t = 0; t < 4; ++t) SK_TRY(pack(u.tap[t], false));
