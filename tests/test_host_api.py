@@ -143,12 +143,14 @@ def test_usknet_handle_host_logic(golden_rows):
     assert e.value.status_name == "SK_EUNSUPPORTED"
 
 
-def test_unet_training_plan_is_fp32_only():
-    net = B.UNet(1, 2, depth=2, base_ch=8, dtype="bf16")
-    with pytest.raises(B.SknetError) as e:
-        net.plan(1, 60, 60, training=True)      # refused before anything is allocated
-    assert e.value.status_name == "SK_EUNSUPPORTED"
-    net.close()
+def test_unet_training_plan_checks_the_shape_before_anything_is_allocated():
+    # 16-bit and fp32 training plans alike: an image whose maps cannot be pooled is refused on the host
+    for dtype in ("bf16", "f32"):
+        net = B.UNet(1, 2, depth=2, base_ch=8, dtype=dtype)
+        with pytest.raises(B.SknetError) as e:
+            net.plan(1, 62, 62, training=True)      # 62 - 4 = 58 -> 29 - 4 = 25: odd at the second pool
+        assert e.value.status_name == "SK_ESHAPE"
+        net.close()
 
 
 def test_sknet3d_handle_host_logic():
