@@ -12,7 +12,7 @@ A step is one such pass over one synthetic image that is resident in HBM before 
 --workload c5 / c5bf16 : U-Net forward on one 572x572 image (configs[4]) in fp32 / bf16
 --workload papersk / paperskbf16, usk / uskbf16 : the paper's own SK-Net (128^2 tile) and USK-Net (692^2), fp32 / bf16
 --workload sk3d / sk3dbf16 / sk3dtrain : 3-D SK net on a stack of 81 sections of 145x145 (Section 5.2.2), fp32 (bf16: forward)
---workload unettrain / usktrain : U-Net / USK-Net training step, fp32 (unettrainbf16 / usktrainbf16: bf16 storage)
+--workload unettrain / usktrain : U-Net / USK-Net training step, fp32 (unettrainbf16 / usktrainbf16 / sk3dtrainbf16: bf16 storage)
 --workload copy    : only the streaming-copy probe on 2 x 1 GiB (the known-size kernel that the HBM
                      byte counters of a profiler run are calibrated against)
 The default run also appends short measurements of the other workloads under "extras" (skip with --no-extras).
@@ -431,13 +431,13 @@ def measure_sknet3d(torch, B, S, steps, warmup, dtype="f32"):
             "gflop": round(gflop, 1), "tflops": round(gflop / dt / 1e3, 1)}
 
 
-def measure_sknet3d_train(torch, B, S, steps, warmup):
+def measure_sknet3d_train(torch, B, S, steps, warmup, dtype="f32"):
     """One training step of the 3-D SK net of measure_sknet3d on the same volume: forward on a training plan,
-    masked softmax loss, backward, SGD."""
+    masked softmax loss, backward, SGD; dtype = storage type of activations and error maps."""
     import numpy as np
     layers = S.sknet3d_layers(classes=2)
     ws, bs = S.he_normal_weights3d(layers, 1, 1100)
-    net = B.SKNet3D(layers, 1, 2)
+    net = B.SKNet3D(layers, 1, 2, dtype=dtype)
     for i, (w, b) in enumerate(zip(ws, bs)):
         net.set_weights(i, w, b)
     dz, h, w = 81, 145, 145
@@ -531,7 +531,7 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", choices=["c2", "c3", "c4", "c3train", "c5", "c5bf16", "usk", "uskbf16", "papersk", "paperskbf16", "sk3d", "sk3dbf16", "sk3dtrain",
-                                           "unettrain", "usktrain", "unettrainbf16", "usktrainbf16", "copy"], default="c2")
+                                           "unettrain", "usktrain", "unettrainbf16", "usktrainbf16", "sk3dtrainbf16", "copy"], default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
     args = ap.parse_args()
@@ -579,11 +579,11 @@ def main():
         print(json.dumps(out))
         return
 
-    if args.workload in ("usk", "uskbf16", "papersk", "paperskbf16", "sk3d", "sk3dbf16", "sk3dtrain"):
+    if args.workload in ("usk", "uskbf16", "papersk", "paperskbf16", "sk3d", "sk3dbf16", "sk3dtrain", "sk3dtrainbf16"):
         wdt = "bf16" if args.workload.endswith("bf16") else "f32"
-        if args.workload == "sk3dtrain":
-            r = measure_sknet3d_train(torch, B, S, args.steps, args.warmup)
-            px, what = r["labelled_voxels_per_s"], "3-D SK net training step, 81x145x145 -> 64x128x128 labels, fp32: forward, masked softmax loss, backward, SGD; value = labelled voxels per second"
+        if args.workload in ("sk3dtrain", "sk3dtrainbf16"):
+            r = measure_sknet3d_train(torch, B, S, args.steps, args.warmup, wdt)
+            px, what = r["labelled_voxels_per_s"], "3-D SK net training step, 81x145x145 -> 64x128x128 labels, %s: forward, masked softmax loss, backward, SGD; value = labelled voxels per second" % wdt
         elif args.workload in ("sk3d", "sk3dbf16"):
             r = measure_sknet3d(torch, B, S, args.steps, args.warmup, wdt)
             px, what = r["labelled_voxels_per_s"], "3-D SK net forward, 81x145x145 -> 2x64x128x128 (context 17), %s; value = labelled voxels per second" % wdt
@@ -659,6 +659,7 @@ def main():
         extras["sknet3d_81x145x145_f32_forward"] = measure_sknet3d(torch, B, S, 5, 2)
         extras["sknet3d_81x145x145_bf16_forward"] = measure_sknet3d(torch, B, S, 5, 2, "bf16")
         extras["sknet3d_81x145x145_f32_train_step"] = measure_sknet3d_train(torch, B, S, 3, 1)
+        extras["sknet3d_81x145x145_bf16_train_step"] = measure_sknet3d_train(torch, B, S, 3, 1, "bf16")
         extras["unet_572_f32_train_step"] = measure_unet_train(torch, B, S, "unet", 3, 1)
         extras["usknet_692_f32_train_step"] = measure_unet_train(torch, B, S, "usk", 3, 1)
         extras["unet_572_bf16_train_step"] = measure_unet_train(torch, B, S, "unet", 3, 1, "bf16")

@@ -318,11 +318,11 @@ sk_status unet_get_activation(unet_t *net, const char *stage, float *nchw_host, 
  * [depth][maps][height][width] fp32 -- a stack of multi-map 2-D sections; for one input map that is the
  * plain [depth][height][width] image stack.  Weights are [f_out][f_in][k][k][k] (depth, height, width taps). */
 sk_status sknet3d_create(const sk_layer *layers, int32_t n_layers, int32_t c_in, int32_t n_classes, sknet3d_t **out);
-/* The same with the storage type of the activations: SK_F32 (what sknet3d_create builds), or SK_BF16 / SK_F16 for
- * the forward pass (inference plans, modes 0 and 2): activations in the 16-bit slice-major octet layout inside the
- * library, fp32 accumulation, fp32 volumes and probabilities at this interface as before; the net must end in a
- * convolution.  SK_EUNSUPPORTED for a convolution the 16-bit kernels have no variant for (see sknet_create);
- * sknet3d_plan refuses a training plan for such a net. */
+/* The same with the storage type of the activations: SK_F32 (what sknet3d_create builds), or SK_BF16 / SK_F16:
+ * activations (and, on a training plan, error maps) in the 16-bit slice-major octet layout inside the library, fp32
+ * accumulation, fp32 weight gradients and master weights, fp32 volumes and probabilities at this interface as before;
+ * the net must end in a convolution.  SK_EUNSUPPORTED for a convolution the 16-bit kernels have no variant for (see
+ * sknet_create).  As in the 2-D nets, fp16 error maps carry the loss's 1 / (labelled voxels) unscaled. */
 sk_status sknet3d_create_dtype(const sk_layer *layers, int32_t n_layers, int32_t c_in, int32_t n_classes, sk_dtype dtype, sknet3d_t **out);
 void sknet3d_destroy(sknet3d_t *net);
 /* *v = sum of (k-1)*d over the layers (SK_ESHAPE if a pool has s != 1). */

@@ -1319,7 +1319,7 @@ hipError_t launch_conv_h(const ConvHArgs &a, hipStream_t stream)
 {
     if (!conv_h_supported(a.k, a.d) || a.Ho < 1 || a.Wo < 1 || a.c8_in < 1 || a.c_out < 1) return hipErrorInvalidValue;
     if (a.xb8 < 0 || a.grp8 < 0 || a.skip8 < 0 || (a.grp8 > 0 && a.c8_in % a.grp8 != 0) || (a.grp8 == 0 && a.skip8 != 0)) return hipErrorInvalidValue;
-    if ((a.xb8 || a.grp8) && (a.vpool || a.hd || a.in_off)) return hipErrorInvalidValue;      // slices as images: plain forward launches only
+    if ((a.xb8 || a.grp8) && (a.vpool || a.hd)) return hipErrorInvalidValue;      // slices as images: no pool work inside the launch
     if ((a.vpool || a.hd) && (a.mt > 0 && a.mt != conv_h_mt(a.c_out, a.k))) return hipErrorInvalidValue;
     if ((a.vpool || a.hd) && !conv_h_pool_fusable(a.k, a.d, a.c_out, a.c8_in, a.Ho, a.hd)) return hipErrorInvalidValue;
     if (a.tap_maps != 0 && (a.tap_maps < 16 || a.tap_maps % 16 != 0 || a.c_out != 4 * a.tap_maps || a.mask || a.out_f32 || a.oy_mul != 2 ||

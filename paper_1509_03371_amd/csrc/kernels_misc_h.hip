@@ -263,10 +263,11 @@ hipError_t launch_maxpool_h(const void *x, void *y, void *tap, int dtype, long p
 }
 
 // ---- 3-D max pooling on the slice-major octet layout [D][C8][H][W][8] (Section 5.2.2) -----------------------
-// Y[z][o8][y][x] = max over the k^3 taps X[s z + a d][o8][s y + i d][s x + j d]; forward only (no winner codes).
+// Y[z][o8][y][x] = max over the k^3 taps X[s z + a d][o8][s y + i d][s x + j d]; tap (optional, laid out like y, one
+// byte per element): the winner's code (a k + i) k + j, the first maximum in that scan order.
 // grid: x = column blocks, y = output row, z = (output slice, octet)
 template <int DT>
-__global__ void maxpool3d_h_kernel(const uint4v *x, uint4v *y, int C8, int H, int W, int Ho, int Wo, int k, int d, int s)
+__global__ void maxpool3d_h_kernel(const uint4v *x, uint4v *y, uint2v *tap, int C8, int H, int W, int Ho, int Wo, int k, int d, int s)
 {
     const int xx = blockIdx.x * blockDim.x + threadIdx.x, yy = blockIdx.y;
     if (xx >= Wo) return;
@@ -275,11 +276,12 @@ __global__ void maxpool3d_h_kernel(const uint4v *x, uint4v *y, int C8, int H, in
     const uint4v *src = x + ((long)s * zo * C8 + o8) * plane + (long)s * yy * W + (long)s * xx;
     const uint4v first = src[0];
     float best[8];
-    unsigned bits[8];
+    unsigned bits[8], code[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         bits[e] = elem16(first, e);
         best[e] = up16<DT>(bits[e]);
+        code[e] = 0;
     }
     for (int a = 0; a < k; ++a)
         for (int i = 0; i < k; ++i)
@@ -289,28 +291,155 @@ __global__ void maxpool3d_h_kernel(const uint4v *x, uint4v *y, int C8, int H, in
                 for (int e = 0; e < 8; ++e) {
                     const unsigned b16 = elem16(u, e);
                     const float v = up16<DT>(b16);
-                    if (v > best[e]) {
+                    if (v > best[e]) {          // strictly greater: the first maximum wins
                         best[e] = v;
                         bits[e] = b16;
+                        code[e] = (a * k + i) * k + j;
                     }
                 }
             }
-    y[((long)blockIdx.z * Ho + yy) * Wo + xx] =
-        uint4v{bits[0] | (bits[1] << 16), bits[2] | (bits[3] << 16), bits[4] | (bits[5] << 16), bits[6] | (bits[7] << 16)};
+    const long q = ((long)blockIdx.z * Ho + yy) * Wo + xx;
+    y[q] = uint4v{bits[0] | (bits[1] << 16), bits[2] | (bits[3] << 16), bits[4] | (bits[5] << 16), bits[6] | (bits[7] << 16)};
+    if (tap)
+        tap[q] = uint2v{code[0] | (code[1] << 8) | (code[2] << 16) | (code[3] << 24),
+                        code[4] | (code[5] << 8) | (code[6] << 16) | (code[7] << 24)};
 }
 
-hipError_t launch_maxpool3d_h(const void *x, void *y, int dtype, int C, int D, int H, int W, int Do, int Ho, int Wo, int k, int d, int s,
-                              hipStream_t stream)
+// Gather form of the 3-D pool gradient (s = 1) on the slice-major octet layout: input unit (z, u, v) of octet o8 collects,
+// per map, dY of the windows whose recorded winner it is; fp32 sums, rounded once; relu_src as in the 2-D kernel.
+// grid: x = column blocks, y = input row, z = (input slice, octet)
+template <int DT>
+__global__ void maxpool3d_bwd_h_kernel(const uint4v *__restrict__ dy, const uint2v *__restrict__ tap, const uint4v *__restrict__ relu_src,
+                                       uint4v *__restrict__ dx, int C8, int H, int W, int Do, int Ho, int Wo, int k, int d)
+{
+    const int v = blockIdx.x * blockDim.x + threadIdx.x, u = blockIdx.y;
+    if (v >= W) return;
+    const int z = blockIdx.z / C8, o8 = blockIdx.z - z * C8;
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+    for (int a = 0; a < k; ++a) {
+        const int zo = z - a * d;
+        if (zo < 0 || zo >= Do) continue;
+        for (int i = 0; i < k; ++i) {
+            const int yo = u - i * d;
+            if (yo < 0 || yo >= Ho) continue;
+            for (int j = 0; j < k; ++j) {
+                const int xo = v - j * d;
+                if (xo < 0 || xo >= Wo) continue;
+                const long o = (((long)zo * C8 + o8) * Ho + yo) * Wo + xo;
+                const uint2v c = tap[o];
+                const uint4v g = dy[o];
+                const unsigned want = (unsigned)((a * k + i) * k + j);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const unsigned code = (c[e >> 2] >> ((e & 3) * 8)) & 0xffu;
+                    if (code == want) acc[e] += up16<DT>(elem16(g, e));
+                }
+            }
+        }
+    }
+    const long q = ((long)blockIdx.z * H + u) * W + v;
+    uint4v rs = uint4v{0u, 0u, 0u, 0u};
+    if (relu_src) rs = relu_src[q];
+    unsigned hv[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        float t = acc[e];
+        if (relu_src && !(up16<DT>(elem16(rs, e)) > 0.f)) t = 0.f;
+        hv[e] = down16<DT>(t);
+    }
+    dx[q] = uint4v{hv[0] | (hv[1] << 16), hv[2] | (hv[3] << 16), hv[4] | (hv[5] << 16), hv[6] | (hv[7] << 16)};
+}
+
+hipError_t launch_maxpool3d_bwd_h(const void *dy, const void *tap, const void *relu_src, void *dx, int dtype, int C, int D, int H, int W,
+                                  int Do, int Ho, int Wo, int k, int d, hipStream_t stream)
+{
+    const int C8 = (C + 7) / 8;
+    if (H > 65535 || (long)D * C8 > 65535 || (dtype != 1 && dtype != 2) || k < 1 || k > 6) return hipErrorInvalidValue;
+    if (Do != D - (k - 1) * d || Ho != H - (k - 1) * d || Wo != W - (k - 1) * d || Do < 1 || Ho < 1 || Wo < 1) return hipErrorInvalidValue;
+    const dim3 grid((W + 255) / 256, H, (unsigned)(D * C8));
+    const uint4v *g = static_cast<const uint4v *>(dy), *rs = static_cast<const uint4v *>(relu_src);
+    const uint2v *tp = static_cast<const uint2v *>(tap);
+    uint4v *out = static_cast<uint4v *>(dx);
+    if (dtype == 1) hipLaunchKernelGGL(maxpool3d_bwd_h_kernel<1>, grid, dim3(256), 0, stream, g, tp, rs, out, C8, H, W, Do, Ho, Wo, k, d);
+    else hipLaunchKernelGGL(maxpool3d_bwd_h_kernel<2>, grid, dim3(256), 0, stream, g, tp, rs, out, C8, H, W, Do, Ho, Wo, k, d);
+    return hipGetLastError();
+}
+
+// winner codes of a 3-D pool on the octet layout -> flat offsets ((z_in*H + y_in)*W + x_in) inside the map's input
+// volume, int32 [Do][C][Ho][Wo] (for the parity accessor)
+__global__ void tap3d_to_index_h_kernel(const uint2v *tap, int32_t *idx, int C, int Do, int Ho, int Wo, int H, int W, int k, int d, int s,
+                                        long total)
+{
+    const int C8 = (C + 7) / 8;
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
+        const int xo = (int)(q % Wo);
+        long t = q / Wo;
+        const int yo = (int)(t % Ho);
+        t /= Ho;
+        const int c = (int)(t % C), zo = (int)(t / C);
+        const uint2v w = tap[(((long)zo * C8 + (c >> 3)) * Ho + yo) * Wo + xo];
+        const int e = c & 7;
+        const int code = (int)((w[e >> 2] >> ((e & 3) * 8)) & 0xffu);
+        const int j = code % k, i = (code / k) % k, a = code / (k * k);
+        idx[q] = (int32_t)((((long)s * zo + a * d) * H + s * yo + i * d) * W + s * xo + j * d);
+    }
+}
+
+hipError_t launch_tap3d_to_index_h(const void *tap, int32_t *idx, int C, int Do, int Ho, int Wo, int H, int W, int k, int d, int s,
+                                   hipStream_t stream)
+{
+    const long total = (long)C * Do * Ho * Wo;
+    hipLaunchKernelGGL(tap3d_to_index_h_kernel, dim3(grid_for(total)), dim3(256), 0, stream, static_cast<const uint2v *>(tap), idx, C, Do, Ho, Wo,
+                       H, W, k, d, s, total);
+    return hipGetLastError();
+}
+
+// A 3-D kernel [o][c][a][i][j] (fp32 master) as the OIHW master of the 2-D convolution that computes it on the slice-major
+// octet layout.  Forward (bwd = 0): out[o][a * C8*8 + c][i][j] = w[o][c][a][i][j] (c_out x k*C8*8 maps; the maps an octet pads
+// stay zero).  Data gradient (bwd = 1): out[a' * O8*8 + o][c][i][j] = w[o][c][k-1-a'][i][j] (k*O8*8 x c_in maps), which the
+// 2-D data-gradient packing then flips in the plane and transposes.
+__global__ void expand_taps3d_kernel(const float *__restrict__ w, float *__restrict__ out, int c_out, int c_in, int k, int bwd, long total)
+{
+    const int kk = k * k, C8 = (c_in + 7) / 8 * 8, O8 = (c_out + 7) / 8 * 8;
+    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < total; q += (long)gridDim.x * blockDim.x) {
+        const int r = (int)(q % kk);
+        long t = q / kk;
+        float v = 0.f;
+        if (!bwd) {
+            const int m = (int)(t % (k * C8)), o = (int)(t / (k * C8));
+            const int a = m / C8, c = m - a * C8;
+            if (c < c_in) v = w[(((long)o * c_in + c) * k + a) * kk + r];
+        } else {
+            const int c = (int)(t % c_in), m = (int)(t / c_in);
+            const int a = m / O8, o = m - a * O8;
+            if (o < c_out) v = w[(((long)o * c_in + c) * k + (k - 1 - a)) * kk + r];
+        }
+        out[q] = v;
+    }
+}
+
+hipError_t launch_expand_taps3d(const float *w, float *out, int c_out, int c_in, int k, int bwd, hipStream_t stream)
+{
+    if (c_out < 1 || c_in < 1 || k < 1) return hipErrorInvalidValue;
+    const long total = bwd ? (long)k * ((c_out + 7) / 8 * 8) * c_in * k * k : (long)c_out * k * ((c_in + 7) / 8 * 8) * k * k;
+    hipLaunchKernelGGL(expand_taps3d_kernel, dim3(grid_for(total)), dim3(256), 0, stream, w, out, c_out, c_in, k, bwd, total);
+    return hipGetLastError();
+}
+
+hipError_t launch_maxpool3d_h(const void *x, void *y, void *tap, int dtype, int C, int D, int H, int W, int Do, int Ho, int Wo, int k, int d,
+                              int s, hipStream_t stream)
 {
     const int C8 = (C + 7) / 8;
     if (Ho > 65535 || (long)Do * C8 > 65535 || (dtype != 1 && dtype != 2) || D < 1) return hipErrorInvalidValue;
     const dim3 grid((Wo + 255) / 256, Ho, (unsigned)(Do * C8));
     if (dtype == 1)
-        hipLaunchKernelGGL(maxpool3d_h_kernel<1>, grid, dim3(256), 0, stream, static_cast<const uint4v *>(x), static_cast<uint4v *>(y), C8, H, W, Ho,
-                           Wo, k, d, s);
+        hipLaunchKernelGGL(maxpool3d_h_kernel<1>, grid, dim3(256), 0, stream, static_cast<const uint4v *>(x), static_cast<uint4v *>(y),
+                           static_cast<uint2v *>(tap), C8, H, W, Ho, Wo, k, d, s);
     else
-        hipLaunchKernelGGL(maxpool3d_h_kernel<2>, grid, dim3(256), 0, stream, static_cast<const uint4v *>(x), static_cast<uint4v *>(y), C8, H, W, Ho,
-                           Wo, k, d, s);
+        hipLaunchKernelGGL(maxpool3d_h_kernel<2>, grid, dim3(256), 0, stream, static_cast<const uint4v *>(x), static_cast<uint4v *>(y),
+                           static_cast<uint2v *>(tap), C8, H, W, Ho, Wo, k, d, s);
     return hipGetLastError();
 }
 

@@ -207,8 +207,15 @@ hipError_t launch_maxpool_bwd_f32(const float *dy, const uint8_t *tap, const flo
 // 3-D pool on the slice-major layout X[D][C][H][W] -> Y[Do][C][Ho][Wo]; k, d, s act on the three axes alike;
 // tap (optional, k <= 6) receives the winner's code (a*k + i)*k + j, first maximum in (a, i, j) order
 // the same on the 16-bit slice-major octet layout [D][ceil(C/8)][H][W][8], forward only
-hipError_t launch_maxpool3d_h(const void *x, void *y, int dtype, int C, int D, int H, int W, int Do, int Ho, int Wo, int k, int d, int s,
-                              hipStream_t stream);
+// tap (optional): one byte per element laid out like y, the winner's code (a k + i) k + j
+hipError_t launch_maxpool3d_h(const void *x, void *y, void *tap, int dtype, int C, int D, int H, int W, int Do, int Ho, int Wo, int k, int d,
+                              int s, hipStream_t stream);
+hipError_t launch_maxpool3d_bwd_h(const void *dy, const void *tap, const void *relu_src, void *dx, int dtype, int C, int D, int H, int W,
+                                  int Do, int Ho, int Wo, int k, int d, hipStream_t stream);
+hipError_t launch_tap3d_to_index_h(const void *tap, int32_t *idx, int C, int Do, int Ho, int Wo, int H, int W, int k, int d, int s,
+                                   hipStream_t stream);
+// a 3-D kernel's fp32 master as the OIHW master of the 2-D convolution over (depth tap, map) pairs; bwd = 1: of its data gradient
+hipError_t launch_expand_taps3d(const float *w, float *out, int c_out, int c_in, int k, int bwd, hipStream_t stream);
 hipError_t launch_maxpool3d_f32(const float *x, float *y, uint8_t *tap, int C, int D, int H, int W, int Do, int Ho, int Wo, int k,
                                 int d, int s, hipStream_t stream);
 // gradient of the s = 1 pool from its winner codes; relu_src (optional, like dx) zeroes the result where it is <= 0

@@ -47,6 +47,8 @@ struct Conv3 {
     float *w_dev = nullptr, *b_dev = nullptr;   // device master (b_dev: n_pad entries, zero padded)
     std::vector<TapRun> fwd, bwd;      // bwd: runs over the flipped taps, for the data gradient
     void *wp16 = nullptr;              // 16-bit nets: the kernel as a 2-D convolution over k * 8*ceil(c_in/8) input maps, packed MFMA fragments
+    void *wp16_bwd = nullptr;          // ... and its data gradient: a 2-D convolution over k * 8*ceil(c_out/8) maps of the zero-padded gradient
+    float *exp2d = nullptr;            // fp32 staging of the two 2-D masters these are packed from
     float *dw = nullptr, *db = nullptr, *vw = nullptr, *vb = nullptr, *dw_tap = nullptr;
     // weight gradient of all depth taps in one launch: k > 1 and (d = 1, the tapped slices adjacent, or a power-of-two
     // map count, which the kernel's grouped addressing needs)
@@ -73,6 +75,8 @@ void release_conv3(Conv3 &c)
 {
     free_dev(c.w_dev); free_dev(c.b_dev);
     if (c.wp16) { (void)hipFree(c.wp16); c.wp16 = nullptr; }
+    if (c.wp16_bwd) { (void)hipFree(c.wp16_bwd); c.wp16_bwd = nullptr; }
+    free_dev(c.exp2d);
     for (auto &r : c.fwd) free_dev(r.wp);
     for (auto &r : c.bwd) free_dev(r.wp);
     c.bwd.clear();
@@ -101,23 +105,28 @@ sk_status upload_conv3(Conv3 &c, hipStream_t stream)
 }
 
 // 16-bit storage: depth tap a of input map c becomes input map a * 8*ceil(c_in/8) + c of a 2-D convolution (the maps an
-// octet pads are zero), packed as the 2-D 16-bit kernels want it
-sk_status upload_conv3_h(Conv3 &c, int dtype)
+// octet pads are zero), packed as the 2-D 16-bit kernels want it; with_bwd: also the data gradient's 2-D convolution
+// over the (flipped depth tap, output map) pairs.  Built on the device from the device master (asynchronous).
+sk_status repack_conv3_h(Conv3 &c, int dtype, bool with_bwd, hipStream_t stream)
 {
-    const int c8 = (c.c_in + 7) / 8, cin2 = c.k * c8 * 8, kk = c.k * c.k;
-    std::vector<float> w2((size_t)c.c_out * cin2 * kk, 0.f);
-    for (int o = 0; o < c.c_out; ++o)
-        for (int ci = 0; ci < c.c_in; ++ci)
-            for (int a = 0; a < c.k; ++a)
-                std::memcpy(&w2[((size_t)o * cin2 + (size_t)a * c8 * 8 + ci) * kk], &c.w[(((size_t)o * c.c_in + ci) * c.k + a) * kk], sizeof(float) * kk);
-    float *tmp = nullptr;
-    SK_TRY(alloc_f(&tmp, (long)w2.size()));
-    hipError_t e = hipMemcpy(tmp, w2.data(), sizeof(float) * w2.size(), hipMemcpyHostToDevice);
-    if (!c.wp16 && e == hipSuccess) e = hipMalloc(&c.wp16, sizeof(unsigned short) * (size_t)sk::packed_h_elems(c.c_out, c.k * c8, c.k));
-    if (e == hipSuccess) e = sk::launch_pack_weights_h(tmp, c.wp16, dtype, c.c_out, cin2, c.k, 0, 0, nullptr);
-    if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
-    free_dev(tmp);
-    if (e != hipSuccess) return fail(SK_EDEVICE, "packing 16-bit weights: %s", hipGetErrorString(e));
+    const int c8 = (c.c_in + 7) / 8, o8 = (c.c_out + 7) / 8, kk = c.k * c.k;
+    const long fwd_floats = (long)c.c_out * c.k * c8 * 8 * kk, bwd_floats = (long)c.k * o8 * 8 * c.c_in * kk;
+    if (!c.exp2d) SK_TRY(alloc_f(&c.exp2d, std::max(fwd_floats, bwd_floats)));
+    if (!c.wp16) SK_HIP(hipMalloc(&c.wp16, sizeof(unsigned short) * (size_t)sk::packed_h_elems(c.c_out, c.k * c8, c.k)));
+    SK_HIP(sk::launch_expand_taps3d(c.w_dev, c.exp2d, c.c_out, c.c_in, c.k, 0, stream));
+    SK_HIP(sk::launch_pack_weights_h(c.exp2d, c.wp16, dtype, c.c_out, c.k * c8 * 8, c.k, 0, 0, stream));
+    if (with_bwd) {
+        if (!c.wp16_bwd) SK_HIP(hipMalloc(&c.wp16_bwd, sizeof(unsigned short) * (size_t)sk::packed_h_elems(c.c_in, c.k * o8, c.k)));
+        SK_HIP(sk::launch_expand_taps3d(c.w_dev, c.exp2d, c.c_out, c.c_in, c.k, 1, stream));
+        SK_HIP(sk::launch_pack_weights_h(c.exp2d, c.wp16_bwd, dtype, c.k * o8 * 8, c.c_in, c.k, 1, 0, stream));
+    }
+    return SK_OK;
+}
+
+sk_status upload_conv3_h(Conv3 &c, int dtype, bool with_bwd = false)
+{
+    SK_TRY(repack_conv3_h(c, dtype, with_bwd, nullptr));
+    SK_HIP(hipStreamSynchronize(nullptr));
     return SK_OK;
 }
 
@@ -161,6 +170,7 @@ struct sknet3d {
     bool fuse_head = false;        // last two 1x1x1 convolutions + softmax as one kernel
     float *head_w1p = nullptr, *zero_page = nullptr;
     float *gbuf[2] = {nullptr, nullptr}, *loss_partial = nullptr, *wgrad_scratch = nullptr;
+    float *dz_f32 = nullptr;       // 16-bit training plans: the loss kernel's fp32 gradient of the logits
     hipStream_t last_stream = nullptr;
     bool half() const { return dtype != SK_F32; }
     const float *last_volume = nullptr;
@@ -175,6 +185,7 @@ struct sknet3d {
         }
         tap.clear();
         free_dev(head_w1p); free_dev(zero_page); free_dev(gbuf[0]); free_dev(gbuf[1]); free_dev(loss_partial); free_dev(wgrad_scratch);
+        free_dev(dz_f32);
         for (auto &c : convs) release_conv3(c);
         planned = training = forward_done = backward_done = false;
         fuse_head = false;
@@ -252,7 +263,8 @@ sk_status run_layer3(sknet3d *net, int li, hipStream_t stream)
         // 16-bit storage, slice-major octet layout: act[0] holds the converted volume
         const int dt = net->dtype, c8 = (in.c + 7) / 8;
         if (l.kind == SK_MAXPOOL) {
-            SK_HIP(sk::launch_maxpool3d_h(net->act[li], y, dt, in.c, in.dz, in.h, in.w, out.dz, out.h, out.w, l.k, l.d, l.s, stream));
+            SK_HIP(sk::launch_maxpool3d_h(net->act[li], y, net->training ? net->tap[li] : nullptr, dt, in.c, in.dz, in.h, in.w, out.dz, out.h,
+                                          out.w, l.k, l.d, l.s, stream));
             return SK_OK;
         }
         // one 2-D launch: the output slices are its images (one input slice apart), the (depth tap, octet) pairs its input octets
@@ -267,7 +279,7 @@ sk_status run_layer3(sknet3d *net, int li, hipStream_t stream)
         a.c8_out_total = (out.c + 7) / 8; a.o8_off = 0; a.OH = out.h; a.OW = out.w;
         a.oy_mul = 1; a.oy_off = 0; a.ox_mul = 1; a.ox_off = 0;
         a.mt = 0;
-        a.xb8 = c8;
+        if (l.k > 1) a.xb8 = c8;
         if (l.k > 1 && l.d > 1) { a.grp8 = c8; a.skip8 = (l.d - 1) * c8; }
         SK_HIP(sk::launch_conv_h(a, stream));
         return SK_OK;
@@ -405,7 +417,7 @@ sk_status sknet3d_set_weights(sknet3d_t *net, int32_t conv_idx, const float *w_h
     if (!b_host)   // keep the device's current biases (an SGD step may have changed them)
         SK_HIP(hipMemcpy(c.b.data(), c.b_dev, sizeof(float) * c.c_out, hipMemcpyDeviceToHost));
     SK_TRY(upload_conv3(c, nullptr));
-    if (net->half()) SK_TRY(upload_conv3_h(c, net->dtype));
+    if (net->half()) SK_TRY(upload_conv3_h(c, net->dtype, c.wp16_bwd != nullptr));
     if (net->fuse_head && conv_idx == (int)net->convs.size() - 2) {
         SK_HIP(sk::launch_pack_head_w1(c.w_dev, net->head_w1p, net->dtype, c.c_out, c.c_in, nullptr));
         SK_HIP(hipStreamSynchronize(nullptr));
@@ -433,7 +445,6 @@ sk_status sknet3d_plan(sknet3d_t *net, int32_t dz, int32_t h, int32_t w, int32_t
     SK_TRY(check3(net));
     if (mode < 0 || mode > 2) return fail(SK_EINVAL, "plan: mode must be 0 (inference), 1 (training) or 2 (inference, every layer kept)");
     const bool training = mode == 1;
-    if (training && net->half()) return fail(SK_EUNSUPPORTED, "plan: 3-D training runs in fp32 storage only");
     std::vector<Dims3> dims;
     SK_TRY(infer3(net, dz, h, w, dims));
     const int L = (int)net->layers.size();
@@ -470,11 +481,14 @@ sk_status sknet3d_plan(sknet3d_t *net, int32_t dz, int32_t h, int32_t w, int32_t
     if (st == SK_OK && half) st = alloc_zero_page(&net->zero_page);
     for (int i = 0; i < L && st == SK_OK && training; ++i) {
         const sk_layer &l = net->layers[i];
-        const long padded = dims[i + 1].count() + 2L * grad_pad(net, i) * dims[i + 1].slice();
+        // (16-bit storage: error maps in the slice-major octet layout, counted in floats; winner codes one byte per element of it)
+        auto slice_floats = [&](const Dims3 &dm) { return half ? (long)((dm.c + 7) / 8) * dm.h * dm.w * 4 : dm.slice(); };
+        const long padded = (dims[i + 1].dz + 2L * grad_pad(net, i)) * slice_floats(dims[i + 1]);
         if (padded > max_grad) max_grad = padded;
-        if (dims[i].count() > max_grad) max_grad = dims[i].count();
+        if (dims[i].dz * slice_floats(dims[i]) > max_grad) max_grad = dims[i].dz * slice_floats(dims[i]);
         if (l.kind == SK_MAXPOOL) {
-            hipError_t e = hipMalloc(reinterpret_cast<void **>(&net->tap[i]), (size_t)dims[i + 1].count());
+            const size_t tap_bytes = half ? (size_t)dims[i + 1].dz * slice_floats(dims[i + 1]) * 2 : (size_t)dims[i + 1].count();
+            hipError_t e = hipMalloc(reinterpret_cast<void **>(&net->tap[i]), tap_bytes);
             if (e != hipSuccess) st = fail(SK_ENOMEM, "plan: winner codes: %s", hipGetErrorString(e));
         } else {
             // one launch over all depth taps (k * C input maps) or one per tap: the larger need
@@ -487,7 +501,9 @@ sk_status sknet3d_plan(sknet3d_t *net, int32_t dz, int32_t h, int32_t w, int32_t
         Conv3 &c = net->convs[net->conv_of_layer[i]];
         st = alloc_conv3(c, training, i > 0);
         if (st == SK_OK) st = upload_conv3(c, nullptr);
-        if (st == SK_OK && half) st = upload_conv3_h(c, net->dtype);
+        if (st == SK_OK && half) st = upload_conv3_h(c, net->dtype, training && i > 0);
+        if (st == SK_OK && half && training && i > 0 && !sk::conv_h_supported(c.k, c.d, c.c_in))
+            st = fail(SK_EUNSUPPORTED, "plan: the data gradient of layer %d is not built for 16-bit storage", i);
     }
     if (st == SK_OK && net->fuse_head) {
         Conv3 &c1 = net->convs[net->conv_of_layer[L - 2]];
@@ -503,6 +519,8 @@ sk_status sknet3d_plan(sknet3d_t *net, int32_t dz, int32_t h, int32_t w, int32_t
         if (st == SK_OK) st = alloc_f(&net->gbuf[1], max_grad);
         if (st == SK_OK) st = alloc_f(&net->loss_partial, sk::softmax_loss_partials(dims[L].count() / dims[L].c));
         if (st == SK_OK) st = alloc_f(&net->wgrad_scratch, (long)scratch);
+        if (st == SK_OK && half) st = alloc_f(&net->dz_f32, dims[L].count());
+        if (st == SK_OK && half && net->layers[L - 1].kind != SK_CONV) st = fail(SK_EUNSUPPORTED, "plan: a 16-bit 3-D net must end in a convolution");
     }
     if (st != SK_OK) {
         net->release_plan();
@@ -527,7 +545,7 @@ sk_status sknet3d_forward(sknet3d_t *net, const float *volume_dev, float *prob_d
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     net->last_stream = stream;
     net->last_volume = volume_dev;
-    if (net->training) {   // the backward pass reads the volume again: keep a copy
+    if (net->training && !net->half()) {   // the backward pass reads the volume again: keep a copy (16-bit plans convert it into act[0] anyway)
         SK_HIP(hipMemcpyAsync(net->act[0], volume_dev, sizeof(float) * net->dims[0].count(), hipMemcpyDeviceToDevice, stream));
         net->last_volume = net->act[0];
     }
@@ -556,6 +574,67 @@ sk_status sknet3d_forward(sknet3d_t *net, const float *volume_dev, float *prob_d
     return SK_OK;
 }
 
+// The backward pass in 16-bit storage: error maps in the slice-major octet layout (fp32 sums in every kernel, fp32 weight
+// gradients).  A convolution's weight gradient is one 2-D launch per depth tap (the input slices shifted by a*d against
+// the output gradient); its data gradient is ONE 2-D launch over the (flipped depth tap, map) pairs of the gradient, which
+// sits between (k-1)d cleared slices, with the ReLU mask of the layer below in the epilogue.
+static sk_status backward3_h(sknet3d *net, const int32_t *labels_dev, float *loss_dev, hipStream_t stream)
+{
+    const int L = (int)net->layers.size(), dt = net->dtype;
+    const Dims3 &o = net->dims[L];
+    auto slice_floats = [](const Dims3 &dm) { return (long)((dm.c + 7) / 8) * dm.h * dm.w * 4; };
+    float *gcur = net->gbuf[0], *gnext = net->gbuf[1];
+    {
+        float *dz16 = gcur + (long)grad_pad(net, L - 1) * slice_floats(o);
+        const bool masked = net->layers[L - 1].relu != 0;
+        const bool direct = !masked && sk::softmax_loss_writes_octets(o.c, o.h * o.w);
+        SK_HIP(sk::launch_softmax_loss_f32(net->act[L], labels_dev, net->dz_f32, loss_dev, net->loss_partial, o.dz, o.c, o.h * o.w, stream,
+                                           direct ? dz16 : nullptr, direct ? dt : 0));
+        if (masked) SK_HIP(sk::launch_relu_mask_f32(net->dz_f32, net->act[L], o.count(), stream));
+        if (!direct) SK_HIP(sk::launch_pad_pack_h(net->dz_f32, dz16, dt, o.dz, o.c, o.h, o.w, 0, 0, o.h, o.w, 0, stream));
+    }
+    for (int li = L - 1; li >= 0; --li) {
+        const sk_layer &l = net->layers[li];
+        const Dims3 &in = net->dims[li], &out = net->dims[li + 1];
+        const int pad = grad_pad(net, li);
+        const long in_slice = slice_floats(in), out_slice = slice_floats(out);
+        const float *g = gcur + (long)pad * out_slice;        // gradient of this layer's output
+        const float *relu_src = (li > 0 && net->layers[li - 1].kind == SK_CONV && net->layers[li - 1].relu) ? net->act[li] : nullptr;
+        float *dst = li > 0 ? gnext + (long)grad_pad(net, li - 1) * in_slice : nullptr;
+        if (l.kind == SK_CONV) {
+            Conv3 &c = net->convs[net->conv_of_layer[li]];
+            for (int a = 0; a < l.k; ++a) {
+                SK_HIP(sk::launch_wgrad_h(net->act[li] + (long)a * l.d * in_slice, g, c.dw_tap, a + 1 == l.k ? c.db : nullptr, net->wgrad_scratch,
+                                          dt, out.dz, in.c, in.h, in.w, c.c_out, l.k, l.d, stream, 0, net->zero_page));
+                SK_HIP(sk::launch_place_tap_f32(c.dw_tap, c.dw, (long)c.c_out * c.c_in, l.k, a, stream));
+            }
+            if (li == 0) break;   // nothing below needs the volume's gradient
+            if (pad > 0) {
+                SK_HIP(sk::launch_fill_f32(gcur, 0.f, (long)pad * out_slice, stream));
+                SK_HIP(sk::launch_fill_f32(gcur + (long)(pad + out.dz) * out_slice, 0.f, (long)pad * out_slice, stream));
+            }
+            const int o8 = (out.c + 7) / 8;
+            sk::ConvHArgs a{};
+            a.zeros = net->zero_page;
+            a.x = gcur; a.wp = c.wp16_bwd; a.bias = nullptr; a.mask = relu_src; a.y = dst; a.dtype = dt;
+            a.n = in.dz; a.c8_in = l.k * o8; a.H = out.h; a.W = out.w;
+            a.c_out = in.c; a.c8_out = (in.c + 7) / 8;
+            a.k = l.k; a.d = l.d; a.in_off = (l.k - 1) * l.d; a.Ho = in.h; a.Wo = in.w; a.relu = 0; a.out_f32 = 0;
+            a.c8_out_total = (in.c + 7) / 8; a.o8_off = 0; a.OH = in.h; a.OW = in.w;
+            a.oy_mul = 1; a.oy_off = 0; a.ox_mul = 1; a.ox_off = 0;
+            a.mt = 0;
+            if (l.k > 1) a.xb8 = o8;
+            if (l.k > 1 && l.d > 1) { a.grp8 = o8; a.skip8 = (l.d - 1) * o8; }
+            SK_HIP(sk::launch_conv_h(a, stream));
+        } else {
+            if (li == 0) break;
+            SK_HIP(sk::launch_maxpool3d_bwd_h(g, net->tap[li], relu_src, dst, dt, in.c, in.dz, in.h, in.w, out.dz, out.h, out.w, l.k, l.d, stream));
+        }
+        float *t = gcur; gcur = gnext; gnext = t;
+    }
+    return SK_OK;
+}
+
 sk_status sknet3d_backward(sknet3d_t *net, const int32_t *labels_dev, float *loss_dev, void *hip_stream)
 {
     SK_TRY(check3(net));
@@ -567,6 +646,11 @@ sk_status sknet3d_backward(sknet3d_t *net, const int32_t *labels_dev, float *los
     const int L = (int)net->layers.size();
     const Dims3 &o = net->dims[L];
     float *gcur = net->gbuf[0], *gnext = net->gbuf[1];
+    if (net->half()) {
+        SK_TRY(backward3_h(net, labels_dev, loss_dev, stream));
+        net->backward_done = true;
+        return SK_OK;
+    }
     {
         float *dz = gcur + (long)grad_pad(net, L - 1) * o.slice();
         SK_HIP(sk::launch_softmax_loss_f32(net->act[L], labels_dev, dz, loss_dev, net->loss_partial, o.dz, o.c, o.h * o.w, stream));
@@ -631,6 +715,8 @@ sk_status sknet3d_sgd_step(sknet3d_t *net, float lr, float momentum, float weigh
     }
     if (sb.n > 0) SK_HIP(sk::launch_sgd_batch_f32(sb, lr, momentum, weight_decay, stream));
     for (auto &c : net->convs) SK_TRY(repack_conv3(c, stream));
+    if (net->half())
+        for (auto &c : net->convs) SK_TRY(repack_conv3_h(c, net->dtype, c.wp16_bwd != nullptr, stream));
     return SK_OK;
 }
 
@@ -683,7 +769,8 @@ sk_status sknet3d_get_pool_argmax(sknet3d_t *net, int32_t pool_idx, int32_t *idx
     if ((long)in.dz * in.h * in.w > 0x7fffffffL) return fail(SK_EUNSUPPORTED, "get_pool_argmax: offsets exceed 32 bits");
     int32_t *tmp = nullptr;
     SK_HIP(hipMalloc(reinterpret_cast<void **>(&tmp), sizeof(int32_t) * (size_t)out.count()));
-    hipError_t e = sk::launch_tap3d_to_index(net->tap[li], tmp, out.c, out.dz, out.h, out.w, in.h, in.w, l.k, l.d, l.s, net->last_stream);
+    hipError_t e = net->half() ? sk::launch_tap3d_to_index_h(net->tap[li], tmp, out.c, out.dz, out.h, out.w, in.h, in.w, l.k, l.d, l.s, net->last_stream)
+                               : sk::launch_tap3d_to_index(net->tap[li], tmp, out.c, out.dz, out.h, out.w, in.h, in.w, l.k, l.d, l.s, net->last_stream);
     if (e == hipSuccess) e = hipStreamSynchronize(net->last_stream);
     if (e == hipSuccess) e = hipMemcpy(idx_host, tmp, sizeof(int32_t) * (size_t)out.count(), hipMemcpyDeviceToHost);
     (void)hipFree(tmp);
