@@ -274,9 +274,12 @@ template <> __device__ __forceinline__ floatx4 mfma32<2>(uint4v a, uint4v b, flo
 {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(halfx8v, a), __builtin_bit_cast(halfx8v, b), c, 0, 0, 0);
 }
-// 8 consecutive 16-bit elements from LDS at an address aligned to RB bytes
-template <int RB> __device__ __forceinline__ uint4v lds_read8(const unsigned short *p)
+// 8 consecutive 16-bit elements from LDS, starting `off` elements into the 4-byte aligned array `base`; base + off is
+// aligned to RB bytes.  RB = 2 (odd kernel strides, 3x3 kernels at d = 1): five aligned 4-byte reads and a funnel
+// shift by 0 or 16 bits per lane instead of eight 2-byte reads.
+template <int RB> __device__ __forceinline__ uint4v lds_read8(const unsigned short *base, int off)
 {
+    const unsigned short *p = base + off;
     if constexpr (RB == 16) return *reinterpret_cast<const uint4v *>(p);
     else if constexpr (RB == 8) {
         const uint2v lo = *reinterpret_cast<const uint2v *>(p), hi = *reinterpret_cast<const uint2v *>(p + 4);
@@ -285,10 +288,11 @@ template <int RB> __device__ __forceinline__ uint4v lds_read8(const unsigned sho
         const unsigned *q = reinterpret_cast<const unsigned *>(p);
         return uint4v{q[0], q[1], q[2], q[3]};
     } else {
-        uint4v r;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) r[e] = (unsigned)p[2 * e] | ((unsigned)p[2 * e + 1] << 16);
-        return r;
+        const unsigned *q = reinterpret_cast<const unsigned *>(base) + (off >> 1);
+        const unsigned sh = (unsigned)(off & 1) * 16u;
+        const unsigned w0 = q[0], w1 = q[1], w2 = q[2], w3 = q[3], w4 = q[4];
+        return uint4v{__builtin_amdgcn_alignbit(w1, w0, sh), __builtin_amdgcn_alignbit(w2, w1, sh), __builtin_amdgcn_alignbit(w3, w2, sh),
+                      __builtin_amdgcn_alignbit(w4, w3, sh)};
     }
 }
 
@@ -444,7 +448,7 @@ __global__ __launch_bounds__(256) void wgrad_h_kernel(WgradArgs a)
             }
 #pragma unroll
             for (int q = 0; q < NB; ++q) {
-                const uint4v bv = lds_read8<RB>(xs + xoff[q] + p);
+                const uint4v bv = lds_read8<RB>(xs, xoff[q] + p);
 #pragma unroll
                 for (int m = 0; m < MB; ++m) acc[m][q] = mfma32<DT>(av[m], bv, acc[m][q]);
             }

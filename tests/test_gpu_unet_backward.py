@@ -197,7 +197,9 @@ def test_unet_backward_state_and_type_errors():
     with pytest.raises(B.SknetError):
         net.get_grad(0)
     net.close()
-    half = B.UNet(1, 2, depth=1, base_ch=8, dtype="bf16")
-    with pytest.raises(B.SknetError):
-        half.plan(1, 28, 28, training=True)                                         # fp32 only
+    half = B.UNet(1, 2, depth=1, base_ch=8, dtype="bf16")                           # the same rules in 16-bit storage
+    half.plan(1, 28, 28, training=True)
+    with pytest.raises(B.SknetError) as e:
+        half.backward(torch.zeros(1, 12, 12, dtype=torch.int32, device="cuda"))
+    assert e.value.status_name == "SK_ESTATE"
     half.close()

@@ -83,6 +83,7 @@ def test_usknet_rejections():
     with pytest.raises(B.SknetError):
         B.USKNet(1, 2, base_ch=12, dtype="bf16")    # 16-bit storage keeps maps in groups of 8
     half = B.USKNet(1, 2, base_ch=8, dtype="bf16")
-    with pytest.raises(B.SknetError):
-        half.plan(1, 182, 182, training=True)       # the training pass of these nets is fp32 only
+    with pytest.raises(B.SknetError) as e:
+        half.plan(1, 183, 182, training=True)       # 16-bit training plans check the shape like every other plan
+    assert e.value.status_name == "SK_ESHAPE"
     half.close()
