@@ -14,44 +14,38 @@ class ConversionError(ValueError):
 
 def convert_sw_to_sk(sw_layers, w0_sw):
     """Return (sk_layers, w_sw, w_sk): converted layers and the per-layer map sizes of both
-    nets when the SK net is fed the SW patch size (so its last size is 1)."""
-    d_temp = 1
-    w_sw, w_sk = [w0_sw], [w0_sw]
-    sk = []
-    for l in sw_layers:
-        t = l["type"]
-        if t == "conv":
-            k = l["k"]
-            sk.append({"type": "conv", "f_out": l["f_out"], "k": k, "d": d_temp,
-                       "relu": l.get("relu", False)})
-            w_sk.append(w_sk[-1] - (k - 1) * d_temp)
-            w_sw.append(w_sw[-1] - (k - 1))
-        elif t == "pool":
-            k = l["k"]
-            if w_sw[-1] % k != 0 or k != l["s"]:
-                raise ConversionError("pooling needs w mod k = 0 and k = s (got w=%d k=%d s=%d)"
-                                      % (w_sw[-1], k, l["s"]))
-            sk.append({"type": "pool", "k": k, "d": d_temp, "s": 1})
-            w_sk.append(w_sk[-1] - (k - 1) * d_temp)
-            w_sw.append(-(-w_sw[-1] // k))
-            d_temp *= k
-        elif t == "ip":
-            k = w_sw[-1]                      # the inner product spans the whole remaining map
-            sk.append({"type": "conv", "f_out": l["f_out"], "k": k, "d": d_temp,
-                       "relu": l.get("relu", False)})
-            w_sk.append(w_sk[-1] - (k - 1) * d_temp)
-            w_sw.append(1)
-            d_temp = 1
+    nets when the SK net is fed the SW patch size (so its last size is 1).
+
+    What Algorithm 1 states, in one walk over the layers: a layer keeps its kernel and takes as kernel
+    stride the product of the pooling strides in front of it (counted from the last inner product, which
+    sees a 1 x 1 map again); a pool loses its layer stride; an inner product is a convolution whose kernel
+    is the whole remaining patch.  Pools must divide their map and have k = s, anything else with a kernel
+    cannot be converted, and the stride product must be back at 1 at the end."""
+    sk, w_sw, w_sk = [], [w0_sw], [w0_sw]
+    spacing = 1                                   # product of the pooling strides since the last inner product
+    for lay in sw_layers:
+        kind, patch = lay["type"], w_sw[-1]
+        if kind in ("conv", "pool", "ip"):
+            k = patch if kind == "ip" else lay["k"]
+            if kind == "pool" and (lay["s"] != k or patch % k != 0):
+                raise ConversionError("pooling needs w mod k = 0 and k = s (got w=%d k=%d s=%d)" % (patch, k, lay["s"]))
+            if kind == "pool":
+                sk.append({"type": "pool", "k": k, "d": spacing, "s": 1})
+            else:
+                sk.append({"type": "conv", "f_out": lay["f_out"], "k": k, "d": spacing, "relu": lay.get("relu", False)})
+            w_sk.append(w_sk[-1] - (k - 1) * spacing)
+            w_sw.append({"conv": patch - (k - 1), "pool": patch // k, "ip": 1}[kind])
+            spacing = {"conv": spacing, "pool": spacing * k, "ip": 1}[kind]
         else:
-            if l.get("k", 1) > 1:
+            if lay.get("k", 1) > 1:
                 raise ConversionError("a layer with k > 1 that is not conv/pool/ip cannot be converted")
-            sk.append(dict(l))
+            sk.append(dict(lay))
             w_sk.append(w_sk[-1])
-            w_sw.append(w_sw[-1])
+            w_sw.append(patch)
         if w_sk[-1] < 1 or w_sw[-1] < 1:
             raise ConversionError("feature map shrank below one pixel")
-    if d_temp != 1:
-        raise ConversionError("kernel stride is %d after the last layer; it must be 1" % d_temp)
+    if spacing != 1:
+        raise ConversionError("kernel stride is %d after the last layer; it must be 1" % spacing)
     return sk, w_sw, w_sk
 
 
