@@ -409,7 +409,7 @@ __global__ __launch_bounds__(CH_THREADS + 64 * NP) void conv_h_ring_kernel(ConvH
     constexpr int RR = R + KS - 1;
     constexpr int OC = MAP4 ? 1 : 4;
     constexpr int CS = MAP4 ? 1 : KS;
-    static_assert(!MAP4 || KS == 4, "the ring kernel maps the four lane groups to the four columns of a 4x4 kernel");
+    static_assert(!MAP4 || KS == 4 || KS == 3, "the ring kernel maps the four lane groups to four kernel columns (a 3x3 kernel leaves the fourth zero)");
     constexpr int ROWS = OC * RR;
     constexpr int RU = (ROWS + LW - 1) / LW;
     constexpr int WUNITS = CS * KS * MT * 64;
@@ -422,7 +422,7 @@ __global__ __launch_bounds__(CH_THREADS + 64 * NP) void conv_h_ring_kernel(ConvH
     // rows from one row tile to the next: R, or (VPOOL on a launch with few tiles per workgroup) R - 1, so that every
     // tile holds the row below its last pooled row itself and nothing is carried from tile to tile
     const int ypitch = VPOOL ? a.ypitch : R;
-    const int PWL = CH_TX + (KS - 1) * d;                      // tile width the multiplication reads
+    const int PWL = CH_TX + (MAP4 ? 3 : KS - 1) * d;           // tile width the multiplication reads
     const int PW = PWL;                                        // staged row pitch
     const int tile_units = ROWS * PW;
     // RESW: the weights of every chunk stay in LDS for the whole kernel (one map group only) and the
@@ -1152,7 +1152,7 @@ template <int KS, int MT, bool MAP4, int R, int S, bool RESW>
 static size_t ring_smem(int d, int c_out, int c8_in, int Ho, int hd = 0)
 {
     constexpr int RR = R + KS - 1, OC = MAP4 ? 1 : 4, CS = MAP4 ? 1 : KS;
-    const int PW = CH_TX + (KS - 1) * d;                       // (a pending pool of the input is finished before the tile is staged)
+    const int PW = CH_TX + (MAP4 ? 3 : KS - 1) * d;            // (a pending pool of the input is finished before the tile is staged)
     (void)hd;
     const size_t tile = (size_t)OC * RR * PW, slab = (size_t)CS * KS * MT * 64;
     const int nchunks = (c8_in + OC - 1) / OC;
@@ -1263,6 +1263,34 @@ static hipError_t launch_conv_h_mt(const ConvHArgs &a, hipStream_t stream)
     }
 }
 
+// 3x3 kernels on a single input octet (the first layer of the U-Net and the USK-Net): the ring kernel with the lane
+// groups on the kernel columns (the fourth column's weights are zero), so the one octet that exists fills a K step with
+// three of its four columns instead of one quarter of a four-octet chunk, and eight output rows per tile.  Measured on
+// the U-Net's 1 -> 64 layer at 570^2: 29.5 -> 19.9 us.  With more input maps the register-staged kernel is faster
+// (64 -> 128 at 282^2: 30.7 against 45.7 us; 128 -> 128 at 280^2: 47.5 against 75.6 us).
+template <int DT, int MT>
+static hipError_t launch_conv_h_k3_tapcols(const ConvHArgs &a, hipStream_t stream)
+{
+    if (CH_TX + 3 * a.d > 64 * 3) return hipErrorInvalidValue;
+    const bool one_group = ((a.c_out + 15) / 16 + MT - 1) / MT == 1;
+    if (one_group && ring_smem<3, MT, true, 8, 3, true>(a.d, a.c_out, a.c8_in, a.Ho) <= 160 * 1024)
+        return launch_conv_h_ring_m<DT, 3, MT, true, 8, false, 3, true>(a, stream);
+    if (ring_smem<3, MT, true, 8, 4, false>(a.d, a.c_out, a.c8_in, a.Ho) <= 160 * 1024)
+        return launch_conv_h_ring_m<DT, 3, MT, true, 8, false, 4, false>(a, stream);
+    return hipErrorInvalidValue;
+}
+
+// Map tiles per workgroup for a forward layer, with CONV_H_TAPCOLS set where launch_conv_h_k3_tapcols is the better
+// kernel: 3x3 at d = 1, one input octet and at least 128 x 128 output pixels per image
+int conv_h_pick_mode(int c_out, int c_in, int k, int d, int n, int Ho, int Wo)
+{
+    if (k == 3 && d == 1 && c_in <= 8 && c_out >= 32 && (long)Ho * Wo >= 128L * 128) {
+        const int tiles = (c_out + 15) / 16;
+        return ((tiles % 3 == 0 || tiles >= 8) ? 3 : 2) | CONV_H_TAPCOLS;
+    }
+    return conv_h_pick_mt(c_out, k, n, Ho, Wo);
+}
+
 // output-map tiles (16 maps each) per workgroup: as few padded tiles as possible; a 3x3 kernel's
 // weight slab (k*k KB per tile and chunk) only leaves LDS room for three
 int conv_h_mt(int c_out, int k)
@@ -1325,6 +1353,15 @@ hipError_t launch_conv_h(const ConvHArgs &a, hipStream_t stream)
     if (a.tap_maps != 0 && (a.tap_maps < 16 || a.tap_maps % 16 != 0 || a.c_out != 4 * a.tap_maps || a.mask || a.out_f32 || a.oy_mul != 2 ||
                             a.ox_mul != 2 || a.k != 1))
         return hipErrorInvalidValue;
+    // 3x3 layers whose weights were packed with the kernel columns on the lane groups (conv_h_pick_mode)
+    if (a.mt > 0 && (a.mt & CONV_H_TAPCOLS)) {
+        if (a.k != 3 || a.mask || a.in_off || a.vpool || a.hd || a.tap_maps || a.xb8 || a.grp8) return hipErrorInvalidValue;
+        ConvHArgs b = a;
+        b.mt = a.mt & ~CONV_H_TAPCOLS;
+        if (a.dtype == 1) return b.mt == 2 ? launch_conv_h_k3_tapcols<1, 2>(b, stream) : (b.mt == 3 ? launch_conv_h_k3_tapcols<1, 3>(b, stream) : hipErrorInvalidValue);
+        if (a.dtype == 2) return b.mt == 2 ? launch_conv_h_k3_tapcols<2, 2>(b, stream) : (b.mt == 3 ? launch_conv_h_k3_tapcols<2, 3>(b, stream) : hipErrorInvalidValue);
+        return hipErrorInvalidValue;
+    }
     // the packed weights were laid out for this many map tiles per group (0 = the default choice)
     const int mt = a.mt > 0 ? a.mt : conv_h_mt(a.c_out, a.k);
     if (mt > 4 || (a.k == 3 && mt > 3)) return hipErrorInvalidValue;
@@ -1419,9 +1456,11 @@ int conv_h_pick_mt(int c_out, int k, int n, int Ho, int Wo)
 
 long packed_h_elems(int gemm_m, int gemm_c8, int k, int mt)
 {
+    const bool tapcols = mt > 0 && (mt & CONV_H_TAPCOLS) != 0;
+    if (mt > 0) mt &= ~CONV_H_TAPCOLS;
     if (mt <= 0) mt = conv_h_mt(gemm_m, k);
     const int m_tiles = (gemm_m + 15) / 16, mgroups = (m_tiles + mt - 1) / mt;
-    const bool map4 = k >= 4;
+    const bool map4 = k >= 4 || tapcols;
     const int OC = map4 ? 1 : 4, CS = map4 ? (k + 3) / 4 : k;
     const int nchunks = (gemm_c8 + OC - 1) / OC;
     return (long)mgroups * nchunks * CS * k * mt * 512;
@@ -1432,15 +1471,17 @@ hipError_t launch_pack_weights_h(const float *w_oihw, void *wp, int dtype, int c
 {
     const int gemm_m = flip_transpose ? c_in : c_out;
     const int gemm_c8 = ((flip_transpose ? c_out : c_in) + 7) / 8;
-    if (mt <= 0) mt = conv_h_mt(gemm_m, k);
+    const int map4 = (k >= 4 || (mt > 0 && (mt & CONV_H_TAPCOLS))) ? 1 : 0;
     const long total = packed_h_elems(gemm_m, gemm_c8, k, mt);
+    if (mt > 0) mt &= ~CONV_H_TAPCOLS;
+    if (mt <= 0) mt = conv_h_mt(gemm_m, k);
     const int blocks = (int)((total + 255) / 256 < 2048 ? (total + 255) / 256 : 2048);
     if (dtype == 1)
         hipLaunchKernelGGL(pack_weights_h_kernel<1>, dim3(blocks), dim3(256), 0, stream, w_oihw,
-                           static_cast<unsigned short *>(wp), c_out, c_in, k, flip_transpose, mt, k >= 4 ? 1 : 0, gemm_m, gemm_c8, total);
+                           static_cast<unsigned short *>(wp), c_out, c_in, k, flip_transpose, mt, map4, gemm_m, gemm_c8, total);
     else
         hipLaunchKernelGGL(pack_weights_h_kernel<2>, dim3(blocks), dim3(256), 0, stream, w_oihw,
-                           static_cast<unsigned short *>(wp), c_out, c_in, k, flip_transpose, mt, k >= 4 ? 1 : 0, gemm_m, gemm_c8, total);
+                           static_cast<unsigned short *>(wp), c_out, c_in, k, flip_transpose, mt, map4, gemm_m, gemm_c8, total);
     return hipGetLastError();
 }
 
@@ -1456,9 +1497,10 @@ hipError_t launch_pack_weights_h_batch(const PackHJob *jobs, int n, int dtype, h
         o.c_out = j.c_out; o.c_in = j.c_in; o.k = j.k; o.flip_transpose = j.flip_transpose;
         o.gemm_m = j.flip_transpose ? j.c_in : j.c_out;
         o.gemm_c8 = ((j.flip_transpose ? j.c_out : j.c_in) + 7) / 8;
-        o.mt = j.mt > 0 ? j.mt : conv_h_mt(o.gemm_m, j.k);
-        o.map4 = j.k >= 4 ? 1 : 0;
-        o.total = packed_h_elems(o.gemm_m, o.gemm_c8, j.k, o.mt);
+        o.map4 = (j.k >= 4 || (j.mt > 0 && (j.mt & CONV_H_TAPCOLS))) ? 1 : 0;
+        o.total = packed_h_elems(o.gemm_m, o.gemm_c8, j.k, j.mt);
+        o.mt = j.mt > 0 ? (j.mt & ~CONV_H_TAPCOLS) : 0;
+        if (o.mt <= 0) o.mt = conv_h_mt(o.gemm_m, j.k);
         most = o.total > most ? o.total : most;
     }
     const int blocks = (int)((most + 255) / 256 < 256 ? (most + 255) / 256 : 256);

@@ -96,6 +96,10 @@ hipError_t launch_conv_h(const ConvHArgs &a, hipStream_t stream);
 long packed_h_elems(int gemm_m, int gemm_c8, int k, int mt = 0);
 // map tiles per workgroup (mt) that suit a forward layer of this output size; pass it to the packing too
 int conv_h_pick_mt(int c_out, int k, int n, int Ho, int Wo);
+// ... or that value with CONV_H_TAPCOLS set: a 3x3 layer whose weights are packed (and whose launch runs) with the kernel
+// columns on the lane groups; pass the value to the packing and in ConvHArgs.mt as it is
+constexpr int CONV_H_TAPCOLS = 16;
+int conv_h_pick_mode(int c_out, int c_in, int k, int d, int n, int Ho, int Wo);
 // forward packing (flip_transpose = 0: gemm_m = c_out, input octets of c_in) or data-gradient
 // packing (flip_transpose = 1: gemm_m = c_in, input octets of c_out) from OIHW fp32 master weights
 hipError_t launch_pack_weights_h(const float *w_oihw, void *wp, int dtype, int c_out, int c_in, int k,

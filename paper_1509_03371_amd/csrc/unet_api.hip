@@ -462,7 +462,7 @@ static sk_status plan_impl(unet_t *net, int32_t n, int32_t h_in, int32_t w_in, b
         for (const auto &op : net->ops) {
             if (op.kind == 0) {
                 ConvParams &c = net->convs[op.param];
-                c.mt16 = sk::conv_h_pick_mt(c.c_out, c.k, n, op.out.h, op.out.w);
+                c.mt16 = sk::conv_h_pick_mode(c.c_out, c.c_in, c.k, op.d, n, op.out.h, op.out.w);
             } else if (op.kind == 2) {
                 for (auto &t : net->ups[op.param].tap) t.mt16 = sk::conv_h_pick_mt(net->ups[op.param].c_out, 1, n, op.in.h, op.in.w);
                 net->ups[op.param].cat.mt16 = sk::conv_h_pick_mt(4 * net->ups[op.param].c_out, 1, n, op.in.h, op.in.w);
