@@ -1343,6 +1343,158 @@ bool conv_h_supported(int k, int d, int gemm_m)
     return 2 * stage * 16 + m_tiles_all * 64 <= 160 * 1024;
 }
 
+// ------------------------------------------------------------------------------------------------
+// First layer of a net on a one-map image (k = 4: 16 taps): HBM-write-bound -- 2 bytes read and 2 * c_out written per
+// pixel -- so it gets a kernel built for the stores instead of the ring kernel's tile machinery.  The 16 taps of the
+// single input map ARE the K dimension of one MFMA 16x16x32 (lane groups 0 and 1 carry taps 0..7 and 8..15, groups 2 and
+// 3 zeros), so 16 pixels x 16 output maps cost one MFMA.  A workgroup of four waves takes 64 columns x rb rows: the
+// input tile (one 16-bit sample per pixel) goes to LDS once; a wave takes all 64 columns of rb / 4 rows.  The MFMA leaves
+// a lane with four maps of one pixel; the wave passes its row through LDS so that lane L holds the whole octets of pixel
+// L and every store instruction writes 1 KB of consecutive addresses per octet plane (the 8-byte halves of 16-pixel
+// groups the other kernels store reach about half the rate on a layer that does nothing but store).  With VP (the
+// vertical half of the SK pool that follows, kernel stride 1; ReLU required, so the 16-bit patterns order like the
+// values) a wave computes one row more, keeps the previous row's packed values and stores max(Y[y], Y[y + 1]).
+constexpr int C1_TX = 64;
+
+template <int DT, int MT, bool VP>
+__global__ __launch_bounds__(256) void conv_c1_h_kernel(ConvHArgs a, int xtiles, int ytiles, int pitch, int rb)
+{
+    extern __shared__ uint4v c1_smem[];
+    const int KS = a.k, d = a.d, halo = (KS - 1) * d;
+    const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, g = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int xt = blockIdx.x % xtiles, rest = blockIdx.x / xtiles, yt = rest % ytiles, b = rest / ytiles;
+    const int x0 = xt * C1_TX, y0 = yt * rb;
+    int nrows = a.Ho - y0;                                          // convolution rows of this tile
+    nrows = nrows < rb + (VP ? 1 : 0) ? nrows : rb + (VP ? 1 : 0);
+    const int in_rows = nrows + halo;
+    // LDS: per wave 2 * MT octet planes x 64 pixels x 16 bytes for the row exchange, then the input tile
+    char *xch = reinterpret_cast<char *>(c1_smem) + wave * (2 * MT * 64 * 16);
+    unsigned short *tile = reinterpret_cast<unsigned short *>(reinterpret_cast<char *>(c1_smem) + 4 * (2 * MT * 64 * 16));
+
+    // input tile: map 0 of the octet at every pixel (addresses clamped into the image: such samples only reach
+    // outputs that are not stored)
+    const unsigned *xin = static_cast<const unsigned *>(a.x) + (long)b * a.H * a.W * 4;
+    for (int idx = tid; idx < in_rows * pitch; idx += 256) {
+        const int r = idx / pitch, c = idx - r * pitch;
+        int gy = y0 + r, gx = x0 + c;
+        gy = gy < a.H ? gy : a.H - 1;
+        gx = gx < a.W ? gx : a.W - 1;
+        tile[idx] = (unsigned short)(xin[((long)gy * a.W + gx) * 4] & 0xffffu);
+    }
+    // A fragments from the packed weights ([kernel row i][map tile][lane group = kernel column j][map][channel]): this
+    // lane's K values are taps 8g .. 8g + 7 of map 16 mt + l16, channel 0
+    const unsigned short *wp = static_cast<const unsigned short *>(a.wp);
+    uint4v af[MT];
+    int toff[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int t = 8 * g + e, i = t / KS, j = t - i * KS;
+        toff[e] = t < KS * KS ? i * d * pitch + j * d : 0;
+    }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        unsigned short v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int t = 8 * g + e, i = t / KS, j = t - i * KS;
+            v[e] = t < KS * KS ? wp[(((long)i * MT + mt) * 64 + j * 16 + l16) * 8] : (unsigned short)0;
+        }
+        af[mt] = uint4v{v[0] | ((unsigned)v[1] << 16), v[2] | ((unsigned)v[3] << 16), v[4] | ((unsigned)v[5] << 16), v[6] | ((unsigned)v[7] << 16)};
+    }
+    float bia[MT][4];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) bia[mt][r4] = a.bias ? a.bias[mt * 16 + 4 * g + r4] : 0.f;
+    __syncthreads();
+
+    const int rw = rb >> 2;                                         // rows of this wave
+    const int r_first = wave * rw;
+    int r_end = r_first + rw + (VP ? 1 : 0);
+    r_end = r_end < nrows ? r_end : nrows;
+    const int ox = x0 + lane;
+    const bool colok = ox < a.Wo;
+    const long plane = (long)a.OH * a.OW;
+    uint4v *ybase = static_cast<uint4v *>(a.y) + ((long)b * a.c8_out_total + a.o8_off) * plane + (colok ? ox : 0);
+    const bool taps_here = 8 * g < KS * KS;
+    uint2v prev[4][MT];
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) prev[ct][mt] = uint2v{0u, 0u};
+    for (int r = r_first; r < r_end; ++r) {
+        uint4v bf[4];
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct) {
+            const unsigned short *src = tile + r * pitch + 16 * ct + l16;
+            unsigned short v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = taps_here ? src[toff[e]] : (unsigned short)0;
+            bf[ct] = uint4v{v[0] | ((unsigned)v[1] << 16), v[2] | ((unsigned)v[3] << 16), v[4] | ((unsigned)v[5] << 16), v[6] | ((unsigned)v[7] << 16)};
+        }
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const floatx4 acc = H<DT>::mfma(af[mt], bf[ct], floatx4{0.f, 0.f, 0.f, 0.f});
+                float val[4];
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    val[r4] = acc[r4] + bia[mt][r4];
+                    if (a.relu) val[r4] = fmaxf(val[r4], 0.f);
+                }
+                uint2v pk = uint2v{(unsigned)H<DT>::cvt(val[0]) | ((unsigned)H<DT>::cvt(val[1]) << 16),
+                                   (unsigned)H<DT>::cvt(val[2]) | ((unsigned)H<DT>::cvt(val[3]) << 16)};
+                uint2v out = pk;
+                if constexpr (VP) {
+                    out = uint2v{pk_max_u16(prev[ct][mt][0], pk[0]), pk_max_u16(prev[ct][mt][1], pk[1])};
+                    prev[ct][mt] = pk;
+                }
+                // this lane's four maps of pixel 16 ct + l16: half (g & 1) of octet 2 mt + (g >> 1)
+                *reinterpret_cast<uint2v *>(xch + ((2 * mt + (g >> 1)) * 64 + 16 * ct + l16) * 16 + (g & 1) * 8) = out;
+            }
+        if (!VP || r > r_first) {                                   // (uniform)
+            const int oy = VP ? y0 + r - 1 : y0 + r;
+            uint4v oct[2 * MT];
+#pragma unroll
+            for (int o = 0; o < 2 * MT; ++o) oct[o] = *reinterpret_cast<const uint4v *>(xch + (o * 64 + lane) * 16);
+#pragma unroll
+            for (int o = 0; o < 2 * MT; ++o)
+                if (colok && o < a.c8_out) ybase[(long)o * plane + (long)oy * a.OW] = oct[o];
+        }
+    }
+}
+
+// can (and should) this launch run on conv_c1_h_kernel?
+static bool conv_c1_h_applies(const ConvHArgs &a, int mt_packed)
+{
+    const int m_tiles = (a.c_out + 15) / 16;
+    return a.single_map && a.c8_in == 1 && a.k == 4 && a.d >= 1 && 3 * a.d <= 32 && !a.mask && a.in_off == 0 && a.hd == 0 && !a.out_f32 &&
+           a.tap_maps == 0 && a.oy_mul == 1 && a.ox_mul == 1 && a.oy_off == 0 && a.ox_off == 0 && !a.xb8 && !a.grp8 && m_tiles <= 3 &&
+           mt_packed == m_tiles && (!a.vpool || (a.d == 1 && a.relu && a.OH == a.Ho - 1 && a.OW == a.Wo)) &&
+           (a.vpool || (a.OH == a.Ho && a.OW == a.Wo));
+}
+
+template <int DT, int MT>
+static hipError_t launch_conv_c1_h(const ConvHArgs &a, hipStream_t stream)
+{
+    const int xtiles = (a.Wo + C1_TX - 1) / C1_TX;
+    const int out_rows = a.vpool ? a.Ho - 1 : a.Ho;
+    if (out_rows < 1) return hipErrorInvalidValue;
+    // rows per workgroup: 32, or fewer where that leaves the GPU short of workgroups (a 512^2 image)
+    int rb = 32;
+    while (rb > 8 && (long)xtiles * ((out_rows + rb - 1) / rb) * a.n < 8L * device_cus()) rb >>= 1;
+    const int ytiles = (out_rows + rb - 1) / rb;
+    const int pitch = (C1_TX + 3 * a.d + 2) & ~1;
+    const size_t smem = (size_t)4 * 2 * MT * 64 * 16 + sizeof(unsigned short) * (size_t)(rb + 1 + 3 * a.d) * pitch;
+    const long blocks = (long)xtiles * ytiles * a.n;
+    if (blocks < 1 || blocks > 0x7fffffffL || smem > 48 * 1024) return hipErrorInvalidValue;
+    if (a.vpool) hipLaunchKernelGGL((conv_c1_h_kernel<DT, MT, true>), dim3((unsigned)blocks), dim3(256), smem, stream, a, xtiles, ytiles, pitch, rb);
+    else hipLaunchKernelGGL((conv_c1_h_kernel<DT, MT, false>), dim3((unsigned)blocks), dim3(256), smem, stream, a, xtiles, ytiles, pitch, rb);
+    return hipGetLastError();
+}
+
 hipError_t launch_conv_h(const ConvHArgs &a, hipStream_t stream)
 {
     if (!conv_h_supported(a.k, a.d) || a.Ho < 1 || a.Wo < 1 || a.c8_in < 1 || a.c_out < 1) return hipErrorInvalidValue;
@@ -1364,6 +1516,10 @@ hipError_t launch_conv_h(const ConvHArgs &a, hipStream_t stream)
     }
     // the packed weights were laid out for this many map tiles per group (0 = the default choice)
     const int mt = a.mt > 0 ? a.mt : conv_h_mt(a.c_out, a.k);
+    if (conv_c1_h_applies(a, mt)) {
+        if (a.dtype == 1) return mt == 1 ? launch_conv_c1_h<1, 1>(a, stream) : (mt == 2 ? launch_conv_c1_h<1, 2>(a, stream) : launch_conv_c1_h<1, 3>(a, stream));
+        if (a.dtype == 2) return mt == 1 ? launch_conv_c1_h<2, 1>(a, stream) : (mt == 2 ? launch_conv_c1_h<2, 2>(a, stream) : launch_conv_c1_h<2, 3>(a, stream));
+    }
     if (mt > 4 || (a.k == 3 && mt > 3)) return hipErrorInvalidValue;
     if (a.k > 4 && !conv_h_supported(a.k, a.d, a.c_out)) return hipErrorInvalidValue;
     if (a.dtype == 1) {

@@ -184,6 +184,7 @@ inline sk::ConvHArgs conv_h_args(const ConvParams &c, int dtype, const void *x, 
     a.c8_out_total = (out.c + 7) / 8; a.o8_off = 0; a.OH = out.h; a.OW = out.w;
     a.oy_mul = 1; a.oy_off = 0; a.ox_mul = 1; a.ox_off = 0;
     a.mt = c.mt16;
+    a.single_map = c.c_in == 1 ? 1 : 0;
     return a;
 }
 

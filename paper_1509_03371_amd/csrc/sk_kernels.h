@@ -77,6 +77,7 @@ struct ConvHArgs {
     // by a layer with kernel stride hd and has W + hd columns per row in memory, of which this launch reads
     // max(X[x], X[x + hd]) for x < W.  Both only where conv_h_pool_fusable() says so.
     int vpool, hd;
+    int single_map;       // != 0: the layer has ONE input map (map 0 of the single input octet; the rest of the octet is padding)
     const void *zeros;    // CONV_H_ZERO_BYTES of zeros in device memory, read in place of samples outside the image (the launcher
                           // allocates nothing: the owner of the plan provides the page)
     // Slices of a volume as images (3-D layers on the slice-major layout): xb8 > 0: image b starts xb8 octet planes after
