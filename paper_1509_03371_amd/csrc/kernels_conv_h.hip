@@ -1375,12 +1375,23 @@ __global__ __launch_bounds__(256) void conv_c1_h_kernel(ConvHArgs a, int xtiles,
     // input tile: map 0 of the octet at every pixel (addresses clamped into the image: such samples only reach
     // outputs that are not stored)
     const unsigned *xin = static_cast<const unsigned *>(a.x) + (long)b * a.H * a.W * 4;
+    const float *img = a.img ? a.img + (long)b * a.img_h * a.img_w : nullptr;
+    auto mirror = [&](int t, int len) {
+        if (len == 1) return 0;
+        const int period = a.pad_mode == 0 ? 2 * (len - 1) : 2 * len;
+        t %= period;
+        if (t < 0) t += period;
+        return t < len ? t : (a.pad_mode == 0 ? period - t : period - 1 - t);
+    };
     for (int idx = tid; idx < in_rows * pitch; idx += 256) {
         const int r = idx / pitch, c = idx - r * pitch;
         int gy = y0 + r, gx = x0 + c;
         gy = gy < a.H ? gy : a.H - 1;
         gx = gx < a.W ? gx : a.W - 1;
-        tile[idx] = (unsigned short)(xin[((long)gy * a.W + gx) * 4] & 0xffffu);
+        if (img)                                                    // the caller's image, mirror-padded and rounded here
+            tile[idx] = H<DT>::cvt(img[(long)mirror(gy - a.pad_top, a.img_h) * a.img_w + mirror(gx - a.pad_left, a.img_w)]);
+        else
+            tile[idx] = (unsigned short)(xin[((long)gy * a.W + gx) * 4] & 0xffffu);
     }
     // A fragments from the packed weights ([kernel row i][map tile][lane group = kernel column j][map][channel]): this
     // lane's K values are taps 8g .. 8g + 7 of map 16 mt + l16, channel 0
@@ -1495,6 +1506,12 @@ static hipError_t launch_conv_c1_h(const ConvHArgs &a, hipStream_t stream)
     return hipGetLastError();
 }
 
+bool conv_h_reads_image(const ConvHArgs &a)
+{
+    if (a.img || (a.dtype != 1 && a.dtype != 2) || !conv_h_supported(a.k, a.d)) return false;
+    return conv_c1_h_applies(a, a.mt > 0 ? a.mt : conv_h_mt(a.c_out, a.k));
+}
+
 hipError_t launch_conv_h(const ConvHArgs &a, hipStream_t stream)
 {
     if (!conv_h_supported(a.k, a.d) || a.Ho < 1 || a.Wo < 1 || a.c8_in < 1 || a.c_out < 1) return hipErrorInvalidValue;
@@ -1516,6 +1533,8 @@ hipError_t launch_conv_h(const ConvHArgs &a, hipStream_t stream)
     }
     // the packed weights were laid out for this many map tiles per group (0 = the default choice)
     const int mt = a.mt > 0 ? a.mt : conv_h_mt(a.c_out, a.k);
+    if (a.img && (!conv_c1_h_applies(a, mt) || a.img_h < 1 || a.img_w < 1 || a.pad_top < 0 || a.pad_left < 0 || (a.pad_mode != 0 && a.pad_mode != 1)))
+        return hipErrorInvalidValue;                                // only that kernel reads the image
     if (conv_c1_h_applies(a, mt)) {
         if (a.dtype == 1) return mt == 1 ? launch_conv_c1_h<1, 1>(a, stream) : (mt == 2 ? launch_conv_c1_h<1, 2>(a, stream) : launch_conv_c1_h<1, 3>(a, stream));
         if (a.dtype == 2) return mt == 1 ? launch_conv_c1_h<2, 1>(a, stream) : (mt == 2 ? launch_conv_c1_h<2, 2>(a, stream) : launch_conv_c1_h<2, 3>(a, stream));

@@ -78,6 +78,11 @@ struct ConvHArgs {
     // max(X[x], X[x + hd]) for x < W.  Both only where conv_h_pool_fusable() says so.
     int vpool, hd;
     int single_map;       // != 0: the layer has ONE input map (map 0 of the single input octet; the rest of the octet is padding)
+    // img != nullptr (only where conv_h_reads_image() says so): the layer reads the caller's fp32 image [n][1][img_h][img_w]
+    // itself instead of x -- mirror padding by pad_top / pad_left (pad_mode as in launch_pad_pack_h) to the H x W map this
+    // launch convolves, each sample rounded to the storage type as launch_pad_pack_h rounds it
+    const float *img;
+    int img_h, img_w, pad_top, pad_left, pad_mode;
     const void *zeros;    // CONV_H_ZERO_BYTES of zeros in device memory, read in place of samples outside the image (the launcher
                           // allocates nothing: the owner of the plan provides the page)
     // Slices of a volume as images (3-D layers on the slice-major layout): xb8 > 0: image b starts xb8 octet planes after
@@ -92,6 +97,8 @@ bool conv_h_supported(int k, int d);
 bool conv_h_pool_fusable(int k, int d, int c_out, int c8_in, int Ho, int hd);
 // ... and for a GEMM with gemm_m output maps (c_out forward, c_in for the data gradient) the tile fits the LDS
 bool conv_h_supported(int k, int d, int gemm_m);
+// does this launch (single_map set, img left null) run on the kernel that can read the fp32 image itself?
+bool conv_h_reads_image(const ConvHArgs &a);
 hipError_t launch_conv_h(const ConvHArgs &a, hipStream_t stream);
 // 16-bit elements of the packed weights of a GEMM with gemm_m output maps and gemm_c8 input octets
 long packed_h_elems(int gemm_m, int gemm_c8, int k, int mt = 0);

@@ -53,6 +53,7 @@ struct sknet {
     std::vector<Dims> dims;           // dims[0] padded image, dims[i+1] output of layer i
     std::vector<float *> act;         // same indexing
     std::vector<uint8_t *> tap;       // per layer (pools on a training plan), else nullptr
+    bool image_direct = false;        // 16-bit inference plans: the first layer reads the caller's image (no padded copy is made)
     float *gbuf[2] = {nullptr, nullptr};
     float *loss_partial = nullptr, *wgrad_scratch = nullptr;
     // forward schedule of the plan: kind 0 = pad / convert, 1 = layer `arg`, 2 = softmax, 3 = fused head
@@ -173,6 +174,7 @@ sk_status run_forward_step(sknet *net, int step_idx, hipStream_t stream)
     const int step = st.kind == 0 ? 0 : (st.kind == 1 ? st.arg + 1 : L + 1);
     if (step == 0) {
         const Dims &d0 = net->dims[0];
+        if (half && net->image_direct) return SK_OK;   // the first layer pads and converts the image itself
         if (half)   // mirror padding fused into the conversion to the 16-bit octet layout
             SK_HIP(sk::launch_pad_pack_h(net->last_image, net->act[0], net->dtype, net->n, net->c_in, net->h, net->w,
                                          net->pad ? net->pad_top : 0, net->pad ? net->pad_left : 0, d0.h, d0.w,
@@ -196,6 +198,11 @@ sk_status run_forward_step(sknet *net, int step_idx, hipStream_t stream)
                 sk::ConvHArgs a = conv_h_args(c, net->dtype, hd ? net->act[li - 1] : net->act[li], net->n, in, l.d, l.relu, net->act[li + 1], out,
                                               li == L - 1, net->zero_page);   // the last conv writes fp32 logits
                 a.hd = hd;
+                if (li == 0 && net->image_direct) {
+                    a.x = nullptr;
+                    a.img = net->last_image; a.img_h = net->h; a.img_w = net->w;
+                    a.pad_top = net->pad ? net->pad_top : 0; a.pad_left = net->pad ? net->pad_left : 0; a.pad_mode = net->pad_mode;
+                }
                 if (net->vpool[li]) {
                     a.vpool = 1;
                     a.OH = out.h - l.d;
@@ -510,6 +517,14 @@ sk_status sknet_plan(sknet_t *net, int32_t n, int32_t h, int32_t w, int32_t pad,
             if (net->fuse_head && i + 2 == L - 2) net->pending_head = l.d;
             ++i;                                       // the pool is spoken for
         }
+    }
+    // inference plans whose first layer runs on the one-input-map kernel: that kernel reads the caller's image itself
+    net->image_direct = false;
+    if (mode == 0 && half && net->c_in == 1 && net->layers[0].kind == SK_CONV) {
+        const ConvParams &c0 = net->convs[net->conv_of_layer[0]];
+        sk::ConvHArgs a0 = conv_h_args(c0, net->dtype, nullptr, n, dims[0], net->layers[0].d, net->layers[0].relu, nullptr, dims[1], L == 1, nullptr);
+        if (net->vpool[0]) { a0.vpool = 1; a0.OH = dims[1].h - net->layers[0].d; }
+        net->image_direct = sk::conv_h_reads_image(a0);
     }
     net->steps.clear();
     net->steps.push_back({0, 0});

@@ -228,3 +228,34 @@ def test_unsupported_kernel_size_is_reported():
         net.plan(1, 40, 40, pad=True, training=True)                                               # large kernels: forward only
     assert e.value.status_name == "SK_EUNSUPPORTED"
     net.close()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("pad_mode", [0, 1])
+@pytest.mark.parametrize("pad", [True, False])
+def test_first_layer_reads_the_image_itself(dtype, pad_mode, pad):
+    """Inference plans of a one-map net hand the caller's fp32 image to the first layer's kernel, which mirror-pads and
+    rounds it while it stages its tile; a plan that keeps every layer converts the padded image first and runs the same
+    kernel on that copy.  The two must agree bit for bit (both padding modes, two images, sizes off every tile), and
+    with the oracle."""
+    from paper_1509_03371_amd import binding as B
+    layers = [S.conv(40, 4, 1), S.pool(2, 1), S.conv(24, 4, 2), S.pool(2, 2), S.conv(3, 1, 1, relu=False)]
+    ws, bs = S.he_normal_weights(layers, 1, 910, bias_scale=0.1)
+    h, w = (75, 139) if pad else (83, 147)
+    img = S.em_like_batch(2, h, w, 911)
+    nets = []
+    for keep in (False, True):
+        net = B.SKNet(layers, 1, 3, dtype=dtype, pad_mode=pad_mode)
+        for i, (wt, b) in enumerate(zip(ws, bs)):
+            net.set_weights(i, wt, b)
+        net.plan(2, h, w, pad=pad, keep=keep)
+        nets.append(net)
+    dev = torch.from_numpy(img).cuda()
+    direct, kept = nets[0].forward(dev).cpu().numpy(), nets[1].forward(dev).cpu().numpy()
+    assert np.array_equal(direct, kept)
+    ow = [x.astype(np.float64) for x in ws]
+    ob = [x.astype(np.float64) for x in bs]
+    ref = ON.sknet_forward(img, layers, ow, ob, pad=pad, pad_mode=pad_mode) if pad else ON.sknet_forward(img, layers, ow, ob, pad=False)
+    assert np.abs(direct - ref).max() <= HALF_TOL
+    for net in nets:
+        net.close()
