@@ -483,6 +483,200 @@ __global__ __launch_bounds__(256) void wgrad_h_kernel(WgradArgs a)
     }
 }
 
+// ---- 16 input maps or more: operands staged as octets, fragments by the transposing LDS read ---------------------------
+// The segment kernel above scatters every loaded octet into eight map-major LDS rows (eight 2-byte writes) so that a
+// fragment -- 8 consecutive pixels of one map -- is a plain read, and reads it in pieces of whatever alignment the tap
+// offset j*d leaves.  Here an octet goes to LDS as it is (ONE 16-byte write: [row][pixel][8 maps]) and ds_read_b64_tr_b16
+// does the transposition on the way out: of a group of 16 lanes, lane 4r + q addresses pixel r, maps 4q..4q+3, and lane
+// 4q + e receives map 4q + e of pixels 0..3.  A tile of 16 GEMM columns is then 16 consecutive input maps (two octets) at
+// ONE tap (i, j) -- column tile nk = (map pair, i, j), against 16 consecutive (c, i, j) in the kernel above -- and a tap's
+// offset moves whole 16-byte pixels, so there are no alignment classes.  The private copies have the columns in that
+// order; the reduction maps them back (tr_k2).  Tiles over the output maps, tile groups, persistent workgroups, the bias
+// sums on the matrix unit and the prefetch of the next segment are those of the kernel above.
+typedef short short4tr __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4v read_frag_tr(const char *lds_base, unsigned off_lo, unsigned off_hi)
+{
+    typedef short4tr __attribute__((address_space(3))) *lds_s4;
+    const short4tr lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(lds_base + off_lo));
+    const short4tr hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(lds_base + off_hi));
+    const uint2v l2 = __builtin_bit_cast(uint2v, lo), h2 = __builtin_bit_cast(uint2v, hi);
+    return uint4v{l2[0], l2[1], h2[0], h2[1]};
+}
+
+constexpr int WG_TRP = WG_SEG + 4;      // LDS pitch (16-byte units) of a dY octet row: row starts alternate between the two halves of the banks
+
+template <int MB, int NB, int DT>
+__global__ __launch_bounds__(256) void wgrad_tr_h_kernel(WgradArgs a)
+{
+    constexpr int DYL = (2 * MB + 3) / 4;   // dY octet loads per wave and segment
+    constexpr int XU = 6, XV = 2;           // input loads per wave and batch: XU row ids x XV groups of 64 columns
+    extern __shared__ uint4v smem16[];
+    const int k = a.k, d = a.d, kk = k * k;
+    const int m_rows = a.MTo * 16;
+    uint4v *dys = smem16;                               // [2*MB octets][WG_TRP pixels]
+    uint4v *xs = dys + 2 * MB * WG_TRP;                 // [(octets of the group) * k rows][xpitch pixels]
+    const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, g = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int rr = l16 >> 2, qq = l16 & 3;              // the transposing read: this lane addresses pixel rr, map quad qq
+    const int PW = WG_SEG + (k - 1) * d;                // <= 64 * XV (checked by the launcher)
+
+    const int ngroups = (a.NTk + 4 * NB - 1) / (4 * NB);
+    const int mgroup = blockIdx.y / ngroups, ngroup = blockIdx.y - mgroup * ngroups;
+    const int mo0 = mgroup * MB;
+    const int c8o = (a.c_out + 7) / 8, c8i = (a.c_in + 7) / 8;
+    // input octets of this group's column tiles (map pair, i, j): [oc0, oc0 + noct); octets beyond the last real one are zeros
+    const int nk_lo = ngroup * NB * 4;
+    int nk_hi = nk_lo + NB * 4 - 1;
+    nk_hi = nk_hi < a.NTk - 1 ? nk_hi : a.NTk - 1;
+    const int oc0 = 2 * (nk_lo / kk), noct = 2 * (nk_hi / kk) + 2 - oc0;
+    unsigned xoff[NB], aoff[MB];
+#pragma unroll
+    for (int q = 0; q < NB; ++q) {
+        const int nk = (ngroup * NB + q) * 4 + wave;
+        unsigned off = (unsigned)((8 * g + rr) * 16);
+        if (nk < a.NTk) {
+            const int op = nk / kk, r = nk - op * kk, i = r / k, j = r - i * k;
+            off = (unsigned)((((2 * op - oc0 + (qq >> 1)) * k + i) * a.xpitch + j * d + 8 * g + rr) * 16 + (qq & 1) * 8);
+        }
+        xoff[q] = off;
+    }
+#pragma unroll
+    for (int m = 0; m < MB; ++m) aoff[m] = (unsigned)(((2 * m + (qq >> 1)) * WG_TRP + 8 * g + rr) * 16 + (qq & 1) * 8);
+    floatx4 acc[MB][NB];
+#pragma unroll
+    for (int m = 0; m < MB; ++m)
+#pragma unroll
+        for (int q = 0; q < NB; ++q) acc[m][q] = floatx4{0.f, 0.f, 0.f, 0.f};
+    const bool sum_dy = a.bias_part != nullptr && ngroup == 0 && wave < MB && mo0 + wave < a.MTo;
+    floatx4 bacc = floatx4{0.f, 0.f, 0.f, 0.f};
+    const unsigned one2 = DT == 1 ? 0x3F803F80u : 0x3C003C00u;      // two ones in the storage type
+    const uint4v ones = uint4v{one2, one2, one2, one2};
+
+    const long xplane = (long)a.H * a.W, yplane = (long)a.Ho * a.Wo;
+    const uint4v *dyp = static_cast<const uint4v *>(a.dy), *xp = static_cast<const uint4v *>(a.x);
+    const int oc_end = 2 * MB;                                       // dY octet rows of the tile group (relative)
+    const int nrid = noct * k;                                       // (input octet, kernel row) pairs to stage
+    const int nbat = (nrid + 4 * XU - 1) / (4 * XU);
+    const uint4v zero = uint4v{0u, 0u, 0u, 0u};
+
+    uint4v pdy[DYL], px[XU][XV];
+    // all addresses are clamped into the tensors; what lies outside is replaced by zero when it is stored
+    auto load_dy = [&](int b, int y, int x0) {
+        const int xl = x0 + lane < a.Wo ? x0 + lane : a.Wo - 1;
+#pragma unroll
+        for (int t = 0; t < DYL; ++t) {
+            const int oc = mo0 * 2 + wave + 4 * t;
+            const int occ = oc < c8o ? oc : c8o - 1;
+            pdy[t] = dyp[((long)b * c8o + occ) * yplane + (long)y * a.Wo + xl];
+        }
+    };
+    auto load_x = [&](int bat, int b, int y, int x0) {
+#pragma unroll
+        for (int u = 0; u < XU; ++u) {
+            const int rid = wave + 4 * (bat * XU + u);
+            const int ridc = rid < nrid ? rid : nrid - 1;
+            const int ocr = ridc / k, i = ridc - ocr * k;
+            int oc = oc0 + ocr;
+            oc = oc < c8i ? oc : c8i - 1;
+            const uint4v *src = xp + ((long)b * c8i + oc) * xplane + (long)(y + i * d) * a.W;
+#pragma unroll
+            for (int v = 0; v < XV; ++v) {
+                const int xc = lane + 64 * v;
+                px[u][v] = src[x0 + xc < a.W ? x0 + xc : a.W - 1];
+            }
+        }
+    };
+    auto store_dy = [&](int x0) {
+#pragma unroll
+        for (int t = 0; t < DYL; ++t) {
+            const int rel = wave + 4 * t;
+            if (rel < oc_end) dys[rel * WG_TRP + lane] = (mo0 * 2 + rel < c8o && x0 + lane < a.Wo) ? pdy[t] : zero;
+        }
+    };
+    auto store_x = [&](int bat, int x0) {
+#pragma unroll
+        for (int u = 0; u < XU; ++u) {
+            const int rid = wave + 4 * (bat * XU + u);
+            if (rid >= nrid) continue;                          // uniform
+            const int ocr = rid / k;
+#pragma unroll
+            for (int v = 0; v < XV; ++v) {
+                const int xc = lane + 64 * v;
+                if (xc < PW) xs[rid * a.xpitch + xc] = (x0 + xc < a.W && oc0 + ocr < c8i) ? px[u][v] : zero;
+            }
+        }
+    };
+    auto locate = [&](int seg, int &b, int &y, int &x0) {
+        const int xs_i = seg % a.xsegs, t = seg / a.xsegs;
+        y = t % a.Ho;
+        b = t / a.Ho;
+        x0 = xs_i * WG_SEG;
+    };
+
+    const char *dys_b = reinterpret_cast<const char *>(dys), *xs_b = reinterpret_cast<const char *>(xs);
+    int seg = blockIdx.x, b = 0, y = 0, x0 = 0;
+    if (seg < a.total_segs) {
+        locate(seg, b, y, x0);
+        load_dy(b, y, x0);
+        load_x(0, b, y, x0);
+    }
+    for (; seg < a.total_segs; seg += gridDim.x) {
+        __syncthreads();                                        // the previous segment's MFMAs have read LDS
+        store_dy(x0);
+        store_x(0, x0);
+        for (int bat = 1; bat < nbat; ++bat) {
+            load_x(bat, b, y, x0);
+            store_x(bat, x0);
+        }
+        __syncthreads();
+        const int nseg = seg + gridDim.x;
+        if (nseg < a.total_segs) {                              // in flight while this segment is multiplied
+            locate(nseg, b, y, x0);
+            load_dy(b, y, x0);
+            load_x(0, b, y, x0);
+        }
+#pragma unroll
+        for (int p = 0; p < WG_SEG; p += 32) {
+            uint4v av[MB];
+#pragma unroll
+            for (int m = 0; m < MB; ++m) av[m] = read_frag_tr(dys_b, aoff[m] + p * 16, aoff[m] + p * 16 + 64);
+#pragma unroll
+            for (int q = 0; q < NB; ++q) {
+                const uint4v bv = read_frag_tr(xs_b, xoff[q] + p * 16, xoff[q] + p * 16 + 64);
+#pragma unroll
+                for (int m = 0; m < MB; ++m) acc[m][q] = mfma32<DT>(av[m], bv, acc[m][q]);
+            }
+            if (sum_dy) {                                        // wave-uniform
+                uint4v aw = av[0];
+#pragma unroll
+                for (int m = 1; m < MB; ++m) aw = wave == m ? av[m] : aw;
+                bacc = mfma32<DT>(aw, ones, bacc);
+            }
+        }
+    }
+    if (sum_dy && l16 == 0) {                                   // every column of bacc holds the same sums
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+            const int o = (mo0 + wave) * 16 + 4 * g + r4;
+            if (o < a.c_out) a.bias_part[(long)o * gridDim.x + blockIdx.x] = bacc[r4];
+        }
+    }
+    const long ncols = (long)a.NTk * 16;
+    float *dst = a.scratch + (long)blockIdx.x * m_rows * ncols;
+#pragma unroll
+    for (int m = 0; m < MB; ++m) {
+        if (mo0 + m >= a.MTo) continue;
+#pragma unroll
+        for (int q = 0; q < NB; ++q) {
+            const int nk = (ngroup * NB + q) * 4 + wave;
+            if (nk >= a.NTk) continue;
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4)
+                dst[((long)(mo0 + m) * 16 + 4 * g + r4) * ncols + nk * 16 + l16] = acc[m][q][r4];
+        }
+    }
+}
+
 // dW[o][cij] = sum over the private copies, and (last workgroups of the grid) db[o] = sum over the
 // slices of the bias partials.  A workgroup of 256 threads sums 64 consecutive elements: wave w takes
 // the copies w, w+4, w+8, ... with four running sums (copies w+4(4i+u), u = 0..3), so that sixteen
@@ -491,7 +685,7 @@ __global__ __launch_bounds__(256) void wgrad_h_kernel(WgradArgs a)
 constexpr int RED_ELEMS = 64;
 __global__ void __launch_bounds__(256) wgrad_reduce_kernel(const float *__restrict__ scratch, float *__restrict__ dw, int copies, int c_out, int K,
                                                            int m_rows, int ncols, int dw_blocks, const float *__restrict__ bias_part,
-                                                           float *__restrict__ db, int slices)
+                                                           float *__restrict__ db, int slices, int tr_k2)
 {
     __shared__ float sh[4][RED_ELEMS];
     const int e = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -506,12 +700,29 @@ __global__ void __launch_bounds__(256) wgrad_reduce_kernel(const float *__restri
         if (w == 0 && o < c_out) db[o] = (sh[0][e] + sh[1][e]) + (sh[2][e] + sh[3][e]);
         return;
     }
-    const long total = (long)c_out * K, stride = (long)m_rows * ncols;
-    const long q = (long)blockIdx.x * RED_ELEMS + e;
+    // Elements are walked in the order the copies hold them (consecutive threads read consecutive addresses of every
+    // copy).  tr_k2 = 0: copy column = (c, i, j) = the gradient's own order.  tr_k2 = k*k (copies of wgrad_tr_h_kernel):
+    // copy column = ((map pair, i, j), map within the pair); columns of maps beyond c_in are skipped, and the one
+    // write per element goes to dw[o][c][i][j].
+    const long total = tr_k2 > 0 ? (long)c_out * ncols : (long)c_out * K, stride = (long)m_rows * ncols;
+    const long qe = (long)blockIdx.x * RED_ELEMS + e;
+    long q = -1;                                        // index into dw, -1: nothing to write
+    int o = 0, col = 0;
+    if (qe < total) {
+        if (tr_k2 > 0) {
+            o = (int)(qe / ncols);
+            col = (int)(qe - (long)o * ncols);
+            const int tile = col >> 4, pr = tile / tr_k2, r = tile - pr * tr_k2, c = pr * 16 + (col & 15);
+            if (c * tr_k2 < K) q = (long)o * K + (long)c * tr_k2 + r;
+        } else {
+            o = (int)(qe / K);
+            col = (int)(qe - (long)o * K);
+            q = qe;
+        }
+    }
     float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-    if (q < total) {
-        const int o = (int)(q / K), cij = (int)(q - (long)o * K);
-        const float *src = scratch + (long)o * ncols + cij;
+    if (q >= 0) {
+        const float *src = scratch + (long)o * ncols + col;
         int cpy = w;
         for (; cpy + 12 < copies; cpy += 16) {
             s0 += src[(cpy + 0) * stride];
@@ -523,7 +734,7 @@ __global__ void __launch_bounds__(256) wgrad_reduce_kernel(const float *__restri
     }
     sh[w][e] = (s0 + s1) + (s2 + s3);
     __syncthreads();
-    if (w == 0 && q < total) dw[q] = (sh[0][e] + sh[1][e]) + (sh[2][e] + sh[3][e]);
+    if (w == 0 && q >= 0) dw[q] = (sh[0][e] + sh[1][e]) + (sh[2][e] + sh[3][e]);
 }
 
 // Bias gradient db[o] = sum over images and pixels of dY, in two stages with a fixed summation order.
@@ -576,6 +787,10 @@ static void wgrad_tiling(int c_out, int c_in, int k, bool f32, int &MTo, int &NT
     }
 }
 
+// column tiles of wgrad_tr_h_kernel (16-bit storage, 16 input maps or more): (pair of input octets, i, j)
+static bool wgrad_tr_applies(int c_in) { return c_in >= 16; }
+static int wgrad_tr_ntk(int c_in, int k) { return (c_in + 15) / 16 * k * k; }
+
 // Private copies of a gradient.  A small gradient (one tile group: the 48x768 of the BASELINE nets)
 // takes one copy per resident workgroup; a large one is split over tile groups (blockIdx.y), which
 // already spread it over the GPU, so it gets proportionally fewer copies -- 512 copies of a
@@ -603,6 +818,14 @@ size_t wgrad_f32_scratch_floats(int c_out, int c_in, int k)
     int copies = wgrad_max_copies(wgrad_tile_groups(MTo, NTk, MB, NB));
     wgrad_tiling(c_out, c_in, k, true, MTo, NTk, MB, NB);
     copies = std::max(copies, wgrad_max_copies(wgrad_tile_groups(MTo, NTk, MB, NB)));
+    if (wgrad_tr_applies(c_in)) {            // the transposing-read kernel: its own column tiles, groups and (wider) copies
+        int MT2, NT2, MB2, NB2;
+        wgrad_tiling(c_out, c_in, k, false, MT2, NT2, MB2, NB2);
+        NT2 = wgrad_tr_ntk(c_in, k);
+        NB2 = NT2 >= 48 ? 12 : (NT2 > 4 ? 4 : 1);
+        copies = std::max(copies, wgrad_max_copies(wgrad_tile_groups(MT2, NT2, MB2, NB2)));
+        NTk = std::max(NTk, NT2);
+    }
     const size_t segs = (size_t)copies * MTo * 16 * NTk * 16 + wgrad_bias_floats(c_out);
     return std::max(segs, wgrad_rows_h_supported(c_in, c_out, k, 1) ? wgrad_rows_h_scratch_floats(c_in, c_out) : (size_t)0);
 }
@@ -649,10 +872,39 @@ static hipError_t launch_wgrad_h_rb(const WgradArgs &a, int MB, int NB, size_t s
     return e;
 }
 
+template <int MB, int NB, int DT>
+static hipError_t launch_wgrad_tr_t(const WgradArgs &a, size_t smem, int blocks, hipStream_t stream)
+{
+    static bool attr_set = false;
+    if (smem > 48 * 1024 && !attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_tr_h_kernel<MB, NB, DT>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int mgroups = (a.MTo + MB - 1) / MB, ngroups = (a.NTk + 4 * NB - 1) / (4 * NB);
+    hipLaunchKernelGGL((wgrad_tr_h_kernel<MB, NB, DT>), dim3(blocks, mgroups * ngroups), dim3(256), smem, stream, a);
+    return hipGetLastError();
+}
+
+template <int DT>
+static hipError_t launch_wgrad_tr(const WgradArgs &a, int MB, int NB, size_t smem, int blocks, hipStream_t stream)
+{
+    hipError_t e = hipErrorInvalidValue;
+#define SK_WG_CASE(mb, nb) if (MB == mb && NB == nb) e = launch_wgrad_tr_t<mb, nb, DT>(a, smem, blocks, stream);
+    SK_WG_CASE(1, 1) SK_WG_CASE(1, 4) SK_WG_CASE(1, 12)
+    SK_WG_CASE(3, 1) SK_WG_CASE(3, 4) SK_WG_CASE(3, 12)
+    SK_WG_CASE(4, 1) SK_WG_CASE(4, 4) SK_WG_CASE(4, 12)
+#undef SK_WG_CASE
+    return e;
+}
+
 // floats of one private copy of a gradient, and of its bias partials
 static size_t wgrad_copy_floats(int c_out, int c_in, int k)
 {
-    return (size_t)((c_out + 15) / 16 * 16) * (size_t)((c_in * k * k + 15) / 16 * 16);
+    int ntk = (c_in * k * k + 15) / 16;
+    if (wgrad_tr_applies(c_in)) ntk = std::max(ntk, wgrad_tr_ntk(c_in, k));
+    return (size_t)((c_out + 15) / 16 * 16) * (size_t)ntk * 16;
 }
 
 size_t wgrad_min_scratch_floats(int c_out, int c_in, int k) { return wgrad_copy_floats(c_out, c_in, k) + wgrad_bias_floats(c_out); }
@@ -697,10 +949,23 @@ static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, floa
         while (NB > 1 && f32_smem(NB) > 150 * 1024) NB = NB == 12 ? 4 : NB - 1;
     // 16-bit storage (and a window of at most 128 columns): the 16-bit matrix path
     const bool h_path = DT != 0 && PW <= 128;
-    a.xpitch = h_path ? (PW + 7) / 8 * 8 + 8 : (PW + 31) / 32 * 32 + 4;
+    // ... with 16 input maps or more: octets staged as they are, fragments by the transposing LDS read
+    const bool tr_path = h_path && wgrad_tr_applies(c_in);
+    if (tr_path) {
+        a.NTk = wgrad_tr_ntk(c_in, k);
+        NB = a.NTk >= 48 ? 12 : (a.NTk > 4 ? 4 : 1);
+    }
+    a.xpitch = tr_path ? (PW + 7) / 8 * 8 + 4 : (h_path ? (PW + 7) / 8 * 8 + 8 : (PW + 31) / 32 * 32 + 4);
     // 16-bit matrix path: a tile group stages the input octets its columns touch (the most any group has)
     int goct = (c_in + 7) / 8;
-    if (h_path) {
+    if (tr_path) {
+        const int ngroups = (a.NTk + 4 * NB - 1) / (4 * NB), kk = k * k;
+        goct = 2;
+        for (int gi = 0; gi < ngroups; ++gi) {
+            const int lo = gi * NB * 4, hi = std::min(lo + NB * 4, a.NTk) - 1;
+            goct = std::max(goct, 2 * (hi / kk) + 2 - 2 * (lo / kk));
+        }
+    } else if (h_path) {
         const int K = c_in * k * k, ngroups = (a.NTk + 4 * NB - 1) / (4 * NB);
         goct = 1;
         for (int gi = 0; gi < ngroups; ++gi) {
@@ -710,7 +975,8 @@ static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, floa
     }
     const int x_rows = (DT == 0 ? c_in : goct * 8) * k;
     const size_t smem = DT == 0 ? f32_smem(NB)
-                                : sizeof(unsigned short) * ((size_t)MB * 16 * (h_path ? WG_DYH : WG_DYP) + (size_t)x_rows * a.xpitch);
+                        : tr_path ? 16 * ((size_t)2 * MB * WG_TRP + (size_t)goct * k * a.xpitch)
+                                  : sizeof(unsigned short) * ((size_t)MB * 16 * (h_path ? WG_DYH : WG_DYP) + (size_t)x_rows * a.xpitch);
     if (smem > 150 * 1024) return hipErrorInvalidValue;
     // as many persistent workgroups as fit on the GPU at once (more would only add private copies
     // for the reduction to read): LDS decides
@@ -739,7 +1005,9 @@ static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, floa
     if (bias_in_kernel) a.bias_part = bias_part;
     hipError_t e = hipErrorInvalidValue;
     if constexpr (DT != 0) {
-        if (h_path) {
+        if (tr_path) {
+            e = launch_wgrad_tr<DT>(a, MB, NB, smem, blocks, stream);
+        } else if (h_path) {
             if (k == 1 || d % 8 == 0) e = launch_wgrad_h_rb<DT, 16>(a, MB, NB, smem, blocks, stream);
             else if (d % 4 == 0) e = launch_wgrad_h_rb<DT, 8>(a, MB, NB, smem, blocks, stream);
             else if (d % 2 == 0) e = launch_wgrad_h_rb<DT, 4>(a, MB, NB, smem, blocks, stream);
@@ -775,9 +1043,10 @@ static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, floa
     }
     const int K = c_in * k * k;
     const long total = (long)c_out * K;
-    const int dw_blocks = (int)((total + RED_ELEMS - 1) / RED_ELEMS), db_blocks = db ? (c_out + RED_ELEMS - 1) / RED_ELEMS : 0;
+    const long walked = tr_path ? (long)c_out * a.NTk * 16 : total;       // (the reduction walks the copies' columns)
+    const int dw_blocks = (int)((walked + RED_ELEMS - 1) / RED_ELEMS), db_blocks = db ? (c_out + RED_ELEMS - 1) / RED_ELEMS : 0;
     hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(dw_blocks + db_blocks), dim3(256), 0, stream, scratch, dw, blocks, c_out, K,
-                       a.MTo * 16, a.NTk * 16, dw_blocks, bias_part, db, bias_in_kernel ? blocks : BG_SLICES);
+                       a.MTo * 16, a.NTk * 16, dw_blocks, bias_part, db, bias_in_kernel ? blocks : BG_SLICES, tr_path ? k * k : 0);
     return hipGetLastError();
 }
 
