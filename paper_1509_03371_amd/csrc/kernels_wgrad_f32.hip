@@ -790,6 +790,28 @@ static void wgrad_tiling(int c_out, int c_in, int k, bool f32, int &MTo, int &NT
 // column tiles of wgrad_tr_h_kernel (16-bit storage, 16 input maps or more): (pair of input octets, i, j)
 static bool wgrad_tr_applies(int c_in) { return c_in >= 16; }
 static int wgrad_tr_ntk(int c_in, int k) { return (c_in + 15) / 16 * k * k; }
+// input octets the column tiles of one tile group touch, at most (groups of 4*nb consecutive tiles; k*k tiles per map pair)
+static int wgrad_tr_goct(int ntk, int nb, int kk)
+{
+    const int ngroups = (ntk + 4 * nb - 1) / (4 * nb);
+    int goct = 2;
+    for (int gi = 0; gi < ngroups; ++gi) {
+        const int lo = gi * nb * 4, hi = std::min(lo + nb * 4, ntk) - 1;
+        goct = std::max(goct, 2 * (hi / kk) + 2 - 2 * (lo / kk));
+    }
+    return goct;
+}
+// Column tiles per wave.  The kernel prefetches ONE batch of 24 (octet, kernel row) input rows while it multiplies; a
+// group that needs more loads the rest in place and waits for it every segment.  So, for a gradient with many column
+// tiles: the largest count whose groups stay within one batch (3x3: 9 = four map pairs exactly, 8x8: 8 = half a pair,
+// 4x4: 12 = three pairs); 1x1 kernels touch a new octet pair with every tile and keep 12.
+static int wgrad_tr_nb(int ntk, int k)
+{
+    if (ntk < 48) return ntk > 4 ? 4 : 1;
+    for (int nb : {12, 9, 8, 6})
+        if (wgrad_tr_goct(ntk, nb, k * k) * k <= 24) return nb;
+    return 12;
+}
 
 // Private copies of a gradient.  A small gradient (one tile group: the 48x768 of the BASELINE nets)
 // takes one copy per resident workgroup; a large one is split over tile groups (blockIdx.y), which
@@ -822,7 +844,7 @@ size_t wgrad_f32_scratch_floats(int c_out, int c_in, int k)
         int MT2, NT2, MB2, NB2;
         wgrad_tiling(c_out, c_in, k, false, MT2, NT2, MB2, NB2);
         NT2 = wgrad_tr_ntk(c_in, k);
-        NB2 = NT2 >= 48 ? 12 : (NT2 > 4 ? 4 : 1);
+        NB2 = wgrad_tr_nb(NT2, k);
         copies = std::max(copies, wgrad_max_copies(wgrad_tile_groups(MT2, NT2, MB2, NB2)));
         NTk = std::max(NTk, NT2);
     }
@@ -892,9 +914,9 @@ static hipError_t launch_wgrad_tr(const WgradArgs &a, int MB, int NB, size_t sme
 {
     hipError_t e = hipErrorInvalidValue;
 #define SK_WG_CASE(mb, nb) if (MB == mb && NB == nb) e = launch_wgrad_tr_t<mb, nb, DT>(a, smem, blocks, stream);
-    SK_WG_CASE(1, 1) SK_WG_CASE(1, 4) SK_WG_CASE(1, 12)
-    SK_WG_CASE(3, 1) SK_WG_CASE(3, 4) SK_WG_CASE(3, 12)
-    SK_WG_CASE(4, 1) SK_WG_CASE(4, 4) SK_WG_CASE(4, 12)
+    SK_WG_CASE(1, 1) SK_WG_CASE(1, 4) SK_WG_CASE(1, 12) SK_WG_CASE(1, 6) SK_WG_CASE(1, 8) SK_WG_CASE(1, 9)
+    SK_WG_CASE(3, 1) SK_WG_CASE(3, 4) SK_WG_CASE(3, 12) SK_WG_CASE(3, 6) SK_WG_CASE(3, 8) SK_WG_CASE(3, 9)
+    SK_WG_CASE(4, 1) SK_WG_CASE(4, 4) SK_WG_CASE(4, 12) SK_WG_CASE(4, 6) SK_WG_CASE(4, 8) SK_WG_CASE(4, 9)
 #undef SK_WG_CASE
     return e;
 }
@@ -953,18 +975,13 @@ static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, floa
     const bool tr_path = h_path && wgrad_tr_applies(c_in);
     if (tr_path) {
         a.NTk = wgrad_tr_ntk(c_in, k);
-        NB = a.NTk >= 48 ? 12 : (a.NTk > 4 ? 4 : 1);
+        NB = wgrad_tr_nb(a.NTk, k);
     }
     a.xpitch = tr_path ? (PW + 7) / 8 * 8 + 4 : (h_path ? (PW + 7) / 8 * 8 + 8 : (PW + 31) / 32 * 32 + 4);
     // 16-bit matrix path: a tile group stages the input octets its columns touch (the most any group has)
     int goct = (c_in + 7) / 8;
     if (tr_path) {
-        const int ngroups = (a.NTk + 4 * NB - 1) / (4 * NB), kk = k * k;
-        goct = 2;
-        for (int gi = 0; gi < ngroups; ++gi) {
-            const int lo = gi * NB * 4, hi = std::min(lo + NB * 4, a.NTk) - 1;
-            goct = std::max(goct, 2 * (hi / kk) + 2 - 2 * (lo / kk));
-        }
+        goct = wgrad_tr_goct(a.NTk, NB, k * k);
     } else if (h_path) {
         const int K = c_in * k * k, ngroups = (a.NTk + 4 * NB - 1) / (4 * NB);
         goct = 1;
