@@ -555,7 +555,13 @@ __global__ __launch_bounds__(256) void wgrad_tr_h_kernel(WgradArgs a)
     const long xplane = (long)a.H * a.W, yplane = (long)a.Ho * a.Wo;
     const uint4v *dyp = static_cast<const uint4v *>(a.dy), *xp = static_cast<const uint4v *>(a.x);
     const int oc_end = 2 * MB;                                       // dY octet rows of the tile group (relative)
-    const int nrid = noct * k;                                       // (input octet, kernel row) pairs to stage
+    // kernel rows the group's tiles use: all k, or (a group inside one map pair: kernels with more than 4*NB taps) a range
+    int i_lo = 0, ni = k;
+    if (nk_lo / kk == nk_hi / kk) {
+        i_lo = (nk_lo % kk) / k;
+        ni = (nk_hi % kk) / k - i_lo + 1;
+    }
+    const int nrid = noct * ni;                                      // (input octet, kernel row) pairs to stage
     const int nbat = (nrid + 4 * XU - 1) / (4 * XU);
     const uint4v zero = uint4v{0u, 0u, 0u, 0u};
 
@@ -575,7 +581,7 @@ __global__ __launch_bounds__(256) void wgrad_tr_h_kernel(WgradArgs a)
         for (int u = 0; u < XU; ++u) {
             const int rid = wave + 4 * (bat * XU + u);
             const int ridc = rid < nrid ? rid : nrid - 1;
-            const int ocr = ridc / k, i = ridc - ocr * k;
+            const int ocr = ridc / ni, i = i_lo + ridc - ocr * ni;
             int oc = oc0 + ocr;
             oc = oc < c8i ? oc : c8i - 1;
             const uint4v *src = xp + ((long)b * c8i + oc) * xplane + (long)(y + i * d) * a.W;
@@ -598,11 +604,11 @@ __global__ __launch_bounds__(256) void wgrad_tr_h_kernel(WgradArgs a)
         for (int u = 0; u < XU; ++u) {
             const int rid = wave + 4 * (bat * XU + u);
             if (rid >= nrid) continue;                          // uniform
-            const int ocr = rid / k;
+            const int ocr = rid / ni, row = ocr * k + i_lo + rid - ocr * ni;
 #pragma unroll
             for (int v = 0; v < XV; ++v) {
                 const int xc = lane + 64 * v;
-                if (xc < PW) xs[rid * a.xpitch + xc] = (x0 + xc < a.W && oc0 + ocr < c8i) ? px[u][v] : zero;
+                if (xc < PW) xs[row * a.xpitch + xc] = (x0 + xc < a.W && oc0 + ocr < c8i) ? px[u][v] : zero;
             }
         }
     };
