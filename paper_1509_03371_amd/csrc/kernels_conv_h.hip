@@ -1608,12 +1608,53 @@ __global__ void pack_weights_h_kernel(const float *w, unsigned short *wp, int c_
 }
 
 struct PackHJobDev { const float *w; unsigned short *wp; int c_out, c_in, k, flip_transpose, mt, map4, gemm_m, gemm_c8; long total; };
-struct PackHJobs { PackHJobDev job[BATCH_MAX]; };
+// Batched packing through LDS.  One workgroup builds the fragments of one (map tile, chunk): it reads the slab of
+// W they come from -- 16 maps x (8 or 32) input maps x k*k taps, runs of whole rows of W, consecutive threads on
+// consecutive floats -- into LDS (zero where the maps end), and writes each 16-byte unit (eight input maps of one
+// row of a fragment) with one store.  Workgroups are dealt out over the jobs in proportion to their tile counts
+// (start[t] = first workgroup of job t).
+struct PackHJobs { PackHJobDev job[BATCH_MAX]; int start[BATCH_MAX + 1]; int n; };
+
 template <int DT>
-__global__ void pack_weights_h_batch_kernel(PackHJobs b)
+__global__ void __launch_bounds__(256) pack_weights_h_batch_kernel(PackHJobs b)
 {
-    const PackHJobDev &j = b.job[blockIdx.y];
-    pack_weights_h_body<DT>(j.w, j.wp, j.c_out, j.c_in, j.k, j.flip_transpose, j.mt, j.map4, j.gemm_m, j.gemm_c8, j.total);
+    extern __shared__ float pack_slab[];
+    int t = 0;
+    while (t + 1 < b.n && (int)blockIdx.x >= b.start[t + 1]) ++t;
+    const PackHJobDev &jb = b.job[t];
+    const int k = jb.k, k2 = k * k, MT = jb.mt, map4 = jb.map4, flip = jb.flip_transpose;
+    const int OC = map4 ? 1 : 4, CS = map4 ? (k + 3) / 4 : k, nchunks = (jb.gemm_c8 + OC - 1) / OC, Cc = 8 * OC;
+    const int lb = (int)blockIdx.x - b.start[t], mtile = lb / nchunks, ch = lb - mtile * nchunks;
+    const int m0 = mtile * 16, c0 = ch * Cc;                  // first GEMM output map / GEMM input map of the slab
+    // forward: slab[ml][cl*k2 + tap] = W[m0+ml][c0+cl][tap]; data-gradient operator: slab[cl][ml*k2 + tap] =
+    // W[c0+cl][m0+ml][tap] -- in both cases the order the floats have in W; rows one float apart from a multiple of
+    // the bank count
+    const int run = (flip ? 16 : Cc) * k2, rows = flip ? Cc : 16, row_lim = jb.c_out, col0 = flip ? m0 : c0;
+    const int row0 = flip ? c0 : m0;
+    for (int s = threadIdx.x; s < rows * run; s += 256) {
+        const int r = s / run, rem = s - r * run, cc = rem / k2;
+        float v = 0.f;
+        if (row0 + r < row_lim && col0 + cc < jb.c_in) v = jb.w[((long)(row0 + r) * jb.c_in + col0) * k2 + rem];
+        pack_slab[r * (run + 1) + rem] = v;
+    }
+    __syncthreads();
+    const int units = CS * k * 64;
+    const long frag0 = (((long)(mtile / MT) * nchunks + ch) * CS * k) * MT + mtile % MT;
+    for (int u = threadIdx.x; u < units; u += 256) {
+        const int l16 = u & 15, g = (u >> 4) & 3, ci = u >> 6, cs = ci / k, i = ci - cs * k;
+        const int j = map4 ? 4 * cs + g : cs;
+        unsigned short h[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int cl = map4 ? e : g * 8 + e;
+            float v = 0.f;
+            if (j < k) v = flip ? pack_slab[cl * (run + 1) + l16 * k2 + (k - 1 - i) * k + (k - 1 - j)] : pack_slab[l16 * (run + 1) + cl * k2 + i * k + j];
+            h[e] = H<DT>::cvt(v);
+        }
+        uint4v out = {(unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16),
+                      (unsigned)h[4] | ((unsigned)h[5] << 16), (unsigned)h[6] | ((unsigned)h[7] << 16)};
+        *reinterpret_cast<uint4v *>(jb.wp + (frag0 + (long)ci * MT) * 512 + (g * 16 + l16) * 8) = out;
+    }
 }
 
 // size in 16-bit elements of the packing of a GEMM with gemm_m output maps and gemm_c8 input octets
@@ -1664,7 +1705,8 @@ hipError_t launch_pack_weights_h_batch(const PackHJob *jobs, int n, int dtype, h
 {
     if (n < 1 || n > BATCH_MAX || (dtype != 1 && dtype != 2)) return hipErrorInvalidValue;
     PackHJobs b;
-    long most = 1;
+    long blocks = 0;
+    size_t smem = 0;
     for (int t = 0; t < n; ++t) {
         const PackHJob &j = jobs[t];
         PackHJobDev &o = b.job[t];
@@ -1676,11 +1718,28 @@ hipError_t launch_pack_weights_h_batch(const PackHJob *jobs, int n, int dtype, h
         o.total = packed_h_elems(o.gemm_m, o.gemm_c8, j.k, j.mt);
         o.mt = j.mt > 0 ? (j.mt & ~CONV_H_TAPCOLS) : 0;
         if (o.mt <= 0) o.mt = conv_h_mt(o.gemm_m, j.k);
-        most = o.total > most ? o.total : most;
+        const int OC = o.map4 ? 1 : 4, CS = o.map4 ? (j.k + 3) / 4 : j.k, nchunks = (o.gemm_c8 + OC - 1) / OC;
+        const long tiles = o.total / ((long)CS * j.k * 512);                 // (map tiles of all groups) x chunks
+        if (tiles % nchunks != 0) return hipErrorInvalidValue;
+        smem = std::max(smem, sizeof(float) * (16 * 8 * OC * j.k * j.k + 32));
+        b.start[t] = (int)blocks;
+        blocks += tiles;
+        if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
     }
-    const int blocks = (int)((most + 255) / 256 < 256 ? (most + 255) / 256 : 256);
-    if (dtype == 1) hipLaunchKernelGGL(pack_weights_h_batch_kernel<1>, dim3(blocks, n), dim3(256), 0, stream, b);
-    else hipLaunchKernelGGL(pack_weights_h_batch_kernel<2>, dim3(blocks, n), dim3(256), 0, stream, b);
+    for (int t = n; t <= BATCH_MAX; ++t) b.start[t] = (int)blocks;
+    b.n = n;
+    if (blocks == 0) return hipSuccess;
+    if (smem > 64 * 1024) {
+        // kernels too large for the slab: one plain launch per job
+        for (int t = 0; t < n; ++t) {
+            const hipError_t e = launch_pack_weights_h(jobs[t].w, jobs[t].wp, dtype, jobs[t].c_out, jobs[t].c_in, jobs[t].k, jobs[t].flip_transpose,
+                                                       jobs[t].mt, stream);
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
+    }
+    if (dtype == 1) hipLaunchKernelGGL(pack_weights_h_batch_kernel<1>, dim3((unsigned)blocks), dim3(256), smem, stream, b);
+    else hipLaunchKernelGGL(pack_weights_h_batch_kernel<2>, dim3((unsigned)blocks), dim3(256), smem, stream, b);
     return hipGetLastError();
 }
 

@@ -775,16 +775,51 @@ hipError_t launch_sgd_f32(float *w, const float *dw, float *v, long count, float
     return hipGetLastError();
 }
 
-// one launch for all parameter tensors of a net: blockIdx.y selects the tensor
-__global__ void sgd_batch_f32_kernel(SgdBatch b, float lr, float mu, float wd)
+// one launch for all parameter tensors of a net.  Workgroups are dealt out in proportion to the tensors' sizes
+// (SGD_CHUNK elements each; start[t] = first workgroup of tensor t), so the largest tensor does not finish alone;
+// a thread updates four float4 when the tensor's three arrays are 16-byte aligned.
+constexpr int SGD_CHUNK = 4096;
+struct SgdBatchDev { SgdBatch b; int start[BATCH_MAX + 1]; };
+
+// new velocity of one element (momentum mu, weight decay wd); the weight moves by minus this
+__device__ __forceinline__ float sgd_velocity(float w, float dw, float v_old, float lr, float mu, float wd)
 {
-    const int t = blockIdx.y;
-    float *w = b.w[t], *v = b.v[t];
-    const float *dw = b.dw[t];
-    const long count = b.count[t];
-    for (long q = blockIdx.x * (long)blockDim.x + threadIdx.x; q < count; q += (long)gridDim.x * blockDim.x) {
-        const float g = dw[q] + wd * w[q];
-        const float vel = (v ? mu * v[q] : 0.f) + lr * g;
+    return mu * v_old + lr * (dw + wd * w);
+}
+
+__global__ void __launch_bounds__(256) sgd_batch_f32_kernel(SgdBatchDev d, float lr, float mu, float wd)
+{
+    int t = 0;
+    while (t + 1 < d.b.n && (int)blockIdx.x >= d.start[t + 1]) ++t;
+    float *w = d.b.w[t], *v = d.b.v[t];
+    const float *dw = d.b.dw[t];
+    const long count = d.b.count[t], q0 = (long)((int)blockIdx.x - d.start[t]) * SGD_CHUNK;
+    const bool vec = ((reinterpret_cast<size_t>(w) | reinterpret_cast<size_t>(dw) | reinterpret_cast<size_t>(v)) & 15) == 0;
+    if (vec && q0 + SGD_CHUNK <= count) {
+        float4v wv[4], gv[4], vv[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const long q = q0 + (u * 256 + threadIdx.x) * 4;
+            wv[u] = *reinterpret_cast<const float4v *>(w + q);
+            gv[u] = *reinterpret_cast<const float4v *>(dw + q);
+            if (v) vv[u] = *reinterpret_cast<const float4v *>(v + q);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const long q = q0 + (u * 256 + threadIdx.x) * 4;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float vel = sgd_velocity(wv[u][i], gv[u][i], v ? vv[u][i] : 0.f, lr, mu, wd);
+                vv[u][i] = vel;
+                wv[u][i] -= vel;
+            }
+            *reinterpret_cast<float4v *>(w + q) = wv[u];
+            if (v) *reinterpret_cast<float4v *>(v + q) = vv[u];
+        }
+        return;
+    }
+    for (long q = q0 + threadIdx.x; q < q0 + SGD_CHUNK && q < count; q += 256) {
+        const float vel = sgd_velocity(w[q], dw[q], v ? v[q] : 0.f, lr, mu, wd);
         if (v) v[q] = vel;
         w[q] -= vel;
     }
@@ -793,9 +828,17 @@ __global__ void sgd_batch_f32_kernel(SgdBatch b, float lr, float mu, float wd)
 hipError_t launch_sgd_batch_f32(const SgdBatch &b, float lr, float mu, float wd, hipStream_t stream)
 {
     if (b.n < 1 || b.n > BATCH_MAX) return hipErrorInvalidValue;
-    long most = 1;
-    for (int t = 0; t < b.n; ++t) most = b.count[t] > most ? b.count[t] : most;
-    hipLaunchKernelGGL(sgd_batch_f32_kernel, dim3(grid_for(most, 256, 256), b.n), dim3(256), 0, stream, b, lr, mu, wd);
+    SgdBatchDev d;
+    d.b = b;
+    long blocks = 0;
+    for (int t = 0; t < b.n; ++t) {
+        d.start[t] = (int)blocks;
+        blocks += (b.count[t] + SGD_CHUNK - 1) / SGD_CHUNK;
+        if (b.count[t] < 0 || blocks > 0x7fffffffL) return hipErrorInvalidValue;
+    }
+    for (int t = b.n; t <= BATCH_MAX; ++t) d.start[t] = (int)blocks;
+    if (blocks == 0) return hipSuccess;
+    hipLaunchKernelGGL(sgd_batch_f32_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, d, lr, mu, wd);
     return hipGetLastError();
 }
 

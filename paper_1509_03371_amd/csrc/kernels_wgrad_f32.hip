@@ -743,6 +743,79 @@ __global__ void __launch_bounds__(256) wgrad_reduce_kernel(const float *__restri
     if (w == 0 && q >= 0) dw[q] = (sh[0][e] + sh[1][e]) + (sh[2][e] + sh[3][e]);
 }
 
+// Reduction of the copies of wgrad_tr_h_kernel with 16-byte accesses on both sides.  A copy row holds, per pair of
+// input octets, k*k column tiles of 16 maps: a run of 16*k*k floats that is the same stretch of dw[o] with (tap, map)
+// transposed to (map, tap).  A workgroup takes `rpb` whole runs of one row: `lanes` = span / 4 threads each sum a
+// float4 of every copy (the 256 / lanes thread groups share the copies out), the partial sums meet in LDS, and the
+// span leaves in the gradient's own order, again as float4 per thread.  Fixed summation order.
+constexpr int TRR_SPAN = 1024;     // floats of one row per workgroup at most
+
+__global__ void __launch_bounds__(256) wgrad_tr_reduce_kernel(const float *__restrict__ scratch, float *__restrict__ dw, int copies, int c_out, int K,
+                                                              int m_rows, int ncols, int k2, int rpb, int parts, int dw_blocks,
+                                                              const float *__restrict__ bias_part, float *__restrict__ db, int slices)
+{
+    __shared__ __attribute__((aligned(16))) float sh[TRR_SPAN];
+    const int t = threadIdx.x;
+    if ((int)blockIdx.x >= dw_blocks) {
+        // bias: 64 maps per workgroup, wave w adds slices w, w+4, ...; then the waves in order
+        const int e = t & 63, w = t >> 6;
+        const int o = ((int)blockIdx.x - dw_blocks) * 64 + e;
+        float v = 0.f;
+        if (o < c_out)
+            for (int sl = w; sl < slices; sl += 4) v += bias_part[(long)o * slices + sl];
+        sh[w * 64 + e] = v;
+        __syncthreads();
+        if (w == 0 && o < c_out) db[o] = (sh[e] + sh[64 + e]) + (sh[128 + e] + sh[192 + e]);
+        return;
+    }
+    const int o = (int)blockIdx.x / parts, part = (int)blockIdx.x - o * parts;
+    const int run_len = 16 * k2, col0 = part * rpb * run_len;
+    const int span = min(rpb * run_len, ncols - col0);            // whole runs: a multiple of 16
+    const int lanes = span >> 2;
+    int nsplit = 256 / lanes;
+    nsplit = nsplit < copies ? nsplit : copies;
+    const int cw = t / lanes, tt = t - cw * lanes;
+    if (cw < nsplit) {
+        const long stride = (long)m_rows * ncols;
+        const float *src = scratch + (long)o * ncols + col0 + 4 * tt;
+        floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = s0, s2 = s0, s3 = s0;
+        int c = cw;
+        for (; c + 3 * nsplit < copies; c += 4 * nsplit) {
+            const floatx4 v0 = *reinterpret_cast<const floatx4 *>(src + (long)c * stride);
+            const floatx4 v1 = *reinterpret_cast<const floatx4 *>(src + (long)(c + nsplit) * stride);
+            const floatx4 v2 = *reinterpret_cast<const floatx4 *>(src + (long)(c + 2 * nsplit) * stride);
+            const floatx4 v3 = *reinterpret_cast<const floatx4 *>(src + (long)(c + 3 * nsplit) * stride);
+            s0 += v0;
+            s1 += v1;
+            s2 += v2;
+            s3 += v3;
+        }
+        for (; c < copies; c += nsplit) s0 += *reinterpret_cast<const floatx4 *>(src + (long)c * stride);
+        *reinterpret_cast<floatx4 *>(sh + cw * span + 4 * tt) = (s0 + s1) + (s2 + s3);
+    }
+    __syncthreads();
+    if (t >= lanes) return;
+    // floats 4t .. 4t+3 of the span in the gradient's order: (run, map l, tap r) sits at run*run_len + r*16 + l
+    float v[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int e = 4 * t + i, run = e / run_len, within = e - run * run_len, l = within / k2, r = within - l * k2;
+        const int at = run * run_len + r * 16 + l;
+        float s = sh[at];
+        for (int p = 1; p < nsplit; ++p) s += sh[p * span + at];
+        v[i] = s;
+    }
+    const int pos = col0 + 4 * t;                                   // position in dw[o]; maps beyond c_in lie at pos >= K
+    float *dst = dw + (long)o * K + pos;
+    if ((K & 3) == 0 && (reinterpret_cast<size_t>(dw) & 15) == 0) {
+        if (pos < K) *reinterpret_cast<floatx4 *>(dst) = floatx4{v[0], v[1], v[2], v[3]};
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (pos + i < K) dst[i] = v[i];
+    }
+}
+
 // Bias gradient db[o] = sum over images and pixels of dY, in two stages with a fixed summation order.
 // Stage 1 (fp32 NCHW): workgroup (s, o) sums slice s of the pixels of map o over all images.
 constexpr int BG_SLICES = 64;
@@ -1068,6 +1141,19 @@ static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, floa
     const long total = (long)c_out * K;
     const long walked = tr_path ? (long)c_out * a.NTk * 16 : total;       // (the reduction walks the copies' columns)
     const int dw_blocks = (int)((walked + RED_ELEMS - 1) / RED_ELEMS), db_blocks = db ? (c_out + RED_ELEMS - 1) / RED_ELEMS : 0;
+    if (tr_path && 16 * k * k <= TRR_SPAN) {
+        // whole runs of 16*k*k floats per workgroup: few copies -> long spans (every thread a float4), many copies ->
+        // short spans, so that the thread groups of a workgroup share the copies out
+        const int k2 = k * k, run_len = 16 * k2, nruns = a.NTk / k2;
+        int want_split = blocks / 4;
+        want_split = want_split < 1 ? 1 : (want_split > 16 ? 16 : want_split);
+        int rpb = (256 / want_split) * 4 / run_len;
+        rpb = rpb < 1 ? 1 : (rpb > nruns ? nruns : rpb);
+        const int parts = (nruns + rpb - 1) / rpb, tr_blocks = c_out * parts;
+        hipLaunchKernelGGL(wgrad_tr_reduce_kernel, dim3(tr_blocks + db_blocks), dim3(256), 0, stream, scratch, dw, blocks, c_out, K, a.MTo * 16,
+                           a.NTk * 16, k2, rpb, parts, tr_blocks, bias_part, db, bias_in_kernel ? blocks : BG_SLICES);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(dw_blocks + db_blocks), dim3(256), 0, stream, scratch, dw, blocks, c_out, K,
                        a.MTo * 16, a.NTk * 16, dw_blocks, bias_part, db, bias_in_kernel ? blocks : BG_SLICES, tr_path ? k * k : 0);
     return hipGetLastError();
