@@ -844,8 +844,8 @@ hipError_t launch_sgd_batch_f32(const SgdBatch &b, float lr, float mu, float wd,
 
 // SGD on the bias of a 2x2 up-convolution, which its four taps share: the gradient is the sum of the four
 // taps' bias gradients (db4[t*c_out + o]); the new value goes to each tap's own copy.
-__global__ void up_bias_sgd_f32_kernel(float *b0, float *b1, float *b2, float *b3, const float *db4, float *v, int c_out, float lr,
-                                       float mu, float wd)
+__global__ void up_bias_sgd_f32_kernel(float *b0, float *b1, float *b2, float *b3, float *b_stacked, const float *db4, float *v, int c_out,
+                                       float lr, float mu, float wd)
 {
     const int o = blockIdx.x * blockDim.x + threadIdx.x;
     if (o >= c_out) return;
@@ -854,12 +854,17 @@ __global__ void up_bias_sgd_f32_kernel(float *b0, float *b1, float *b2, float *b
     if (v) v[o] = vel;
     const float nb = b0[o] - vel;
     b0[o] = nb; b1[o] = nb; b2[o] = nb; b3[o] = nb;
+    if (b_stacked) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) b_stacked[t * c_out + o] = nb;
+    }
 }
 
-hipError_t launch_up_bias_sgd_f32(float *b0, float *b1, float *b2, float *b3, const float *db4, float *v, int c_out, float lr, float mu,
-                                  float wd, hipStream_t stream)
+hipError_t launch_up_bias_sgd_f32(float *b0, float *b1, float *b2, float *b3, float *b_stacked, const float *db4, float *v, int c_out, float lr,
+                                  float mu, float wd, hipStream_t stream)
 {
-    hipLaunchKernelGGL(up_bias_sgd_f32_kernel, dim3((c_out + 255) / 256), dim3(256), 0, stream, b0, b1, b2, b3, db4, v, c_out, lr, mu, wd);
+    hipLaunchKernelGGL(up_bias_sgd_f32_kernel, dim3((c_out + 255) / 256), dim3(256), 0, stream, b0, b1, b2, b3, b_stacked, db4, v, c_out, lr, mu,
+                       wd);
     return hipGetLastError();
 }
 

@@ -267,9 +267,10 @@ struct SgdBatch {
     int n;
 };
 hipError_t launch_sgd_batch_f32(const SgdBatch &b, float lr, float mu, float wd, hipStream_t stream);
-// bias shared by the four taps of an up-convolution: gradient = sum of the taps' gradients db4[t*c_out + o]
-hipError_t launch_up_bias_sgd_f32(float *b0, float *b1, float *b2, float *b3, const float *db4, float *v, int c_out, float lr, float mu,
-                                  float wd, hipStream_t stream);
+// bias shared by the four taps of an up-convolution: gradient = sum of the taps' gradients db4[t*c_out + o]; the new
+// value goes to each tap's copy and, if given, four times into b_stacked[4*c_out] (the stacked 1x1 form's bias)
+hipError_t launch_up_bias_sgd_f32(float *b0, float *b1, float *b2, float *b3, float *b_stacked, const float *db4, float *v, int c_out, float lr,
+                                  float mu, float wd, hipStream_t stream);
 // out[b, o_off + c, y, x] = in[b, c, y + oy, x + ox] for c < maps (crop-and-place, MergeCrop halves)
 hipError_t launch_crop_copy_f32(const float *in, float *out, int n, int maps, int hi, int wi,
                                 int out_maps, int o_off, int ho, int wo, int oy, int ox,

@@ -908,15 +908,13 @@ sk_status unet_sgd_step(unet_t *net, float lr, float momentum, float weight_deca
     };
     for (auto &u : net->ups) {
         // the shared bias (its momentum lives in the stacked form's first c_out entries), then the taps' weights
-        SK_HIP(sk::launch_up_bias_sgd_f32(u.tap[0].b_dev, u.tap[1].b_dev, u.tap[2].b_dev, u.tap[3].b_dev, u.cat.db,
+        SK_HIP(sk::launch_up_bias_sgd_f32(u.tap[0].b_dev, u.tap[1].b_dev, u.tap[2].b_dev, u.tap[3].b_dev, u.cat.b_dev, u.cat.db,
                                           momentum != 0.f ? u.cat.vb : nullptr, u.c_out, lr, momentum, weight_decay, stream));
         // (the per-tap weights are only launched where the stacked form is not: map counts off the 16-map tile)
-        for (int t = 0; t < 4; ++t) {
-            SK_HIP(hipMemcpyAsync(u.cat.b_dev + (size_t)t * u.c_out, u.tap[0].b_dev, sizeof(float) * u.c_out, hipMemcpyDeviceToDevice, stream));
-            if (u.c_out % 16 != 0)
+        if (u.c_out % 16 != 0)
+            for (int t = 0; t < 4; ++t)
                 SK_HIP(hipMemcpyAsync(u.tap[t].w_dev, u.cat.w_dev + (size_t)t * u.c_out * u.c_in, sizeof(float) * u.c_out * u.c_in,
                                       hipMemcpyDeviceToDevice, stream));
-        }
     }
     if (net->dtype != SK_F32) {
         // 16-bit plans: the forward and data-gradient packings in the storage type
