@@ -367,7 +367,7 @@ __global__ void place_tap_f32_kernel(const float *src, float *dst, long maps, in
     }
 }
 
-__global__ void place_taps_f32_kernel(const float *src, float *dst, int c_out, int C, int k)
+__global__ void place_taps_f32_kernel(const float *src, float *dst, int c_out, int C, int k, int Cs)
 {
     const int kk = k * k;
     const long total = (long)c_out * C * k * kk;
@@ -377,13 +377,15 @@ __global__ void place_taps_f32_kernel(const float *src, float *dst, int c_out, i
         const int c = (int)(t % C);
         t /= C;
         const int a = (int)(t % k), o = (int)(t / k);
-        dst[(((long)o * C + c) * k + a) * kk + r] = src[q];
+        dst[(((long)o * C + c) * k + a) * kk + r] = src[(((long)o * k + a) * Cs + c) * kk + r];
     }
 }
 
-hipError_t launch_place_taps_f32(const float *src, float *dst, int c_out, int C, int k, hipStream_t stream)
+hipError_t launch_place_taps_f32(const float *src, float *dst, int c_out, int C, int k, hipStream_t stream, int src_maps_per_tap)
 {
-    hipLaunchKernelGGL(place_taps_f32_kernel, dim3(grid_for((long)c_out * C * k * k * k)), dim3(256), 0, stream, src, dst, c_out, C, k);
+    const int Cs = src_maps_per_tap > 0 ? src_maps_per_tap : C;
+    if (Cs < C) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(place_taps_f32_kernel, dim3(grid_for((long)c_out * C * k * k * k)), dim3(256), 0, stream, src, dst, c_out, C, k, Cs);
     return hipGetLastError();
 }
 

@@ -49,6 +49,10 @@ struct WgradArgs {
     // convolution: see launch_conv_f32); grp_shift = 31: no groups
     long x_bstride, grp_skip;
     int grp_shift;
+    // transposing-read 16-bit kernel only, in octet planes: consecutive images start xb8 planes apart (default: the
+    // octets of c_in), and the input octets come in groups of grp8 with skip8 more planes between groups (the depth
+    // taps of a 3-D convolution on slice-major volumes: slices as overlapping images)
+    int xb8, grp8, skip8;
     // 16-bit matrix path: bias_part != nullptr makes the kernel sum dY over the pixels as well (one more MFMA per map tile
     // against a fragment of ones) and write bias_part[map * gridDim.x + blockIdx.x]
     float *bias_part;
@@ -375,7 +379,7 @@ __global__ __launch_bounds__(256) void wgrad_h_kernel(WgradArgs a)
             const int ocr = ridc / k, i = ridc - ocr * k;
             int oc = oc0 + ocr;
             oc = oc < c8i ? oc : c8i - 1;
-            const uint4v *src = xp + ((long)b * c8i + oc) * xplane + (long)(y + i * d) * a.W;
+            const uint4v *src = xp + ((long)b * a.xb8 + oc + (oc / a.grp8) * a.skip8) * xplane + (long)(y + i * d) * a.W;
 #pragma unroll
             for (int v = 0; v < XV; ++v) {
                 const int xc = lane + 64 * v;
@@ -584,7 +588,7 @@ __global__ __launch_bounds__(256) void wgrad_tr_h_kernel(WgradArgs a)
             const int ocr = ridc / ni, i = i_lo + ridc - ocr * ni;
             int oc = oc0 + ocr;
             oc = oc < c8i ? oc : c8i - 1;
-            const uint4v *src = xp + ((long)b * c8i + oc) * xplane + (long)(y + i * d) * a.W;
+            const uint4v *src = xp + ((long)b * a.xb8 + oc + (oc / a.grp8) * a.skip8) * xplane + (long)(y + i * d) * a.W;
 #pragma unroll
             for (int v = 0; v < XV; ++v) {
                 const int xc = lane + 64 * v;
@@ -1018,12 +1022,20 @@ static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, floa
     WgradArgs a;
     a.x_bstride = x_bstride ? x_bstride : (long)c_in * H * W;
     a.grp_shift = 31; a.grp_skip = 0;
-    if (grp_maps > 0) {
-        if (DT != 0 || (grp_maps & (grp_maps - 1)) != 0 || c_in % grp_maps != 0 || grp_skip < 0) return hipErrorInvalidValue;
+    a.xb8 = (c_in + 7) / 8; a.grp8 = 1 << 30; a.skip8 = 0;
+    const bool grouped_h = DT != 0 && (grp_maps > 0 || x_bstride != 0);
+    if (grouped_h) {
+        // 16-bit storage: x_bstride and grp_skip count octet planes, grp_maps is a multiple of 8 (transposing-read kernel only)
+        if (grp_maps < 0 || grp_maps % 8 != 0 || grp_skip < 0 || x_bstride < 0 || x_bstride > 0x7fffffffL || grp_skip > 0x7fffffffL ||
+            (grp_maps > 0 && c_in % grp_maps != 0))
+            return hipErrorInvalidValue;
+        if (x_bstride > 0) a.xb8 = (int)x_bstride;
+        if (grp_maps > 0) { a.grp8 = grp_maps / 8; a.skip8 = (int)grp_skip; }
+        a.x_bstride = 0;
+    } else if (grp_maps > 0) {
+        if ((grp_maps & (grp_maps - 1)) != 0 || c_in % grp_maps != 0 || grp_skip < 0) return hipErrorInvalidValue;
         a.grp_shift = __builtin_ctz((unsigned)grp_maps);
         a.grp_skip = grp_skip;
-    } else if (DT != 0 && x_bstride != 0) {
-        return hipErrorInvalidValue;
     }
     a.x = x; a.dy = dy; a.scratch = scratch; a.bias_part = nullptr;
     a.n = n; a.c_in = c_in; a.H = H; a.W = W; a.c_out = c_out; a.k = k; a.d = d;
@@ -1052,6 +1064,7 @@ static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, floa
     const bool h_path = DT != 0 && PW <= 128;
     // ... with 16 input maps or more: octets staged as they are, fragments by the transposing LDS read
     const bool tr_path = h_path && wgrad_tr_applies(c_in);
+    if (grouped_h && !tr_path) return hipErrorInvalidValue;
     if (tr_path) {
         a.NTk = wgrad_tr_ntk(c_in, k);
         NB = wgrad_tr_nb(a.NTk, k);
@@ -1170,6 +1183,28 @@ hipError_t launch_wgrad_f32_grouped(const float *x, const float *dy, float *dw, 
                                     int W, int c_out, int k, int d, long x_bstride, int grp_maps, long grp_skip, hipStream_t stream)
 {
     return launch_wgrad_dt<0>(x, dy, dw, db, scratch, n, c_in, H, W, c_out, k, d, stream, x_bstride, grp_maps, grp_skip);
+}
+
+// 16-bit storage, input maps in groups (the depth taps of a 3-D convolution as input maps; see WgradArgs): images start
+// xb8 octet planes apart, groups of grp_maps maps (a multiple of 8, 0 = none) lie skip8 more planes apart.  Needs at
+// least 16 input maps and a staged window of at most 128 columns (wgrad_h_grouped_supported).
+bool wgrad_h_grouped_supported(int c_in, int c_out, int k, int d)
+{
+    if (!wgrad_tr_applies(c_in) || c_in % 8 != 0 || WG_SEG + (k - 1) * d > 128) return false;
+    int MTo, NTk, MB, NB;
+    wgrad_tiling(c_out, c_in, k, false, MTo, NTk, MB, NB);
+    NTk = wgrad_tr_ntk(c_in, k);
+    NB = wgrad_tr_nb(NTk, k);
+    const int PW = WG_SEG + (k - 1) * d, xpitch = (PW + 7) / 8 * 8 + 4;
+    return 16 * ((size_t)2 * MB * WG_TRP + (size_t)wgrad_tr_goct(NTk, NB, k * k) * k * xpitch) <= 150 * 1024;
+}
+
+hipError_t launch_wgrad_h_grouped(const void *x, const void *dy, float *dw, float *db, float *scratch, int dtype, int n, int c_in, int H, int W,
+                                  int c_out, int k, int d, int xb8, int grp_maps, int skip8, hipStream_t stream, size_t scratch_cap)
+{
+    if (dtype != 1 && dtype != 2) return hipErrorInvalidValue;
+    return dtype == 1 ? launch_wgrad_dt<1>(x, dy, dw, db, scratch, n, c_in, H, W, c_out, k, d, stream, xb8, grp_maps, skip8, scratch_cap)
+                      : launch_wgrad_dt<2>(x, dy, dw, db, scratch, n, c_in, H, W, c_out, k, d, stream, xb8, grp_maps, skip8, scratch_cap);
 }
 
 // same gradient from 16-bit octet-layout activations (dtype 1 = bf16, 2 = fp16): the operands are

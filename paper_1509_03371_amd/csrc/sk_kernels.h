@@ -194,6 +194,13 @@ hipError_t launch_wgrad_f32(const float *x, const float *dy, float *dw, float *d
 hipError_t launch_wgrad_f32_grouped(const float *x, const float *dy, float *dw, float *db, float *scratch, int n, int c_in, int H,
                                     int W, int c_out, int k, int d, long x_bstride, int grp_maps, long grp_skip, hipStream_t stream);
 
+// 16-bit storage with the input maps in groups: consecutive images start xb8 octet planes apart (0 = the octets of c_in),
+// groups of grp_maps maps (a multiple of 8, 0 = none) lie skip8 more planes apart -- the depth taps of a 3-D convolution
+// on slice-major volumes as input maps.  c_in is a multiple of 8; ask wgrad_h_grouped_supported first.
+bool wgrad_h_grouped_supported(int c_in, int c_out, int k, int d);
+hipError_t launch_wgrad_h_grouped(const void *x, const void *dy, float *dw, float *db, float *scratch, int dtype, int n, int c_in, int H, int W,
+                                  int c_out, int k, int d, int xb8, int grp_maps, int skip8, hipStream_t stream, size_t scratch_cap = 0);
+
 // zeros: at least 1 KB of zeros in device memory (the row-streaming form of the 4x4 gradient reads the gradient rows
 // beyond the image from there); nullptr keeps every shape on the segment kernel
 hipError_t launch_wgrad_h(const void *x, const void *dy, float *dw, float *db, float *scratch, int dtype,
@@ -237,8 +244,9 @@ hipError_t launch_tap3d_to_index(const uint8_t *tap, int32_t *idx, int C, int Do
                                  hipStream_t stream);
 // dst[(m*k + a)*k*k + r] = src[m*k*k + r] for m < maps, r < k*k
 hipError_t launch_place_tap_f32(const float *src, float *dst, long maps, int k, int a, hipStream_t stream);
-// dst[((o*C + c)*k + a)*k*k + r] = src[((o*k + a)*C + c)*k*k + r]: a gradient whose input maps are (depth tap, map) pairs
-hipError_t launch_place_taps_f32(const float *src, float *dst, int c_out, int C, int k, hipStream_t stream);
+// dst[((o*C + c)*k + a)*k*k + r] = src[((o*k + a)*Cs + c)*k*k + r]: a gradient whose input maps are (depth tap, map) pairs;
+// Cs = src_maps_per_tap (0: C) -- the 16-bit gradient carries 8*ceil(C/8) maps per tap
+hipError_t launch_place_taps_f32(const float *src, float *dst, int c_out, int C, int k, hipStream_t stream, int src_maps_per_tap = 0);
 // packings of a 3-D kernel [c_out][C][k][k][k] for launch_conv_f32 (see kernels_conv_f32.hip)
 hipError_t launch_pack_weights3d_f32(const float *w3, float *wp, int c_out, int C, int k, int a0, int len, int flip_transpose, int rows,
                                      int n_pad, hipStream_t stream);

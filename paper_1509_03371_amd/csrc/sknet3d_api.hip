@@ -51,7 +51,8 @@ struct Conv3 {
     float *exp2d = nullptr;            // fp32 staging of the two 2-D masters these are packed from
     float *dw = nullptr, *db = nullptr, *vw = nullptr, *vb = nullptr, *dw_tap = nullptr;
     // weight gradient of all depth taps in one launch: k > 1 and (d = 1, the tapped slices adjacent, or a power-of-two
-    // map count, which the kernel's grouped addressing needs)
+    // map count, which the kernel's grouped addressing needs); 16-bit storage: whole octets per tap, where the grouped
+    // form of the 16-bit gradient takes the shape
     bool wgrad_merged = false;
     long wcount() const { return (long)c_out * c_in * k * k * k; }
 };
@@ -130,7 +131,7 @@ sk_status upload_conv3_h(Conv3 &c, int dtype, bool with_bwd = false)
     return SK_OK;
 }
 
-sk_status alloc_conv3(Conv3 &c, bool training, bool needs_dgrad)
+sk_status alloc_conv3(Conv3 &c, bool training, bool needs_dgrad, bool half)
 {
     release_conv3(c);
     c.n_pad = round_up(c.c_out, 16);
@@ -147,8 +148,10 @@ sk_status alloc_conv3(Conv3 &c, bool training, bool needs_dgrad)
         SK_TRY(alloc_f(&c.db, c.c_out));
         SK_TRY(alloc_f(&c.vw, c.wcount()));
         SK_TRY(alloc_f(&c.vb, c.c_out));
-        c.wgrad_merged = c.k > 1 && (c.d == 1 || (c.c_in & (c.c_in - 1)) == 0);
-        SK_TRY(alloc_f(&c.dw_tap, (long)c.c_out * c.c_in * c.k * c.k * (c.wgrad_merged ? c.k : 1)));
+        const int maps8 = (c.c_in + 7) / 8 * 8;
+        if (half) c.wgrad_merged = c.k > 1 && sk::wgrad_h_grouped_supported(c.k * maps8, c.c_out, c.k, c.d);
+        else c.wgrad_merged = c.k > 1 && (c.d == 1 || (c.c_in & (c.c_in - 1)) == 0);
+        SK_TRY(alloc_f(&c.dw_tap, (long)c.c_out * (half && c.wgrad_merged ? maps8 : c.c_in) * c.k * c.k * (c.wgrad_merged ? c.k : 1)));
         SK_HIP(hipMemset(c.vw, 0, sizeof(float) * c.wcount()));
         SK_HIP(hipMemset(c.vb, 0, sizeof(float) * c.c_out));
     }
@@ -492,14 +495,15 @@ sk_status sknet3d_plan(sknet3d_t *net, int32_t dz, int32_t h, int32_t w, int32_t
             if (e != hipSuccess) st = fail(SK_ENOMEM, "plan: winner codes: %s", hipGetErrorString(e));
         } else {
             // one launch over all depth taps (k * C input maps) or one per tap: the larger need
-            const size_t s = std::max(sk::wgrad_f32_scratch_floats(l.c_out, dims[i].c, l.k), sk::wgrad_f32_scratch_floats(l.c_out, l.k * dims[i].c, l.k));
+            size_t s = std::max(sk::wgrad_f32_scratch_floats(l.c_out, dims[i].c, l.k), sk::wgrad_f32_scratch_floats(l.c_out, l.k * dims[i].c, l.k));
+            if (half) s = std::max(s, sk::wgrad_f32_scratch_floats(l.c_out, l.k * ((dims[i].c + 7) / 8 * 8), l.k));
             if (s > scratch) scratch = s;
         }
     }
     for (int i = 0; i < L && st == SK_OK; ++i) {
         if (net->layers[i].kind != SK_CONV) continue;
         Conv3 &c = net->convs[net->conv_of_layer[i]];
-        st = alloc_conv3(c, training, i > 0);
+        st = alloc_conv3(c, training, i > 0, half);
         if (st == SK_OK) st = upload_conv3(c, nullptr);
         if (st == SK_OK && half) st = upload_conv3_h(c, net->dtype, training && i > 0);
         if (st == SK_OK && half && training && i > 0 && !sk::conv_h_supported(c.k, c.d, c.c_in))
@@ -603,10 +607,18 @@ static sk_status backward3_h(sknet3d *net, const int32_t *labels_dev, float *los
         float *dst = li > 0 ? gnext + (long)grad_pad(net, li - 1) * in_slice : nullptr;
         if (l.kind == SK_CONV) {
             Conv3 &c = net->convs[net->conv_of_layer[li]];
-            for (int a = 0; a < l.k; ++a) {
-                SK_HIP(sk::launch_wgrad_h(net->act[li] + (long)a * l.d * in_slice, g, c.dw_tap, a + 1 == l.k ? c.db : nullptr, net->wgrad_scratch,
-                                          dt, out.dz, in.c, in.h, in.w, c.c_out, l.k, l.d, stream, 0, net->zero_page));
-                SK_HIP(sk::launch_place_tap_f32(c.dw_tap, c.dw, (long)c.c_out * c.c_in, l.k, a, stream));
+            if (c.wgrad_merged) {
+                // all depth taps in one launch: the (tap, octet) pairs are the input octets, as in the forward pass
+                const int i8 = (in.c + 7) / 8;
+                SK_HIP(sk::launch_wgrad_h_grouped(net->act[li], g, c.dw_tap, c.db, net->wgrad_scratch, dt, out.dz, l.k * i8 * 8, in.h, in.w, c.c_out,
+                                                  l.k, l.d, i8, l.d > 1 ? i8 * 8 : 0, (l.d - 1) * i8, stream));
+                SK_HIP(sk::launch_place_taps_f32(c.dw_tap, c.dw, c.c_out, c.c_in, l.k, stream, i8 * 8));
+            } else {
+                for (int a = 0; a < l.k; ++a) {
+                    SK_HIP(sk::launch_wgrad_h(net->act[li] + (long)a * l.d * in_slice, g, c.dw_tap, a + 1 == l.k ? c.db : nullptr,
+                                              net->wgrad_scratch, dt, out.dz, in.c, in.h, in.w, c.c_out, l.k, l.d, stream, 0, net->zero_page));
+                    SK_HIP(sk::launch_place_tap_f32(c.dw_tap, c.dw, (long)c.c_out * c.c_in, l.k, a, stream));
+                }
             }
             if (li == 0) break;   // nothing below needs the volume's gradient
             if (pad > 0) {
