@@ -687,6 +687,224 @@ __global__ __launch_bounds__(256) void wgrad_tr_h_kernel(WgradArgs a)
     }
 }
 
+// The same gradient with the staged input rows kept across steps (k >= 2, every tile group uses all k kernel rows).
+// A workgroup walks a strip -- one image, one 64-column segment, the output rows of one residue class y = r, r + d,
+// r + 2d, ... -- so that consecutive steps share k - 1 of their k input rows: the rows sit in a ring of k LDS slots per
+// input octet (input row y + i*d of step t in slot (t + i) mod k), a step loads one new row per octet instead of k,
+// and the column tiles' read offsets rotate with the step.  The steps of all strips, in strip order, are dealt out
+// to the workgroups in equal contiguous ranges; the first step of a range or of a strip loads all k rows.
+template <int MB, int NB, int DT>
+__global__ __launch_bounds__(256, MB * NB > 36 ? 1 : 2) void wgrad_trr_h_kernel(WgradArgs a)
+{
+    constexpr int DYL = (2 * MB + 3) / 4;   // dY octet loads per wave and step
+    constexpr int XU = 3, XV = 2;           // input loads per wave and batch: XU row ids x XV groups of 64 columns
+    extern __shared__ uint4v smem16[];
+    const int k = a.k, d = a.d, kk = k * k;
+    const int m_rows = a.MTo * 16;
+    uint4v *dys = smem16;                               // [2*MB octets][WG_TRP pixels]
+    uint4v *xs = dys + 2 * MB * WG_TRP;                 // [(octets of the group) * k slots][xpitch pixels]
+    const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, g = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int rr = l16 >> 2, qq = l16 & 3;
+    const int PW = WG_SEG + (k - 1) * d;                // <= 64 * XV (checked by the launcher)
+
+    const int ngroups = (a.NTk + 4 * NB - 1) / (4 * NB);
+    const int mgroup = blockIdx.y / ngroups, ngroup = blockIdx.y - mgroup * ngroups;
+    const int mo0 = mgroup * MB;
+    const int c8o = (a.c_out + 7) / 8, c8i = (a.c_in + 7) / 8;
+    const int nk_lo = ngroup * NB * 4;
+    int nk_hi = nk_lo + NB * 4 - 1;
+    nk_hi = nk_hi < a.NTk - 1 ? nk_hi : a.NTk - 1;
+    const int oc0 = 2 * (nk_lo / kk), noct = 2 * (nk_hi / kk) + 2 - oc0;     // <= 4 * XU = 12 (checked by the launcher)
+    const unsigned slot_bytes = (unsigned)a.xpitch * 16;
+    unsigned xoff[NB], aoff[MB];
+    int iq[NB];                                         // kernel row of column tile q (wave-uniform)
+#pragma unroll
+    for (int q = 0; q < NB; ++q) {
+        const int nk = (ngroup * NB + q) * 4 + wave;
+        unsigned off = (unsigned)((8 * g + rr) * 16);
+        iq[q] = 0;
+        if (nk < a.NTk) {
+            const int op = nk / kk, r = nk - op * kk, i = r / k, j = r - i * k;
+            off = (unsigned)((((2 * op - oc0 + (qq >> 1)) * k) * a.xpitch + j * d + 8 * g + rr) * 16 + (qq & 1) * 8);
+            iq[q] = i;
+        }
+        xoff[q] = off;
+    }
+#pragma unroll
+    for (int m = 0; m < MB; ++m) aoff[m] = (unsigned)(((2 * m + (qq >> 1)) * WG_TRP + 8 * g + rr) * 16 + (qq & 1) * 8);
+    floatx4 acc[MB][NB];
+#pragma unroll
+    for (int m = 0; m < MB; ++m)
+#pragma unroll
+        for (int q = 0; q < NB; ++q) acc[m][q] = floatx4{0.f, 0.f, 0.f, 0.f};
+    const bool sum_dy = a.bias_part != nullptr && ngroup == 0 && wave < MB && mo0 + wave < a.MTo;
+    floatx4 bacc = floatx4{0.f, 0.f, 0.f, 0.f};
+    const unsigned one2 = DT == 1 ? 0x3F803F80u : 0x3C003C00u;
+    const uint4v ones = uint4v{one2, one2, one2, one2};
+
+    const long xplane = (long)a.H * a.W, yplane = (long)a.Ho * a.Wo;
+    const uint4v *dyp = static_cast<const uint4v *>(a.dy), *xp = static_cast<const uint4v *>(a.x);
+    const int oc_end = 2 * MB;
+    const int nrid = noct * k;                                       // (input octet, kernel row) pairs of a fresh step
+    const int nbat = (nrid + 4 * XU - 1) / (4 * XU);
+    const uint4v zero = uint4v{0u, 0u, 0u, 0u};
+
+    uint4v pdy[DYL], px[XU][XV];
+    auto load_dy = [&](int b, int y, int x0) {
+        const int xl = x0 + lane < a.Wo ? x0 + lane : a.Wo - 1;
+#pragma unroll
+        for (int t = 0; t < DYL; ++t) {
+            const int oc = mo0 * 2 + wave + 4 * t;
+            const int occ = oc < c8o ? oc : c8o - 1;
+            pdy[t] = dyp[((long)b * c8o + occ) * yplane + (long)y * a.Wo + xl];
+        }
+    };
+    // fresh: row ids run over (octet, kernel row); else over the octets, each loading its one new row (kernel row k - 1)
+    auto load_x = [&](int bat, int b, int y, int x0, bool fresh) {
+        const int lim = fresh ? nrid : noct;
+#pragma unroll
+        for (int u = 0; u < XU; ++u) {
+            const int rid = wave + 4 * (bat * XU + u);
+            const int ridc = rid < lim ? rid : lim - 1;
+            const int ocr = fresh ? ridc / k : ridc, i = fresh ? ridc - ocr * k : k - 1;
+            int oc = oc0 + ocr;
+            oc = oc < c8i ? oc : c8i - 1;
+            const uint4v *src = xp + ((long)b * a.xb8 + oc + (oc / a.grp8) * a.skip8) * xplane + (long)(y + i * d) * a.W;
+#pragma unroll
+            for (int v = 0; v < XV; ++v) {
+                const int xc = lane + 64 * v;
+                px[u][v] = src[x0 + xc < a.W ? x0 + xc : a.W - 1];
+            }
+        }
+    };
+    auto store_dy = [&](int x0) {
+#pragma unroll
+        for (int t = 0; t < DYL; ++t) {
+            const int rel = wave + 4 * t;
+            if (rel < oc_end) dys[rel * WG_TRP + lane] = (mo0 * 2 + rel < c8o && x0 + lane < a.Wo) ? pdy[t] : zero;
+        }
+    };
+    auto store_x = [&](int bat, int x0, bool fresh, int rot) {
+        const int lim = fresh ? nrid : noct;
+#pragma unroll
+        for (int u = 0; u < XU; ++u) {
+            const int rid = wave + 4 * (bat * XU + u);
+            if (rid >= lim) continue;                           // uniform
+            const int ocr = fresh ? rid / k : rid, i = fresh ? rid - ocr * k : k - 1;
+            int slot = i + rot;
+            slot = slot >= k ? slot - k : slot;
+            const int row = ocr * k + slot;
+#pragma unroll
+            for (int v = 0; v < XV; ++v) {
+                const int xc = lane + 64 * v;
+                if (xc < PW) xs[row * a.xpitch + xc] = (x0 + xc < a.W && oc0 + ocr < c8i) ? px[u][v] : zero;
+            }
+        }
+    };
+    // steps of this workgroup: [g0, g1) of the strip order (image and segment, residue class, step within the class)
+    const int per = (a.total_segs + (int)gridDim.x - 1) / (int)gridDim.x;
+    const int g0 = (int)blockIdx.x * per;
+    const int g1 = g0 + per < a.total_segs ? g0 + per : a.total_segs;
+    auto class_len = [&](int r) { return r < a.Ho ? (a.Ho - r + d - 1) / d : 0; };
+    int bx = 0, r = 0, t = 0;
+    if (g0 < g1) {
+        bx = g0 / a.Ho;
+        int rem = g0 - bx * a.Ho;
+        while (rem >= class_len(r)) { rem -= class_len(r); ++r; }
+        t = rem;
+    }
+    // position of the step after (bx, r, t); fresh = it starts a strip
+    auto advance = [&](int &bx_, int &r_, int &t_, bool &fresh_) {
+        ++t_;
+        fresh_ = false;
+        if (t_ >= class_len(r_)) {
+            t_ = 0; ++r_; fresh_ = true;
+            if (r_ >= d || class_len(r_) == 0) { r_ = 0; ++bx_; }
+        }
+    };
+    auto place = [&](int bx_, int r_, int t_, int &b_, int &y_, int &x0_) {
+        b_ = bx_ / a.xsegs;
+        x0_ = (bx_ - b_ * a.xsegs) * WG_SEG;
+        y_ = r_ + t_ * d;
+    };
+
+    const char *dys_b = reinterpret_cast<const char *>(dys), *xs_b = reinterpret_cast<const char *>(xs);
+    int b = 0, y = 0, x0 = 0, rot = 0;
+    bool fresh = true;
+    if (g0 < g1) {
+        place(bx, r, t, b, y, x0);
+        load_dy(b, y, x0);
+        load_x(0, b, y, x0, true);
+    }
+    for (int gs = g0; gs < g1; ++gs) {
+        __syncthreads();                                        // the previous step's MFMAs have read LDS
+        store_dy(x0);
+        store_x(0, x0, fresh, rot);
+        if (fresh) {
+            for (int bat = 1; bat < nbat; ++bat) {
+                load_x(bat, b, y, x0, true);
+                store_x(bat, x0, true, rot);
+            }
+        }
+        __syncthreads();
+        const int rot_now = rot;
+        if (gs + 1 < g1) {                                      // in flight while this step is multiplied
+            advance(bx, r, t, fresh);
+            rot = fresh ? 0 : (rot + 1 == k ? 0 : rot + 1);
+            place(bx, r, t, b, y, x0);
+            load_dy(b, y, x0);
+            load_x(0, b, y, x0, fresh);
+        }
+        unsigned xo[NB];
+#pragma unroll
+        for (int q = 0; q < NB; ++q) {
+            int slot = iq[q] + rot_now;
+            slot = slot >= k ? slot - k : slot;
+            xo[q] = xoff[q] + (unsigned)slot * slot_bytes;
+        }
+#pragma unroll
+        for (int p = 0; p < WG_SEG; p += 32) {
+            uint4v av[MB];
+#pragma unroll
+            for (int m = 0; m < MB; ++m) av[m] = read_frag_tr(dys_b, aoff[m] + p * 16, aoff[m] + p * 16 + 64);
+#pragma unroll
+            for (int q = 0; q < NB; ++q) {
+                const uint4v bv = read_frag_tr(xs_b, xo[q] + p * 16, xo[q] + p * 16 + 64);
+#pragma unroll
+                for (int m = 0; m < MB; ++m) acc[m][q] = mfma32<DT>(av[m], bv, acc[m][q]);
+            }
+            if (sum_dy) {                                        // wave-uniform
+                uint4v aw = av[0];
+#pragma unroll
+                for (int m = 1; m < MB; ++m) aw = wave == m ? av[m] : aw;
+                bacc = mfma32<DT>(aw, ones, bacc);
+            }
+        }
+    }
+    if (sum_dy && l16 == 0) {                                   // every column of bacc holds the same sums
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+            const int o = (mo0 + wave) * 16 + 4 * g + r4;
+            if (o < a.c_out) a.bias_part[(long)o * gridDim.x + blockIdx.x] = bacc[r4];
+        }
+    }
+    const long ncols = (long)a.NTk * 16;
+    float *dst = a.scratch + (long)blockIdx.x * m_rows * ncols;
+#pragma unroll
+    for (int m = 0; m < MB; ++m) {
+        if (mo0 + m >= a.MTo) continue;
+#pragma unroll
+        for (int q = 0; q < NB; ++q) {
+            const int nk = (ngroup * NB + q) * 4 + wave;
+            if (nk >= a.NTk) continue;
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4)
+                dst[((long)(mo0 + m) * 16 + 4 * g + r4) * ncols + nk * 16 + l16] = acc[m][q][r4];
+        }
+    }
+}
+
 // dW[o][cij] = sum over the private copies, and (last workgroups of the grid) db[o] = sum over the
 // slices of the bias partials.  A workgroup of 256 threads sums 64 consecutive elements: wave w takes
 // the copies w, w+4, w+8, ... with four running sums (copies w+4(4i+u), u = 0..3), so that sixteen
@@ -992,11 +1210,28 @@ static hipError_t launch_wgrad_tr_t(const WgradArgs &a, size_t smem, int blocks,
     return hipGetLastError();
 }
 
+template <int MB, int NB, int DT>
+static hipError_t launch_wgrad_trr_t(const WgradArgs &a, size_t smem, int blocks, hipStream_t stream)
+{
+    static bool attr_set = false;
+    if (smem > 48 * 1024 && !attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_trr_h_kernel<MB, NB, DT>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int mgroups = (a.MTo + MB - 1) / MB, ngroups = (a.NTk + 4 * NB - 1) / (4 * NB);
+    hipLaunchKernelGGL((wgrad_trr_h_kernel<MB, NB, DT>), dim3(blocks, mgroups * ngroups), dim3(256), smem, stream, a);
+    return hipGetLastError();
+}
+
+// ring = the strip-walking kernel that keeps the staged input rows across steps
 template <int DT>
-static hipError_t launch_wgrad_tr(const WgradArgs &a, int MB, int NB, size_t smem, int blocks, hipStream_t stream)
+static hipError_t launch_wgrad_tr(const WgradArgs &a, int MB, int NB, size_t smem, int blocks, hipStream_t stream, bool ring)
 {
     hipError_t e = hipErrorInvalidValue;
-#define SK_WG_CASE(mb, nb) if (MB == mb && NB == nb) e = launch_wgrad_tr_t<mb, nb, DT>(a, smem, blocks, stream);
+#define SK_WG_CASE(mb, nb) \
+    if (MB == mb && NB == nb) e = ring ? launch_wgrad_trr_t<mb, nb, DT>(a, smem, blocks, stream) : launch_wgrad_tr_t<mb, nb, DT>(a, smem, blocks, stream);
     SK_WG_CASE(1, 1) SK_WG_CASE(1, 4) SK_WG_CASE(1, 12) SK_WG_CASE(1, 6) SK_WG_CASE(1, 8) SK_WG_CASE(1, 9)
     SK_WG_CASE(3, 1) SK_WG_CASE(3, 4) SK_WG_CASE(3, 12) SK_WG_CASE(3, 6) SK_WG_CASE(3, 8) SK_WG_CASE(3, 9)
     SK_WG_CASE(4, 1) SK_WG_CASE(4, 4) SK_WG_CASE(4, 12) SK_WG_CASE(4, 6) SK_WG_CASE(4, 8) SK_WG_CASE(4, 9)
@@ -1115,7 +1350,9 @@ static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, floa
     hipError_t e = hipErrorInvalidValue;
     if constexpr (DT != 0) {
         if (tr_path) {
-            e = launch_wgrad_tr<DT>(a, MB, NB, smem, blocks, stream);
+            // input rows kept across steps: kernels of two rows or more whose tile groups all use every kernel row
+            const bool ring = k >= 2 && 4 * NB >= k * k && goct <= 12;
+            e = launch_wgrad_tr<DT>(a, MB, NB, smem, blocks, stream, ring);
         } else if (h_path) {
             if (k == 1 || d % 8 == 0) e = launch_wgrad_h_rb<DT, 16>(a, MB, NB, smem, blocks, stream);
             else if (d % 4 == 0) e = launch_wgrad_h_rb<DT, 8>(a, MB, NB, smem, blocks, stream);
