@@ -159,6 +159,10 @@ def test_training_step_half(dtype):
     (20, [(48, 4, 3), (2, 1, 1)], 70, 65),
     (48, [(5, 4, 21), (2, 1, 1)], 90, 63),
     (1, [(16, 4, 1), (40, 4, 2), (3, 1, 1)], 33, 129),
+    # 16 input maps or more, kernels of two rows or more: the strip-walking kernel (input rows kept in an LDS ring).
+    # Fewer output rows than the kernel stride (7 < 12: every strip is one step; a wide image, so that single ReLU flips average out), ragged last segments, 2x2 and 3x3, an odd number of input octets
+    (16, [(32, 2, 12), (2, 1, 1)], 7, 700),
+    (24, [(16, 3, 1), (72, 2, 3), (16, 3, 2), (3, 1, 1)], 37, 150),
 ])
 def test_weight_gradient_kernel_strides_half(dtype, c_in, spec, h, w):
     """The 16-bit weight gradient reads its input fragments at the alignment the kernel stride allows:
