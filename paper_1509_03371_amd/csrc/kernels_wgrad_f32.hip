@@ -687,10 +687,11 @@ __global__ __launch_bounds__(256) void wgrad_tr_h_kernel(WgradArgs a)
     }
 }
 
-// The same gradient with the staged input rows kept across steps (k >= 2, every tile group uses all k kernel rows).
+// The same gradient with the staged input rows kept across steps (k >= 2).
 // A workgroup walks a strip -- one image, one 64-column segment, the output rows of one residue class y = r, r + d,
 // r + 2d, ... -- so that consecutive steps share k - 1 of their k input rows: the rows sit in a ring of k LDS slots per
-// input octet (input row y + i*d of step t in slot (t + i) mod k), a step loads one new row per octet instead of k,
+// input octet (input row y + i*d of step t in slot (t + i) mod k; a tile group inside one map pair keeps only the
+// kernel rows its taps use), a step loads one new row per octet instead of k,
 // and the column tiles' read offsets rotate with the step.  The steps of all strips, in strip order, are dealt out
 // to the workgroups in equal contiguous ranges; the first step of a range or of a strip loads all k rows.
 template <int MB, int NB, int DT>
@@ -716,9 +717,16 @@ __global__ __launch_bounds__(256, MB * NB > 36 ? 1 : 2) void wgrad_trr_h_kernel(
     int nk_hi = nk_lo + NB * 4 - 1;
     nk_hi = nk_hi < a.NTk - 1 ? nk_hi : a.NTk - 1;
     const int oc0 = 2 * (nk_lo / kk), noct = 2 * (nk_hi / kk) + 2 - oc0;     // <= 4 * XU = 12 (checked by the launcher)
+    // kernel rows the group's tiles use: all k, or (a group inside one map pair: kernels with more than 4*NB taps) a
+    // range [i_lo, i_lo + ni); the ring holds those ni rows
+    int i_lo = 0, ni = k;
+    if (nk_lo / kk == nk_hi / kk) {
+        i_lo = (nk_lo % kk) / k;
+        ni = (nk_hi % kk) / k - i_lo + 1;
+    }
     const unsigned slot_bytes = (unsigned)a.xpitch * 16;
     unsigned xoff[NB], aoff[MB];
-    int iq[NB];                                         // kernel row of column tile q (wave-uniform)
+    int iq[NB];                                         // kernel row of column tile q within the ring (wave-uniform)
 #pragma unroll
     for (int q = 0; q < NB; ++q) {
         const int nk = (ngroup * NB + q) * 4 + wave;
@@ -727,7 +735,7 @@ __global__ __launch_bounds__(256, MB * NB > 36 ? 1 : 2) void wgrad_trr_h_kernel(
         if (nk < a.NTk) {
             const int op = nk / kk, r = nk - op * kk, i = r / k, j = r - i * k;
             off = (unsigned)((((2 * op - oc0 + (qq >> 1)) * k) * a.xpitch + j * d + 8 * g + rr) * 16 + (qq & 1) * 8);
-            iq[q] = i;
+            iq[q] = i - i_lo;
         }
         xoff[q] = off;
     }
@@ -746,7 +754,7 @@ __global__ __launch_bounds__(256, MB * NB > 36 ? 1 : 2) void wgrad_trr_h_kernel(
     const long xplane = (long)a.H * a.W, yplane = (long)a.Ho * a.Wo;
     const uint4v *dyp = static_cast<const uint4v *>(a.dy), *xp = static_cast<const uint4v *>(a.x);
     const int oc_end = 2 * MB;
-    const int nrid = noct * k;                                       // (input octet, kernel row) pairs of a fresh step
+    const int nrid = noct * ni;                                      // (input octet, kernel row) pairs of a fresh step
     const int nbat = (nrid + 4 * XU - 1) / (4 * XU);
     const uint4v zero = uint4v{0u, 0u, 0u, 0u};
 
@@ -760,17 +768,17 @@ __global__ __launch_bounds__(256, MB * NB > 36 ? 1 : 2) void wgrad_trr_h_kernel(
             pdy[t] = dyp[((long)b * c8o + occ) * yplane + (long)y * a.Wo + xl];
         }
     };
-    // fresh: row ids run over (octet, kernel row); else over the octets, each loading its one new row (kernel row k - 1)
+    // fresh: row ids run over (octet, kernel row); else over the octets, each loading its one new row (the last kernel row of the ring)
     auto load_x = [&](int bat, int b, int y, int x0, bool fresh) {
         const int lim = fresh ? nrid : noct;
 #pragma unroll
         for (int u = 0; u < XU; ++u) {
             const int rid = wave + 4 * (bat * XU + u);
             const int ridc = rid < lim ? rid : lim - 1;
-            const int ocr = fresh ? ridc / k : ridc, i = fresh ? ridc - ocr * k : k - 1;
+            const int ocr = fresh ? ridc / ni : ridc, i = fresh ? ridc - ocr * ni : ni - 1;
             int oc = oc0 + ocr;
             oc = oc < c8i ? oc : c8i - 1;
-            const uint4v *src = xp + ((long)b * a.xb8 + oc + (oc / a.grp8) * a.skip8) * xplane + (long)(y + i * d) * a.W;
+            const uint4v *src = xp + ((long)b * a.xb8 + oc + (oc / a.grp8) * a.skip8) * xplane + (long)(y + (i_lo + i) * d) * a.W;
 #pragma unroll
             for (int v = 0; v < XV; ++v) {
                 const int xc = lane + 64 * v;
@@ -791,9 +799,9 @@ __global__ __launch_bounds__(256, MB * NB > 36 ? 1 : 2) void wgrad_trr_h_kernel(
         for (int u = 0; u < XU; ++u) {
             const int rid = wave + 4 * (bat * XU + u);
             if (rid >= lim) continue;                           // uniform
-            const int ocr = fresh ? rid / k : rid, i = fresh ? rid - ocr * k : k - 1;
+            const int ocr = fresh ? rid / ni : rid, i = fresh ? rid - ocr * ni : ni - 1;
             int slot = i + rot;
-            slot = slot >= k ? slot - k : slot;
+            slot = slot >= ni ? slot - ni : slot;
             const int row = ocr * k + slot;
 #pragma unroll
             for (int v = 0; v < XV; ++v) {
@@ -851,7 +859,7 @@ __global__ __launch_bounds__(256, MB * NB > 36 ? 1 : 2) void wgrad_trr_h_kernel(
         const int rot_now = rot;
         if (gs + 1 < g1) {                                      // in flight while this step is multiplied
             advance(bx, r, t, fresh);
-            rot = fresh ? 0 : (rot + 1 == k ? 0 : rot + 1);
+            rot = fresh ? 0 : (rot + 1 == ni ? 0 : rot + 1);
             place(bx, r, t, b, y, x0);
             load_dy(b, y, x0);
             load_x(0, b, y, x0, fresh);
@@ -860,7 +868,7 @@ __global__ __launch_bounds__(256, MB * NB > 36 ? 1 : 2) void wgrad_trr_h_kernel(
 #pragma unroll
         for (int q = 0; q < NB; ++q) {
             int slot = iq[q] + rot_now;
-            slot = slot >= k ? slot - k : slot;
+            slot = slot >= ni ? slot - ni : slot;
             xo[q] = xoff[q] + (unsigned)slot * slot_bytes;
         }
 #pragma unroll
@@ -1350,8 +1358,8 @@ static hipError_t launch_wgrad_dt(const void *x, const void *dy, float *dw, floa
     hipError_t e = hipErrorInvalidValue;
     if constexpr (DT != 0) {
         if (tr_path) {
-            // input rows kept across steps: kernels of two rows or more whose tile groups all use every kernel row
-            const bool ring = k >= 2 && 4 * NB >= k * k && goct <= 12;
+            // input rows kept across steps: kernels of two rows or more
+            const bool ring = k >= 2 && goct <= 12;
             e = launch_wgrad_tr<DT>(a, MB, NB, smem, blocks, stream, ring);
         } else if (h_path) {
             if (k == 1 || d % 8 == 0) e = launch_wgrad_h_rb<DT, 16>(a, MB, NB, smem, blocks, stream);
