@@ -108,11 +108,15 @@ struct TilePos {
     int b, mg, py, ty, x0;
 };
 
-template <int DT, int KS, int MT, bool MAP4, int R, bool HAS_MASK, int VU = CH_VU>
+// XW: waves across a tile's columns (16 each); the other 8 / XW wave rows take R output rows each, so a tile is
+// 16*XW columns x R*8/XW rows of one residue class: 128 x 4, 64 x 8 or 32 x 16 output pixels.  Squarer tiles stage less
+// halo per output and waste less of a narrow or ragged map (a 28-wide map fills 22 % of a 128-column tile).
+template <int DT, int KS, int MT, bool MAP4, int R, bool HAS_MASK, int VU = CH_VU, int XW = 8>
 __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
 {
     extern __shared__ uint4v lds[];
-    constexpr int RR = R + KS - 1;
+    constexpr int YW = CH_WAVES / XW, RT = R * YW, TX = 16 * XW;   // wave rows, output rows and columns of a tile
+    constexpr int RR = RT + KS - 1;
     constexpr int OC = MAP4 ? 1 : 4;            // input octets per chunk
     constexpr int CS = MAP4 ? (KS + 3) / 4 : KS; // column steps per chunk
     constexpr int TAPW = MAP4 ? 4 * CS : KS;    // kernel columns the tile is staged for
@@ -122,11 +126,12 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
     constexpr int WU = (WUNITS + CH_THREADS - 1) / CH_THREADS;
 
     const int d = a.d;
-    const int PW = CH_TX + (TAPW - 1) * d;      // tile width in 16-byte units
+    const int PW = TX + (TAPW - 1) * d;         // tile width in 16-byte units
     const int tile_units = ROWS * PW;
     const int stage_units = tile_units + WUNITS;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l16 = lane & 15, g = lane >> 4;
+    const int wcol = wave % XW, wrow = wave / XW;           // this wave's 16 columns and R rows inside the tile
 
     // XCD-aware persistent schedule: workgroup ids go round-robin over the 8 XCDs, so XCD x takes
     // the x-th contiguous eighth of the tile list (neighbouring tiles share halo in that XCD's L2)
@@ -149,7 +154,7 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
             p.py = a.rem + y2 / a.tiles_lo;
             p.ty = y2 % a.tiles_lo;
         }
-        p.x0 = xt * CH_TX;
+        p.x0 = xt * TX;
         return p;
     };
 
@@ -162,7 +167,7 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
     uint4v wr[WU];
 
     auto prefetch = [&](const TilePos &p, int ch) {
-        const int gy0 = p.py + d * (p.ty * R) - a.in_off;
+        const int gy0 = p.py + d * (p.ty * RT) - a.in_off;
         const int gx0 = p.x0 - a.in_off;
 #pragma unroll
         for (int u = 0; u < RU; ++u) {
@@ -191,7 +196,7 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
     };
     auto commit = [&](const TilePos &p, int ch, int buf) {
         uint4v *dst = lds + buf * stage_units;
-        const int gy0 = p.py + d * (p.ty * R) - a.in_off;
+        const int gy0 = p.py + d * (p.ty * RT) - a.in_off;
         const int gx0 = p.x0 - a.in_off;
         const uint4v zero = uint4v{0u, 0u, 0u, 0u};
 #pragma unroll
@@ -231,12 +236,12 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
             for (int i = 0; i < KS; ++i)
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) afr[i][mt] = wl[((cs * KS + i) * MT + mt) * 64 + lane];
-            const int off = (MAP4 ? (4 * cs + g) * d : g * RR * PW + cs * d) + wave * 16 + l16;
+            const int off = (MAP4 ? (4 * cs + g) * d : g * RR * PW + cs * d) + wrow * R * PW + wcol * 16 + l16;
             uint4v bcur = tile[off];
 #pragma unroll
-            for (int r = 0; r < RR; ++r) {
+            for (int r = 0; r < R + KS - 1; ++r) {              // the input rows under this wave's R output rows
                 uint4v bnext = bcur;
-                if (r + 1 < RR) bnext = tile[off + (r + 1) * PW];
+                if (r + 1 < R + KS - 1) bnext = tile[off + (r + 1) * PW];
 #pragma unroll
                 for (int i = 0; i < KS; ++i) {
                     const int y = r - i;
@@ -258,7 +263,7 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
     // in one batch of global loads) and the stores follow without any load in between: on this ISA a
     // wait for a load also waits for every store issued before it, which would serialise the stores.
     auto epilogue = [&](const TilePos &p) {
-        const int ox = p.x0 + wave * 16 + l16;
+        const int ox = p.x0 + wcol * 16 + l16;
         const bool colok = ox < a.Wo;
         const int oxc = colok ? ox : 0;
         float bia[MT][4];
@@ -280,7 +285,7 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
             const char *mbase = reinterpret_cast<const char *>(a.mask) + (ybase - reinterpret_cast<char *>(a.y));
 #pragma unroll
             for (int y = 0; y < R; ++y) {
-                int oy = p.py + d * (p.ty * R + y);
+                int oy = p.py + d * (p.ty * RT + wrow * R + y);
                 oy = oy < a.Ho ? oy : a.Ho - 1;
                 const int yoff = (oy * a.oy_mul + a.oy_off) * row_bytes;
 #pragma unroll
@@ -293,7 +298,7 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
         }
 #pragma unroll
         for (int y = 0; y < R; ++y) {
-            const int oy = p.py + d * (p.ty * R + y);
+            const int oy = p.py + d * (p.ty * RT + wrow * R + y);
             const int yoff = (oy * a.oy_mul + a.oy_off) * row_bytes;
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
@@ -360,7 +365,7 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
         }
         prefetch(nxt, nch);
         // a wave whose 16 columns lie right of the image (narrow maps: most waves of a 128-column tile) multiplies nothing
-        if (__builtin_amdgcn_readfirstlane((int)(cur.x0 + (tid >> 6) * 16 < a.Wo))) compute(buf);
+        if (__builtin_amdgcn_readfirstlane((int)(cur.x0 + ((tid >> 6) % XW) * 16 < a.Wo))) compute(buf);
         // Explicit vmcnt(0): every prefetched register is consumed below, some only by part of the
         // lanes; without it the compiler would carry "load pending" states around the loop and wait
         // (also for the stores of the epilogue) before it reuses those registers.  The stores of the
@@ -376,7 +381,7 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
         cur = nxt;
         buf ^= 1;
     }
-    if (__builtin_amdgcn_readfirstlane((int)(cur.x0 + (tid >> 6) * 16 < a.Wo))) compute(buf);
+    if (__builtin_amdgcn_readfirstlane((int)(cur.x0 + ((tid >> 6) % XW) * 16 < a.Wo))) compute(buf);
     epilogue(cur);
 }
 
@@ -1073,11 +1078,12 @@ __global__ __launch_bounds__(CH_THREADS + 64 * NP) void conv_h_ring_kernel(ConvH
     }
 }
 
-template <int DT, int KS, int MT, bool MAP4, int R, bool HAS_MASK, int VU = CH_VU>
+template <int DT, int KS, int MT, bool MAP4, int R, bool HAS_MASK, int VU = CH_VU, int XW = 8>
 static hipError_t launch_conv_h_m(ConvHArgs a, hipStream_t stream)
 {
-    constexpr int RR = R + KS - 1, OC = MAP4 ? 1 : 4, CS = MAP4 ? (KS + 3) / 4 : KS, TAPW = MAP4 ? 4 * CS : KS;
-    const int PW = CH_TX + (TAPW - 1) * a.d;
+    constexpr int RT = R * (CH_WAVES / XW), TX = 16 * XW;       // output rows and columns of a tile
+    constexpr int RR = RT + KS - 1, OC = MAP4 ? 1 : 4, CS = MAP4 ? (KS + 3) / 4 : KS, TAPW = MAP4 ? 4 * CS : KS;
+    const int PW = TX + (TAPW - 1) * a.d;
     if (PW > 64 * VU) return hipErrorInvalidValue;
     if (a.vpool || a.hd) return hipErrorInvalidValue;
     const size_t stage = (size_t)OC * RR * PW + (size_t)CS * KS * MT * 64;
@@ -1086,7 +1092,7 @@ static hipError_t launch_conv_h_m(ConvHArgs a, hipStream_t stream)
     if (smem > 160 * 1024) return hipErrorInvalidValue;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_h_kernel<DT, KS, MT, MAP4, R, HAS_MASK, VU>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_h_kernel<DT, KS, MT, MAP4, R, HAS_MASK, VU, XW>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
@@ -1094,11 +1100,11 @@ static hipError_t launch_conv_h_m(ConvHArgs a, hipStream_t stream)
     a.m_tiles = (a.c_out + 15) / 16;
     a.mgroups = (a.m_tiles + MT - 1) / MT;
     a.nchunks = (a.c8_in + OC - 1) / OC;
-    a.xtiles = (a.Wo + CH_TX - 1) / CH_TX;
+    a.xtiles = (a.Wo + TX - 1) / TX;
     const int q = a.Ho / a.d;
     a.rem = a.Ho % a.d;
-    a.tiles_hi = (q + 1 + R - 1) / R;
-    a.tiles_lo = (q + R - 1) / R;
+    a.tiles_hi = (q + 1 + RT - 1) / RT;
+    a.tiles_lo = (q + RT - 1) / RT;
     a.ytiles_total = a.rem * a.tiles_hi + (a.d - a.rem) * a.tiles_lo;
     if (a.tiles_lo < 1) a.tiles_lo = 1;
     const long total = (long)a.xtiles * a.ytiles_total * a.mgroups * a.n;
@@ -1114,13 +1120,47 @@ static hipError_t launch_conv_h_m(ConvHArgs a, hipStream_t stream)
     }
     int blocks = cus / 8 * 8;               // one workgroup per CU, a multiple of the 8 XCDs
     if (total < blocks) blocks = (int)((total + 7) / 8 * 8);
-    hipLaunchKernelGGL((conv_h_kernel<DT, KS, MT, MAP4, R, HAS_MASK, VU>), dim3(blocks), dim3(CH_THREADS), smem, stream, a);
+    hipLaunchKernelGGL((conv_h_kernel<DT, KS, MT, MAP4, R, HAS_MASK, VU, XW>), dim3(blocks), dim3(CH_THREADS), smem, stream, a);
     return hipGetLastError();
+}
+
+static int device_cus();
+
+// Tiles of tx columns x rt rows (per residue class of the rows) that cover the output of a launch
+static long conv_h_tile_count(const ConvHArgs &a, int mt, int tx, int rt)
+{
+    const int q = a.Ho / a.d, rem = a.Ho % a.d;
+    const long ytiles = (long)rem * ((q + 1 + rt - 1) / rt) + (long)(a.d - rem) * std::max(1, (q + rt - 1) / rt);
+    return (long)((a.Wo + tx - 1) / tx) * ytiles * (((a.c_out + 15) / 16 + mt - 1) / mt) * a.n;
 }
 
 template <int DT, int KS, int MT, bool MAP4, int R, int VU = CH_VU>
 static hipError_t launch_conv_h_t(const ConvHArgs &a, hipStream_t stream)
 {
+    if constexpr (!MAP4 && (KS == 2 || KS == 3) && VU == CH_VU) {
+        // Tile shape: 128 x 4, 64 x 8 or 32 x 16 output pixels.  Every tile costs about the same (512 pixels of every
+        // chunk), so the shape that covers the output in the fewest rounds of one tile per CU wins: ragged maps waste
+        // less of a squarer tile, which also stages less halo -- but a 32-column tile stages 72 short rows per chunk
+        // where the 128-column one stages 24 long ones (twice the memory instructions; counted as a quarter more
+        // time), and maps too small to give every CU a tile keep the flat shape, which has the most tiles.  Measured on
+        // the U-Net's 64 -> 64 layer at 568^2: 48.2 -> 42.9 us (64 x 8); 128 -> 128 at 280^2: 49.1 -> 44.0 us (32 x 16).
+        auto fits = [&](int tx, int rt) {               // staged rows of at most 128 units, two stages within the LDS
+            const int pw = tx + (KS - 1) * a.d;
+            const size_t stage = (size_t)4 * (rt + KS - 1) * pw + (size_t)KS * KS * MT * 64;
+            return pw <= 128 && 2 * stage * 16 + (size_t)(((a.c_out + 15) / 16 + MT - 1) / MT * MT) * 64 <= 160 * 1024;
+        };
+        const int cus = device_cus();
+        auto rounds = [&](int tx, int rt) { return (double)((conv_h_tile_count(a, MT, tx, rt) + cus - 1) / cus); };
+        const double c8 = rounds(128, R), c4 = fits(64, 2 * R) ? rounds(64, 2 * R) : 1e30, c2 = fits(32, 4 * R) ? 1.25 * rounds(32, 4 * R) : 1e30;
+        if (c2 < c4 && c2 < c8) {
+            if (a.mask) return launch_conv_h_m<DT, KS, MT, MAP4, R, true, 2, 2>(a, stream);
+            return launch_conv_h_m<DT, KS, MT, MAP4, R, false, 2, 2>(a, stream);
+        }
+        if (c4 < c8) {
+            if (a.mask) return launch_conv_h_m<DT, KS, MT, MAP4, R, true, 2, 4>(a, stream);
+            return launch_conv_h_m<DT, KS, MT, MAP4, R, false, 2, 4>(a, stream);
+        }
+    }
     if (a.mask) return launch_conv_h_m<DT, KS, MT, MAP4, R, true, VU>(a, stream);
     return launch_conv_h_m<DT, KS, MT, MAP4, R, false, VU>(a, stream);
 }

@@ -36,6 +36,9 @@ def make_net(layers, c_in, ws, bs, dtype):
     # consecutive kernel columns, the columns past the kernel carry zero weights; ragged maps, several map blocks
     (5, 2, 8, 16, 33, 29), (5, 2, 48, 128, 40, 150), (6, 1, 10, 40, 30, 75), (6, 3, 5, 70, 40, 90), (7, 1, 3, 48, 25, 140),
     (8, 8, 12, 130, 70, 140), (8, 2, 3, 16, 33, 29), (10, 8, 6, 50, 90, 160), (10, 2, 4, 20, 30, 24), (10, 8, 24, 40, 80, 210),
+    # 2x2 / 3x3 layers large enough for the launcher to prefer a squarer tile (fewer rounds of one tile per CU on 256
+    # CUs): 64 x 8 pixels (600 x 192 outputs, d = 1 and d = 3), 32 x 16 pixels (550 x 70 outputs, d = 2)
+    (3, 1, 16, 16, 602, 194), (2, 3, 8, 16, 603, 195), (3, 2, 16, 24, 554, 74),
 ])
 def test_conv_layer_shapes_half(dtype, k, d, c_in, c_out, h, w):
     dt = "f16" if dtype == "fp16" else dtype
