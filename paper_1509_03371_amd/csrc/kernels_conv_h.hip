@@ -1171,7 +1171,18 @@ template <int DT, int KS, int MT>
 static hipError_t launch_conv_h_big(const ConvHArgs &a, hipStream_t stream)
 {
     if (a.mask) return hipErrorInvalidValue;
-    constexpr int TAPW = 4 * ((KS + 3) / 4);
+    constexpr int TAPW = 4 * ((KS + 3) / 4), CS = (KS + 3) / 4;
+    if constexpr (KS == 6 || KS == 8 || KS == 10) {
+        // 64 x 8 pixel tiles where they cover the output in fewer rounds of one tile per CU (see launch_conv_h_t): the
+        // k - 1 halo rows weigh less under eight output rows than under four, and ragged maps waste less
+        const int pw = 64 + (TAPW - 1) * a.d, cus = device_cus();
+        const size_t stage = (size_t)(8 + KS - 1) * pw + (size_t)CS * KS * MT * 64;
+        const bool fits = pw <= 192 && 2 * stage * 16 + (size_t)(((a.c_out + 15) / 16 + MT - 1) / MT * MT) * 64 <= 160 * 1024;
+        if (fits && (conv_h_tile_count(a, MT, 64, 8) + cus - 1) / cus < (conv_h_tile_count(a, MT, 128, 4) + cus - 1) / cus) {
+            if (pw <= 128) return launch_conv_h_m<DT, KS, MT, true, 4, false, 2, 4>(a, stream);
+            return launch_conv_h_m<DT, KS, MT, true, 4, false, 3, 4>(a, stream);
+        }
+    }
     if (CH_TX + (TAPW - 1) * a.d > 64 * CH_VU) return launch_conv_h_m<DT, KS, MT, true, 4, false, 4>(a, stream);
     return launch_conv_h_m<DT, KS, MT, true, 4, false, CH_VU>(a, stream);
 }

@@ -39,6 +39,8 @@ def make_net(layers, c_in, ws, bs, dtype):
     # 2x2 / 3x3 layers large enough for the launcher to prefer a squarer tile (fewer rounds of one tile per CU on 256
     # CUs): 64 x 8 pixels (600 x 192 outputs, d = 1 and d = 3), 32 x 16 pixels (550 x 70 outputs, d = 2)
     (3, 1, 16, 16, 602, 194), (2, 3, 8, 16, 603, 195), (3, 2, 16, 24, 554, 74),
+    # ... and 6x6 / 8x8 / 10x10 layers that take the 64 x 8 tile (staged rows of two and of three 64-unit groups)
+    (6, 3, 5, 70, 315, 207), (8, 8, 12, 130, 176, 248), (10, 8, 6, 50, 352, 264),
 ])
 def test_conv_layer_shapes_half(dtype, k, d, c_in, c_out, h, w):
     dt = "f16" if dtype == "fp16" else dtype
