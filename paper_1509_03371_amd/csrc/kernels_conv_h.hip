@@ -131,7 +131,8 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
     const int stage_units = tile_units + WUNITS;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l16 = lane & 15, g = lane >> 4;
-    const int wcol = wave % XW, wrow = wave / XW;           // this wave's 16 columns and R rows inside the tile
+    // this wave's 16 columns and R rows inside the tile (constants of the flat shape spelled out for the compiler)
+    const int wcol = XW == CH_WAVES ? wave : wave % XW, wrow = XW == CH_WAVES ? 0 : wave / XW;
 
     // XCD-aware persistent schedule: workgroup ids go round-robin over the 8 XCDs, so XCD x takes
     // the x-th contiguous eighth of the tile list (neighbouring tiles share halo in that XCD's L2)
@@ -365,7 +366,7 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
         }
         prefetch(nxt, nch);
         // a wave whose 16 columns lie right of the image (narrow maps: most waves of a 128-column tile) multiplies nothing
-        if (__builtin_amdgcn_readfirstlane((int)(cur.x0 + ((tid >> 6) % XW) * 16 < a.Wo))) compute(buf);
+        if (__builtin_amdgcn_readfirstlane((int)(cur.x0 + (XW == CH_WAVES ? (tid >> 6) : (tid >> 6) % XW) * 16 < a.Wo))) compute(buf);
         // Explicit vmcnt(0): every prefetched register is consumed below, some only by part of the
         // lanes; without it the compiler would carry "load pending" states around the loop and wait
         // (also for the stores of the epilogue) before it reuses those registers.  The stores of the
@@ -381,7 +382,7 @@ __global__ __launch_bounds__(CH_THREADS) void conv_h_kernel(ConvHArgs a)
         cur = nxt;
         buf ^= 1;
     }
-    if (__builtin_amdgcn_readfirstlane((int)(cur.x0 + ((tid >> 6) % XW) * 16 < a.Wo))) compute(buf);
+    if (__builtin_amdgcn_readfirstlane((int)(cur.x0 + (XW == CH_WAVES ? (tid >> 6) : (tid >> 6) % XW) * 16 < a.Wo))) compute(buf);
     epilogue(cur);
 }
 
