@@ -603,7 +603,7 @@ static hipError_t launch_conv_f32_nt(const ConvF32Args &a, hipStream_t stream)
 }
 
 // ------------------------------------------------------------------------------------------------
-// One input map (the first layer of the BASELINE nets): K = k*k is a single MFMA step or two, and
+// One input map (the first layer of the benchmark nets): K = k*k is a single MFMA step or two, and
 // the layer is bound by writing its output, so it runs on the vector ALU instead.  A thread owns PX
 // output pixels (64 apart in the flattened [Ho*Wo] plane, so every load and store of a wave covers
 // 64 consecutive pixels), keeps their k*k taps in registers and walks over the output maps four at a

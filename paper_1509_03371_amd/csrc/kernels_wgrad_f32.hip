@@ -1122,7 +1122,7 @@ static int wgrad_tr_nb(int ntk, int k)
     return 12;
 }
 
-// Private copies of a gradient.  A small gradient (one tile group: the 48x768 of the BASELINE nets)
+// Private copies of a gradient.  A small gradient (one tile group: the 48x768 of the benchmark nets)
 // takes one copy per resident workgroup; a large one is split over tile groups (blockIdx.y), which
 // already spread it over the GPU, so it gets proportionally fewer copies -- 512 copies of a
 // 1024 x 9216 gradient would be 19 GB to write and to sum.

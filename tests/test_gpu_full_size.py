@@ -1,4 +1,4 @@
-"""GPU parity at BASELINE's full sizes, in the launch configuration bench.py times.
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
 
 C3 (8 x 1024^2, bf16) is too large for the oracle as a whole, but every output pixel depends only
 on its (v+1)^2 input window (Sections 1.3 and 3.1: output-size invariance), so the oracle computes
