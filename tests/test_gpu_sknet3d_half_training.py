@@ -87,6 +87,15 @@ def test_gradients_benchmark_net_map_counts(dtype):
     net.close()
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_gradients_three_octets_per_depth_tap(dtype):
+    # 20 input maps = three octets per depth tap: the merged weight gradient's map pairs straddle two depth taps, and
+    # with kernel stride 2 every third octet jumps to the next tapped slice; the third layer has 12 maps = two octets
+    layers = [S.conv(20, 3, 1), S.pool(2, 1), S.conv(12, 3, 2), S.conv(24, 2, 2), S.conv(2, 1, 1, relu=False)]
+    net, *_ = run_training(layers, 3, 2, (16, 26, 90), 630, dtype)
+    net.close()
+
+
 def test_gradients_wider_pool_unmasked_bf16():
     layers = [S.conv(8, 3, 1), S.pool(3, 1), S.conv(12, 2, 3), S.conv(10, 1, 1), S.conv(2, 1, 1, relu=False)]
     net, *_ = run_training(layers, 1, 2, (12, 20, 70), 620, "bf16", masked=False)
